@@ -1,0 +1,266 @@
+"""Seeded synthetic decode workloads (queries, KV cache, budgets) for the LFPS hot path.
+
+This module only *makes inputs*.  It holds none of the method's arithmetic (no
+scores, no selection, no softmax) and is the one piece of code that both the CPU
+oracle's tests and the HIP path's tests/bench consume.
+
+Every K/V element is a pure function of (seed, tensor, request b, KV head g, row,
+channel) through a counter-based generator, so the CPU side can regenerate any
+row of a multi-GB cache without copying it back from the device, and the device
+fill (fill.hip, same integer recipe) produces the same bits in place.
+
+Recipe (shapes follow the paper's evaluation model: 32 query heads, 8 KV heads,
+head_dim 128, contexts 4K-128K, budget about 2 %, first four tokens act as sinks;
+Sec. 5 "Setup" and App. A of the paper):
+
+* hash      : splitmix64 finaliser  mix64(x).
+* normal    : z(e) = (sum of twelve 10-bit fields of mix64(key+2e*PHI), mix64(key+(2e+1)*PHI)
+              - 6138) / 1024, an Irwin-Hall(12) variate: mean 0, variance 1 - 2^-20,
+              exactly representable in fp32.
+* direction : u[b,g] = unit-RMS normal vector; uhat = u/|u|.
+* keys      : K[b,g,i] = z + beta(i) * uhat[b,g] (one fp32 add of a host-made bias row);
+              beta = 8 for the 4 sink rows, 2 for n_hot fixed "vertical" rows, 3 for the
+              recency band (last 64 prefill rows and every appended row), else 0.
+* values    : V[b,g,i] = z (its own stream).
+* bf16      : one round-to-nearest-even of the fp32 value, done in integer arithmetic.
+* queries   : q0[b,h] = rms(u[b,g(h)] + 0.3 N), q_t = rms(q_{t-1} + d_t N), d_t = drift
+              (optionally a larger drift every `spike_every` steps); rms(x) scales to unit RMS.
+"""
+from __future__ import annotations
+
+import dataclasses
+from typing import Optional, Tuple
+
+import numpy as np
+
+PHI = np.uint64(0x9E3779B97F4A7C15)
+_M1 = np.uint64(0xBF58476D1CE4E5B9)
+_M2 = np.uint64(0x94D049BB133111EB)
+
+TENSOR_K, TENSOR_V, TENSOR_U, TENSOR_Q0, TENSOR_DRIFT, TENSOR_HOT, TENSOR_LEN = 1, 2, 3, 4, 5, 6, 7
+
+N_SINK_ROWS = 4
+BETA_SINK, BETA_HOT, BETA_RECENT = 8.0, 2.0, 3.0
+CLASS_NONE, CLASS_SINK, CLASS_HOT, CLASS_RECENT = 0, 1, 2, 3
+
+
+def mix64(x: np.ndarray) -> np.ndarray:
+    """splitmix64 finaliser on uint64 arrays (wrap-around arithmetic)."""
+    x = np.asarray(x, dtype=np.uint64).copy()
+    x ^= x >> np.uint64(30)
+    x *= _M1
+    x ^= x >> np.uint64(27)
+    x *= _M2
+    x ^= x >> np.uint64(31)
+    return x
+
+
+def stream_key(seed: int, tensor: int, b: int = 0, g: int = 0) -> np.uint64:
+    """Key of one independent stream; request b uses seed + b."""
+    s = np.array([(seed + b) & 0xFFFFFFFFFFFFFFFF], dtype=np.uint64)
+    k = mix64(s)
+    k = mix64(k + np.array([tensor], dtype=np.uint64) * PHI)
+    k = mix64(k + np.array([g + 1], dtype=np.uint64) * PHI)
+    return k[0]
+
+
+def normal12(key, e: np.ndarray) -> np.ndarray:
+    """Irwin-Hall(12) standard-normal stand-in for counters e -> float32.
+    `key` is one uint64 or an array broadcastable against e."""
+    e = np.asarray(e, dtype=np.uint64)
+    key = np.asarray(key, dtype=np.uint64)
+    two = np.uint64(2)
+    ha = mix64(key + (two * e) * PHI)
+    hb = mix64(key + (two * e + np.uint64(1)) * PHI)
+    acc = np.zeros(ha.shape, dtype=np.int64)
+    mask = np.uint64(1023)
+    for i in range(6):
+        sh = np.uint64(10 * i)
+        acc += ((ha >> sh) & mask).astype(np.int64)
+        acc += ((hb >> sh) & mask).astype(np.int64)
+    return ((acc - 6138).astype(np.float32)) * np.float32(1.0 / 1024.0)
+
+
+def f32_to_bf16_bits(x: np.ndarray) -> np.ndarray:
+    """Round-to-nearest-even fp32 -> bf16 bit patterns (finite inputs)."""
+    u = np.ascontiguousarray(x, dtype=np.float32).view(np.uint32)
+    rnd = ((u >> np.uint32(16)) & np.uint32(1)) + np.uint32(0x7FFF)
+    return ((u + rnd) >> np.uint32(16)).astype(np.uint16)
+
+
+def bf16_bits_to_f32(bits: np.ndarray) -> np.ndarray:
+    return (bits.astype(np.uint32) << np.uint32(16)).view(np.float32)
+
+
+def _rms(x: np.ndarray) -> np.ndarray:
+    """Scale the last axis to unit root-mean-square."""
+    n = np.sqrt(np.mean(np.square(x), axis=-1, keepdims=True))
+    return x / n
+
+
+@dataclasses.dataclass(frozen=True)
+class CaseSpec:
+    name: str
+    B: int
+    L: Optional[int] = None                 # fixed context length ...
+    L_range: Optional[Tuple[int, int]] = None  # ... or ragged, uniform in [lo, hi]
+    kv_dtype: str = "bf16"                   # "bf16" | "f32"
+    k: Optional[int] = None                  # fixed budget ...
+    k_frac: Optional[float] = None           # ... or fraction of the initial length, multiple of 64
+    r: int = 4                               # expansion radius
+    T: int = 64                              # decode steps after the seeding step
+    drift: float = 0.1
+    spike_every: int = 0
+    spike: float = 0.5
+    n_hot: int = 16
+    recency: int = 64
+    Hq: int = 32
+    Hkv: int = 8
+    D: int = 128
+    seed: int = 20250615
+
+    @property
+    def G(self) -> int:
+        return self.Hq // self.Hkv
+
+
+# The five workloads named by the benchmark definition.
+C1 = CaseSpec("C1", B=1, L=4096, kv_dtype="f32", k=128, r=2, T=16, n_hot=0)
+C2 = CaseSpec("C2", B=1, L=32768, k=1024, r=4, T=64)
+C3 = CaseSpec("C3", B=8, L=32768, k=1024, r=4, T=64, spike_every=16)
+C4 = CaseSpec("C4", B=16, L=131072, k=2048, r=4, T=32)
+C5 = CaseSpec("C5", B=32, L_range=(16384, 65536), k_frac=0.02, r=2, T=32)
+WORKLOADS = {c.name: c for c in (C1, C2, C3, C4, C5)}
+
+
+class Case:
+    """Host-side description of one workload: lengths, budgets, queries, and the
+    small tables the K/V generator needs.  The K/V payload itself is produced on
+    demand (rows on the CPU, the whole cache on the device)."""
+
+    def __init__(self, spec: CaseSpec):
+        self.spec = spec
+        B, Hq, Hkv, D, T = spec.B, spec.Hq, spec.Hkv, spec.D, spec.T
+        G = spec.G
+        # --- lengths and budgets
+        if spec.L_range is not None:
+            lo, hi = spec.L_range
+            h = mix64(np.uint64(stream_key(spec.seed, TENSOR_LEN)) + np.arange(B, dtype=np.uint64) * PHI)
+            self.seq_lens0 = (lo + (h % np.uint64(hi - lo + 1)).astype(np.int64)).astype(np.int32)
+        else:
+            self.seq_lens0 = np.full(B, spec.L, dtype=np.int32)
+        if spec.k_frac is not None:
+            kb = 64 * np.rint(spec.k_frac * self.seq_lens0.astype(np.float64) / 64.0)
+            self.k = np.maximum(kb, 64).astype(np.int32)
+        else:
+            self.k = np.full(B, spec.k, dtype=np.int32)
+        self.kmax = int(self.k.max())
+        self.Lcap = int(self.seq_lens0.max()) + T
+        # --- stream keys
+        self.key_k = np.zeros((B, Hkv), dtype=np.uint64)
+        self.key_v = np.zeros((B, Hkv), dtype=np.uint64)
+        for b in range(B):
+            for g in range(Hkv):
+                self.key_k[b, g] = stream_key(spec.seed, TENSOR_K, b, g)
+                self.key_v[b, g] = stream_key(spec.seed, TENSOR_V, b, g)
+        # --- group directions, bias rows, hot rows
+        ch = np.arange(D, dtype=np.uint64)
+        self.u = np.zeros((B, Hkv, D), dtype=np.float64)
+        self.bias = np.zeros((B, Hkv, 4, D), dtype=np.float32)
+        self.hot_pos = np.full((B, Hkv, max(spec.n_hot, 1)), -1, dtype=np.int32)
+        for b in range(B):
+            Lb = int(self.seq_lens0[b])
+            for g in range(Hkv):
+                u = _rms(normal12(stream_key(spec.seed, TENSOR_U, b, g), ch).astype(np.float64))
+                self.u[b, g] = u
+                uhat = u / np.linalg.norm(u)
+                self.bias[b, g, CLASS_SINK] = (BETA_SINK * uhat).astype(np.float32)
+                self.bias[b, g, CLASS_HOT] = (BETA_HOT * uhat).astype(np.float32)
+                self.bias[b, g, CLASS_RECENT] = (BETA_RECENT * uhat).astype(np.float32)
+                if spec.n_hot > 0:
+                    span = Lb - spec.recency - N_SINK_ROWS
+                    hk = np.uint64(stream_key(spec.seed, TENSOR_HOT, b, g))
+                    hh = mix64(hk + np.arange(spec.n_hot, dtype=np.uint64) * PHI)
+                    self.hot_pos[b, g, : spec.n_hot] = (N_SINK_ROWS + (hh % np.uint64(span)).astype(np.int64)).astype(np.int32)
+        # --- queries for the seeding step (t = 0) and the T decode steps
+        self.q = np.zeros((T + 1, B, Hq, D), dtype=np.float32)
+        key_q0 = np.zeros((B, Hq, 1), dtype=np.uint64)
+        key_dr = np.zeros((B, Hq, 1), dtype=np.uint64)
+        for b in range(B):
+            for h in range(Hq):
+                key_q0[b, h, 0] = stream_key(spec.seed, TENSOR_Q0, b, h)
+                key_dr[b, h, 0] = stream_key(spec.seed, TENSOR_DRIFT, b, h)
+        u_of_head = np.repeat(self.u, G, axis=1)                      # [B, Hq, D]
+        q_prev = _rms(u_of_head + 0.3 * normal12(key_q0, ch[None, None, :]).astype(np.float64))
+        self.q[0] = q_prev.astype(np.float32)
+        for t in range(1, T + 1):
+            d = spec.spike if (spec.spike_every and t % spec.spike_every == 0) else spec.drift
+            nz = normal12(key_dr, (np.uint64(t) * np.uint64(D) + ch)[None, None, :]).astype(np.float64)
+            q_prev = _rms(q_prev + d * nz)
+            self.q[t] = q_prev.astype(np.float32)
+
+    # ------------------------------------------------------------------ lengths
+    def seq_lens(self, t: int) -> np.ndarray:
+        """Rows visible at step t: the seeding step sees L, step t >= 1 sees L + t
+        (one appended row per decode step)."""
+        return (self.seq_lens0 + t).astype(np.int32)
+
+    # ------------------------------------------------------------------ K/V rows
+    def row_class(self, b: int, g: int, rows: np.ndarray) -> np.ndarray:
+        spec = self.spec
+        rows = np.asarray(rows, dtype=np.int64)
+        cls = np.zeros(rows.shape, dtype=np.int64)
+        if spec.n_hot > 0:
+            cls[np.isin(rows, self.hot_pos[b, g, : spec.n_hot].astype(np.int64))] = CLASS_HOT
+        cls[rows >= int(self.seq_lens0[b]) - spec.recency] = CLASS_RECENT
+        cls[rows < N_SINK_ROWS] = CLASS_SINK
+        return cls
+
+    def kv_rows(self, which: str, b: int, g: int, rows: np.ndarray):
+        """Regenerate rows of K ("k") or V ("v") of (request b, KV head g) on the CPU.
+
+        Returns (values float32 [len(rows), D] as stored, bits) where bits is the uint16
+        bf16 pattern array for bf16 caches and None for fp32 caches."""
+        spec = self.spec
+        D = spec.D
+        rows = np.asarray(rows, dtype=np.int64)
+        e = rows.astype(np.uint64)[:, None] * np.uint64(D) + np.arange(D, dtype=np.uint64)[None, :]
+        if which == "k":
+            x = normal12(self.key_k[b, g], e)
+            x = x + self.bias[b, g][self.row_class(b, g, rows)]   # one fp32 add per element
+        elif which == "v":
+            x = normal12(self.key_v[b, g], e)
+        else:
+            raise ValueError(which)
+        x = x.astype(np.float32)
+        if spec.kv_dtype == "bf16":
+            bits = f32_to_bf16_bits(x)
+            return bf16_bits_to_f32(bits), bits
+        return x, None
+
+    def kv_group(self, b: int, g: int, n_rows: Optional[int] = None, chunk: int = 16384):
+        """K and V of one (b, g) for rows [0, n_rows) as float32 arrays (stored values)."""
+        if n_rows is None:
+            n_rows = int(self.seq_lens0[b]) + self.spec.T
+        K = np.empty((n_rows, self.spec.D), dtype=np.float32)
+        V = np.empty((n_rows, self.spec.D), dtype=np.float32)
+        for r0 in range(0, n_rows, chunk):
+            rows = np.arange(r0, min(n_rows, r0 + chunk))
+            K[r0:r0 + len(rows)] = self.kv_rows("k", b, g, rows)[0]
+            V[r0:r0 + len(rows)] = self.kv_rows("v", b, g, rows)[0]
+        return K, V
+
+    def kv_bytes(self) -> int:
+        e = 2 if self.spec.kv_dtype == "bf16" else 4
+        return 2 * self.spec.B * self.spec.Hkv * self.Lcap * self.spec.D * e
+
+
+def make_case(spec: CaseSpec) -> Case:
+    return Case(spec)
+
+
+def tiny_spec(name="tiny", **kw) -> CaseSpec:
+    """A small workload of the same structure, for tests that must run in seconds."""
+    base = dict(B=2, L=777, kv_dtype="bf16", k=48, r=2, T=4, n_hot=4, recency=16)
+    base.update(kw)
+    return CaseSpec(name, **base)

@@ -1,0 +1,74 @@
+"""The seeded input generator: determinism, statistics, structure, bf16 rounding."""
+import numpy as np
+import torch
+
+import gen
+from gen import cases
+
+
+def test_mix64_known_values():
+    # splitmix64 reference stream for state 0: first outputs of the published generator
+    x = np.array([0x9E3779B97F4A7C15, 2 * 0x9E3779B97F4A7C15 & 0xFFFFFFFFFFFFFFFF], dtype=np.uint64)
+    out = gen.mix64(x)
+    assert int(out[0]) == 0xE220A8397B1DCDAF
+    assert int(out[1]) == 0x6E789E6AA1B965F4
+
+
+def test_normal12_statistics_and_grid():
+    z = gen.normal12(gen.stream_key(1, 1, 0, 0), np.arange(1 << 20))
+    assert abs(float(z.mean())) < 5e-3 and abs(float(z.std()) - 1.0) < 5e-3
+    assert np.all(z * 1024 == np.round(z * 1024))           # exact multiples of 2^-10
+    assert abs(float(np.mean(z ** 4)) - 3.0) < 0.15          # close to Gaussian kurtosis (2.9)
+    z2 = gen.normal12(gen.stream_key(1, 1, 0, 1), np.arange(1 << 16))
+    assert abs(float(np.corrcoef(z[: 1 << 16], z2)[0, 1])) < 0.02
+
+
+def test_bf16_rounding_matches_torch():
+    x = (np.random.default_rng(0).standard_normal(100000) * 3).astype(np.float32)
+    bits = gen.f32_to_bf16_bits(x)
+    ref = torch.from_numpy(x).to(torch.bfloat16).view(torch.int16).numpy().view(np.uint16)
+    np.testing.assert_array_equal(bits, ref)
+    np.testing.assert_array_equal(gen.bf16_bits_to_f32(bits), torch.from_numpy(x).to(torch.bfloat16).float().numpy())
+
+
+def test_case_is_deterministic_and_addressable():
+    a, b = gen.make_case(gen.tiny_spec()), gen.make_case(gen.tiny_spec())
+    np.testing.assert_array_equal(a.q, b.q)
+    K, V = a.kv_group(1, 3)
+    rows = np.array([5, 700, 33])
+    np.testing.assert_array_equal(a.kv_rows("k", 1, 3, rows)[0], K[rows])
+    np.testing.assert_array_equal(b.kv_rows("v", 1, 3, rows)[0], V[rows])
+    assert not np.array_equal(K[:50], a.kv_group(0, 3)[0][:50])     # requests are independent
+    assert not np.array_equal(K[:50], a.kv_group(1, 2)[0][:50])     # heads are independent
+    assert not np.array_equal(K[:50], V[:50])
+
+
+def test_case_structure():
+    spec = gen.tiny_spec(L=2000, T=8)
+    c = gen.make_case(spec)
+    assert c.q.shape == (9, 2, 32, 128) and c.q.dtype == np.float32
+    np.testing.assert_allclose(np.sqrt((c.q.astype(np.float64) ** 2).mean(-1)), 1.0, rtol=1e-6)
+    assert c.Lcap == 2008 and c.seq_lens(3).tolist() == [2003, 2003]
+    K, _ = c.kv_group(0, 0)
+    s = K.astype(np.float64) @ c.q[0, 0, 0].astype(np.float64) / np.sqrt(128)
+    hot = c.hot_pos[0, 0]
+    plain = np.setdiff1d(np.arange(4, 2000 - 16), hot)
+    assert s[:4].min() > 5.0                                   # sinks dominate
+    assert s[hot].mean() > 1.2 and s[2000 - 16:].mean() > 2.0  # +2 sigma verticals, +3 recency/appended
+    assert abs(s[plain].mean()) < 0.1 and abs(s[plain].std() - 1.0) < 0.1
+    # heads of one group look in similar directions; consecutive steps drift slowly
+    q = c.q.astype(np.float64)
+    assert np.dot(q[0, 0, 0], q[0, 0, 1]) / 128 > 0.85
+    assert np.dot(q[0, 0, 0], q[1, 0, 0]) / 128 > 0.98
+
+
+def test_named_workloads_shapes():
+    c5 = gen.make_case(gen.C5)
+    assert c5.seq_lens0.min() >= 16384 and c5.seq_lens0.max() <= 65536 and len(set(c5.seq_lens0.tolist())) > 16
+    assert np.all(c5.k % 64 == 0) and np.all(np.abs(c5.k - 0.02 * c5.seq_lens0) <= 32)
+    c4 = gen.make_case(gen.C4)
+    assert c4.kv_bytes() == 2 * 16 * 8 * (131072 + 32) * 128 * 2
+    c3 = gen.make_case(gen.C3)
+    q = c3.q.astype(np.float64)
+    step_cos = [np.dot(q[t, 0, 0], q[t - 1, 0, 0]) / 128 for t in range(1, 33)]
+    assert step_cos[15] < 0.93 and step_cos[31] < 0.93 and min(step_cos[:15]) > 0.98   # drift spikes at t = 16, 32
