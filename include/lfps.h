@@ -1,0 +1,175 @@
+/*
+ * liblfps — the decode-step hot path of LFPS ("Learn from the Past: Fast Sparse Indexing
+ * for LLM Decoding") as hand-written HIP kernels for gfx950 (MI355X), behind a C ABI.
+ *
+ * One decode step of one attention layer, for B requests in GQA form (Hq query heads,
+ * Hkv KV heads, G = Hq/Hkv heads per group, head_dim D = 128), with the KV cache resident
+ * in device memory:
+ *
+ *   S1  candidates   previous step's per-head Top-k  ->  sorted candidate positions per KV group
+ *   S2  score        q . K_j / sqrt(D) for candidate rows only (all G heads of the group)
+ *   S3  select       per query head, the k best candidates  ->  Top-k index set of this step
+ *   S4  sparse attn  Softmax over the selected scores, weighted sum of the selected V rows
+ *
+ * plus two baselines over the whole context: full attention and exact Top-k.
+ *
+ * Conventions
+ *   - Every function returns an int status: LFPS_OK (0) or a negative lfps_status.  Nothing
+ *     throws, exits, or synchronises the host (except lfps_create/destroy, lfps_timing_read and
+ *     lfps_poll_status, which say so).  After lfps_create no entry point allocates memory.
+ *   - All array arguments are DEVICE pointers owned by the caller, unless marked "host".
+ *     The context owns only its workspace (candidate scores, split partials, event pool).
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  All work is
+ *     enqueued asynchronously on it, in order.  Use one context per stream at a time.
+ *   - Positions and counts are int32.  A negative entry in an index array is padding.
+ *   - q is fp32 [B, Hq, D].  K and V rows are D contiguous elements (bf16 or fp32); the view
+ *     struct gives the element strides between requests, KV heads and rows.
+ *   - Argument errors that the host can see (NULL pointers, bad shapes/strides) return
+ *     LFPS_EINVAL before anything is launched.  Values that live in device memory (k, seq_lens,
+ *     indices) are clamped by the kernels: k_b to [0, max_k], seq_lens to [0, max_seq_len],
+ *     index entries outside [0, n_b) are ignored.
+ */
+#ifndef LFPS_H
+#define LFPS_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+#pragma GCC visibility push(default) /* the declarations below are the library's whole export list */
+
+typedef struct lfps_ctx lfps_ctx;
+
+typedef enum {
+  LFPS_OK = 0,
+  LFPS_EINVAL = -1, /* NULL pointer, unsupported shape/dtype, bad stride */
+  LFPS_ECAP = -2,   /* a capacity in lfps_config cannot be met (LDS bitmap, workspace) */
+  LFPS_EHIP = -3,   /* HIP runtime error; text via lfps_last_error */
+  LFPS_ENOMEM = -4  /* workspace allocation failed in lfps_create */
+} lfps_status;
+
+typedef enum { LFPS_F32 = 0, LFPS_BF16 = 1 } lfps_dtype;
+
+typedef struct {
+  int32_t batch;       /* B >= 1 */
+  int32_t n_q_heads;   /* Hq, a multiple of n_kv_heads; Hq/Hkv must be 1, 2 or 4 */
+  int32_t n_kv_heads;  /* Hkv */
+  int32_t head_dim;    /* D, must be 128 */
+  int32_t kv_dtype;    /* lfps_dtype of the K/V cache */
+  int32_t max_seq_len; /* Lcap: rows allocated per (request, KV head); n_b <= Lcap always */
+  int32_t max_k;       /* kmax: row length of every Top-k array; k_b <= kmax */
+  int32_t radius;      /* r >= 0: positional expansion radius around each predicted position */
+  int32_t n_recent;    /* the newest n_recent rows are always candidates (>= 0) */
+  int32_t n_sink;      /* the first n_sink rows are always candidates (>= 0) */
+  int32_t cand_cap;    /* row length of candidate arrays; 0 = min(Lcap, G*kmax*(2r+2)+n_recent+n_sink) */
+  int32_t device;      /* HIP device ordinal */
+} lfps_config;
+
+/* View of the KV cache.  Element (b, g, i, c) of K is k[b*stride_b + g*stride_h + i*stride_n + c]
+ * (strides in elements, stride_n >= D, rows 16-byte aligned), same for v.  seq_lens[b] = n_b, the
+ * number of valid rows of request b at this step.  The struct itself is host memory; k, v and
+ * seq_lens are device pointers. */
+typedef struct {
+  const void* k;
+  const void* v;
+  int64_t stride_b, stride_h, stride_n;
+  const int32_t* seq_lens; /* [B] */
+} lfps_kv;
+
+/* Create / destroy.  lfps_create validates the config, selects cfg->device, allocates the
+ * workspace (lfps_workspace_bytes) and synchronises the device once.  *out is NULL on error. */
+int lfps_create(const lfps_config* cfg, lfps_ctx** out);
+int lfps_destroy(lfps_ctx* ctx);
+/* Text of the last error on this context (host string owned by the context; "" if none).
+ * With ctx == NULL: text of the last lfps_create failure in this thread. */
+const char* lfps_last_error(const lfps_ctx* ctx);
+/* Device bytes lfps_create will allocate for this config (host out-pointer). */
+int lfps_workspace_bytes(const lfps_config* cfg, int64_t* out);
+/* The candidate row length in effect (cfg.cand_cap or its default). */
+int32_t lfps_cand_cap(const lfps_ctx* ctx);
+
+/* S1 — candidate set (Alg. 1 lines 6-7; Eq. 7 and Eq. 9 in their memoryless form).
+ * For every (b, g):  C = clip_[0,n_b)( U_{h in g} U_{i in prev_topk[b,h,0:k_b]} {i-r, ..., i+r+1} )
+ *                        U {n_b - n_recent, ..., n_b - 1} U {0, ..., n_sink - 1}
+ * i.e. the previous Top-k itself (vertical pattern), the same positions shifted by +1 (slash
+ * pattern, the direction Eq. 10 moves slash history), each widened by +-r (at r = 1 the offsets
+ * are the {-1,0,1,2} of Sec. 4.2 stage 3).  Output is ascending and duplicate-free, hence
+ * bit-reproducible.
+ *   prev_topk  [B, Hq, kmax] int32, first k_b entries of a row are used, entries outside [0,n_b) ignored
+ *   k          [B] int32;  seq_lens [B] int32
+ *   cand       [B, Hkv, cand_cap] int32 out (entries past cand_count are left untouched)
+ *   cand_count [B, Hkv] int32 out.  If a set would exceed cand_cap it is truncated to its
+ *              cand_cap smallest positions and LFPS_FLAG_CAND_OVERFLOW is raised (lfps_poll_status). */
+int lfps_candidates(lfps_ctx* ctx, const int32_t* prev_topk, const int32_t* k, const int32_t* seq_lens,
+                    int32_t* cand, int32_t* cand_count, void* stream);
+
+/* S2 + S3 — exact dot products over the candidates only, then the k best per query head
+ * (Alg. 1 line 8; Sec. 1 Steps 1-2 restricted to the candidate set).
+ * score(b,h,j) = q[b,h] . K[b,g(h),cand[b,g,j]] / sqrt(D), fp32 accumulate.
+ *   cand, cand_count  as produced by lfps_candidates (ascending positions in [0, n_b))
+ *   topk_idx   [B, Hq, kmax] int32 out: the min(k_b, c) selected positions, ascending; rest -1.
+ *              Equal scores at the cut are resolved towards the lower position.
+ *   topk_score [B, Hq, kmax] fp32 out or NULL: the score of each selected position (0 for padding)
+ *   cand_score [B, Hq, cand_cap] fp32 out or NULL: every candidate's score (parity/debug dump) */
+int lfps_score_topk(lfps_ctx* ctx, const float* q, const lfps_kv* kv, const int32_t* cand,
+                    const int32_t* cand_count, const int32_t* k, int32_t* topk_idx, float* topk_score,
+                    float* cand_score, void* stream);
+
+/* S4 — sparse attention output (Eq. 1):  out[b,h] = sum_i softmax_i(s_i) V[b,g(h),i],  i in idx[b,h,0:k_b],
+ * s_i = q.K_i/sqrt(D).  Negative entries and entries >= n_b are skipped.
+ *   idx       [B, Hq, kmax] int32
+ *   idx_score [B, Hq, kmax] fp32 scores of those positions, or NULL to recompute q.K from the cache
+ *   out       [B, Hq, D] fp32 (zeros for a head with no valid index) */
+int lfps_sparse_attn(lfps_ctx* ctx, const float* q, const lfps_kv* kv, const int32_t* idx,
+                     const float* idx_score, const int32_t* k, float* out, void* stream);
+
+/* S1..S4 in one call (Alg. 1 lines 6-8 and 10, then Eq. 1): candidates from prev_topk, score,
+ * select into topk_idx (this step's index set, the next step's prev_topk), attention into out.
+ * S4 reuses S3's scores, so only V rows are gathered.  prev_topk and topk_idx must not overlap.
+ *   topk_score [B, Hq, kmax] fp32 out or NULL */
+int lfps_step(lfps_ctx* ctx, const float* q, const lfps_kv* kv, const int32_t* prev_topk, const int32_t* k,
+              int32_t* topk_idx, float* topk_score, float* out, void* stream);
+
+/* Baseline: full attention decode, softmax(q K^T / sqrt(D)) V over all n_b rows
+ * (Sec. 1 with idx = all; the "full attention" upper bound of Sec. 5).  out [B, Hq, D] fp32. */
+int lfps_full_attn_decode(lfps_ctx* ctx, const float* q, const lfps_kv* kv, float* out, void* stream);
+
+/* Baseline: exact Top-k, Sec. 1 Steps 1-2 over all n_b keys (the "exact Top-k" upper bound of
+ * Sec. 5): scores every row, selects the k_b best per head.  Outputs as lfps_score_topk.
+ * Also the seed of step 0 (the previous Top-k of the first LFPS step). */
+int lfps_exact_topk(lfps_ctx* ctx, const float* q, const lfps_kv* kv, const int32_t* k, int32_t* topk_idx,
+                    float* topk_score, void* stream);
+
+/* Status flags raised by kernels since the last poll.  Synchronises `stream`, copies the flag
+ * word to *flags (host) and clears it. */
+#define LFPS_FLAG_CAND_OVERFLOW 1
+int lfps_poll_status(lfps_ctx* ctx, int32_t* flags, void* stream);
+
+/* Per-kernel timing for benchmarks.  While enabled, every kernel launch is bracketed by HIP
+ * events on the launch stream (at most LFPS_TIMING_MAX_LAUNCHES launches between reads; later
+ * ones go untimed).  lfps_timing_read synchronises the stream and writes, for kernel slot i,
+ * the summed milliseconds to ms[i] and the number of timed launches to launches[i] (host
+ * arrays of LFPS_N_KERNELS), then resets the accumulators. */
+enum {
+  LFPS_KERNEL_CANDIDATES = 0,
+  LFPS_KERNEL_GATHER_SCORE = 1,
+  LFPS_KERNEL_SELECT = 2,
+  LFPS_KERNEL_SPARSE_ATTN = 3,
+  LFPS_KERNEL_ATTN_MERGE = 4,
+  LFPS_KERNEL_DENSE_SCORE = 5,
+  LFPS_KERNEL_FULL_ATTN = 6,
+  LFPS_KERNEL_FULL_MERGE = 7,
+  LFPS_KERNEL_HEAD_SCORE = 8,
+  LFPS_N_KERNELS = 9
+};
+#define LFPS_TIMING_MAX_LAUNCHES 4096
+int lfps_timing_enable(lfps_ctx* ctx, int32_t on);
+int lfps_timing_read(lfps_ctx* ctx, float* ms, int32_t* launches, void* stream);
+const char* lfps_kernel_name(int32_t slot);
+
+#pragma GCC visibility pop
+#ifdef __cplusplus
+}
+#endif
+#endif /* LFPS_H */

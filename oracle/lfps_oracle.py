@@ -102,9 +102,12 @@ def score_topk(q_h: np.ndarray, K: np.ndarray, C: np.ndarray, k: int):
 
 
 def sparse_attn(q_h: np.ndarray, K: np.ndarray, V: np.ndarray, I_h: np.ndarray) -> np.ndarray:
-    """O(I) = Softmax(q K_I^T / sqrt(d)) V_I; negative entries of I are padding."""
+    """O(I) = Softmax(q K_I^T / sqrt(d)) V_I; negative entries of I are padding.
+    An empty index set (nothing to attend to) gives the zero vector."""
     I_h = np.asarray(I_h, dtype=np.int64)
     I_h = I_h[I_h >= 0]
+    if len(I_h) == 0:
+        return np.zeros(np.asarray(V).shape[-1], dtype=np.float64)
     p = _softmax(scores(q_h, K, I_h))
     return p @ np.asarray(V[I_h], dtype=np.float64)
 

@@ -1,0 +1,224 @@
+"""ctypes binding of liblfps.so: same names as the C ABI, argument marshalling only.
+
+Every array argument is a torch tensor living on the GPU (PyTorch is used for device memory
+and streams, nothing else); its dtype/shape/contiguity are checked here and its data pointer
+is handed to the library.  There is no fallback: if the shared library is missing the import
+of this module fails.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import Optional
+
+import torch
+
+_PKG = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_PKG, "liblfps.so")
+
+LFPS_F32, LFPS_BF16 = 0, 1
+LFPS_OK, LFPS_EINVAL, LFPS_ECAP, LFPS_EHIP, LFPS_ENOMEM = 0, -1, -2, -3, -4
+LFPS_FLAG_CAND_OVERFLOW = 1
+N_KERNELS = 9
+
+
+class LfpsError(RuntimeError):
+    def __init__(self, code: int, msg: str):
+        super().__init__(f"liblfps error {code}: {msg}")
+        self.code = code
+
+
+class lfps_config(ctypes.Structure):
+    _fields_ = [(n, ctypes.c_int32) for n in (
+        "batch", "n_q_heads", "n_kv_heads", "head_dim", "kv_dtype", "max_seq_len", "max_k",
+        "radius", "n_recent", "n_sink", "cand_cap", "device")]
+
+
+class lfps_kv(ctypes.Structure):
+    _fields_ = [("k", ctypes.c_void_p), ("v", ctypes.c_void_p),
+                ("stride_b", ctypes.c_int64), ("stride_h", ctypes.c_int64), ("stride_n", ctypes.c_int64),
+                ("seq_lens", ctypes.c_void_p)]
+
+
+def _load() -> ctypes.CDLL:
+    if not os.path.exists(LIB_PATH):
+        raise ImportError(
+            f"{LIB_PATH} is missing: build it with `python -m paper_2506_15704_amd.build` "
+            "(there is no CPU fallback)")
+    lib = ctypes.CDLL(LIB_PATH)
+    P, I32, VP = ctypes.c_void_p, ctypes.c_int32, ctypes.c_void_p
+    sig = {
+        "lfps_create": (ctypes.c_int, [ctypes.POINTER(lfps_config), ctypes.POINTER(P)]),
+        "lfps_destroy": (ctypes.c_int, [P]),
+        "lfps_last_error": (ctypes.c_char_p, [P]),
+        "lfps_workspace_bytes": (ctypes.c_int, [ctypes.POINTER(lfps_config), ctypes.POINTER(ctypes.c_int64)]),
+        "lfps_cand_cap": (I32, [P]),
+        "lfps_candidates": (ctypes.c_int, [P, VP, VP, VP, VP, VP, VP]),
+        "lfps_score_topk": (ctypes.c_int, [P, VP, ctypes.POINTER(lfps_kv), VP, VP, VP, VP, VP, VP, VP]),
+        "lfps_sparse_attn": (ctypes.c_int, [P, VP, ctypes.POINTER(lfps_kv), VP, VP, VP, VP, VP]),
+        "lfps_step": (ctypes.c_int, [P, VP, ctypes.POINTER(lfps_kv), VP, VP, VP, VP, VP, VP]),
+        "lfps_full_attn_decode": (ctypes.c_int, [P, VP, ctypes.POINTER(lfps_kv), VP, VP]),
+        "lfps_exact_topk": (ctypes.c_int, [P, VP, ctypes.POINTER(lfps_kv), VP, VP, VP, VP]),
+        "lfps_poll_status": (ctypes.c_int, [P, ctypes.POINTER(I32), VP]),
+        "lfps_timing_enable": (ctypes.c_int, [P, I32]),
+        "lfps_timing_read": (ctypes.c_int, [P, ctypes.POINTER(ctypes.c_float), ctypes.POINTER(I32), VP]),
+        "lfps_kernel_name": (ctypes.c_char_p, [I32]),
+    }
+    for name, (res, args) in sig.items():
+        fn = getattr(lib, name)
+        fn.restype, fn.argtypes = res, args
+    return lib
+
+
+_lib = _load()
+
+
+def kernel_names():
+    return [_lib.lfps_kernel_name(i).decode() for i in range(N_KERNELS)]
+
+
+def workspace_bytes(**cfg) -> int:
+    c = lfps_config(**cfg)
+    out = ctypes.c_int64(0)
+    rc = _lib.lfps_workspace_bytes(ctypes.byref(c), ctypes.byref(out))
+    if rc != LFPS_OK:
+        raise LfpsError(rc, _lib.lfps_last_error(None).decode())
+    return out.value
+
+
+def _ptr(t: Optional[torch.Tensor], dtype, shape, name: str, device) -> Optional[int]:
+    if t is None:
+        return None
+    if not isinstance(t, torch.Tensor) or not t.is_cuda or t.device != device:
+        raise TypeError(f"{name}: expected a tensor on {device}")
+    if t.dtype != dtype:
+        raise TypeError(f"{name}: expected dtype {dtype}, got {t.dtype}")
+    if tuple(t.shape) != tuple(shape):
+        raise ValueError(f"{name}: expected shape {tuple(shape)}, got {tuple(t.shape)}")
+    if not t.is_contiguous():
+        raise ValueError(f"{name}: must be contiguous")
+    return t.data_ptr()
+
+
+class Lfps:
+    """A liblfps context.  Methods mirror the C entry points one to one."""
+
+    def __init__(self, batch: int, n_q_heads: int = 32, n_kv_heads: int = 8, head_dim: int = 128,
+                 kv_dtype: str = "bf16", max_seq_len: int = 0, max_k: int = 0, radius: int = 0,
+                 n_recent: int = 1, n_sink: int = 0, cand_cap: int = 0, device: int = 0):
+        self.cfg = lfps_config(batch, n_q_heads, n_kv_heads, head_dim,
+                               LFPS_BF16 if kv_dtype == "bf16" else LFPS_F32, max_seq_len, max_k,
+                               radius, n_recent, n_sink, cand_cap, device)
+        self.kv_torch_dtype = torch.bfloat16 if kv_dtype == "bf16" else torch.float32
+        self.device = torch.device("cuda", device)
+        self._ctx = ctypes.c_void_p(None)
+        rc = _lib.lfps_create(ctypes.byref(self.cfg), ctypes.byref(self._ctx))
+        if rc != LFPS_OK:
+            raise LfpsError(rc, _lib.lfps_last_error(None).decode())
+        self.B, self.Hq, self.Hkv, self.D = batch, n_q_heads, n_kv_heads, head_dim
+        self.kmax, self.Lcap = max_k, max_seq_len
+        self.cand_cap = int(_lib.lfps_cand_cap(self._ctx))
+
+    # ------------------------------------------------------------------ plumbing
+    def close(self):
+        if self._ctx:
+            _lib.lfps_destroy(self._ctx)
+            self._ctx = ctypes.c_void_p(None)
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+    def _check(self, rc: int):
+        if rc != LFPS_OK:
+            raise LfpsError(rc, _lib.lfps_last_error(self._ctx).decode())
+
+    def _stream(self) -> int:
+        return torch.cuda.current_stream(self.device).cuda_stream
+
+    def kv_view(self, K: torch.Tensor, V: Optional[torch.Tensor], seq_lens: torch.Tensor) -> lfps_kv:
+        """View of a [B, Hkv, Lcap', D] cache (any strides with a contiguous last dim)."""
+        for name, t in (("K", K), ("V", V)):
+            if t is None:
+                continue
+            if not t.is_cuda or t.dtype != self.kv_torch_dtype or t.dim() != 4:
+                raise TypeError(f"{name}: expected a 4-d {self.kv_torch_dtype} tensor on the GPU")
+            if t.shape[0] != self.B or t.shape[1] != self.Hkv or t.shape[3] != self.D or t.stride(3) != 1:
+                raise ValueError(f"{name}: expected [B={self.B}, Hkv={self.Hkv}, rows, D={self.D}] with unit channel stride")
+            if t.shape[2] < self.Lcap:
+                raise ValueError(f"{name}: holds {t.shape[2]} rows per head, fewer than max_seq_len={self.Lcap}")
+        if V is not None and V.stride() != K.stride():
+            raise ValueError("K and V must share strides")
+        sl = _ptr(seq_lens, torch.int32, (self.B,), "seq_lens", self.device)
+        return lfps_kv(K.data_ptr(), V.data_ptr() if V is not None else None,
+                       K.stride(0), K.stride(1), K.stride(2), sl)
+
+    # ------------------------------------------------------------------ entry points
+    def lfps_candidates(self, prev_topk, k, seq_lens, cand, cand_count):
+        d = self.device
+        self._check(_lib.lfps_candidates(
+            self._ctx, _ptr(prev_topk, torch.int32, (self.B, self.Hq, self.kmax), "prev_topk", d),
+            _ptr(k, torch.int32, (self.B,), "k", d), _ptr(seq_lens, torch.int32, (self.B,), "seq_lens", d),
+            _ptr(cand, torch.int32, (self.B, self.Hkv, self.cand_cap), "cand", d),
+            _ptr(cand_count, torch.int32, (self.B, self.Hkv), "cand_count", d), self._stream()))
+
+    def lfps_score_topk(self, q, kv: lfps_kv, cand, cand_count, k, topk_idx, topk_score=None, cand_score=None):
+        d = self.device
+        self._check(_lib.lfps_score_topk(
+            self._ctx, _ptr(q, torch.float32, (self.B, self.Hq, self.D), "q", d), ctypes.byref(kv),
+            _ptr(cand, torch.int32, (self.B, self.Hkv, self.cand_cap), "cand", d),
+            _ptr(cand_count, torch.int32, (self.B, self.Hkv), "cand_count", d),
+            _ptr(k, torch.int32, (self.B,), "k", d),
+            _ptr(topk_idx, torch.int32, (self.B, self.Hq, self.kmax), "topk_idx", d),
+            _ptr(topk_score, torch.float32, (self.B, self.Hq, self.kmax), "topk_score", d),
+            _ptr(cand_score, torch.float32, (self.B, self.Hq, self.cand_cap), "cand_score", d), self._stream()))
+
+    def lfps_sparse_attn(self, q, kv: lfps_kv, idx, idx_score, k, out):
+        d = self.device
+        self._check(_lib.lfps_sparse_attn(
+            self._ctx, _ptr(q, torch.float32, (self.B, self.Hq, self.D), "q", d), ctypes.byref(kv),
+            _ptr(idx, torch.int32, (self.B, self.Hq, self.kmax), "idx", d),
+            _ptr(idx_score, torch.float32, (self.B, self.Hq, self.kmax), "idx_score", d),
+            _ptr(k, torch.int32, (self.B,), "k", d),
+            _ptr(out, torch.float32, (self.B, self.Hq, self.D), "out", d), self._stream()))
+
+    def lfps_step(self, q, kv: lfps_kv, prev_topk, k, topk_idx, out, topk_score=None):
+        d = self.device
+        self._check(_lib.lfps_step(
+            self._ctx, _ptr(q, torch.float32, (self.B, self.Hq, self.D), "q", d), ctypes.byref(kv),
+            _ptr(prev_topk, torch.int32, (self.B, self.Hq, self.kmax), "prev_topk", d),
+            _ptr(k, torch.int32, (self.B,), "k", d),
+            _ptr(topk_idx, torch.int32, (self.B, self.Hq, self.kmax), "topk_idx", d),
+            _ptr(topk_score, torch.float32, (self.B, self.Hq, self.kmax), "topk_score", d),
+            _ptr(out, torch.float32, (self.B, self.Hq, self.D), "out", d), self._stream()))
+
+    def lfps_full_attn_decode(self, q, kv: lfps_kv, out):
+        d = self.device
+        self._check(_lib.lfps_full_attn_decode(
+            self._ctx, _ptr(q, torch.float32, (self.B, self.Hq, self.D), "q", d), ctypes.byref(kv),
+            _ptr(out, torch.float32, (self.B, self.Hq, self.D), "out", d), self._stream()))
+
+    def lfps_exact_topk(self, q, kv: lfps_kv, k, topk_idx, topk_score=None):
+        d = self.device
+        self._check(_lib.lfps_exact_topk(
+            self._ctx, _ptr(q, torch.float32, (self.B, self.Hq, self.D), "q", d), ctypes.byref(kv),
+            _ptr(k, torch.int32, (self.B,), "k", d),
+            _ptr(topk_idx, torch.int32, (self.B, self.Hq, self.kmax), "topk_idx", d),
+            _ptr(topk_score, torch.float32, (self.B, self.Hq, self.kmax), "topk_score", d), self._stream()))
+
+    def lfps_poll_status(self) -> int:
+        flags = ctypes.c_int32(0)
+        self._check(_lib.lfps_poll_status(self._ctx, ctypes.byref(flags), self._stream()))
+        return flags.value
+
+    def lfps_timing_enable(self, on: bool):
+        self._check(_lib.lfps_timing_enable(self._ctx, int(bool(on))))
+
+    def lfps_timing_read(self):
+        """-> {kernel name: (total ms, launches)} since the last read."""
+        ms = (ctypes.c_float * N_KERNELS)()
+        n = (ctypes.c_int32 * N_KERNELS)()
+        self._check(_lib.lfps_timing_read(self._ctx, ms, n, self._stream()))
+        return {name: (float(ms[i]), int(n[i])) for i, name in enumerate(kernel_names())}

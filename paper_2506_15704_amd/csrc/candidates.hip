@@ -1,0 +1,129 @@
+// S1 — candidate set of one (request, KV group) from the previous step's per-head Top-k
+// (Alg. 1 lines 6-7 in the memoryless form: vertical = same position, slash = position + 1,
+// both widened by the expansion radius; Sec. 4.2 stages 2-3).
+//
+// One workgroup per (b, g).  The set is built as a bitmap over positions in LDS: every valid
+// previous index ORs the (2r+2)-bit window [i-r, i+r+1] (clipped to [0, n)) into the words it
+// spans, which also dedupes within a head and across the G heads of the group.  A popcount +
+// block scan then assigns each word its output offset and the set bits are emitted in ascending
+// order, so the output is sorted and identical from run to run.
+#include "lfps_internal.h"
+
+namespace lfps {
+
+constexpr int kCandThreads = 1024;
+
+__device__ __forceinline__ void set_bit_range(uint32_t* bm, int lo, int hi) {  // inclusive, lo <= hi
+  int w0 = lo >> 5, w1 = hi >> 5;
+  for (int w = w0; w <= w1; ++w) {
+    int a = (w == w0) ? (lo & 31) : 0;
+    int b = (w == w1) ? (hi & 31) : 31;
+    uint32_t m = (b == 31 ? 0xFFFFFFFFu : ((1u << (b + 1)) - 1u)) & ~((1u << a) - 1u);
+    atomicOr(&bm[w], m);
+  }
+}
+
+__global__ __launch_bounds__(kCandThreads) void k_candidates(Shape s, const int32_t* __restrict__ prev_topk,
+                                                             const int32_t* __restrict__ kk,
+                                                             const int32_t* __restrict__ seq_lens,
+                                                             int32_t* __restrict__ cand,
+                                                             int32_t* __restrict__ cand_count,
+                                                             int32_t* __restrict__ flags) {
+  extern __shared__ uint32_t lds[];
+  __shared__ int wave_tot[kCandThreads / 64];
+  const int bg = blockIdx.x, b = bg / s.Hkv, g = bg % s.Hkv;
+  const int tid = threadIdx.x;
+  int n = seq_lens[b];
+  n = n < 0 ? 0 : (n > s.Lcap ? s.Lcap : n);
+  int kb = kk[b];
+  kb = kb < 0 ? 0 : (kb > s.kmax ? s.kmax : kb);
+  const int W = (n + 31) >> 5;
+  uint32_t* bm = lds;
+
+  for (int w = tid; w < W; w += kCandThreads) bm[w] = 0u;
+  __syncthreads();
+
+  const int r = s.radius;
+  const int32_t* pt = prev_topk + ((int64_t)b * s.Hq + (int64_t)g * s.G) * s.kmax;
+  for (int e = tid; e < s.G * kb; e += kCandThreads) {
+    int h = e / kb, j = e - h * kb;
+    int i = pt[(int64_t)h * s.kmax + j];
+    if (i >= 0 && i < n) {
+      int lo = i - r < 0 ? 0 : i - r;
+      int64_t hi64 = (int64_t)i + r + 1;
+      int hi = hi64 > n - 1 ? n - 1 : (int)hi64;
+      set_bit_range(bm, lo, hi);
+    }
+  }
+  if (tid == 0 && n > 0) {
+    if (s.n_recent > 0) set_bit_range(bm, n - s.n_recent < 0 ? 0 : n - s.n_recent, n - 1);
+    if (s.n_sink > 0) set_bit_range(bm, 0, (s.n_sink > n ? n : s.n_sink) - 1);
+  }
+  __syncthreads();
+
+  // each thread owns a contiguous slice of words
+  const int wpt = (W + kCandThreads - 1) / kCandThreads;
+  const int w_lo = tid * wpt, w_hi = (w_lo + wpt < W) ? w_lo + wpt : W;
+  int cnt = 0;
+  for (int w = w_lo; w < w_hi; ++w) cnt += __popc(bm[w]);
+
+  // block exclusive scan of cnt: in-wave inclusive scan, then wave totals
+  const int lane = tid & 63, wv = tid >> 6;
+  int inc = cnt;
+#pragma unroll
+  for (int d = 1; d < 64; d <<= 1) {
+    int o = __shfl_up(inc, d);
+    if (lane >= d) inc += o;
+  }
+  if (lane == 63) wave_tot[wv] = inc;
+  __syncthreads();
+  int base = 0, total = 0;
+#pragma unroll
+  for (int i = 0; i < kCandThreads / 64; ++i) {
+    int t = wave_tot[i];
+    if (i < wv) base += t;
+    total += t;
+  }
+  int off = base + inc - cnt;
+
+  int32_t* out = cand + (int64_t)bg * s.cand_cap;
+  for (int w = w_lo; w < w_hi; ++w) {
+    uint32_t bits = bm[w];
+    while (bits) {
+      int p = __ffs(bits) - 1;
+      bits &= bits - 1;
+      if (off < s.cand_cap) out[off] = (w << 5) + p;
+      ++off;
+    }
+  }
+  if (tid == 0) {
+    if (total > s.cand_cap) {
+      atomicOr(flags, LFPS_FLAG_CAND_OVERFLOW);
+      total = s.cand_cap;
+    }
+    cand_count[bg] = total;
+  }
+}
+
+static size_t candidates_lds_bytes(const Shape& s) {
+  size_t b = ((size_t)(s.Lcap + 31) / 32) * 4;
+  return b < 4 ? 4 : b;
+}
+
+// Called once per context at creation: raises the kernel's dynamic-LDS limit when the bitmap of
+// the longest sequence needs more than the default 64 KB.
+hipError_t configure_candidates(const Shape& s) {
+  const size_t lds_bytes = candidates_lds_bytes(s);
+  if (lds_bytes > 32 * 1024)
+    return hipFuncSetAttribute((const void*)k_candidates, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes);
+  return hipSuccess;
+}
+
+hipError_t launch_candidates(const Shape& s, const int32_t* prev_topk, const int32_t* k, const int32_t* seq_lens,
+                             int32_t* cand, int32_t* cand_count, int32_t* flags, hipStream_t st) {
+  hipLaunchKernelGGL(k_candidates, dim3(s.B * s.Hkv), dim3(kCandThreads), candidates_lds_bytes(s), st, s, prev_topk, k,
+                     seq_lens, cand, cand_count, flags);
+  return hipGetLastError();
+}
+
+}  // namespace lfps

@@ -1,0 +1,385 @@
+// The C ABI of liblfps: context, argument validation, workspace, per-kernel timing, and the
+// sequencing of the kernels for each entry point.  No arithmetic of the method lives here.
+#include <stdio.h>
+#include <string.h>
+
+#include <new>
+
+#include "lfps_internal.h"
+
+using namespace lfps;
+
+struct lfps_ctx {
+  lfps_config cfg;
+  Shape shape;
+  int n_split_sparse, n_split_full;
+  // workspace (device)
+  float* score;        // [B, Hq, score_stride]
+  int32_t* cand;       // [B, Hkv, cand_cap]
+  int32_t* cand_count; // [B, Hkv]
+  float* sel_score;    // [B, Hq, kmax]
+  float* part;         // split partials (max of the two layouts)
+  int32_t* flags;      // [1]
+  int64_t ws_bytes;
+  // timing
+  int timing_on;
+  int n_timed;
+  hipEvent_t ev[LFPS_TIMING_MAX_LAUNCHES][2];
+  int8_t ev_slot[LFPS_TIMING_MAX_LAUNCHES];
+  int events_made;
+  char err[512];
+};
+
+static thread_local char g_create_err[512] = "";
+
+static const char* const kKernelNames[LFPS_N_KERNELS] = {
+    "candidates", "gather_score", "select", "sparse_attn", "attn_merge",
+    "dense_score", "full_attn", "full_merge", "head_score"};
+
+namespace {
+
+struct Sizes {
+  int32_t G, cand_cap, score_stride, n_split_sparse, n_split_full;
+  int64_t score_b, cand_b, count_b, sel_b, part_b, total;
+};
+
+int64_t align256(int64_t x) { return (x + 255) & ~(int64_t)255; }
+
+int check_config(const lfps_config* c, Sizes* z, char* err, size_t errn) {
+#define BAD(...)                      \
+  do {                                \
+    snprintf(err, errn, __VA_ARGS__); \
+    return LFPS_EINVAL;               \
+  } while (0)
+  if (!c) BAD("config is NULL");
+  if (c->batch < 1) BAD("batch must be >= 1 (got %d)", c->batch);
+  if (c->n_kv_heads < 1 || c->n_q_heads < 1 || c->n_q_heads % c->n_kv_heads != 0)
+    BAD("n_q_heads (%d) must be a positive multiple of n_kv_heads (%d)", c->n_q_heads, c->n_kv_heads);
+  const int G = c->n_q_heads / c->n_kv_heads;
+  if (G != 1 && G != 2 && G != 4) BAD("heads per KV group must be 1, 2 or 4 (got %d)", G);
+  if (c->head_dim != kD) BAD("head_dim must be %d (got %d)", kD, c->head_dim);
+  if (c->kv_dtype != LFPS_F32 && c->kv_dtype != LFPS_BF16) BAD("kv_dtype must be LFPS_F32 or LFPS_BF16");
+  if (c->max_seq_len < 1) BAD("max_seq_len must be >= 1");
+  if (c->max_k < 1 || c->max_k > c->max_seq_len) BAD("max_k must be in [1, max_seq_len]");
+  if (c->radius < 0 || c->n_recent < 0 || c->n_sink < 0) BAD("radius, n_recent, n_sink must be >= 0");
+  if (c->cand_cap < 0) BAD("cand_cap must be >= 0");
+  if (c->device < 0) BAD("device must be >= 0");
+#undef BAD
+  // LDS bitmap of the candidate kernel: one bit per position, 160 KB of LDS per workgroup
+  if (((int64_t)c->max_seq_len + 31) / 32 * 4 > 156 * 1024) {
+    snprintf(err, errn, "max_seq_len %d exceeds the candidate bitmap capacity (%d positions)", c->max_seq_len,
+             156 * 1024 * 8);
+    return LFPS_ECAP;
+  }
+  int64_t bound = (int64_t)G * c->max_k * (2 * (int64_t)c->radius + 2) + c->n_recent + c->n_sink;
+  if (bound > c->max_seq_len) bound = c->max_seq_len;
+  z->G = G;
+  z->cand_cap = c->cand_cap > 0 ? c->cand_cap : (int32_t)bound;
+  if (z->cand_cap > c->max_seq_len) z->cand_cap = c->max_seq_len;
+  z->score_stride = (c->max_seq_len + 63) & ~63;    // holds candidate scores and dense scores
+  Shape s{};
+  s.B = c->batch; s.Hq = c->n_q_heads; s.Hkv = c->n_kv_heads; s.G = G;
+  s.Lcap = c->max_seq_len; s.kmax = c->max_k; s.cand_cap = z->cand_cap;
+  z->n_split_sparse = sparse_attn_splits(s);
+  z->n_split_full = full_attn_splits(s);
+  z->score_b = align256((int64_t)c->batch * c->n_q_heads * z->score_stride * 4);
+  z->cand_b = align256((int64_t)c->batch * c->n_kv_heads * z->cand_cap * 4);
+  z->count_b = align256((int64_t)c->batch * c->n_kv_heads * 4);
+  z->sel_b = align256((int64_t)c->batch * c->n_q_heads * c->max_k * 4);
+  int64_t p_sparse = (int64_t)c->batch * c->n_q_heads * z->n_split_sparse * (kD + 1) * 4;
+  int64_t p_full = (int64_t)c->batch * c->n_kv_heads * z->n_split_full * G * (kD + 2) * 4;
+  z->part_b = align256(p_sparse > p_full ? p_sparse : p_full);
+  z->total = z->score_b + z->cand_b + z->count_b + z->sel_b + z->part_b + 256;
+  return LFPS_OK;
+}
+
+int fail(lfps_ctx* ctx, int code, const char* what, hipError_t e = hipSuccess) {
+  if (e != hipSuccess)
+    snprintf(ctx->err, sizeof ctx->err, "%s: %s", what, hipGetErrorString(e));
+  else
+    snprintf(ctx->err, sizeof ctx->err, "%s", what);
+  return code;
+}
+
+int check_kv(lfps_ctx* ctx, const lfps_kv* kv, bool need_v, KvView* out) {
+  if (!kv) return fail(ctx, LFPS_EINVAL, "kv view is NULL");
+  if (!kv->k) return fail(ctx, LFPS_EINVAL, "kv->k is NULL");
+  if (need_v && !kv->v) return fail(ctx, LFPS_EINVAL, "kv->v is NULL");
+  if (!kv->seq_lens) return fail(ctx, LFPS_EINVAL, "kv->seq_lens is NULL");
+  const int esz = ctx->cfg.kv_dtype == LFPS_BF16 ? 2 : 4;
+  if (kv->stride_n < kD || kv->stride_b < 0 || kv->stride_h < 0)
+    return fail(ctx, LFPS_EINVAL, "kv strides: stride_n must be >= head_dim, stride_b/stride_h >= 0");
+  if ((kv->stride_n * esz) % 16 || (kv->stride_b * esz) % 16 || (kv->stride_h * esz) % 16 ||
+      ((uintptr_t)kv->k % 16) || (kv->v && ((uintptr_t)kv->v % 16)))
+    return fail(ctx, LFPS_EINVAL, "kv rows must be 16-byte aligned (base pointers and strides)");
+  out->k = kv->k; out->v = kv->v;
+  out->stride_b = kv->stride_b; out->stride_h = kv->stride_h; out->stride_n = kv->stride_n;
+  out->seq_lens = kv->seq_lens;
+  return LFPS_OK;
+}
+
+// Brackets one launch with events when timing is on.
+struct Timed {
+  lfps_ctx* c;
+  hipStream_t st;
+  int i;
+  Timed(lfps_ctx* ctx, int slot, hipStream_t s) : c(ctx), st(s), i(-1) {
+    if (c->timing_on && c->n_timed < LFPS_TIMING_MAX_LAUNCHES) {
+      i = c->n_timed++;
+      c->ev_slot[i] = (int8_t)slot;
+      hipEventRecord(c->ev[i][0], st);
+    }
+  }
+  ~Timed() {
+    if (i >= 0) hipEventRecord(c->ev[i][1], st);
+  }
+};
+
+#define LAUNCH(ctx, slot, st, call)                                         \
+  do {                                                                      \
+    hipError_t e_;                                                          \
+    {                                                                       \
+      Timed t_(ctx, slot, st);                                              \
+      e_ = (call);                                                          \
+    }                                                                       \
+    if (e_ != hipSuccess) return fail(ctx, LFPS_EHIP, kKernelNames[slot], e_); \
+  } while (0)
+
+}  // namespace
+
+extern "C" {
+
+int lfps_workspace_bytes(const lfps_config* cfg, int64_t* out) {
+  Sizes z;
+  int rc = check_config(cfg, &z, g_create_err, sizeof g_create_err);
+  if (rc != LFPS_OK) return rc;
+  if (!out) return LFPS_EINVAL;
+  *out = z.total;
+  return LFPS_OK;
+}
+
+int lfps_create(const lfps_config* cfg, lfps_ctx** out) {
+  if (!out) {
+    snprintf(g_create_err, sizeof g_create_err, "out pointer is NULL");
+    return LFPS_EINVAL;
+  }
+  *out = nullptr;
+  Sizes z;
+  int rc = check_config(cfg, &z, g_create_err, sizeof g_create_err);
+  if (rc != LFPS_OK) return rc;
+  hipError_t e = hipSetDevice(cfg->device);
+  if (e != hipSuccess) {
+    snprintf(g_create_err, sizeof g_create_err, "hipSetDevice(%d): %s", cfg->device, hipGetErrorString(e));
+    return LFPS_EHIP;
+  }
+  lfps_ctx* c = new (std::nothrow) lfps_ctx();
+  if (!c) return LFPS_ENOMEM;
+  c->cfg = *cfg;
+  c->cfg.cand_cap = z.cand_cap;
+  Shape& s = c->shape;
+  s.B = cfg->batch; s.Hq = cfg->n_q_heads; s.Hkv = cfg->n_kv_heads; s.G = z.G;
+  s.Lcap = cfg->max_seq_len; s.kmax = cfg->max_k; s.cand_cap = z.cand_cap;
+  s.radius = cfg->radius; s.n_recent = cfg->n_recent; s.n_sink = cfg->n_sink;
+  s.score_stride = z.score_stride;
+  c->n_split_sparse = z.n_split_sparse;
+  c->n_split_full = z.n_split_full;
+  c->ws_bytes = z.total;
+  char* base = nullptr;
+  e = hipMalloc((void**)&base, (size_t)z.total);
+  if (e != hipSuccess) {
+    snprintf(g_create_err, sizeof g_create_err, "hipMalloc(%lld bytes): %s", (long long)z.total, hipGetErrorString(e));
+    delete c;
+    (void)hipGetLastError();
+    return LFPS_ENOMEM;
+  }
+  c->score = (float*)base;
+  c->cand = (int32_t*)(base + z.score_b);
+  c->cand_count = (int32_t*)(base + z.score_b + z.cand_b);
+  c->sel_score = (float*)(base + z.score_b + z.cand_b + z.count_b);
+  c->part = (float*)(base + z.score_b + z.cand_b + z.count_b + z.sel_b);
+  c->flags = (int32_t*)(base + z.score_b + z.cand_b + z.count_b + z.sel_b + z.part_b);
+  e = hipMemset(c->flags, 0, 256);
+  if (e == hipSuccess) e = configure_candidates(s);
+  if (e == hipSuccess) e = hipDeviceSynchronize();
+  if (e != hipSuccess) {
+    snprintf(g_create_err, sizeof g_create_err, "workspace setup: %s", hipGetErrorString(e));
+    (void)hipFree(base);
+    delete c;
+    return LFPS_EHIP;
+  }
+  *out = c;
+  return LFPS_OK;
+}
+
+int lfps_destroy(lfps_ctx* ctx) {
+  if (!ctx) return LFPS_EINVAL;
+  (void)hipSetDevice(ctx->cfg.device);
+  (void)hipDeviceSynchronize();
+  for (int i = 0; i < ctx->events_made; ++i) {
+    (void)hipEventDestroy(ctx->ev[i][0]);
+    (void)hipEventDestroy(ctx->ev[i][1]);
+  }
+  hipError_t e = hipFree(ctx->score);
+  delete ctx;
+  return e == hipSuccess ? LFPS_OK : LFPS_EHIP;
+}
+
+const char* lfps_last_error(const lfps_ctx* ctx) { return ctx ? ctx->err : g_create_err; }
+
+int32_t lfps_cand_cap(const lfps_ctx* ctx) { return ctx ? ctx->shape.cand_cap : 0; }
+
+const char* lfps_kernel_name(int32_t slot) {
+  return (slot >= 0 && slot < LFPS_N_KERNELS) ? kKernelNames[slot] : "";
+}
+
+int lfps_candidates(lfps_ctx* ctx, const int32_t* prev_topk, const int32_t* k, const int32_t* seq_lens,
+                    int32_t* cand, int32_t* cand_count, void* stream) {
+  if (!ctx) return LFPS_EINVAL;
+  if (!prev_topk || !k || !seq_lens || !cand || !cand_count)
+    return fail(ctx, LFPS_EINVAL, "lfps_candidates: NULL argument");
+  hipStream_t st = (hipStream_t)stream;
+  LAUNCH(ctx, LFPS_KERNEL_CANDIDATES, st,
+         launch_candidates(ctx->shape, prev_topk, k, seq_lens, cand, cand_count, ctx->flags, st));
+  return LFPS_OK;
+}
+
+int lfps_score_topk(lfps_ctx* ctx, const float* q, const lfps_kv* kv, const int32_t* cand,
+                    const int32_t* cand_count, const int32_t* k, int32_t* topk_idx, float* topk_score,
+                    float* cand_score, void* stream) {
+  if (!ctx) return LFPS_EINVAL;
+  if (!q || !cand || !cand_count || !k || !topk_idx) return fail(ctx, LFPS_EINVAL, "lfps_score_topk: NULL argument");
+  KvView v;
+  int rc = check_kv(ctx, kv, false, &v);
+  if (rc != LFPS_OK) return rc;
+  hipStream_t st = (hipStream_t)stream;
+  const Shape& s = ctx->shape;
+  float* sc = cand_score ? cand_score : ctx->score;
+  const int64_t stride = cand_score ? s.cand_cap : s.score_stride;
+  LAUNCH(ctx, LFPS_KERNEL_GATHER_SCORE, st,
+         launch_group_score(s, ctx->cfg.kv_dtype, q, v, cand, cand_count, sc, stride, st));
+  LAUNCH(ctx, LFPS_KERNEL_SELECT, st, launch_select(s, sc, stride, cand, cand_count, k, topk_idx, topk_score, st));
+  return LFPS_OK;
+}
+
+int lfps_sparse_attn(lfps_ctx* ctx, const float* q, const lfps_kv* kv, const int32_t* idx, const float* idx_score,
+                     const int32_t* k, float* out, void* stream) {
+  if (!ctx) return LFPS_EINVAL;
+  if (!idx || !k || !out) return fail(ctx, LFPS_EINVAL, "lfps_sparse_attn: NULL argument");
+  if (!idx_score && !q) return fail(ctx, LFPS_EINVAL, "lfps_sparse_attn: q is needed when idx_score is NULL");
+  KvView v;
+  int rc = check_kv(ctx, kv, true, &v);
+  if (rc != LFPS_OK) return rc;
+  hipStream_t st = (hipStream_t)stream;
+  const Shape& s = ctx->shape;
+  if (!idx_score) {
+    LAUNCH(ctx, LFPS_KERNEL_HEAD_SCORE, st, launch_head_score(s, ctx->cfg.kv_dtype, q, v, idx, k, ctx->sel_score, st));
+    idx_score = ctx->sel_score;
+  }
+  LAUNCH(ctx, LFPS_KERNEL_SPARSE_ATTN, st,
+         launch_sparse_attn(s, ctx->cfg.kv_dtype, v, idx, idx_score, k, ctx->part, st));
+  LAUNCH(ctx, LFPS_KERNEL_ATTN_MERGE, st, launch_attn_merge(s, k, ctx->part, out, st));
+  return LFPS_OK;
+}
+
+int lfps_step(lfps_ctx* ctx, const float* q, const lfps_kv* kv, const int32_t* prev_topk, const int32_t* k,
+              int32_t* topk_idx, float* topk_score, float* out, void* stream) {
+  if (!ctx) return LFPS_EINVAL;
+  if (!q || !prev_topk || !k || !topk_idx || !out) return fail(ctx, LFPS_EINVAL, "lfps_step: NULL argument");
+  const Shape& s = ctx->shape;
+  {
+    const int64_t nn = (int64_t)s.B * s.Hq * s.kmax;
+    if ((prev_topk < topk_idx + nn) && (topk_idx < prev_topk + nn))
+      return fail(ctx, LFPS_EINVAL, "lfps_step: prev_topk and topk_idx overlap");
+  }
+  KvView v;
+  int rc = check_kv(ctx, kv, true, &v);
+  if (rc != LFPS_OK) return rc;
+  hipStream_t st = (hipStream_t)stream;
+  float* sel = topk_score ? topk_score : ctx->sel_score;
+  LAUNCH(ctx, LFPS_KERNEL_CANDIDATES, st,
+         launch_candidates(s, prev_topk, k, v.seq_lens, ctx->cand, ctx->cand_count, ctx->flags, st));
+  LAUNCH(ctx, LFPS_KERNEL_GATHER_SCORE, st,
+         launch_group_score(s, ctx->cfg.kv_dtype, q, v, ctx->cand, ctx->cand_count, ctx->score, s.score_stride, st));
+  LAUNCH(ctx, LFPS_KERNEL_SELECT, st,
+         launch_select(s, ctx->score, s.score_stride, ctx->cand, ctx->cand_count, k, topk_idx, sel, st));
+  LAUNCH(ctx, LFPS_KERNEL_SPARSE_ATTN, st, launch_sparse_attn(s, ctx->cfg.kv_dtype, v, topk_idx, sel, k, ctx->part, st));
+  LAUNCH(ctx, LFPS_KERNEL_ATTN_MERGE, st, launch_attn_merge(s, k, ctx->part, out, st));
+  return LFPS_OK;
+}
+
+int lfps_full_attn_decode(lfps_ctx* ctx, const float* q, const lfps_kv* kv, float* out, void* stream) {
+  if (!ctx) return LFPS_EINVAL;
+  if (!q || !out) return fail(ctx, LFPS_EINVAL, "lfps_full_attn_decode: NULL argument");
+  KvView v;
+  int rc = check_kv(ctx, kv, true, &v);
+  if (rc != LFPS_OK) return rc;
+  hipStream_t st = (hipStream_t)stream;
+  const Shape& s = ctx->shape;
+  LAUNCH(ctx, LFPS_KERNEL_FULL_ATTN, st,
+         launch_full_attn(s, ctx->cfg.kv_dtype, q, v, ctx->part, ctx->n_split_full, st));
+  LAUNCH(ctx, LFPS_KERNEL_FULL_MERGE, st, launch_full_merge(s, v.seq_lens, ctx->part, ctx->n_split_full, out, st));
+  return LFPS_OK;
+}
+
+int lfps_exact_topk(lfps_ctx* ctx, const float* q, const lfps_kv* kv, const int32_t* k, int32_t* topk_idx,
+                    float* topk_score, void* stream) {
+  if (!ctx) return LFPS_EINVAL;
+  if (!q || !k || !topk_idx) return fail(ctx, LFPS_EINVAL, "lfps_exact_topk: NULL argument");
+  KvView v;
+  int rc = check_kv(ctx, kv, false, &v);
+  if (rc != LFPS_OK) return rc;
+  hipStream_t st = (hipStream_t)stream;
+  const Shape& s = ctx->shape;
+  LAUNCH(ctx, LFPS_KERNEL_DENSE_SCORE, st,
+         launch_group_score(s, ctx->cfg.kv_dtype, q, v, nullptr, nullptr, ctx->score, s.score_stride, st));
+  LAUNCH(ctx, LFPS_KERNEL_SELECT, st,
+         launch_select(s, ctx->score, s.score_stride, nullptr, v.seq_lens, k, topk_idx, topk_score, st));
+  return LFPS_OK;
+}
+
+int lfps_poll_status(lfps_ctx* ctx, int32_t* flags, void* stream) {
+  if (!ctx) return LFPS_EINVAL;
+  if (!flags) return fail(ctx, LFPS_EINVAL, "lfps_poll_status: NULL argument");
+  hipStream_t st = (hipStream_t)stream;
+  hipError_t e = hipMemcpyAsync(flags, ctx->flags, 4, hipMemcpyDeviceToHost, st);
+  if (e == hipSuccess) e = hipMemsetAsync(ctx->flags, 0, 4, st);
+  if (e == hipSuccess) e = hipStreamSynchronize(st);
+  if (e != hipSuccess) return fail(ctx, LFPS_EHIP, "lfps_poll_status", e);
+  return LFPS_OK;
+}
+
+int lfps_timing_enable(lfps_ctx* ctx, int32_t on) {
+  if (!ctx) return LFPS_EINVAL;
+  if (on && ctx->events_made == 0) {
+    for (int i = 0; i < LFPS_TIMING_MAX_LAUNCHES; ++i) {
+      hipError_t e = hipEventCreate(&ctx->ev[i][0]);
+      if (e == hipSuccess) e = hipEventCreate(&ctx->ev[i][1]);
+      if (e != hipSuccess) return fail(ctx, LFPS_EHIP, "hipEventCreate", e);
+      ctx->events_made = i + 1;
+    }
+  }
+  ctx->timing_on = on ? 1 : 0;
+  return LFPS_OK;
+}
+
+int lfps_timing_read(lfps_ctx* ctx, float* ms, int32_t* launches, void* stream) {
+  if (!ctx) return LFPS_EINVAL;
+  if (!ms || !launches) return fail(ctx, LFPS_EINVAL, "lfps_timing_read: NULL argument");
+  hipError_t e = hipStreamSynchronize((hipStream_t)stream);
+  if (e != hipSuccess) return fail(ctx, LFPS_EHIP, "lfps_timing_read", e);
+  for (int i = 0; i < LFPS_N_KERNELS; ++i) {
+    ms[i] = 0.f;
+    launches[i] = 0;
+  }
+  for (int i = 0; i < ctx->n_timed; ++i) {
+    float t = 0.f;
+    e = hipEventElapsedTime(&t, ctx->ev[i][0], ctx->ev[i][1]);
+    if (e != hipSuccess) return fail(ctx, LFPS_EHIP, "hipEventElapsedTime", e);
+    ms[ctx->ev_slot[i]] += t;
+    launches[ctx->ev_slot[i]] += 1;
+  }
+  ctx->n_timed = 0;
+  return LFPS_OK;
+}
+
+}  // extern "C"

@@ -1,0 +1,76 @@
+// Internal declarations shared by the translation units of liblfps (not part of the ABI).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "lfps.h"
+
+namespace lfps {
+
+constexpr int kD = 128;           // head_dim the kernels are written for
+constexpr int kMaxSplits = 64;    // upper bound of split-K partials per head (full attention)
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+
+// Strided view of K or V in elements, resolved for one launch.
+struct KvView {
+  const void* k;
+  const void* v;
+  int64_t stride_b, stride_h, stride_n;
+  const int32_t* seq_lens;
+};
+
+// Shapes every kernel needs.
+struct Shape {
+  int32_t B, Hq, Hkv, G;
+  int32_t Lcap, kmax, cand_cap;
+  int32_t radius, n_recent, n_sink;
+  int32_t score_stride;   // row length of the workspace score buffer [B, Hq, score_stride]
+};
+
+// ---- kernel launchers (each enqueues on `st` and returns the launch error) -------------
+hipError_t configure_candidates(const Shape& s);
+hipError_t launch_candidates(const Shape& s, const int32_t* prev_topk, const int32_t* k, const int32_t* seq_lens,
+                             int32_t* cand, int32_t* cand_count, int32_t* flags, hipStream_t st);
+
+// Scores of candidate rows (cand != NULL) or of all rows 0..n_b-1 (cand == NULL) for the G heads
+// of each KV group.  score is [B, Hq, score_stride].
+hipError_t launch_group_score(const Shape& s, int dtype, const float* q, const KvView& kv, const int32_t* cand,
+                              const int32_t* cand_count, float* score, int64_t score_stride, hipStream_t st);
+
+// Per (b, h): the k_b best of score[b,h,0:count]; count = cand_count[b, g(h)] when cand != NULL,
+// else seq_lens[b].  Writes positions (ascending) and their scores.
+hipError_t launch_select(const Shape& s, const float* score, int64_t score_stride, const int32_t* cand,
+                         const int32_t* count, const int32_t* k, int32_t* topk_idx, float* topk_score,
+                         hipStream_t st);
+
+// Scores of idx[b,h,0:k_b] rows against q[b,h] (one head at a time, no group sharing).
+hipError_t launch_head_score(const Shape& s, int dtype, const float* q, const KvView& kv, const int32_t* idx,
+                             const int32_t* k, float* idx_score, hipStream_t st);
+
+// Sparse attention partials + merge.  part is [B*Hq, n_split, D+1] floats.
+int sparse_attn_splits(const Shape& s);
+hipError_t launch_sparse_attn(const Shape& s, int dtype, const KvView& kv, const int32_t* idx, const float* idx_score,
+                              const int32_t* k, float* part, hipStream_t st);
+hipError_t launch_attn_merge(const Shape& s, const int32_t* k, const float* part, float* out, hipStream_t st);
+
+// Full attention: split partials [B*Hkv, n_split, G, D+2] + merge.
+int full_attn_splits(const Shape& s);
+hipError_t launch_full_attn(const Shape& s, int dtype, const float* q, const KvView& kv, float* part, int n_split,
+                            hipStream_t st);
+hipError_t launch_full_merge(const Shape& s, const int32_t* seq_lens, const float* part, int n_split, float* out,
+                             hipStream_t st);
+
+// ---- small device helpers ------------------------------------------------------------
+__device__ __forceinline__ float bf16_lo(uint32_t w) { return __uint_as_float(w << 16); }
+__device__ __forceinline__ float bf16_hi(uint32_t w) { return __uint_as_float(w & 0xFFFF0000u); }
+
+// Order-preserving map fp32 -> uint32 (larger float <=> larger key).
+__device__ __forceinline__ uint32_t f2key(float f) {
+  uint32_t u = __float_as_uint(f);
+  return (u & 0x80000000u) ? ~u : (u | 0x80000000u);
+}
+
+}  // namespace lfps

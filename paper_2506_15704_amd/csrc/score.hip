@@ -1,0 +1,284 @@
+// S2 — scores q . K_j / sqrt(D) of selected rows for the G query heads that share a KV head
+// (Alg. 1 line 8; Sec. 1 Step 1 restricted to the candidates).  Also the dense variant over all
+// rows (the exact Top-k baseline's Step 1), and a per-head variant for arbitrary index lists.
+//
+// The path is bound by the bytes of the K rows it gathers; the arithmetic is kept off the
+// vector ALU so it cannot become the limit:
+//   bf16 cache: one wave handles 16 rows at a time with v_mfma_f32_16x16x32_bf16.  The B operand
+//     is the K tile exactly as it lies in memory (lane (j, kb) loads 16 bytes = channels
+//     [32*kk + 8*kb, +8) of row j), so a row is fetched once for all G heads.  The A operand is
+//     the query: each fp32 q is split into three bf16 terms q = q0 + q1 + q2 (24 mantissa bits),
+//     and A's row 4*h + t holds term t of head h.  bf16 x bf16 products are exact in fp32, so
+//     the sum D[4h+0] + D[4h+1] + D[4h+2] is the fp32-accumulated dot product with the fp32
+//     query; it lands in lane group h without any cross-lane reduction.
+//   fp32 cache: 16 lanes per row, 8 channels each, fp32 FMAs and a 4-step xor-shuffle reduce.
+#include "lfps_internal.h"
+
+namespace lfps {
+
+constexpr int kScoreThreads = 256;           // 4 waves
+constexpr int kRowsPerWaveIter = 64;         // rows a wave scores per loop iteration
+
+// Three-term bf16 split of x: returns term t (0,1,2) as bf16 bits; t == 3 -> 0.
+__device__ __forceinline__ uint16_t bf16_rne_bits(float x) {
+  uint32_t u = __float_as_uint(x);
+  u += 0x7FFFu + ((u >> 16) & 1u);
+  return (uint16_t)(u >> 16);
+}
+__device__ __forceinline__ uint16_t split_term(float x, int t) {
+  uint16_t a = bf16_rne_bits(x);
+  if (t == 0) return a;
+  float r1 = x - __uint_as_float((uint32_t)a << 16);
+  uint16_t b = bf16_rne_bits(r1);
+  if (t == 1) return b;
+  float r2 = r1 - __uint_as_float((uint32_t)b << 16);
+  uint16_t c = bf16_rne_bits(r2);
+  return t == 2 ? c : (uint16_t)0;
+}
+
+union Bf16x8Bits {
+  bf16x8 v;
+  u32x4 u;
+  uint16_t h[8];
+};
+
+// ----------------------------------------------------------------------------- bf16, MFMA
+// grid: (tiles_x, B*Hkv).  GATHER: rows come from cand[bg, 0:count]; else rows are 0..n_b-1.
+template <int G, bool GATHER>
+__global__ __launch_bounds__(kScoreThreads) void k_group_score_bf16(Shape s, const float* __restrict__ q,
+                                                                    const __bf16* __restrict__ K, int64_t stride_b,
+                                                                    int64_t stride_h, int64_t stride_n,
+                                                                    const int32_t* __restrict__ seq_lens,
+                                                                    const int32_t* __restrict__ cand,
+                                                                    const int32_t* __restrict__ cand_count,
+                                                                    float* __restrict__ score, int64_t score_stride,
+                                                                    float scale) {
+  const int bg = blockIdx.y, b = bg / s.Hkv, g = bg % s.Hkv;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int j = lane & 15, kb = lane >> 4;
+  int n = seq_lens[b];
+  n = n < 0 ? 0 : (n > s.Lcap ? s.Lcap : n);
+  int count = GATHER ? cand_count[bg] : n;
+  if (GATHER) count = count < 0 ? 0 : (count > s.cand_cap ? s.cand_cap : count);
+  const int first = (blockIdx.x * 4 + wave) * kRowsPerWaveIter;
+  if (first >= count) return;
+
+  // A operand: row m = j of the 16x32 A tile of step kk holds term (m & 3) of head (m >> 2),
+  // channels [32*kk + 8*kb, +8).  Heads >= G contribute zeros.
+  bf16x8 A[4];
+  {
+    const int h = j >> 2, t = j & 3;
+    const float* qh = q + ((int64_t)b * s.Hq + (int64_t)g * G + (h < G ? h : 0)) * kD;
+#pragma unroll
+    for (int kk = 0; kk < 4; ++kk) {
+      Bf16x8Bits a;
+#pragma unroll
+      for (int c = 0; c < 8; ++c) {
+        float x = qh[32 * kk + 8 * kb + c];
+        a.h[c] = (h < G) ? split_term(x, t) : (uint16_t)0;
+      }
+      A[kk] = a.v;
+    }
+  }
+
+  const __bf16* Kbg = K + (int64_t)b * stride_b + (int64_t)g * stride_h;
+  const int32_t* cbg = GATHER ? cand + (int64_t)bg * s.cand_cap : nullptr;
+  float* sc = score + ((int64_t)b * s.Hq + (int64_t)g * G + kb) * score_stride;   // lane group kb -> head kb
+  const int step = gridDim.x * 4 * kRowsPerWaveIter;
+
+  for (int base = first; base < count; base += step) {
+    int my_row = -1;
+    if (base + lane < count) my_row = GATHER ? cbg[base + lane] : base + lane;
+    bf16x8 Bt[4][4];
+#pragma unroll
+    for (int t = 0; t < 4; ++t) {
+      int row = __shfl(my_row, 16 * t + j);
+      row = (row < 0 || row >= n) ? 0 : row;            // padding slots read row 0 (n > 0 here) and are not stored
+      const bf16x8* p = reinterpret_cast<const bf16x8*>(Kbg + (int64_t)row * stride_n) + kb;
+#pragma unroll
+      for (int kk = 0; kk < 4; ++kk) Bt[t][kk] = p[4 * kk];
+    }
+#pragma unroll
+    for (int t = 0; t < 4; ++t) {
+      f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+      for (int kk = 0; kk < 4; ++kk) acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(A[kk], Bt[t][kk], acc, 0, 0, 0);
+      // lane (j, kb): D rows 4*kb .. 4*kb+3 = the three terms (and a zero row) of head kb, column j
+      float v = ((acc[0] + acc[1]) + acc[2]) * scale;
+      int slot = base + 16 * t + j;
+      if (kb < G && slot < count) sc[slot] = v;
+    }
+  }
+}
+
+// ----------------------------------------------------------------------------- fp32, vector ALU
+template <int G, bool GATHER>
+__global__ __launch_bounds__(kScoreThreads) void k_group_score_f32(Shape s, const float* __restrict__ q,
+                                                                   const float* __restrict__ K, int64_t stride_b,
+                                                                   int64_t stride_h, int64_t stride_n,
+                                                                   const int32_t* __restrict__ seq_lens,
+                                                                   const int32_t* __restrict__ cand,
+                                                                   const int32_t* __restrict__ cand_count,
+                                                                   float* __restrict__ score, int64_t score_stride,
+                                                                   float scale) {
+  const int bg = blockIdx.y, b = bg / s.Hkv, g = bg % s.Hkv;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int j = lane & 15, rs = lane >> 4;     // 16 lanes per row, 4 rows per wave instruction
+  int n = seq_lens[b];
+  n = n < 0 ? 0 : (n > s.Lcap ? s.Lcap : n);
+  int count = GATHER ? cand_count[bg] : n;
+  if (GATHER) count = count < 0 ? 0 : (count > s.cand_cap ? s.cand_cap : count);
+  const int first = (blockIdx.x * 4 + wave) * kRowsPerWaveIter;
+  if (first >= count) return;
+
+  float qr[G][8];
+#pragma unroll
+  for (int h = 0; h < G; ++h) {
+    const float* qh = q + ((int64_t)b * s.Hq + (int64_t)g * G + h) * kD + 8 * j;
+#pragma unroll
+    for (int c = 0; c < 8; ++c) qr[h][c] = qh[c];
+  }
+  const float* Kbg = K + (int64_t)b * stride_b + (int64_t)g * stride_h;
+  const int32_t* cbg = GATHER ? cand + (int64_t)bg * s.cand_cap : nullptr;
+  float* sc = score + ((int64_t)b * s.Hq + (int64_t)g * G) * score_stride;
+  const int step = gridDim.x * 4 * kRowsPerWaveIter;
+
+  for (int base = first; base < count; base += step) {
+    int my_row = -1;
+    if (base + lane < count) my_row = GATHER ? cbg[base + lane] : base + lane;
+#pragma unroll 4
+    for (int t = 0; t < 16; ++t) {
+      int row = __shfl(my_row, 4 * t + rs);
+      bool ok = row >= 0 && row < n;
+      const float4* p = reinterpret_cast<const float4*>(Kbg + (int64_t)(ok ? row : 0) * stride_n) + 2 * j;
+      float4 x0 = p[0], x1 = p[1];
+      float acc[G];
+#pragma unroll
+      for (int h = 0; h < G; ++h) {
+        float a = qr[h][0] * x0.x;
+        a = fmaf(qr[h][1], x0.y, a);
+        a = fmaf(qr[h][2], x0.z, a);
+        a = fmaf(qr[h][3], x0.w, a);
+        a = fmaf(qr[h][4], x1.x, a);
+        a = fmaf(qr[h][5], x1.y, a);
+        a = fmaf(qr[h][6], x1.z, a);
+        a = fmaf(qr[h][7], x1.w, a);
+        acc[h] = a;
+      }
+#pragma unroll
+      for (int d = 1; d < 16; d <<= 1) {
+#pragma unroll
+        for (int h = 0; h < G; ++h) acc[h] += __shfl_xor(acc[h], d);
+      }
+      int slot = base + 4 * t + rs;
+      if (ok && slot < count && j < G) {
+        float v = acc[0];
+#pragma unroll
+        for (int h = 1; h < G; ++h) v = (j == h) ? acc[h] : v;
+        sc[(int64_t)j * score_stride + slot] = v * scale;
+      }
+    }
+  }
+}
+
+// ----------------------------------------------------------------------------- per-head index lists
+// Scores of idx[b,h,0:k_b] against q[b,h]; 16 lanes per row.  Used only when the caller of the
+// sparse attention does not supply scores.  grid: (ceil(kmax/256), B*Hq).
+template <typename T>
+__global__ __launch_bounds__(256) void k_head_score(Shape s, const float* __restrict__ q, const T* __restrict__ K,
+                                                    int64_t stride_b, int64_t stride_h, int64_t stride_n,
+                                                    const int32_t* __restrict__ seq_lens,
+                                                    const int32_t* __restrict__ idx, const int32_t* __restrict__ kk,
+                                                    float* __restrict__ out, float scale) {
+  const int bh = blockIdx.y, b = bh / s.Hq, h = bh % s.Hq, g = h / s.G;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int j = lane & 15, rs = lane >> 4;
+  int n = seq_lens[b];
+  n = n < 0 ? 0 : (n > s.Lcap ? s.Lcap : n);
+  int kb = kk[b];
+  kb = kb < 0 ? 0 : (kb > s.kmax ? s.kmax : kb);
+  const int base = (blockIdx.x * 4 + wave) * 64;
+  if (base >= kb) return;
+  float qr[8];
+  const float* qh = q + (int64_t)bh * kD + 8 * j;
+#pragma unroll
+  for (int c = 0; c < 8; ++c) qr[c] = qh[c];
+  const T* Kbg = K + (int64_t)b * stride_b + (int64_t)g * stride_h;
+  int my_row = (base + lane < kb) ? idx[(int64_t)bh * s.kmax + base + lane] : -1;
+  for (int t = 0; t < 16; ++t) {
+    int row = __shfl(my_row, 4 * t + rs);
+    bool ok = row >= 0 && row < n;
+    const T* p = Kbg + (int64_t)(ok ? row : 0) * stride_n + 8 * j;
+    float x[8];
+    if constexpr (sizeof(T) == 2) {
+      u32x4 w = *reinterpret_cast<const u32x4*>(p);
+#pragma unroll
+      for (int c = 0; c < 4; ++c) {
+        x[2 * c] = bf16_lo(w[c]);
+        x[2 * c + 1] = bf16_hi(w[c]);
+      }
+    } else {
+      float4 x0 = reinterpret_cast<const float4*>(p)[0], x1 = reinterpret_cast<const float4*>(p)[1];
+      x[0] = x0.x; x[1] = x0.y; x[2] = x0.z; x[3] = x0.w;
+      x[4] = x1.x; x[5] = x1.y; x[6] = x1.z; x[7] = x1.w;
+    }
+    float a = qr[0] * x[0];
+#pragma unroll
+    for (int c = 1; c < 8; ++c) a = fmaf(qr[c], x[c], a);
+#pragma unroll
+    for (int d = 1; d < 16; d <<= 1) a += __shfl_xor(a, d);
+    int slot = base + 4 * t + rs;
+    if (j == 0 && slot < kb) out[(int64_t)bh * s.kmax + slot] = ok ? a * scale : -INFINITY;
+  }
+}
+
+// ----------------------------------------------------------------------------- launchers
+template <int G, bool GATHER>
+static hipError_t launch_gs(const Shape& s, int dtype, const float* q, const KvView& kv, const int32_t* cand,
+                            const int32_t* cand_count, float* score, int64_t score_stride, hipStream_t st) {
+  const int rows_max = GATHER ? s.cand_cap : s.Lcap;
+  const int per_block = 4 * kRowsPerWaveIter;
+  int tiles = (rows_max + per_block - 1) / per_block;
+  // enough workgroups to fill 256 CUs several times over, but no more than there are tiles
+  int want = (256 * 8 + s.B * s.Hkv - 1) / (s.B * s.Hkv);
+  int gx = tiles < want ? tiles : want;
+  if (gx < 1) gx = 1;
+  dim3 grid(gx, s.B * s.Hkv), block(kScoreThreads);
+  const float scale = 0.08838834764831845f;   // 1/sqrt(128)
+  if (dtype == LFPS_BF16)
+    hipLaunchKernelGGL((k_group_score_bf16<G, GATHER>), grid, block, 0, st, s, q, (const __bf16*)kv.k, kv.stride_b,
+                       kv.stride_h, kv.stride_n, kv.seq_lens, cand, cand_count, score, score_stride, scale);
+  else
+    hipLaunchKernelGGL((k_group_score_f32<G, GATHER>), grid, block, 0, st, s, q, (const float*)kv.k, kv.stride_b,
+                       kv.stride_h, kv.stride_n, kv.seq_lens, cand, cand_count, score, score_stride, scale);
+  return hipGetLastError();
+}
+
+hipError_t launch_group_score(const Shape& s, int dtype, const float* q, const KvView& kv, const int32_t* cand,
+                              const int32_t* cand_count, float* score, int64_t score_stride, hipStream_t st) {
+  const bool gather = cand != nullptr;
+  switch (s.G) {
+    case 1: return gather ? launch_gs<1, true>(s, dtype, q, kv, cand, cand_count, score, score_stride, st)
+                          : launch_gs<1, false>(s, dtype, q, kv, cand, cand_count, score, score_stride, st);
+    case 2: return gather ? launch_gs<2, true>(s, dtype, q, kv, cand, cand_count, score, score_stride, st)
+                          : launch_gs<2, false>(s, dtype, q, kv, cand, cand_count, score, score_stride, st);
+    case 4: return gather ? launch_gs<4, true>(s, dtype, q, kv, cand, cand_count, score, score_stride, st)
+                          : launch_gs<4, false>(s, dtype, q, kv, cand, cand_count, score, score_stride, st);
+    default: return hipErrorInvalidValue;
+  }
+}
+
+hipError_t launch_head_score(const Shape& s, int dtype, const float* q, const KvView& kv, const int32_t* idx,
+                             const int32_t* k, float* idx_score, hipStream_t st) {
+  dim3 grid((s.kmax + 255) / 256, s.B * s.Hq), block(256);
+  const float scale = 0.08838834764831845f;
+  if (dtype == LFPS_BF16)
+    hipLaunchKernelGGL((k_head_score<uint16_t>), grid, block, 0, st, s, q, (const uint16_t*)kv.k, kv.stride_b,
+                       kv.stride_h, kv.stride_n, kv.seq_lens, idx, k, idx_score, scale);
+  else
+    hipLaunchKernelGGL((k_head_score<float>), grid, block, 0, st, s, q, (const float*)kv.k, kv.stride_b, kv.stride_h,
+                       kv.stride_n, kv.seq_lens, idx, k, idx_score, scale);
+  return hipGetLastError();
+}
+
+}  // namespace lfps

@@ -1,0 +1,57 @@
+"""The C-ABI library loads on a machine without a GPU and exports exactly what the header declares."""
+import ctypes
+import os
+import re
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+HEADER = os.path.join(ROOT, "include", "lfps.h")
+
+
+def _declared():
+    src = open(HEADER).read()
+    src = re.sub(r"/\*.*?\*/", "", src, flags=re.S)
+    return sorted(set(re.findall(r"\b(lfps_[a-z_0-9]+)\s*\(", src)))
+
+
+def test_header_declares_the_named_entry_points():
+    names = _declared()
+    for must in ("lfps_create", "lfps_candidates", "lfps_score_topk", "lfps_sparse_attn", "lfps_step",
+                 "lfps_full_attn_decode", "lfps_exact_topk", "lfps_destroy"):
+        assert must in names
+
+
+def test_library_exports_every_declared_symbol():
+    from paper_2506_15704_amd import binding
+    lib = ctypes.CDLL(binding.LIB_PATH)
+    for name in _declared():
+        assert hasattr(lib, name), f"{name} declared in lfps.h but not exported"
+
+
+def test_binding_covers_every_declared_symbol():
+    from paper_2506_15704_amd import binding
+    for name in _declared():
+        assert hasattr(binding._lib, name)
+        assert getattr(binding._lib, name).argtypes is not None, f"{name} has no ctypes signature"
+
+
+def test_config_validation_without_gpu():
+    from paper_2506_15704_amd import binding as b
+    good = dict(batch=2, n_q_heads=32, n_kv_heads=8, head_dim=128, kv_dtype=1, max_seq_len=4096, max_k=128,
+                radius=2, n_recent=1, n_sink=0, cand_cap=0, device=0)
+    assert b.workspace_bytes(**good) > 0
+    for bad in (dict(head_dim=64), dict(n_q_heads=24), dict(batch=0), dict(max_k=0), dict(max_k=5000),
+                dict(radius=-1), dict(kv_dtype=7), dict(n_q_heads=64)):
+        with pytest.raises(b.LfpsError) as ei:
+            b.workspace_bytes(**{**good, **bad})
+        assert ei.value.code == b.LFPS_EINVAL
+    with pytest.raises(b.LfpsError) as ei:
+        b.workspace_bytes(**{**good, "max_seq_len": 3_000_000})
+    assert ei.value.code == b.LFPS_ECAP
+
+
+def test_kernel_names():
+    from paper_2506_15704_amd import binding as b
+    names = b.kernel_names()
+    assert len(names) == b.N_KERNELS and names[0] == "candidates" and "gather_score" in names
