@@ -1,0 +1,298 @@
+#!/usr/bin/env python3
+"""Benchmark of the LFPS decode-step hot path on one MI355X.
+
+A "step" is one pass of the whole hot path for one attention layer over one batch of synthetic
+input: candidates -> gather-score -> per-head Top-k -> sparse attention (one lfps_step call),
+with the KV cache already resident in HBM.  Prints ONE JSON line:
+
+  value        decode steps/s per layer of the named workload (whole job, this GPU)
+  roofline     the dominant kernel (gather_score): algorithmic bytes per launch / its average launch
+               duration from HIP events recorded around every launch on the launch stream
+  cpu_baseline the CPU oracle (fp64 numpy, one thread) on a bounded sample of the same workload
+
+Usage: python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload C4] [--all-workloads]
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0   # MI355X published HBM3E peak
+
+# HBM bytes per gather_score launch measured with rocprofv3 --pmc (FETCH_SIZE, WRITE_SIZE), scaled by
+# the same counters' reading for a plain copy kernel; see profiles/ for the runs.  None = not measured.
+MEASURED_TRAFFIC_BYTES = {}
+
+
+def parse_args():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=0, help="timed steps (default: the workload's decode steps minus warmup)")
+    ap.add_argument("--warmup", type=int, default=2)
+    ap.add_argument("--workload", default="C4", choices=["C1", "C2", "C3", "C4", "C5"])
+    ap.add_argument("--all-workloads", action="store_true", help="also report the other four workloads")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-seconds", type=float, default=15.0, help="CPU-oracle sample budget")
+    return ap.parse_args()
+
+
+class Runner:
+    """Device state of one workload and the step loop."""
+
+    def __init__(self, name):
+        import numpy as np
+        import torch
+
+        import gen
+        from gen import device as gen_device
+        from paper_2506_15704_amd.binding import Lfps
+
+        self.torch, self.np = torch, np
+        self.spec = spec = gen.WORKLOADS[name]
+        self.case = case = gen.make_case(spec)
+        self.dev = "cuda:0"
+        self.K, self.V = gen_device.fill_kv(case, self.dev)
+        self.ctx = Lfps(batch=spec.B, n_q_heads=spec.Hq, n_kv_heads=spec.Hkv, head_dim=spec.D,
+                        kv_dtype=spec.kv_dtype, max_seq_len=case.Lcap, max_k=case.kmax, radius=spec.r,
+                        n_recent=1, n_sink=0)
+        to = lambda a: torch.from_numpy(np.ascontiguousarray(a)).to(self.dev)
+        self.q = to(case.q)                                                 # [T+1, B, Hq, D]
+        self.seq = to(np.stack([case.seq_lens(t) for t in range(spec.T + 1)]))  # [T+1, B]
+        self.k = to(case.k)
+        self.views = [self.ctx.kv_view(self.K, self.V, self.seq[t]) for t in range(spec.T + 1)]
+        shp = (spec.B, spec.Hq, case.kmax)
+        self.seed = torch.zeros(shp, dtype=torch.int32, device=self.dev)
+        self.buf = [torch.zeros(shp, dtype=torch.int32, device=self.dev) for _ in range(2)]
+        self.out = torch.zeros((spec.B, spec.Hq, spec.D), dtype=torch.float32, device=self.dev)
+        self.cand = torch.zeros((spec.B, spec.Hkv, self.ctx.cand_cap), dtype=torch.int32, device=self.dev)
+        self.sel_score = torch.zeros(shp, dtype=torch.float32, device=self.dev)
+        # step 0: exact Top-k seeds the history
+        self.ctx.lfps_exact_topk(self.q[0], self.views[0], self.k, self.seed)
+        torch.cuda.synchronize()
+        self.reset()
+
+    def reset(self):
+        self.t = 0
+        self.prev = self.seed
+        self.cur = 0
+
+    def _advance(self):
+        self.t += 1
+        if self.t > self.spec.T:       # more steps asked than the workload has: start over from the seed
+            self.t = 1
+            self.prev = self.seed
+        return self.t
+
+    def step(self):
+        t = self._advance()
+        dst = self.buf[self.cur]
+        self.ctx.lfps_step(self.q[t], self.views[t], self.prev, self.k, dst, self.out)
+        self.prev = dst
+        self.cur ^= 1
+
+    def step_staged(self, cnt_out):
+        """The same kernels in the same order through the per-stage entry points (so the candidate
+        counts of every step are visible to the caller)."""
+        t = self._advance()
+        dst = self.buf[self.cur]
+        self.ctx.lfps_candidates(self.prev, self.k, self.seq[t], self.cand, cnt_out)
+        self.ctx.lfps_score_topk(self.q[t], self.views[t], self.cand, cnt_out, self.k, dst, self.sel_score, None)
+        self.ctx.lfps_sparse_attn(self.q[t], self.views[t], dst, self.sel_score, self.k, self.out)
+        self.prev = dst
+        self.cur ^= 1
+
+    def run_timed(self, steps, warmup):
+        torch = self.torch
+        self.reset()
+        for _ in range(warmup):
+            self.step()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(steps):
+            self.step()
+        torch.cuda.synchronize()
+        return (time.perf_counter() - t0) / steps
+
+    def run_kernel_timing(self, steps, warmup):
+        """Second pass over the same steps with HIP events around every kernel launch."""
+        torch, spec = self.torch, self.spec
+        self.reset()
+        cnts = torch.zeros((steps + warmup, spec.B, spec.Hkv), dtype=torch.int32, device=self.dev)
+        for i in range(warmup):
+            self.step_staged(cnts[i])
+        torch.cuda.synchronize()
+        self.ctx.lfps_timing_enable(True)
+        for i in range(steps):
+            self.step_staged(cnts[warmup + i])
+        tm = self.ctx.lfps_timing_read()
+        self.ctx.lfps_timing_enable(False)
+        return tm, cnts[warmup:].cpu().numpy()
+
+    def time_baseline(self, which, reps):
+        torch = self.torch
+        t = min(self.spec.T, 2)
+        idx = self.buf[0]
+        fn = (lambda: self.ctx.lfps_full_attn_decode(self.q[t], self.views[t], self.out)) if which == "full" else \
+             (lambda: (self.ctx.lfps_exact_topk(self.q[t], self.views[t], self.k, idx, self.sel_score),
+                       self.ctx.lfps_sparse_attn(self.q[t], self.views[t], idx, self.sel_score, self.k, self.out)))
+        for _ in range(2):
+            fn()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(reps):
+            fn()
+        torch.cuda.synchronize()
+        return (time.perf_counter() - t0) / reps
+
+    def recall_vs_exact(self):
+        """Eq. 2 overlap of the chained LFPS Top-k with the exact Top-k at the last step run."""
+        torch = self.torch
+        ex = torch.zeros_like(self.seed)
+        self.ctx.lfps_exact_topk(self.q[self.t], self.views[self.t], self.k, ex)
+        got = self.prev
+        L = int(self.seq[self.t].max().item()) + 1
+        hits = 0
+        tot = 0
+        for b in range(self.spec.B):
+            kb = int(self.case.k[b])
+            a = torch.zeros((self.spec.Hq, L), dtype=torch.bool, device=self.dev)
+            a.scatter_(1, ex[b, :, :kb].long(), True)
+            hits += int(a.gather(1, got[b, :, :kb].clamp_min(0).long()).sum().item())
+            tot += self.spec.Hq * kb
+        return hits / tot
+
+    def close(self):
+        self.ctx.close()
+        del self.K, self.V
+
+
+def algorithmic_bytes_gather_score(spec, cnts):
+    """Bytes one gather_score launch must move: per candidate row its K row (R = D*e bytes), its
+    position (4) and G scores written (4G); plus the G query rows per (b, g)."""
+    e = 2 if spec.kv_dtype == "bf16" else 4
+    per_row = spec.D * e + 4 + 4 * spec.G
+    per_group = spec.G * spec.D * 4
+    return cnts.sum(axis=(1, 2)).astype(float) * per_row + cnts.shape[1] * cnts.shape[2] * per_group
+
+
+def measure(name, steps, warmup, with_baselines=True):
+    r = Runner(name)
+    spec = r.spec
+    if steps <= 0:
+        steps = max(1, spec.T - warmup)
+    sec = r.run_timed(steps, warmup)
+    recall = r.recall_vs_exact()
+    tm, cnts = r.run_kernel_timing(steps, warmup)
+    gs_ms, gs_n = tm["gather_score"]
+    bytes_per_launch = float(algorithmic_bytes_gather_score(spec, cnts).mean())
+    gs_avg_s = gs_ms / max(gs_n, 1) * 1e-3
+    achieved = bytes_per_launch / gs_avg_s / 1e9
+    res = {
+        "steps_per_s": 1.0 / sec, "ms_per_step": sec * 1e3, "steps": steps,
+        "roofline": {"bound": "hbm", "kernel": "gather_score", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS,
+                     "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4),
+                     "traffic": MEASURED_TRAFFIC_BYTES.get(name),
+                     "bytes_per_launch": round(bytes_per_launch), "avg_launch_us": round(gs_avg_s * 1e6, 2),
+                     "launches": gs_n, "timed_by": "HIP events around each launch, second pass over the same steps"},
+        "kernel_us": {k: round(v[0] / max(v[1], 1) * 1e3, 2) for k, v in tm.items() if v[1]},
+        "cand_frac": round(float(cnts.mean() / (spec.L or r.case.seq_lens0.mean())), 4),
+        "recall_vs_exact_topk": round(recall, 4),
+    }
+    if with_baselines:
+        reps = 5 if name in ("C4", "C5") else 20
+        exact = r.time_baseline("exact", reps)
+        full = r.time_baseline("full", reps)
+        res.update({"exact_topk_ms": round(exact * 1e3, 4), "full_attn_ms": round(full * 1e3, 4),
+                    "speedup_vs_exact_topk": round(exact / sec, 3), "speedup_vs_full_attn": round(full / sec, 3)})
+    r.close()
+    return res, r.case
+
+
+def cpu_baseline(case, budget_s):
+    """The oracle's LFPS step (fp64 numpy, one thread) chained over a few steps on a sample of
+    (request, KV group) pairs, scaled to the whole batch."""
+    import numpy as np
+    from threadpoolctl import threadpool_limits
+
+    from oracle import lfps_oracle as orc
+
+    spec = case.spec
+    groups = [(0, 0), (spec.B - 1, spec.Hkv - 1), (spec.B // 2, 3)]
+    n_steps_max = spec.T
+    spent, done = 0.0, 0
+    t_start = time.perf_counter()
+    with threadpool_limits(limits=1):
+        for (b, g) in groups:
+            K, V = case.kv_group(b, g)                                 # input generation: not timed
+            kb = int(case.k[b])
+            prev = [orc.exact_topk(case.q[0, b, spec.G * g + h], K, int(case.seq_lens0[b]), kb)[0] for h in range(spec.G)]
+            for t in range(1, n_steps_max + 1):
+                t0 = time.perf_counter()
+                res = orc.lfps_step(case.q[t, b, spec.G * g: spec.G * (g + 1)], K, V, prev,
+                                    int(case.seq_lens(t)[b]), kb, spec.r, 1, 0)
+                spent += time.perf_counter() - t0
+                done += 1
+                prev = res["topk_idx"]
+                if spent > budget_s:
+                    break
+            if spent > budget_s or time.perf_counter() - t_start > 4 * budget_s + 60:
+                break
+    per_group_step = spent / max(done, 1)
+    step_s = per_group_step * spec.B * spec.Hkv
+    return {"value": 1.0 / step_s, "unit": "steps/s", "cores": 1, "kind": "oracle",
+            "sample": f"{done} oracle lfps_step calls (fp64 numpy, 1 thread) on (request, KV group) samples of {spec.name}, "
+                      f"{per_group_step * 1e3:.1f} ms each, scaled by B*Hkv = {spec.B * spec.Hkv} groups per step"}
+
+
+def main():
+    args = parse_args()
+    if args.gpus != 1:
+        print("bench.py measures the one-GPU hot path only: run it with --gpus 1 "
+              "(no collective or multi-GPU path is part of this build)", file=sys.stderr)
+        sys.exit(2)
+    import torch
+    if not torch.cuda.is_available():
+        print("bench.py needs a GPU (no CPU fallback exists)", file=sys.stderr)
+        sys.exit(2)
+
+    main_res, case = measure(args.workload, args.steps, args.warmup)
+    spec = case.spec
+    line = {
+        "metric": "LFPS decode steps/s per layer", "value": round(main_res["steps_per_s"], 2), "unit": "steps/s",
+        "n_gpus": 1, "steps": main_res["steps"], "warmup": args.warmup, "ms_per_step": round(main_res["ms_per_step"], 4),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16" if spec.kv_dtype == "bf16" else "f32", "data": "synthetic",
+        "config": {"workload": f"{spec.name}: B={spec.B} x L={spec.L or list(spec.L_range)}, 32/8 GQA heads, d=128, "
+                               f"{spec.kv_dtype} K/V, k={spec.k or spec.k_frac}, r={spec.r}, {spec.T} decode steps",
+                   "B": spec.B, "L": spec.L or list(spec.L_range), "k": spec.k or spec.k_frac, "r": spec.r},
+        "roofline": main_res["roofline"],
+        "kernel_us": main_res["kernel_us"],
+        "cand_frac": main_res["cand_frac"], "recall_vs_exact_topk": main_res["recall_vs_exact_topk"],
+        "exact_topk_ms": main_res.get("exact_topk_ms"), "full_attn_ms": main_res.get("full_attn_ms"),
+        "speedup_vs_exact_topk": main_res.get("speedup_vs_exact_topk"),
+        "speedup_vs_full_attn": main_res.get("speedup_vs_full_attn"),
+    }
+    if args.all_workloads:
+        others = {}
+        for name in ("C1", "C2", "C3", "C4", "C5"):
+            if name == args.workload:
+                continue
+            res, _ = measure(name, 0, args.warmup)
+            others[name] = {k: res[k] for k in ("steps_per_s", "ms_per_step", "cand_frac", "recall_vs_exact_topk",
+                                                "speedup_vs_exact_topk", "speedup_vs_full_attn", "kernel_us")}
+            others[name]["roofline_frac"] = res["roofline"]["frac"]
+            others[name]["steps_per_s"] = round(others[name]["steps_per_s"], 2)
+            others[name]["ms_per_step"] = round(others[name]["ms_per_step"], 4)
+        line["other_workloads"] = others
+    if not args.no_cpu_baseline:
+        line["cpu_baseline"] = cpu_baseline(case, args.cpu_seconds)
+    print(json.dumps(line), flush=True)
+
+
+if __name__ == "__main__":
+    main()

@@ -152,8 +152,10 @@ class Lfps:
         if V is not None and V.stride() != K.stride():
             raise ValueError("K and V must share strides")
         sl = _ptr(seq_lens, torch.int32, (self.B,), "seq_lens", self.device)
-        return lfps_kv(K.data_ptr(), V.data_ptr() if V is not None else None,
+        view = lfps_kv(K.data_ptr(), V.data_ptr() if V is not None else None,
                        K.stride(0), K.stride(1), K.stride(2), sl)
+        view._keep = (K, V, seq_lens)   # the struct holds raw pointers: keep their tensors alive with it
+        return view
 
     # ------------------------------------------------------------------ entry points
     def lfps_candidates(self, prev_topk, k, seq_lens, cand, cand_count):
