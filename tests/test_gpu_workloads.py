@@ -1,0 +1,111 @@
+"""Full-size parity on the five benchmark workloads, in the launch configuration bench.py times
+(same context parameters, same cache layout, same entry point), on sampled (request, KV group)
+pairs the oracle recomputes one by one from regenerated rows.  Teacher-forced: before each step
+the sampled groups' previous Top-k rows are replaced by the oracle's own."""
+import numpy as np
+import pytest
+import torch
+
+import bench
+from oracle import lfps_oracle as orc
+from tests.harness import assert_out_close, assert_scores_close, assert_topk_equal_mod_ties
+
+pytestmark = pytest.mark.gpu
+
+SAMPLES = {
+    "C1": [(0, 0), (0, 5), (0, 7)],
+    "C2": [(0, 1), (0, 6)],
+    "C3": [(2, 0), (7, 7)],
+    "C4": [(0, 3), (15, 4)],
+    "C5": None,     # chosen below: the shortest and the longest request
+}
+
+
+@pytest.mark.parametrize("name", ["C1", "C2", "C3", "C4", "C5"])
+def test_workload_steps_match_oracle_on_sampled_groups(name):
+    r = bench.Runner(name)
+    try:
+        spec, case = r.spec, r.case
+        G = spec.G
+        samples = SAMPLES[name] or [(int(np.argmin(case.seq_lens0)), 2), (int(np.argmax(case.seq_lens0)), 6)]
+        kv_cpu = {bg: case.kv_group(*bg) for bg in samples}
+        # seeding step: device exact Top-k vs oracle exact Top-k
+        seed = r.seed.cpu().numpy()
+        prev_orc = {}
+        for (b, g) in samples:
+            K, _ = kv_cpu[(b, g)]
+            kb, n0 = int(case.k[b]), int(case.seq_lens0[b])
+            rows = []
+            for hh in range(G):
+                h = G * g + hh
+                I, _ = orc.exact_topk(case.q[0, b, h], K, n0, kb)
+                assert_topk_equal_mod_ties(seed[b, h, :kb], I, lambda p: orc.scores(case.q[0, b, h], K, p), kb,
+                                           f"{name} seed b{b} h{h}")
+                rows.append(I)
+            prev_orc[(b, g)] = rows
+        n_steps = 3 if name != "C1" else spec.T
+        prev_dev = r.seed.clone()
+        out = torch.zeros_like(r.out)
+        sc = torch.zeros_like(r.sel_score)
+        for t in range(1, n_steps + 1):
+            for (b, g) in samples:                               # teacher forcing on the sampled groups
+                for hh in range(G):
+                    row = np.full(case.kmax, -1, dtype=np.int32)
+                    row[: len(prev_orc[(b, g)][hh])] = prev_orc[(b, g)][hh]
+                    prev_dev[b, G * g + hh] = torch.from_numpy(row).to(prev_dev.device)
+            nxt = torch.zeros_like(prev_dev)
+            r.ctx.lfps_step(r.q[t], r.views[t], prev_dev, r.k, nxt, out, sc)
+            idx_h, out_h, sc_h = nxt.cpu().numpy(), out.cpu().numpy(), sc.cpu().numpy()
+            for (b, g) in samples:
+                K, V = kv_cpu[(b, g)]
+                kb, n = int(case.k[b]), int(case.seq_lens(t)[b])
+                res = orc.lfps_step(case.q[t, b, G * g: G * g + G], K, V, prev_orc[(b, g)], n, kb, spec.r, 1, 0)
+                for hh in range(G):
+                    h = G * g + hh
+                    got = idx_h[b, h, :kb]
+                    assert np.all(idx_h[b, h, kb:] == -1)
+                    assert set(got.tolist()) <= set(res["cand"].tolist()), "selected rows must be candidates"
+                    nd = assert_topk_equal_mod_ties(got, res["topk_idx"][hh], lambda p: orc.scores(case.q[t, b, h], K, p),
+                                                    kb, f"{name} t{t} b{b} h{h}")
+                    assert_scores_close(sc_h[b, h, :kb], orc.scores(case.q[t, b, h], K, got), f"{name} t{t} b{b} h{h}")
+                    assert_out_close(out_h[b, h], orc.sparse_attn(case.q[t, b, h], K, V, got), f"{name} out t{t} b{b} h{h}")
+                    if nd == 0:
+                        assert_out_close(out_h[b, h], res["out"][hh], f"{name} out t{t} b{b} h{h}")
+                prev_orc[(b, g)] = res["topk_idx"]
+            prev_dev = nxt
+        # baselines at full size on the same sampled groups
+        t = n_steps
+        full = torch.zeros_like(r.out)
+        r.ctx.lfps_full_attn_decode(r.q[t], r.views[t], full)
+        full_h = full.cpu().numpy()
+        for (b, g) in samples:
+            K, V = kv_cpu[(b, g)]
+            for hh in (0, G - 1):
+                h = G * g + hh
+                assert_out_close(full_h[b, h], orc.full_attn(case.q[t, b, h], K, V, int(case.seq_lens(t)[b])),
+                                 f"{name} full b{b} h{h}")
+    finally:
+        r.close()
+
+
+def test_candidate_counts_and_capacity_at_full_size():
+    """Properties that hold at any size: counts within [k, min(n, G k (2r+2) + 1)], ascending unique
+    positions inside [0, n), previous Top-k contained in the candidates, no overflow flag."""
+    r = bench.Runner("C5")
+    try:
+        spec, case = r.spec, r.case
+        cnt = torch.zeros((spec.B, spec.Hkv), dtype=torch.int32, device=r.dev)
+        r.ctx.lfps_candidates(r.seed, r.k, r.seq[1], r.cand, cnt)
+        assert r.ctx.lfps_poll_status() == 0
+        cnt_h, cand_h, seed = cnt.cpu().numpy(), r.cand.cpu().numpy(), r.seed.cpu().numpy()
+        for b in range(spec.B):
+            kb, n = int(case.k[b]), int(case.seq_lens(1)[b])
+            for g in range(spec.Hkv):
+                c = int(cnt_h[b, g])
+                assert kb <= c <= min(n, spec.G * kb * (2 * spec.r + 2) + 1)
+                C = cand_h[b, g, :c]
+                assert np.all(np.diff(C) > 0) and C[0] >= 0 and C[-1] == n - 1
+                for hh in range(spec.G):
+                    assert np.isin(seed[b, spec.G * g + hh, :kb], C).all()
+    finally:
+        r.close()
