@@ -26,7 +26,7 @@ HBM_PEAK_GBS = 8000.0   # MI355X published HBM3E peak
 
 # HBM bytes per gather_score launch measured with rocprofv3 --pmc (FETCH_SIZE, WRITE_SIZE), scaled by
 # the same counters' reading for a plain copy kernel; see profiles/ for the runs.  None = not measured.
-MEASURED_TRAFFIC_BYTES = {}
+MEASURED_TRAFFIC_BYTES = {"C4": 1019.6e6}   # profiles/lfps_kernels_C4.md: 958.2 MB fetched + 61.4 MB written
 
 
 def parse_args():
@@ -37,6 +37,8 @@ def parse_args():
     ap.add_argument("--workload", default="C4", choices=["C1", "C2", "C3", "C4", "C5"])
     ap.add_argument("--all-workloads", action="store_true", help="also report the other four workloads")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--calib-copy", action="store_true",
+                    help="run only the plain copy kernel (1 GiB, 10 launches): the known-traffic reference for rocprofv3 --pmc")
     ap.add_argument("--cpu-seconds", type=float, default=15.0, help="CPU-oracle sample budget")
     return ap.parse_args()
 
@@ -259,6 +261,21 @@ def main():
     if not torch.cuda.is_available():
         print("bench.py needs a GPU (no CPU fallback exists)", file=sys.stderr)
         sys.exit(2)
+
+    if args.calib_copy:
+        from paper_2506_15704_amd.binding import lfps_calib_copy
+        src = torch.ones(1 << 28, dtype=torch.float32, device="cuda:0")
+        dst = torch.zeros_like(src)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(10):
+            lfps_calib_copy(dst, src)
+        torch.cuda.synchronize()
+        dt = (time.perf_counter() - t0) / 10
+        assert bool((dst == 1).all())
+        print(json.dumps({"calib_copy_bytes_read": 1 << 30, "calib_copy_bytes_written": 1 << 30, "launches": 10,
+                          "avg_ms": round(dt * 1e3, 4), "GB_per_s_read_plus_write": round(2 * (1 << 30) / dt / 1e9, 1)}))
+        return
 
     main_res, case = measure(args.workload, args.steps, args.warmup)
     spec = case.spec

@@ -168,6 +168,12 @@ int lfps_timing_enable(lfps_ctx* ctx, int32_t on);
 int lfps_timing_read(lfps_ctx* ctx, float* ms, int32_t* launches, void* stream);
 const char* lfps_kernel_name(int32_t slot);
 
+/* Plain device-to-device copy of `bytes` bytes (a multiple of 16; both pointers 16-byte aligned),
+ * one 16-byte load and store per lane, grid-strided.  Not part of the method: it exists so that
+ * hardware memory counters (bytes fetched / written per dispatch) can be scaled against a kernel
+ * whose traffic is known exactly. */
+int lfps_calib_copy(void* dst, const void* src, int64_t bytes, void* stream);
+
 #pragma GCC visibility pop
 #ifdef __cplusplus
 }

@@ -63,6 +63,7 @@ def _load() -> ctypes.CDLL:
         "lfps_timing_enable": (ctypes.c_int, [P, I32]),
         "lfps_timing_read": (ctypes.c_int, [P, ctypes.POINTER(ctypes.c_float), ctypes.POINTER(I32), VP]),
         "lfps_kernel_name": (ctypes.c_char_p, [I32]),
+        "lfps_calib_copy": (ctypes.c_int, [VP, VP, ctypes.c_int64, VP]),
     }
     for name, (res, args) in sig.items():
         fn = getattr(lib, name)
@@ -98,6 +99,18 @@ def _ptr(t: Optional[torch.Tensor], dtype, shape, name: str, device) -> Optional
     if not t.is_contiguous():
         raise ValueError(f"{name}: must be contiguous")
     return t.data_ptr()
+
+
+def lfps_calib_copy(dst: torch.Tensor, src: torch.Tensor):
+    """Plain device copy with exactly known traffic (src.nbytes read, the same written)."""
+    if not (dst.is_cuda and src.is_cuda and dst.is_contiguous() and src.is_contiguous()):
+        raise TypeError("lfps_calib_copy: contiguous GPU tensors expected")
+    nbytes = src.numel() * src.element_size()
+    if nbytes != dst.numel() * dst.element_size():
+        raise ValueError("lfps_calib_copy: size mismatch")
+    rc = _lib.lfps_calib_copy(dst.data_ptr(), src.data_ptr(), nbytes, torch.cuda.current_stream(src.device).cuda_stream)
+    if rc != LFPS_OK:
+        raise LfpsError(rc, "lfps_calib_copy")
 
 
 class Lfps:

@@ -147,7 +147,23 @@ struct Timed {
 
 }  // namespace
 
+__global__ __launch_bounds__(256) void k_calib_copy(const uint4* __restrict__ src, uint4* __restrict__ dst, int64_t n16) {
+  const int64_t stride = (int64_t)gridDim.x * 256;
+  for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < n16; i += stride) dst[i] = src[i];
+}
+
 extern "C" {
+
+int lfps_calib_copy(void* dst, const void* src, int64_t bytes, void* stream) {
+  if (!dst || !src || bytes < 0 || (bytes % 16) || ((uintptr_t)dst % 16) || ((uintptr_t)src % 16)) return LFPS_EINVAL;
+  if (bytes == 0) return LFPS_OK;
+  const int64_t n16 = bytes / 16;
+  int64_t blocks = (n16 + 255) / 256;
+  if (blocks > 65536) blocks = 65536;
+  hipLaunchKernelGGL(k_calib_copy, dim3((unsigned)blocks), dim3(256), 0, (hipStream_t)stream, (const uint4*)src,
+                     (uint4*)dst, n16);
+  return hipGetLastError() == hipSuccess ? LFPS_OK : LFPS_EHIP;
+}
 
 int lfps_workspace_bytes(const lfps_config* cfg, int64_t* out) {
   Sizes z;
