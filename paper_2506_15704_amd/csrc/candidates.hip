@@ -6,7 +6,8 @@
 // previous index ORs the (2r+2)-bit window [i-r, i+r+1] (clipped to [0, n)) into the words it
 // spans, which also dedupes within a head and across the G heads of the group.  A popcount +
 // block scan then assigns each word its output offset and the set bits are emitted in ascending
-// order, so the output is sorted and identical from run to run.
+// order, so the output is sorted and identical from run to run.  (The G <= 4 heads per group
+// that the library supports are unrolled.)
 #include "lfps_internal.h"
 
 namespace lfps {
@@ -23,6 +24,7 @@ __device__ __forceinline__ void set_bit_range(uint32_t* bm, int lo, int hi) {  /
   }
 }
 
+// Dynamic LDS: bitmap words [W] followed by the exclusive output offset of every word [W].
 __global__ __launch_bounds__(kCandThreads) void k_candidates(Shape s, const int32_t* __restrict__ prev_topk,
                                                              const int32_t* __restrict__ kk,
                                                              const int32_t* __restrict__ seq_lens,
@@ -39,20 +41,51 @@ __global__ __launch_bounds__(kCandThreads) void k_candidates(Shape s, const int3
   kb = kb < 0 ? 0 : (kb > s.kmax ? s.kmax : kb);
   const int W = (n + 31) >> 5;
   uint32_t* bm = lds;
+  uint32_t* woff = lds + ((s.Lcap + 31) >> 5);
+
+  // The previous Top-k of the group's heads: issue every load of a round before touching LDS, so
+  // their latencies overlap (4 heads x 2 entries per thread and round).
+  constexpr int kU = 2;
+  const int r = s.radius;
+  const int32_t* pt = prev_topk + ((int64_t)b * s.Hq + (int64_t)g * s.G) * s.kmax;
+  int first_ids[4 * kU];
+#pragma unroll
+  for (int h = 0; h < 4; ++h)
+#pragma unroll
+    for (int u = 0; u < kU; ++u) {
+      const int j = tid + u * kCandThreads;
+      first_ids[h * kU + u] = (h < s.G && j < kb) ? pt[(int64_t)h * s.kmax + j] : -1;
+    }
 
   for (int w = tid; w < W; w += kCandThreads) bm[w] = 0u;
   __syncthreads();
 
-  const int r = s.radius;
-  const int32_t* pt = prev_topk + ((int64_t)b * s.Hq + (int64_t)g * s.G) * s.kmax;
-  for (int e = tid; e < s.G * kb; e += kCandThreads) {
-    int h = e / kb, j = e - h * kb;
-    int i = pt[(int64_t)h * s.kmax + j];
+#pragma unroll
+  for (int e = 0; e < 4 * kU; ++e) {
+    const int i = first_ids[e];
     if (i >= 0 && i < n) {
-      int lo = i - r < 0 ? 0 : i - r;
-      int64_t hi64 = (int64_t)i + r + 1;
-      int hi = hi64 > n - 1 ? n - 1 : (int)hi64;
-      set_bit_range(bm, lo, hi);
+      const int lo = i - r < 0 ? 0 : i - r;
+      const int64_t hi64 = (int64_t)i + r + 1;
+      set_bit_range(bm, lo, hi64 > n - 1 ? n - 1 : (int)hi64);
+    }
+  }
+  for (int j0 = kU * kCandThreads; j0 < kb; j0 += kU * kCandThreads) {   // budgets beyond 2048 per head
+    int ids[4 * kU];
+#pragma unroll
+    for (int h = 0; h < 4; ++h)
+#pragma unroll
+      for (int u = 0; u < kU; ++u) {
+        const int j = j0 + tid + u * kCandThreads;
+        ids[h * kU + u] = (h < s.G && j < kb) ? pt[(int64_t)h * s.kmax + j] : -1;
+      }
+#pragma unroll
+    for (int e = 0; e < 4 * kU; ++e) {
+      const int i = ids[e];
+      if (i >= 0 && i < n) {
+        const int lo = i - r < 0 ? 0 : i - r;
+        const int64_t hi64 = (int64_t)i + r + 1;
+        set_bit_range(bm, lo, hi64 > n - 1 ? n - 1 : (int)hi64);
+      }
     }
   }
   if (tid == 0 && n > 0) {
@@ -61,13 +94,15 @@ __global__ __launch_bounds__(kCandThreads) void k_candidates(Shape s, const int3
   }
   __syncthreads();
 
-  // each thread owns a contiguous slice of words
+  // exclusive output offset of every word: each thread scans a contiguous slice of words,
+  // then a block scan of the slice totals
   const int wpt = (W + kCandThreads - 1) / kCandThreads;
   const int w_lo = tid * wpt, w_hi = (w_lo + wpt < W) ? w_lo + wpt : W;
   int cnt = 0;
-  for (int w = w_lo; w < w_hi; ++w) cnt += __popc(bm[w]);
-
-  // block exclusive scan of cnt: in-wave inclusive scan, then wave totals
+  for (int w = w_lo; w < w_hi; ++w) {
+    woff[w] = (uint32_t)cnt;
+    cnt += __popc(bm[w]);
+  }
   const int lane = tid & 63, wv = tid >> 6;
   int inc = cnt;
 #pragma unroll
@@ -84,13 +119,17 @@ __global__ __launch_bounds__(kCandThreads) void k_candidates(Shape s, const int3
     if (i < wv) base += t;
     total += t;
   }
-  int off = base + inc - cnt;
+  const int slice_off = base + inc - cnt;
+  for (int w = w_lo; w < w_hi; ++w) woff[w] += (uint32_t)slice_off;
+  __syncthreads();
 
+  // emit: consecutive threads expand consecutive words, so a wave writes one contiguous stretch
   int32_t* out = cand + (int64_t)bg * s.cand_cap;
-  for (int w = w_lo; w < w_hi; ++w) {
+  for (int w = tid; w < W; w += kCandThreads) {
     uint32_t bits = bm[w];
+    int off = (int)woff[w];
     while (bits) {
-      int p = __ffs(bits) - 1;
+      const int p = __ffs(bits) - 1;
       bits &= bits - 1;
       if (off < s.cand_cap) out[off] = (w << 5) + p;
       ++off;
@@ -106,8 +145,8 @@ __global__ __launch_bounds__(kCandThreads) void k_candidates(Shape s, const int3
 }
 
 static size_t candidates_lds_bytes(const Shape& s) {
-  size_t b = ((size_t)(s.Lcap + 31) / 32) * 4;
-  return b < 4 ? 4 : b;
+  size_t b = ((size_t)(s.Lcap + 31) / 32) * 8;     // bitmap + per-word offsets
+  return b < 8 ? 8 : b;
 }
 
 // Called once per context at creation: raises the kernel's dynamic-LDS limit when the bitmap of

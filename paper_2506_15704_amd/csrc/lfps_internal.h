@@ -32,6 +32,7 @@ struct Shape {
 
 // ---- kernel launchers (each enqueues on `st` and returns the launch error) -------------
 hipError_t configure_candidates(const Shape& s);
+hipError_t configure_select(const Shape& s);
 hipError_t launch_candidates(const Shape& s, const int32_t* prev_topk, const int32_t* k, const int32_t* seq_lens,
                              int32_t* cand, int32_t* cand_count, int32_t* flags, hipStream_t st);
 

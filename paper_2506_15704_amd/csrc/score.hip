@@ -5,8 +5,8 @@
 // The path is bound by the bytes of the K rows it gathers; the arithmetic is kept off the
 // vector ALU so it cannot become the limit:
 //   bf16 cache: one wave handles 16 rows at a time with v_mfma_f32_16x16x32_bf16.  The B operand
-//     is the K tile exactly as it lies in memory (lane (j, kb) loads 16 bytes = channels
-//     [32*kk + 8*kb, +8) of row j), so a row is fetched once for all G heads.  The A operand is
+//     is the K tile exactly as it lies in memory (each lane loads 16-byte pieces of one row),
+//     so a row is fetched once for all G heads.  The A operand is
 //     the query: each fp32 q is split into three bf16 terms q = q0 + q1 + q2 (24 mantissa bits),
 //     and A's row 4*h + t holds term t of head h.  bf16 x bf16 products are exact in fp32, so
 //     the sum D[4h+0] + D[4h+1] + D[4h+2] is the fp32-accumulated dot product with the fp32
@@ -44,6 +44,15 @@ union Bf16x8Bits {
 
 // ----------------------------------------------------------------------------- bf16, MFMA
 // grid: (tiles_x, B*Hkv).  GATHER: rows come from cand[bg, 0:count]; else rows are 0..n_b-1.
+//
+// Lane (j, kb) = (lane & 15, lane >> 4) supplies column j of the B operand: for MFMA step kk it
+// loads the 16-byte chunk kk + 4*kb of row j, i.e. every lane walks its own contiguous 64 bytes of
+// the row over the four steps (measured faster than splitting a row into four 64-byte quarters
+// per step: all four loads of a tile touch both cache lines of every row).  Any assignment of
+// channels to (kk, kb) is valid as long as the A operand uses the same one.
+// The loop is software-pipelined around the stores: the row ids of the next iteration are fetched
+// and the scores of the previous iteration are stored right after this iteration's loads are
+// issued, so no wait for a load ever has only a store in front of it.
 template <int G, bool GATHER>
 __global__ __launch_bounds__(kScoreThreads) void k_group_score_bf16(Shape s, const float* __restrict__ q,
                                                                     const __bf16* __restrict__ K, int64_t stride_b,
@@ -64,7 +73,7 @@ __global__ __launch_bounds__(kScoreThreads) void k_group_score_bf16(Shape s, con
   if (first >= count) return;
 
   // A operand: row m = j of the 16x32 A tile of step kk holds term (m & 3) of head (m >> 2),
-  // channels [32*kk + 8*kb, +8).  Heads >= G contribute zeros.
+  // channels of chunk kk + 4*kb.  Heads >= G contribute zeros.
   bf16x8 A[4];
   {
     const int h = j >> 2, t = j & 3;
@@ -74,7 +83,7 @@ __global__ __launch_bounds__(kScoreThreads) void k_group_score_bf16(Shape s, con
       Bf16x8Bits a;
 #pragma unroll
       for (int c = 0; c < 8; ++c) {
-        float x = qh[32 * kk + 8 * kb + c];
+        float x = qh[8 * (kk + 4 * kb) + c];
         a.h[c] = (h < G) ? split_term(x, t) : (uint16_t)0;
       }
       A[kk] = a.v;
@@ -86,17 +95,29 @@ __global__ __launch_bounds__(kScoreThreads) void k_group_score_bf16(Shape s, con
   float* sc = score + ((int64_t)b * s.Hq + (int64_t)g * G + kb) * score_stride;   // lane group kb -> head kb
   const int step = gridDim.x * 4 * kRowsPerWaveIter;
 
+  float pv[4] = {0.f, 0.f, 0.f, 0.f};   // scores of the previous iteration, not yet stored
+  int pbase = -1;
+  int my_row = -1;
+  if (first + lane < count) my_row = GATHER ? cbg[first + lane] : first + lane;
   for (int base = first; base < count; base += step) {
-    int my_row = -1;
-    if (base + lane < count) my_row = GATHER ? cbg[base + lane] : base + lane;
     bf16x8 Bt[4][4];
 #pragma unroll
     for (int t = 0; t < 4; ++t) {
       int row = __shfl(my_row, 16 * t + j);
-      row = (row < 0 || row >= n) ? 0 : row;            // padding slots read row 0 (n > 0 here) and are not stored
-      const bf16x8* p = reinterpret_cast<const bf16x8*>(Kbg + (int64_t)row * stride_n) + kb;
+      row = (row < 0 || row >= n) ? 0 : row;            // padding slots read row 0 and are not stored
+      const bf16x8* p = reinterpret_cast<const bf16x8*>(Kbg + (int64_t)row * stride_n) + 4 * kb;
 #pragma unroll
-      for (int kk = 0; kk < 4; ++kk) Bt[t][kk] = p[4 * kk];
+      for (int kk = 0; kk < 4; ++kk) Bt[t][kk] = p[kk];
+    }
+    const int nb = base + step;
+    int next_row = -1;
+    if (nb + lane < count) next_row = GATHER ? cbg[nb + lane] : nb + lane;
+    if (pbase >= 0) {
+#pragma unroll
+      for (int t = 0; t < 4; ++t) {
+        const int slot = pbase + 16 * t + j;
+        if (kb < G && slot < count) sc[slot] = pv[t];
+      }
     }
 #pragma unroll
     for (int t = 0; t < 4; ++t) {
@@ -104,10 +125,15 @@ __global__ __launch_bounds__(kScoreThreads) void k_group_score_bf16(Shape s, con
 #pragma unroll
       for (int kk = 0; kk < 4; ++kk) acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(A[kk], Bt[t][kk], acc, 0, 0, 0);
       // lane (j, kb): D rows 4*kb .. 4*kb+3 = the three terms (and a zero row) of head kb, column j
-      float v = ((acc[0] + acc[1]) + acc[2]) * scale;
-      int slot = base + 16 * t + j;
-      if (kb < G && slot < count) sc[slot] = v;
+      pv[t] = ((acc[0] + acc[1]) + acc[2]) * scale;
     }
+    pbase = base;
+    my_row = next_row;
+  }
+#pragma unroll
+  for (int t = 0; t < 4; ++t) {
+    const int slot = pbase + 16 * t + j;
+    if (kb < G && slot < count) sc[slot] = pv[t];
   }
 }
 
@@ -239,8 +265,8 @@ static hipError_t launch_gs(const Shape& s, int dtype, const float* q, const KvV
   const int rows_max = GATHER ? s.cand_cap : s.Lcap;
   const int per_block = 4 * kRowsPerWaveIter;
   int tiles = (rows_max + per_block - 1) / per_block;
-  // enough workgroups to fill 256 CUs several times over, but no more than there are tiles
-  int want = (256 * 8 + s.B * s.Hkv - 1) / (s.B * s.Hkv);
+  // about four workgroups (16 waves) per CU, all resident at once, but no more than there are tiles
+  int want = (256 * 4 + s.B * s.Hkv - 1) / (s.B * s.Hkv);
   int gx = tiles < want ? tiles : want;
   if (gx < 1) gx = 1;
   dim3 grid(gx, s.B * s.Hkv), block(kScoreThreads);

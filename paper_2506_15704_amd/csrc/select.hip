@@ -1,12 +1,24 @@
 // S3 — per query head, the k best of the scored rows (Alg. 1 line 8 / Sec. 1 Step 2).
 //
-// One workgroup per (b, h).  Scores are mapped to order-preserving 32-bit keys and the k-th
-// largest key is found exactly by a most-significant-digit radix descent (11 + 11 + 10 bits)
-// with LDS histograms; the scores are streamed from global memory/L2 on every pass because a
-// head can have more scores than LDS holds.  The final pass writes every row above the k-th
-// key, plus as many rows equal to it as are still needed, lowest position first.  Output is
-// compacted in row order (ballot + prefix counts, no atomics), so it is ascending in position
-// and identical from run to run.
+// One workgroup (16 waves) per (b, h); wave w owns the contiguous slice w of the head's scores.
+// When the head has at most 32768 scores they are read from global memory once and kept in LDS
+// (128 KB) for every later pass; otherwise each pass streams them again (L2).
+//
+//  1. block min/max of the scores;
+//  2. one LDS histogram of 2048 bins that are *linear in the score* between min and max.  (Bins
+//     taken from the raw float bits would put a bell-shaped score distribution into a few dozen
+//     bins and serialise the LDS atomics; linear bins spread it and leave only a handful of
+//     scores in the bin that holds the k-th largest.)
+//  3. the bin of the k-th largest score, by a suffix scan over the histogram;
+//  4. the exact k-th largest inside that bin: its members go to a small LDS list and each is
+//     ranked against the others; if the bin is too full for the list (degenerate inputs: all
+//     scores equal, one huge outlier) an exact most-significant-digit radix descent over the
+//     order-preserving 32-bit keys of the bin's members finds it instead;
+//  5. ordered compaction (ballot + prefix counts, no atomics): every row above the k-th key plus
+//     as many rows equal to it as still needed, lowest position first.  The output is ascending
+//     in position and identical from run to run.
+#include <float.h>
+
 #include "lfps_internal.h"
 
 namespace lfps {
@@ -14,23 +26,255 @@ namespace lfps {
 constexpr int kSelThreads = 1024;
 constexpr int kSelWaves = kSelThreads / 64;
 constexpr int kBins = 2048;
+constexpr int kCacheElems = 32768;  // scores of one head kept in LDS (dynamic, 128 KB)
+constexpr int kListCap = 1024;  // members of the threshold bin ranked directly
+
+struct SelectShared {
+  uint32_t hist[kBins];
+  uint32_t list[kListCap];
+  uint32_t wsum[kSelWaves];
+  float wlo[kSelWaves], whi[kSelWaves];
+  uint32_t cnt_gt[kSelWaves], cnt_eq[kSelWaves];
+  uint32_t need, bin, list_n, thr, need_eq;
+};
 
 __device__ __forceinline__ int lanes_below(uint64_t m) {   // set bits of m at lanes lower than mine
   return __builtin_amdgcn_mbcnt_hi((uint32_t)(m >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)m, 0));
+}
+
+// Scores are made finite and -0 becomes +0, so that float comparisons order them exactly like
+// their 32-bit keys and the linear bins are monotone.
+__device__ __forceinline__ float sanitize(float x) { return fmaxf(fminf(x, FLT_MAX), -FLT_MAX) + 0.0f; }
+
+__device__ __forceinline__ float key2f(uint32_t k) {       // inverse of f2key
+  return __uint_as_float((k & 0x80000000u) ? (k & 0x7FFFFFFFu) : ~k);
+}
+
+// Largest digit d (bins 2t, 2t+1 owned by thread t) whose suffix count reaches `need`.
+// Writes sm.bin = d and sm.need = need - (count in bins above d).  All threads must call.
+__device__ __forceinline__ void find_bin(SelectShared& sm, uint32_t need, int tid, int lane, int wv) {
+  const uint32_t lo = sm.hist[2 * tid], hi = sm.hist[2 * tid + 1];
+  const uint32_t mine = lo + hi;
+  uint32_t inc = mine;                       // inclusive suffix sum within the wave
+#pragma unroll
+  for (int d = 1; d < 64; d <<= 1) {
+    uint32_t o = __shfl_down(inc, d);
+    if (lane + d < 64) inc += o;
+  }
+  if (lane == 0) sm.wsum[wv] = inc;
+  __syncthreads();
+  uint32_t above_waves = 0;
+  for (int w = wv + 1; w < kSelWaves; ++w) above_waves += sm.wsum[w];
+  const uint32_t suffix_incl = above_waves + inc;    // count in bins >= 2t
+  const uint32_t suffix_excl = suffix_incl - mine;   // count in bins >  2t+1
+  if (suffix_incl >= need && suffix_excl < need) {   // exactly one thread
+    if (suffix_excl + hi >= need) {
+      sm.bin = 2 * tid + 1;
+      sm.need = need - suffix_excl;
+    } else {
+      sm.bin = 2 * tid;
+      sm.need = need - (suffix_excl + hi);
+    }
+  }
+  __syncthreads();
+}
+
+// Visits the wave's slice: `i` = row slot, `in` = slot valid, `x` = its sanitised score (from the
+// LDS copy when CACHED, else from global memory).  The trip count is wave-uniform, so ballots
+// inside see the whole wave.
+#define LFPS_FOR_EACH(...)                                                   \
+  _Pragma("unroll 4") for (int it = 0; it < nit; ++it) {                     \
+    const int i = r0 + 64 * it + lane;                                       \
+    const bool in = i < r1;                                                  \
+    const float x = CACHED ? cache[in ? i : r0] : sanitize(sc[in ? i : r0]); \
+    __VA_ARGS__                                                              \
+  }
+
+template <bool CACHED>
+__device__ __forceinline__ void select_body(SelectShared& sm, float* __restrict__ cache,
+                                            const float* __restrict__ sc, int c, int ksel,
+                                            const int32_t* __restrict__ cbg, int32_t* __restrict__ oi,
+                                            float* __restrict__ os) {
+  const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
+  const int chunk = (((c + kSelWaves - 1) / kSelWaves) + 63) & ~63;
+  const int r0 = wv * chunk, r1 = (r0 + chunk < c) ? r0 + chunk : c;
+  const int nit = r1 > r0 ? (r1 - r0 + 63) >> 6 : 0;
+
+  // ---- 1. load (once, into LDS, if the head fits) and block min / max
+  if (CACHED) {
+#pragma unroll 8
+    for (int it = 0; it < nit; ++it) {
+      const int i = r0 + 64 * it + lane;
+      if (i < r1) cache[i] = sanitize(sc[i]);
+    }
+  }
+  float lo = FLT_MAX, hi = -FLT_MAX;
+  LFPS_FOR_EACH(lo = in ? fminf(lo, x) : lo; hi = in ? fmaxf(hi, x) : hi;)
+#pragma unroll
+  for (int d = 1; d < 64; d <<= 1) {
+    lo = fminf(lo, __shfl_xor(lo, d));
+    hi = fmaxf(hi, __shfl_xor(hi, d));
+  }
+  if (lane == 0) {
+    sm.wlo[wv] = lo;
+    sm.whi[wv] = hi;
+  }
+  for (int i = tid; i < kBins; i += kSelThreads) sm.hist[i] = 0u;
+  if (tid == 0) sm.list_n = 0u;
+  __syncthreads();
+#pragma unroll
+  for (int w = 0; w < kSelWaves; ++w) {
+    lo = fminf(lo, sm.wlo[w]);
+    hi = fmaxf(hi, sm.whi[w]);
+  }
+  const float range = hi - lo;
+  const float scale = (range > 0.f && range < FLT_MAX) ? (float)kBins / range : 0.f;
+  // monotone in x; the unsigned min also catches a NaN-poisoned or negative conversion
+#define LFPS_BIN(x) ((int)min((uint32_t)(int)(((x)-lo) * scale), (uint32_t)(kBins - 1)))
+
+  // ---- 2. histogram over linear bins
+  LFPS_FOR_EACH(if (in) atomicAdd(&sm.hist[LFPS_BIN(x)], 1u);)
+  __syncthreads();
+  // ---- 3. bin of the ksel-th largest
+  find_bin(sm, (uint32_t)ksel, tid, lane, wv);
+  const int tb = (int)sm.bin;
+  uint32_t need = sm.need;                 // rows still to take from bin tb (>= 1)
+  const uint32_t m = sm.hist[tb];          // members of bin tb (>= need)
+  __syncthreads();
+
+  // ---- 4. exact threshold inside bin tb
+  if (m <= (uint32_t)kListCap) {
+    // members of bin tb lie within one bin width of its lower edge: a cheap float test first
+    const float inv = scale > 0.f ? 1.0f / scale : 0.f;
+    const float e_lo = lo + ((float)tb - 1.0f) * inv, e_hi = lo + ((float)tb + 2.0f) * inv;
+    LFPS_FOR_EACH({
+      const bool near = in && (scale == 0.f || (x >= e_lo && x <= e_hi));
+      if (__ballot(near)) {
+        const bool hit = near && LFPS_BIN(x) == tb;
+        const uint64_t mh = __ballot(hit);
+        if (mh) {
+          uint32_t base = 0;
+          if (lane == 0) base = atomicAdd(&sm.list_n, (uint32_t)__popcll(mh));
+          base = __shfl(base, 0);
+          if (hit) sm.list[base + lanes_below(mh)] = f2key(x);
+        }
+      }
+    })
+    __syncthreads();
+    if (tid < (int)m) {
+      const uint32_t u = sm.list[tid];
+      uint32_t gt = 0, ge = 0;
+      for (uint32_t jj = 0; jj < m; ++jj) {
+        const uint32_t o = sm.list[jj];
+        gt += o > u;
+        ge += o >= u;
+      }
+      if (gt < need && need <= ge) {       // u is the need-th largest (equal keys write equal values)
+        sm.thr = u;
+        sm.need_eq = need - gt;
+      }
+    }
+    __syncthreads();
+  } else {
+    uint32_t prefix = 0, mask = 0;
+#pragma unroll 1
+    for (int pass = 0; pass < 3; ++pass) {
+      const int shift = pass == 0 ? 21 : (pass == 1 ? 10 : 0);
+      const uint32_t dmask = pass == 2 ? 1023u : 2047u;
+      for (int i = tid; i < kBins; i += kSelThreads) sm.hist[i] = 0u;
+      __syncthreads();
+      LFPS_FOR_EACH(if (in && LFPS_BIN(x) == tb) {
+        const uint32_t key = f2key(x);
+        if (((key ^ prefix) & mask) == 0u) atomicAdd(&sm.hist[(key >> shift) & dmask], 1u);
+      })
+      __syncthreads();
+      find_bin(sm, need, tid, lane, wv);
+      prefix |= sm.bin << shift;
+      need = sm.need;
+      mask |= dmask << shift;
+      __syncthreads();
+    }
+    if (tid == 0) {
+      sm.thr = prefix;
+      sm.need_eq = need;
+    }
+    __syncthreads();
+  }
+  const float thr = key2f(sm.thr);          // the ksel-th largest score
+  const uint32_t need_eq = sm.need_eq;      // rows equal to it that are taken
+
+  // ---- 5. ordered compaction
+  uint32_t ngt = 0, neq = 0;
+  LFPS_FOR_EACH(ngt += __popcll(__ballot(in && x > thr)); neq += __popcll(__ballot(in && x == thr));)
+  if (lane == 0) {
+    sm.cnt_gt[wv] = ngt;
+    sm.cnt_eq[wv] = neq;
+  }
+  __syncthreads();
+  uint32_t gt_before = 0, eq_before = 0, eq_total = 0;
+#pragma unroll
+  for (int w = 0; w < kSelWaves; ++w) {
+    const uint32_t g_ = sm.cnt_gt[w], e_ = sm.cnt_eq[w];
+    gt_before += w < wv ? g_ : 0u;
+    eq_before += w < wv ? e_ : 0u;
+    eq_total += e_;
+  }
+  if (eq_total == need_eq) {
+    // every row equal to the threshold is taken (the usual case): one comparison per row
+    uint32_t out_run = gt_before + eq_before;
+    LFPS_FOR_EACH({
+      const bool take = in && x >= thr;
+      const uint64_t m_take = __ballot(take);
+      if (take) {
+        const uint32_t pos = out_run + lanes_below(m_take);
+        if (pos < (uint32_t)ksel) {
+          oi[pos] = cbg ? cbg[i] : i;
+          if (os) os[pos] = x;
+        }
+      }
+      out_run += __popcll(m_take);
+    })
+  } else {
+    uint32_t eq_run = eq_before;
+    uint32_t out_run = gt_before + (eq_before < need_eq ? eq_before : need_eq);
+    LFPS_FOR_EACH({
+      const bool gt = in && x > thr;
+      const bool eq = in && x == thr;
+      const uint64_t m_eq = __ballot(eq);
+      const bool take = gt || (eq && eq_run + lanes_below(m_eq) < need_eq);
+      const uint64_t m_take = __ballot(take);
+      if (take) {
+        const uint32_t pos = out_run + lanes_below(m_take);
+        if (pos < (uint32_t)ksel) {
+          oi[pos] = cbg ? cbg[i] : i;
+          if (os) os[pos] = x;
+        }
+      }
+      eq_run += __popcll(m_eq);
+      out_run += __popcll(m_take);
+    })
+  }
+#undef LFPS_BIN
+}
+#undef LFPS_FOR_EACH
+
+// The streaming variant is a real call, so that its code does not compete for registers with
+// the register-resident variant.
+__device__ __noinline__ void select_stream(SelectShared& sm, const float* __restrict__ sc, int c, int ksel,
+                                           const int32_t* __restrict__ cbg, int32_t* __restrict__ oi,
+                                           float* __restrict__ os) {
+  select_body<false>(sm, nullptr, sc, c, ksel, cbg, oi, os);
 }
 
 __global__ __launch_bounds__(kSelThreads) void k_select(Shape s, const float* __restrict__ score,
                                                         int64_t score_stride, const int32_t* __restrict__ cand,
                                                         const int32_t* __restrict__ count_arr,
                                                         const int32_t* __restrict__ kk, int32_t* __restrict__ topk_idx,
-                                                        float* __restrict__ topk_score) {
-  __shared__ uint32_t hist[kBins];
-  __shared__ uint32_t wsum[kSelWaves];
-  __shared__ uint32_t sh_prefix, sh_need;
-  __shared__ uint32_t cnt_gt[kSelWaves], cnt_eq[kSelWaves];
-
+                                                        float* __restrict__ topk_score, int cache_elems) {
+  __shared__ SelectShared sm;
+  extern __shared__ float cache[];
   const int bh = blockIdx.x, b = bh / s.Hq, h = bh % s.Hq, g = h / s.G;
-  const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
+  const int tid = threadIdx.x;
   const bool gather = cand != nullptr;
   int c = gather ? count_arr[b * s.Hkv + g] : count_arr[b];
   const int c_max = gather ? s.cand_cap : s.Lcap;
@@ -49,106 +293,29 @@ __global__ __launch_bounds__(kSelThreads) void k_select(Shape s, const float* __
 
   const float* sc = score + (int64_t)bh * score_stride;
   const int32_t* cbg = gather ? cand + ((int64_t)b * s.Hkv + g) * s.cand_cap : nullptr;
+  if (c <= cache_elems)
+    select_body<true>(sm, cache, sc, c, ksel, cbg, oi, os);
+  else
+    select_stream(sm, sc, c, ksel, cbg, oi, os);
+}
 
-  // ---- radix descent for the ksel-th largest key
-  uint32_t prefix = 0, mask = 0, need = (uint32_t)ksel;
-  const int shifts[3] = {21, 10, 0};
-  const int widths[3] = {11, 11, 10};
-#pragma unroll 1
-  for (int pass = 0; pass < 3; ++pass) {
-    const int shift = shifts[pass];
-    const uint32_t dmask = (1u << widths[pass]) - 1u;
-    for (int i = tid; i < kBins; i += kSelThreads) hist[i] = 0u;
-    __syncthreads();
-    for (int i = tid; i < c; i += kSelThreads) {
-      uint32_t key = f2key(sc[i]);
-      if (((key ^ prefix) & mask) == 0u) atomicAdd(&hist[(key >> shift) & dmask], 1u);
-    }
-    __syncthreads();
-    // thread t owns bins 2t (low) and 2t+1 (high); suffix sums from the top bin down
-    const uint32_t lo = hist[2 * tid], hi = hist[2 * tid + 1];
-    const uint32_t mine = lo + hi;
-    uint32_t inc = mine;   // inclusive suffix sum over lanes >= mine within the wave
-#pragma unroll
-    for (int d = 1; d < 64; d <<= 1) {
-      uint32_t o = __shfl_down(inc, d);
-      if (lane + d < 64) inc += o;
-    }
-    if (lane == 0) wsum[wv] = inc;
-    __syncthreads();
-    uint32_t above_waves = 0;
-    for (int w = wv + 1; w < kSelWaves; ++w) above_waves += wsum[w];
-    const uint32_t suffix_incl = above_waves + inc;      // keys in bins >= 2t
-    const uint32_t suffix_excl = suffix_incl - mine;     // keys in bins >  2t+1
-    if (suffix_incl >= need && suffix_excl < need) {     // exactly one thread
-      uint32_t digit, above;
-      if (suffix_excl + hi >= need) {
-        digit = 2 * tid + 1;
-        above = suffix_excl;
-      } else {
-        digit = 2 * tid;
-        above = suffix_excl + hi;
-      }
-      sh_prefix = prefix | (digit << shift);
-      sh_need = need - above;
-    }
-    __syncthreads();
-    prefix = sh_prefix;
-    need = sh_need;
-    mask |= dmask << shift;
-    __syncthreads();
-  }
-  const uint32_t thr = prefix;   // the ksel-th largest key; `need` rows equal to it are taken
+static int select_cache_elems(const Shape& s, bool gather) {
+  const int rows_max = gather ? s.cand_cap : s.Lcap;
+  const int e = rows_max < kCacheElems ? rows_max : kCacheElems;
+  return (e + 63) & ~63;
+}
 
-  // ---- ordered compaction: wave w owns rows [w*chunk, (w+1)*chunk)
-  const int chunk = (((c + kSelWaves - 1) / kSelWaves) + 63) & ~63;
-  const int r0 = wv * chunk, r1 = (r0 + chunk < c) ? r0 + chunk : c;
-  uint32_t ngt = 0, neq = 0;
-  for (int base = r0; base < r1; base += 64) {          // wave-uniform trip count
-    const int i = base + lane;
-    const bool in = i < r1;
-    const uint32_t key = in ? f2key(sc[i]) : 0u;
-    ngt += __popcll(__ballot(in && key > thr));
-    neq += __popcll(__ballot(in && key == thr));
-  }
-  if (lane == 0) {
-    cnt_gt[wv] = ngt;
-    cnt_eq[wv] = neq;
-  }
-  __syncthreads();
-  uint32_t gt_before = 0, eq_before = 0;
-  for (int w = 0; w < wv; ++w) {
-    gt_before += cnt_gt[w];
-    eq_before += cnt_eq[w];
-  }
-  uint32_t eq_run = eq_before;
-  uint32_t out_run = gt_before + (eq_before < need ? eq_before : need);
-  for (int base = r0; base < r1; base += 64) {
-    const int i = base + lane;
-    const bool in = i < r1;
-    const float v = in ? sc[i] : 0.f;
-    const uint32_t key = in ? f2key(v) : 0u;
-    const bool gt = in && key > thr, eq = in && key == thr;
-    const uint64_t m_eq = __ballot(eq);
-    const bool take = gt || (eq && eq_run + lanes_below(m_eq) < need);
-    const uint64_t m_take = __ballot(take);
-    if (take) {
-      uint32_t pos = out_run + lanes_below(m_take);
-      if (pos < (uint32_t)ksel) {
-        oi[pos] = gather ? cbg[i] : i;
-        if (os) os[pos] = v;
-      }
-    }
-    eq_run += __popcll(m_eq);
-    out_run += __popcll(m_take);
-  }
+// Called once per context at creation: the score cache needs more dynamic LDS than the default limit.
+hipError_t configure_select(const Shape& s) {
+  return hipFuncSetAttribute((const void*)k_select, hipFuncAttributeMaxDynamicSharedMemorySize, kCacheElems * 4);
 }
 
 hipError_t launch_select(const Shape& s, const float* score, int64_t score_stride, const int32_t* cand,
                          const int32_t* count, const int32_t* k, int32_t* topk_idx, float* topk_score,
                          hipStream_t st) {
-  hipLaunchKernelGGL(k_select, dim3(s.B * s.Hq), dim3(kSelThreads), 0, st, s, score, score_stride, cand, count, k,
-                     topk_idx, topk_score);
+  const int ce = select_cache_elems(s, cand != nullptr);
+  hipLaunchKernelGGL(k_select, dim3(s.B * s.Hq), dim3(kSelThreads), (size_t)ce * 4, st, s, score, score_stride, cand,
+                     count, k, topk_idx, topk_score, ce);
   return hipGetLastError();
 }
 

@@ -47,7 +47,7 @@ def test_config_validation_without_gpu():
             b.workspace_bytes(**{**good, **bad})
         assert ei.value.code == b.LFPS_EINVAL
     with pytest.raises(b.LfpsError) as ei:
-        b.workspace_bytes(**{**good, "max_seq_len": 3_000_000})
+        b.workspace_bytes(**{**good, "max_seq_len": 1_000_000})
     assert ei.value.code == b.LFPS_ECAP
 
 
