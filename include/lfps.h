@@ -127,7 +127,13 @@ int lfps_sparse_attn(lfps_ctx* ctx, const float* q, const lfps_kv* kv, const int
 /* S1..S4 in one call (Alg. 1 lines 6-8 and 10, then Eq. 1): candidates from prev_topk, score,
  * select into topk_idx (this step's index set, the next step's prev_topk), attention into out.
  * S4 reuses S3's scores, so only V rows are gathered.  prev_topk and topk_idx must not overlap.
- *   topk_score [B, Hq, kmax] fp32 out or NULL */
+ *   topk_score [B, Hq, kmax] fp32 out or NULL
+ * With a bf16 cache the scoring pass keeps, per head, only rows whose score reaches the k-th best
+ * score of the PREVIOUS lfps_step call on this context minus a margin (the context remembers one
+ * float per head); a head for which that leaves fewer than k rows is rescored without the filter
+ * in the same call.  The result is therefore the same exact Top-k over the candidates whatever
+ * the remembered value is; only the time differs.  lfps_set_filter(ctx, 0) turns the filter off,
+ * lfps_reset_history forgets the remembered scores (e.g. when the context moves to other requests). */
 int lfps_step(lfps_ctx* ctx, const float* q, const lfps_kv* kv, const int32_t* prev_topk, const int32_t* k,
               int32_t* topk_idx, float* topk_score, float* out, void* stream);
 
@@ -140,6 +146,12 @@ int lfps_full_attn_decode(lfps_ctx* ctx, const float* q, const lfps_kv* kv, floa
  * Also the seed of step 0 (the previous Top-k of the first LFPS step). */
 int lfps_exact_topk(lfps_ctx* ctx, const float* q, const lfps_kv* kv, const int32_t* k, int32_t* topk_idx,
                     float* topk_score, void* stream);
+
+int lfps_set_filter(lfps_ctx* ctx, int32_t on);
+int lfps_reset_history(lfps_ctx* ctx, void* stream);
+/* Copies the candidate counts [B, Hkv] of the last lfps_step call into dst (device, int32),
+ * asynchronously on `stream` (for benchmarks: bytes moved per step). */
+int lfps_copy_cand_count(lfps_ctx* ctx, int32_t* dst, void* stream);
 
 /* Status flags raised by kernels since the last poll.  Synchronises `stream`, copies the flag
  * word to *flags (host) and clears it. */
@@ -161,7 +173,9 @@ enum {
   LFPS_KERNEL_FULL_ATTN = 6,
   LFPS_KERNEL_FULL_MERGE = 7,
   LFPS_KERNEL_HEAD_SCORE = 8,
-  LFPS_N_KERNELS = 9
+  LFPS_KERNEL_FILTER_SCORE = 9,
+  LFPS_KERNEL_FILTER_SELECT = 10,
+  LFPS_N_KERNELS = 11
 };
 #define LFPS_TIMING_MAX_LAUNCHES 4096
 int lfps_timing_enable(lfps_ctx* ctx, int32_t on);

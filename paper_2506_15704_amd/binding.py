@@ -19,7 +19,7 @@ LIB_PATH = os.path.join(_PKG, "liblfps.so")
 LFPS_F32, LFPS_BF16 = 0, 1
 LFPS_OK, LFPS_EINVAL, LFPS_ECAP, LFPS_EHIP, LFPS_ENOMEM = 0, -1, -2, -3, -4
 LFPS_FLAG_CAND_OVERFLOW = 1
-N_KERNELS = 9
+N_KERNELS = 11
 
 
 class LfpsError(RuntimeError):
@@ -64,6 +64,9 @@ def _load() -> ctypes.CDLL:
         "lfps_timing_read": (ctypes.c_int, [P, ctypes.POINTER(ctypes.c_float), ctypes.POINTER(I32), VP]),
         "lfps_kernel_name": (ctypes.c_char_p, [I32]),
         "lfps_calib_copy": (ctypes.c_int, [VP, VP, ctypes.c_int64, VP]),
+        "lfps_set_filter": (ctypes.c_int, [P, I32]),
+        "lfps_reset_history": (ctypes.c_int, [P, VP]),
+        "lfps_copy_cand_count": (ctypes.c_int, [P, VP, VP]),
     }
     for name, (res, args) in sig.items():
         fn = getattr(lib, name)
@@ -222,6 +225,16 @@ class Lfps:
             _ptr(k, torch.int32, (self.B,), "k", d),
             _ptr(topk_idx, torch.int32, (self.B, self.Hq, self.kmax), "topk_idx", d),
             _ptr(topk_score, torch.float32, (self.B, self.Hq, self.kmax), "topk_score", d), self._stream()))
+
+    def lfps_set_filter(self, on: bool):
+        self._check(_lib.lfps_set_filter(self._ctx, int(bool(on))))
+
+    def lfps_reset_history(self):
+        self._check(_lib.lfps_reset_history(self._ctx, self._stream()))
+
+    def lfps_copy_cand_count(self, dst):
+        self._check(_lib.lfps_copy_cand_count(
+            self._ctx, _ptr(dst, torch.int32, (self.B, self.Hkv), "dst", self.device), self._stream()))
 
     def lfps_poll_status(self) -> int:
         flags = ctypes.c_int32(0)

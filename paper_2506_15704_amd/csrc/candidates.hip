@@ -30,7 +30,9 @@ __global__ __launch_bounds__(kCandThreads) void k_candidates(Shape s, const int3
                                                              const int32_t* __restrict__ seq_lens,
                                                              int32_t* __restrict__ cand,
                                                              int32_t* __restrict__ cand_count,
-                                                             int32_t* __restrict__ flags) {
+                                                             int32_t* __restrict__ flags,
+                                                             int32_t* __restrict__ redo_g,
+                                                             int32_t* __restrict__ redo_h) {
   extern __shared__ uint32_t lds[];
   __shared__ int wave_tot[kCandThreads / 64];
   const int bg = blockIdx.x, b = bg / s.Hkv, g = bg % s.Hkv;
@@ -39,6 +41,9 @@ __global__ __launch_bounds__(kCandThreads) void k_candidates(Shape s, const int3
   n = n < 0 ? 0 : (n > s.Lcap ? s.Lcap : n);
   int kb = kk[b];
   kb = kb < 0 ? 0 : (kb > s.kmax ? s.kmax : kb);
+  // first kernel of a step: clear the group's "needs the unfiltered pass" marks
+  if (redo_g && tid == 0) redo_g[bg] = 0;
+  if (redo_h && tid < s.G) redo_h[(int64_t)b * s.Hq + (int64_t)g * s.G + tid] = 0;
   const int W = (n + 31) >> 5;
   uint32_t* bm = lds;
   uint32_t* woff = lds + ((s.Lcap + 31) >> 5);
@@ -159,9 +164,10 @@ hipError_t configure_candidates(const Shape& s) {
 }
 
 hipError_t launch_candidates(const Shape& s, const int32_t* prev_topk, const int32_t* k, const int32_t* seq_lens,
-                             int32_t* cand, int32_t* cand_count, int32_t* flags, hipStream_t st) {
+                             int32_t* cand, int32_t* cand_count, int32_t* flags, int32_t* redo_g, int32_t* redo_h,
+                             hipStream_t st) {
   hipLaunchKernelGGL(k_candidates, dim3(s.B * s.Hkv), dim3(kCandThreads), candidates_lds_bytes(s), st, s, prev_topk, k,
-                     seq_lens, cand, cand_count, flags);
+                     seq_lens, cand, cand_count, flags, redo_g, redo_h);
   return hipGetLastError();
 }
 

@@ -13,8 +13,15 @@ struct lfps_ctx {
   lfps_config cfg;
   Shape shape;
   int n_split_sparse, n_split_full;
+  int filter_on;       // filtered scoring inside lfps_step (bf16 caches)
+  int nseg;            // survivor segments per head
   // workspace (device)
   float* score;        // [B, Hq, score_stride]
+  int32_t* slot;       // [B, Hq, score_stride] candidate slots of the filtered survivors
+  int32_t* seg_count;  // [B, Hq, nseg]
+  float* thr_state;    // [B, Hq] k-th best score of the previous step
+  int32_t* redo_g;     // [B, Hkv]
+  int32_t* redo_h;     // [B, Hq]
   int32_t* cand;       // [B, Hkv, cand_cap]
   int32_t* cand_count; // [B, Hkv]
   float* sel_score;    // [B, Hq, kmax]
@@ -34,13 +41,16 @@ static thread_local char g_create_err[512] = "";
 
 static const char* const kKernelNames[LFPS_N_KERNELS] = {
     "candidates", "gather_score", "select", "sparse_attn", "attn_merge",
-    "dense_score", "full_attn", "full_merge", "head_score"};
+    "dense_score", "full_attn", "full_merge", "head_score", "filter_score", "filter_select"};
+
+// Margin below the previous step's k-th best score at which the filtered pass keeps a row.
+static const float kFilterMargin = 0.125f;
 
 namespace {
 
 struct Sizes {
-  int32_t G, cand_cap, score_stride, n_split_sparse, n_split_full;
-  int64_t score_b, cand_b, count_b, sel_b, part_b, total;
+  int32_t G, cand_cap, score_stride, n_split_sparse, n_split_full, nseg;
+  int64_t score_b, cand_b, count_b, sel_b, part_b, slot_b, seg_b, thr_b, redo_b, total;
 };
 
 int64_t align256(int64_t x) { return (x + 255) & ~(int64_t)255; }
@@ -89,7 +99,14 @@ int check_config(const lfps_config* c, Sizes* z, char* err, size_t errn) {
   int64_t p_sparse = (int64_t)c->batch * c->n_q_heads * z->n_split_sparse * (kD + 1) * 4;
   int64_t p_full = (int64_t)c->batch * c->n_kv_heads * z->n_split_full * G * (kD + 2) * 4;
   z->part_b = align256(p_sparse > p_full ? p_sparse : p_full);
-  z->total = z->score_b + z->cand_b + z->count_b + z->sel_b + z->part_b + 256;
+  const bool filt = c->kv_dtype == LFPS_BF16;
+  z->nseg = 4 * filter_blocks_x(s);
+  z->slot_b = filt ? z->score_b : 0;
+  z->seg_b = align256((int64_t)c->batch * c->n_q_heads * z->nseg * 4);
+  z->thr_b = align256((int64_t)c->batch * c->n_q_heads * 4);
+  z->redo_b = align256((int64_t)c->batch * (c->n_q_heads + c->n_kv_heads) * 4);
+  z->total = z->score_b + z->cand_b + z->count_b + z->sel_b + z->part_b + z->slot_b + z->seg_b + z->thr_b +
+             z->redo_b + 256;
   return LFPS_OK;
 }
 
@@ -127,11 +144,11 @@ struct Timed {
     if (c->timing_on && c->n_timed < LFPS_TIMING_MAX_LAUNCHES) {
       i = c->n_timed++;
       c->ev_slot[i] = (int8_t)slot;
-      hipEventRecord(c->ev[i][0], st);
+      (void)hipEventRecord(c->ev[i][0], st);
     }
   }
   ~Timed() {
-    if (i >= 0) hipEventRecord(c->ev[i][1], st);
+    if (i >= 0) (void)hipEventRecord(c->ev[i][1], st);
   }
 };
 
@@ -213,8 +230,22 @@ int lfps_create(const lfps_config* cfg, lfps_ctx** out) {
   c->cand_count = (int32_t*)(base + z.score_b + z.cand_b);
   c->sel_score = (float*)(base + z.score_b + z.cand_b + z.count_b);
   c->part = (float*)(base + z.score_b + z.cand_b + z.count_b + z.sel_b);
-  c->flags = (int32_t*)(base + z.score_b + z.cand_b + z.count_b + z.sel_b + z.part_b);
+  char* p = base + z.score_b + z.cand_b + z.count_b + z.sel_b + z.part_b;
+  c->slot = z.slot_b ? (int32_t*)p : nullptr;
+  p += z.slot_b;
+  c->seg_count = (int32_t*)p;
+  p += z.seg_b;
+  c->thr_state = (float*)p;
+  p += z.thr_b;
+  c->redo_g = (int32_t*)p;
+  c->redo_h = c->redo_g + (int64_t)cfg->batch * cfg->n_kv_heads;
+  p += z.redo_b;
+  c->flags = (int32_t*)p;
+  c->nseg = z.nseg;
+  c->filter_on = z.slot_b ? 1 : 0;
   e = hipMemset(c->flags, 0, 256);
+  if (e == hipSuccess) e = hipMemset(c->seg_count, 0, (size_t)(z.seg_b + z.redo_b));
+  if (e == hipSuccess) e = hipMemset(c->thr_state, 0xFF, (size_t)z.thr_b);   // all-ones = NaN: "no history"
   if (e == hipSuccess) e = configure_candidates(s);
   if (e == hipSuccess) e = configure_select(s);
   if (e == hipSuccess) e = hipDeviceSynchronize();
@@ -256,7 +287,7 @@ int lfps_candidates(lfps_ctx* ctx, const int32_t* prev_topk, const int32_t* k, c
     return fail(ctx, LFPS_EINVAL, "lfps_candidates: NULL argument");
   hipStream_t st = (hipStream_t)stream;
   LAUNCH(ctx, LFPS_KERNEL_CANDIDATES, st,
-         launch_candidates(ctx->shape, prev_topk, k, seq_lens, cand, cand_count, ctx->flags, st));
+         launch_candidates(ctx->shape, prev_topk, k, seq_lens, cand, cand_count, ctx->flags, nullptr, nullptr, st));
   return LFPS_OK;
 }
 
@@ -273,8 +304,9 @@ int lfps_score_topk(lfps_ctx* ctx, const float* q, const lfps_kv* kv, const int3
   float* sc = cand_score ? cand_score : ctx->score;
   const int64_t stride = cand_score ? s.cand_cap : s.score_stride;
   LAUNCH(ctx, LFPS_KERNEL_GATHER_SCORE, st,
-         launch_group_score(s, ctx->cfg.kv_dtype, q, v, cand, cand_count, sc, stride, st));
-  LAUNCH(ctx, LFPS_KERNEL_SELECT, st, launch_select(s, sc, stride, cand, cand_count, k, topk_idx, topk_score, st));
+         launch_group_score(s, ctx->cfg.kv_dtype, q, v, cand, cand_count, sc, stride, nullptr, st));
+  LAUNCH(ctx, LFPS_KERNEL_SELECT, st,
+         launch_select(s, sc, stride, cand, cand_count, k, topk_idx, topk_score, nullptr, nullptr, st));
   return LFPS_OK;
 }
 
@@ -314,11 +346,26 @@ int lfps_step(lfps_ctx* ctx, const float* q, const lfps_kv* kv, const int32_t* p
   hipStream_t st = (hipStream_t)stream;
   float* sel = topk_score ? topk_score : ctx->sel_score;
   LAUNCH(ctx, LFPS_KERNEL_CANDIDATES, st,
-         launch_candidates(s, prev_topk, k, v.seq_lens, ctx->cand, ctx->cand_count, ctx->flags, st));
+         launch_candidates(s, prev_topk, k, v.seq_lens, ctx->cand, ctx->cand_count, ctx->flags, ctx->redo_g,
+                           ctx->redo_h, st));
+  const int32_t *only_g = nullptr, *only_h = nullptr;
+  if (ctx->filter_on) {
+    // survivors of the per-head threshold first; heads left short are rescored below
+    LAUNCH(ctx, LFPS_KERNEL_FILTER_SCORE, st,
+           launch_filter_score(s, q, v, ctx->cand, ctx->cand_count, ctx->thr_state, kFilterMargin, ctx->score,
+                               ctx->slot, s.score_stride, ctx->seg_count, st));
+    LAUNCH(ctx, LFPS_KERNEL_FILTER_SELECT, st,
+           launch_filter_select(s, ctx->score, ctx->slot, s.score_stride, ctx->seg_count, ctx->nseg, ctx->cand,
+                                ctx->cand_count, k, topk_idx, sel, ctx->thr_state, ctx->redo_g, ctx->redo_h, st));
+    only_g = ctx->redo_g;
+    only_h = ctx->redo_h;
+  }
   LAUNCH(ctx, LFPS_KERNEL_GATHER_SCORE, st,
-         launch_group_score(s, ctx->cfg.kv_dtype, q, v, ctx->cand, ctx->cand_count, ctx->score, s.score_stride, st));
+         launch_group_score(s, ctx->cfg.kv_dtype, q, v, ctx->cand, ctx->cand_count, ctx->score, s.score_stride,
+                            only_g, st));
   LAUNCH(ctx, LFPS_KERNEL_SELECT, st,
-         launch_select(s, ctx->score, s.score_stride, ctx->cand, ctx->cand_count, k, topk_idx, sel, st));
+         launch_select(s, ctx->score, s.score_stride, ctx->cand, ctx->cand_count, k, topk_idx, sel, only_h,
+                       ctx->thr_state, st));
   LAUNCH(ctx, LFPS_KERNEL_SPARSE_ATTN, st, launch_sparse_attn(s, ctx->cfg.kv_dtype, v, topk_idx, sel, k, ctx->part, st));
   LAUNCH(ctx, LFPS_KERNEL_ATTN_MERGE, st, launch_attn_merge(s, k, ctx->part, out, st));
   return LFPS_OK;
@@ -348,9 +395,40 @@ int lfps_exact_topk(lfps_ctx* ctx, const float* q, const lfps_kv* kv, const int3
   hipStream_t st = (hipStream_t)stream;
   const Shape& s = ctx->shape;
   LAUNCH(ctx, LFPS_KERNEL_DENSE_SCORE, st,
-         launch_group_score(s, ctx->cfg.kv_dtype, q, v, nullptr, nullptr, ctx->score, s.score_stride, st));
+         launch_group_score(s, ctx->cfg.kv_dtype, q, v, nullptr, nullptr, ctx->score, s.score_stride, nullptr, st));
   LAUNCH(ctx, LFPS_KERNEL_SELECT, st,
-         launch_select(s, ctx->score, s.score_stride, nullptr, v.seq_lens, k, topk_idx, topk_score, st));
+         launch_select(s, ctx->score, s.score_stride, nullptr, v.seq_lens, k, topk_idx, topk_score, nullptr, nullptr,
+                       st));
+  return LFPS_OK;
+}
+
+__global__ void k_fill_f32(float* p, int n, float v) {
+  const int i = blockIdx.x * 256 + threadIdx.x;
+  if (i < n) p[i] = v;
+}
+
+int lfps_set_filter(lfps_ctx* ctx, int32_t on) {
+  if (!ctx) return LFPS_EINVAL;
+  ctx->filter_on = (on && ctx->slot) ? 1 : 0;
+  return LFPS_OK;
+}
+
+int lfps_reset_history(lfps_ctx* ctx, void* stream) {
+  if (!ctx) return LFPS_EINVAL;
+  const int n = ctx->shape.B * ctx->shape.Hq;
+  hipLaunchKernelGGL(k_fill_f32, dim3((n + 255) / 256), dim3(256), 0, (hipStream_t)stream, ctx->thr_state, n,
+                     __builtin_nanf(""));
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return fail(ctx, LFPS_EHIP, "lfps_reset_history", e);
+  return LFPS_OK;
+}
+
+int lfps_copy_cand_count(lfps_ctx* ctx, int32_t* dst, void* stream) {
+  if (!ctx) return LFPS_EINVAL;
+  if (!dst) return fail(ctx, LFPS_EINVAL, "lfps_copy_cand_count: NULL argument");
+  hipError_t e = hipMemcpyAsync(dst, ctx->cand_count, (size_t)ctx->shape.B * ctx->shape.Hkv * 4,
+                                hipMemcpyDeviceToDevice, (hipStream_t)stream);
+  if (e != hipSuccess) return fail(ctx, LFPS_EHIP, "lfps_copy_cand_count", e);
   return LFPS_OK;
 }
 

@@ -33,19 +33,36 @@ struct Shape {
 // ---- kernel launchers (each enqueues on `st` and returns the launch error) -------------
 hipError_t configure_candidates(const Shape& s);
 hipError_t configure_select(const Shape& s);
+// redo_g [B,Hkv] / redo_h [B,Hq] (or NULL): marks cleared here, set by the filtered select.
 hipError_t launch_candidates(const Shape& s, const int32_t* prev_topk, const int32_t* k, const int32_t* seq_lens,
-                             int32_t* cand, int32_t* cand_count, int32_t* flags, hipStream_t st);
+                             int32_t* cand, int32_t* cand_count, int32_t* flags, int32_t* redo_g, int32_t* redo_h,
+                             hipStream_t st);
 
 // Scores of candidate rows (cand != NULL) or of all rows 0..n_b-1 (cand == NULL) for the G heads
 // of each KV group.  score is [B, Hq, score_stride].
+// only_if [B,Hkv] (or NULL): groups whose entry is 0 are skipped.
 hipError_t launch_group_score(const Shape& s, int dtype, const float* q, const KvView& kv, const int32_t* cand,
-                              const int32_t* cand_count, float* score, int64_t score_stride, hipStream_t st);
+                              const int32_t* cand_count, float* score, int64_t score_stride, const int32_t* only_if,
+                              hipStream_t st);
+
+// Filtered scoring (bf16 cache): per head only rows with score >= thr_state[b,h] - margin are kept, as
+// (score, slot) lists in 4*filter_blocks_x(s) segments per head; see score.hip.
+int filter_blocks_x(const Shape& s);
+hipError_t launch_filter_score(const Shape& s, const float* q, const KvView& kv, const int32_t* cand,
+                               const int32_t* cand_count, const float* thr_state, float margin, float* score,
+                               int32_t* slot_out, int64_t score_stride, int32_t* seg_count, hipStream_t st);
+hipError_t launch_filter_select(const Shape& s, const float* score, const int32_t* slot_in, int64_t score_stride,
+                                const int32_t* seg_count, int nseg, const int32_t* cand, const int32_t* cand_count,
+                                const int32_t* k, int32_t* topk_idx, float* topk_score, float* thr_state,
+                                int32_t* redo_g, int32_t* redo_h, hipStream_t st);
 
 // Per (b, h): the k_b best of score[b,h,0:count]; count = cand_count[b, g(h)] when cand != NULL,
 // else seq_lens[b].  Writes positions (ascending) and their scores.
+// only_if [B,Hq] (or NULL): heads whose entry is 0 are skipped.  thr_state [B,Hq] (or NULL) receives
+// each head's k-th best score.
 hipError_t launch_select(const Shape& s, const float* score, int64_t score_stride, const int32_t* cand,
                          const int32_t* count, const int32_t* k, int32_t* topk_idx, float* topk_score,
-                         hipStream_t st);
+                         const int32_t* only_if, float* thr_state, hipStream_t st);
 
 // Scores of idx[b,h,0:k_b] rows against q[b,h] (one head at a time, no group sharing).
 hipError_t launch_head_score(const Shape& s, int dtype, const float* q, const KvView& kv, const int32_t* idx,

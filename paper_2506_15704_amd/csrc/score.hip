@@ -19,28 +19,52 @@ namespace lfps {
 constexpr int kScoreThreads = 256;           // 4 waves
 constexpr int kRowsPerWaveIter = 64;         // rows a wave scores per loop iteration
 
-// Three-term bf16 split of x: returns term t (0,1,2) as bf16 bits; t == 3 -> 0.
+// Round-to-nearest-even bf16 bits of x (the building block of the three-term split q = q0 + q1 + q2).
 __device__ __forceinline__ uint16_t bf16_rne_bits(float x) {
   uint32_t u = __float_as_uint(x);
   u += 0x7FFFu + ((u >> 16) & 1u);
   return (uint16_t)(u >> 16);
 }
-__device__ __forceinline__ uint16_t split_term(float x, int t) {
-  uint16_t a = bf16_rne_bits(x);
-  if (t == 0) return a;
-  float r1 = x - __uint_as_float((uint32_t)a << 16);
-  uint16_t b = bf16_rne_bits(r1);
-  if (t == 1) return b;
-  float r2 = r1 - __uint_as_float((uint32_t)b << 16);
-  uint16_t c = bf16_rne_bits(r2);
-  return t == 2 ? c : (uint16_t)0;
-}
-
 union Bf16x8Bits {
   bf16x8 v;
   u32x4 u;
   uint16_t h[8];
 };
+
+// The MFMA A operand of lane (j, kb): row m = j of the 16x32 A tile of step kk holds term (m & 3)
+// of head (m >> 2), channels of the 16-byte chunk kk + 4*kb of the row (the chunk that lane group kb
+// loads from K at step kk).  Heads >= G contribute zeros.  The query is fetched with eight 16-byte
+// loads issued together; a lane-dependent branch here would serialise 32 single loads.
+template <int G>
+__device__ __forceinline__ void load_query_operand(bf16x8 (&A)[4], const float* __restrict__ q, int64_t head0, int j,
+                                                   int kb) {
+  const int h = j >> 2, t = j & 3;
+  const float4* qh = reinterpret_cast<const float4*>(q + (head0 + (h < G ? h : 0)) * kD);
+  float4 x[4][2];
+#pragma unroll
+  for (int kk = 0; kk < 4; ++kk) {
+    x[kk][0] = qh[2 * (kk + 4 * kb)];
+    x[kk][1] = qh[2 * (kk + 4 * kb) + 1];
+  }
+  const bool live = h < G && t < 3;
+#pragma unroll
+  for (int kk = 0; kk < 4; ++kk) {
+    const float f[8] = {x[kk][0].x, x[kk][0].y, x[kk][0].z, x[kk][0].w, x[kk][1].x, x[kk][1].y, x[kk][1].z, x[kk][1].w};
+    Bf16x8Bits a;
+#pragma unroll
+    for (int c = 0; c < 8; ++c) {
+      // terms 0, 1, 2 of the three-way bf16 split, selected without branching
+      const uint16_t t0 = bf16_rne_bits(f[c]);
+      const float r1 = f[c] - __uint_as_float((uint32_t)t0 << 16);
+      const uint16_t t1 = bf16_rne_bits(r1);
+      const float r2 = r1 - __uint_as_float((uint32_t)t1 << 16);
+      const uint16_t t2 = bf16_rne_bits(r2);
+      const uint16_t sel = t == 0 ? t0 : (t == 1 ? t1 : t2);
+      a.h[c] = live ? sel : (uint16_t)0;
+    }
+    A[kk] = a.v;
+  }
+}
 
 // ----------------------------------------------------------------------------- bf16, MFMA
 // grid: (tiles_x, B*Hkv).  GATHER: rows come from cand[bg, 0:count]; else rows are 0..n_b-1.
@@ -61,8 +85,9 @@ __global__ __launch_bounds__(kScoreThreads) void k_group_score_bf16(Shape s, con
                                                                     const int32_t* __restrict__ cand,
                                                                     const int32_t* __restrict__ cand_count,
                                                                     float* __restrict__ score, int64_t score_stride,
-                                                                    float scale) {
+                                                                    float scale, const int32_t* __restrict__ only_if) {
   const int bg = blockIdx.y, b = bg / s.Hkv, g = bg % s.Hkv;
+  if (only_if && only_if[bg] == 0) return;      // group already settled by the filtered pass
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int j = lane & 15, kb = lane >> 4;
   int n = seq_lens[b];
@@ -72,23 +97,8 @@ __global__ __launch_bounds__(kScoreThreads) void k_group_score_bf16(Shape s, con
   const int first = (blockIdx.x * 4 + wave) * kRowsPerWaveIter;
   if (first >= count) return;
 
-  // A operand: row m = j of the 16x32 A tile of step kk holds term (m & 3) of head (m >> 2),
-  // channels of chunk kk + 4*kb.  Heads >= G contribute zeros.
   bf16x8 A[4];
-  {
-    const int h = j >> 2, t = j & 3;
-    const float* qh = q + ((int64_t)b * s.Hq + (int64_t)g * G + (h < G ? h : 0)) * kD;
-#pragma unroll
-    for (int kk = 0; kk < 4; ++kk) {
-      Bf16x8Bits a;
-#pragma unroll
-      for (int c = 0; c < 8; ++c) {
-        float x = qh[8 * (kk + 4 * kb) + c];
-        a.h[c] = (h < G) ? split_term(x, t) : (uint16_t)0;
-      }
-      A[kk] = a.v;
-    }
-  }
+  load_query_operand<G>(A, q, (int64_t)b * s.Hq + (int64_t)g * G, j, kb);
 
   const __bf16* Kbg = K + (int64_t)b * stride_b + (int64_t)g * stride_h;
   const int32_t* cbg = GATHER ? cand + (int64_t)bg * s.cand_cap : nullptr;
@@ -137,6 +147,118 @@ __global__ __launch_bounds__(kScoreThreads) void k_group_score_bf16(Shape s, con
   }
 }
 
+// ----------------------------------------------------------------------------- bf16, MFMA, filtered output
+// The same scoring, but only rows whose score reaches a per-head threshold are written out
+// (the threshold is the previous step's k-th best score minus a margin: consecutive decode steps
+// select almost the same rows, the premise of the method).  Writing every score costs far more
+// than its share of bytes because the small writes interleave with the row gather; survivors are
+// a few per cent of the rows.  Wave `wg` of a group owns the contiguous candidate slots
+// [wg*R, (wg+1)*R) and appends its survivors, in slot order, at offset wg*R of each head's score /
+// slot rows (staged in LDS, written when the wave is done); the count goes to seg_count[head, wg].
+// No atomics: the lists are reproducible and ascending in slot.  A threshold of -inf keeps every row; NaN means there is no previous step.
+constexpr int kFilterStage = 256;   // survivors one wave can hold per head before it must write them out
+
+template <int G>
+__global__ __launch_bounds__(kScoreThreads) void k_filter_score_bf16(
+    Shape s, const float* __restrict__ q, const __bf16* __restrict__ K, int64_t stride_b, int64_t stride_h,
+    int64_t stride_n, const int32_t* __restrict__ seq_lens, const int32_t* __restrict__ cand,
+    const int32_t* __restrict__ cand_count, const float* __restrict__ thr_state, float margin,
+    float* __restrict__ score, int32_t* __restrict__ slot_out, int64_t score_stride,
+    int32_t* __restrict__ seg_count, int nseg, float scale) {
+  __shared__ float stage_score[4][G][kFilterStage];
+  __shared__ int32_t stage_slot[4][G][kFilterStage];
+  const int bg = blockIdx.y, b = bg / s.Hkv, g = bg % s.Hkv;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int j = lane & 15, kb = lane >> 4;
+  int n = seq_lens[b];
+  n = n < 0 ? 0 : (n > s.Lcap ? s.Lcap : n);
+  int count = cand_count[bg];
+  count = count < 0 ? 0 : (count > s.cand_cap ? s.cand_cap : count);
+  const int wg = blockIdx.x * 4 + wave;
+  const int R = (((count + nseg - 1) / nseg) + 63) & ~63;
+  const int seg_lo = wg * R;
+  const int seg_hi = seg_lo + R < count ? seg_lo + R : count;
+  const int64_t head = (int64_t)b * s.Hq + (int64_t)g * G + (kb < G ? kb : 0);
+  // NaN in thr_state = "no previous step": skip the group here, the unfiltered pass will take it
+  bool no_history = false;
+#pragma unroll
+  for (int h = 0; h < G; ++h) no_history |= isnan(thr_state[(int64_t)b * s.Hq + (int64_t)g * G + h]);
+  if (seg_lo >= count || no_history) {
+    if (j == 0 && kb < G) seg_count[head * nseg + wg] = 0;
+    return;
+  }
+  const float tau = kb < G ? thr_state[head] - margin : INFINITY;
+
+  bf16x8 A[4];
+  load_query_operand<G>(A, q, (int64_t)b * s.Hq + (int64_t)g * G, j, kb);
+  const __bf16* Kbg = K + (int64_t)b * stride_b + (int64_t)g * stride_h;
+  const int32_t* cbg = cand + (int64_t)bg * s.cand_cap;
+  float* sc = score + head * score_stride + seg_lo;
+  int32_t* so = slot_out + head * score_stride + seg_lo;
+  const uint32_t below = (1u << j) - 1u;            // lanes of my 16-lane group with a lower row
+  int run = 0;                                        // survivors of my head already in global memory
+  int staged = 0;                                     // survivors of my head waiting in LDS
+
+  // Survivors are staged in LDS and written out when the wave is done (or the stage is nearly
+  // full).  Global stores inside the loop would share the vector-memory counter with the row
+  // loads, so that every wait for a load would also wait for the stores before it.
+  float* st_s = stage_score[wave][kb < G ? kb : 0];
+  int32_t* st_i = stage_slot[wave][kb < G ? kb : 0];
+  auto flush = [&]() {
+#pragma unroll
+    for (int h = 0; h < G; ++h) {
+      const int cnt_h = __shfl(staged, 16 * h);
+      const int run_h = __shfl(run, 16 * h);
+      float* dsc = score + ((int64_t)b * s.Hq + (int64_t)g * G + h) * score_stride + seg_lo + run_h;
+      int32_t* dsl = slot_out + ((int64_t)b * s.Hq + (int64_t)g * G + h) * score_stride + seg_lo + run_h;
+      for (int e = lane; e < cnt_h; e += 64) {
+        dsc[e] = stage_score[wave][h][e];
+        dsl[e] = stage_slot[wave][h][e];
+      }
+    }
+    run += staged;
+    staged = 0;
+  };
+
+  int my_row = -1;
+  if (seg_lo + lane < seg_hi) my_row = cbg[seg_lo + lane];
+  for (int base = seg_lo; base < seg_hi; base += kRowsPerWaveIter) {
+    bf16x8 Bt[4][4];
+#pragma unroll
+    for (int t = 0; t < 4; ++t) {
+      int row = __shfl(my_row, 16 * t + j);
+      row = (row < 0 || row >= n) ? 0 : row;          // padding slots read row 0 and are never kept
+      const bf16x8* p = reinterpret_cast<const bf16x8*>(Kbg + (int64_t)row * stride_n) + 4 * kb;
+#pragma unroll
+      for (int kk = 0; kk < 4; ++kk) Bt[t][kk] = p[kk];
+    }
+    const int nb = base + kRowsPerWaveIter;
+    int next_row = -1;
+    if (nb + lane < seg_hi) next_row = cbg[nb + lane];
+#pragma unroll
+    for (int t = 0; t < 4; ++t) {
+      f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+      for (int kk = 0; kk < 4; ++kk) acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(A[kk], Bt[t][kk], acc, 0, 0, 0);
+      const float v = ((acc[0] + acc[1]) + acc[2]) * scale;
+      const int slot = base + 16 * t + j;
+      const bool pass = kb < G && slot < seg_hi && v >= tau;
+      const uint32_t gm = (uint32_t)(__ballot(pass) >> (16 * kb)) & 0xFFFFu;   // my head's 16 rows
+      if (pass) {
+        const int o = staged + __popc(gm & below);
+        st_s[o] = v;
+        st_i[o] = slot;
+      }
+      staged += __popc(gm);
+    }
+    // room for one more iteration (64 rows) in every head's stage?  (wave-uniform test)
+    if (__ballot(staged > kFilterStage - kRowsPerWaveIter)) flush();
+    my_row = next_row;
+  }
+  flush();
+  if (j == 0 && kb < G) seg_count[head * nseg + wg] = run;
+}
+
 // ----------------------------------------------------------------------------- fp32, vector ALU
 template <int G, bool GATHER>
 __global__ __launch_bounds__(kScoreThreads) void k_group_score_f32(Shape s, const float* __restrict__ q,
@@ -146,8 +268,9 @@ __global__ __launch_bounds__(kScoreThreads) void k_group_score_f32(Shape s, cons
                                                                    const int32_t* __restrict__ cand,
                                                                    const int32_t* __restrict__ cand_count,
                                                                    float* __restrict__ score, int64_t score_stride,
-                                                                   float scale) {
+                                                                   float scale, const int32_t* __restrict__ only_if) {
   const int bg = blockIdx.y, b = bg / s.Hkv, g = bg % s.Hkv;
+  if (only_if && only_if[bg] == 0) return;
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int j = lane & 15, rs = lane >> 4;     // 16 lanes per row, 4 rows per wave instruction
   int n = seq_lens[b];
@@ -261,7 +384,8 @@ __global__ __launch_bounds__(256) void k_head_score(Shape s, const float* __rest
 // ----------------------------------------------------------------------------- launchers
 template <int G, bool GATHER>
 static hipError_t launch_gs(const Shape& s, int dtype, const float* q, const KvView& kv, const int32_t* cand,
-                            const int32_t* cand_count, float* score, int64_t score_stride, hipStream_t st) {
+                            const int32_t* cand_count, float* score, int64_t score_stride, const int32_t* only_if,
+                            hipStream_t st) {
   const int rows_max = GATHER ? s.cand_cap : s.Lcap;
   const int per_block = 4 * kRowsPerWaveIter;
   int tiles = (rows_max + per_block - 1) / per_block;
@@ -273,25 +397,54 @@ static hipError_t launch_gs(const Shape& s, int dtype, const float* q, const KvV
   const float scale = 0.08838834764831845f;   // 1/sqrt(128)
   if (dtype == LFPS_BF16)
     hipLaunchKernelGGL((k_group_score_bf16<G, GATHER>), grid, block, 0, st, s, q, (const __bf16*)kv.k, kv.stride_b,
-                       kv.stride_h, kv.stride_n, kv.seq_lens, cand, cand_count, score, score_stride, scale);
+                       kv.stride_h, kv.stride_n, kv.seq_lens, cand, cand_count, score, score_stride, scale, only_if);
   else
     hipLaunchKernelGGL((k_group_score_f32<G, GATHER>), grid, block, 0, st, s, q, (const float*)kv.k, kv.stride_b,
-                       kv.stride_h, kv.stride_n, kv.seq_lens, cand, cand_count, score, score_stride, scale);
+                       kv.stride_h, kv.stride_n, kv.seq_lens, cand, cand_count, score, score_stride, scale, only_if);
   return hipGetLastError();
 }
 
 hipError_t launch_group_score(const Shape& s, int dtype, const float* q, const KvView& kv, const int32_t* cand,
-                              const int32_t* cand_count, float* score, int64_t score_stride, hipStream_t st) {
+                              const int32_t* cand_count, float* score, int64_t score_stride, const int32_t* only_if,
+                              hipStream_t st) {
   const bool gather = cand != nullptr;
   switch (s.G) {
-    case 1: return gather ? launch_gs<1, true>(s, dtype, q, kv, cand, cand_count, score, score_stride, st)
-                          : launch_gs<1, false>(s, dtype, q, kv, cand, cand_count, score, score_stride, st);
-    case 2: return gather ? launch_gs<2, true>(s, dtype, q, kv, cand, cand_count, score, score_stride, st)
-                          : launch_gs<2, false>(s, dtype, q, kv, cand, cand_count, score, score_stride, st);
-    case 4: return gather ? launch_gs<4, true>(s, dtype, q, kv, cand, cand_count, score, score_stride, st)
-                          : launch_gs<4, false>(s, dtype, q, kv, cand, cand_count, score, score_stride, st);
+    case 1: return gather ? launch_gs<1, true>(s, dtype, q, kv, cand, cand_count, score, score_stride, only_if, st)
+                          : launch_gs<1, false>(s, dtype, q, kv, cand, cand_count, score, score_stride, only_if, st);
+    case 2: return gather ? launch_gs<2, true>(s, dtype, q, kv, cand, cand_count, score, score_stride, only_if, st)
+                          : launch_gs<2, false>(s, dtype, q, kv, cand, cand_count, score, score_stride, only_if, st);
+    case 4: return gather ? launch_gs<4, true>(s, dtype, q, kv, cand, cand_count, score, score_stride, only_if, st)
+                          : launch_gs<4, false>(s, dtype, q, kv, cand, cand_count, score, score_stride, only_if, st);
     default: return hipErrorInvalidValue;
   }
+}
+
+int filter_blocks_x(const Shape& s) {
+  int gx = (256 * 4 + s.B * s.Hkv - 1) / (s.B * s.Hkv);   // about four workgroups per CU in total
+  const int tiles = (s.cand_cap + 4 * kRowsPerWaveIter - 1) / (4 * kRowsPerWaveIter);
+  if (gx > tiles) gx = tiles;
+  if (gx > 128) gx = 128;                                  // 4*gx segments per group, <= 1024 / 2
+  return gx < 1 ? 1 : gx;
+}
+
+hipError_t launch_filter_score(const Shape& s, const float* q, const KvView& kv, const int32_t* cand,
+                               const int32_t* cand_count, const float* thr_state, float margin, float* score,
+                               int32_t* slot_out, int64_t score_stride, int32_t* seg_count, hipStream_t st) {
+  const int gx = filter_blocks_x(s);
+  dim3 grid(gx, s.B * s.Hkv), block(kScoreThreads);
+  const float scale = 0.08838834764831845f;
+#define LFPS_LAUNCH_FILTER(GG)                                                                                     \
+  hipLaunchKernelGGL((k_filter_score_bf16<GG>), grid, block, 0, st, s, q, (const __bf16*)kv.k, kv.stride_b,       \
+                     kv.stride_h, kv.stride_n, kv.seq_lens, cand, cand_count, thr_state, margin, score, slot_out, \
+                     score_stride, seg_count, 4 * gx, scale)
+  switch (s.G) {
+    case 1: LFPS_LAUNCH_FILTER(1); break;
+    case 2: LFPS_LAUNCH_FILTER(2); break;
+    case 4: LFPS_LAUNCH_FILTER(4); break;
+    default: return hipErrorInvalidValue;
+  }
+#undef LFPS_LAUNCH_FILTER
+  return hipGetLastError();
 }
 
 hipError_t launch_head_score(const Shape& s, int dtype, const float* q, const KvView& kv, const int32_t* idx,

@@ -90,18 +90,22 @@ __device__ __forceinline__ void find_bin(SelectShared& sm, uint32_t need, int ti
     __VA_ARGS__                                                              \
   }
 
+// `slot_of` (LDS, or NULL for identity) maps an element of the scored list to its candidate slot;
+// `cbg` (or NULL for identity) maps a candidate slot to its position.  `thr_out` receives the
+// k-th largest score.
 template <bool CACHED>
 __device__ __forceinline__ void select_body(SelectShared& sm, float* __restrict__ cache,
                                             const float* __restrict__ sc, int c, int ksel,
-                                            const int32_t* __restrict__ cbg, int32_t* __restrict__ oi,
-                                            float* __restrict__ os) {
+                                            const int32_t* __restrict__ slot_of, const int32_t* __restrict__ cbg,
+                                            int32_t* __restrict__ oi, float* __restrict__ os,
+                                            float* __restrict__ thr_out) {
   const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
   const int chunk = (((c + kSelWaves - 1) / kSelWaves) + 63) & ~63;
   const int r0 = wv * chunk, r1 = (r0 + chunk < c) ? r0 + chunk : c;
   const int nit = r1 > r0 ? (r1 - r0 + 63) >> 6 : 0;
 
   // ---- 1. load (once, into LDS, if the head fits) and block min / max
-  if (CACHED) {
+  if (CACHED && sc) {                      // sc == NULL: the caller has already filled the cache
 #pragma unroll 8
     for (int it = 0; it < nit; ++it) {
       const int i = r0 + 64 * it + lane;
@@ -201,6 +205,7 @@ __device__ __forceinline__ void select_body(SelectShared& sm, float* __restrict_
     __syncthreads();
   }
   const float thr = key2f(sm.thr);          // the ksel-th largest score
+  if (thr_out && tid == 0) *thr_out = thr;
   const uint32_t need_eq = sm.need_eq;      // rows equal to it that are taken
 
   // ---- 5. ordered compaction
@@ -228,7 +233,8 @@ __device__ __forceinline__ void select_body(SelectShared& sm, float* __restrict_
       if (take) {
         const uint32_t pos = out_run + lanes_below(m_take);
         if (pos < (uint32_t)ksel) {
-          oi[pos] = cbg ? cbg[i] : i;
+          const int sl = slot_of ? slot_of[i] : i;
+          oi[pos] = cbg ? cbg[sl] : sl;
           if (os) os[pos] = x;
         }
       }
@@ -246,7 +252,8 @@ __device__ __forceinline__ void select_body(SelectShared& sm, float* __restrict_
       if (take) {
         const uint32_t pos = out_run + lanes_below(m_take);
         if (pos < (uint32_t)ksel) {
-          oi[pos] = cbg ? cbg[i] : i;
+          const int sl = slot_of ? slot_of[i] : i;
+          oi[pos] = cbg ? cbg[sl] : sl;
           if (os) os[pos] = x;
         }
       }
@@ -262,19 +269,22 @@ __device__ __forceinline__ void select_body(SelectShared& sm, float* __restrict_
 // the register-resident variant.
 __device__ __noinline__ void select_stream(SelectShared& sm, const float* __restrict__ sc, int c, int ksel,
                                            const int32_t* __restrict__ cbg, int32_t* __restrict__ oi,
-                                           float* __restrict__ os) {
-  select_body<false>(sm, nullptr, sc, c, ksel, cbg, oi, os);
+                                           float* __restrict__ os, float* __restrict__ thr_out) {
+  select_body<false>(sm, nullptr, sc, c, ksel, nullptr, cbg, oi, os, thr_out);
 }
 
 __global__ __launch_bounds__(kSelThreads) void k_select(Shape s, const float* __restrict__ score,
                                                         int64_t score_stride, const int32_t* __restrict__ cand,
                                                         const int32_t* __restrict__ count_arr,
                                                         const int32_t* __restrict__ kk, int32_t* __restrict__ topk_idx,
-                                                        float* __restrict__ topk_score, int cache_elems) {
+                                                        float* __restrict__ topk_score, int cache_elems,
+                                                        const int32_t* __restrict__ only_if,
+                                                        float* __restrict__ thr_state) {
   __shared__ SelectShared sm;
   extern __shared__ float cache[];
   const int bh = blockIdx.x, b = bh / s.Hq, h = bh % s.Hq, g = h / s.G;
   const int tid = threadIdx.x;
+  if (only_if && only_if[bh] == 0) return;          // this head was already settled by the filtered pass
   const bool gather = cand != nullptr;
   int c = gather ? count_arr[b * s.Hkv + g] : count_arr[b];
   const int c_max = gather ? s.cand_cap : s.Lcap;
@@ -289,15 +299,111 @@ __global__ __launch_bounds__(kSelThreads) void k_select(Shape s, const float* __
     oi[i] = -1;
     if (os) os[i] = 0.f;
   }
-  if (ksel == 0) return;
+  float* thr_out = thr_state ? thr_state + bh : nullptr;
+  if (ksel == 0) {
+    if (thr_out && tid == 0) *thr_out = -INFINITY;
+    return;
+  }
 
   const float* sc = score + (int64_t)bh * score_stride;
   const int32_t* cbg = gather ? cand + ((int64_t)b * s.Hkv + g) * s.cand_cap : nullptr;
   if (c <= cache_elems)
-    select_body<true>(sm, cache, sc, c, ksel, cbg, oi, os);
+    select_body<true>(sm, cache, sc, c, ksel, nullptr, cbg, oi, os, thr_out);
   else
-    select_stream(sm, sc, c, ksel, cbg, oi, os);
+    select_stream(sm, sc, c, ksel, cbg, oi, os, thr_out);
 }
+
+// ----------------------------------------------------------------------------- filtered input
+// Select from the survivor lists written by the filtered score kernel: segment sgm of head (b, h)
+// holds seg_count[bh, sgm] (score, slot) pairs at offset sgm * R of the head's score / slot rows,
+// ascending in slot within and across segments.  If the survivors are fewer than k (the filter
+// threshold was too high) or more than the LDS list holds, the head is flagged for the unfiltered
+// pass instead and nothing is written.
+__device__ __forceinline__ int filter_segment_rows(int count, int nseg) { return (((count + nseg - 1) / nseg) + 63) & ~63; }
+
+__global__ __launch_bounds__(kSelThreads) void k_filter_select(Shape s, const float* __restrict__ score,
+                                                               const int32_t* __restrict__ slot_in,
+                                                               int64_t score_stride,
+                                                               const int32_t* __restrict__ seg_count, int nseg,
+                                                               const int32_t* __restrict__ cand,
+                                                               const int32_t* __restrict__ cand_count,
+                                                               const int32_t* __restrict__ kk,
+                                                               int32_t* __restrict__ topk_idx,
+                                                               float* __restrict__ topk_score,
+                                                               float* __restrict__ thr_state,
+                                                               int32_t* __restrict__ redo_g,
+                                                               int32_t* __restrict__ redo_h, int cap) {
+  __shared__ SelectShared sm;
+  __shared__ int seg_off[kSelThreads + 1];
+  __shared__ int wtot[kSelWaves];
+  extern __shared__ float cache[];                 // cap scores, then cap slots
+  int32_t* lslot = reinterpret_cast<int32_t*>(cache + cap);
+  const int bh = blockIdx.x, b = bh / s.Hq, h = bh % s.Hq, g = h / s.G;
+  const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
+  int c = cand_count[b * s.Hkv + g];
+  c = c < 0 ? 0 : (c > s.cand_cap ? s.cand_cap : c);
+  int kb = kk[b];
+  kb = kb < 0 ? 0 : (kb > s.kmax ? s.kmax : kb);
+  const int ksel = kb < c ? kb : c;
+  const int R = filter_segment_rows(c, nseg);
+
+  // exclusive prefix of the segment counts (nseg <= 1024: one per thread)
+  int cnt = 0;
+  if (tid < nseg) {
+    cnt = seg_count[(int64_t)bh * nseg + tid];
+    const int room = c - tid * R;                    // rows the segment can hold
+    cnt = cnt < 0 ? 0 : (cnt > R ? R : cnt);
+    cnt = room <= 0 ? 0 : (cnt > room ? room : cnt);
+  }
+  int inc = cnt;
+#pragma unroll
+  for (int d = 1; d < 64; d <<= 1) {
+    int o = __shfl_up(inc, d);
+    if (lane >= d) inc += o;
+  }
+  if (lane == 63) wtot[wv] = inc;
+  __syncthreads();
+  int base = 0, n = 0;
+#pragma unroll
+  for (int w = 0; w < kSelWaves; ++w) {
+    const int t = wtot[w];
+    base += w < wv ? t : 0;
+    n += t;
+  }
+  seg_off[tid] = base + inc - cnt;
+  if (tid == 0) seg_off[kSelThreads] = n;
+  if (n < ksel || n > cap) {                        // block-uniform
+    if (tid == 0) {
+      redo_g[b * s.Hkv + g] = 1;
+      redo_h[bh] = 1;
+    }
+    return;
+  }
+  int32_t* oi = topk_idx + (int64_t)bh * s.kmax;
+  float* os = topk_score ? topk_score + (int64_t)bh * s.kmax : nullptr;
+  for (int i = ksel + tid; i < s.kmax; i += kSelThreads) {   // padding
+    oi[i] = -1;
+    if (os) os[i] = 0.f;
+  }
+  if (ksel == 0) {
+    if (tid == 0) thr_state[bh] = -INFINITY;
+    return;
+  }
+  __syncthreads();
+  const float* sc = score + (int64_t)bh * score_stride;
+  const int32_t* sl = slot_in + (int64_t)bh * score_stride;
+  for (int sgm = wv; sgm < nseg; sgm += kSelWaves) {
+    const int o = seg_off[sgm], e_n = (sgm + 1 < nseg ? seg_off[sgm + 1] : n) - o;
+    for (int e = lane; e < e_n; e += 64) {
+      cache[o + e] = sanitize(sc[(int64_t)sgm * R + e]);
+      lslot[o + e] = sl[(int64_t)sgm * R + e];
+    }
+  }
+  __syncthreads();
+  const int32_t* cbg = cand + ((int64_t)b * s.Hkv + g) * s.cand_cap;
+  select_body<true>(sm, cache, nullptr, n, ksel, lslot, cbg, oi, os, thr_state + bh);
+}
+
 
 static int select_cache_elems(const Shape& s, bool gather) {
   const int rows_max = gather ? s.cand_cap : s.Lcap;
@@ -305,17 +411,38 @@ static int select_cache_elems(const Shape& s, bool gather) {
   return (e + 63) & ~63;
 }
 
+int filter_list_cap(const Shape& s) {
+  int cap = 4 * s.kmax;
+  if (cap < 1024) cap = 1024;
+  if (cap > 7680) cap = 7680;   // 60 KB of LDS: two workgroups per CU
+  return cap;
+}
+
 // Called once per context at creation: the score cache needs more dynamic LDS than the default limit.
 hipError_t configure_select(const Shape& s) {
-  return hipFuncSetAttribute((const void*)k_select, hipFuncAttributeMaxDynamicSharedMemorySize, kCacheElems * 4);
+  hipError_t e = hipFuncSetAttribute((const void*)k_select, hipFuncAttributeMaxDynamicSharedMemorySize, kCacheElems * 4);
+  if (e != hipSuccess) return e;
+  return hipFuncSetAttribute((const void*)k_filter_select, hipFuncAttributeMaxDynamicSharedMemorySize,
+                             filter_list_cap(s) * 8);
 }
 
 hipError_t launch_select(const Shape& s, const float* score, int64_t score_stride, const int32_t* cand,
                          const int32_t* count, const int32_t* k, int32_t* topk_idx, float* topk_score,
-                         hipStream_t st) {
+                         const int32_t* only_if, float* thr_state, hipStream_t st) {
   const int ce = select_cache_elems(s, cand != nullptr);
   hipLaunchKernelGGL(k_select, dim3(s.B * s.Hq), dim3(kSelThreads), (size_t)ce * 4, st, s, score, score_stride, cand,
-                     count, k, topk_idx, topk_score, ce);
+                     count, k, topk_idx, topk_score, ce, only_if, thr_state);
+  return hipGetLastError();
+}
+
+hipError_t launch_filter_select(const Shape& s, const float* score, const int32_t* slot_in, int64_t score_stride,
+                                const int32_t* seg_count, int nseg, const int32_t* cand, const int32_t* cand_count,
+                                const int32_t* k, int32_t* topk_idx, float* topk_score, float* thr_state,
+                                int32_t* redo_g, int32_t* redo_h, hipStream_t st) {
+  const int cap = filter_list_cap(s);
+  hipLaunchKernelGGL(k_filter_select, dim3(s.B * s.Hq), dim3(kSelThreads), (size_t)cap * 8, st, s, score, slot_in,
+                     score_stride, seg_count, nseg, cand, cand_count, k, topk_idx, topk_score, thr_state, redo_g,
+                     redo_h, cap);
   return hipGetLastError();
 }
 

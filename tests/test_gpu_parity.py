@@ -431,5 +431,44 @@ def test_timing_interface(small_bf16):
         ctx.lfps_step(dc.q(1), kv, a, dc.k, b_, out)
     tm = ctx.lfps_timing_read()
     assert tm["gather_score"][1] == 3 and tm["candidates"][1] == 3 and tm["dense_score"][1] == 1
+    assert tm["filter_score"][1] == 3 and tm["filter_select"][1] == 3
     assert tm["select"][1] == 4 and tm["gather_score"][0] > 0
     assert all(v == (0.0, 0) for v in ctx.lfps_timing_read().values())
+
+
+# ------------------------------------------------------------------------ filtered scoring inside lfps_step
+def test_filtered_step_equals_unfiltered_step_whatever_the_history(small_bf16):
+    """lfps_step with the score filter (history from the previous call, including deliberately wrong
+    histories that force the rescoring path) returns bit-identical Top-k and outputs to the
+    unfiltered path."""
+    dc = small_bf16
+    case, spec = dc.case, dc.spec
+    ref, flt = dc.make_ctx(), dc.make_ctx()
+    ref.lfps_set_filter(False)
+    shp = (spec.B, spec.Hq, case.kmax)
+    prev = dev(_teacher_inputs(dc, 1))
+    flt.lfps_timing_enable(True)
+    used_filter = 0
+    for rnd, (t, qscale) in enumerate([(1, 1.0), (2, 1.0), (3, 1.0), (3, 4.0), (4, 1.0), (2, 0.01), (3, 1.0), (4, 1.0)]):
+        kv = ref.kv_view(dc.K, dc.V, dc.seq_lens(t))
+        q = dc.q(t) * qscale                      # scaled queries leave a history that is far too high / low
+        outs = []
+        for ctx in (ref, flt):
+            idx = torch.zeros(shp, dtype=torch.int32, device=DEV)
+            sc = torch.zeros(shp, dtype=torch.float32, device=DEV)
+            out = torch.zeros((spec.B, spec.Hq, spec.D), dtype=torch.float32, device=DEV)
+            ctx.lfps_step(q, kv, prev, dc.k, idx, out, sc)
+            outs.append((idx.cpu().numpy(), sc.cpu().numpy(), out.cpu().numpy()))
+        for a, b_ in zip(*outs):
+            np.testing.assert_array_equal(a, b_, err_msg=f"round {rnd}")
+        tm = flt.lfps_timing_read()
+        assert tm["filter_score"][1] == 1 and tm["filter_select"][1] == 1
+        prev = torch.from_numpy(outs[0][0]).to(DEV)
+    flt.lfps_reset_history()
+    kv = ref.kv_view(dc.K, dc.V, dc.seq_lens(4))
+    a = torch.zeros(shp, dtype=torch.int32, device=DEV)
+    b_ = torch.zeros_like(a)
+    out = torch.zeros((spec.B, spec.Hq, spec.D), dtype=torch.float32, device=DEV)
+    ref.lfps_step(dc.q(4), kv, prev, dc.k, a, out)
+    flt.lfps_step(dc.q(4), kv, prev, dc.k, b_, out)
+    np.testing.assert_array_equal(a.cpu().numpy(), b_.cpu().numpy())
