@@ -7,7 +7,8 @@
 // spans, which also dedupes within a head and across the G heads of the group.  A popcount +
 // block scan then assigns each word its output offset and the set bits are emitted in ascending
 // order, so the output is sorted and identical from run to run.  (The G <= 4 heads per group
-// that the library supports are unrolled.)
+// that the library supports are unrolled.)  Capacity: 64 * 1024 rounds of words is far above what
+// the LDS bitmap can hold, so the bitmap size is the limit.
 #include "lfps_internal.h"
 
 namespace lfps {
@@ -24,7 +25,8 @@ __device__ __forceinline__ void set_bit_range(uint32_t* bm, int lo, int hi) {  /
   }
 }
 
-// Dynamic LDS: bitmap words [W] followed by the exclusive output offset of every word [W].
+// Dynamic LDS: bitmap words [ceil(Lcap/32)], round counts/offsets [ceil(words/64)], then a
+// 4 KB stage per wave (64 words x 32 bits as 16-bit (word-in-round, bit) codes).
 __global__ __launch_bounds__(kCandThreads) void k_candidates(Shape s, const int32_t* __restrict__ prev_topk,
                                                              const int32_t* __restrict__ kk,
                                                              const int32_t* __restrict__ seq_lens,
@@ -46,7 +48,9 @@ __global__ __launch_bounds__(kCandThreads) void k_candidates(Shape s, const int3
   if (redo_h && tid < s.G) redo_h[(int64_t)b * s.Hq + (int64_t)g * s.G + tid] = 0;
   const int W = (n + 31) >> 5;
   uint32_t* bm = lds;
-  uint32_t* woff = lds + ((s.Lcap + 31) >> 5);
+  const int words_cap = (s.Lcap + 31) >> 5;
+  uint32_t* rcnt = lds + words_cap;
+  uint16_t* stage = reinterpret_cast<uint16_t*>(rcnt + ((words_cap + 63) >> 6));
 
   // The previous Top-k of the group's heads: issue every load of a round before touching LDS, so
   // their latencies overlap (4 heads x 2 entries per thread and round).
@@ -99,16 +103,21 @@ __global__ __launch_bounds__(kCandThreads) void k_candidates(Shape s, const int3
   }
   __syncthreads();
 
-  // exclusive output offset of every word: each thread scans a contiguous slice of words,
-  // then a block scan of the slice totals
-  const int wpt = (W + kCandThreads - 1) / kCandThreads;
-  const int w_lo = tid * wpt, w_hi = (w_lo + wpt < W) ? w_lo + wpt : W;
-  int cnt = 0;
-  for (int w = w_lo; w < w_hi; ++w) {
-    woff[w] = (uint32_t)cnt;
-    cnt += __popc(bm[w]);
-  }
+  // Emit in rounds of 64 consecutive words, one round per wave at a time.
+  // (a) set bits per round, (b) exclusive offsets of the rounds by a block scan, (c) per round:
+  // every lane expands its word into a wave-private LDS stage at the lane's offset within the
+  // round, then the wave copies the stage out with consecutive lanes writing consecutive entries.
   const int lane = tid & 63, wv = tid >> 6;
+  const int nr = (W + 63) >> 6;                                  // rounds (<= kCandThreads, checked at creation)
+  for (int r_ = wv; r_ < nr; r_ += kCandThreads / 64) {
+    const int w = r_ * 64 + lane;
+    int c_ = w < W ? __popc(bm[w]) : 0;
+#pragma unroll
+    for (int d = 1; d < 64; d <<= 1) c_ += __shfl_xor(c_, d);
+    if (lane == 0) rcnt[r_] = (uint32_t)c_;
+  }
+  __syncthreads();
+  int cnt = tid < nr ? (int)rcnt[tid] : 0;
   int inc = cnt;
 #pragma unroll
   for (int d = 1; d < 64; d <<= 1) {
@@ -124,21 +133,38 @@ __global__ __launch_bounds__(kCandThreads) void k_candidates(Shape s, const int3
     if (i < wv) base += t;
     total += t;
   }
-  const int slice_off = base + inc - cnt;
-  for (int w = w_lo; w < w_hi; ++w) woff[w] += (uint32_t)slice_off;
+  if (tid < nr) rcnt[tid] = (uint32_t)(base + inc - cnt);        // now the exclusive offset of round tid
   __syncthreads();
 
-  // emit: consecutive threads expand consecutive words, so a wave writes one contiguous stretch
   int32_t* out = cand + (int64_t)bg * s.cand_cap;
-  for (int w = tid; w < W; w += kCandThreads) {
-    uint32_t bits = bm[w];
-    int off = (int)woff[w];
+  uint16_t* st = stage + wv * 2048;
+  for (int r_ = wv; r_ < nr; r_ += kCandThreads / 64) {
+    const int w = r_ * 64 + lane;
+    uint32_t bits = w < W ? bm[w] : 0u;
+    const int c_ = __popc(bits);
+    int incl = c_;
+#pragma unroll
+    for (int d = 1; d < 64; d <<= 1) {
+      int o = __shfl_up(incl, d);
+      if (lane >= d) incl += o;
+    }
+    const int tot = __shfl(incl, 63);
+    int o_ = incl - c_;
     while (bits) {
       const int p = __ffs(bits) - 1;
       bits &= bits - 1;
-      if (off < s.cand_cap) out[off] = (w << 5) + p;
-      ++off;
+      st[o_++] = (uint16_t)((lane << 5) | p);
     }
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+    const int ro = (int)rcnt[r_];
+    for (int e = lane; e < tot; e += 64) {
+      const uint32_t v = st[e];
+      if (ro + e < s.cand_cap) out[ro + e] = (((r_ << 6) + (int)(v >> 5)) << 5) + (int)(v & 31u);
+    }
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
   }
   if (tid == 0) {
     if (total > s.cand_cap) {
@@ -150,8 +176,8 @@ __global__ __launch_bounds__(kCandThreads) void k_candidates(Shape s, const int3
 }
 
 static size_t candidates_lds_bytes(const Shape& s) {
-  size_t b = ((size_t)(s.Lcap + 31) / 32) * 8;     // bitmap + per-word offsets
-  return b < 8 ? 8 : b;
+  const size_t words = ((size_t)s.Lcap + 31) / 32;
+  return words * 4 + ((words + 63) / 64) * 4 + (kCandThreads / 64) * 4096;   // bitmap + round offsets + stages
 }
 
 // Called once per context at creation: raises the kernel's dynamic-LDS limit when the bitmap of

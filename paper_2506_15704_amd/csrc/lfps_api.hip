@@ -75,10 +75,10 @@ int check_config(const lfps_config* c, Sizes* z, char* err, size_t errn) {
   if (c->cand_cap < 0) BAD("cand_cap must be >= 0");
   if (c->device < 0) BAD("device must be >= 0");
 #undef BAD
-  // LDS of the candidate kernel: one bit plus 1/32 of a 4-byte offset per position, 160 KB per workgroup
-  if (((int64_t)c->max_seq_len + 31) / 32 * 8 > 156 * 1024) {
+  // LDS of the candidate kernel: one bit per position beside 64 KB of staging, 160 KB per workgroup
+  if (((int64_t)c->max_seq_len + 31) / 32 * 4 > 88 * 1024) {
     snprintf(err, errn, "max_seq_len %d exceeds the candidate bitmap capacity (%d positions)", c->max_seq_len,
-             156 * 1024 * 4);
+             88 * 1024 * 8);
     return LFPS_ECAP;
   }
   int64_t bound = (int64_t)G * c->max_k * (2 * (int64_t)c->radius + 2) + c->n_recent + c->n_sink;

@@ -420,7 +420,7 @@ hipError_t launch_group_score(const Shape& s, int dtype, const float* q, const K
 }
 
 int filter_blocks_x(const Shape& s) {
-  int gx = (256 * 4 + s.B * s.Hkv - 1) / (s.B * s.Hkv);   // about four workgroups per CU in total
+  int gx = (256 * 2 + s.B * s.Hkv - 1) / (s.B * s.Hkv);   // about two workgroups (8 waves) per CU in total
   const int tiles = (s.cand_cap + 4 * kRowsPerWaveIter - 1) / (4 * kRowsPerWaveIter);
   if (gx > tiles) gx = tiles;
   if (gx > 128) gx = 128;                                  // 4*gx segments per group, <= 1024 / 2

@@ -23,18 +23,18 @@
 
 namespace lfps {
 
-constexpr int kSelThreads = 1024;
-constexpr int kSelWaves = kSelThreads / 64;
-constexpr int kBins = 2048;
-constexpr int kCacheElems = 32768;  // scores of one head kept in LDS (dynamic, 128 KB)
-constexpr int kListCap = 1024;  // members of the threshold bin ranked directly
+constexpr int kSelThreads = 1024;       // workgroup of the general kernel
+constexpr int kFilterSelThreads = 256;  // workgroup of the kernel that selects from the short survivor lists
+constexpr int kCacheElems = 32768;      // scores of one head kept in LDS (dynamic, 128 KB)
 
+// NT threads: 2*NT histogram bins (two per thread), up to NT members of the threshold bin ranked directly.
+template <int NT>
 struct SelectShared {
-  uint32_t hist[kBins];
-  uint32_t list[kListCap];
-  uint32_t wsum[kSelWaves];
-  float wlo[kSelWaves], whi[kSelWaves];
-  uint32_t cnt_gt[kSelWaves], cnt_eq[kSelWaves];
+  uint32_t hist[2 * NT];
+  uint32_t list[NT];
+  uint32_t wsum[NT / 64];
+  float wlo[NT / 64], whi[NT / 64];
+  uint32_t cnt_gt[NT / 64], cnt_eq[NT / 64];
   uint32_t need, bin, list_n, thr, need_eq;
 };
 
@@ -52,7 +52,9 @@ __device__ __forceinline__ float key2f(uint32_t k) {       // inverse of f2key
 
 // Largest digit d (bins 2t, 2t+1 owned by thread t) whose suffix count reaches `need`.
 // Writes sm.bin = d and sm.need = need - (count in bins above d).  All threads must call.
-__device__ __forceinline__ void find_bin(SelectShared& sm, uint32_t need, int tid, int lane, int wv) {
+template <int NT>
+__device__ __forceinline__ void find_bin(SelectShared<NT>& sm, uint32_t need, int tid, int lane, int wv) {
+  constexpr int kSelWaves = NT / 64;
   const uint32_t lo = sm.hist[2 * tid], hi = sm.hist[2 * tid + 1];
   const uint32_t mine = lo + hi;
   uint32_t inc = mine;                       // inclusive suffix sum within the wave
@@ -93,12 +95,13 @@ __device__ __forceinline__ void find_bin(SelectShared& sm, uint32_t need, int ti
 // `slot_of` (LDS, or NULL for identity) maps an element of the scored list to its candidate slot;
 // `cbg` (or NULL for identity) maps a candidate slot to its position.  `thr_out` receives the
 // k-th largest score.
-template <bool CACHED>
-__device__ __forceinline__ void select_body(SelectShared& sm, float* __restrict__ cache,
+template <bool CACHED, int NT>
+__device__ __forceinline__ void select_body(SelectShared<NT>& sm, float* __restrict__ cache,
                                             const float* __restrict__ sc, int c, int ksel,
                                             const int32_t* __restrict__ slot_of, const int32_t* __restrict__ cbg,
                                             int32_t* __restrict__ oi, float* __restrict__ os,
                                             float* __restrict__ thr_out) {
+  constexpr int kSelWaves = NT / 64, kBins = 2 * NT, kListCap = NT;
   const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
   const int chunk = (((c + kSelWaves - 1) / kSelWaves) + 63) & ~63;
   const int r0 = wv * chunk, r1 = (r0 + chunk < c) ? r0 + chunk : c;
@@ -123,7 +126,7 @@ __device__ __forceinline__ void select_body(SelectShared& sm, float* __restrict_
     sm.wlo[wv] = lo;
     sm.whi[wv] = hi;
   }
-  for (int i = tid; i < kBins; i += kSelThreads) sm.hist[i] = 0u;
+  for (int i = tid; i < kBins; i += NT) sm.hist[i] = 0u;
   if (tid == 0) sm.list_n = 0u;
   __syncthreads();
 #pragma unroll
@@ -182,10 +185,14 @@ __device__ __forceinline__ void select_body(SelectShared& sm, float* __restrict_
   } else {
     uint32_t prefix = 0, mask = 0;
 #pragma unroll 1
-    for (int pass = 0; pass < 3; ++pass) {
-      const int shift = pass == 0 ? 21 : (pass == 1 ? 10 : 0);
-      const uint32_t dmask = pass == 2 ? 1023u : 2047u;
-      for (int i = tid; i < kBins; i += kSelThreads) sm.hist[i] = 0u;
+    for (int pass = 0; pass < 4; ++pass) {
+      // digits of log2(kBins) bits from the top; the last pass takes what is left
+      constexpr int kDigit = NT == 1024 ? 11 : 9;
+      constexpr int kPasses = (32 + kDigit - 1) / kDigit;
+      if (pass >= kPasses) break;
+      const int shift = 32 - kDigit * (pass + 1) > 0 ? 32 - kDigit * (pass + 1) : 0;
+      const uint32_t dmask = (pass == kPasses - 1) ? ((1u << (32 - kDigit * (kPasses - 1))) - 1u) : ((1u << kDigit) - 1u);
+      for (int i = tid; i < kBins; i += NT) sm.hist[i] = 0u;
       __syncthreads();
       LFPS_FOR_EACH(if (in && LFPS_BIN(x) == tb) {
         const uint32_t key = f2key(x);
@@ -267,10 +274,10 @@ __device__ __forceinline__ void select_body(SelectShared& sm, float* __restrict_
 
 // The streaming variant is a real call, so that its code does not compete for registers with
 // the register-resident variant.
-__device__ __noinline__ void select_stream(SelectShared& sm, const float* __restrict__ sc, int c, int ksel,
+__device__ __noinline__ void select_stream(SelectShared<kSelThreads>& sm, const float* __restrict__ sc, int c, int ksel,
                                            const int32_t* __restrict__ cbg, int32_t* __restrict__ oi,
                                            float* __restrict__ os, float* __restrict__ thr_out) {
-  select_body<false>(sm, nullptr, sc, c, ksel, nullptr, cbg, oi, os, thr_out);
+  select_body<false, kSelThreads>(sm, nullptr, sc, c, ksel, nullptr, cbg, oi, os, thr_out);
 }
 
 __global__ __launch_bounds__(kSelThreads) void k_select(Shape s, const float* __restrict__ score,
@@ -280,7 +287,7 @@ __global__ __launch_bounds__(kSelThreads) void k_select(Shape s, const float* __
                                                         float* __restrict__ topk_score, int cache_elems,
                                                         const int32_t* __restrict__ only_if,
                                                         float* __restrict__ thr_state) {
-  __shared__ SelectShared sm;
+  __shared__ SelectShared<kSelThreads> sm;
   extern __shared__ float cache[];
   const int bh = blockIdx.x, b = bh / s.Hq, h = bh % s.Hq, g = h / s.G;
   const int tid = threadIdx.x;
@@ -308,7 +315,7 @@ __global__ __launch_bounds__(kSelThreads) void k_select(Shape s, const float* __
   const float* sc = score + (int64_t)bh * score_stride;
   const int32_t* cbg = gather ? cand + ((int64_t)b * s.Hkv + g) * s.cand_cap : nullptr;
   if (c <= cache_elems)
-    select_body<true>(sm, cache, sc, c, ksel, nullptr, cbg, oi, os, thr_out);
+    select_body<true, kSelThreads>(sm, cache, sc, c, ksel, nullptr, cbg, oi, os, thr_out);
   else
     select_stream(sm, sc, c, ksel, cbg, oi, os, thr_out);
 }
@@ -321,7 +328,7 @@ __global__ __launch_bounds__(kSelThreads) void k_select(Shape s, const float* __
 // pass instead and nothing is written.
 __device__ __forceinline__ int filter_segment_rows(int count, int nseg) { return (((count + nseg - 1) / nseg) + 63) & ~63; }
 
-__global__ __launch_bounds__(kSelThreads) void k_filter_select(Shape s, const float* __restrict__ score,
+__global__ __launch_bounds__(kFilterSelThreads) void k_filter_select(Shape s, const float* __restrict__ score,
                                                                const int32_t* __restrict__ slot_in,
                                                                int64_t score_stride,
                                                                const int32_t* __restrict__ seg_count, int nseg,
@@ -333,8 +340,9 @@ __global__ __launch_bounds__(kSelThreads) void k_filter_select(Shape s, const fl
                                                                float* __restrict__ thr_state,
                                                                int32_t* __restrict__ redo_g,
                                                                int32_t* __restrict__ redo_h, int cap) {
-  __shared__ SelectShared sm;
-  __shared__ int seg_off[kSelThreads + 1];
+  constexpr int NT = kFilterSelThreads, kSelWaves = NT / 64;
+  __shared__ SelectShared<NT> sm;
+  __shared__ int seg_off[512];
   __shared__ int wtot[kSelWaves];
   extern __shared__ float cache[];                 // cap scores, then cap slots
   int32_t* lslot = reinterpret_cast<int32_t*>(cache + cap);
@@ -347,14 +355,19 @@ __global__ __launch_bounds__(kSelThreads) void k_filter_select(Shape s, const fl
   const int ksel = kb < c ? kb : c;
   const int R = filter_segment_rows(c, nseg);
 
-  // exclusive prefix of the segment counts (nseg <= 1024: one per thread)
-  int cnt = 0;
-  if (tid < nseg) {
-    cnt = seg_count[(int64_t)bh * nseg + tid];
-    const int room = c - tid * R;                    // rows the segment can hold
-    cnt = cnt < 0 ? 0 : (cnt > R ? R : cnt);
-    cnt = room <= 0 ? 0 : (cnt > room ? room : cnt);
+  // exclusive prefix of the segment counts (nseg <= 512: two consecutive segments per thread)
+  int cnt2[2] = {0, 0};
+#pragma unroll
+  for (int u = 0; u < 2; ++u) {
+    const int sgm = 2 * tid + u;
+    if (sgm < nseg) {
+      int v = seg_count[(int64_t)bh * nseg + sgm];
+      const int room = c - sgm * R;                  // rows the segment can hold
+      v = v < 0 ? 0 : (v > R ? R : v);
+      cnt2[u] = room <= 0 ? 0 : (v > room ? room : v);
+    }
   }
+  const int cnt = cnt2[0] + cnt2[1];
   int inc = cnt;
 #pragma unroll
   for (int d = 1; d < 64; d <<= 1) {
@@ -370,8 +383,8 @@ __global__ __launch_bounds__(kSelThreads) void k_filter_select(Shape s, const fl
     base += w < wv ? t : 0;
     n += t;
   }
-  seg_off[tid] = base + inc - cnt;
-  if (tid == 0) seg_off[kSelThreads] = n;
+  seg_off[2 * tid] = base + inc - cnt;
+  seg_off[2 * tid + 1] = base + inc - cnt + cnt2[0];
   if (n < ksel || n > cap) {                        // block-uniform
     if (tid == 0) {
       redo_g[b * s.Hkv + g] = 1;
@@ -381,7 +394,7 @@ __global__ __launch_bounds__(kSelThreads) void k_filter_select(Shape s, const fl
   }
   int32_t* oi = topk_idx + (int64_t)bh * s.kmax;
   float* os = topk_score ? topk_score + (int64_t)bh * s.kmax : nullptr;
-  for (int i = ksel + tid; i < s.kmax; i += kSelThreads) {   // padding
+  for (int i = ksel + tid; i < s.kmax; i += NT) {   // padding
     oi[i] = -1;
     if (os) os[i] = 0.f;
   }
@@ -392,16 +405,21 @@ __global__ __launch_bounds__(kSelThreads) void k_filter_select(Shape s, const fl
   __syncthreads();
   const float* sc = score + (int64_t)bh * score_stride;
   const int32_t* sl = slot_in + (int64_t)bh * score_stride;
-  for (int sgm = wv; sgm < nseg; sgm += kSelWaves) {
-    const int o = seg_off[sgm], e_n = (sgm + 1 < nseg ? seg_off[sgm + 1] : n) - o;
-    for (int e = lane; e < e_n; e += 64) {
-      cache[o + e] = sanitize(sc[(int64_t)sgm * R + e]);
-      lslot[o + e] = sl[(int64_t)sgm * R + e];
+  // flat copy of the survivors into LDS: element e lies in the segment found by a binary search over
+  // the offsets, so every load of the copy is independent of the others
+  for (int e = tid; e < n; e += NT) {
+    int lo_s = 0, hi_s = nseg - 1;                  // last segment with seg_off <= e
+    while (lo_s < hi_s) {
+      const int mid = (lo_s + hi_s + 1) >> 1;
+      if (seg_off[mid] <= e) lo_s = mid; else hi_s = mid - 1;
     }
+    const int64_t src = (int64_t)lo_s * R + (e - seg_off[lo_s]);
+    cache[e] = sanitize(sc[src]);
+    lslot[e] = sl[src];
   }
   __syncthreads();
   const int32_t* cbg = cand + ((int64_t)b * s.Hkv + g) * s.cand_cap;
-  select_body<true>(sm, cache, nullptr, n, ksel, lslot, cbg, oi, os, thr_state + bh);
+  select_body<true, NT>(sm, cache, nullptr, n, ksel, lslot, cbg, oi, os, thr_state + bh);
 }
 
 
@@ -440,7 +458,7 @@ hipError_t launch_filter_select(const Shape& s, const float* score, const int32_
                                 const int32_t* k, int32_t* topk_idx, float* topk_score, float* thr_state,
                                 int32_t* redo_g, int32_t* redo_h, hipStream_t st) {
   const int cap = filter_list_cap(s);
-  hipLaunchKernelGGL(k_filter_select, dim3(s.B * s.Hq), dim3(kSelThreads), (size_t)cap * 8, st, s, score, slot_in,
+  hipLaunchKernelGGL(k_filter_select, dim3(s.B * s.Hq), dim3(kFilterSelThreads), (size_t)cap * 8, st, s, score, slot_in,
                      score_stride, seg_count, nseg, cand, cand_count, k, topk_idx, topk_score, thr_state, redo_g,
                      redo_h, cap);
   return hipGetLastError();
