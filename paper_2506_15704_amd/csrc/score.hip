@@ -153,8 +153,8 @@ __global__ __launch_bounds__(kScoreThreads) void k_group_score_bf16(Shape s, con
 // select almost the same rows, the premise of the method).  Writing every score costs far more
 // than its share of bytes because the small writes interleave with the row gather; survivors are
 // a few per cent of the rows.  Wave `wg` of a group owns the contiguous candidate slots
-// [wg*R, (wg+1)*R) and appends its survivors, in slot order, at offset wg*R of each head's score /
-// slot rows (staged in LDS, written when the wave is done); the count goes to seg_count[head, wg].
+// [wg*R, (wg+1)*R) and appends its survivors (score, row position), in slot order, at offset wg*R
+// of each head's score / position rows (staged in LDS, written when the wave is done); the count goes to seg_count[head, wg].
 // No atomics: the lists are reproducible and ascending in slot.  A threshold of -inf keeps every row; NaN means there is no previous step.
 constexpr int kFilterStage = 256;   // survivors one wave can hold per head before it must write them out
 
@@ -224,10 +224,12 @@ __global__ __launch_bounds__(kScoreThreads) void k_filter_score_bf16(
   if (seg_lo + lane < seg_hi) my_row = cbg[seg_lo + lane];
   for (int base = seg_lo; base < seg_hi; base += kRowsPerWaveIter) {
     bf16x8 Bt[4][4];
+    int rows[4];
 #pragma unroll
     for (int t = 0; t < 4; ++t) {
       int row = __shfl(my_row, 16 * t + j);
       row = (row < 0 || row >= n) ? 0 : row;          // padding slots read row 0 and are never kept
+      rows[t] = row;
       const bf16x8* p = reinterpret_cast<const bf16x8*>(Kbg + (int64_t)row * stride_n) + 4 * kb;
 #pragma unroll
       for (int kk = 0; kk < 4; ++kk) Bt[t][kk] = p[kk];
@@ -247,7 +249,7 @@ __global__ __launch_bounds__(kScoreThreads) void k_filter_score_bf16(
       if (pass) {
         const int o = staged + __popc(gm & below);
         st_s[o] = v;
-        st_i[o] = slot;
+        st_i[o] = rows[t];                            // the row position itself: the select needs no lookup
       }
       staged += __popc(gm);
     }

@@ -215,39 +215,58 @@ __device__ __forceinline__ void select_body(SelectShared<NT>& sm, float* __restr
   if (thr_out && tid == 0) *thr_out = thr;
   const uint32_t need_eq = sm.need_eq;      // rows equal to it that are taken
 
-  // ---- 5. ordered compaction
-  uint32_t ngt = 0, neq = 0;
-  LFPS_FOR_EACH(ngt += __popcll(__ballot(in && x > thr)); neq += __popcll(__ballot(in && x == thr));)
-  if (lane == 0) {
-    sm.cnt_gt[wv] = ngt;
-    sm.cnt_eq[wv] = neq;
-  }
-  __syncthreads();
-  uint32_t gt_before = 0, eq_before = 0, eq_total = 0;
+  // ---- 5. ordered compaction: every row above the threshold, plus the first need_eq rows equal to it
+  if (CACHED) {
+    // Thread t owns the contiguous elements [t*E, (t+1)*E) of the LDS copy (E odd: no bank conflicts).
+    // Count, one block scan, write: no cross-lane traffic inside the loops.
+    const int E = ((c + NT - 1) / NT) | 1;
+    const int e0 = tid * E < c ? tid * E : c, e1 = e0 + E < c ? e0 + E : c;
+    uint32_t mine = 0;                                  // (rows > thr) << 16 | (rows == thr)
+    for (int i = e0; i < e1; ++i) {
+      const float x = cache[i];
+      mine += (x > thr ? 0x10000u : 0u) + (x == thr ? 1u : 0u);
+    }
+    uint32_t inc = mine;
 #pragma unroll
-  for (int w = 0; w < kSelWaves; ++w) {
-    const uint32_t g_ = sm.cnt_gt[w], e_ = sm.cnt_eq[w];
-    gt_before += w < wv ? g_ : 0u;
-    eq_before += w < wv ? e_ : 0u;
-    eq_total += e_;
-  }
-  if (eq_total == need_eq) {
-    // every row equal to the threshold is taken (the usual case): one comparison per row
-    uint32_t out_run = gt_before + eq_before;
-    LFPS_FOR_EACH({
-      const bool take = in && x >= thr;
-      const uint64_t m_take = __ballot(take);
+    for (int d = 1; d < 64; d <<= 1) {
+      const uint32_t o = __shfl_up(inc, d);
+      if (lane >= d) inc += o;
+    }
+    if (lane == 63) sm.cnt_gt[wv] = inc;
+    __syncthreads();
+    uint32_t before = inc - mine;
+#pragma unroll
+    for (int w = 0; w < kSelWaves; ++w) before += w < wv ? sm.cnt_gt[w] : 0u;
+    uint32_t eq_run = before & 0xFFFFu;
+    uint32_t pos = (before >> 16) + (eq_run < need_eq ? eq_run : need_eq);
+    for (int i = e0; i < e1; ++i) {
+      const float x = cache[i];
+      const bool eq = x == thr;
+      const bool take = x > thr || (eq && eq_run < need_eq);
+      eq_run += eq ? 1u : 0u;
       if (take) {
-        const uint32_t pos = out_run + lanes_below(m_take);
         if (pos < (uint32_t)ksel) {
           const int sl = slot_of ? slot_of[i] : i;
           oi[pos] = cbg ? cbg[sl] : sl;
           if (os) os[pos] = x;
         }
+        ++pos;
       }
-      out_run += __popcll(m_take);
-    })
+    }
   } else {
+    uint32_t ngt = 0, neq = 0;
+    LFPS_FOR_EACH(ngt += __popcll(__ballot(in && x > thr)); neq += __popcll(__ballot(in && x == thr));)
+    if (lane == 0) {
+      sm.cnt_gt[wv] = ngt;
+      sm.cnt_eq[wv] = neq;
+    }
+    __syncthreads();
+    uint32_t gt_before = 0, eq_before = 0;
+#pragma unroll
+    for (int w = 0; w < kSelWaves; ++w) {
+      gt_before += w < wv ? sm.cnt_gt[w] : 0u;
+      eq_before += w < wv ? sm.cnt_eq[w] : 0u;
+    }
     uint32_t eq_run = eq_before;
     uint32_t out_run = gt_before + (eq_before < need_eq ? eq_before : need_eq);
     LFPS_FOR_EACH({
@@ -322,8 +341,8 @@ __global__ __launch_bounds__(kSelThreads) void k_select(Shape s, const float* __
 
 // ----------------------------------------------------------------------------- filtered input
 // Select from the survivor lists written by the filtered score kernel: segment sgm of head (b, h)
-// holds seg_count[bh, sgm] (score, slot) pairs at offset sgm * R of the head's score / slot rows,
-// ascending in slot within and across segments.  If the survivors are fewer than k (the filter
+// holds seg_count[bh, sgm] (score, row position) pairs at offset sgm * R of the head's score /
+// position rows, ascending in position within and across segments.  If the survivors are fewer than k (the filter
 // threshold was too high) or more than the LDS list holds, the head is flagged for the unfiltered
 // pass instead and nothing is written.
 __device__ __forceinline__ int filter_segment_rows(int count, int nseg) { return (((count + nseg - 1) / nseg) + 63) & ~63; }
@@ -344,7 +363,7 @@ __global__ __launch_bounds__(kFilterSelThreads) void k_filter_select(Shape s, co
   __shared__ SelectShared<NT> sm;
   __shared__ int seg_off[512];
   __shared__ int wtot[kSelWaves];
-  extern __shared__ float cache[];                 // cap scores, then cap slots
+  extern __shared__ float cache[];                 // cap scores, then cap row positions
   int32_t* lslot = reinterpret_cast<int32_t*>(cache + cap);
   const int bh = blockIdx.x, b = bh / s.Hq, h = bh % s.Hq, g = h / s.G;
   const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
@@ -415,11 +434,10 @@ __global__ __launch_bounds__(kFilterSelThreads) void k_filter_select(Shape s, co
     }
     const int64_t src = (int64_t)lo_s * R + (e - seg_off[lo_s]);
     cache[e] = sanitize(sc[src]);
-    lslot[e] = sl[src];
+    lslot[e] = sl[src];                               // the row position, written by the scoring pass
   }
   __syncthreads();
-  const int32_t* cbg = cand + ((int64_t)b * s.Hkv + g) * s.cand_cap;
-  select_body<true, NT>(sm, cache, nullptr, n, ksel, lslot, cbg, oi, os, thr_state + bh);
+  select_body<true, NT>(sm, cache, nullptr, n, ksel, lslot, nullptr, oi, os, thr_state + bh);
 }
 
 
