@@ -37,15 +37,20 @@ __global__ __launch_bounds__(kCandThreads) void k_candidates(Shape s, const int3
                                                              int32_t* __restrict__ redo_h) {
   extern __shared__ uint32_t lds[];
   __shared__ int wave_tot[kCandThreads / 64];
-  const int bg = blockIdx.x, b = bg / s.Hkv, g = bg % s.Hkv;
+  // gridDim.x workgroups share one (b, g): each builds the whole bitmap (cheap) and emits every
+  // gridDim.x-th round of words, so that small batches still spread over the chip.
+  const int bg = blockIdx.y, b = bg / s.Hkv, g = bg % s.Hkv;
+  const int part = blockIdx.x, nparts = gridDim.x;
   const int tid = threadIdx.x;
   int n = seq_lens[b];
   n = n < 0 ? 0 : (n > s.Lcap ? s.Lcap : n);
   int kb = kk[b];
   kb = kb < 0 ? 0 : (kb > s.kmax ? s.kmax : kb);
   // first kernel of a step: clear the group's "needs the unfiltered pass" marks
-  if (redo_g && tid == 0) redo_g[bg] = 0;
-  if (redo_h && tid < s.G) redo_h[(int64_t)b * s.Hq + (int64_t)g * s.G + tid] = 0;
+  if (part == 0) {
+    if (redo_g && tid == 0) redo_g[bg] = 0;
+    if (redo_h && tid < s.G) redo_h[(int64_t)b * s.Hq + (int64_t)g * s.G + tid] = 0;
+  }
   const int W = (n + 31) >> 5;
   uint32_t* bm = lds;
   const int words_cap = (s.Lcap + 31) >> 5;
@@ -78,7 +83,7 @@ __global__ __launch_bounds__(kCandThreads) void k_candidates(Shape s, const int3
       set_bit_range(bm, lo, hi64 > n - 1 ? n - 1 : (int)hi64);
     }
   }
-  for (int j0 = kU * kCandThreads; j0 < kb; j0 += kU * kCandThreads) {   // budgets beyond 2048 per head
+  for (int j0 = kU * kCandThreads; j0 < kb; j0 += kU * kCandThreads) {   // budgets beyond kU * kCandThreads per head
     int ids[4 * kU];
 #pragma unroll
     for (int h = 0; h < 4; ++h)
@@ -138,7 +143,7 @@ __global__ __launch_bounds__(kCandThreads) void k_candidates(Shape s, const int3
 
   int32_t* out = cand + (int64_t)bg * s.cand_cap;
   uint16_t* st = stage + wv * 2048;
-  for (int r_ = wv; r_ < nr; r_ += kCandThreads / 64) {
+  for (int r_ = wv * nparts + part; r_ < nr; r_ += (kCandThreads / 64) * nparts) {
     const int w = r_ * 64 + lane;
     uint32_t bits = w < W ? bm[w] : 0u;
     const int c_ = __popc(bits);
@@ -166,7 +171,7 @@ __global__ __launch_bounds__(kCandThreads) void k_candidates(Shape s, const int3
     __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
     __builtin_amdgcn_wave_barrier();
   }
-  if (tid == 0) {
+  if (tid == 0 && part == 0) {
     if (total > s.cand_cap) {
       atomicOr(flags, LFPS_FLAG_CAND_OVERFLOW);
       total = s.cand_cap;
@@ -192,8 +197,10 @@ hipError_t configure_candidates(const Shape& s) {
 hipError_t launch_candidates(const Shape& s, const int32_t* prev_topk, const int32_t* k, const int32_t* seq_lens,
                              int32_t* cand, int32_t* cand_count, int32_t* flags, int32_t* redo_g, int32_t* redo_h,
                              hipStream_t st) {
-  hipLaunchKernelGGL(k_candidates, dim3(s.B * s.Hkv), dim3(kCandThreads), candidates_lds_bytes(s), st, s, prev_topk, k,
-                     seq_lens, cand, cand_count, flags, redo_g, redo_h);
+  int nparts = 256 / (s.B * s.Hkv);                    // one workgroup per CU in total (82 KB of LDS each)
+  nparts = nparts < 1 ? 1 : (nparts > 8 ? 8 : nparts);
+  hipLaunchKernelGGL(k_candidates, dim3(nparts, s.B * s.Hkv), dim3(kCandThreads), candidates_lds_bytes(s), st, s,
+                     prev_topk, k, seq_lens, cand, cand_count, flags, redo_g, redo_h);
   return hipGetLastError();
 }
 

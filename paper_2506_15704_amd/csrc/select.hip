@@ -465,7 +465,9 @@ hipError_t configure_select(const Shape& s) {
 hipError_t launch_select(const Shape& s, const float* score, int64_t score_stride, const int32_t* cand,
                          const int32_t* count, const int32_t* k, int32_t* topk_idx, float* topk_score,
                          const int32_t* only_if, float* thr_state, hipStream_t st) {
-  const int ce = select_cache_elems(s, cand != nullptr);
+  // A conditional launch (only_if) is expected to find nothing to do: it streams from global memory
+  // instead of reserving the LDS cache, so that its workgroups are cheap to place and retire.
+  const int ce = only_if ? 0 : select_cache_elems(s, cand != nullptr);
   hipLaunchKernelGGL(k_select, dim3(s.B * s.Hq), dim3(kSelThreads), (size_t)ce * 4, st, s, score, score_stride, cand,
                      count, k, topk_idx, topk_score, ce, only_if, thr_state);
   return hipGetLastError();
