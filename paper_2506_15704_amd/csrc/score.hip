@@ -220,23 +220,20 @@ __global__ __launch_bounds__(kScoreThreads) void k_filter_score_bf16(
     staged = 0;
   };
 
-  int my_row = -1;
-  if (seg_lo + lane < seg_hi) my_row = cbg[seg_lo + lane];
-  for (int base = seg_lo; base < seg_hi; base += kRowsPerWaveIter) {
-    bf16x8 Bt[4][4];
-    int rows[4];
+  // Two 64-row tiles are kept in flight per wave: while tile i is multiplied, the loads of tile
+  // i+1 (issued before) are still arriving, and the row ids of tile i+2 are being fetched.
+  auto issue = [&](bf16x8 (&Bt)[4][4], int (&rows)[4], int ids) {
 #pragma unroll
     for (int t = 0; t < 4; ++t) {
-      int row = __shfl(my_row, 16 * t + j);
+      int row = __shfl(ids, 16 * t + j);
       row = (row < 0 || row >= n) ? 0 : row;          // padding slots read row 0 and are never kept
       rows[t] = row;
       const bf16x8* p = reinterpret_cast<const bf16x8*>(Kbg + (int64_t)row * stride_n) + 4 * kb;
 #pragma unroll
       for (int kk = 0; kk < 4; ++kk) Bt[t][kk] = p[kk];
     }
-    const int nb = base + kRowsPerWaveIter;
-    int next_row = -1;
-    if (nb + lane < seg_hi) next_row = cbg[nb + lane];
+  };
+  auto consume = [&](bf16x8 (&Bt)[4][4], int (&rows)[4], int base) {
 #pragma unroll
     for (int t = 0; t < 4; ++t) {
       f32x4 acc = {0.f, 0.f, 0.f, 0.f};
@@ -253,9 +250,31 @@ __global__ __launch_bounds__(kScoreThreads) void k_filter_score_bf16(
       }
       staged += __popc(gm);
     }
-    // room for one more iteration (64 rows) in every head's stage?  (wave-uniform test)
+    // room for one more tile (64 rows) in every head's stage?  (wave-uniform test)
     if (__ballot(staged > kFilterStage - kRowsPerWaveIter)) flush();
-    my_row = next_row;
+  };
+  auto fetch_ids = [&](int base) { return base + lane < seg_hi ? cbg[base + lane] : -1; };
+
+  bf16x8 Bt0[4][4], Bt1[4][4];
+  int rows0[4], rows1[4];
+  constexpr int T = kRowsPerWaveIter;
+  issue(Bt0, rows0, fetch_ids(seg_lo));
+  int ids_b = fetch_ids(seg_lo + T);                  // ids of the tile whose loads are issued next
+  for (int base = seg_lo; base < seg_hi; base += 2 * T) {
+    const bool has_b = base + T < seg_hi;             // wave-uniform
+    int ids_a2 = -1;
+    if (has_b) {
+      issue(Bt1, rows1, ids_b);
+      ids_a2 = fetch_ids(base + 2 * T);
+    }
+    consume(Bt0, rows0, base);
+    if (has_b) {
+      if (base + 2 * T < seg_hi) {
+        issue(Bt0, rows0, ids_a2);
+        ids_b = fetch_ids(base + 3 * T);
+      }
+      consume(Bt1, rows1, base + T);
+    }
   }
   flush();
   if (j == 0 && kb < G) seg_count[head * nseg + wg] = run;
