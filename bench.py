@@ -24,9 +24,11 @@ if ROOT not in sys.path:
 
 HBM_PEAK_GBS = 8000.0   # MI355X published HBM3E peak
 
-# HBM bytes per gather_score launch measured with rocprofv3 --pmc (FETCH_SIZE, WRITE_SIZE), scaled by
-# the same counters' reading for a plain copy kernel; see profiles/ for the runs.  None = not measured.
-MEASURED_TRAFFIC_BYTES = {"C4": 1019.6e6}   # profiles/lfps_kernels_C4.md: 958.2 MB fetched + 61.4 MB written
+# HBM bytes per launch of the scoring kernel measured with rocprofv3 --pmc (FETCH_SIZE, WRITE_SIZE), scaled
+# by the same counters' reading for a plain copy kernel; see profiles/ for the runs.  None = not measured.
+# Median over the steady-state dispatches of the scoring kernel (k_filter_score_bf16):
+#   profiles/lfps_kernels_C4.md: 938.6 MB fetched + 10.2 MB written; profiles/lfps_kernels_C3.md: 221.6 + 2.8 MB.
+MEASURED_TRAFFIC_BYTES = {"C4": 948.8e6, "C3": 224.4e6}
 
 
 def parse_args():
