@@ -113,6 +113,42 @@ class Runner:
         torch.cuda.synchronize()
         return (time.perf_counter() - t0) / steps
 
+    def run_timed_graph(self, steps, warmup):
+        """The same K steps captured once into a HIP graph and replayed: removes the host launch gaps
+        between the kernels of a step.  Returns (seconds per step, outputs equal to the eager run?)."""
+        torch = self.torch
+
+        def prepare():
+            self.reset()
+            self.ctx.lfps_reset_history()
+            for _ in range(warmup):
+                self.step()
+            torch.cuda.synchronize()
+
+        prepare()
+        state = (self.t, self.prev, self.cur)
+        for _ in range(steps):                       # eager reference of the final state
+            self.step()
+        torch.cuda.synchronize()
+        ref_idx, ref_out = self.prev.clone(), self.out.clone()
+        prepare()
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph):
+            for _ in range(steps):
+                self.step()
+        self.t, self.prev, self.cur = state
+        graph.replay()                               # untimed: first replay
+        torch.cuda.synchronize()
+        prepare()
+        t0 = time.perf_counter()
+        graph.replay()
+        torch.cuda.synchronize()
+        sec = (time.perf_counter() - t0) / steps
+        # the replay wrote into the same ping-pong buffers the eager run used
+        final = self.buf[(state[2] + steps - 1) % 2] if steps else self.prev
+        same = bool(torch.equal(final, ref_idx)) and bool(torch.equal(self.out, ref_out))
+        return sec, same
+
     def run_kernel_timing(self, steps, warmup):
         """Second pass over the same steps (same lfps_step calls) with HIP events around every kernel
         launch; the candidate counts of each step are copied out after the step."""
@@ -182,13 +218,14 @@ def algorithmic_bytes_score(spec, case, cnts, filtered):
     return rows * (spec.D * e + 4 + 4 * spec.G) + cnts.shape[1] * cnts.shape[2] * per_group
 
 
-def measure(name, steps, warmup, with_baselines=True):
+def measure(name, steps, warmup, with_baselines=True, use_graph=True):
     r = Runner(name)
     spec = r.spec
     if steps <= 0:
         steps = max(1, spec.T - warmup)
     sec = r.run_timed(steps, warmup)
     recall = r.recall_vs_exact()
+    sec_graph, graph_ok = r.run_timed_graph(steps, warmup) if use_graph else (None, None)
     tm, cnts = r.run_kernel_timing(steps, warmup)
     filtered = tm["filter_score"][1] > 0
     kname = "filter_score" if filtered else "gather_score"
@@ -198,6 +235,7 @@ def measure(name, steps, warmup, with_baselines=True):
     achieved = bytes_per_launch / gs_avg_s / 1e9
     res = {
         "steps_per_s": 1.0 / sec, "ms_per_step": sec * 1e3, "steps": steps,
+        "ms_per_step_hip_graph": round(sec_graph * 1e3, 4) if sec_graph else None, "hip_graph_matches_eager": graph_ok,
         "roofline": {"bound": "hbm", "kernel": kname, "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS,
                      "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4),
                      "traffic": MEASURED_TRAFFIC_BYTES.get(name),
@@ -292,6 +330,8 @@ def main():
                    "B": spec.B, "L": spec.L or list(spec.L_range), "k": spec.k or spec.k_frac, "r": spec.r},
         "roofline": main_res["roofline"],
         "kernel_us": main_res["kernel_us"],
+        "ms_per_step_hip_graph": main_res["ms_per_step_hip_graph"],
+        "hip_graph_matches_eager": main_res["hip_graph_matches_eager"],
         "cand_frac": main_res["cand_frac"], "recall_vs_exact_topk": main_res["recall_vs_exact_topk"],
         "exact_topk_ms": main_res.get("exact_topk_ms"), "full_attn_ms": main_res.get("full_attn_ms"),
         "speedup_vs_exact_topk": main_res.get("speedup_vs_exact_topk"),
@@ -303,7 +343,7 @@ def main():
             if name == args.workload:
                 continue
             res, _ = measure(name, 0, args.warmup)
-            others[name] = {k: res[k] for k in ("steps_per_s", "ms_per_step", "cand_frac", "recall_vs_exact_topk",
+            others[name] = {k: res[k] for k in ("steps_per_s", "ms_per_step", "ms_per_step_hip_graph", "cand_frac", "recall_vs_exact_topk",
                                                 "speedup_vs_exact_topk", "speedup_vs_full_attn", "kernel_us")}
             others[name]["roofline_frac"] = res["roofline"]["frac"]
             others[name]["steps_per_s"] = round(others[name]["steps_per_s"], 2)
