@@ -74,9 +74,8 @@ __device__ __forceinline__ void load_query_operand(bf16x8 (&A)[4], const float* 
 // the row over the four steps (measured faster than splitting a row into four 64-byte quarters
 // per step: all four loads of a tile touch both cache lines of every row).  Any assignment of
 // channels to (kk, kb) is valid as long as the A operand uses the same one.
-// The loop is software-pipelined around the stores: the row ids of the next iteration are fetched
-// and the scores of the previous iteration are stored right after this iteration's loads are
-// issued, so no wait for a load ever has only a store in front of it.
+// The row ids of the next iteration are fetched, and the scores of the previous iteration stored,
+// right after this iteration's loads are issued.
 template <int G, bool GATHER>
 __global__ __launch_bounds__(kScoreThreads) void k_group_score_bf16(Shape s, const float* __restrict__ q,
                                                                     const __bf16* __restrict__ K, int64_t stride_b,

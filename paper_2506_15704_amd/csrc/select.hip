@@ -14,9 +14,12 @@
 //     ranked against the others; if the bin is too full for the list (degenerate inputs: all
 //     scores equal, one huge outlier) an exact most-significant-digit radix descent over the
 //     order-preserving 32-bit keys of the bin's members finds it instead;
-//  5. ordered compaction (ballot + prefix counts, no atomics): every row above the k-th key plus
-//     as many rows equal to it as still needed, lowest position first.  The output is ascending
-//     in position and identical from run to run.
+//  5. ordered compaction (per-thread contiguous runs of the LDS copy + one block scan; ballots and
+//     prefix counts when streaming; no atomics): every row above the k-th value plus as many rows
+//     equal to it as still needed, lowest position first.  The output is ascending in position
+//     and identical from run to run.
+// The second kernel applies the same steps to the short (score, position) lists that the filtered
+// scoring pass leaves per head.
 #include <float.h>
 
 #include "lfps_internal.h"
