@@ -472,3 +472,44 @@ def test_filtered_step_equals_unfiltered_step_whatever_the_history(small_bf16):
     ref.lfps_step(dc.q(4), kv, prev, dc.k, a, out)
     flt.lfps_step(dc.q(4), kv, prev, dc.k, b_, out)
     np.testing.assert_array_equal(a.cpu().numpy(), b_.cpu().numpy())
+
+
+# ------------------------------------------------------------------------ other GQA group sizes
+@pytest.mark.parametrize("Hq,Hkv", [(8, 8), (16, 8), (4, 1)])
+def test_lfps_step_other_group_sizes(Hq, Hkv):
+    """G = 1, 2 and a single KV head: two chained steps (the second one through the score filter)."""
+    dc = DeviceCase(gen.tiny_spec(f"g{Hq}_{Hkv}", B=2, L=1500, k=64, r=2, T=3, Hq=Hq, Hkv=Hkv))
+    case, spec = dc.case, dc.spec
+    G = spec.G
+    ctx = dc.make_ctx()
+    prev = np.full((spec.B, spec.Hq, case.kmax), -1, dtype=np.int32)
+    for b in range(spec.B):
+        for h in range(spec.Hq):
+            K, _ = dc.group(b, h // G)
+            prev[b, h] = orc.exact_topk(case.q[0, b, h], K, int(case.seq_lens0[b]), int(case.k[b]))[0]
+    for t in (1, 2, 3):
+        kv = ctx.kv_view(dc.K, dc.V, dc.seq_lens(t))
+        idx = torch.zeros((spec.B, spec.Hq, case.kmax), dtype=torch.int32, device=DEV)
+        out = torch.zeros((spec.B, spec.Hq, spec.D), dtype=torch.float32, device=DEV)
+        ctx.lfps_step(dc.q(t), kv, dev(prev), dc.k, idx, out)
+        idx_h, out_h = idx.cpu().numpy(), out.cpu().numpy()
+        nxt = np.full_like(prev, -1)
+        for b in range(spec.B):
+            kb, n = int(case.k[b]), int(case.seq_lens(t)[b])
+            for g in range(spec.Hkv):
+                K, V = dc.group(b, g)
+                res = orc.lfps_step(case.q[t, b, G * g: G * g + G], K, V, [prev[b, G * g + i, :kb] for i in range(G)],
+                                    n, kb, spec.r, 1, 0)
+                for hh in range(G):
+                    h = G * g + hh
+                    assert_topk_equal_mod_ties(idx_h[b, h, :kb], res["topk_idx"][hh],
+                                               lambda p: orc.scores(case.q[t, b, h], K, p), kb, f"G{G} t{t} b{b} h{h}")
+                    assert_out_close(out_h[b, h], orc.sparse_attn(case.q[t, b, h], K, V, idx_h[b, h, :kb]), f"G{G} out")
+                    nxt[b, h, :kb] = res["topk_idx"][hh]
+        prev = nxt
+    full = torch.zeros((spec.B, spec.Hq, spec.D), dtype=torch.float32, device=DEV)
+    ctx.lfps_full_attn_decode(dc.q(3), ctx.kv_view(dc.K, dc.V, dc.seq_lens(3)), full)
+    K, V = dc.group(1, spec.Hkv - 1)
+    assert_out_close(full[1, spec.Hq - 1].cpu().numpy(), orc.full_attn(case.q[3, 1, spec.Hq - 1], K, V, int(case.seq_lens(3)[1])), "full")
+    tm_ctx = dc.make_ctx()
+    del tm_ctx
