@@ -285,11 +285,28 @@ def cpu_baseline(case, budget_s):
                     break
             if spent > budget_s or time.perf_counter() - t_start > 4 * budget_s + 60:
                 break
+        # the oracle's exact Top-k (+ sparse attention) and full attention on the last sampled group, for context
+        t_ref = min(spec.T, 2)
+        n_ref = int(case.seq_lens(t_ref)[b])
+        t0 = time.perf_counter()
+        for h in range(spec.G):
+            I, _ = orc.exact_topk(case.q[t_ref, b, spec.G * g + h], K, n_ref, kb)
+            orc.sparse_attn(case.q[t_ref, b, spec.G * g + h], K, V, I)
+        exact_group = time.perf_counter() - t0
+        t0 = time.perf_counter()
+        for h in range(spec.G):
+            orc.full_attn(case.q[t_ref, b, spec.G * g + h], K, V, n_ref)
+        full_group = time.perf_counter() - t0
     per_group_step = spent / max(done, 1)
-    step_s = per_group_step * spec.B * spec.Hkv
+    groups_n = spec.B * spec.Hkv
+    step_s = per_group_step * groups_n
     return {"value": 1.0 / step_s, "unit": "steps/s", "cores": 1, "kind": "oracle",
             "sample": f"{done} oracle lfps_step calls (fp64 numpy, 1 thread) on (request, KV group) samples of {spec.name}, "
-                      f"{per_group_step * 1e3:.1f} ms each, scaled by B*Hkv = {spec.B * spec.Hkv} groups per step"}
+                      f"{per_group_step * 1e3:.1f} ms each, scaled by B*Hkv = {groups_n} groups per step",
+            "oracle_exact_topk_steps_per_s": 1.0 / (exact_group * groups_n),
+            "oracle_full_attn_steps_per_s": 1.0 / (full_group * groups_n),
+            "oracle_speedup_vs_exact_topk": exact_group / per_group_step,
+            "host_cores_available": os.cpu_count()}
 
 
 def main():

@@ -188,8 +188,7 @@ __global__ __launch_bounds__(kScoreThreads) void k_filter_score_bf16(
   }
   const float tau = kb < G ? thr_state[head] - margin : INFINITY;
 
-  bf16x8 A[4];
-  load_query_operand<G>(A, q, (int64_t)b * s.Hq + (int64_t)g * G, j, kb);
+  bf16x8 A[4];                                        // filled after the first tile's loads are on their way
   const __bf16* Kbg = K + (int64_t)b * stride_b + (int64_t)g * stride_h;
   const int32_t* cbg = cand + (int64_t)bg * s.cand_cap;
   float* sc = score + head * score_stride + seg_lo;
@@ -259,6 +258,7 @@ __global__ __launch_bounds__(kScoreThreads) void k_filter_score_bf16(
   constexpr int T = kRowsPerWaveIter;
   issue(Bt0, rows0, fetch_ids(seg_lo));
   int ids_b = fetch_ids(seg_lo + T);                  // ids of the tile whose loads are issued next
+  load_query_operand<G>(A, q, (int64_t)b * s.Hq + (int64_t)g * G, j, kb);   // overlaps the first tile's latency
   for (int base = seg_lo; base < seg_hi; base += 2 * T) {
     const bool has_b = base + T < seg_hi;             // wave-uniform
     int ids_a2 = -1;

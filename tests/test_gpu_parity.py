@@ -513,3 +513,39 @@ def test_lfps_step_other_group_sizes(Hq, Hkv):
     assert_out_close(full[1, spec.Hq - 1].cpu().numpy(), orc.full_attn(case.q[3, 1, spec.Hq - 1], K, V, int(case.seq_lens(3)[1])), "full")
     tm_ctx = dc.make_ctx()
     del tm_ctx
+
+
+@pytest.mark.parametrize("seed", [1, 20250616, 987654321])
+def test_small_workload_other_seeds(seed):
+    """The 4K fp32 workload under three more seeds: teacher-forced steps on two sampled groups."""
+    import dataclasses
+    dc = DeviceCase(dataclasses.replace(gen.C1, name=f"C1s{seed}", seed=seed, T=4))
+    case, spec = dc.case, dc.spec
+    ctx = dc.make_ctx()
+    samples = [(0, seed % 8), (0, (seed + 3) % 8)]
+    seedk = torch.zeros((spec.B, spec.Hq, case.kmax), dtype=torch.int32, device=DEV)
+    ctx.lfps_exact_topk(dc.q(0), ctx.kv_view(dc.K, dc.V, dc.seq_lens(0)), dc.k, seedk)
+    prev_dev = seedk.clone()
+    prev_orc = {}
+    for (b, g) in samples:
+        K, _ = dc.group(b, g)
+        prev_orc[(b, g)] = [orc.exact_topk(case.q[0, b, 4 * g + hh], K, int(case.seq_lens0[b]), int(case.k[b]))[0] for hh in range(4)]
+    for t in range(1, spec.T + 1):
+        for (b, g) in samples:
+            for hh in range(4):
+                prev_dev[b, 4 * g + hh] = torch.from_numpy(prev_orc[(b, g)][hh].astype(np.int32)).to(DEV)
+        nxt = torch.zeros_like(prev_dev)
+        out = torch.zeros((spec.B, spec.Hq, spec.D), dtype=torch.float32, device=DEV)
+        ctx.lfps_step(dc.q(t), ctx.kv_view(dc.K, dc.V, dc.seq_lens(t)), prev_dev, dc.k, nxt, out)
+        idx_h, out_h = nxt.cpu().numpy(), out.cpu().numpy()
+        for (b, g) in samples:
+            K, V = dc.group(b, g)
+            kb, n = int(case.k[b]), int(case.seq_lens(t)[b])
+            res = orc.lfps_step(case.q[t, b, 4 * g: 4 * g + 4], K, V, prev_orc[(b, g)], n, kb, spec.r, 1, 0)
+            for hh in range(4):
+                h = 4 * g + hh
+                assert_topk_equal_mod_ties(idx_h[b, h, :kb], res["topk_idx"][hh], lambda p: orc.scores(case.q[t, b, h], K, p), kb,
+                                           f"seed {seed} t{t} h{h}")
+                assert_out_close(out_h[b, h], orc.sparse_attn(case.q[t, b, h], K, V, idx_h[b, h, :kb]), f"seed {seed} out")
+            prev_orc[(b, g)] = res["topk_idx"]
+        prev_dev = nxt
