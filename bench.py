@@ -37,7 +37,9 @@ def parse_args():
     ap.add_argument("--steps", type=int, default=0, help="timed steps (default: the workload's decode steps minus warmup)")
     ap.add_argument("--warmup", type=int, default=2)
     ap.add_argument("--workload", default="C4", choices=["C1", "C2", "C3", "C4", "C5"])
-    ap.add_argument("--all-workloads", action="store_true", help="also report the other four workloads")
+    ap.add_argument("--all-workloads", action="store_true", default=True,
+                    help="also report the other four workloads in the same line (default)")
+    ap.add_argument("--main-only", dest="all_workloads", action="store_false", help="only the main workload")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--calib-copy", action="store_true",
                     help="run only the plain copy kernel (1 GiB, 10 launches): the known-traffic reference for rocprofv3 --pmc")

@@ -109,3 +109,40 @@ def test_candidate_counts_and_capacity_at_full_size():
                     assert np.isin(seed[b, spec.G * g + hh, :kb], C).all()
     finally:
         r.close()
+
+
+def test_worst_case_candidate_count_at_full_size():
+    """Maximum sizes: the four heads of every group disagree completely (random previous Top-k), so the
+    candidate set approaches its capacity G*k*(2r+2)+1 = 81921 at the 128K workload; the score filter has
+    no usable history, and the select streams more scores than its LDS cache holds."""
+    r = bench.Runner("C4")
+    try:
+        spec, case = r.spec, r.case
+        G = spec.G
+        rng = np.random.default_rng(7)
+        n = int(case.seq_lens(1)[0])
+        prev = np.stack([np.stack([np.sort(rng.choice(n - 1, size=case.kmax, replace=False)).astype(np.int32)
+                                   for _ in range(spec.Hq)]) for _ in range(spec.B)])
+        samples = [(3, 5), (12, 0)]
+        nxt = torch.zeros_like(r.seed)
+        sc = torch.zeros_like(r.sel_score)
+        out = torch.zeros_like(r.out)
+        cnt = torch.zeros((spec.B, spec.Hkv), dtype=torch.int32, device=r.dev)
+        for attempt in range(2):                     # second call: a history exists but is useless for these inputs
+            r.ctx.lfps_step(r.q[1], r.views[1], torch.from_numpy(prev).to(r.dev), r.k, nxt, out, sc)
+        r.ctx.lfps_copy_cand_count(cnt)
+        assert r.ctx.lfps_poll_status() == 0
+        cnt_h, idx_h, out_h = cnt.cpu().numpy(), nxt.cpu().numpy(), out.cpu().numpy()
+        assert cnt_h.min() > 60000 and cnt_h.max() <= r.ctx.cand_cap
+        for (b, g) in samples:
+            K, V = case.kv_group(b, g)
+            kb = int(case.k[b])
+            res = orc.lfps_step(case.q[1, b, G * g: G * g + G], K, V, [prev[b, G * g + i] for i in range(G)], n, kb, spec.r, 1, 0)
+            assert len(res["cand"]) == cnt_h[b, g]
+            for hh in range(G):
+                h = G * g + hh
+                assert_topk_equal_mod_ties(idx_h[b, h, :kb], res["topk_idx"][hh], lambda p: orc.scores(case.q[1, b, h], K, p),
+                                           kb, f"worst case b{b} h{h}")
+                assert_out_close(out_h[b, h], orc.sparse_attn(case.q[1, b, h], K, V, idx_h[b, h, :kb]), f"worst case out b{b} h{h}")
+    finally:
+        r.close()
