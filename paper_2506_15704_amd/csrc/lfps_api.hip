@@ -26,7 +26,7 @@ struct lfps_ctx {
   int32_t* cand_count; // [B, Hkv]
   float* sel_score;    // [B, Hq, kmax]
   float* part;         // split partials (max of the two layouts)
-  int32_t* flags;      // [1]
+  int32_t* flags;      // [0] status flags, [1] segment size chosen by the last filtered scoring pass
   int64_t ws_bytes;
   // timing
   int timing_on;
@@ -100,7 +100,7 @@ int check_config(const lfps_config* c, Sizes* z, char* err, size_t errn) {
   int64_t p_full = (int64_t)c->batch * c->n_kv_heads * z->n_split_full * G * (kD + 2) * 4;
   z->part_b = align256(p_sparse > p_full ? p_sparse : p_full);
   const bool filt = c->kv_dtype == LFPS_BF16;
-  z->nseg = 4 * filter_blocks_x(s);
+  z->nseg = filter_nseg(s);
   z->slot_b = filt ? z->score_b : 0;
   z->seg_b = align256((int64_t)c->batch * c->n_q_heads * z->nseg * 4);
   z->thr_b = align256((int64_t)c->batch * c->n_q_heads * 4);
@@ -353,9 +353,10 @@ int lfps_step(lfps_ctx* ctx, const float* q, const lfps_kv* kv, const int32_t* p
     // survivors of the per-head threshold first; heads left short are rescored below
     LAUNCH(ctx, LFPS_KERNEL_FILTER_SCORE, st,
            launch_filter_score(s, q, v, ctx->cand, ctx->cand_count, ctx->thr_state, kFilterMargin, ctx->score,
-                               ctx->slot, s.score_stride, ctx->seg_count, st));
+                               ctx->slot, s.score_stride, ctx->seg_count, ctx->flags + 1, st));
     LAUNCH(ctx, LFPS_KERNEL_FILTER_SELECT, st,
-           launch_filter_select(s, ctx->score, ctx->slot, s.score_stride, ctx->seg_count, ctx->nseg, ctx->cand,
+           launch_filter_select(s, ctx->score, ctx->slot, s.score_stride, ctx->seg_count, ctx->flags + 1, ctx->nseg,
+                                ctx->cand,
                                 ctx->cand_count, k, topk_idx, sel, ctx->thr_state, ctx->redo_g, ctx->redo_h, st));
     only_g = ctx->redo_g;
     only_h = ctx->redo_h;

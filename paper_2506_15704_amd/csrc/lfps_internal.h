@@ -46,15 +46,17 @@ hipError_t launch_group_score(const Shape& s, int dtype, const float* q, const K
                               hipStream_t st);
 
 // Filtered scoring (bf16 cache): per head only rows with score >= thr_state[b,h] - margin are kept, as
-// (score, slot) lists in 4*filter_blocks_x(s) segments per head; see score.hip.
-int filter_blocks_x(const Shape& s);
+// (score, position) lists in at most filter_nseg(s) segments per head; the segment size of a step is
+// written to *seg_rows_out by the scoring pass and read by the select; see score.hip.
+int filter_nseg(const Shape& s);
 hipError_t launch_filter_score(const Shape& s, const float* q, const KvView& kv, const int32_t* cand,
                                const int32_t* cand_count, const float* thr_state, float margin, float* score,
-                               int32_t* slot_out, int64_t score_stride, int32_t* seg_count, hipStream_t st);
+                               int32_t* slot_out, int64_t score_stride, int32_t* seg_count, int32_t* seg_rows_out,
+                               hipStream_t st);
 hipError_t launch_filter_select(const Shape& s, const float* score, const int32_t* slot_in, int64_t score_stride,
-                                const int32_t* seg_count, int nseg, const int32_t* cand, const int32_t* cand_count,
-                                const int32_t* k, int32_t* topk_idx, float* topk_score, float* thr_state,
-                                int32_t* redo_g, int32_t* redo_h, hipStream_t st);
+                                const int32_t* seg_count, const int32_t* seg_rows, int nseg, const int32_t* cand,
+                                const int32_t* cand_count, const int32_t* k, int32_t* topk_idx, float* topk_score,
+                                float* thr_state, int32_t* redo_g, int32_t* redo_h, hipStream_t st);
 
 // Per (b, h): the k_b best of score[b,h,0:count]; count = cand_count[b, g(h)] when cand != NULL,
 // else seq_lens[b].  Writes positions (ascending) and their scores.

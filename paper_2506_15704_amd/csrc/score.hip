@@ -151,11 +151,12 @@ __global__ __launch_bounds__(kScoreThreads) void k_group_score_bf16(Shape s, con
 // (the threshold is the previous step's k-th best score minus a margin: consecutive decode steps
 // select almost the same rows, the premise of the method).  Writing every score costs far more
 // than its share of bytes because the small writes interleave with the row gather; survivors are
-// a few per cent of the rows.  Wave `wg` of a group owns the contiguous candidate slots
-// [wg*R, (wg+1)*R) and appends its survivors (score, row position), in slot order, at offset wg*R
+// a few per cent of the rows.  Wave-item `wg` of a group owns the contiguous candidate slots
+// [wg*R, (wg+1)*R), R = seg_rows, and appends its survivors (score, row position), in slot order, at offset wg*R
 // of each head's score / position rows (staged in LDS, written when the wave is done); the count goes to seg_count[head, wg].
 // No atomics: the lists are reproducible and ascending in slot.  A threshold of -inf keeps every row; NaN means there is no previous step.
 constexpr int kFilterStage = 256;   // survivors one wave can hold per head before it must write them out
+constexpr int kFilterWaves = 2048;  // wave-items aimed at per launch: 256 CUs x 2 workgroups x 4 waves
 
 template <int G>
 __global__ __launch_bounds__(kScoreThreads) void k_filter_score_bf16(
@@ -163,20 +164,78 @@ __global__ __launch_bounds__(kScoreThreads) void k_filter_score_bf16(
     int64_t stride_n, const int32_t* __restrict__ seq_lens, const int32_t* __restrict__ cand,
     const int32_t* __restrict__ cand_count, const float* __restrict__ thr_state, float margin,
     float* __restrict__ score, int32_t* __restrict__ slot_out, int64_t score_stride,
-    int32_t* __restrict__ seg_count, int nseg, float scale) {
+    int32_t* __restrict__ seg_count, int32_t* __restrict__ seg_rows_out, int min_seg_rows, int nseg, float scale) {
   __shared__ float stage_score[4][G][kFilterStage];
   __shared__ int32_t stage_slot[4][G][kFilterStage];
-  const int bg = blockIdx.y, b = bg / s.Hkv, g = bg % s.Hkv;
-  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  __shared__ int pre[kScoreThreads];
+  __shared__ int wtot[4];
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int j = lane & 15, kb = lane >> 4;
+
+  // Work items = (group, segment of seg_rows candidate slots), flattened over the groups in order, one
+  // item per wave: a group gets as many waves as it has candidates, so ragged batches stay balanced.
+  // seg_rows is chosen from this step's total candidate count so that there are about kFilterWaves
+  // items (one per resident wave).  Every workgroup derives the same numbers from cand_count.
+  const int n_groups = s.B * s.Hkv;
+  const int item = blockIdx.x * 4 + wave;
+  int64_t total = 0;
+  for (int c0 = tid; c0 < n_groups; c0 += kScoreThreads) {
+    const int c = cand_count[c0];
+    total += c < 0 ? 0 : (c > s.cand_cap ? s.cand_cap : c);
+  }
+#pragma unroll
+  for (int d = 1; d < 64; d <<= 1) total += __shfl_xor(total, d);
+  if (lane == 0) pre[wave] = (int)total;
+  __syncthreads();
+  total = (int64_t)pre[0] + pre[1] + pre[2] + pre[3];
+  __syncthreads();
+  int seg_rows = (int)(((total + kFilterWaves - 1) / kFilterWaves + 63) & ~(int64_t)63);
+  seg_rows = seg_rows < min_seg_rows ? min_seg_rows : seg_rows;
+  if (blockIdx.x == 0 && tid == 0) *seg_rows_out = seg_rows;      // the select reads it
+  int bg = -1, wg = 0, base = 0;
+  for (int c0 = 0; c0 < n_groups && base <= blockIdx.x * 4 + 3; c0 += kScoreThreads) {
+    int v = 0;
+    if (c0 + tid < n_groups) {
+      int c = cand_count[c0 + tid];
+      c = c < 0 ? 0 : (c > s.cand_cap ? s.cand_cap : c);
+      v = (c + seg_rows - 1) / seg_rows;
+    }
+    int inc = v;
+#pragma unroll
+    for (int d = 1; d < 64; d <<= 1) {
+      const int o = __shfl_up(inc, d);
+      if (lane >= d) inc += o;
+    }
+    if (lane == 63) wtot[wave] = inc;
+    __syncthreads();
+    int before = 0, chunk_total = 0;
+#pragma unroll
+    for (int w = 0; w < 4; ++w) {
+      before += w < wave ? wtot[w] : 0;
+      chunk_total += wtot[w];
+    }
+    pre[tid] = base + before + inc - v;                // first item of group c0 + tid
+    __syncthreads();
+    if (bg < 0 && item < base + chunk_total) {         // wave-uniform: my item belongs to this chunk
+      int lo_t = 0, hi_t = kScoreThreads - 1;          // last group whose first item is <= mine
+      while (lo_t < hi_t) {
+        const int mid = (lo_t + hi_t + 1) >> 1;
+        if (pre[mid] <= item) lo_t = mid; else hi_t = mid - 1;
+      }
+      bg = c0 + lo_t;
+      wg = item - pre[lo_t];
+    }
+    base += chunk_total;
+    __syncthreads();
+  }
+  if (bg < 0) return;                                   // more waves than items
+  const int b = bg / s.Hkv, g = bg % s.Hkv;
   int n = seq_lens[b];
   n = n < 0 ? 0 : (n > s.Lcap ? s.Lcap : n);
   int count = cand_count[bg];
   count = count < 0 ? 0 : (count > s.cand_cap ? s.cand_cap : count);
-  const int wg = blockIdx.x * 4 + wave;
-  const int R = (((count + nseg - 1) / nseg) + 63) & ~63;
-  const int seg_lo = wg * R;
-  const int seg_hi = seg_lo + R < count ? seg_lo + R : count;
+  const int seg_lo = wg * seg_rows;
+  const int seg_hi = seg_lo + seg_rows < count ? seg_lo + seg_rows : count;
   const int64_t head = (int64_t)b * s.Hq + (int64_t)g * G + (kb < G ? kb : 0);
   // NaN in thr_state = "no previous step": skip the group here, the unfiltered pass will take it
   bool no_history = false;
@@ -439,24 +498,23 @@ hipError_t launch_group_score(const Shape& s, int dtype, const float* q, const K
   }
 }
 
-int filter_blocks_x(const Shape& s) {
-  int gx = (256 * 2 + s.B * s.Hkv - 1) / (s.B * s.Hkv);   // about two workgroups (8 waves) per CU in total
-  const int tiles = (s.cand_cap + 4 * kRowsPerWaveIter - 1) / (4 * kRowsPerWaveIter);
-  if (gx > tiles) gx = tiles;
-  if (gx > 128) gx = 128;                                  // 4*gx segments per group, <= 1024 / 2
-  return gx < 1 ? 1 : gx;
-}
+// Smallest segment (= wave-item) size in candidate slots, and the segments a head can then have (<= 512).
+int filter_min_seg_rows(const Shape& s) { return (((s.cand_cap + 511) / 512) + 63) & ~63; }
+int filter_nseg(const Shape& s) { return (s.cand_cap + filter_min_seg_rows(s) - 1) / filter_min_seg_rows(s); }
 
 hipError_t launch_filter_score(const Shape& s, const float* q, const KvView& kv, const int32_t* cand,
                                const int32_t* cand_count, const float* thr_state, float margin, float* score,
-                               int32_t* slot_out, int64_t score_stride, int32_t* seg_count, hipStream_t st) {
-  const int gx = filter_blocks_x(s);
-  dim3 grid(gx, s.B * s.Hkv), block(kScoreThreads);
+                               int32_t* slot_out, int64_t score_stride, int32_t* seg_count, int32_t* seg_rows_out,
+                               hipStream_t st) {
+  const int nseg = filter_nseg(s);
+  // items <= total/seg_rows + groups <= kFilterWaves + groups
+  const int64_t max_items = (int64_t)kFilterWaves + (int64_t)s.B * s.Hkv;
+  dim3 grid((unsigned)((max_items + 3) / 4)), block(kScoreThreads);
   const float scale = 0.08838834764831845f;
 #define LFPS_LAUNCH_FILTER(GG)                                                                                     \
   hipLaunchKernelGGL((k_filter_score_bf16<GG>), grid, block, 0, st, s, q, (const __bf16*)kv.k, kv.stride_b,       \
                      kv.stride_h, kv.stride_n, kv.seq_lens, cand, cand_count, thr_state, margin, score, slot_out, \
-                     score_stride, seg_count, 4 * gx, scale)
+                     score_stride, seg_count, seg_rows_out, filter_min_seg_rows(s), nseg, scale)
   switch (s.G) {
     case 1: LFPS_LAUNCH_FILTER(1); break;
     case 2: LFPS_LAUNCH_FILTER(2); break;

@@ -348,12 +348,11 @@ __global__ __launch_bounds__(kSelThreads) void k_select(Shape s, const float* __
 // position rows, ascending in position within and across segments.  If the survivors are fewer than k (the filter
 // threshold was too high) or more than the LDS list holds, the head is flagged for the unfiltered
 // pass instead and nothing is written.
-__device__ __forceinline__ int filter_segment_rows(int count, int nseg) { return (((count + nseg - 1) / nseg) + 63) & ~63; }
-
 __global__ __launch_bounds__(kFilterSelThreads) void k_filter_select(Shape s, const float* __restrict__ score,
                                                                const int32_t* __restrict__ slot_in,
                                                                int64_t score_stride,
-                                                               const int32_t* __restrict__ seg_count, int nseg,
+                                                               const int32_t* __restrict__ seg_count,
+                                                               const int32_t* __restrict__ seg_rows_in, int nseg,
                                                                const int32_t* __restrict__ cand,
                                                                const int32_t* __restrict__ cand_count,
                                                                const int32_t* __restrict__ kk,
@@ -375,7 +374,8 @@ __global__ __launch_bounds__(kFilterSelThreads) void k_filter_select(Shape s, co
   int kb = kk[b];
   kb = kb < 0 ? 0 : (kb > s.kmax ? s.kmax : kb);
   const int ksel = kb < c ? kb : c;
-  const int R = filter_segment_rows(c, nseg);
+  int R = *seg_rows_in;                              // chosen by the scoring pass of this step
+  R = R < 64 ? 64 : R;
 
   // exclusive prefix of the segment counts (nseg <= 512: two consecutive segments per thread)
   int cnt2[2] = {0, 0};
@@ -477,12 +477,12 @@ hipError_t launch_select(const Shape& s, const float* score, int64_t score_strid
 }
 
 hipError_t launch_filter_select(const Shape& s, const float* score, const int32_t* slot_in, int64_t score_stride,
-                                const int32_t* seg_count, int nseg, const int32_t* cand, const int32_t* cand_count,
-                                const int32_t* k, int32_t* topk_idx, float* topk_score, float* thr_state,
-                                int32_t* redo_g, int32_t* redo_h, hipStream_t st) {
+                                const int32_t* seg_count, const int32_t* seg_rows, int nseg, const int32_t* cand,
+                                const int32_t* cand_count, const int32_t* k, int32_t* topk_idx, float* topk_score,
+                                float* thr_state, int32_t* redo_g, int32_t* redo_h, hipStream_t st) {
   const int cap = filter_list_cap(s);
   hipLaunchKernelGGL(k_filter_select, dim3(s.B * s.Hq), dim3(kFilterSelThreads), (size_t)cap * 8, st, s, score, slot_in,
-                     score_stride, seg_count, nseg, cand, cand_count, k, topk_idx, topk_score, thr_state, redo_g,
+                     score_stride, seg_count, seg_rows, nseg, cand, cand_count, k, topk_idx, topk_score, thr_state, redo_g,
                      redo_h, cap);
   return hipGetLastError();
 }
