@@ -168,14 +168,13 @@ enum {
   LFPS_KERNEL_GATHER_SCORE = 1,
   LFPS_KERNEL_SELECT = 2,
   LFPS_KERNEL_SPARSE_ATTN = 3,
-  LFPS_KERNEL_ATTN_MERGE = 4,
-  LFPS_KERNEL_DENSE_SCORE = 5,
-  LFPS_KERNEL_FULL_ATTN = 6,
-  LFPS_KERNEL_FULL_MERGE = 7,
-  LFPS_KERNEL_HEAD_SCORE = 8,
-  LFPS_KERNEL_FILTER_SCORE = 9,
-  LFPS_KERNEL_FILTER_SELECT = 10,
-  LFPS_N_KERNELS = 11
+  LFPS_KERNEL_DENSE_SCORE = 4,
+  LFPS_KERNEL_FULL_ATTN = 5,
+  LFPS_KERNEL_FULL_MERGE = 6,
+  LFPS_KERNEL_HEAD_SCORE = 7,
+  LFPS_KERNEL_FILTER_SCORE = 8,
+  LFPS_KERNEL_FILTER_SELECT = 9,
+  LFPS_N_KERNELS = 10
 };
 #define LFPS_TIMING_MAX_LAUNCHES 4096
 int lfps_timing_enable(lfps_ctx* ctx, int32_t on);

@@ -2,10 +2,11 @@
 // (Sec. 1 with idx = every row; the "full attention" upper bound of Sec. 5).
 //
 // Sparse: the scores of the selected rows are already known (from S3, or recomputed by the
-// per-head score kernel), so the softmax maximum is known before any V row is read and every
-// split of a head uses the same reference; partial sums then merge by plain addition.
-// Split s of head (b, h) gathers rows idx[256 s, 256 s + 256): 16 lanes per V row, 16-byte loads,
-// sixteen independent row loads in flight per wave.
+// per-head score kernel), so the softmax maximum is known before any V row is read and the
+// partial sums of the waves merge by plain addition.  One workgroup of 4, 8 or 16 waves per
+// (b, h): wave w gathers its share of the head's rows, 16 lanes per V row, 16-byte loads, sixteen
+// independent row loads in flight per wave; the partial sums meet in LDS and the output row is
+// written once (no partials in global memory, no second kernel).
 //
 // Full: split-K over contiguous row ranges with the G heads of a group sharing every K and V
 // row; running (max, sum, acc) per lane group, merged with the online-softmax rule.
@@ -13,8 +14,7 @@
 
 namespace lfps {
 
-constexpr int kAttnThreads = 256;
-constexpr int kRowsPerSplit = 256;   // sparse attention: rows per workgroup
+constexpr int kAttnThreads = 256;       // full attention
 
 template <typename T>
 __device__ __forceinline__ void load8(const T* p, float x[8]) {
@@ -32,66 +32,82 @@ __device__ __forceinline__ void load8(const T* p, float x[8]) {
   }
 }
 
-int sparse_attn_splits(const Shape& s) { return (s.kmax + kRowsPerSplit - 1) / kRowsPerSplit; }
-
-// grid (n_split, B*Hq); part [B*Hq, n_split, D+1]
-template <typename T>
-__global__ __launch_bounds__(kAttnThreads) void k_sparse_attn(Shape s, const T* __restrict__ V, int64_t stride_b,
-                                                              int64_t stride_h, int64_t stride_n,
-                                                              const int32_t* __restrict__ seq_lens,
-                                                              const int32_t* __restrict__ idx,
-                                                              const float* __restrict__ idx_score,
-                                                              const int32_t* __restrict__ kk, float* __restrict__ part,
-                                                              int n_split) {
-  __shared__ float red[4][kD];
-  __shared__ float redm[4], redl[4];
-  const int bh = blockIdx.y, b = bh / s.Hq, h = bh % s.Hq, g = h / s.G;
-  const int split = blockIdx.x;
+// grid B*Hq, kSparseWaves waves per workgroup
+template <typename T, int kSparseWaves>
+__global__ __launch_bounds__(kSparseWaves * 64) void k_sparse_attn(Shape s, const T* __restrict__ V, int64_t stride_b,
+                                                                int64_t stride_h, int64_t stride_n,
+                                                                const int32_t* __restrict__ seq_lens,
+                                                                const int32_t* __restrict__ idx,
+                                                                const float* __restrict__ idx_score,
+                                                                const int32_t* __restrict__ kk,
+                                                                float* __restrict__ out) {
+  __shared__ float red[kSparseWaves][kD];
+  __shared__ float redm[kSparseWaves], redl[kSparseWaves];
+  const int bh = blockIdx.x, b = bh / s.Hq, h = bh % s.Hq, g = h / s.G;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int j = lane & 15, rs = lane >> 4;
   int n = seq_lens[b];
   n = n < 0 ? 0 : (n > s.Lcap ? s.Lcap : n);
   int kb = kk[b];
   kb = kb < 0 ? 0 : (kb > s.kmax ? s.kmax : kb);
-  if (split * kRowsPerSplit >= kb) return;
   const int32_t* ih = idx + (int64_t)bh * s.kmax;
   const float* sh = idx_score + (int64_t)bh * s.kmax;
 
-  // softmax reference: the largest score among the head's valid rows
+  // wave w takes entries [r0, r1) of the head's index list
+  const int chunk = (((kb + kSparseWaves - 1) / kSparseWaves) + 63) & ~63;
+  const int r0 = wave * chunk, r1 = r0 + chunk < kb ? r0 + chunk : kb;
+
+  // softmax reference: the largest score among the head's valid rows.  Each lane looks at the
+  // entries it will own in the loop below (first 64-entry tile kept in registers).
+  int first_row = -1;
+  float first_s = -INFINITY;
   float m = -INFINITY;
-  for (int i = tid; i < kb; i += kAttnThreads) {
-    int r = ih[i];
-    if (r >= 0 && r < n) m = fmaxf(m, sh[i]);
+  for (int i = r0 + lane; i < r1; i += 64) {
+    const int r = ih[i];
+    const float sv = sh[i];
+    const bool ok = r >= 0 && r < n;
+    if (i < r0 + 64) {
+      first_row = ok ? r : -1;
+      first_s = sv;
+    }
+    if (ok) m = fmaxf(m, sv);
   }
 #pragma unroll
   for (int d = 1; d < 64; d <<= 1) m = fmaxf(m, __shfl_xor(m, d));
   if (lane == 0) redm[wave] = m;
   __syncthreads();
-  m = fmaxf(fmaxf(redm[0], redm[1]), fmaxf(redm[2], redm[3]));
+  m = redm[0];
+#pragma unroll
+  for (int w = 1; w < kSparseWaves; ++w) m = fmaxf(m, redm[w]);
 
-  const int my_i = split * kRowsPerSplit + wave * 64 + lane;
-  int my_row = -1;
-  float my_p = 0.f;
-  if (my_i < kb) {
-    int r = ih[my_i];
-    if (r >= 0 && r < n) {
-      my_row = r;
-      my_p = __expf(sh[my_i] - m);
-    }
-  }
   const T* Vbg = V + (int64_t)b * stride_b + (int64_t)g * stride_h + 8 * j;
   float acc[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+  float l = 0.f;
+  for (int base = r0; base < r1; base += 64) {
+    int my_row = -1;
+    float my_p = 0.f;
+    if (base == r0) {
+      my_row = first_row;
+      my_p = my_row >= 0 ? __expf(first_s - m) : 0.f;
+    } else if (base + lane < r1) {
+      const int r = ih[base + lane];
+      if (r >= 0 && r < n) {
+        my_row = r;
+        my_p = __expf(sh[base + lane] - m);
+      }
+    }
+    l += my_p;
 #pragma unroll
-  for (int t = 0; t < 16; ++t) {
-    int row = __shfl(my_row, 4 * t + rs);
-    float p = __shfl(my_p, 4 * t + rs);
-    float x[8];
-    load8(Vbg + (int64_t)(row < 0 ? 0 : row) * stride_n, x);
-    p = row < 0 ? 0.f : p;
+    for (int t = 0; t < 16; ++t) {
+      const int row = __shfl(my_row, 4 * t + rs);
+      float p = __shfl(my_p, 4 * t + rs);
+      float x[8];
+      load8(Vbg + (int64_t)(row < 0 ? 0 : row) * stride_n, x);
+      p = row < 0 ? 0.f : p;
 #pragma unroll
-    for (int c = 0; c < 8; ++c) acc[c] = fmaf(p, x[c], acc[c]);
+      for (int c = 0; c < 8; ++c) acc[c] = fmaf(p, x[c], acc[c]);
+    }
   }
-  float l = my_p;
 #pragma unroll
   for (int d = 1; d < 64; d <<= 1) l += __shfl_xor(l, d);
 #pragma unroll
@@ -105,44 +121,37 @@ __global__ __launch_bounds__(kAttnThreads) void k_sparse_attn(Shape s, const T* 
   }
   if (lane == 0) redl[wave] = l;
   __syncthreads();
-  float* po = part + ((int64_t)bh * n_split + split) * (kD + 1);
-  if (tid < kD) po[tid] = (red[0][tid] + red[1][tid]) + (red[2][tid] + red[3][tid]);
-  if (tid == kD) po[kD] = (redl[0] + redl[1]) + (redl[2] + redl[3]);
+  if (tid < kD) {
+    float a = 0.f, ls = 0.f;
+#pragma unroll
+    for (int w = 0; w < kSparseWaves; ++w) {
+      a += red[w][tid];
+      ls += redl[w];
+    }
+    out[(int64_t)bh * kD + tid] = ls > 0.f ? a / ls : 0.f;
+  }
 }
 
-// grid B*Hq, 128 threads
-__global__ __launch_bounds__(kD) void k_attn_merge(Shape s, const int32_t* __restrict__ kk,
-                                                   const float* __restrict__ part, int n_split,
-                                                   float* __restrict__ out) {
-  const int bh = blockIdx.x, b = bh / s.Hq, c = threadIdx.x;
-  int kb = kk[b];
-  kb = kb < 0 ? 0 : (kb > s.kmax ? s.kmax : kb);
-  const int nv = (kb + kRowsPerSplit - 1) / kRowsPerSplit;
-  float a = 0.f, l = 0.f;
-  for (int sp = 0; sp < nv; ++sp) {
-    const float* p = part + ((int64_t)bh * n_split + sp) * (kD + 1);
-    a += p[c];
-    l += p[kD];
-  }
-  out[(int64_t)bh * kD + c] = l > 0.f ? a / l : 0.f;
+template <typename T>
+static hipError_t launch_sparse_t(const Shape& s, const KvView& kv, const int32_t* idx, const float* idx_score,
+                                  const int32_t* k, float* out, hipStream_t st) {
+  // as many waves per head as keep every head's workgroup resident at once (256 CUs x 32 waves)
+  const int heads = s.B * s.Hq;
+  const T* V = (const T*)kv.v;
+#define LFPS_LAUNCH_SPARSE(NW)                                                                                   \
+  hipLaunchKernelGGL((k_sparse_attn<T, NW>), dim3(heads), dim3(NW * 64), 0, st, s, V, kv.stride_b, kv.stride_h, \
+                     kv.stride_n, kv.seq_lens, idx, idx_score, k, out)
+  if (heads * 16 <= 8192) LFPS_LAUNCH_SPARSE(16);
+  else if (heads * 8 <= 8192) LFPS_LAUNCH_SPARSE(8);
+  else LFPS_LAUNCH_SPARSE(4);
+#undef LFPS_LAUNCH_SPARSE
+  return hipGetLastError();
 }
 
 hipError_t launch_sparse_attn(const Shape& s, int dtype, const KvView& kv, const int32_t* idx, const float* idx_score,
-                              const int32_t* k, float* part, hipStream_t st) {
-  const int ns = sparse_attn_splits(s);
-  dim3 grid(ns, s.B * s.Hq), block(kAttnThreads);
-  if (dtype == LFPS_BF16)
-    hipLaunchKernelGGL((k_sparse_attn<uint16_t>), grid, block, 0, st, s, (const uint16_t*)kv.v, kv.stride_b,
-                       kv.stride_h, kv.stride_n, kv.seq_lens, idx, idx_score, k, part, ns);
-  else
-    hipLaunchKernelGGL((k_sparse_attn<float>), grid, block, 0, st, s, (const float*)kv.v, kv.stride_b, kv.stride_h,
-                       kv.stride_n, kv.seq_lens, idx, idx_score, k, part, ns);
-  return hipGetLastError();
-}
-
-hipError_t launch_attn_merge(const Shape& s, const int32_t* k, const float* part, float* out, hipStream_t st) {
-  hipLaunchKernelGGL(k_attn_merge, dim3(s.B * s.Hq), dim3(kD), 0, st, s, k, part, sparse_attn_splits(s), out);
-  return hipGetLastError();
+                              const int32_t* k, float* out, hipStream_t st) {
+  return dtype == LFPS_BF16 ? launch_sparse_t<uint16_t>(s, kv, idx, idx_score, k, out, st)
+                            : launch_sparse_t<float>(s, kv, idx, idx_score, k, out, st);
 }
 
 // ============================================================================ full attention

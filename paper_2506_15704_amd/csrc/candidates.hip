@@ -34,7 +34,9 @@ __global__ __launch_bounds__(kCandThreads) void k_candidates(Shape s, const int3
                                                              int32_t* __restrict__ cand_count,
                                                              int32_t* __restrict__ flags,
                                                              int32_t* __restrict__ redo_g,
-                                                             int32_t* __restrict__ redo_h) {
+                                                             int32_t* __restrict__ redo_h,
+                                                             int64_t* __restrict__ group_start,
+                                                             unsigned long long* __restrict__ line_total) {
   extern __shared__ uint32_t lds[];
   __shared__ int wave_tot[kCandThreads / 64];
   // gridDim.x workgroups share one (b, g): each builds the whole bitmap (cheap) and emits every
@@ -177,6 +179,9 @@ __global__ __launch_bounds__(kCandThreads) void k_candidates(Shape s, const int3
       total = s.cand_cap;
     }
     cand_count[bg] = total;
+    // the group's place on the line of all candidate slots that the filtered scoring pass cuts into
+    // equal parts (the caller has left *line_total at zero)
+    if (group_start) group_start[bg] = (int64_t)atomicAdd(line_total, (unsigned long long)total);
   }
 }
 
@@ -196,11 +201,12 @@ hipError_t configure_candidates(const Shape& s) {
 
 hipError_t launch_candidates(const Shape& s, const int32_t* prev_topk, const int32_t* k, const int32_t* seq_lens,
                              int32_t* cand, int32_t* cand_count, int32_t* flags, int32_t* redo_g, int32_t* redo_h,
-                             hipStream_t st) {
+                             int64_t* group_start, int64_t* line_total, hipStream_t st) {
   int nparts = 256 / (s.B * s.Hkv);                    // one workgroup per CU in total (82 KB of LDS each)
   nparts = nparts < 1 ? 1 : (nparts > 8 ? 8 : nparts);
   hipLaunchKernelGGL(k_candidates, dim3(nparts, s.B * s.Hkv), dim3(kCandThreads), candidates_lds_bytes(s), st, s,
-                     prev_topk, k, seq_lens, cand, cand_count, flags, redo_g, redo_h);
+                     prev_topk, k, seq_lens, cand, cand_count, flags, redo_g, redo_h, group_start,
+                     reinterpret_cast<unsigned long long*>(line_total));
   return hipGetLastError();
 }
 

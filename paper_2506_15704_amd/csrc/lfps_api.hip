@@ -12,9 +12,10 @@ using namespace lfps;
 struct lfps_ctx {
   lfps_config cfg;
   Shape shape;
-  int n_split_sparse, n_split_full;
+  int n_split_full;
   int filter_on;       // filtered scoring inside lfps_step (bf16 caches)
-  int nseg;            // survivor segments per head
+  int nseg;            // survivor pieces per head (row length of seg_count)
+  int filter_blocks;   // launch size of the filtered scoring kernel: the workgroups the device holds at once
   // workspace (device)
   float* score;        // [B, Hq, score_stride]
   int32_t* slot;       // [B, Hq, score_stride] candidate slots of the filtered survivors
@@ -22,11 +23,12 @@ struct lfps_ctx {
   float* thr_state;    // [B, Hq] k-th best score of the previous step
   int32_t* redo_g;     // [B, Hkv]
   int32_t* redo_h;     // [B, Hq]
+  int64_t* group_start; // [B, Hkv] place of each group on the line of all candidate slots; [B*Hkv] = the line's length
   int32_t* cand;       // [B, Hkv, cand_cap]
   int32_t* cand_count; // [B, Hkv]
   float* sel_score;    // [B, Hq, kmax]
-  float* part;         // split partials (max of the two layouts)
-  int32_t* flags;      // [0] status flags, [1] segment size chosen by the last filtered scoring pass
+  float* part;         // split partials of the full-attention baseline
+  int32_t* flags;      // [0] status flags, [1] part size chosen by the last filtered scoring pass
   int64_t ws_bytes;
   // timing
   int timing_on;
@@ -40,7 +42,7 @@ struct lfps_ctx {
 static thread_local char g_create_err[512] = "";
 
 static const char* const kKernelNames[LFPS_N_KERNELS] = {
-    "candidates", "gather_score", "select", "sparse_attn", "attn_merge",
+    "candidates", "gather_score", "select", "sparse_attn",
     "dense_score", "full_attn", "full_merge", "head_score", "filter_score", "filter_select"};
 
 // Margin below the previous step's k-th best score at which the filtered pass keeps a row.
@@ -49,7 +51,7 @@ static const float kFilterMargin = 0.125f;
 namespace {
 
 struct Sizes {
-  int32_t G, cand_cap, score_stride, n_split_sparse, n_split_full, nseg;
+  int32_t G, cand_cap, score_stride, n_split_full, nseg;
   int64_t score_b, cand_b, count_b, sel_b, part_b, slot_b, seg_b, thr_b, redo_b, total;
 };
 
@@ -90,21 +92,19 @@ int check_config(const lfps_config* c, Sizes* z, char* err, size_t errn) {
   Shape s{};
   s.B = c->batch; s.Hq = c->n_q_heads; s.Hkv = c->n_kv_heads; s.G = G;
   s.Lcap = c->max_seq_len; s.kmax = c->max_k; s.cand_cap = z->cand_cap;
-  z->n_split_sparse = sparse_attn_splits(s);
   z->n_split_full = full_attn_splits(s);
   z->score_b = align256((int64_t)c->batch * c->n_q_heads * z->score_stride * 4);
   z->cand_b = align256((int64_t)c->batch * c->n_kv_heads * z->cand_cap * 4);
   z->count_b = align256((int64_t)c->batch * c->n_kv_heads * 4);
   z->sel_b = align256((int64_t)c->batch * c->n_q_heads * c->max_k * 4);
-  int64_t p_sparse = (int64_t)c->batch * c->n_q_heads * z->n_split_sparse * (kD + 1) * 4;
-  int64_t p_full = (int64_t)c->batch * c->n_kv_heads * z->n_split_full * G * (kD + 2) * 4;
-  z->part_b = align256(p_sparse > p_full ? p_sparse : p_full);
+  z->part_b = align256((int64_t)c->batch * c->n_kv_heads * z->n_split_full * G * (kD + 2) * 4);
   const bool filt = c->kv_dtype == LFPS_BF16;
   z->nseg = filter_nseg(s);
   z->slot_b = filt ? z->score_b : 0;
   z->seg_b = align256((int64_t)c->batch * c->n_q_heads * z->nseg * 4);
   z->thr_b = align256((int64_t)c->batch * c->n_q_heads * 4);
-  z->redo_b = align256((int64_t)c->batch * (c->n_q_heads + c->n_kv_heads) * 4);
+  z->redo_b = align256((int64_t)c->batch * (c->n_q_heads + c->n_kv_heads) * 4) +
+              align256(((int64_t)c->batch * c->n_kv_heads + 1) * 8);   // + group_start and the line's length
   z->total = z->score_b + z->cand_b + z->count_b + z->sel_b + z->part_b + z->slot_b + z->seg_b + z->thr_b +
              z->redo_b + 256;
   return LFPS_OK;
@@ -214,7 +214,6 @@ int lfps_create(const lfps_config* cfg, lfps_ctx** out) {
   s.Lcap = cfg->max_seq_len; s.kmax = cfg->max_k; s.cand_cap = z.cand_cap;
   s.radius = cfg->radius; s.n_recent = cfg->n_recent; s.n_sink = cfg->n_sink;
   s.score_stride = z.score_stride;
-  c->n_split_sparse = z.n_split_sparse;
   c->n_split_full = z.n_split_full;
   c->ws_bytes = z.total;
   char* base = nullptr;
@@ -239,15 +238,17 @@ int lfps_create(const lfps_config* cfg, lfps_ctx** out) {
   p += z.thr_b;
   c->redo_g = (int32_t*)p;
   c->redo_h = c->redo_g + (int64_t)cfg->batch * cfg->n_kv_heads;
+  c->group_start = (int64_t*)(p + align256((int64_t)cfg->batch * (cfg->n_q_heads + cfg->n_kv_heads) * 4));
   p += z.redo_b;
   c->flags = (int32_t*)p;
   c->nseg = z.nseg;
   c->filter_on = z.slot_b ? 1 : 0;
   e = hipMemset(c->flags, 0, 256);
-  if (e == hipSuccess) e = hipMemset(c->seg_count, 0, (size_t)(z.seg_b + z.redo_b));
+  if (e == hipSuccess) e = hipMemset(c->seg_count, 0, (size_t)(z.seg_b + z.thr_b + z.redo_b));   // counts, marks, line length
   if (e == hipSuccess) e = hipMemset(c->thr_state, 0xFF, (size_t)z.thr_b);   // all-ones = NaN: "no history"
   if (e == hipSuccess) e = configure_candidates(s);
   if (e == hipSuccess) e = configure_select(s);
+  if (e == hipSuccess && c->filter_on) e = filter_score_blocks(s, &c->filter_blocks);
   if (e == hipSuccess) e = hipDeviceSynchronize();
   if (e != hipSuccess) {
     snprintf(g_create_err, sizeof g_create_err, "workspace setup: %s", hipGetErrorString(e));
@@ -287,7 +288,8 @@ int lfps_candidates(lfps_ctx* ctx, const int32_t* prev_topk, const int32_t* k, c
     return fail(ctx, LFPS_EINVAL, "lfps_candidates: NULL argument");
   hipStream_t st = (hipStream_t)stream;
   LAUNCH(ctx, LFPS_KERNEL_CANDIDATES, st,
-         launch_candidates(ctx->shape, prev_topk, k, seq_lens, cand, cand_count, ctx->flags, nullptr, nullptr, st));
+         launch_candidates(ctx->shape, prev_topk, k, seq_lens, cand, cand_count, ctx->flags, nullptr, nullptr, nullptr,
+                           nullptr, st));
   return LFPS_OK;
 }
 
@@ -324,9 +326,7 @@ int lfps_sparse_attn(lfps_ctx* ctx, const float* q, const lfps_kv* kv, const int
     LAUNCH(ctx, LFPS_KERNEL_HEAD_SCORE, st, launch_head_score(s, ctx->cfg.kv_dtype, q, v, idx, k, ctx->sel_score, st));
     idx_score = ctx->sel_score;
   }
-  LAUNCH(ctx, LFPS_KERNEL_SPARSE_ATTN, st,
-         launch_sparse_attn(s, ctx->cfg.kv_dtype, v, idx, idx_score, k, ctx->part, st));
-  LAUNCH(ctx, LFPS_KERNEL_ATTN_MERGE, st, launch_attn_merge(s, k, ctx->part, out, st));
+  LAUNCH(ctx, LFPS_KERNEL_SPARSE_ATTN, st, launch_sparse_attn(s, ctx->cfg.kv_dtype, v, idx, idx_score, k, out, st));
   return LFPS_OK;
 }
 
@@ -345,19 +345,21 @@ int lfps_step(lfps_ctx* ctx, const float* q, const lfps_kv* kv, const int32_t* p
   if (rc != LFPS_OK) return rc;
   hipStream_t st = (hipStream_t)stream;
   float* sel = topk_score ? topk_score : ctx->sel_score;
+  int64_t* line_total = ctx->group_start + (int64_t)s.B * s.Hkv;   // zero between steps: the filtered select resets it
   LAUNCH(ctx, LFPS_KERNEL_CANDIDATES, st,
          launch_candidates(s, prev_topk, k, v.seq_lens, ctx->cand, ctx->cand_count, ctx->flags, ctx->redo_g,
-                           ctx->redo_h, st));
+                           ctx->redo_h, ctx->filter_on ? ctx->group_start : nullptr, line_total, st));
   const int32_t *only_g = nullptr, *only_h = nullptr;
   if (ctx->filter_on) {
     // survivors of the per-head threshold first; heads left short are rescored below
     LAUNCH(ctx, LFPS_KERNEL_FILTER_SCORE, st,
-           launch_filter_score(s, q, v, ctx->cand, ctx->cand_count, ctx->thr_state, kFilterMargin, ctx->score,
-                               ctx->slot, s.score_stride, ctx->seg_count, ctx->flags + 1, st));
+           launch_filter_score(s, q, v, ctx->cand, ctx->cand_count, ctx->group_start, line_total, ctx->thr_state,
+                               kFilterMargin, ctx->score,
+                               ctx->slot, s.score_stride, ctx->seg_count, ctx->flags + 1, ctx->filter_blocks, st));
     LAUNCH(ctx, LFPS_KERNEL_FILTER_SELECT, st,
            launch_filter_select(s, ctx->score, ctx->slot, s.score_stride, ctx->seg_count, ctx->flags + 1, ctx->nseg,
-                                ctx->cand,
-                                ctx->cand_count, k, topk_idx, sel, ctx->thr_state, ctx->redo_g, ctx->redo_h, st));
+                                ctx->cand_count, ctx->group_start, line_total, k, topk_idx, sel, ctx->thr_state,
+                                ctx->redo_g, ctx->redo_h, st));
     only_g = ctx->redo_g;
     only_h = ctx->redo_h;
   }
@@ -367,8 +369,7 @@ int lfps_step(lfps_ctx* ctx, const float* q, const lfps_kv* kv, const int32_t* p
   LAUNCH(ctx, LFPS_KERNEL_SELECT, st,
          launch_select(s, ctx->score, s.score_stride, ctx->cand, ctx->cand_count, k, topk_idx, sel, only_h,
                        ctx->thr_state, st));
-  LAUNCH(ctx, LFPS_KERNEL_SPARSE_ATTN, st, launch_sparse_attn(s, ctx->cfg.kv_dtype, v, topk_idx, sel, k, ctx->part, st));
-  LAUNCH(ctx, LFPS_KERNEL_ATTN_MERGE, st, launch_attn_merge(s, k, ctx->part, out, st));
+  LAUNCH(ctx, LFPS_KERNEL_SPARSE_ATTN, st, launch_sparse_attn(s, ctx->cfg.kv_dtype, v, topk_idx, sel, k, out, st));
   return LFPS_OK;
 }
 

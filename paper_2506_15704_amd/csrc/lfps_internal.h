@@ -34,9 +34,11 @@ struct Shape {
 hipError_t configure_candidates(const Shape& s);
 hipError_t configure_select(const Shape& s);
 // redo_g [B,Hkv] / redo_h [B,Hq] (or NULL): marks cleared here, set by the filtered select.
+// group_start [B,Hkv] / line_total [1] (or NULL): every group adds its candidate count to *line_total
+// (zero on entry) and keeps the value before the addition as its place on the line of all candidate slots.
 hipError_t launch_candidates(const Shape& s, const int32_t* prev_topk, const int32_t* k, const int32_t* seq_lens,
                              int32_t* cand, int32_t* cand_count, int32_t* flags, int32_t* redo_g, int32_t* redo_h,
-                             hipStream_t st);
+                             int64_t* group_start, int64_t* line_total, hipStream_t st);
 
 // Scores of candidate rows (cand != NULL) or of all rows 0..n_b-1 (cand == NULL) for the G heads
 // of each KV group.  score is [B, Hq, score_stride].
@@ -46,16 +48,22 @@ hipError_t launch_group_score(const Shape& s, int dtype, const float* q, const K
                               hipStream_t st);
 
 // Filtered scoring (bf16 cache): per head only rows with score >= thr_state[b,h] - margin are kept, as
-// (score, position) lists in at most filter_nseg(s) segments per head; the segment size of a step is
-// written to *seg_rows_out by the scoring pass and read by the select; see score.hip.
+// (score, position) lists in at most filter_nseg(s) pieces per head.  The kernel runs with exactly
+// n_blocks workgroups (filter_score_blocks: what the device holds at once) and cuts the candidate
+// slots of all groups (placed on one line by the candidates kernel: group_start, line_total) into
+// equal parts, one per wave; the part size of a step is written to *seg_rows_out by the scoring
+// pass and read by the select, which also resets *line_total; see score.hip.
 int filter_nseg(const Shape& s);
+hipError_t filter_score_blocks(const Shape& s, int* out);
 hipError_t launch_filter_score(const Shape& s, const float* q, const KvView& kv, const int32_t* cand,
-                               const int32_t* cand_count, const float* thr_state, float margin, float* score,
+                               const int32_t* cand_count, const int64_t* group_start, const int64_t* line_total,
+                               const float* thr_state, float margin, float* score,
                                int32_t* slot_out, int64_t score_stride, int32_t* seg_count, int32_t* seg_rows_out,
-                               hipStream_t st);
+                               int n_blocks, hipStream_t st);
 hipError_t launch_filter_select(const Shape& s, const float* score, const int32_t* slot_in, int64_t score_stride,
-                                const int32_t* seg_count, const int32_t* seg_rows, int nseg, const int32_t* cand,
-                                const int32_t* cand_count, const int32_t* k, int32_t* topk_idx, float* topk_score,
+                                const int32_t* seg_count, const int32_t* seg_rows, int nseg,
+                                const int32_t* cand_count, const int64_t* group_start, int64_t* line_total,
+                                const int32_t* k, int32_t* topk_idx, float* topk_score,
                                 float* thr_state, int32_t* redo_g, int32_t* redo_h, hipStream_t st);
 
 // Per (b, h): the k_b best of score[b,h,0:count]; count = cand_count[b, g(h)] when cand != NULL,
@@ -70,11 +78,9 @@ hipError_t launch_select(const Shape& s, const float* score, int64_t score_strid
 hipError_t launch_head_score(const Shape& s, int dtype, const float* q, const KvView& kv, const int32_t* idx,
                              const int32_t* k, float* idx_score, hipStream_t st);
 
-// Sparse attention partials + merge.  part is [B*Hq, n_split, D+1] floats.
-int sparse_attn_splits(const Shape& s);
+// Sparse attention: one workgroup per (b, h), output row written directly.
 hipError_t launch_sparse_attn(const Shape& s, int dtype, const KvView& kv, const int32_t* idx, const float* idx_score,
-                              const int32_t* k, float* part, hipStream_t st);
-hipError_t launch_attn_merge(const Shape& s, const int32_t* k, const float* part, float* out, hipStream_t st);
+                              const int32_t* k, float* out, hipStream_t st);
 
 // Full attention: split partials [B*Hkv, n_split, G, D+2] + merge.
 int full_attn_splits(const Shape& s);

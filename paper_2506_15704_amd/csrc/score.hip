@@ -151,191 +151,185 @@ __global__ __launch_bounds__(kScoreThreads) void k_group_score_bf16(Shape s, con
 // (the threshold is the previous step's k-th best score minus a margin: consecutive decode steps
 // select almost the same rows, the premise of the method).  Writing every score costs far more
 // than its share of bytes because the small writes interleave with the row gather; survivors are
-// a few per cent of the rows.  Wave-item `wg` of a group owns the contiguous candidate slots
-// [wg*R, (wg+1)*R), R = seg_rows, and appends its survivors (score, row position), in slot order, at offset wg*R
-// of each head's score / position rows (staged in LDS, written when the wave is done); the count goes to seg_count[head, wg].
-// No atomics: the lists are reproducible and ascending in slot.  A threshold of -inf keeps every row; NaN means there is no previous step.
+// a few per cent of the rows.
+//
+// Work split: the candidate slots of all groups, laid end to end, form one line [0, total); it is
+// cut into equal parts of S slots, one per wave of the launch, and the launch has exactly as many
+// waves as the chip holds at once.  Every wave therefore reads the same number of rows whatever
+// the mix of sequence lengths, and no workgroup waits for a slot.  The candidates kernel has given
+// every group its place on the line (group_start; the order of the groups on the line is the
+// order in which they finished there, which changes nothing in the result) and left the line's
+// length in *line_total.  A part that crosses a group boundary is handled as several pieces, one
+// per group.  Piece `seg` of a group (seg = wave index minus the index of the first wave that
+// touches the group) covers the group's slots [lo, hi) and appends its survivors (score, row
+// position), in slot order, at offset lo of each head's score / position rows (staged in LDS,
+// written when the piece is done); their number goes to seg_count[head, seg].  No atomics here:
+// the lists are ascending in position and the same from run to run.
+// A threshold of -inf keeps every row; NaN means there is no previous step.
 constexpr int kFilterStage = 256;   // survivors one wave can hold per head before it must write them out
-constexpr int kFilterWaves = 2048;  // wave-items aimed at per launch: 256 CUs x 2 workgroups x 4 waves
 
 template <int G>
-__global__ __launch_bounds__(kScoreThreads) void k_filter_score_bf16(
+__global__ __launch_bounds__(kScoreThreads, 2) void k_filter_score_bf16(
     Shape s, const float* __restrict__ q, const __bf16* __restrict__ K, int64_t stride_b, int64_t stride_h,
     int64_t stride_n, const int32_t* __restrict__ seq_lens, const int32_t* __restrict__ cand,
-    const int32_t* __restrict__ cand_count, const float* __restrict__ thr_state, float margin,
+    const int32_t* __restrict__ cand_count, const int64_t* __restrict__ group_start,
+    const int64_t* __restrict__ line_total, const float* __restrict__ thr_state, float margin,
     float* __restrict__ score, int32_t* __restrict__ slot_out, int64_t score_stride,
     int32_t* __restrict__ seg_count, int32_t* __restrict__ seg_rows_out, int min_seg_rows, int nseg, float scale) {
   __shared__ float stage_score[4][G][kFilterStage];
   __shared__ int32_t stage_slot[4][G][kFilterStage];
-  __shared__ int pre[kScoreThreads];
-  __shared__ int wtot[4];
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // wave-uniform values stay in scalar registers
   const int j = lane & 15, kb = lane >> 4;
-
-  // Work items = (group, segment of seg_rows candidate slots), flattened over the groups in order, one
-  // item per wave: a group gets as many waves as it has candidates, so ragged batches stay balanced.
-  // seg_rows is chosen from this step's total candidate count so that there are about kFilterWaves
-  // items (one per resident wave).  Every workgroup derives the same numbers from cand_count.
   const int n_groups = s.B * s.Hkv;
-  const int item = blockIdx.x * 4 + wave;
-  int64_t total = 0;
-  for (int c0 = tid; c0 < n_groups; c0 += kScoreThreads) {
-    const int c = cand_count[c0];
-    total += c < 0 ? 0 : (c > s.cand_cap ? s.cand_cap : c);
-  }
-#pragma unroll
-  for (int d = 1; d < 64; d <<= 1) total += __shfl_xor(total, d);
-  if (lane == 0) pre[wave] = (int)total;
-  __syncthreads();
-  total = (int64_t)pre[0] + pre[1] + pre[2] + pre[3];
-  __syncthreads();
-  int seg_rows = (int)(((total + kFilterWaves - 1) / kFilterWaves + 63) & ~(int64_t)63);
-  seg_rows = seg_rows < min_seg_rows ? min_seg_rows : seg_rows;
-  if (blockIdx.x == 0 && tid == 0) *seg_rows_out = seg_rows;      // the select reads it
-  int bg = -1, wg = 0, base = 0;
-  for (int c0 = 0; c0 < n_groups && base <= blockIdx.x * 4 + 3; c0 += kScoreThreads) {
-    int v = 0;
-    if (c0 + tid < n_groups) {
-      int c = cand_count[c0 + tid];
-      c = c < 0 ? 0 : (c > s.cand_cap ? s.cand_cap : c);
-      v = (c + seg_rows - 1) / seg_rows;
-    }
-    int inc = v;
-#pragma unroll
-    for (int d = 1; d < 64; d <<= 1) {
-      const int o = __shfl_up(inc, d);
-      if (lane >= d) inc += o;
-    }
-    if (lane == 63) wtot[wave] = inc;
-    __syncthreads();
-    int before = 0, chunk_total = 0;
-#pragma unroll
-    for (int w = 0; w < 4; ++w) {
-      before += w < wave ? wtot[w] : 0;
-      chunk_total += wtot[w];
-    }
-    pre[tid] = base + before + inc - v;                // first item of group c0 + tid
-    __syncthreads();
-    if (bg < 0 && item < base + chunk_total) {         // wave-uniform: my item belongs to this chunk
-      int lo_t = 0, hi_t = kScoreThreads - 1;          // last group whose first item is <= mine
-      while (lo_t < hi_t) {
-        const int mid = (lo_t + hi_t + 1) >> 1;
-        if (pre[mid] <= item) lo_t = mid; else hi_t = mid - 1;
-      }
-      bg = c0 + lo_t;
-      wg = item - pre[lo_t];
-    }
-    base += chunk_total;
-    __syncthreads();
-  }
-  if (bg < 0) return;                                   // more waves than items
-  const int b = bg / s.Hkv, g = bg % s.Hkv;
-  int n = seq_lens[b];
-  n = n < 0 ? 0 : (n > s.Lcap ? s.Lcap : n);
-  int count = cand_count[bg];
-  count = count < 0 ? 0 : (count > s.cand_cap ? s.cand_cap : count);
-  const int seg_lo = wg * seg_rows;
-  const int seg_hi = seg_lo + seg_rows < count ? seg_lo + seg_rows : count;
-  const int64_t head = (int64_t)b * s.Hq + (int64_t)g * G + (kb < G ? kb : 0);
-  // NaN in thr_state = "no previous step": skip the group here, the unfiltered pass will take it
-  bool no_history = false;
-#pragma unroll
-  for (int h = 0; h < G; ++h) no_history |= isnan(thr_state[(int64_t)b * s.Hq + (int64_t)g * G + h]);
-  if (seg_lo >= count || no_history) {
-    if (j == 0 && kb < G) seg_count[head * nseg + wg] = 0;
-    return;
-  }
-  const float tau = kb < G ? thr_state[head] - margin : INFINITY;
 
-  bf16x8 A[4];                                        // filled after the first tile's loads are on their way
-  const __bf16* Kbg = K + (int64_t)b * stride_b + (int64_t)g * stride_h;
-  const int32_t* cbg = cand + (int64_t)bg * s.cand_cap;
-  float* sc = score + head * score_stride + seg_lo;
-  int32_t* so = slot_out + head * score_stride + seg_lo;
-  const uint32_t below = (1u << j) - 1u;            // lanes of my 16-lane group with a lower row
-  int run = 0;                                        // survivors of my head already in global memory
-  int staged = 0;                                     // survivors of my head waiting in LDS
+  // ---- the part of this wave: S slots from wave_index * S; every wave derives the same S
+  const int64_t total = *line_total;
+  const int64_t n_waves = (int64_t)gridDim.x * 4;
+  int64_t S = ((total + n_waves - 1) / n_waves + 63) & ~(int64_t)63;
+  S = S < min_seg_rows ? min_seg_rows : S;
+  if (blockIdx.x == 0 && tid == 0) *seg_rows_out = (int32_t)S;      // the select reads it
+  const int64_t w = (int64_t)blockIdx.x * 4 + wave;
+  const int64_t part_lo = w * S;
+  const int64_t part_hi = part_lo + S < total ? part_lo + S : total;
+  if (part_lo >= total) return;                          // nothing left for this wave
 
-  // Survivors are staged in LDS and written out when the wave is done (or the stage is nearly
-  // full).  Global stores inside the loop would share the vector-memory counter with the row
-  // loads, so that every wait for a load would also wait for the stores before it.
+  const uint32_t below = (1u << j) - 1u;                // lanes of my 16-lane group with a lower row
   float* st_s = stage_score[wave][kb < G ? kb : 0];
   int32_t* st_i = stage_slot[wave][kb < G ? kb : 0];
-  auto flush = [&]() {
-#pragma unroll
-    for (int h = 0; h < G; ++h) {
-      const int cnt_h = __shfl(staged, 16 * h);
-      const int run_h = __shfl(run, 16 * h);
-      float* dsc = score + ((int64_t)b * s.Hq + (int64_t)g * G + h) * score_stride + seg_lo + run_h;
-      int32_t* dsl = slot_out + ((int64_t)b * s.Hq + (int64_t)g * G + h) * score_stride + seg_lo + run_h;
-      for (int e = lane; e < cnt_h; e += 64) {
-        dsc[e] = stage_score[wave][h][e];
-        dsl[e] = stage_slot[wave][h][e];
-      }
-    }
-    run += staged;
-    staged = 0;
-  };
-
-  // Two 64-row tiles are kept in flight per wave: while tile i is multiplied, the loads of tile
-  // i+1 (issued before) are still arriving, and the row ids of tile i+2 are being fetched.
-  auto issue = [&](bf16x8 (&Bt)[4][4], int (&rows)[4], int ids) {
-#pragma unroll
-    for (int t = 0; t < 4; ++t) {
-      int row = __shfl(ids, 16 * t + j);
-      row = (row < 0 || row >= n) ? 0 : row;          // padding slots read row 0 and are never kept
-      rows[t] = row;
-      const bf16x8* p = reinterpret_cast<const bf16x8*>(Kbg + (int64_t)row * stride_n) + 4 * kb;
-#pragma unroll
-      for (int kk = 0; kk < 4; ++kk) Bt[t][kk] = p[kk];
-    }
-  };
-  auto consume = [&](bf16x8 (&Bt)[4][4], int (&rows)[4], int base) {
-#pragma unroll
-    for (int t = 0; t < 4; ++t) {
-      f32x4 acc = {0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-      for (int kk = 0; kk < 4; ++kk) acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(A[kk], Bt[t][kk], acc, 0, 0, 0);
-      const float v = ((acc[0] + acc[1]) + acc[2]) * scale;
-      const int slot = base + 16 * t + j;
-      const bool pass = kb < G && slot < seg_hi && v >= tau;
-      const uint32_t gm = (uint32_t)(__ballot(pass) >> (16 * kb)) & 0xFFFFu;   // my head's 16 rows
-      if (pass) {
-        const int o = staged + __popc(gm & below);
-        st_s[o] = v;
-        st_i[o] = rows[t];                            // the row position itself: the select needs no lookup
-      }
-      staged += __popc(gm);
-    }
-    // room for one more tile (64 rows) in every head's stage?  (wave-uniform test)
-    if (__ballot(staged > kFilterStage - kRowsPerWaveIter)) flush();
-  };
-  auto fetch_ids = [&](int base) { return base + lane < seg_hi ? cbg[base + lane] : -1; };
-
-  bf16x8 Bt0[4][4], Bt1[4][4];
-  int rows0[4], rows1[4];
   constexpr int T = kRowsPerWaveIter;
-  issue(Bt0, rows0, fetch_ids(seg_lo));
-  int ids_b = fetch_ids(seg_lo + T);                  // ids of the tile whose loads are issued next
-  load_query_operand<G>(A, q, (int64_t)b * s.Hq + (int64_t)g * G, j, kb);   // overlaps the first tile's latency
-  for (int base = seg_lo; base < seg_hi; base += 2 * T) {
-    const bool has_b = base + T < seg_hi;             // wave-uniform
-    int ids_a2 = -1;
-    if (has_b) {
-      issue(Bt1, rows1, ids_b);
-      ids_a2 = fetch_ids(base + 2 * T);
+
+  // the groups that overlap my part: 64 groups are tested at a time, one per lane
+  for (int g0 = 0; g0 < n_groups; g0 += 64) {
+    int64_t st = 0;
+    int cnt_l = 0;
+    if (g0 + lane < n_groups) {
+      st = group_start[g0 + lane];
+      const int c = cand_count[g0 + lane];
+      cnt_l = c < 0 ? 0 : (c > s.cand_cap ? s.cand_cap : c);
     }
-    consume(Bt0, rows0, base);
-    if (has_b) {
-      if (base + 2 * T < seg_hi) {
-        issue(Bt0, rows0, ids_a2);
-        ids_b = fetch_ids(base + 3 * T);
+    uint64_t hits = __ballot(cnt_l > 0 && st < part_hi && st + cnt_l > part_lo);
+  while (hits) {                                          // one piece per overlapping group
+    const int src = __builtin_ctzll(hits);
+    hits &= hits - 1;
+    const int bg = g0 + src;
+    const int64_t pg = ((int64_t)__builtin_amdgcn_readlane((int)(st >> 32), src) << 32) |
+                       (uint32_t)__builtin_amdgcn_readlane((int)(uint32_t)st, src);   // the group's place on the line
+    const int count = __builtin_amdgcn_readlane(cnt_l, src);
+    const int seg_lo = part_lo > pg ? (int)(part_lo - pg) : 0;
+    const int seg_hi = part_hi - pg < count ? (int)(part_hi - pg) : count;
+    const int seg = (int)(w - pg / S);
+
+    const int b = bg / s.Hkv, g = bg % s.Hkv;
+    int n = seq_lens[b];
+    n = n < 0 ? 0 : (n > s.Lcap ? s.Lcap : n);
+    const int64_t head = (int64_t)b * s.Hq + (int64_t)g * G + (kb < G ? kb : 0);
+    // NaN in thr_state = "no previous step": skip the group here, the unfiltered pass will take it
+    bool no_history = false;
+#pragma unroll
+    for (int h = 0; h < G; ++h) no_history |= isnan(thr_state[(int64_t)b * s.Hq + (int64_t)g * G + h]);
+    if (no_history) {
+      if (j == 0 && kb < G) seg_count[head * nseg + seg] = 0;
+      continue;
+    }
+    const float tau = kb < G ? thr_state[head] - margin : INFINITY;
+
+    bf16x8 A[4];                                        // filled after the first tile's loads are on their way
+    const __bf16* Kbg = K + (int64_t)b * stride_b + (int64_t)g * stride_h;
+    const int32_t* cbg = cand + (int64_t)bg * s.cand_cap;
+    int run = 0;                                        // survivors of my head already in global memory
+    int staged = 0;                                     // survivors of my head waiting in LDS
+
+    // Survivors are staged in LDS and written out when the piece is done (or the stage is nearly
+    // full).  Global stores inside the loop would share the vector-memory counter with the row
+    // loads, so that every wait for a load would also wait for the stores before it.
+    auto flush = [&]() {
+#pragma unroll
+      for (int h = 0; h < G; ++h) {
+        const int cnt_h = __shfl(staged, 16 * h);
+        const int run_h = __shfl(run, 16 * h);
+        float* dsc = score + ((int64_t)b * s.Hq + (int64_t)g * G + h) * score_stride + seg_lo + run_h;
+        int32_t* dsl = slot_out + ((int64_t)b * s.Hq + (int64_t)g * G + h) * score_stride + seg_lo + run_h;
+        for (int e = lane; e < cnt_h; e += 64) {
+          dsc[e] = stage_score[wave][h][e];
+          dsl[e] = stage_slot[wave][h][e];
+        }
       }
-      consume(Bt1, rows1, base + T);
+      run += staged;
+      staged = 0;
+    };
+
+    // Two 64-row tiles are kept in flight per wave: while tile i is multiplied, the loads of tile
+    // i+1 (issued before) are still arriving.
+    auto issue = [&](bf16x8 (&Bt)[4][4], int (&rows)[4], int ids) {
+#pragma unroll
+      for (int t = 0; t < 4; ++t) {
+        int row = __shfl(ids, 16 * t + j);
+        row = (row < 0 || row >= n) ? 0 : row;          // padding slots read row 0 and are never kept
+        rows[t] = row;
+        const bf16x8* p = reinterpret_cast<const bf16x8*>(Kbg + (int64_t)row * stride_n) + 4 * kb;
+#pragma unroll
+        for (int kk = 0; kk < 4; ++kk) Bt[t][kk] = p[kk];
+      }
+    };
+    auto consume = [&](bf16x8 (&Bt)[4][4], int (&rows)[4], int base_slot) {
+#pragma unroll
+      for (int t = 0; t < 4; ++t) {
+        f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int kk = 0; kk < 4; ++kk) acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(A[kk], Bt[t][kk], acc, 0, 0, 0);
+        const float v = ((acc[0] + acc[1]) + acc[2]) * scale;
+        const int slot = base_slot + 16 * t + j;
+        const bool pass = kb < G && slot < seg_hi && v >= tau;
+        const uint32_t gm = (uint32_t)(__ballot(pass) >> (16 * kb)) & 0xFFFFu;   // my head's 16 rows
+        if (pass) {
+          const int o = staged + __popc(gm & below);
+          st_s[o] = v;
+          st_i[o] = rows[t];                            // the row position itself: the select needs no lookup
+        }
+        staged += __popc(gm);
+      }
+      // room for one more tile (64 rows) in every head's stage?  (wave-uniform test)
+      if (__ballot(staged > kFilterStage - kRowsPerWaveIter)) flush();
+    };
+    // Slots past the end of the piece read the id of its last slot (a valid row) and are never kept:
+    // no load of the loop below sits behind a branch, so the waits the compiler derives for the
+    // two tiles in flight are exact counts instead of "everything outstanding".
+    auto fetch_ids = [&](int base_slot) {
+      const int sl = base_slot + lane;
+      return cbg[sl < seg_hi ? sl : seg_hi - 1];
+    };
+
+    // Row ids are fetched three tiles ahead, always BEFORE the loads of the tile that precedes
+    // their use are issued: a wait for ids then never has to wait for a tile still in flight
+    // (the vector-memory counter completes in issue order).
+    bf16x8 Bt0[4][4], Bt1[4][4];
+    int rows0[4], rows1[4];
+    const int ids_0 = fetch_ids(seg_lo);
+    int ids_b = fetch_ids(seg_lo + T);                  // ids of the next odd tile
+    int ids_a = fetch_ids(seg_lo + 2 * T);              // ids of the next even tile
+    issue(Bt0, rows0, ids_0);
+    load_query_operand<G>(A, q, (int64_t)b * s.Hq + (int64_t)g * G, j, kb);   // overlaps the first tile's latency
+    int base_slot = seg_lo;
+    for (; base_slot + 2 * T < seg_hi; base_slot += 2 * T) {   // at least three tiles left: no conditions inside
+      issue(Bt1, rows1, ids_b);
+      ids_b = fetch_ids(base_slot + 3 * T);
+      consume(Bt0, rows0, base_slot);
+      issue(Bt0, rows0, ids_a);
+      ids_a = fetch_ids(base_slot + 4 * T);
+      consume(Bt1, rows1, base_slot + T);
     }
+    if (base_slot + T < seg_hi) {                       // two tiles left (wave-uniform)
+      issue(Bt1, rows1, ids_b);
+      consume(Bt0, rows0, base_slot);
+      consume(Bt1, rows1, base_slot + T);
+    } else {
+      consume(Bt0, rows0, base_slot);
+    }
+    flush();
+    if (j == 0 && kb < G) seg_count[head * nseg + seg] = run;
   }
-  flush();
-  if (j == 0 && kb < G) seg_count[head * nseg + wg] = run;
+  }
 }
 
 // ----------------------------------------------------------------------------- fp32, vector ALU
@@ -498,22 +492,45 @@ hipError_t launch_group_score(const Shape& s, int dtype, const float* q, const K
   }
 }
 
-// Smallest segment (= wave-item) size in candidate slots, and the segments a head can then have (<= 512).
-int filter_min_seg_rows(const Shape& s) { return (((s.cand_cap + 511) / 512) + 63) & ~63; }
-int filter_nseg(const Shape& s) { return (s.cand_cap + filter_min_seg_rows(s) - 1) / filter_min_seg_rows(s); }
+// Smallest part size in candidate slots, and the pieces a group can then be cut into (<= 1024).
+int filter_min_seg_rows(const Shape& s) { return (((s.cand_cap + 999) / 1000) + 63) & ~63; }
+int filter_nseg(const Shape& s) { return s.cand_cap / filter_min_seg_rows(s) + 2; }
+
+template <int G>
+static hipError_t filter_resident_blocks(int* out) {
+  int per_cu = 0, dev = 0;
+  hipDeviceProp_t prop;
+  hipError_t e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, k_filter_score_bf16<G>, kScoreThreads, 0);
+  if (e == hipSuccess) e = hipGetDevice(&dev);
+  if (e == hipSuccess) e = hipGetDeviceProperties(&prop, dev);
+  if (e != hipSuccess) return e;
+  *out = per_cu * prop.multiProcessorCount;
+  return hipSuccess;
+}
+
+// Workgroups of the filtered scoring kernel that the current device holds at once (its launch size).
+hipError_t filter_score_blocks(const Shape& s, int* out) {
+  switch (s.G) {
+    case 1: return filter_resident_blocks<1>(out);
+    case 2: return filter_resident_blocks<2>(out);
+    case 4: return filter_resident_blocks<4>(out);
+    default: return hipErrorInvalidValue;
+  }
+}
 
 hipError_t launch_filter_score(const Shape& s, const float* q, const KvView& kv, const int32_t* cand,
-                               const int32_t* cand_count, const float* thr_state, float margin, float* score,
+                               const int32_t* cand_count, const int64_t* group_start, const int64_t* line_total,
+                               const float* thr_state, float margin, float* score,
                                int32_t* slot_out, int64_t score_stride, int32_t* seg_count, int32_t* seg_rows_out,
-                               hipStream_t st) {
+                               int n_blocks, hipStream_t st) {
   const int nseg = filter_nseg(s);
-  // items <= total/seg_rows + groups <= kFilterWaves + groups
-  const int64_t max_items = (int64_t)kFilterWaves + (int64_t)s.B * s.Hkv;
-  dim3 grid((unsigned)((max_items + 3) / 4)), block(kScoreThreads);
+  if (n_blocks < 1) return hipErrorInvalidValue;
+  dim3 grid((unsigned)n_blocks), block(kScoreThreads);
   const float scale = 0.08838834764831845f;
 #define LFPS_LAUNCH_FILTER(GG)                                                                                     \
   hipLaunchKernelGGL((k_filter_score_bf16<GG>), grid, block, 0, st, s, q, (const __bf16*)kv.k, kv.stride_b,       \
-                     kv.stride_h, kv.stride_n, kv.seq_lens, cand, cand_count, thr_state, margin, score, slot_out, \
+                     kv.stride_h, kv.stride_n, kv.seq_lens, cand, cand_count, group_start, line_total, thr_state, margin, score, \
+                     slot_out,                                                                                     \
                      score_stride, seg_count, seg_rows_out, filter_min_seg_rows(s), nseg, scale)
   switch (s.G) {
     case 1: LFPS_LAUNCH_FILTER(1); break;

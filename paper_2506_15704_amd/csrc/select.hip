@@ -343,18 +343,22 @@ __global__ __launch_bounds__(kSelThreads) void k_select(Shape s, const float* __
 }
 
 // ----------------------------------------------------------------------------- filtered input
-// Select from the survivor lists written by the filtered score kernel: segment sgm of head (b, h)
-// holds seg_count[bh, sgm] (score, row position) pairs at offset sgm * R of the head's score /
-// position rows, ascending in position within and across segments.  If the survivors are fewer than k (the filter
+// Select from the survivor lists written by the filtered score kernel.  That kernel cuts the
+// line of all groups' candidate slots into parts of S slots (S = *seg_rows_in), one per wave; my
+// group starts at slot pg = group_start[b, g] of the line, and its piece `sgm` is what wave
+// w_first + sgm took of it, w_first = pg / S: the group's slots [lo, hi).  The piece holds
+// seg_count[bh, sgm] (score, row position) pairs at offset lo of the head's score / position rows,
+// ascending in position within and across pieces.  If the survivors are fewer than k (the filter
 // threshold was too high) or more than the LDS list holds, the head is flagged for the unfiltered
-// pass instead and nothing is written.
+// pass instead and nothing is written.  Workgroup 0 leaves *line_total at zero for the next step.
 __global__ __launch_bounds__(kFilterSelThreads) void k_filter_select(Shape s, const float* __restrict__ score,
                                                                const int32_t* __restrict__ slot_in,
                                                                int64_t score_stride,
                                                                const int32_t* __restrict__ seg_count,
                                                                const int32_t* __restrict__ seg_rows_in, int nseg,
-                                                               const int32_t* __restrict__ cand,
                                                                const int32_t* __restrict__ cand_count,
+                                                               const int64_t* __restrict__ group_start,
+                                                               int64_t* __restrict__ line_total,
                                                                const int32_t* __restrict__ kk,
                                                                int32_t* __restrict__ topk_idx,
                                                                float* __restrict__ topk_score,
@@ -362,34 +366,58 @@ __global__ __launch_bounds__(kFilterSelThreads) void k_filter_select(Shape s, co
                                                                int32_t* __restrict__ redo_g,
                                                                int32_t* __restrict__ redo_h, int cap) {
   constexpr int NT = kFilterSelThreads, kSelWaves = NT / 64;
+  constexpr int kPiecesPerThread = 4;              // nseg <= 1024
   __shared__ SelectShared<NT> sm;
-  __shared__ int seg_off[512];
+  __shared__ int seg_off[kPiecesPerThread * NT];
   __shared__ int wtot[kSelWaves];
   extern __shared__ float cache[];                 // cap scores, then cap row positions
   int32_t* lslot = reinterpret_cast<int32_t*>(cache + cap);
   const int bh = blockIdx.x, b = bh / s.Hq, h = bh % s.Hq, g = h / s.G;
   const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
-  int c = cand_count[b * s.Hkv + g];
+  const int bg = b * s.Hkv + g;
+  if (bh == 0 && tid == 0) *line_total = 0;          // the scoring pass that read it has finished
+  int raw[kPiecesPerThread];                         // piece counts of this head, masked once the geometry is known
+#pragma unroll
+  for (int u = 0; u < kPiecesPerThread; ++u) {
+    const int sgm = kPiecesPerThread * tid + u;
+    raw[u] = sgm < nseg ? seg_count[(int64_t)bh * nseg + sgm] : 0;
+  }
+  int c = cand_count[bg];
   c = c < 0 ? 0 : (c > s.cand_cap ? s.cand_cap : c);
   int kb = kk[b];
   kb = kb < 0 ? 0 : (kb > s.kmax ? s.kmax : kb);
   const int ksel = kb < c ? kb : c;
-  int R = *seg_rows_in;                              // chosen by the scoring pass of this step
-  R = R < 64 ? 64 : R;
+  int64_t S = *seg_rows_in;                          // chosen by the scoring pass of this step
+  S = S < 64 ? 64 : S;
+  const int64_t pg = group_start[bg];
+  const int64_t w_first = pg / S;
+  auto piece_lo = [&](int sgm) {                     // first slot of piece sgm within my group
+    const int64_t lo = (w_first + sgm) * S - pg;
+    return lo < 0 ? (int64_t)0 : lo;
+  };
+  auto piece_hi = [&](int sgm) {
+    const int64_t hi = (w_first + sgm + 1) * S - pg;
+    return hi > c ? (int64_t)c : hi;
+  };
 
-  // exclusive prefix of the segment counts (nseg <= 512: two consecutive segments per thread)
-  int cnt2[2] = {0, 0};
+  // exclusive prefix of the piece counts (kPiecesPerThread consecutive pieces per thread); the counts
+  // were loaded above, before the group's geometry was known: entries of pieces that do not exist
+  // hold stale values and are masked here
+  int cntp[kPiecesPerThread];
+  int cnt = 0;
 #pragma unroll
-  for (int u = 0; u < 2; ++u) {
-    const int sgm = 2 * tid + u;
+  for (int u = 0; u < kPiecesPerThread; ++u) {
+    const int sgm = kPiecesPerThread * tid + u;
+    cntp[u] = 0;
     if (sgm < nseg) {
-      int v = seg_count[(int64_t)bh * nseg + sgm];
-      const int room = c - sgm * R;                  // rows the segment can hold
-      v = v < 0 ? 0 : (v > R ? R : v);
-      cnt2[u] = room <= 0 ? 0 : (v > room ? room : v);
+      const int64_t room = piece_hi(sgm) - piece_lo(sgm);   // rows the piece covers
+      if (room > 0) {
+        const int v = raw[u] < 0 ? 0 : raw[u];
+        cntp[u] = v > room ? (int)room : v;
+      }
     }
+    cnt += cntp[u];
   }
-  const int cnt = cnt2[0] + cnt2[1];
   int inc = cnt;
 #pragma unroll
   for (int d = 1; d < 64; d <<= 1) {
@@ -405,11 +433,17 @@ __global__ __launch_bounds__(kFilterSelThreads) void k_filter_select(Shape s, co
     base += w < wv ? t : 0;
     n += t;
   }
-  seg_off[2 * tid] = base + inc - cnt;
-  seg_off[2 * tid + 1] = base + inc - cnt + cnt2[0];
+  {
+    int off = base + inc - cnt;
+#pragma unroll
+    for (int u = 0; u < kPiecesPerThread; ++u) {
+      seg_off[kPiecesPerThread * tid + u] = off;
+      off += cntp[u];
+    }
+  }
   if (n < ksel || n > cap) {                        // block-uniform
     if (tid == 0) {
-      redo_g[b * s.Hkv + g] = 1;
+      redo_g[bg] = 1;
       redo_h[bh] = 1;
     }
     return;
@@ -427,17 +461,49 @@ __global__ __launch_bounds__(kFilterSelThreads) void k_filter_select(Shape s, co
   __syncthreads();
   const float* sc = score + (int64_t)bh * score_stride;
   const int32_t* sl = slot_in + (int64_t)bh * score_stride;
-  // flat copy of the survivors into LDS: element e lies in the segment found by a binary search over
-  // the offsets, so every load of the copy is independent of the others
-  for (int e = tid; e < n; e += NT) {
-    int lo_s = 0, hi_s = nseg - 1;                  // last segment with seg_off <= e
-    while (lo_s < hi_s) {
-      const int mid = (lo_s + hi_s + 1) >> 1;
-      if (seg_off[mid] <= e) lo_s = mid; else hi_s = mid - 1;
+  // Flat copy of the survivors into LDS: element e lies in the piece found by a binary search over
+  // the offsets.  kGatherBatch elements per thread are searched together (fixed trip count, no
+  // branches) and all their loads are issued before the first is used, so the copy costs a few
+  // memory round trips instead of one per element.
+  int np = (int)((pg + c - 1) / S - w_first) + 1;   // pieces my group was cut into
+  np = np < 1 ? 1 : (np > nseg ? nseg : np);
+  np = np < kPiecesPerThread * NT ? np : kPiecesPerThread * NT;
+  int top = 1;
+  while (top < np) top <<= 1;
+  constexpr int kGatherBatch = 12;
+  for (int e0 = tid; e0 < n; e0 += kGatherBatch * NT) {
+    int pc[kGatherBatch];
+#pragma unroll
+    for (int u = 0; u < kGatherBatch; ++u) pc[u] = 0;
+    for (int half = top >> 1; half >= 1; half >>= 1) {   // last piece with seg_off <= e (seg_off[0] = 0)
+#pragma unroll
+      for (int u = 0; u < kGatherBatch; ++u) {
+        const int mid = pc[u] + half;
+        const int e = e0 + u * NT;
+        if (mid < np && seg_off[mid] <= e) pc[u] = mid;
+      }
     }
-    const int64_t src = (int64_t)lo_s * R + (e - seg_off[lo_s]);
-    cache[e] = sanitize(sc[src]);
-    lslot[e] = sl[src];                               // the row position, written by the scoring pass
+    float v[kGatherBatch];
+    int32_t ps[kGatherBatch];
+#pragma unroll
+    for (int u = 0; u < kGatherBatch; ++u) {
+      const int e = e0 + u * NT;
+      v[u] = 0.f;
+      ps[u] = 0;
+      if (e < n) {
+        const int64_t src = piece_lo(pc[u]) + (e - seg_off[pc[u]]);
+        v[u] = sc[src];
+        ps[u] = sl[src];                              // the row position, written by the scoring pass
+      }
+    }
+#pragma unroll
+    for (int u = 0; u < kGatherBatch; ++u) {
+      const int e = e0 + u * NT;
+      if (e < n) {
+        cache[e] = sanitize(v[u]);
+        lslot[e] = ps[u];
+      }
+    }
   }
   __syncthreads();
   select_body<true, NT>(sm, cache, nullptr, n, ksel, lslot, nullptr, oi, os, thr_state + bh);
@@ -477,12 +543,13 @@ hipError_t launch_select(const Shape& s, const float* score, int64_t score_strid
 }
 
 hipError_t launch_filter_select(const Shape& s, const float* score, const int32_t* slot_in, int64_t score_stride,
-                                const int32_t* seg_count, const int32_t* seg_rows, int nseg, const int32_t* cand,
-                                const int32_t* cand_count, const int32_t* k, int32_t* topk_idx, float* topk_score,
+                                const int32_t* seg_count, const int32_t* seg_rows, int nseg,
+                                const int32_t* cand_count, const int64_t* group_start, int64_t* line_total,
+                                const int32_t* k, int32_t* topk_idx, float* topk_score,
                                 float* thr_state, int32_t* redo_g, int32_t* redo_h, hipStream_t st) {
   const int cap = filter_list_cap(s);
   hipLaunchKernelGGL(k_filter_select, dim3(s.B * s.Hq), dim3(kFilterSelThreads), (size_t)cap * 8, st, s, score, slot_in,
-                     score_stride, seg_count, seg_rows, nseg, cand, cand_count, k, topk_idx, topk_score, thr_state, redo_g,
+                     score_stride, seg_count, seg_rows, nseg, cand_count, group_start, line_total, k, topk_idx, topk_score, thr_state, redo_g,
                      redo_h, cap);
   return hipGetLastError();
 }
