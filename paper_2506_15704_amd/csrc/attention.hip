@@ -43,7 +43,19 @@ __global__ __launch_bounds__(kSparseWaves * 64) void k_sparse_attn(Shape s, cons
                                                                 float* __restrict__ out) {
   __shared__ float red[kSparseWaves][kD];
   __shared__ float redm[kSparseWaves], redl[kSparseWaves];
-  const int bh = blockIdx.x, b = bh / s.Hq, h = bh % s.Hq, g = h / s.G;
+  // Workgroups are dealt to the 8 XCDs round-robin (workgroup i runs on XCD i % 8) and every XCD has
+  // its own L2.  The heads of a KV group select largely the same rows, so the G workgroups of a group
+  // are given ids that differ by multiples of 8: they run on one XCD at about the same time and a V
+  // row fetched for one head is an L2 hit for the others.
+  int bh = blockIdx.x;
+  {
+    const int n_kvg = s.B * s.Hkv;                 // KV groups in the launch
+    if (n_kvg % 8 == 0) {
+      const int xcd = bh & 7, slot = bh >> 3;
+      bh = ((slot / s.G) * 8 + xcd) * s.G + slot % s.G;
+    }
+  }
+  const int b = bh / s.Hq, h = bh % s.Hq, g = h / s.G;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int j = lane & 15, rs = lane >> 4;
   int n = seq_lens[b];
