@@ -1,0 +1,254 @@
+"""Pins of the score-table oracle (Eq. 4, 7-10, 12 of the paper) against things other than itself:
+a library kurtosis, closed forms, the sum invariant the paper states, geometric-series fixed points,
+per-position brute force, and the printed offset set."""
+import math
+import os
+
+import numpy as np
+import pytest
+import scipy.stats
+import torch
+
+from oracle import lfps_tables_oracle as tor
+
+GOLDEN = os.path.join(os.path.dirname(__file__), "golden")
+
+
+def _softmax_rows(x):
+    return torch.softmax(torch.from_numpy(x), dim=-1).numpy()
+
+
+# ----------------------------------------------------------------------------- Eq. 8
+@pytest.mark.parametrize("seed,n", [(0, 5), (1, 64), (2, 1000)])
+def test_kappa_is_library_kurtosis_over_n(seed, n):
+    x = np.random.default_rng(seed).gamma(0.3, size=n)
+    # Pearson kurtosis (biased) = n * sum d^4 / (sum d^2)^2
+    want = scipy.stats.kurtosis(x, fisher=False, bias=True) / n
+    assert tor.kappa(x) == pytest.approx(want, rel=1e-12)
+
+
+@pytest.mark.parametrize("n,m,v", [(100, 1, 2.0), (4096, 7, 0.3), (50, 25, 1.0)])
+def test_kappa_closed_form_for_equal_spikes(n, m, v):
+    x = np.zeros(n)
+    x[np.random.default_rng(n + m).choice(n, m, replace=False)] = v
+    p = m / n
+    want = ((1 - p) ** 3 + p ** 3) / (n * p * (1 - p))
+    assert tor.kappa(x) == pytest.approx(want, rel=1e-10)
+    # one spike in a long table: kappa -> 1, so tau -> a * mean
+    if m == 1:
+        assert tor.tau(x, 0.2) == pytest.approx(0.2 * v / n / want, rel=1e-12)
+
+
+def test_kappa_undefined_for_a_flat_table_selects_nothing():
+    x = np.full(30, 0.25)
+    assert math.isnan(tor.kappa(x))
+    assert tor.tau(x, 0.2) == float("inf")
+    assert len(tor.initial_candidates(x, x, 30, 0.2)) == 0
+
+
+def test_selection_is_invariant_under_scaling_of_the_tables():
+    rng = np.random.default_rng(5)
+    ver, sla = rng.gamma(0.2, size=300), rng.gamma(0.2, size=300)
+    c0 = tor.head_candidates(ver, sla, 300, 0.3, 2)
+    c1 = tor.head_candidates(7.5 * ver, 7.5 * sla, 300, 0.3, 2)
+    np.testing.assert_array_equal(c0, c1)
+    assert 0 < len(c0) < 300
+
+
+def test_larger_a_never_adds_initial_candidates():
+    rng = np.random.default_rng(6)
+    ver, sla = rng.gamma(0.1, size=500), rng.gamma(0.1, size=500)
+    prev = None
+    for a in (0.05, 0.1, 0.2, 0.4, 0.8):
+        c = set(tor.initial_candidates(ver, sla, 500, a).tolist())
+        if prev is not None:
+            assert c <= prev
+        prev = c
+
+
+# ----------------------------------------------------------------------------- Eq. 7 / Eq. 9 brute force
+@pytest.mark.parametrize("seed", range(5))
+def test_candidates_by_per_position_predicate(seed):
+    rng = np.random.default_rng(100 + seed)
+    n, r, a, n_sink = int(rng.integers(20, 200)), int(rng.integers(0, 4)), 0.25, int(rng.integers(0, 3))
+    ver, sla = rng.gamma(0.15, size=n + 5), rng.gamma(0.15, size=n + 5)
+    ver[:n_sink] = 0
+    sla[:n_sink] = 0
+    xv, xs = ver[n_sink:n], sla[n_sink:n]
+
+    def t(x):
+        d = x - x.mean()
+        return a * x.mean() * (d ** 2).sum() ** 2 / (d ** 4).sum()
+
+    tv, ts, mv, ms = t(xv), t(xs), xv.mean(), xs.mean()
+    in_c0 = lambda i: n_sink <= i < n and (ver[i] > tv or sla[i] > ts)
+    # gather form: j is kept iff it passes the mean test and some offset leads back to an initial candidate
+    want = [j for j in range(n_sink, n)
+            if (ver[j] > mv or sla[j] > ms) and any(in_c0(j - d) for d in range(-r, r + 2))]
+    got = tor.head_candidates(ver, sla, n, a, r, n_sink)
+    np.testing.assert_array_equal(got, np.array(want, dtype=np.int64))
+    c0 = tor.initial_candidates(ver, sla, n, a, n_sink)
+    np.testing.assert_array_equal(c0, np.array([i for i in range(n) if in_c0(i)], dtype=np.int64))
+
+
+def test_expansion_offsets_at_r1_are_the_papers():
+    offsets = [int(l) for l in open(os.path.join(GOLDEN, "expansion_offsets.txt")) if l.strip() and not l.startswith("#")]
+    n, p = 60, 30
+    ver = np.zeros(n)
+    ver[p] = 500.0                     # the one initial candidate
+    sla = np.full(n, 1.0)
+    sla[p - 4:p + 6] += 1e-3           # the neighbourhood clears the mean filter through the slash table,
+                                       # far below tau_sla = a * mean / kappa ~ 2.6
+    c0 = tor.initial_candidates(ver, sla, n, 0.2)
+    np.testing.assert_array_equal(c0, [p])
+    c1 = tor.expand(c0, ver, sla, n, 1)
+    assert sorted(int(j) - p for j in c1) == sorted(offsets)
+
+
+def test_expansion_keeps_only_positions_above_a_mean():
+    n, p = 40, 20
+    ver = np.zeros(n)
+    sla = np.zeros(n)
+    ver[p] = 10.0
+    ver[p + 1] = 1.0                   # above mean(ver) = 11/40
+    sla[p - 1] = 0.5                   # above mean(sla)
+    c1 = tor.expand(np.array([p]), ver, sla, n, 2)
+    np.testing.assert_array_equal(c1, [p - 1, p, p + 1])
+
+
+def test_group_candidates_add_recent_and_sink_rows():
+    n = 50
+    z = np.zeros(n)
+    c = tor.group_candidates([(z, z), (z, z)], n, 0.2, 1, n_recent=2, n_sink=3)
+    np.testing.assert_array_equal(c, [0, 1, 2, 48, 49])
+
+
+# ----------------------------------------------------------------------------- Eq. 4 and Eq. 12
+def test_init_tables_sum_and_diagonal_alignment():
+    rng = np.random.default_rng(9)
+    n, s, gamma = 40, 5, 0.9
+    logits = rng.standard_normal((s, n))
+    for j in range(1, s + 1):          # query n-j sees positions <= n-j
+        logits[j - 1, n - j + 1:] = -np.inf
+    w = _softmax_rows(logits)
+    ver, sla = tor.init_tables(w, gamma)
+    assert ver.sum() == pytest.approx(1 / (2 * (1 - gamma)), rel=1e-12)      # Eq. 12 / App. B.2
+    assert sla.sum() == pytest.approx(1 / (2 * (1 - gamma)), rel=1e-12)
+    # one query (s = 1): both tables are its weights over 2 (1 - gamma)
+    v1, s1 = tor.init_tables(w[:1], gamma)
+    np.testing.assert_allclose(v1, w[0] / (2 * (1 - gamma)), rtol=1e-13)
+    np.testing.assert_allclose(s1, v1, rtol=0, atol=0)
+    # a query j steps back that looked only at position p predicts p + j - 1 on the slash table
+    onehot = np.zeros((3, n))
+    onehot[2, 11] = 1.0                # j = 3
+    v3, s3 = tor.init_tables(onehot, gamma)
+    assert np.argmax(v3) == 11 and np.argmax(s3) == 13
+    assert v3[11] == pytest.approx(1 / (6 * (1 - gamma))) and s3[13] == pytest.approx(v3[11])
+
+
+@pytest.mark.parametrize("gamma", [0.0, 0.5, 0.95])
+def test_table_sums_follow_the_stated_recurrence(gamma):
+    rng = np.random.default_rng(11)
+    n = 64
+    ver, sla = rng.random(n), rng.random(n)
+    S_v, S_s = ver.sum(), sla.sum()
+    for step in range(400):
+        k = int(rng.integers(1, 20))
+        sel = rng.choice(n, k, replace=False)
+        ver, sla = tor.update_tables(ver, sla, n, sel, rng.standard_normal(k) * 3, gamma)
+        n += 1
+        S_v, S_s = gamma * S_v + 0.5, gamma * S_s + 0.5
+        assert ver.sum() == pytest.approx(S_v, rel=1e-10, abs=1e-12)
+        assert sla.sum() == pytest.approx(S_s, rel=1e-10, abs=1e-12)
+    # Eq. 12: both sums settle at 0.5 / (1 - gamma)
+    assert ver.sum() == pytest.approx(0.5 / (1 - gamma), rel=1e-6)
+    assert sla.sum() == pytest.approx(0.5 / (1 - gamma), rel=1e-6)
+
+
+def test_unselected_positions_only_decay_and_slash_moves_by_one():
+    rng = np.random.default_rng(12)
+    n, gamma = 30, 0.8
+    ver, sla = rng.random(n), rng.random(n)
+    sel = np.array([4, 17, -1])
+    nv, ns = tor.update_tables(ver, sla, n, sel, np.array([0.3, -1.0, 9.9]), gamma)
+    assert len(nv) == len(ns) == n + 1
+    others = [i for i in range(n) if i not in (4, 17)]
+    np.testing.assert_allclose(nv[others], gamma * ver[others], rtol=1e-15)
+    np.testing.assert_allclose(ns[[i for i in others if i >= 1]], gamma * sla[[i - 1 for i in others if i >= 1]], rtol=1e-15)
+    assert nv[n] == 0.0 and ns[n] == pytest.approx(gamma * sla[n - 1]) and ns[0] == 0.0
+    # the two selected positions receive softmax weight minus 1/(2*2); the padding entry is ignored
+    w = _softmax_rows(np.array([[0.3, -1.0]]))[0]
+    assert nv[4] - gamma * ver[4] == pytest.approx(w[0] - 0.25)
+    assert ns[17] - gamma * sla[16] == pytest.approx(w[1] - 0.25)
+
+
+def test_constant_selection_reaches_the_geometric_series_limit():
+    gamma, n0 = 0.7, 25
+    sel = np.array([3, 9, 10])
+    sc = np.array([1.0, 2.0, 0.5])
+    w = _softmax_rows(sc[None])[0]
+    ver, sla = np.zeros(n0), np.zeros(n0)
+    n = n0
+    for _ in range(120):
+        ver, sla = tor.update_tables(ver, sla, n, sel, sc, gamma)
+        n += 1
+    for p, wp in zip(sel, w):
+        assert ver[p] == pytest.approx((wp - 1 / 6) / (1 - gamma), rel=1e-9)
+    # slash: what position p received m steps ago now sits at p + m, decayed m times
+    d = {int(p): wp - 1 / 6 for p, wp in zip(sel, w)}
+    for i in (3, 4, 9, 10, 11, 12, 40):
+        want = sum(gamma ** m * d.get(i - m, 0.0) for m in range(0, 120))
+        assert sla[i] == pytest.approx(want, rel=1e-9, abs=1e-15)
+
+
+def test_single_hit_travels_down_the_slash_diagonal():
+    gamma, n, p = 0.9, 20, 5
+    ver, sla = tor.update_tables(np.zeros(n), np.zeros(n), n, np.array([p]), np.array([0.0]), gamma)
+    n += 1
+    for m in range(1, 8):
+        ver, sla = tor.update_tables(ver, sla, n, np.array([], dtype=np.int64), np.array([]), gamma)
+        n += 1
+        assert ver[p] == pytest.approx(0.5 * gamma ** m) and np.count_nonzero(ver) == 1
+        assert sla[p + m] == pytest.approx(0.5 * gamma ** m) and np.count_nonzero(sla) == 1
+
+
+def test_sink_positions_stay_outside_the_tables():
+    rng = np.random.default_rng(13)
+    n, gamma, n_sink = 30, 0.9, 4
+    ver, sla = rng.random(n), rng.random(n)
+    ver[:n_sink] = 0
+    sla[:n_sink] = 0
+    sel = np.array([0, 2, 10, 20])
+    sc = np.array([50.0, 40.0, 1.0, 2.0])          # the sinks would swallow the softmax
+    nv, ns = tor.update_tables(ver, sla, n, sel, sc, gamma, n_sink)
+    assert not nv[:n_sink].any() and not ns[:n_sink].any()
+    w = _softmax_rows(np.array([[1.0, 2.0]]))[0]
+    assert nv[10] - gamma * ver[10] == pytest.approx(w[0] - 0.25)
+    assert nv.sum() == pytest.approx(gamma * ver.sum() + 0.5)
+    c0 = tor.initial_candidates(np.r_[np.full(n_sink, 1e9), ver[n_sink:]], sla, n, 0.2, n_sink)
+    assert (c0 >= n_sink).all()
+
+
+# ----------------------------------------------------------------------------- one whole step
+def test_table_step_selects_the_best_candidates_and_attends_over_them():
+    rng = np.random.default_rng(14)
+    n, d, G, k = 120, 16, 2, 8
+    K, V = rng.standard_normal((n + 1, d)), rng.standard_normal((n + 1, d))
+    q = rng.standard_normal((G, d))
+    tables = []
+    for h in range(G):
+        ver, sla = rng.gamma(0.1, size=n), rng.gamma(0.1, size=n)
+        tables.append((ver, sla))
+    res = tor.table_step(q, K, V, tables, n, k, 1, 0.2, 0.95, n_recent=1, n_sink=0)
+    C = res["cand"]
+    assert n - 1 in C and len(C) == len(set(C.tolist())) and list(C) == sorted(C)
+    for h in range(G):
+        s_all = (K[:n] @ q[h]) / math.sqrt(d)
+        want = C[np.argsort(-s_all[C], kind="stable")[:k]]
+        assert set(res["topk_idx"][h].tolist()) == set(want.tolist())
+        I = torch.from_numpy(res["topk_idx"][h])
+        ref = torch.softmax(torch.from_numpy(s_all)[I], 0) @ torch.from_numpy(V)[I]
+        np.testing.assert_allclose(res["out"][h], ref.numpy(), rtol=1e-12, atol=1e-14)
+        nv, ns = res["tables"][h]
+        assert len(nv) == n + 1
+        assert nv.sum() == pytest.approx(0.95 * tables[h][0].sum() + 0.5)
