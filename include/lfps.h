@@ -62,8 +62,11 @@ typedef struct {
   int32_t radius;      /* r >= 0: positional expansion radius around each predicted position */
   int32_t n_recent;    /* the newest n_recent rows are always candidates (>= 0) */
   int32_t n_sink;      /* the first n_sink rows are always candidates (>= 0) */
-  int32_t cand_cap;    /* row length of candidate arrays; 0 = min(Lcap, G*kmax*(2r+2)+n_recent+n_sink) */
+  int32_t cand_cap;    /* row length of candidate arrays; 0 = min(Lcap, G*kmax*(2r+2)+n_recent+n_sink), or Lcap in table mode */
   int32_t device;      /* HIP device ordinal */
+  int32_t table_mode;  /* 1: also allocate the per-head score tables used by the lfps_table_* entry points */
+  float table_decay;   /* gamma of Eq. 10 (the paper's decay factor r = 0.95); table mode needs 0 < gamma < 1 */
+  float table_a;       /* a of Eq. 8 (0.2 / 0.3 in the paper); table mode needs a > 0 */
 } lfps_config;
 
 /* View of the KV cache.  Element (b, g, i, c) of K is k[b*stride_b + g*stride_h + i*stride_n + c]
@@ -147,6 +150,36 @@ int lfps_full_attn_decode(lfps_ctx* ctx, const float* q, const lfps_kv* kv, floa
 int lfps_exact_topk(lfps_ctx* ctx, const float* q, const lfps_kv* kv, const int32_t* k, int32_t* topk_idx,
                     float* topk_score, void* stream);
 
+/* ---- LFPS with score tables: the paper's own candidate rule (Sec. 4.2, Alg. 1 lines 5-9) --------------
+ * The context (created with table_mode = 1) keeps, per query head, a vertical and a slash score table over
+ * positions.  Sink rows (< n_sink) are outside the tables, as in the paper: always candidates, never
+ * counted or updated.  Radius must be <= 30.  One row is expected to be appended between steps (the
+ * statistics of a step are those of the previous update plus one new position). */
+
+/* Eq. 4 with s = 1: both tables = (softmax over rows [n_sink, n_b) of q.K/sqrt(D)) / (2 (1 - gamma)),
+ * from the one query q [B, Hq, D] (e.g. the last prefill query). */
+int lfps_tables_init(lfps_ctx* ctx, const float* q, const lfps_kv* kv, void* stream);
+/* Set / read the tables as true values per position: phi_ver, phi_sla [B, Hq, max_seq_len], rows
+ * [0, seq_lens[b]) used (fp32 in, fp64 out; entries of sink rows and rows >= n_b read as 0). */
+int lfps_tables_import(lfps_ctx* ctx, const float* phi_ver, const float* phi_sla, const int32_t* seq_lens,
+                       void* stream);
+int lfps_tables_export(lfps_ctx* ctx, double* phi_ver, double* phi_sla, const int32_t* seq_lens, void* stream);
+/* S1 in table form (Eq. 7, 8, 9): per head the positions whose vertical or slash score exceeds
+ * tau = a * mean / kappa of its table, widened by the offsets -r ... r+1 and kept where the vertical or the
+ * slash score exceeds the table mean; union over the heads of a KV group, plus the newest n_recent and
+ * the n_sink first rows.  Outputs as lfps_candidates. */
+int lfps_table_candidates(lfps_ctx* ctx, const int32_t* seq_lens, int32_t* cand, int32_t* cand_count, void* stream);
+/* Eq. 10: decay by gamma, slash history moved from i-1 to i, and on the selected positions
+ * idx[b,h,0:k_b] (scaled scores idx_score) the softmax weight over the selected set minus 1/(2|C_2|).
+ * seq_lens is the length the step saw.  Returns LFPS_ECAP after max_seq_len - 1 updates without an
+ * import or init. */
+int lfps_table_update(lfps_ctx* ctx, const int32_t* idx, const float* idx_score, const int32_t* k,
+                      const int32_t* seq_lens, void* stream);
+/* Alg. 1 lines 5-9 then Eq. 1: table candidates, exact scores over them, per-head Top-k (fewer than k_b
+ * when the candidate set is smaller: padded with -1), sparse attention, table update. */
+int lfps_table_step(lfps_ctx* ctx, const float* q, const lfps_kv* kv, const int32_t* k, int32_t* topk_idx,
+                    float* topk_score, float* out, void* stream);
+
 int lfps_set_filter(lfps_ctx* ctx, int32_t on);
 int lfps_reset_history(lfps_ctx* ctx, void* stream);
 /* Copies the candidate counts [B, Hkv] of the last lfps_step call into dst (device, int32),
@@ -174,7 +207,10 @@ enum {
   LFPS_KERNEL_HEAD_SCORE = 7,
   LFPS_KERNEL_FILTER_SCORE = 8,
   LFPS_KERNEL_FILTER_SELECT = 9,
-  LFPS_N_KERNELS = 10
+  LFPS_KERNEL_TABLE_FLAGS = 10,
+  LFPS_KERNEL_TABLE_CANDIDATES = 11,
+  LFPS_KERNEL_TABLE_UPDATE = 12,
+  LFPS_N_KERNELS = 13
 };
 #define LFPS_TIMING_MAX_LAUNCHES 4096
 int lfps_timing_enable(lfps_ctx* ctx, int32_t on);

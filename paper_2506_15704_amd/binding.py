@@ -19,7 +19,7 @@ LIB_PATH = os.path.join(_PKG, "liblfps.so")
 LFPS_F32, LFPS_BF16 = 0, 1
 LFPS_OK, LFPS_EINVAL, LFPS_ECAP, LFPS_EHIP, LFPS_ENOMEM = 0, -1, -2, -3, -4
 LFPS_FLAG_CAND_OVERFLOW = 1
-N_KERNELS = 10
+N_KERNELS = 13
 
 
 class LfpsError(RuntimeError):
@@ -31,7 +31,8 @@ class LfpsError(RuntimeError):
 class lfps_config(ctypes.Structure):
     _fields_ = [(n, ctypes.c_int32) for n in (
         "batch", "n_q_heads", "n_kv_heads", "head_dim", "kv_dtype", "max_seq_len", "max_k",
-        "radius", "n_recent", "n_sink", "cand_cap", "device")]
+        "radius", "n_recent", "n_sink", "cand_cap", "device", "table_mode")] + [
+        ("table_decay", ctypes.c_float), ("table_a", ctypes.c_float)]
 
 
 class lfps_kv(ctypes.Structure):
@@ -67,6 +68,12 @@ def _load() -> ctypes.CDLL:
         "lfps_set_filter": (ctypes.c_int, [P, I32]),
         "lfps_reset_history": (ctypes.c_int, [P, VP]),
         "lfps_copy_cand_count": (ctypes.c_int, [P, VP, VP]),
+        "lfps_tables_init": (ctypes.c_int, [P, VP, ctypes.POINTER(lfps_kv), VP]),
+        "lfps_tables_import": (ctypes.c_int, [P, VP, VP, VP, VP]),
+        "lfps_tables_export": (ctypes.c_int, [P, VP, VP, VP, VP]),
+        "lfps_table_candidates": (ctypes.c_int, [P, VP, VP, VP, VP]),
+        "lfps_table_update": (ctypes.c_int, [P, VP, VP, VP, VP, VP]),
+        "lfps_table_step": (ctypes.c_int, [P, VP, ctypes.POINTER(lfps_kv), VP, VP, VP, VP, VP]),
     }
     for name, (res, args) in sig.items():
         fn = getattr(lib, name)
@@ -121,10 +128,12 @@ class Lfps:
 
     def __init__(self, batch: int, n_q_heads: int = 32, n_kv_heads: int = 8, head_dim: int = 128,
                  kv_dtype: str = "bf16", max_seq_len: int = 0, max_k: int = 0, radius: int = 0,
-                 n_recent: int = 1, n_sink: int = 0, cand_cap: int = 0, device: int = 0):
+                 n_recent: int = 1, n_sink: int = 0, cand_cap: int = 0, device: int = 0,
+                 table_mode: bool = False, table_decay: float = 0.95, table_a: float = 0.2):
         self.cfg = lfps_config(batch, n_q_heads, n_kv_heads, head_dim,
                                LFPS_BF16 if kv_dtype == "bf16" else LFPS_F32, max_seq_len, max_k,
-                               radius, n_recent, n_sink, cand_cap, device)
+                               radius, n_recent, n_sink, cand_cap, device, int(bool(table_mode)),
+                               float(table_decay), float(table_a))
         self.kv_torch_dtype = torch.bfloat16 if kv_dtype == "bf16" else torch.float32
         self.device = torch.device("cuda", device)
         self._ctx = ctypes.c_void_p(None)
@@ -225,6 +234,48 @@ class Lfps:
             _ptr(k, torch.int32, (self.B,), "k", d),
             _ptr(topk_idx, torch.int32, (self.B, self.Hq, self.kmax), "topk_idx", d),
             _ptr(topk_score, torch.float32, (self.B, self.Hq, self.kmax), "topk_score", d), self._stream()))
+
+    # ------------------------------------------------------------------ score tables
+    def lfps_tables_init(self, q, kv: lfps_kv):
+        self._check(_lib.lfps_tables_init(
+            self._ctx, _ptr(q, torch.float32, (self.B, self.Hq, self.D), "q", self.device), ctypes.byref(kv),
+            self._stream()))
+
+    def lfps_tables_import(self, phi_ver, phi_sla, seq_lens):
+        d, shp = self.device, (self.B, self.Hq, self.Lcap)
+        self._check(_lib.lfps_tables_import(
+            self._ctx, _ptr(phi_ver, torch.float32, shp, "phi_ver", d), _ptr(phi_sla, torch.float32, shp, "phi_sla", d),
+            _ptr(seq_lens, torch.int32, (self.B,), "seq_lens", d), self._stream()))
+
+    def lfps_tables_export(self, phi_ver, phi_sla, seq_lens):
+        d, shp = self.device, (self.B, self.Hq, self.Lcap)
+        self._check(_lib.lfps_tables_export(
+            self._ctx, _ptr(phi_ver, torch.float64, shp, "phi_ver", d), _ptr(phi_sla, torch.float64, shp, "phi_sla", d),
+            _ptr(seq_lens, torch.int32, (self.B,), "seq_lens", d), self._stream()))
+
+    def lfps_table_candidates(self, seq_lens, cand, cand_count):
+        d = self.device
+        self._check(_lib.lfps_table_candidates(
+            self._ctx, _ptr(seq_lens, torch.int32, (self.B,), "seq_lens", d),
+            _ptr(cand, torch.int32, (self.B, self.Hkv, self.cand_cap), "cand", d),
+            _ptr(cand_count, torch.int32, (self.B, self.Hkv), "cand_count", d), self._stream()))
+
+    def lfps_table_update(self, idx, idx_score, k, seq_lens):
+        d = self.device
+        self._check(_lib.lfps_table_update(
+            self._ctx, _ptr(idx, torch.int32, (self.B, self.Hq, self.kmax), "idx", d),
+            _ptr(idx_score, torch.float32, (self.B, self.Hq, self.kmax), "idx_score", d),
+            _ptr(k, torch.int32, (self.B,), "k", d), _ptr(seq_lens, torch.int32, (self.B,), "seq_lens", d),
+            self._stream()))
+
+    def lfps_table_step(self, q, kv: lfps_kv, k, topk_idx, out, topk_score=None):
+        d = self.device
+        self._check(_lib.lfps_table_step(
+            self._ctx, _ptr(q, torch.float32, (self.B, self.Hq, self.D), "q", d), ctypes.byref(kv),
+            _ptr(k, torch.int32, (self.B,), "k", d),
+            _ptr(topk_idx, torch.int32, (self.B, self.Hq, self.kmax), "topk_idx", d),
+            _ptr(topk_score, torch.float32, (self.B, self.Hq, self.kmax), "topk_score", d),
+            _ptr(out, torch.float32, (self.B, self.Hq, self.D), "out", d), self._stream()))
 
     def lfps_set_filter(self, on: bool):
         self._check(_lib.lfps_set_filter(self._ctx, int(bool(on))))

@@ -25,6 +25,88 @@ __device__ __forceinline__ void set_bit_range(uint32_t* bm, int lo, int hi) {  /
   }
 }
 
+// Emits the set bits of the LDS bitmap bm[0:W] as ascending positions into cand[bg, :] and leaves the
+// count in cand_count[bg] (truncated to cand_cap with the overflow flag raised).  All threads of the
+// workgroup call it after a barrier that follows the last write to the bitmap.  Emission goes in rounds
+// of 64 consecutive words, one round per wave at a time: (a) set bits per round, (b) exclusive offsets
+// of the rounds by a block scan, (c) per round every lane expands its word into a wave-private LDS
+// stage at the lane's offset within the round, then the wave copies the stage out with consecutive
+// lanes writing consecutive entries.  `part` of `nparts` workgroups that share the group emit every
+// nparts-th round.  Returns the group's total (untruncated) to every thread.
+__device__ __forceinline__ int emit_bitmap(const Shape& s, const uint32_t* bm, int W, uint32_t* rcnt, uint16_t* stage,
+                                           int* wave_tot, int bg, int part, int nparts, int32_t* __restrict__ cand,
+                                           int32_t* __restrict__ cand_count, int32_t* __restrict__ flags) {
+  const int tid = threadIdx.x;
+  const int lane = tid & 63, wv = tid >> 6;
+  const int nr = (W + 63) >> 6;                                  // rounds (<= kCandThreads, checked at creation)
+  for (int r_ = wv; r_ < nr; r_ += kCandThreads / 64) {
+    const int w = r_ * 64 + lane;
+    int c_ = w < W ? __popc(bm[w]) : 0;
+#pragma unroll
+    for (int d = 1; d < 64; d <<= 1) c_ += __shfl_xor(c_, d);
+    if (lane == 0) rcnt[r_] = (uint32_t)c_;
+  }
+  __syncthreads();
+  int cnt = tid < nr ? (int)rcnt[tid] : 0;
+  int inc = cnt;
+#pragma unroll
+  for (int d = 1; d < 64; d <<= 1) {
+    int o = __shfl_up(inc, d);
+    if (lane >= d) inc += o;
+  }
+  if (lane == 63) wave_tot[wv] = inc;
+  __syncthreads();
+  int base = 0, total = 0;
+#pragma unroll
+  for (int i = 0; i < kCandThreads / 64; ++i) {
+    int t = wave_tot[i];
+    if (i < wv) base += t;
+    total += t;
+  }
+  if (tid < nr) rcnt[tid] = (uint32_t)(base + inc - cnt);        // now the exclusive offset of round tid
+  __syncthreads();
+
+  int32_t* out = cand + (int64_t)bg * s.cand_cap;
+  uint16_t* st = stage + wv * 2048;
+  for (int r_ = wv * nparts + part; r_ < nr; r_ += (kCandThreads / 64) * nparts) {
+    const int w = r_ * 64 + lane;
+    uint32_t bits = w < W ? bm[w] : 0u;
+    const int c_ = __popc(bits);
+    int incl = c_;
+#pragma unroll
+    for (int d = 1; d < 64; d <<= 1) {
+      int o = __shfl_up(incl, d);
+      if (lane >= d) incl += o;
+    }
+    const int tot = __shfl(incl, 63);
+    int o_ = incl - c_;
+    while (bits) {
+      const int p = __ffs(bits) - 1;
+      bits &= bits - 1;
+      st[o_++] = (uint16_t)((lane << 5) | p);
+    }
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+    const int ro = (int)rcnt[r_];
+    for (int e = lane; e < tot; e += 64) {
+      const uint32_t v = st[e];
+      if (ro + e < s.cand_cap) out[ro + e] = (((r_ << 6) + (int)(v >> 5)) << 5) + (int)(v & 31u);
+    }
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+  }
+  if (tid == 0 && part == 0) {
+    int kept = total;
+    if (kept > s.cand_cap) {
+      atomicOr(flags, LFPS_FLAG_CAND_OVERFLOW);
+      kept = s.cand_cap;
+    }
+    cand_count[bg] = kept;
+  }
+  return total;
+}
+
 // Dynamic LDS: bitmap words [ceil(Lcap/32)], round counts/offsets [ceil(words/64)], then a
 // 4 KB stage per wave (64 words x 32 bits as 16-bit (word-in-round, bit) codes).
 __global__ __launch_bounds__(kCandThreads) void k_candidates(Shape s, const int32_t* __restrict__ prev_topk,
@@ -110,79 +192,59 @@ __global__ __launch_bounds__(kCandThreads) void k_candidates(Shape s, const int3
   }
   __syncthreads();
 
-  // Emit in rounds of 64 consecutive words, one round per wave at a time.
-  // (a) set bits per round, (b) exclusive offsets of the rounds by a block scan, (c) per round:
-  // every lane expands its word into a wave-private LDS stage at the lane's offset within the
-  // round, then the wave copies the stage out with consecutive lanes writing consecutive entries.
-  const int lane = tid & 63, wv = tid >> 6;
-  const int nr = (W + 63) >> 6;                                  // rounds (<= kCandThreads, checked at creation)
-  for (int r_ = wv; r_ < nr; r_ += kCandThreads / 64) {
-    const int w = r_ * 64 + lane;
-    int c_ = w < W ? __popc(bm[w]) : 0;
-#pragma unroll
-    for (int d = 1; d < 64; d <<= 1) c_ += __shfl_xor(c_, d);
-    if (lane == 0) rcnt[r_] = (uint32_t)c_;
+  const int total = emit_bitmap(s, bm, W, rcnt, stage, wave_tot, bg, part, nparts, cand, cand_count, flags);
+  // the group's place on the line of all candidate slots that the filtered scoring pass cuts into
+  // equal parts (the caller has left *line_total at zero)
+  if (tid == 0 && part == 0 && group_start) {
+    const int kept = total > s.cand_cap ? s.cand_cap : total;
+    group_start[bg] = (int64_t)atomicAdd(line_total, (unsigned long long)kept);
   }
-  __syncthreads();
-  int cnt = tid < nr ? (int)rcnt[tid] : 0;
-  int inc = cnt;
-#pragma unroll
-  for (int d = 1; d < 64; d <<= 1) {
-    int o = __shfl_up(inc, d);
-    if (lane >= d) inc += o;
-  }
-  if (lane == 63) wave_tot[wv] = inc;
-  __syncthreads();
-  int base = 0, total = 0;
-#pragma unroll
-  for (int i = 0; i < kCandThreads / 64; ++i) {
-    int t = wave_tot[i];
-    if (i < wv) base += t;
-    total += t;
-  }
-  if (tid < nr) rcnt[tid] = (uint32_t)(base + inc - cnt);        // now the exclusive offset of round tid
-  __syncthreads();
+}
 
-  int32_t* out = cand + (int64_t)bg * s.cand_cap;
-  uint16_t* st = stage + wv * 2048;
-  for (int r_ = wv * nparts + part; r_ < nr; r_ += (kCandThreads / 64) * nparts) {
-    const int w = r_ * 64 + lane;
-    uint32_t bits = w < W ? bm[w] : 0u;
-    const int c_ = __popc(bits);
-    int incl = c_;
-#pragma unroll
-    for (int d = 1; d < 64; d <<= 1) {
-      int o = __shfl_up(incl, d);
-      if (lane >= d) incl += o;
+// ----------------------------------------------------------------------------- score-table form
+// Candidate set of one (request, KV group) from the per-head flag bitmaps that the table scan left
+// (Eq. 7 and Eq. 9): f0 marks the initial candidates of a head (a table entry above its kurtosis
+// threshold), fm the positions whose vertical or slash score exceeds the table mean.  For every
+// head the initial candidates are widened by the offsets -r ... r+1 (bit shifts across word
+// boundaries) and masked with fm; the heads are OR-ed; the newest and the sink rows are added.
+__global__ __launch_bounds__(kCandThreads) void k_table_candidates(Shape s, const uint32_t* __restrict__ f0,
+                                                                   const uint32_t* __restrict__ fm, int flag_words,
+                                                                   const int32_t* __restrict__ seq_lens,
+                                                                   int32_t* __restrict__ cand,
+                                                                   int32_t* __restrict__ cand_count,
+                                                                   int32_t* __restrict__ flags) {
+  extern __shared__ uint32_t lds[];
+  __shared__ int wave_tot[kCandThreads / 64];
+  const int bg = blockIdx.y, b = bg / s.Hkv, g = bg % s.Hkv;
+  const int part = blockIdx.x, nparts = gridDim.x;
+  const int tid = threadIdx.x;
+  int n = seq_lens[b];
+  n = n < 0 ? 0 : (n > s.Lcap ? s.Lcap : n);
+  const int W = (n + 31) >> 5;
+  uint32_t* bm = lds;
+  const int words_cap = (s.Lcap + 31) >> 5;
+  uint32_t* rcnt = lds + words_cap;
+  uint16_t* stage = reinterpret_cast<uint16_t*>(rcnt + ((words_cap + 63) >> 6));
+  const int r = s.radius;
+  for (int w = tid; w < W; w += kCandThreads) {
+    uint32_t acc = 0u;
+    for (int h = 0; h < s.G; ++h) {
+      const int64_t row = ((int64_t)b * s.Hq + (int64_t)g * s.G + h) * flag_words;
+      const uint32_t lo = w > 0 ? f0[row + w - 1] : 0u, mid = f0[row + w], hi = w + 1 < W ? f0[row + w + 1] : 0u;
+      uint32_t d = mid;
+      for (int e = 1; e <= r + 1; ++e) d |= (mid << e) | (lo >> (32 - e));      // j = i + e
+      for (int e = 1; e <= r; ++e) d |= (mid >> e) | (hi << (32 - e));           // j = i - e
+      acc |= d & fm[row + w];
     }
-    const int tot = __shfl(incl, 63);
-    int o_ = incl - c_;
-    while (bits) {
-      const int p = __ffs(bits) - 1;
-      bits &= bits - 1;
-      st[o_++] = (uint16_t)((lane << 5) | p);
-    }
-    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-    __builtin_amdgcn_wave_barrier();
-    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
-    const int ro = (int)rcnt[r_];
-    for (int e = lane; e < tot; e += 64) {
-      const uint32_t v = st[e];
-      if (ro + e < s.cand_cap) out[ro + e] = (((r_ << 6) + (int)(v >> 5)) << 5) + (int)(v & 31u);
-    }
-    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-    __builtin_amdgcn_wave_barrier();
+    bm[w] = acc;
   }
-  if (tid == 0 && part == 0) {
-    if (total > s.cand_cap) {
-      atomicOr(flags, LFPS_FLAG_CAND_OVERFLOW);
-      total = s.cand_cap;
-    }
-    cand_count[bg] = total;
-    // the group's place on the line of all candidate slots that the filtered scoring pass cuts into
-    // equal parts (the caller has left *line_total at zero)
-    if (group_start) group_start[bg] = (int64_t)atomicAdd(line_total, (unsigned long long)total);
+  __syncthreads();
+  if (tid == 0 && n > 0) {
+    if (s.n_recent > 0) set_bit_range(bm, n - s.n_recent < 0 ? 0 : n - s.n_recent, n - 1);
+    if (s.n_sink > 0) set_bit_range(bm, 0, (s.n_sink > n ? n : s.n_sink) - 1);
   }
+  __syncthreads();
+  emit_bitmap(s, bm, W, rcnt, stage, wave_tot, bg, part, nparts, cand, cand_count, flags);
 }
 
 static size_t candidates_lds_bytes(const Shape& s) {
@@ -194,8 +256,11 @@ static size_t candidates_lds_bytes(const Shape& s) {
 // the longest sequence needs more than the default 64 KB.
 hipError_t configure_candidates(const Shape& s) {
   const size_t lds_bytes = candidates_lds_bytes(s);
-  if (lds_bytes > 32 * 1024)
-    return hipFuncSetAttribute((const void*)k_candidates, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes);
+  if (lds_bytes > 32 * 1024) {
+    hipError_t e = hipFuncSetAttribute((const void*)k_candidates, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes);
+    if (e != hipSuccess) return e;
+    return hipFuncSetAttribute((const void*)k_table_candidates, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes);
+  }
   return hipSuccess;
 }
 
@@ -207,6 +272,16 @@ hipError_t launch_candidates(const Shape& s, const int32_t* prev_topk, const int
   hipLaunchKernelGGL(k_candidates, dim3(nparts, s.B * s.Hkv), dim3(kCandThreads), candidates_lds_bytes(s), st, s,
                      prev_topk, k, seq_lens, cand, cand_count, flags, redo_g, redo_h, group_start,
                      reinterpret_cast<unsigned long long*>(line_total));
+  return hipGetLastError();
+}
+
+hipError_t launch_table_candidates(const Shape& s, const uint32_t* f0, const uint32_t* fm, int flag_words,
+                                   const int32_t* seq_lens, int32_t* cand, int32_t* cand_count, int32_t* flags,
+                                   hipStream_t st) {
+  int nparts = 256 / (s.B * s.Hkv);
+  nparts = nparts < 1 ? 1 : (nparts > 8 ? 8 : nparts);
+  hipLaunchKernelGGL(k_table_candidates, dim3(nparts, s.B * s.Hkv), dim3(kCandThreads), candidates_lds_bytes(s), st, s,
+                     f0, fm, flag_words, seq_lens, cand, cand_count, flags);
   return hipGetLastError();
 }
 

@@ -24,6 +24,16 @@ struct lfps_ctx {
   int32_t* redo_g;     // [B, Hkv]
   int32_t* redo_h;     // [B, Hq]
   int64_t* group_start; // [B, Hkv] place of each group on the line of all candidate slots; [B*Hkv] = the line's length
+  // score tables (table_mode)
+  float* tab_ver;      // [B, Hq, Lcap]
+  float* tab_sla;      // [B, Hq, 2*Lcap]
+  double* tab_state;   // [B, Hq, kTableStateDoubles]
+  uint32_t* tab_f0;    // [B, Hq, flag_words]
+  uint32_t* tab_fm;    // [B, Hq, flag_words]
+  int flag_words;
+  double tab_scale;    // host copy of the tables' scale factor (all heads share it): decides when to fold it back
+  int tab_updates;     // updates since the last import / init
+  int tab_ready;
   int32_t* cand;       // [B, Hkv, cand_cap]
   int32_t* cand_count; // [B, Hkv]
   float* sel_score;    // [B, Hq, kmax]
@@ -43,7 +53,8 @@ static thread_local char g_create_err[512] = "";
 
 static const char* const kKernelNames[LFPS_N_KERNELS] = {
     "candidates", "gather_score", "select", "sparse_attn",
-    "dense_score", "full_attn", "full_merge", "head_score", "filter_score", "filter_select"};
+    "dense_score", "full_attn", "full_merge", "head_score", "filter_score", "filter_select",
+    "table_flags", "table_candidates", "table_update"};
 
 // Margin below the previous step's k-th best score at which the filtered pass keeps a row.
 static const float kFilterMargin = 0.125f;
@@ -51,8 +62,8 @@ static const float kFilterMargin = 0.125f;
 namespace {
 
 struct Sizes {
-  int32_t G, cand_cap, score_stride, n_split_full, nseg;
-  int64_t score_b, cand_b, count_b, sel_b, part_b, slot_b, seg_b, thr_b, redo_b, total;
+  int32_t G, cand_cap, score_stride, n_split_full, nseg, flag_words;
+  int64_t score_b, cand_b, count_b, sel_b, part_b, slot_b, seg_b, thr_b, redo_b, tver_b, tsla_b, tstate_b, tflag_b, total;
 };
 
 int64_t align256(int64_t x) { return (x + 255) & ~(int64_t)255; }
@@ -76,6 +87,12 @@ int check_config(const lfps_config* c, Sizes* z, char* err, size_t errn) {
   if (c->radius < 0 || c->n_recent < 0 || c->n_sink < 0) BAD("radius, n_recent, n_sink must be >= 0");
   if (c->cand_cap < 0) BAD("cand_cap must be >= 0");
   if (c->device < 0) BAD("device must be >= 0");
+  if (c->table_mode != 0 && c->table_mode != 1) BAD("table_mode must be 0 or 1");
+  if (c->table_mode) {
+    if (!(c->table_decay > 0.f && c->table_decay < 1.f)) BAD("table_decay must lie in (0, 1) (got %g)", c->table_decay);
+    if (!(c->table_a > 0.f)) BAD("table_a must be > 0 (got %g)", c->table_a);
+    if (c->radius > 30) BAD("table mode supports radius <= 30 (got %d)", c->radius);
+  }
 #undef BAD
   // LDS of the candidate kernel: one bit per position beside 64 KB of staging, 160 KB per workgroup
   if (((int64_t)c->max_seq_len + 31) / 32 * 4 > 88 * 1024) {
@@ -86,6 +103,7 @@ int check_config(const lfps_config* c, Sizes* z, char* err, size_t errn) {
   int64_t bound = (int64_t)G * c->max_k * (2 * (int64_t)c->radius + 2) + c->n_recent + c->n_sink;
   if (bound > c->max_seq_len) bound = c->max_seq_len;
   z->G = G;
+  if (c->table_mode) bound = c->max_seq_len;      // table candidates are not bounded by the budget
   z->cand_cap = c->cand_cap > 0 ? c->cand_cap : (int32_t)bound;
   if (z->cand_cap > c->max_seq_len) z->cand_cap = c->max_seq_len;
   z->score_stride = (c->max_seq_len + 63) & ~63;    // holds candidate scores and dense scores
@@ -105,8 +123,14 @@ int check_config(const lfps_config* c, Sizes* z, char* err, size_t errn) {
   z->thr_b = align256((int64_t)c->batch * c->n_q_heads * 4);
   z->redo_b = align256((int64_t)c->batch * (c->n_q_heads + c->n_kv_heads) * 4) +
               align256(((int64_t)c->batch * c->n_kv_heads + 1) * 8);   // + group_start and the line's length
+  z->flag_words = ((c->max_seq_len + 63) / 64) * 2 + 2;
+  const int64_t heads = (int64_t)c->batch * c->n_q_heads;
+  z->tver_b = c->table_mode ? align256(heads * c->max_seq_len * 4) : 0;
+  z->tsla_b = c->table_mode ? align256(heads * c->max_seq_len * 8) : 0;
+  z->tstate_b = c->table_mode ? align256(heads * kTableStateDoubles * 8) : 0;
+  z->tflag_b = c->table_mode ? align256(heads * z->flag_words * 4) : 0;
   z->total = z->score_b + z->cand_b + z->count_b + z->sel_b + z->part_b + z->slot_b + z->seg_b + z->thr_b +
-             z->redo_b + 256;
+             z->redo_b + 256 + z->tver_b + z->tsla_b + z->tstate_b + 2 * z->tflag_b;
   return LFPS_OK;
 }
 
@@ -241,11 +265,27 @@ int lfps_create(const lfps_config* cfg, lfps_ctx** out) {
   c->group_start = (int64_t*)(p + align256((int64_t)cfg->batch * (cfg->n_q_heads + cfg->n_kv_heads) * 4));
   p += z.redo_b;
   c->flags = (int32_t*)p;
+  p += 256;
+  if (cfg->table_mode) {
+    c->tab_ver = (float*)p;
+    p += z.tver_b;
+    c->tab_sla = (float*)p;
+    p += z.tsla_b;
+    c->tab_state = (double*)p;
+    p += z.tstate_b;
+    c->tab_f0 = (uint32_t*)p;
+    p += z.tflag_b;
+    c->tab_fm = (uint32_t*)p;
+    c->flag_words = z.flag_words;
+    c->tab_scale = 1.0;
+  }
   c->nseg = z.nseg;
   c->filter_on = z.slot_b ? 1 : 0;
   e = hipMemset(c->flags, 0, 256);
   if (e == hipSuccess) e = hipMemset(c->seg_count, 0, (size_t)(z.seg_b + z.thr_b + z.redo_b));   // counts, marks, line length
   if (e == hipSuccess) e = hipMemset(c->thr_state, 0xFF, (size_t)z.thr_b);   // all-ones = NaN: "no history"
+  if (e == hipSuccess && cfg->table_mode)
+    e = hipMemset(c->tab_ver, 0, (size_t)(z.tver_b + z.tsla_b + z.tstate_b + 2 * z.tflag_b));
   if (e == hipSuccess) e = configure_candidates(s);
   if (e == hipSuccess) e = configure_select(s);
   if (e == hipSuccess && c->filter_on) e = filter_score_blocks(s, &c->filter_blocks);
@@ -402,6 +442,138 @@ int lfps_exact_topk(lfps_ctx* ctx, const float* q, const lfps_kv* kv, const int3
          launch_select(s, ctx->score, s.score_stride, nullptr, v.seq_lens, k, topk_idx, topk_score, nullptr, nullptr,
                        st));
   return LFPS_OK;
+}
+
+// ---------------------------------------------------------------------------- score tables
+static int need_tables(lfps_ctx* ctx, const char* who, bool ready) {
+  if (!ctx->tab_ver) {
+    snprintf(ctx->err, sizeof ctx->err, "%s: the context was created without table_mode", who);
+    return LFPS_EINVAL;
+  }
+  if (ready && !ctx->tab_ready) {
+    snprintf(ctx->err, sizeof ctx->err, "%s: the tables hold nothing yet (lfps_tables_init or lfps_tables_import first)", who);
+    return LFPS_EINVAL;
+  }
+  return LFPS_OK;
+}
+
+int lfps_tables_init(lfps_ctx* ctx, const float* q, const lfps_kv* kv, void* stream) {
+  if (!ctx) return LFPS_EINVAL;
+  if (!q) return fail(ctx, LFPS_EINVAL, "lfps_tables_init: NULL argument");
+  int rc = need_tables(ctx, "lfps_tables_init", false);
+  if (rc != LFPS_OK) return rc;
+  KvView v;
+  rc = check_kv(ctx, kv, false, &v);
+  if (rc != LFPS_OK) return rc;
+  hipStream_t st = (hipStream_t)stream;
+  const Shape& s = ctx->shape;
+  LAUNCH(ctx, LFPS_KERNEL_DENSE_SCORE, st,
+         launch_group_score(s, ctx->cfg.kv_dtype, q, v, nullptr, nullptr, ctx->score, s.score_stride, nullptr, st));
+  hipError_t e = launch_table_init(s, ctx->tab_ver, ctx->tab_sla, ctx->tab_state, v.seq_lens, ctx->score,
+                                   s.score_stride, (double)ctx->cfg.table_decay, (double)ctx->cfg.table_a, st);
+  if (e != hipSuccess) return fail(ctx, LFPS_EHIP, "lfps_tables_init", e);
+  ctx->tab_scale = 1.0;
+  ctx->tab_updates = 0;
+  ctx->tab_ready = 1;
+  return LFPS_OK;
+}
+
+int lfps_tables_import(lfps_ctx* ctx, const float* phi_ver, const float* phi_sla, const int32_t* seq_lens,
+                       void* stream) {
+  if (!ctx) return LFPS_EINVAL;
+  if (!phi_ver || !phi_sla || !seq_lens) return fail(ctx, LFPS_EINVAL, "lfps_tables_import: NULL argument");
+  int rc = need_tables(ctx, "lfps_tables_import", false);
+  if (rc != LFPS_OK) return rc;
+  hipError_t e = launch_table_import(ctx->shape, ctx->tab_ver, ctx->tab_sla, ctx->tab_state, seq_lens, phi_ver,
+                                     phi_sla, (double)ctx->cfg.table_a, (hipStream_t)stream);
+  if (e != hipSuccess) return fail(ctx, LFPS_EHIP, "lfps_tables_import", e);
+  ctx->tab_scale = 1.0;
+  ctx->tab_updates = 0;
+  ctx->tab_ready = 1;
+  return LFPS_OK;
+}
+
+int lfps_tables_export(lfps_ctx* ctx, double* phi_ver, double* phi_sla, const int32_t* seq_lens, void* stream) {
+  if (!ctx) return LFPS_EINVAL;
+  if (!phi_ver || !phi_sla || !seq_lens) return fail(ctx, LFPS_EINVAL, "lfps_tables_export: NULL argument");
+  int rc = need_tables(ctx, "lfps_tables_export", true);
+  if (rc != LFPS_OK) return rc;
+  hipError_t e = launch_table_export(ctx->shape, ctx->tab_ver, ctx->tab_sla, ctx->tab_state, seq_lens, phi_ver,
+                                     phi_sla, (hipStream_t)stream);
+  if (e != hipSuccess) return fail(ctx, LFPS_EHIP, "lfps_tables_export", e);
+  return LFPS_OK;
+}
+
+static int table_candidates_impl(lfps_ctx* ctx, const int32_t* seq_lens, int32_t* cand, int32_t* cand_count,
+                                 hipStream_t st) {
+  const Shape& s = ctx->shape;
+  if (ctx->tab_scale < 1e-20) {          // fold the accumulated decay back into the stored entries
+    hipError_t e = launch_table_renorm(s, ctx->tab_ver, ctx->tab_sla, ctx->tab_state, st);
+    if (e != hipSuccess) return fail(ctx, LFPS_EHIP, "table renormalisation", e);
+    ctx->tab_scale = 1.0;
+  }
+  LAUNCH(ctx, LFPS_KERNEL_TABLE_FLAGS, st,
+         launch_table_flags(s, ctx->tab_ver, ctx->tab_sla, ctx->tab_state, seq_lens, ctx->tab_f0, ctx->tab_fm,
+                            ctx->flag_words, st));
+  LAUNCH(ctx, LFPS_KERNEL_TABLE_CANDIDATES, st,
+         launch_table_candidates(s, ctx->tab_f0, ctx->tab_fm, ctx->flag_words, seq_lens, cand, cand_count, ctx->flags,
+                                 st));
+  return LFPS_OK;
+}
+
+static int table_update_impl(lfps_ctx* ctx, const int32_t* idx, const float* idx_score, const int32_t* k,
+                             const int32_t* seq_lens, hipStream_t st) {
+  const Shape& s = ctx->shape;
+  if (ctx->tab_updates >= s.Lcap - 1)
+    return fail(ctx, LFPS_ECAP, "lfps_table_update: max_seq_len - 1 updates since the last import/init");
+  LAUNCH(ctx, LFPS_KERNEL_TABLE_UPDATE, st,
+         launch_table_update(s, ctx->tab_ver, ctx->tab_sla, ctx->tab_state, seq_lens, idx, idx_score, k,
+                             (double)ctx->cfg.table_decay, (double)ctx->cfg.table_a, st));
+  ctx->tab_scale *= (double)ctx->cfg.table_decay;
+  ctx->tab_updates += 1;
+  return LFPS_OK;
+}
+
+int lfps_table_candidates(lfps_ctx* ctx, const int32_t* seq_lens, int32_t* cand, int32_t* cand_count, void* stream) {
+  if (!ctx) return LFPS_EINVAL;
+  if (!seq_lens || !cand || !cand_count) return fail(ctx, LFPS_EINVAL, "lfps_table_candidates: NULL argument");
+  int rc = need_tables(ctx, "lfps_table_candidates", true);
+  if (rc != LFPS_OK) return rc;
+  return table_candidates_impl(ctx, seq_lens, cand, cand_count, (hipStream_t)stream);
+}
+
+int lfps_table_update(lfps_ctx* ctx, const int32_t* idx, const float* idx_score, const int32_t* k,
+                      const int32_t* seq_lens, void* stream) {
+  if (!ctx) return LFPS_EINVAL;
+  if (!idx || !idx_score || !k || !seq_lens) return fail(ctx, LFPS_EINVAL, "lfps_table_update: NULL argument");
+  int rc = need_tables(ctx, "lfps_table_update", true);
+  if (rc != LFPS_OK) return rc;
+  return table_update_impl(ctx, idx, idx_score, k, seq_lens, (hipStream_t)stream);
+}
+
+int lfps_table_step(lfps_ctx* ctx, const float* q, const lfps_kv* kv, const int32_t* k, int32_t* topk_idx,
+                    float* topk_score, float* out, void* stream) {
+  if (!ctx) return LFPS_EINVAL;
+  if (!q || !k || !topk_idx || !out) return fail(ctx, LFPS_EINVAL, "lfps_table_step: NULL argument");
+  int rc = need_tables(ctx, "lfps_table_step", true);
+  if (rc != LFPS_OK) return rc;
+  KvView v;
+  rc = check_kv(ctx, kv, true, &v);
+  if (rc != LFPS_OK) return rc;
+  hipStream_t st = (hipStream_t)stream;
+  const Shape& s = ctx->shape;
+  float* sel = topk_score ? topk_score : ctx->sel_score;
+  rc = table_candidates_impl(ctx, v.seq_lens, ctx->cand, ctx->cand_count, st);
+  if (rc != LFPS_OK) return rc;
+  // the candidate sets are a few per cent of the rows: every score is written and the general select runs
+  LAUNCH(ctx, LFPS_KERNEL_GATHER_SCORE, st,
+         launch_group_score(s, ctx->cfg.kv_dtype, q, v, ctx->cand, ctx->cand_count, ctx->score, s.score_stride,
+                            nullptr, st));
+  LAUNCH(ctx, LFPS_KERNEL_SELECT, st,
+         launch_select(s, ctx->score, s.score_stride, ctx->cand, ctx->cand_count, k, topk_idx, sel, nullptr, nullptr,
+                       st));
+  LAUNCH(ctx, LFPS_KERNEL_SPARSE_ATTN, st, launch_sparse_attn(s, ctx->cfg.kv_dtype, v, topk_idx, sel, k, out, st));
+  return table_update_impl(ctx, topk_idx, sel, k, v.seq_lens, st);
 }
 
 __global__ void k_fill_f32(float* p, int n, float v) {

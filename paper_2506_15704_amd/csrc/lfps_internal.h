@@ -89,6 +89,25 @@ hipError_t launch_full_attn(const Shape& s, int dtype, const float* q, const KvV
 hipError_t launch_full_merge(const Shape& s, const int32_t* seq_lens, const float* part, int n_split, float* out,
                              hipStream_t st);
 
+// Score tables (Eq. 4, 7-10): see tables.hip.  tab_ver [B*Hq, Lcap], tab_sla [B*Hq, 2*Lcap] unscaled fp32
+// entries; state [B*Hq, kTableStateDoubles]; f0 / fm [B*Hq, flag_words] bitmaps written by the scan.
+constexpr int kTableStateDoubles = 16;
+hipError_t launch_table_flags(const Shape& s, const float* tab_ver, const float* tab_sla, const double* state,
+                              const int32_t* seq_lens, uint32_t* f0, uint32_t* fm, int flag_words, hipStream_t st);
+hipError_t launch_table_candidates(const Shape& s, const uint32_t* f0, const uint32_t* fm, int flag_words,
+                                   const int32_t* seq_lens, int32_t* cand, int32_t* cand_count, int32_t* flags,
+                                   hipStream_t st);
+hipError_t launch_table_update(const Shape& s, float* tab_ver, float* tab_sla, double* state, const int32_t* seq_lens,
+                               const int32_t* idx, const float* sc, const int32_t* k, double gamma, double a,
+                               hipStream_t st);
+hipError_t launch_table_import(const Shape& s, float* tab_ver, float* tab_sla, double* state, const int32_t* seq_lens,
+                               const float* phi_ver, const float* phi_sla, double a, hipStream_t st);
+hipError_t launch_table_export(const Shape& s, const float* tab_ver, const float* tab_sla, const double* state,
+                               const int32_t* seq_lens, double* phi_ver, double* phi_sla, hipStream_t st);
+hipError_t launch_table_renorm(const Shape& s, float* tab_ver, float* tab_sla, double* state, hipStream_t st);
+hipError_t launch_table_init(const Shape& s, float* tab_ver, float* tab_sla, double* state, const int32_t* seq_lens,
+                             const float* score, int64_t score_stride, double gamma, double a, hipStream_t st);
+
 // ---- small device helpers ------------------------------------------------------------
 __device__ __forceinline__ float bf16_lo(uint32_t w) { return __uint_as_float(w << 16); }
 __device__ __forceinline__ float bf16_hi(uint32_t w) { return __uint_as_float(w & 0xFFFF0000u); }

@@ -1,0 +1,440 @@
+// Score tables of LFPS (Sec. 4.2: Eq. 4 initialisation, Eq. 7-8 thresholds, Eq. 10 update; App. B.2).
+//
+// Per query head two tables over positions, vertical and slash.  Eq. 10 decays every entry by gamma each
+// step, moves slash history from i-1 to i, and adds (w_i - 1/(2|C_2|)) on the selected positions only.
+// Stored so that a step touches the selected entries and nothing else:
+//   * scale: a table entry is  Phi(i) = g * A(i)  with one factor g per head.  The decay is g <- gamma g;
+//     a selected entry becomes A(i) += delta_i / (gamma g).  (When g gets small the host asks for a
+//     dense pass that folds g back into A.)
+//   * slash frame: A_sla is stored at index  i - cnt + Lcap  (cnt = updates applied so far), so the move
+//     of history from i-1 to i is the increment of cnt.  The entry of a new position is the slot its
+//     predecessor had; position 0 moves onto a slot that was never written (zero).
+//   * statistics: Eq. 8 needs the mean, sum (x-mean)^2 and sum (x-mean)^4 of each table.  The raw
+//     moments M_p = sum x^p (p = 1..4, fp64) follow the update exactly: M_p <- gamma^p M_p +
+//     sum over selected of ((gamma x + delta)^p - (gamma x)^p); a new position adds a zero.
+//     The thresholds of the next step are derived from them when the update ends.
+// Sink positions (< n_sink) are outside the tables: never flagged, counted or updated.
+//
+// The only dense work of a step is the scan (k_table_flags): both tables are read once and two bits
+// per position and head are written (initial candidate; above the mean).
+#include "lfps_internal.h"
+
+namespace lfps {
+
+constexpr int kTabThreads = 256;
+
+// head state (doubles): scale, update count, rows the moments cover, raw moments of both tables,
+// thresholds of the next scan in true units
+enum {
+  TS_G = 0, TS_CNT = 1, TS_N = 2,
+  TS_MV = 3,            // M1..M4 of the vertical table: [3..6]
+  TS_MS = 7,            // M1..M4 of the slash table:    [7..10]
+  TS_TAU_V = 11, TS_TAU_S = 12, TS_MEAN_V = 13, TS_MEAN_S = 14,
+};
+
+// The update count as stored (a double) brought into [0, Lcap - 1]: every slash-frame index formed with
+// it stays inside the table's 2 * Lcap slots (the host refuses updates beyond that count).
+__device__ __forceinline__ int clamp_count(double c, int Lcap) {
+  const int v = (int)c;
+  return v < 0 ? 0 : (v > Lcap - 1 ? Lcap - 1 : v);
+}
+
+__device__ __forceinline__ double block_sum(double v, double* red, int tid) {
+#pragma unroll
+  for (int d = 1; d < 64; d <<= 1) v += __shfl_xor(v, d);
+  __syncthreads();
+  if ((tid & 63) == 0) red[tid >> 6] = v;
+  __syncthreads();
+  double t = 0.0;
+  for (int w = 0; w < (int)blockDim.x / 64; ++w) t += red[w];
+  return t;
+}
+
+__device__ __forceinline__ float block_min(float v, float* red, int tid) {
+#pragma unroll
+  for (int d = 1; d < 64; d <<= 1) v = fminf(v, __shfl_xor(v, d));
+  __syncthreads();
+  if ((tid & 63) == 0) red[tid >> 6] = v;
+  __syncthreads();
+  float t = red[0];
+  for (int w = 1; w < (int)blockDim.x / 64; ++w) t = fminf(t, red[w]);
+  return t;
+}
+
+// Eq. 8 from raw moments over N entries: thresholds and means in true units.
+__device__ __forceinline__ void thresholds_from_moments(const double* M, double N, double a, bool flat, double* tau,
+                                                        double* mean) {
+  if (N <= 0.0) {
+    *tau = INFINITY;
+    *mean = 0.0;
+    return;
+  }
+  const double m = M[0] / N;
+  *mean = m;
+  const double c2 = M[1] - N * m * m;
+  const double c4 = M[3] - 4.0 * m * M[2] + 6.0 * m * m * M[1] - 3.0 * N * m * m * m * m;
+  if (flat || !(c2 > 0.0) || !(c4 > 0.0)) {
+    *tau = INFINITY;                        // no pattern: nothing exceeds the threshold
+    return;
+  }
+  const double kappa = c4 / (c2 * c2);
+  *tau = a * m / kappa;
+}
+
+// ----------------------------------------------------------------------------- scan (Eq. 7, Eq. 9 predicates)
+// grid (chunks, B*Hq).  Each wave tests 64 consecutive positions per iteration; the ballots are the
+// flag words.  Comparisons are made in fp64 on g * A, the true table value.
+__global__ __launch_bounds__(kTabThreads) void k_table_flags(Shape s, const float* __restrict__ tab_ver,
+                                                             const float* __restrict__ tab_sla,
+                                                             const double* __restrict__ state,
+                                                             const int32_t* __restrict__ seq_lens,
+                                                             uint32_t* __restrict__ f0, uint32_t* __restrict__ fm,
+                                                             int flag_words, int rows_per_block) {
+  const int bh = blockIdx.y, b = bh / s.Hq;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  int n = seq_lens[b];
+  n = n < 0 ? 0 : (n > s.Lcap ? s.Lcap : n);
+  const int n_round = (n + 63) & ~63;                     // whole flag words up to the end of the sequence
+  const double* st = state + (int64_t)bh * kTableStateDoubles;
+  const double g = st[TS_G];
+  const int cnt = clamp_count(st[TS_CNT], s.Lcap);
+  const double tau_v = st[TS_TAU_V], tau_s = st[TS_TAU_S], mean_v = st[TS_MEAN_V], mean_s = st[TS_MEAN_S];
+  const float* ver = tab_ver + (int64_t)bh * s.Lcap;
+  const float* sla = tab_sla + (int64_t)bh * 2 * s.Lcap + (s.Lcap - cnt);
+  uint32_t* o0 = f0 + (int64_t)bh * flag_words;
+  uint32_t* om = fm + (int64_t)bh * flag_words;
+  const int begin = blockIdx.x * rows_per_block;
+  const int end = begin + rows_per_block < n_round ? begin + rows_per_block : n_round;
+#pragma unroll 4
+  for (int base = begin + wave * 64; base < end; base += (kTabThreads / 64) * 64) {
+    const int i = base + lane;
+    const bool in = i >= s.n_sink && i < n;
+    const double xv = in ? g * (double)ver[i] : 0.0;
+    const double xs = in ? g * (double)sla[i] : 0.0;
+    const uint64_t m0 = __ballot(in && (xv > tau_v || xs > tau_s));
+    const uint64_t mm = __ballot(in && (xv > mean_v || xs > mean_s));
+    if (lane == 0) {
+      *reinterpret_cast<uint2*>(o0 + (base >> 5)) = make_uint2((uint32_t)m0, (uint32_t)(m0 >> 32));
+      *reinterpret_cast<uint2*>(om + (base >> 5)) = make_uint2((uint32_t)mm, (uint32_t)(mm >> 32));
+    }
+  }
+}
+
+// ----------------------------------------------------------------------------- update (Eq. 10)
+// grid B*Hq.  The step saw n rows and selected idx[bh, 0:k_b] with scaled scores sc; entries outside
+// [n_sink, n) are padding.  w = softmax over the valid entries; delta = w - 1/(2 * valid).
+__global__ __launch_bounds__(kTabThreads) void k_table_update(Shape s, float* __restrict__ tab_ver,
+                                                              float* __restrict__ tab_sla, double* __restrict__ state,
+                                                              const int32_t* __restrict__ seq_lens,
+                                                              const int32_t* __restrict__ idx,
+                                                              const float* __restrict__ sc,
+                                                              const int32_t* __restrict__ kk, double gamma, double a) {
+  __shared__ double red[kTabThreads / 64];
+  __shared__ float redf[kTabThreads / 64];
+  const int bh = blockIdx.x, b = bh / s.Hq, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  int n = seq_lens[b];
+  n = n < 0 ? 0 : (n > s.Lcap ? s.Lcap : n);
+  int kb = kk[b];
+  kb = kb < 0 ? 0 : (kb > s.kmax ? s.kmax : kb);
+  double* st = state + (int64_t)bh * kTableStateDoubles;
+  const double g = st[TS_G];
+  const int cnt = clamp_count(st[TS_CNT], s.Lcap);
+  const int32_t* ih = idx + (int64_t)bh * s.kmax;
+  const float* sh = sc + (int64_t)bh * s.kmax;
+  float* ver = tab_ver + (int64_t)bh * s.Lcap;
+  float* sla = tab_sla + (int64_t)bh * 2 * s.Lcap + (s.Lcap - cnt);   // indexed by position in the frame of this step
+
+  // softmax over the valid selected entries
+  float m = -INFINITY;
+  int nvalid = 0;
+  for (int e = tid; e < kb; e += kTabThreads) {
+    const int p = ih[e];
+    if (p >= s.n_sink && p < n) {
+      m = fmaxf(m, sh[e]);
+      ++nvalid;
+    }
+  }
+#pragma unroll
+  for (int d = 1; d < 64; d <<= 1) m = fmaxf(m, __shfl_xor(m, d));
+  if (lane == 0) redf[wave] = m;
+  __syncthreads();
+  m = redf[0];
+  for (int w = 1; w < kTabThreads / 64; ++w) m = fmaxf(m, redf[w]);
+  double zsum = 0.0;
+  for (int e = tid; e < kb; e += kTabThreads) {
+    const int p = ih[e];
+    if (p >= s.n_sink && p < n) zsum += (double)expf(sh[e] - m);
+  }
+  zsum = block_sum(zsum, red, tid);
+  const double nv = block_sum((double)nvalid, red, tid);
+  const double half = nv > 0.0 ? 0.5 / nv : 0.0;
+  const double g1 = gamma * g;                               // scale after this step
+
+  // selected entries: moments' change and the new unscaled values
+  double dv[4] = {0, 0, 0, 0}, ds[4] = {0, 0, 0, 0};
+  for (int e = tid; e < kb; e += kTabThreads) {
+    const int p = ih[e];
+    if (p >= s.n_sink && p < n) {
+      const double delta = (double)expf(sh[e] - m) / zsum - half;
+      const double xv = gamma * g * (double)ver[p];          // decayed old value
+      const double xs = p - 1 >= s.n_sink ? gamma * g * (double)sla[p - 1] : 0.0;   // decayed value moving in from p-1
+      const double yv = xv + delta, ys = xs + delta;
+      dv[0] += yv - xv;
+      dv[1] += yv * yv - xv * xv;
+      dv[2] += yv * yv * yv - xv * xv * xv;
+      dv[3] += yv * yv * yv * yv - xv * xv * xv * xv;
+      ds[0] += ys - xs;
+      ds[1] += ys * ys - xs * xs;
+      ds[2] += ys * ys * ys - xs * xs * xs;
+      ds[3] += ys * ys * ys * ys - xs * xs * xs * xs;
+      const float inc = (float)(delta / g1);
+      atomicAdd(&ver[p], inc);
+      // position p in the next frame (cnt + 1) is the slot of p - 1 in this one (for p = 0 the
+      // never-written slot just below the frame)
+      atomicAdd(&sla[p - 1], inc);
+    }
+  }
+  double tv[4], ts[4];
+#pragma unroll
+  for (int p = 0; p < 4; ++p) {
+    tv[p] = block_sum(dv[p], red, tid);
+    ts[p] = block_sum(ds[p], red, tid);
+  }
+  if (tid == 0) {
+    double gp = 1.0;
+    double Mv[4], Ms[4];
+#pragma unroll
+    for (int p = 0; p < 4; ++p) {
+      gp *= gamma;
+      Mv[p] = gp * st[TS_MV + p] + tv[p];
+      Ms[p] = gp * st[TS_MS + p] + ts[p];
+      st[TS_MV + p] = Mv[p];
+      st[TS_MS + p] = Ms[p];
+    }
+    st[TS_G] = g1;
+    st[TS_CNT] = (double)(cnt + 1);
+    const double N = (double)(n + 1 - s.n_sink > 0 ? n + 1 - s.n_sink : 0);   // the next step sees one more row
+    st[TS_N] = N;
+    double tau, mean;
+    thresholds_from_moments(Mv, N, a, Mv[1] == 0.0, &tau, &mean);
+    st[TS_TAU_V] = tau;
+    st[TS_MEAN_V] = mean;
+    thresholds_from_moments(Ms, N, a, Ms[1] == 0.0, &tau, &mean);
+    st[TS_TAU_S] = tau;
+    st[TS_MEAN_S] = mean;
+  }
+}
+
+// ----------------------------------------------------------------------------- import / export / renormalise
+// Import true table values phi_*[bh, 0:n_b] (fp32, position frame): scale 1, count 0, dense moments.
+__global__ __launch_bounds__(kTabThreads) void k_table_import(Shape s, float* __restrict__ tab_ver,
+                                                              float* __restrict__ tab_sla, double* __restrict__ state,
+                                                              const int32_t* __restrict__ seq_lens,
+                                                              const float* __restrict__ phi_ver,
+                                                              const float* __restrict__ phi_sla, double a) {
+  __shared__ double red[kTabThreads / 64];
+  __shared__ float redf[kTabThreads / 64];
+  const int bh = blockIdx.x, b = bh / s.Hq, tid = threadIdx.x;
+  int n = seq_lens[b];
+  n = n < 0 ? 0 : (n > s.Lcap ? s.Lcap : n);
+  float* ver = tab_ver + (int64_t)bh * s.Lcap;
+  float* sla = tab_sla + (int64_t)bh * 2 * s.Lcap;
+  const float* pv = phi_ver + (int64_t)bh * s.Lcap;
+  const float* ps = phi_sla + (int64_t)bh * s.Lcap;
+  double mv[4] = {0, 0, 0, 0}, ms[4] = {0, 0, 0, 0};
+  float lo_v = INFINITY, hi_v = -INFINITY, lo_s = INFINITY, hi_s = -INFINITY;
+  for (int i = tid; i < 2 * s.Lcap; i += kTabThreads) sla[i] = 0.f;
+  __syncthreads();
+  for (int i = tid; i < s.Lcap; i += kTabThreads) {
+    const bool in = i >= s.n_sink && i < n;
+    const float xv = in ? pv[i] : 0.f, xs = in ? ps[i] : 0.f;
+    ver[i] = xv;
+    sla[i + s.Lcap] = xs;
+    if (in) {
+      const double a1 = xv, b1 = xs;
+      mv[0] += a1; mv[1] += a1 * a1; mv[2] += a1 * a1 * a1; mv[3] += a1 * a1 * a1 * a1;
+      ms[0] += b1; ms[1] += b1 * b1; ms[2] += b1 * b1 * b1; ms[3] += b1 * b1 * b1 * b1;
+      lo_v = fminf(lo_v, xv); hi_v = fmaxf(hi_v, xv);
+      lo_s = fminf(lo_s, xs); hi_s = fmaxf(hi_s, xs);
+    }
+  }
+  double Mv[4], Ms[4];
+#pragma unroll
+  for (int p = 0; p < 4; ++p) {
+    Mv[p] = block_sum(mv[p], red, tid);
+    Ms[p] = block_sum(ms[p], red, tid);
+  }
+  // a flat table (every entry equal) has no pattern: block minimum == block maximum
+  lo_v = block_min(lo_v, redf, tid);
+  hi_v = -block_min(-hi_v, redf, tid);
+  lo_s = block_min(lo_s, redf, tid);
+  hi_s = -block_min(-hi_s, redf, tid);
+  const double N = (double)(n - s.n_sink > 0 ? n - s.n_sink : 0);
+  if (tid == 0) {
+    double* st = state + (int64_t)bh * kTableStateDoubles;
+    st[TS_G] = 1.0;
+    st[TS_CNT] = 0.0;
+    st[TS_N] = N;
+#pragma unroll
+    for (int p = 0; p < 4; ++p) {
+      st[TS_MV + p] = Mv[p];
+      st[TS_MS + p] = Ms[p];
+    }
+    double tau, mean;
+    thresholds_from_moments(Mv, N, a, !(hi_v > lo_v), &tau, &mean);
+    st[TS_TAU_V] = tau;
+    st[TS_MEAN_V] = mean;
+    thresholds_from_moments(Ms, N, a, !(hi_s > lo_s), &tau, &mean);
+    st[TS_TAU_S] = tau;
+    st[TS_MEAN_S] = mean;
+  }
+}
+
+// True table values of positions [0, n_b) as fp64 (zeros elsewhere up to Lcap).
+__global__ __launch_bounds__(kTabThreads) void k_table_export(Shape s, const float* __restrict__ tab_ver,
+                                                              const float* __restrict__ tab_sla,
+                                                              const double* __restrict__ state,
+                                                              const int32_t* __restrict__ seq_lens,
+                                                              double* __restrict__ phi_ver,
+                                                              double* __restrict__ phi_sla) {
+  const int bh = blockIdx.y, b = bh / s.Hq;
+  int n = seq_lens[b];
+  n = n < 0 ? 0 : (n > s.Lcap ? s.Lcap : n);
+  const double* st = state + (int64_t)bh * kTableStateDoubles;
+  const double g = st[TS_G];
+  const int cnt = clamp_count(st[TS_CNT], s.Lcap);
+  const int i = blockIdx.x * kTabThreads + threadIdx.x;
+  if (i >= s.Lcap) return;
+  const bool in = i >= s.n_sink && i < n;
+  phi_ver[(int64_t)bh * s.Lcap + i] = in ? g * (double)tab_ver[(int64_t)bh * s.Lcap + i] : 0.0;
+  phi_sla[(int64_t)bh * s.Lcap + i] = in ? g * (double)tab_sla[(int64_t)bh * 2 * s.Lcap + (s.Lcap - cnt) + i] : 0.0;
+}
+
+// Folds the scale into the stored values (A <- g A, g <- 1).  grid (chunks over 2*Lcap, B*Hq).
+__global__ __launch_bounds__(kTabThreads) void k_table_renorm(Shape s, float* __restrict__ tab_ver,
+                                                              float* __restrict__ tab_sla,
+                                                              const double* __restrict__ state) {
+  const int bh = blockIdx.y;
+  const double g = state[(int64_t)bh * kTableStateDoubles + TS_G];
+  const int i = blockIdx.x * kTabThreads + threadIdx.x;
+  if (i < s.Lcap) tab_ver[(int64_t)bh * s.Lcap + i] = (float)(g * (double)tab_ver[(int64_t)bh * s.Lcap + i]);
+  if (i < 2 * s.Lcap) tab_sla[(int64_t)bh * 2 * s.Lcap + i] = (float)(g * (double)tab_sla[(int64_t)bh * 2 * s.Lcap + i]);
+}
+__global__ void k_table_renorm_done(double* __restrict__ state, int n_heads) {
+  const int bh = blockIdx.x * 256 + threadIdx.x;
+  if (bh < n_heads) state[(int64_t)bh * kTableStateDoubles + TS_G] = 1.0;
+}
+
+// ----------------------------------------------------------------------------- Eq. 4 with one query
+// Tables from the attention weights of one query over rows [n_sink, n_b): both tables are
+// w / (2 (1 - gamma)) (with s = 1 the slash sum of Eq. 4 has its single, unshifted term).
+// score[bh, 0:n_b] holds the scaled scores of that query.  grid B*Hq.
+__global__ __launch_bounds__(1024) void k_table_init(Shape s, float* __restrict__ tab_ver, float* __restrict__ tab_sla,
+                                                     double* __restrict__ state, const int32_t* __restrict__ seq_lens,
+                                                     const float* __restrict__ score, int64_t score_stride, double gamma,
+                                                     double a) {
+  __shared__ double red[16];
+  __shared__ float redf[16];
+  const int bh = blockIdx.x, b = bh / s.Hq, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  int n = seq_lens[b];
+  n = n < 0 ? 0 : (n > s.Lcap ? s.Lcap : n);
+  const float* sc = score + (int64_t)bh * score_stride;
+  float* ver = tab_ver + (int64_t)bh * s.Lcap;
+  float* sla = tab_sla + (int64_t)bh * 2 * s.Lcap;
+  float m = -INFINITY;
+  for (int i = s.n_sink + tid; i < n; i += 1024) m = fmaxf(m, sc[i]);
+#pragma unroll
+  for (int d = 1; d < 64; d <<= 1) m = fmaxf(m, __shfl_xor(m, d));
+  if (lane == 0) redf[wave] = m;
+  __syncthreads();
+  m = redf[0];
+  for (int w = 1; w < 16; ++w) m = fmaxf(m, redf[w]);
+  double z = 0.0;
+  for (int i = s.n_sink + tid; i < n; i += 1024) z += (double)expf(sc[i] - m);
+  z = block_sum(z, red, tid);
+  const double norm = z > 0.0 ? 1.0 / (2.0 * (1.0 - gamma) * z) : 0.0;
+  double mv[4] = {0, 0, 0, 0};
+  for (int i = tid; i < 2 * s.Lcap; i += 1024) sla[i] = 0.f;
+  __syncthreads();
+  for (int i = tid; i < s.Lcap; i += 1024) {
+    float x = 0.f;
+    if (i >= s.n_sink && i < n) {
+      x = (float)((double)expf(sc[i] - m) * norm);
+      const double xd = x;
+      mv[0] += xd; mv[1] += xd * xd; mv[2] += xd * xd * xd; mv[3] += xd * xd * xd * xd;
+    }
+    ver[i] = x;
+    sla[i + s.Lcap] = x;
+  }
+  double M[4];
+#pragma unroll
+  for (int p = 0; p < 4; ++p) M[p] = block_sum(mv[p], red, tid);
+  if (tid == 0) {
+    double* st = state + (int64_t)bh * kTableStateDoubles;
+    const double N = (double)(n - s.n_sink > 0 ? n - s.n_sink : 0);
+    st[TS_G] = 1.0;
+    st[TS_CNT] = 0.0;
+    st[TS_N] = N;
+#pragma unroll
+    for (int p = 0; p < 4; ++p) {
+      st[TS_MV + p] = M[p];
+      st[TS_MS + p] = M[p];
+    }
+    double tau, mean;
+    thresholds_from_moments(M, N, a, false, &tau, &mean);
+    st[TS_TAU_V] = st[TS_TAU_S] = tau;
+    st[TS_MEAN_V] = st[TS_MEAN_S] = mean;
+  }
+}
+
+// ----------------------------------------------------------------------------- launchers
+hipError_t launch_table_flags(const Shape& s, const float* tab_ver, const float* tab_sla, const double* state,
+                              const int32_t* seq_lens, uint32_t* f0, uint32_t* fm, int flag_words, hipStream_t st) {
+  // about 8 wave-iterations of 64 positions per wave
+  const int rows_per_block = (kTabThreads / 64) * 64 * 8;
+  const int chunks = (s.Lcap + rows_per_block - 1) / rows_per_block;
+  hipLaunchKernelGGL(k_table_flags, dim3(chunks, s.B * s.Hq), dim3(kTabThreads), 0, st, s, tab_ver, tab_sla, state,
+                     seq_lens, f0, fm, flag_words, rows_per_block);
+  return hipGetLastError();
+}
+
+hipError_t launch_table_update(const Shape& s, float* tab_ver, float* tab_sla, double* state, const int32_t* seq_lens,
+                               const int32_t* idx, const float* sc, const int32_t* k, double gamma, double a,
+                               hipStream_t st) {
+  hipLaunchKernelGGL(k_table_update, dim3(s.B * s.Hq), dim3(kTabThreads), 0, st, s, tab_ver, tab_sla, state, seq_lens,
+                     idx, sc, k, gamma, a);
+  return hipGetLastError();
+}
+
+hipError_t launch_table_import(const Shape& s, float* tab_ver, float* tab_sla, double* state, const int32_t* seq_lens,
+                               const float* phi_ver, const float* phi_sla, double a, hipStream_t st) {
+  hipLaunchKernelGGL(k_table_import, dim3(s.B * s.Hq), dim3(kTabThreads), 0, st, s, tab_ver, tab_sla, state, seq_lens,
+                     phi_ver, phi_sla, a);
+  return hipGetLastError();
+}
+
+hipError_t launch_table_export(const Shape& s, const float* tab_ver, const float* tab_sla, const double* state,
+                               const int32_t* seq_lens, double* phi_ver, double* phi_sla, hipStream_t st) {
+  hipLaunchKernelGGL(k_table_export, dim3((s.Lcap + kTabThreads - 1) / kTabThreads, s.B * s.Hq), dim3(kTabThreads), 0,
+                     st, s, tab_ver, tab_sla, state, seq_lens, phi_ver, phi_sla);
+  return hipGetLastError();
+}
+
+hipError_t launch_table_renorm(const Shape& s, float* tab_ver, float* tab_sla, double* state, hipStream_t st) {
+  hipLaunchKernelGGL(k_table_renorm, dim3((2 * s.Lcap + kTabThreads - 1) / kTabThreads, s.B * s.Hq), dim3(kTabThreads),
+                     0, st, s, tab_ver, tab_sla, state);
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return e;
+  const int nh = s.B * s.Hq;
+  hipLaunchKernelGGL(k_table_renorm_done, dim3((nh + 255) / 256), dim3(256), 0, st, state, nh);
+  return hipGetLastError();
+}
+
+hipError_t launch_table_init(const Shape& s, float* tab_ver, float* tab_sla, double* state, const int32_t* seq_lens,
+                             const float* score, int64_t score_stride, double gamma, double a, hipStream_t st) {
+  hipLaunchKernelGGL(k_table_init, dim3(s.B * s.Hq), dim3(1024), 0, st, s, tab_ver, tab_sla, state, seq_lens, score,
+                     score_stride, gamma, a);
+  return hipGetLastError();
+}
+
+}  // namespace lfps

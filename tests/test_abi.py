@@ -49,6 +49,13 @@ def test_config_validation_without_gpu():
     with pytest.raises(b.LfpsError) as ei:
         b.workspace_bytes(**{**good, "max_seq_len": 1_000_000})
     assert ei.value.code == b.LFPS_ECAP
+    # table mode: decay in (0, 1), a > 0, radius <= 30; the tables add to the workspace
+    tab = {**good, "table_mode": 1, "table_decay": 0.95, "table_a": 0.2}
+    assert b.workspace_bytes(**tab) > b.workspace_bytes(**good) + 2 * 32 * 4096 * 12
+    for bad in (dict(table_decay=0.0), dict(table_decay=1.0), dict(table_a=0.0), dict(radius=31), dict(table_mode=2)):
+        with pytest.raises(b.LfpsError) as ei:
+            b.workspace_bytes(**{**tab, **bad})
+        assert ei.value.code == b.LFPS_EINVAL
 
 
 def test_kernel_names():
