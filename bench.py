@@ -50,7 +50,7 @@ def parse_args():
 class Runner:
     """Device state of one workload and the step loop."""
 
-    def __init__(self, name):
+    def __init__(self, name, table_mode=False, n_sink=0):
         import numpy as np
         import torch
 
@@ -65,7 +65,8 @@ class Runner:
         self.K, self.V = gen_device.fill_kv(case, self.dev)
         self.ctx = Lfps(batch=spec.B, n_q_heads=spec.Hq, n_kv_heads=spec.Hkv, head_dim=spec.D,
                         kv_dtype=spec.kv_dtype, max_seq_len=case.Lcap, max_k=case.kmax, radius=spec.r,
-                        n_recent=1, n_sink=0)
+                        n_recent=1, n_sink=n_sink, table_mode=table_mode, table_decay=0.95, table_a=0.2)
+        self.table_mode = table_mode
         to = lambda a: torch.from_numpy(np.ascontiguousarray(a)).to(self.dev)
         self.q = to(case.q)                                                 # [T+1, B, Hq, D]
         self.seq = to(np.stack([case.seq_lens(t) for t in range(spec.T + 1)]))  # [T+1, B]
@@ -97,7 +98,12 @@ class Runner:
     def step(self):
         t = self._advance()
         dst = self.buf[self.cur]
-        self.ctx.lfps_step(self.q[t], self.views[t], self.prev, self.k, dst, self.out)
+        if self.table_mode:
+            if t == 1:      # (re)start of the chain: Eq. 4 tables from the step-0 query
+                self.ctx.lfps_tables_init(self.q[0], self.views[0])
+            self.ctx.lfps_table_step(self.q[t], self.views[t], self.k, dst, self.out)
+        else:
+            self.ctx.lfps_step(self.q[t], self.views[t], self.prev, self.k, dst, self.out)
         self.prev = dst
         self.cur ^= 1
 
@@ -106,6 +112,7 @@ class Runner:
         torch = self.torch
         self.reset()
         self.ctx.lfps_reset_history()
+        assert warmup >= 1 or not self.table_mode, "table mode: the first step builds the tables (keep it in the warm-up)"
         for _ in range(warmup):
             self.step()
         torch.cuda.synchronize()
@@ -258,6 +265,47 @@ def measure(name, steps, warmup, with_baselines=True, use_graph=True):
     return res, r.case
 
 
+def measure_tables(name, steps, warmup):
+    """The same workload with the paper's own candidate rule (score tables, Eq. 7-10): lfps_table_step per step,
+    tables initialised from the step-0 query (Eq. 4 with one query) during warm-up; first four rows = sinks,
+    kept outside the tables as in the paper.  Reported next to the memoryless path, not as `value`."""
+    r = Runner(name, table_mode=True, n_sink=4)
+    spec = r.spec
+    if steps <= 0:
+        steps = max(1, spec.T - warmup)
+    sec = r.run_timed(steps, max(warmup, 1))
+    recall = r.recall_vs_exact()
+    torch = r.torch
+    # per-kernel times and candidate counts over the same steps
+    r.reset()
+    for _ in range(max(warmup, 1)):
+        r.step()
+    torch.cuda.synchronize()
+    cnts = torch.zeros((steps, spec.B, spec.Hkv), dtype=torch.int32, device=r.dev)
+    r.ctx.lfps_timing_enable(True)
+    for i in range(steps):
+        r.step()
+        r.ctx.lfps_copy_cand_count(cnts[i])
+    tm = r.ctx.lfps_timing_read()
+    r.ctx.lfps_timing_enable(False)
+    cn = cnts.cpu().numpy()
+    heads = spec.B * spec.Hq
+    lens = r.case.seq_lens0.astype(float)
+    scan_bytes = float(lens.sum()) * spec.Hq * 8.0            # both fp32 tables of every head, read once per step
+    scan_us = tm["table_flags"][0] / max(tm["table_flags"][1], 1) * 1e3
+    res = {"steps_per_s": round(1.0 / sec, 2), "ms_per_step": round(sec * 1e3, 4), "steps": steps,
+           "decay": 0.95, "a": 0.2, "n_sink": 4,
+           "cand_frac": round(float(cn.mean() / (spec.L or r.case.seq_lens0.mean())), 4),
+           "recall_vs_exact_topk": round(recall, 4),
+           "kernel_us": {k: round(v[0] / steps * 1e3, 2) for k, v in tm.items() if v[1]},
+           "table_scan": {"bytes_per_launch": round(scan_bytes), "avg_launch_us": round(scan_us, 2),
+                          "GB_per_s": round(scan_bytes / (scan_us * 1e-6) / 1e9, 1) if scan_us > 0 else None,
+                          "frac_of_hbm_peak": round(scan_bytes / (scan_us * 1e-6) / 1e9 / HBM_PEAK_GBS, 4) if scan_us > 0 else None},
+           "heads": heads}
+    r.close()
+    return res
+
+
 def cpu_baseline(case, budget_s):
     """The oracle's LFPS step (fp64 numpy, one thread) chained over a few steps on a sample of
     (request, KV group) pairs, scaled to the whole batch."""
@@ -356,6 +404,9 @@ def main():
         "speedup_vs_exact_topk": main_res.get("speedup_vs_exact_topk"),
         "speedup_vs_full_attn": main_res.get("speedup_vs_full_attn"),
     }
+    tab = measure_tables(args.workload, args.steps, args.warmup)
+    tab["speedup_vs_memoryless_step"] = round(main_res["ms_per_step"] / tab["ms_per_step"], 3)
+    line["score_table_mode"] = tab
     if args.all_workloads:
         others = {}
         for name in ("C1", "C2", "C3", "C4", "C5"):
@@ -367,6 +418,9 @@ def main():
             others[name]["roofline_frac"] = res["roofline"]["frac"]
             others[name]["steps_per_s"] = round(others[name]["steps_per_s"], 2)
             others[name]["ms_per_step"] = round(others[name]["ms_per_step"], 4)
+            t = measure_tables(name, 0, args.warmup)
+            others[name]["score_table_mode"] = {k: t[k] for k in ("steps_per_s", "ms_per_step", "cand_frac",
+                                                                    "recall_vs_exact_topk", "kernel_us")}
         line["other_workloads"] = others
     if not args.no_cpu_baseline:
         line["cpu_baseline"] = cpu_baseline(case, args.cpu_seconds)

@@ -212,7 +212,11 @@ __global__ __launch_bounds__(kCandThreads) void k_table_candidates(Shape s, cons
                                                                    const int32_t* __restrict__ seq_lens,
                                                                    int32_t* __restrict__ cand,
                                                                    int32_t* __restrict__ cand_count,
-                                                                   int32_t* __restrict__ flags) {
+                                                                   int32_t* __restrict__ flags,
+                                                                   int32_t* __restrict__ redo_g,
+                                                                   int32_t* __restrict__ redo_h,
+                                                                   int64_t* __restrict__ group_start,
+                                                                   unsigned long long* __restrict__ line_total) {
   extern __shared__ uint32_t lds[];
   __shared__ int wave_tot[kCandThreads / 64];
   const int bg = blockIdx.y, b = bg / s.Hkv, g = bg % s.Hkv;
@@ -220,6 +224,10 @@ __global__ __launch_bounds__(kCandThreads) void k_table_candidates(Shape s, cons
   const int tid = threadIdx.x;
   int n = seq_lens[b];
   n = n < 0 ? 0 : (n > s.Lcap ? s.Lcap : n);
+  if (part == 0) {                                         // first kernel of a step: clear the group's marks
+    if (redo_g && tid == 0) redo_g[bg] = 0;
+    if (redo_h && tid < s.G) redo_h[(int64_t)b * s.Hq + (int64_t)g * s.G + tid] = 0;
+  }
   const int W = (n + 31) >> 5;
   uint32_t* bm = lds;
   const int words_cap = (s.Lcap + 31) >> 5;
@@ -244,7 +252,11 @@ __global__ __launch_bounds__(kCandThreads) void k_table_candidates(Shape s, cons
     if (s.n_sink > 0) set_bit_range(bm, 0, (s.n_sink > n ? n : s.n_sink) - 1);
   }
   __syncthreads();
-  emit_bitmap(s, bm, W, rcnt, stage, wave_tot, bg, part, nparts, cand, cand_count, flags);
+  const int total = emit_bitmap(s, bm, W, rcnt, stage, wave_tot, bg, part, nparts, cand, cand_count, flags);
+  if (tid == 0 && part == 0 && group_start) {              // the group's place on the line of all candidate slots
+    const int kept = total > s.cand_cap ? s.cand_cap : total;
+    group_start[bg] = (int64_t)atomicAdd(line_total, (unsigned long long)kept);
+  }
 }
 
 static size_t candidates_lds_bytes(const Shape& s) {
@@ -277,11 +289,13 @@ hipError_t launch_candidates(const Shape& s, const int32_t* prev_topk, const int
 
 hipError_t launch_table_candidates(const Shape& s, const uint32_t* f0, const uint32_t* fm, int flag_words,
                                    const int32_t* seq_lens, int32_t* cand, int32_t* cand_count, int32_t* flags,
+                                   int32_t* redo_g, int32_t* redo_h, int64_t* group_start, int64_t* line_total,
                                    hipStream_t st) {
   int nparts = 256 / (s.B * s.Hkv);
   nparts = nparts < 1 ? 1 : (nparts > 8 ? 8 : nparts);
   hipLaunchKernelGGL(k_table_candidates, dim3(nparts, s.B * s.Hkv), dim3(kCandThreads), candidates_lds_bytes(s), st, s,
-                     f0, fm, flag_words, seq_lens, cand, cand_count, flags);
+                     f0, fm, flag_words, seq_lens, cand, cand_count, flags, redo_g, redo_h, group_start,
+                     reinterpret_cast<unsigned long long*>(line_total));
   return hipGetLastError();
 }
 

@@ -370,6 +370,36 @@ int lfps_sparse_attn(lfps_ctx* ctx, const float* q, const lfps_kv* kv, const int
   return LFPS_OK;
 }
 
+// S2 + S3 over ctx->cand / ctx->cand_count inside the chained entry points.  With the score filter on
+// (bf16 caches): survivors of the per-head threshold first, then the unfiltered pass for the heads it
+// left short (both launches exit at once when no head is marked).  The candidates kernel of the same
+// step has cleared the marks and laid the groups on the line (group_start, line_total).
+static int score_and_select(lfps_ctx* ctx, const float* q, const KvView& v, const int32_t* k, int32_t* topk_idx,
+                            float* sel, hipStream_t st) {
+  const Shape& s = ctx->shape;
+  int64_t* line_total = ctx->group_start + (int64_t)s.B * s.Hkv;
+  const int32_t *only_g = nullptr, *only_h = nullptr;
+  if (ctx->filter_on) {
+    LAUNCH(ctx, LFPS_KERNEL_FILTER_SCORE, st,
+           launch_filter_score(s, q, v, ctx->cand, ctx->cand_count, ctx->group_start, line_total, ctx->thr_state,
+                               kFilterMargin, ctx->score, ctx->slot, s.score_stride, ctx->seg_count, ctx->flags + 1,
+                               ctx->filter_blocks, st));
+    LAUNCH(ctx, LFPS_KERNEL_FILTER_SELECT, st,
+           launch_filter_select(s, ctx->score, ctx->slot, s.score_stride, ctx->seg_count, ctx->flags + 1, ctx->nseg,
+                                ctx->cand_count, ctx->group_start, line_total, k, topk_idx, sel, ctx->thr_state,
+                                ctx->redo_g, ctx->redo_h, st));
+    only_g = ctx->redo_g;
+    only_h = ctx->redo_h;
+  }
+  LAUNCH(ctx, LFPS_KERNEL_GATHER_SCORE, st,
+         launch_group_score(s, ctx->cfg.kv_dtype, q, v, ctx->cand, ctx->cand_count, ctx->score, s.score_stride,
+                            only_g, st));
+  LAUNCH(ctx, LFPS_KERNEL_SELECT, st,
+         launch_select(s, ctx->score, s.score_stride, ctx->cand, ctx->cand_count, k, topk_idx, sel, only_h,
+                       ctx->thr_state, st));
+  return LFPS_OK;
+}
+
 int lfps_step(lfps_ctx* ctx, const float* q, const lfps_kv* kv, const int32_t* prev_topk, const int32_t* k,
               int32_t* topk_idx, float* topk_score, float* out, void* stream) {
   if (!ctx) return LFPS_EINVAL;
@@ -389,26 +419,8 @@ int lfps_step(lfps_ctx* ctx, const float* q, const lfps_kv* kv, const int32_t* p
   LAUNCH(ctx, LFPS_KERNEL_CANDIDATES, st,
          launch_candidates(s, prev_topk, k, v.seq_lens, ctx->cand, ctx->cand_count, ctx->flags, ctx->redo_g,
                            ctx->redo_h, ctx->filter_on ? ctx->group_start : nullptr, line_total, st));
-  const int32_t *only_g = nullptr, *only_h = nullptr;
-  if (ctx->filter_on) {
-    // survivors of the per-head threshold first; heads left short are rescored below
-    LAUNCH(ctx, LFPS_KERNEL_FILTER_SCORE, st,
-           launch_filter_score(s, q, v, ctx->cand, ctx->cand_count, ctx->group_start, line_total, ctx->thr_state,
-                               kFilterMargin, ctx->score,
-                               ctx->slot, s.score_stride, ctx->seg_count, ctx->flags + 1, ctx->filter_blocks, st));
-    LAUNCH(ctx, LFPS_KERNEL_FILTER_SELECT, st,
-           launch_filter_select(s, ctx->score, ctx->slot, s.score_stride, ctx->seg_count, ctx->flags + 1, ctx->nseg,
-                                ctx->cand_count, ctx->group_start, line_total, k, topk_idx, sel, ctx->thr_state,
-                                ctx->redo_g, ctx->redo_h, st));
-    only_g = ctx->redo_g;
-    only_h = ctx->redo_h;
-  }
-  LAUNCH(ctx, LFPS_KERNEL_GATHER_SCORE, st,
-         launch_group_score(s, ctx->cfg.kv_dtype, q, v, ctx->cand, ctx->cand_count, ctx->score, s.score_stride,
-                            only_g, st));
-  LAUNCH(ctx, LFPS_KERNEL_SELECT, st,
-         launch_select(s, ctx->score, s.score_stride, ctx->cand, ctx->cand_count, k, topk_idx, sel, only_h,
-                       ctx->thr_state, st));
+  rc = score_and_select(ctx, q, v, k, topk_idx, sel, st);
+  if (rc != LFPS_OK) return rc;
   LAUNCH(ctx, LFPS_KERNEL_SPARSE_ATTN, st, launch_sparse_attn(s, ctx->cfg.kv_dtype, v, topk_idx, sel, k, out, st));
   return LFPS_OK;
 }
@@ -505,7 +517,7 @@ int lfps_tables_export(lfps_ctx* ctx, double* phi_ver, double* phi_sla, const in
 }
 
 static int table_candidates_impl(lfps_ctx* ctx, const int32_t* seq_lens, int32_t* cand, int32_t* cand_count,
-                                 hipStream_t st) {
+                                 bool for_step, hipStream_t st) {
   const Shape& s = ctx->shape;
   if (ctx->tab_scale < 1e-20) {          // fold the accumulated decay back into the stored entries
     hipError_t e = launch_table_renorm(s, ctx->tab_ver, ctx->tab_sla, ctx->tab_state, st);
@@ -517,7 +529,9 @@ static int table_candidates_impl(lfps_ctx* ctx, const int32_t* seq_lens, int32_t
                             ctx->flag_words, st));
   LAUNCH(ctx, LFPS_KERNEL_TABLE_CANDIDATES, st,
          launch_table_candidates(s, ctx->tab_f0, ctx->tab_fm, ctx->flag_words, seq_lens, cand, cand_count, ctx->flags,
-                                 st));
+                                 for_step ? ctx->redo_g : nullptr, for_step ? ctx->redo_h : nullptr,
+                                 for_step && ctx->filter_on ? ctx->group_start : nullptr,
+                                 ctx->group_start + (int64_t)s.B * s.Hkv, st));
   return LFPS_OK;
 }
 
@@ -539,7 +553,7 @@ int lfps_table_candidates(lfps_ctx* ctx, const int32_t* seq_lens, int32_t* cand,
   if (!seq_lens || !cand || !cand_count) return fail(ctx, LFPS_EINVAL, "lfps_table_candidates: NULL argument");
   int rc = need_tables(ctx, "lfps_table_candidates", true);
   if (rc != LFPS_OK) return rc;
-  return table_candidates_impl(ctx, seq_lens, cand, cand_count, (hipStream_t)stream);
+  return table_candidates_impl(ctx, seq_lens, cand, cand_count, false, (hipStream_t)stream);
 }
 
 int lfps_table_update(lfps_ctx* ctx, const int32_t* idx, const float* idx_score, const int32_t* k,
@@ -563,15 +577,10 @@ int lfps_table_step(lfps_ctx* ctx, const float* q, const lfps_kv* kv, const int3
   hipStream_t st = (hipStream_t)stream;
   const Shape& s = ctx->shape;
   float* sel = topk_score ? topk_score : ctx->sel_score;
-  rc = table_candidates_impl(ctx, v.seq_lens, ctx->cand, ctx->cand_count, st);
+  rc = table_candidates_impl(ctx, v.seq_lens, ctx->cand, ctx->cand_count, true, st);
   if (rc != LFPS_OK) return rc;
-  // the candidate sets are a few per cent of the rows: every score is written and the general select runs
-  LAUNCH(ctx, LFPS_KERNEL_GATHER_SCORE, st,
-         launch_group_score(s, ctx->cfg.kv_dtype, q, v, ctx->cand, ctx->cand_count, ctx->score, s.score_stride,
-                            nullptr, st));
-  LAUNCH(ctx, LFPS_KERNEL_SELECT, st,
-         launch_select(s, ctx->score, s.score_stride, ctx->cand, ctx->cand_count, k, topk_idx, sel, nullptr, nullptr,
-                       st));
+  rc = score_and_select(ctx, q, v, k, topk_idx, sel, st);
+  if (rc != LFPS_OK) return rc;
   LAUNCH(ctx, LFPS_KERNEL_SPARSE_ATTN, st, launch_sparse_attn(s, ctx->cfg.kv_dtype, v, topk_idx, sel, k, out, st));
   return table_update_impl(ctx, topk_idx, sel, k, v.seq_lens, st);
 }

@@ -96,6 +96,7 @@ hipError_t launch_table_flags(const Shape& s, const float* tab_ver, const float*
                               const int32_t* seq_lens, uint32_t* f0, uint32_t* fm, int flag_words, hipStream_t st);
 hipError_t launch_table_candidates(const Shape& s, const uint32_t* f0, const uint32_t* fm, int flag_words,
                                    const int32_t* seq_lens, int32_t* cand, int32_t* cand_count, int32_t* flags,
+                                   int32_t* redo_g, int32_t* redo_h, int64_t* group_start, int64_t* line_total,
                                    hipStream_t st);
 hipError_t launch_table_update(const Shape& s, float* tab_ver, float* tab_sla, double* state, const int32_t* seq_lens,
                                const int32_t* idx, const float* sc, const int32_t* k, double gamma, double a,

@@ -22,6 +22,7 @@
 namespace lfps {
 
 constexpr int kTabThreads = 256;
+constexpr int kFlagIters = 8;      // 64-position tests per wave of the scan kernel
 
 // head state (doubles): scale, update count, rows the moments cover, raw moments of both tables,
 // thresholds of the next scan in true units
@@ -82,41 +83,79 @@ __device__ __forceinline__ void thresholds_from_moments(const double* M, double 
 }
 
 // ----------------------------------------------------------------------------- scan (Eq. 7, Eq. 9 predicates)
+// Largest float <= t (t finite or +inf; NaN gives +inf: nothing passes).  For a float x and a double
+// threshold t:  x > t  <=>  x > float_below(t), so the scan can compare in fp32 without changing a decision.
+__device__ __forceinline__ float float_below(double t) {
+  if (!(t == t)) return INFINITY;
+  float f = (float)t;                                   // round to nearest
+  if ((double)f > t) f = nextafterf(f, -INFINITY);
+  return f;
+}
+
 // grid (chunks, B*Hq).  Each wave tests 64 consecutive positions per iteration; the ballots are the
-// flag words.  Comparisons are made in fp64 on g * A, the true table value.
+// flag words.  A table entry is g * A(i); the comparison  g * A > threshold  is made as  A > threshold / g
+// with the quotient (fp64) rounded down to fp32 once per head.
 __global__ __launch_bounds__(kTabThreads) void k_table_flags(Shape s, const float* __restrict__ tab_ver,
                                                              const float* __restrict__ tab_sla,
                                                              const double* __restrict__ state,
                                                              const int32_t* __restrict__ seq_lens,
                                                              uint32_t* __restrict__ f0, uint32_t* __restrict__ fm,
                                                              int flag_words, int rows_per_block) {
+  __shared__ uint32_t w0[kFlagIters * kTabThreads / 32], wm[kFlagIters * kTabThreads / 32];
   const int bh = blockIdx.y, b = bh / s.Hq;
-  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   int n = seq_lens[b];
   n = n < 0 ? 0 : (n > s.Lcap ? s.Lcap : n);
   const int n_round = (n + 63) & ~63;                     // whole flag words up to the end of the sequence
   const double* st = state + (int64_t)bh * kTableStateDoubles;
   const double g = st[TS_G];
   const int cnt = clamp_count(st[TS_CNT], s.Lcap);
-  const double tau_v = st[TS_TAU_V], tau_s = st[TS_TAU_S], mean_v = st[TS_MEAN_V], mean_s = st[TS_MEAN_S];
+  const float tau_v = float_below(st[TS_TAU_V] / g), tau_s = float_below(st[TS_TAU_S] / g);
+  const float mean_v = float_below(st[TS_MEAN_V] / g), mean_s = float_below(st[TS_MEAN_S] / g);
   const float* ver = tab_ver + (int64_t)bh * s.Lcap;
   const float* sla = tab_sla + (int64_t)bh * 2 * s.Lcap + (s.Lcap - cnt);
   uint32_t* o0 = f0 + (int64_t)bh * flag_words;
   uint32_t* om = fm + (int64_t)bh * flag_words;
-  const int begin = blockIdx.x * rows_per_block;
-  const int end = begin + rows_per_block < n_round ? begin + rows_per_block : n_round;
-#pragma unroll 4
-  for (int base = begin + wave * 64; base < end; base += (kTabThreads / 64) * 64) {
-    const int i = base + lane;
-    const bool in = i >= s.n_sink && i < n;
-    const double xv = in ? g * (double)ver[i] : 0.0;
-    const double xs = in ? g * (double)sla[i] : 0.0;
-    const uint64_t m0 = __ballot(in && (xv > tau_v || xs > tau_s));
-    const uint64_t mm = __ballot(in && (xv > mean_v || xs > mean_s));
-    if (lane == 0) {
-      *reinterpret_cast<uint2*>(o0 + (base >> 5)) = make_uint2((uint32_t)m0, (uint32_t)(m0 >> 32));
-      *reinterpret_cast<uint2*>(om + (base >> 5)) = make_uint2((uint32_t)mm, (uint32_t)(mm >> 32));
+  // A workgroup covers rows_per_block consecutive positions in passes of kFlagIters * 256; in a pass wave w
+  // takes every fourth 64-position word pair, and all its loads are issued before the first comparison
+  // (fixed trip count, fully unrolled).  The flag words of a pass meet in LDS and leave as two coalesced stores.
+  constexpr int kPassRows = kFlagIters * kTabThreads, kPassWords = kPassRows / 32;
+  const int block_begin = blockIdx.x * rows_per_block;
+  const int block_end = block_begin + rows_per_block < n_round ? block_begin + rows_per_block : n_round;
+  for (int pass = block_begin; pass < block_end; pass += kPassRows) {
+    const int begin = pass + wave * 64;
+    float av[kFlagIters], as[kFlagIters];
+#pragma unroll
+    for (int it = 0; it < kFlagIters; ++it) {
+      const int i = begin + it * kTabThreads + lane;
+      const bool in = i >= s.n_sink && i < n;
+      av[it] = in ? ver[i] : 0.f;
+      as[it] = in ? sla[i] : 0.f;
     }
+#pragma unroll
+    for (int it = 0; it < kFlagIters; ++it) {
+      const int i = begin + it * kTabThreads + lane;
+      const bool in = i >= s.n_sink && i < n;
+      const uint64_t m0 = __ballot(in && (av[it] > tau_v || as[it] > tau_s));
+      const uint64_t mm = __ballot(in && (av[it] > mean_v || as[it] > mean_s));
+      if (lane == 0) {
+        const int w = (it * kTabThreads + wave * 64) >> 5;
+        w0[w] = (uint32_t)m0;
+        w0[w + 1] = (uint32_t)(m0 >> 32);
+        wm[w] = (uint32_t)mm;
+        wm[w + 1] = (uint32_t)(mm >> 32);
+      }
+    }
+    __syncthreads();
+    {
+      const int w = tid & (kPassWords - 1);
+      const int gw = (pass >> 5) + w;
+      if (gw < (n_round >> 5)) {
+        if (tid < kPassWords) o0[gw] = w0[w];
+        else if (tid < 2 * kPassWords) om[gw] = wm[w];
+      }
+    }
+    __syncthreads();
   }
 }
 
@@ -188,10 +227,11 @@ __global__ __launch_bounds__(kTabThreads) void k_table_update(Shape s, float* __
       ds[2] += ys * ys * ys - xs * xs * xs;
       ds[3] += ys * ys * ys * ys - xs * xs * xs * xs;
       const float inc = (float)(delta / g1);
-      atomicAdd(&ver[p], inc);
+      // (hardware fp32 add in L2; a selected position may appear twice in a caller's list)
+      unsafeAtomicAdd(&ver[p], inc);
       // position p in the next frame (cnt + 1) is the slot of p - 1 in this one (for p = 0 the
       // never-written slot just below the frame)
-      atomicAdd(&sla[p - 1], inc);
+      unsafeAtomicAdd(&sla[p - 1], inc);
     }
   }
   double tv[4], ts[4];
@@ -390,8 +430,12 @@ __global__ __launch_bounds__(1024) void k_table_init(Shape s, float* __restrict_
 // ----------------------------------------------------------------------------- launchers
 hipError_t launch_table_flags(const Shape& s, const float* tab_ver, const float* tab_sla, const double* state,
                               const int32_t* seq_lens, uint32_t* f0, uint32_t* fm, int flag_words, hipStream_t st) {
-  // about 8 wave-iterations of 64 positions per wave
-  const int rows_per_block = (kTabThreads / 64) * 64 * 8;
+  // about 4096 workgroups in all, each a whole number of passes
+  const int pass_rows = kTabThreads * kFlagIters;
+  int per_head = 4096 / (s.B * s.Hq);
+  per_head = per_head < 1 ? 1 : per_head;
+  int rows_per_block = ((s.Lcap + per_head - 1) / per_head + pass_rows - 1) / pass_rows * pass_rows;
+  if (rows_per_block < pass_rows) rows_per_block = pass_rows;
   const int chunks = (s.Lcap + rows_per_block - 1) / rows_per_block;
   hipLaunchKernelGGL(k_table_flags, dim3(chunks, s.B * s.Hq), dim3(kTabThreads), 0, st, s, tab_ver, tab_sla, state,
                      seq_lens, f0, fm, flag_words, rows_per_block);
