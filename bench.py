@@ -27,8 +27,8 @@ HBM_PEAK_GBS = 8000.0   # MI355X published HBM3E peak
 # HBM bytes per launch of the scoring kernel measured with rocprofv3 --pmc (FETCH_SIZE, WRITE_SIZE), scaled
 # by the same counters' reading for a plain copy kernel; see profiles/ for the runs.  None = not measured.
 # Median over the steady-state dispatches of the scoring kernel (k_filter_score_bf16):
-#   profiles/lfps_kernels_C4.md: 938.6 MB fetched + 10.2 MB written; profiles/lfps_kernels_C3.md: 221.6 + 2.8 MB.
-MEASURED_TRAFFIC_BYTES = {"C4": 948.8e6, "C3": 224.4e6}
+#   profiles/lfps_kernels_C4.md: 944.6 MB fetched + 10.5 MB written; C3: 224.9 + 3.1 MB; C5: 480.3 + 8.9 MB.
+MEASURED_TRAFFIC_BYTES = {"C4": 955.1e6, "C3": 228.0e6, "C5": 489.2e6}
 
 
 def parse_args():
@@ -41,6 +41,9 @@ def parse_args():
                     help="also report the other four workloads in the same line (default)")
     ap.add_argument("--main-only", dest="all_workloads", action="store_false", help="only the main workload")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-table-mode", action="store_true", help="skip the score-table mode legs")
+    ap.add_argument("--table-only", action="store_true",
+                    help="run only the score-table mode of the main workload (for profiling) and print its record")
     ap.add_argument("--calib-copy", action="store_true",
                     help="run only the plain copy kernel (1 GiB, 10 launches): the known-traffic reference for rocprofv3 --pmc")
     ap.add_argument("--cpu-seconds", type=float, default=15.0, help="CPU-oracle sample budget")
@@ -385,6 +388,10 @@ def main():
                           "avg_ms": round(dt * 1e3, 4), "GB_per_s_read_plus_write": round(2 * (1 << 30) / dt / 1e9, 1)}))
         return
 
+    if args.table_only:
+        print(json.dumps({"workload": args.workload, "score_table_mode": measure_tables(args.workload, args.steps, args.warmup)}),
+              flush=True)
+        return
     main_res, case = measure(args.workload, args.steps, args.warmup)
     spec = case.spec
     line = {
@@ -404,9 +411,10 @@ def main():
         "speedup_vs_exact_topk": main_res.get("speedup_vs_exact_topk"),
         "speedup_vs_full_attn": main_res.get("speedup_vs_full_attn"),
     }
-    tab = measure_tables(args.workload, args.steps, args.warmup)
-    tab["speedup_vs_memoryless_step"] = round(main_res["ms_per_step"] / tab["ms_per_step"], 3)
-    line["score_table_mode"] = tab
+    if not args.no_table_mode:
+        tab = measure_tables(args.workload, args.steps, args.warmup)
+        tab["speedup_vs_memoryless_step"] = round(main_res["ms_per_step"] / tab["ms_per_step"], 3)
+        line["score_table_mode"] = tab
     if args.all_workloads:
         others = {}
         for name in ("C1", "C2", "C3", "C4", "C5"):
@@ -418,9 +426,10 @@ def main():
             others[name]["roofline_frac"] = res["roofline"]["frac"]
             others[name]["steps_per_s"] = round(others[name]["steps_per_s"], 2)
             others[name]["ms_per_step"] = round(others[name]["ms_per_step"], 4)
-            t = measure_tables(name, 0, args.warmup)
-            others[name]["score_table_mode"] = {k: t[k] for k in ("steps_per_s", "ms_per_step", "cand_frac",
-                                                                    "recall_vs_exact_topk", "kernel_us")}
+            if not args.no_table_mode:
+                t = measure_tables(name, 0, args.warmup)
+                others[name]["score_table_mode"] = {k: t[k] for k in ("steps_per_s", "ms_per_step", "cand_frac",
+                                                                        "recall_vs_exact_topk", "kernel_us")}
         line["other_workloads"] = others
     if not args.no_cpu_baseline:
         line["cpu_baseline"] = cpu_baseline(case, args.cpu_seconds)
