@@ -146,3 +146,74 @@ def test_worst_case_candidate_count_at_full_size():
                 assert_out_close(out_h[b, h], orc.sparse_attn(case.q[1, b, h], K, V, idx_h[b, h, :kb]), f"worst case out b{b} h{h}")
     finally:
         r.close()
+
+
+@pytest.mark.parametrize("name", ["C2", "C4", "C5"])
+def test_score_table_mode_at_full_size_on_sampled_groups(name):
+    """The score-table form (Eq. 4 start, Eq. 7-10 steps) in the configuration bench.py times: tables are
+    exported before and after every step, and for sampled (request, KV group) pairs the oracle redoes the
+    step from the exported state (so each step is compared on its own, whatever the earlier tie choices)."""
+    from oracle import lfps_tables_oracle as tor
+    from tests.test_gpu_tables import _assert_candidates, assert_tables_close
+    r = bench.Runner(name, table_mode=True, n_sink=4)
+    try:
+        spec, case = r.spec, r.case
+        G, gamma, a, n_sink, n_recent = spec.G, 0.95, 0.2, 4, 1
+        samples = SAMPLES[name] or [(int(np.argmin(case.seq_lens0)), 2), (int(np.argmax(case.seq_lens0)), 6)]
+        kv_cpu = {bg: case.kv_group(*bg) for bg in samples}
+        shp = (spec.B, spec.Hq, case.Lcap)
+        ev = torch.zeros(shp, dtype=torch.float64, device=r.dev)
+        es = torch.zeros_like(ev)
+        r.ctx.lfps_tables_init(r.q[0], r.views[0])
+        r.ctx.lfps_tables_export(ev, es, r.seq[0])
+        for (b, g) in samples:                               # Eq. 4 with one query
+            K, _ = kv_cpu[(b, g)]
+            n0 = int(case.seq_lens0[b])
+            h = G * g + 1
+            s0 = orc.scores(case.q[0, b, h], K[:n0])
+            w = np.zeros(n0)
+            e = np.exp(s0[n_sink:] - s0[n_sink:].max())
+            w[n_sink:] = e / e.sum()
+            ver, _ = tor.init_tables(w[None, :], gamma, n_sink) if n0 <= 4096 else (w / (2 * (1 - gamma)), None)
+            np.testing.assert_allclose(ev[b, h, :n0].cpu().numpy(), ver, rtol=3e-5, atol=1e-12)
+        idx = torch.zeros_like(r.seed)
+        sc = torch.zeros_like(r.sel_score)
+        out = torch.zeros_like(r.out)
+        cnt = torch.zeros((spec.B, spec.Hkv), dtype=torch.int32, device=r.dev)
+        for t in (1, 2):
+            n_t = case.seq_lens(t)
+            r.ctx.lfps_tables_export(ev, es, r.seq[t])
+            before = {(b, g): [(ev[b, G * g + hh].cpu().numpy().copy(), es[b, G * g + hh].cpu().numpy().copy())
+                               for hh in range(G)] for (b, g) in samples}
+            r.ctx.lfps_table_candidates(r.seq[t], r.cand, cnt)
+            r.ctx.lfps_table_step(r.q[t], r.views[t], r.k, idx, out, sc)
+            assert r.ctx.lfps_poll_status() == 0
+            r.ctx.lfps_tables_export(ev, es, r.seq[min(t + 1, spec.T)])
+            cnt_h, idx_h, out_h = cnt.cpu().numpy(), idx.cpu().numpy(), out.cpu().numpy()
+            for (b, g) in samples:
+                K, V = kv_cpu[(b, g)]
+                n, kb = int(n_t[b]), int(case.k[b])
+                t64 = before[(b, g)]
+                want = tor.group_candidates(t64, n, a, spec.r, n_recent, n_sink)
+                got_c = r.cand[b, g, : int(cnt_h[b, g])].cpu().numpy()
+                nd = _assert_candidates(got_c, want, t64, n, a, spec.r, n_sink, f"{name} t{t} b{b} g{g}")
+                assert nd <= 2
+                ksel = min(kb, len(got_c))
+                for hh in range(G):
+                    h = G * g + hh
+                    got = idx_h[b, h, :ksel]
+                    assert np.all(idx_h[b, h, ksel:] == -1)
+                    s_c = orc.scores(case.q[t, b, h], K, got_c)
+                    I = got_c[np.lexsort((got_c, -s_c))[:ksel]]
+                    assert_topk_equal_mod_ties(got, I, lambda p: orc.scores(case.q[t, b, h], K, p), ksel, f"{name} t{t} b{b} h{h}")
+                    assert_out_close(out_h[b, h], orc.sparse_attn(case.q[t, b, h], K, V, got), f"{name} out t{t} b{b} h{h}")
+                    # Eq. 10 from the device's own selection
+                    wv, ws = tor.update_tables(t64[hh][0], t64[hh][1], n, got, orc.scores(case.q[t, b, h], K, got), gamma, n_sink)
+                    m = min(n + 1, case.Lcap)
+                    old_v = np.r_[gamma * t64[hh][0][:n], 0.0][:m]
+                    old_s = np.r_[0.0, gamma * t64[hh][1][:n]][:m]
+                    half = 10 * 0.5 / max(ksel - n_sink, 1)
+                    assert_tables_close(ev[b, h, :m].cpu().numpy(), wv[:m], old_v, half, f"{name} vertical t{t} b{b} h{h}")
+                    assert_tables_close(es[b, h, :m].cpu().numpy(), ws[:m], old_s, half, f"{name} slash t{t} b{b} h{h}")
+    finally:
+        r.close()
