@@ -17,6 +17,9 @@ What each function follows:
                      attention weights over the selected set added minus 1/(2|C_2|); positions outside the
                      selected set only decay (their w is defined as 1/(2|C_2|)).
 * table_step         Alg. 1 lines 5-9 and Eq. 1 for the query heads of one KV group.
+* priors             Sec. 4.2 "Prefilling", last paragraph: mean key, mean value, sigma_hat^2.
+* sparsity_ratio     Eq. 5 and Eq. 6 (App. B.1: the global term is the log-normal mean of the weights).
+* gated_table_step   Alg. 1 lines 1-9: the bypass of sparse heads in front of table_step.
 
 Readings where the paper is silent (the same ones the library takes):
   - w in Eq. 10 is the softmax over the selected set (it must sum to 1 for Eq. 12 to hold).
@@ -27,6 +30,11 @@ Readings where the paper is silent (the same ones the library takes):
     selected non-sink positions.  The newest n_recent rows are always candidates too.
   - A table whose entries are all equal has no pattern: kappa is undefined and no position passes Eq. 7.
   - With GQA the candidate set of a KV group is the union of its heads' sets; Top-k stays per head.
+  - Eq. 5: the sink term sums over the n_sink sink rows; the local term over the newest n_local = 6 rows
+    (Eq. 5 writes six terms, the appendix says "e.g. the last five"); sigma^2 is the variance over the
+    offloaded rows of the logits of the last prefill query, so |q|^2 sigma_hat^2 is the logit variance the
+    current query would see; kbar, vbar are means over the offloaded rows.  A bypassed head keeps its
+    tables unchanged (steps 2-4 of Sec. 4.2 are skipped, Eq. 10 among them) and outputs vbar.
 
 Pins (tests/test_tables_oracle_pins.py): scipy's kurtosis, closed forms of kappa for equal spikes,
 scale invariance of tau's selection, Eq. 12 (table sums follow S' = gamma S + 1/2 and start at
@@ -186,3 +194,63 @@ def table_step(q_group: np.ndarray, K: np.ndarray, V: np.ndarray, tables: List, 
             out.append(np.zeros(np.asarray(V).shape[-1]))
         new_tables.append(update_tables(tables[h][0], tables[h][1], n, I_h, s_h, gamma, n_sink))
     return dict(cand=C, topk_idx=idx, topk_score=sc, out=np.array(out), tables=new_tables)
+
+
+# ----------------------------------------------------------------------------- Eq. 5-6, prefill priors
+def priors(q_last: np.ndarray, K: np.ndarray, V: np.ndarray, n: int, n_sink: int = 0):
+    """Sec. 4.2 "Prefilling", last paragraph: mean key and mean value over the offloaded rows
+    [n_sink, n), and sigma_hat^2 = (variance over those rows of the logits q_last.K_i/sqrt(d)) / |q_last|^2.
+    Returns (kbar [d], vbar [d], sigma2_hat)."""
+    Kr = np.asarray(K[n_sink:n], dtype=np.float64)
+    Vr = np.asarray(V[n_sink:n], dtype=np.float64)
+    q = np.asarray(q_last, dtype=np.float64)
+    logits = (Kr @ q) / math.sqrt(q.shape[-1])
+    return Kr.mean(axis=0), Vr.mean(axis=0), float(np.var(logits)) / float(q @ q)
+
+
+def sparsity_ratio(q: np.ndarray, K: np.ndarray, n: int, kbar: np.ndarray, sigma2_hat: float, n_sink: int,
+                   n_local: int = 6) -> float:
+    """Eq. 5 and Eq. 6: rho = w_sink / (w_sink + w_global + w_local) with
+    w_sink   = sum over the sink rows of exp(q.K_i/sqrt(d)),
+    w_global = n * exp(q.kbar/sqrt(d) + |q|^2 sigma2_hat / 2)   (log-normal mean of the weights, App. B.1),
+    w_local  = sum over the newest n_local rows of exp(q.K_i/sqrt(d))."""
+    q = np.asarray(q, dtype=np.float64)
+    sd = math.sqrt(q.shape[-1])
+    Kd = np.asarray(K, dtype=np.float64)
+    w_sink = float(np.sum(np.exp((Kd[: min(n_sink, n)] @ q) / sd)))
+    w_global = n * math.exp(float(np.asarray(kbar, dtype=np.float64) @ q) / sd + float(q @ q) * sigma2_hat / 2.0)
+    lo = max(0, n - n_local)
+    w_local = float(np.sum(np.exp((Kd[lo:n] @ q) / sd)))
+    return w_sink / (w_sink + w_global + w_local)
+
+
+def gated_table_step(q_group, K, V, tables, n, k, r, a, gamma, kbar, vbar, sigma2_hat, eps, n_recent=0, n_sink=0,
+                     n_local=6):
+    """Alg. 1 in full for one KV group: heads whose sparsity ratio exceeds eps return vbar, select nothing
+    and leave their tables as they are (steps 2-4 skipped); the others run table_step's lines, with the
+    candidate set being the union over the heads that are not bypassed."""
+    G = len(q_group)
+    rho = [sparsity_ratio(q_group[h], K, n, kbar, sigma2_hat[h], n_sink, n_local) for h in range(G)]
+    gate = [rh > eps for rh in rho]
+    live = [h for h in range(G) if not gate[h]]
+    C = group_candidates([tables[h] for h in live], n, a, r, n_recent, n_sink)
+    idx, sc, out, new_tables = [], [], [], []
+    for h in range(G):
+        if gate[h]:
+            idx.append(np.zeros(0, dtype=np.int64))
+            sc.append(np.zeros(0))
+            out.append(np.asarray(vbar, dtype=np.float64))
+            new_tables.append((np.asarray(tables[h][0], dtype=np.float64), np.asarray(tables[h][1], dtype=np.float64)))
+            continue
+        s = _scores(q_group[h], K, C) if len(C) else np.zeros(0)
+        I_h, s_h = _k_best(s, C, min(k, len(C)))
+        idx.append(I_h)
+        sc.append(s_h)
+        if len(I_h):
+            e = np.exp(s_h - np.max(s_h))
+            out.append((e / np.sum(e)) @ np.asarray(V[I_h], dtype=np.float64))
+        else:
+            out.append(np.zeros(np.asarray(V).shape[-1]))
+        new_tables.append(update_tables(tables[h][0], tables[h][1], n, I_h, s_h, gamma, n_sink))
+    return dict(rho=np.array(rho), gate=np.array(gate), cand=C, topk_idx=idx, topk_score=sc, out=np.array(out),
+                tables=new_tables)

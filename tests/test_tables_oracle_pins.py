@@ -252,3 +252,86 @@ def test_table_step_selects_the_best_candidates_and_attends_over_them():
         nv, ns = res["tables"][h]
         assert len(nv) == n + 1
         assert nv.sum() == pytest.approx(0.95 * tables[h][0].sum() + 0.5)
+
+
+# ----------------------------------------------------------------------------- Eq. 5-6 (head sparsity), priors
+def test_priors_are_plain_means_and_logit_variance():
+    rng = np.random.default_rng(20)
+    n, d, n_sink = 300, 16, 4
+    K, V, q = rng.standard_normal((n + 3, d)), rng.standard_normal((n + 3, d)), rng.standard_normal(d) * 1.7
+    kbar, vbar, s2 = tor.priors(q, K, V, n, n_sink)
+    tK, tV = torch.from_numpy(K[n_sink:n]), torch.from_numpy(V[n_sink:n])
+    np.testing.assert_allclose(kbar, tK.mean(0).numpy(), rtol=1e-13)
+    np.testing.assert_allclose(vbar, tV.mean(0).numpy(), rtol=1e-13)
+    logits = (tK @ torch.from_numpy(q)) / math.sqrt(d)
+    assert s2 == pytest.approx(float(torch.var(logits, unbiased=False)) / float(q @ q), rel=1e-12)
+
+
+def test_global_term_is_exact_for_identical_keys_and_lognormal_in_general():
+    rng = np.random.default_rng(21)
+    d, n, n_sink = 16, 5000, 2
+    q = rng.standard_normal(d)
+    # (a) every offloaded key equal: sigma = 0 and n * exp(q.kbar/sqrt(d)) is the exact sum of the weights
+    K = np.tile(rng.standard_normal(d), (n, 1))
+    K[:n_sink] = rng.standard_normal((n_sink, d)) * 3
+    kbar, _, s2 = tor.priors(q, K, K, n, n_sink)
+    assert s2 == pytest.approx(0.0, abs=1e-25)
+    w = np.exp((K[:n] @ q) / math.sqrt(d))
+    rho = tor.sparsity_ratio(q, K, n, kbar, s2, n_sink, n_local=0)
+    assert rho == pytest.approx(w[:n_sink].sum() / (w[:n_sink].sum() + n * w[n_sink]), rel=1e-12)
+    # (b) Gaussian logits: geometric mean * exp(sigma^2/2) estimates the arithmetic mean of the weights (App. B.1)
+    K = rng.standard_normal((n, d))
+    kbar, _, s2 = tor.priors(q, K, K, n, n_sink)
+    est = n * math.exp(float(kbar @ q) / math.sqrt(d) + float(q @ q) * s2 / 2)
+    true = np.exp((K[n_sink:n] @ q) / math.sqrt(d)).sum()
+    assert est == pytest.approx(true, rel=0.1)
+    # the variance term matters: without it the estimate is the geometric mean, well below the truth
+    assert n * math.exp(float(kbar @ q) / math.sqrt(d)) < 0.8 * true
+
+
+def test_sparsity_ratio_definition_monotone_and_limits():
+    rng = np.random.default_rng(22)
+    d, n, n_sink = 8, 200, 1
+    K = rng.standard_normal((n, d))
+    q = rng.standard_normal(d)
+    kbar, _, s2 = tor.priors(q, K, K, n, n_sink)
+    prev = 0.0
+    for scale in (0.0, 1.0, 3.0, 10.0, 40.0):          # a sink key ever more aligned with the query
+        K2 = K.copy()
+        K2[0] = scale * q / np.linalg.norm(q)
+        rho = tor.sparsity_ratio(q, K2, n, kbar, s2, n_sink)
+        assert 0.0 < rho <= 1.0 and rho >= prev
+        prev = rho
+    assert prev > 0.999
+    # the local term is the plain sum over the newest six rows
+    w = np.exp((K @ q) / math.sqrt(d))
+    r6 = tor.sparsity_ratio(q, K, n, kbar, s2, n_sink, n_local=6)
+    r0 = tor.sparsity_ratio(q, K, n, kbar, s2, n_sink, n_local=0)
+    assert 1 / r6 - 1 / r0 == pytest.approx(w[n - 6:].sum() / w[0], rel=1e-10)
+
+
+def test_gated_step_bypasses_sparse_heads_and_leaves_their_tables():
+    rng = np.random.default_rng(23)
+    n, d, G, k, n_sink = 150, 16, 3, 8, 2
+    K, V = rng.standard_normal((n + 1, d)), rng.standard_normal((n + 1, d))
+    q = rng.standard_normal((G, d))
+    u = q[1] / np.linalg.norm(q[1])
+    for h in (0, 2):
+        q[h] -= (q[h] @ u) * u                          # the other heads do not see that sink
+    K[0] = 30.0 * u                                     # head 1 looks at the sink only
+    tables = [(rng.gamma(0.1, size=n), rng.gamma(0.1, size=n)) for _ in range(G)]
+    for t in tables:
+        t[0][:n_sink] = 0
+        t[1][:n_sink] = 0
+    kbar, vbar, _ = tor.priors(q[0], K, V, n, n_sink)
+    s2 = [tor.priors(q[h], K, V, n, n_sink)[2] for h in range(G)]
+    res = tor.gated_table_step(q, K, V, tables, n, k, 1, 0.2, 0.9, kbar, vbar, s2, 0.85, n_recent=1, n_sink=n_sink)
+    assert list(res["gate"]) == [False, True, False] and res["rho"][1] > 0.85
+    np.testing.assert_array_equal(res["out"][1], vbar)
+    assert len(res["topk_idx"][1]) == 0
+    np.testing.assert_array_equal(res["tables"][1][0], tables[1][0])
+    # the others behave as in table_step over the candidates of the live heads only
+    ref = tor.table_step(q[[0, 2]], K, V, [tables[0], tables[2]], n, k, 1, 0.2, 0.9, n_recent=1, n_sink=n_sink)
+    np.testing.assert_array_equal(res["cand"], ref["cand"])
+    np.testing.assert_array_equal(res["topk_idx"][2], ref["topk_idx"][1])
+    np.testing.assert_allclose(res["out"][0], ref["out"][0], rtol=1e-14)
