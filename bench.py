@@ -53,7 +53,7 @@ def parse_args():
 class Runner:
     """Device state of one workload and the step loop."""
 
-    def __init__(self, name, table_mode=False, n_sink=0):
+    def __init__(self, name, table_mode=False, n_sink=0, gated=False):
         import numpy as np
         import torch
 
@@ -70,6 +70,12 @@ class Runner:
                         kv_dtype=spec.kv_dtype, max_seq_len=case.Lcap, max_k=case.kmax, radius=spec.r,
                         n_recent=1, n_sink=n_sink, table_mode=table_mode, table_decay=0.95, table_a=0.2)
         self.table_mode = table_mode
+        self.gated = gated
+        if gated:        # prefill priors of the bypass (Sec. 4.2 "Prefilling"), from the step-0 query
+            self.kbar = torch.zeros((spec.B, spec.Hkv, spec.D), dtype=torch.float32, device=self.dev)
+            self.vbar = torch.zeros_like(self.kbar)
+            self.sigma2 = torch.zeros((spec.B, spec.Hq), dtype=torch.float32, device=self.dev)
+            self.gate = torch.zeros((spec.B, spec.Hq), dtype=torch.int32, device=self.dev)
         to = lambda a: torch.from_numpy(np.ascontiguousarray(a)).to(self.dev)
         self.q = to(case.q)                                                 # [T+1, B, Hq, D]
         self.seq = to(np.stack([case.seq_lens(t) for t in range(spec.T + 1)]))  # [T+1, B]
@@ -104,7 +110,11 @@ class Runner:
         if self.table_mode:
             if t == 1:      # (re)start of the chain: Eq. 4 tables from the step-0 query
                 self.ctx.lfps_tables_init(self.q[0], self.views[0])
-            self.ctx.lfps_table_step(self.q[t], self.views[t], self.k, dst, self.out)
+            if self.gated:
+                self.ctx.lfps_table_step_gated(self.q[t], self.views[t], self.k, self.kbar, self.vbar, self.sigma2, 6, 0.85,
+                                               dst, self.out, None, self.gate)
+            else:
+                self.ctx.lfps_table_step(self.q[t], self.views[t], self.k, dst, self.out)
         else:
             self.ctx.lfps_step(self.q[t], self.views[t], self.prev, self.k, dst, self.out)
         self.prev = dst
@@ -306,6 +316,13 @@ def measure_tables(name, steps, warmup):
                           "frac_of_hbm_peak": round(scan_bytes / (scan_us * 1e-6) / 1e9 / HBM_PEAK_GBS, 4) if scan_us > 0 else None},
            "heads": heads}
     r.close()
+    # the same with the head-sparsity bypass in front (Eq. 5-6, eps = 0.85, six local rows)
+    rg = Runner(name, table_mode=True, n_sink=4, gated=True)
+    rg.ctx.lfps_priors(rg.q[0], rg.views[0], rg.kbar, rg.vbar, rg.sigma2)
+    sec_g = rg.run_timed(steps, max(warmup, 1))
+    res["with_bypass"] = {"ms_per_step": round(sec_g * 1e3, 4), "eps": 0.85, "n_local": 6,
+                          "bypassed_head_frac_last_step": round(float(rg.gate.float().mean().item()), 4)}
+    rg.close()
     return res
 
 

@@ -153,8 +153,7 @@ int lfps_exact_topk(lfps_ctx* ctx, const float* q, const lfps_kv* kv, const int3
 /* ---- LFPS with score tables: the paper's own candidate rule (Sec. 4.2, Alg. 1 lines 5-9) --------------
  * The context (created with table_mode = 1) keeps, per query head, a vertical and a slash score table over
  * positions.  Sink rows (< n_sink) are outside the tables, as in the paper: always candidates, never
- * counted or updated.  Radius must be <= 30.  One row is expected to be appended between steps (the
- * statistics of a step are those of the previous update plus one new position). */
+ * counted or updated.  Radius must be <= 30.  Rows appended since the last update enter the tables as zeros. */
 
 /* Eq. 4 with s = 1: both tables = (softmax over rows [n_sink, n_b) of q.K/sqrt(D)) / (2 (1 - gamma)),
  * from the one query q [B, Hq, D] (e.g. the last prefill query). */
@@ -179,6 +178,25 @@ int lfps_table_update(lfps_ctx* ctx, const int32_t* idx, const float* idx_score,
  * when the candidate set is smaller: padded with -1), sparse attention, table update. */
 int lfps_table_step(lfps_ctx* ctx, const float* q, const lfps_kv* kv, const int32_t* k, int32_t* topk_idx,
                     float* topk_score, float* out, void* stream);
+
+/* ---- Head sparsity estimate and bypass (Sec. 4.2 stage 1, Eq. 5-6, App. B.1; Alg. 1 lines 1-4) ------------
+ * Priors of the prefill stage (Sec. 4.2 "Prefilling", last paragraph), from the last prefill query q:
+ *   kbar, vbar  [B, Hkv, D] fp32  mean K row / V row over rows [n_sink, n_b)
+ *   sigma2_hat  [B, Hq]     fp32  variance over those rows of q.K_i/sqrt(D), divided by |q|^2 */
+int lfps_priors(lfps_ctx* ctx, const float* q, const lfps_kv* kv, float* kbar, float* vbar, float* sigma2_hat,
+                void* stream);
+/* rho[b,h] = w_sink / (w_sink + w_global + w_local)  (Eq. 6) with
+ *   w_sink = sum_{i < n_sink} exp(q.K_i/sqrt(D)),  w_local = the same sum over the newest n_local rows (the paper: 6),
+ *   w_global = n_b * exp(q.kbar/sqrt(D) + |q|^2 sigma2_hat / 2);   gate[b,h] = rho > eps (the paper: 0.85).
+ * rho [B, Hq] fp32 or NULL; gate [B, Hq] int32. */
+int lfps_head_sparsity(lfps_ctx* ctx, const float* q, const lfps_kv* kv, const float* kbar, const float* sigma2_hat,
+                       int32_t n_local, float eps, float* rho, int32_t* gate, void* stream);
+/* lfps_table_step with the bypass in front (Alg. 1 in full): a head with rho > eps outputs vbar[b, g(h)],
+ * selects nothing (its topk_idx row is -1), proposes no candidates and keeps its tables as they are.
+ * gate_out [B, Hq] int32 or NULL receives the marks. */
+int lfps_table_step_gated(lfps_ctx* ctx, const float* q, const lfps_kv* kv, const int32_t* k, const float* kbar,
+                          const float* vbar, const float* sigma2_hat, int32_t n_local, float eps, int32_t* topk_idx,
+                          float* topk_score, float* out, int32_t* gate_out, void* stream);
 
 int lfps_set_filter(lfps_ctx* ctx, int32_t on);
 int lfps_reset_history(lfps_ctx* ctx, void* stream);

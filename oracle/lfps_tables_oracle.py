@@ -240,7 +240,9 @@ def gated_table_step(q_group, K, V, tables, n, k, r, a, gamma, kbar, vbar, sigma
             idx.append(np.zeros(0, dtype=np.int64))
             sc.append(np.zeros(0))
             out.append(np.asarray(vbar, dtype=np.float64))
-            new_tables.append((np.asarray(tables[h][0], dtype=np.float64), np.asarray(tables[h][1], dtype=np.float64)))
+            # unchanged; the position the next step appends has no history yet
+            new_tables.append((np.r_[np.asarray(tables[h][0][:n], dtype=np.float64), 0.0],
+                               np.r_[np.asarray(tables[h][1][:n], dtype=np.float64), 0.0]))
             continue
         s = _scores(q_group[h], K, C) if len(C) else np.zeros(0)
         I_h, s_h = _k_best(s, C, min(k, len(C)))

@@ -74,6 +74,10 @@ def _load() -> ctypes.CDLL:
         "lfps_table_candidates": (ctypes.c_int, [P, VP, VP, VP, VP]),
         "lfps_table_update": (ctypes.c_int, [P, VP, VP, VP, VP, VP]),
         "lfps_table_step": (ctypes.c_int, [P, VP, ctypes.POINTER(lfps_kv), VP, VP, VP, VP, VP]),
+        "lfps_priors": (ctypes.c_int, [P, VP, ctypes.POINTER(lfps_kv), VP, VP, VP, VP]),
+        "lfps_head_sparsity": (ctypes.c_int, [P, VP, ctypes.POINTER(lfps_kv), VP, VP, I32, ctypes.c_float, VP, VP, VP]),
+        "lfps_table_step_gated": (ctypes.c_int, [P, VP, ctypes.POINTER(lfps_kv), VP, VP, VP, VP, I32, ctypes.c_float,
+                                                 VP, VP, VP, VP, VP]),
     }
     for name, (res, args) in sig.items():
         fn = getattr(lib, name)
@@ -276,6 +280,38 @@ class Lfps:
             _ptr(topk_idx, torch.int32, (self.B, self.Hq, self.kmax), "topk_idx", d),
             _ptr(topk_score, torch.float32, (self.B, self.Hq, self.kmax), "topk_score", d),
             _ptr(out, torch.float32, (self.B, self.Hq, self.D), "out", d), self._stream()))
+
+    # ------------------------------------------------------------------ head sparsity bypass
+    def lfps_priors(self, q, kv: lfps_kv, kbar, vbar, sigma2_hat):
+        d = self.device
+        self._check(_lib.lfps_priors(
+            self._ctx, _ptr(q, torch.float32, (self.B, self.Hq, self.D), "q", d), ctypes.byref(kv),
+            _ptr(kbar, torch.float32, (self.B, self.Hkv, self.D), "kbar", d),
+            _ptr(vbar, torch.float32, (self.B, self.Hkv, self.D), "vbar", d),
+            _ptr(sigma2_hat, torch.float32, (self.B, self.Hq), "sigma2_hat", d), self._stream()))
+
+    def lfps_head_sparsity(self, q, kv: lfps_kv, kbar, sigma2_hat, n_local, eps, rho, gate):
+        d = self.device
+        self._check(_lib.lfps_head_sparsity(
+            self._ctx, _ptr(q, torch.float32, (self.B, self.Hq, self.D), "q", d), ctypes.byref(kv),
+            _ptr(kbar, torch.float32, (self.B, self.Hkv, self.D), "kbar", d),
+            _ptr(sigma2_hat, torch.float32, (self.B, self.Hq), "sigma2_hat", d), int(n_local), float(eps),
+            _ptr(rho, torch.float32, (self.B, self.Hq), "rho", d),
+            _ptr(gate, torch.int32, (self.B, self.Hq), "gate", d), self._stream()))
+
+    def lfps_table_step_gated(self, q, kv: lfps_kv, k, kbar, vbar, sigma2_hat, n_local, eps, topk_idx, out,
+                              topk_score=None, gate_out=None):
+        d = self.device
+        self._check(_lib.lfps_table_step_gated(
+            self._ctx, _ptr(q, torch.float32, (self.B, self.Hq, self.D), "q", d), ctypes.byref(kv),
+            _ptr(k, torch.int32, (self.B,), "k", d),
+            _ptr(kbar, torch.float32, (self.B, self.Hkv, self.D), "kbar", d),
+            _ptr(vbar, torch.float32, (self.B, self.Hkv, self.D), "vbar", d),
+            _ptr(sigma2_hat, torch.float32, (self.B, self.Hq), "sigma2_hat", d), int(n_local), float(eps),
+            _ptr(topk_idx, torch.int32, (self.B, self.Hq, self.kmax), "topk_idx", d),
+            _ptr(topk_score, torch.float32, (self.B, self.Hq, self.kmax), "topk_score", d),
+            _ptr(out, torch.float32, (self.B, self.Hq, self.D), "out", d),
+            _ptr(gate_out, torch.int32, (self.B, self.Hq), "gate_out", d), self._stream()))
 
     def lfps_set_filter(self, on: bool):
         self._check(_lib.lfps_set_filter(self._ctx, int(bool(on))))

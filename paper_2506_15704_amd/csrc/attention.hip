@@ -40,7 +40,8 @@ __global__ __launch_bounds__(kSparseWaves * 64) void k_sparse_attn(Shape s, cons
                                                                 const int32_t* __restrict__ idx,
                                                                 const float* __restrict__ idx_score,
                                                                 const int32_t* __restrict__ kk,
-                                                                float* __restrict__ out) {
+                                                                float* __restrict__ out,
+                                                                const int32_t* __restrict__ skip_if) {
   __shared__ float red[kSparseWaves][kD];
   __shared__ float redm[kSparseWaves], redl[kSparseWaves];
   // Workgroups are dealt to the 8 XCDs round-robin (workgroup i runs on XCD i % 8) and every XCD has
@@ -55,6 +56,7 @@ __global__ __launch_bounds__(kSparseWaves * 64) void k_sparse_attn(Shape s, cons
       bh = ((slot / s.G) * 8 + xcd) * s.G + slot % s.G;
     }
   }
+  if (skip_if && skip_if[bh] != 0) return;            // bypassed head: the gate wrote its output row
   const int b = bh / s.Hq, h = bh % s.Hq, g = h / s.G;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int j = lane & 15, rs = lane >> 4;
@@ -146,13 +148,13 @@ __global__ __launch_bounds__(kSparseWaves * 64) void k_sparse_attn(Shape s, cons
 
 template <typename T>
 static hipError_t launch_sparse_t(const Shape& s, const KvView& kv, const int32_t* idx, const float* idx_score,
-                                  const int32_t* k, float* out, hipStream_t st) {
+                                  const int32_t* k, float* out, const int32_t* skip_if, hipStream_t st) {
   // as many waves per head as keep every head's workgroup resident at once (256 CUs x 32 waves)
   const int heads = s.B * s.Hq;
   const T* V = (const T*)kv.v;
 #define LFPS_LAUNCH_SPARSE(NW)                                                                                   \
   hipLaunchKernelGGL((k_sparse_attn<T, NW>), dim3(heads), dim3(NW * 64), 0, st, s, V, kv.stride_b, kv.stride_h, \
-                     kv.stride_n, kv.seq_lens, idx, idx_score, k, out)
+                     kv.stride_n, kv.seq_lens, idx, idx_score, k, out, skip_if)
   if (heads * 16 <= 8192) LFPS_LAUNCH_SPARSE(16);
   else if (heads * 8 <= 8192) LFPS_LAUNCH_SPARSE(8);
   else LFPS_LAUNCH_SPARSE(4);
@@ -161,9 +163,9 @@ static hipError_t launch_sparse_t(const Shape& s, const KvView& kv, const int32_
 }
 
 hipError_t launch_sparse_attn(const Shape& s, int dtype, const KvView& kv, const int32_t* idx, const float* idx_score,
-                              const int32_t* k, float* out, hipStream_t st) {
-  return dtype == LFPS_BF16 ? launch_sparse_t<uint16_t>(s, kv, idx, idx_score, k, out, st)
-                            : launch_sparse_t<float>(s, kv, idx, idx_score, k, out, st);
+                              const int32_t* k, float* out, const int32_t* skip_if, hipStream_t st) {
+  return dtype == LFPS_BF16 ? launch_sparse_t<uint16_t>(s, kv, idx, idx_score, k, out, skip_if, st)
+                            : launch_sparse_t<float>(s, kv, idx, idx_score, k, out, skip_if, st);
 }
 
 // ============================================================================ full attention

@@ -34,6 +34,7 @@ struct lfps_ctx {
   double tab_scale;    // host copy of the tables' scale factor (all heads share it): decides when to fold it back
   int tab_updates;     // updates since the last import / init
   int tab_ready;
+  int32_t* gate;       // [B, Hq] bypass marks of the current gated step
   int32_t* cand;       // [B, Hkv, cand_cap]
   int32_t* cand_count; // [B, Hkv]
   float* sel_score;    // [B, Hq, kmax]
@@ -130,7 +131,7 @@ int check_config(const lfps_config* c, Sizes* z, char* err, size_t errn) {
   z->tstate_b = c->table_mode ? align256(heads * kTableStateDoubles * 8) : 0;
   z->tflag_b = c->table_mode ? align256(heads * z->flag_words * 4) : 0;
   z->total = z->score_b + z->cand_b + z->count_b + z->sel_b + z->part_b + z->slot_b + z->seg_b + z->thr_b +
-             z->redo_b + 256 + z->tver_b + z->tsla_b + z->tstate_b + 2 * z->tflag_b;
+             z->redo_b + 256 + z->tver_b + z->tsla_b + z->tstate_b + 2 * z->tflag_b + z->thr_b /* gate marks */;
   return LFPS_OK;
 }
 
@@ -276,9 +277,11 @@ int lfps_create(const lfps_config* cfg, lfps_ctx** out) {
     c->tab_f0 = (uint32_t*)p;
     p += z.tflag_b;
     c->tab_fm = (uint32_t*)p;
+    p += z.tflag_b;
     c->flag_words = z.flag_words;
     c->tab_scale = 1.0;
   }
+  c->gate = (int32_t*)p;
   c->nseg = z.nseg;
   c->filter_on = z.slot_b ? 1 : 0;
   e = hipMemset(c->flags, 0, 256);
@@ -286,6 +289,7 @@ int lfps_create(const lfps_config* cfg, lfps_ctx** out) {
   if (e == hipSuccess) e = hipMemset(c->thr_state, 0xFF, (size_t)z.thr_b);   // all-ones = NaN: "no history"
   if (e == hipSuccess && cfg->table_mode)
     e = hipMemset(c->tab_ver, 0, (size_t)(z.tver_b + z.tsla_b + z.tstate_b + 2 * z.tflag_b));
+  if (e == hipSuccess) e = hipMemset(c->gate, 0, (size_t)z.thr_b);
   if (e == hipSuccess) e = configure_candidates(s);
   if (e == hipSuccess) e = configure_select(s);
   if (e == hipSuccess && c->filter_on) e = filter_score_blocks(s, &c->filter_blocks);
@@ -348,7 +352,7 @@ int lfps_score_topk(lfps_ctx* ctx, const float* q, const lfps_kv* kv, const int3
   LAUNCH(ctx, LFPS_KERNEL_GATHER_SCORE, st,
          launch_group_score(s, ctx->cfg.kv_dtype, q, v, cand, cand_count, sc, stride, nullptr, st));
   LAUNCH(ctx, LFPS_KERNEL_SELECT, st,
-         launch_select(s, sc, stride, cand, cand_count, k, topk_idx, topk_score, nullptr, nullptr, st));
+         launch_select(s, sc, stride, cand, cand_count, k, topk_idx, topk_score, nullptr, nullptr, nullptr, st));
   return LFPS_OK;
 }
 
@@ -366,7 +370,8 @@ int lfps_sparse_attn(lfps_ctx* ctx, const float* q, const lfps_kv* kv, const int
     LAUNCH(ctx, LFPS_KERNEL_HEAD_SCORE, st, launch_head_score(s, ctx->cfg.kv_dtype, q, v, idx, k, ctx->sel_score, st));
     idx_score = ctx->sel_score;
   }
-  LAUNCH(ctx, LFPS_KERNEL_SPARSE_ATTN, st, launch_sparse_attn(s, ctx->cfg.kv_dtype, v, idx, idx_score, k, out, st));
+  LAUNCH(ctx, LFPS_KERNEL_SPARSE_ATTN, st,
+         launch_sparse_attn(s, ctx->cfg.kv_dtype, v, idx, idx_score, k, out, nullptr, st));
   return LFPS_OK;
 }
 
@@ -375,7 +380,7 @@ int lfps_sparse_attn(lfps_ctx* ctx, const float* q, const lfps_kv* kv, const int
 // left short (both launches exit at once when no head is marked).  The candidates kernel of the same
 // step has cleared the marks and laid the groups on the line (group_start, line_total).
 static int score_and_select(lfps_ctx* ctx, const float* q, const KvView& v, const int32_t* k, int32_t* topk_idx,
-                            float* sel, hipStream_t st) {
+                            float* sel, const int32_t* skip_if, hipStream_t st) {
   const Shape& s = ctx->shape;
   int64_t* line_total = ctx->group_start + (int64_t)s.B * s.Hkv;
   const int32_t *only_g = nullptr, *only_h = nullptr;
@@ -387,7 +392,7 @@ static int score_and_select(lfps_ctx* ctx, const float* q, const KvView& v, cons
     LAUNCH(ctx, LFPS_KERNEL_FILTER_SELECT, st,
            launch_filter_select(s, ctx->score, ctx->slot, s.score_stride, ctx->seg_count, ctx->flags + 1, ctx->nseg,
                                 ctx->cand_count, ctx->group_start, line_total, k, topk_idx, sel, ctx->thr_state,
-                                ctx->redo_g, ctx->redo_h, st));
+                                ctx->redo_g, ctx->redo_h, skip_if, st));
     only_g = ctx->redo_g;
     only_h = ctx->redo_h;
   }
@@ -396,7 +401,7 @@ static int score_and_select(lfps_ctx* ctx, const float* q, const KvView& v, cons
                             only_g, st));
   LAUNCH(ctx, LFPS_KERNEL_SELECT, st,
          launch_select(s, ctx->score, s.score_stride, ctx->cand, ctx->cand_count, k, topk_idx, sel, only_h,
-                       ctx->thr_state, st));
+                       ctx->thr_state, skip_if, st));
   return LFPS_OK;
 }
 
@@ -419,9 +424,10 @@ int lfps_step(lfps_ctx* ctx, const float* q, const lfps_kv* kv, const int32_t* p
   LAUNCH(ctx, LFPS_KERNEL_CANDIDATES, st,
          launch_candidates(s, prev_topk, k, v.seq_lens, ctx->cand, ctx->cand_count, ctx->flags, ctx->redo_g,
                            ctx->redo_h, ctx->filter_on ? ctx->group_start : nullptr, line_total, st));
-  rc = score_and_select(ctx, q, v, k, topk_idx, sel, st);
+  rc = score_and_select(ctx, q, v, k, topk_idx, sel, nullptr, st);
   if (rc != LFPS_OK) return rc;
-  LAUNCH(ctx, LFPS_KERNEL_SPARSE_ATTN, st, launch_sparse_attn(s, ctx->cfg.kv_dtype, v, topk_idx, sel, k, out, st));
+  LAUNCH(ctx, LFPS_KERNEL_SPARSE_ATTN, st,
+         launch_sparse_attn(s, ctx->cfg.kv_dtype, v, topk_idx, sel, k, out, nullptr, st));
   return LFPS_OK;
 }
 
@@ -452,7 +458,7 @@ int lfps_exact_topk(lfps_ctx* ctx, const float* q, const lfps_kv* kv, const int3
          launch_group_score(s, ctx->cfg.kv_dtype, q, v, nullptr, nullptr, ctx->score, s.score_stride, nullptr, st));
   LAUNCH(ctx, LFPS_KERNEL_SELECT, st,
          launch_select(s, ctx->score, s.score_stride, nullptr, v.seq_lens, k, topk_idx, topk_score, nullptr, nullptr,
-                       st));
+                       nullptr, st));
   return LFPS_OK;
 }
 
@@ -482,7 +488,7 @@ int lfps_tables_init(lfps_ctx* ctx, const float* q, const lfps_kv* kv, void* str
   LAUNCH(ctx, LFPS_KERNEL_DENSE_SCORE, st,
          launch_group_score(s, ctx->cfg.kv_dtype, q, v, nullptr, nullptr, ctx->score, s.score_stride, nullptr, st));
   hipError_t e = launch_table_init(s, ctx->tab_ver, ctx->tab_sla, ctx->tab_state, v.seq_lens, ctx->score,
-                                   s.score_stride, (double)ctx->cfg.table_decay, (double)ctx->cfg.table_a, st);
+                                   s.score_stride, (double)ctx->cfg.table_decay, st);
   if (e != hipSuccess) return fail(ctx, LFPS_EHIP, "lfps_tables_init", e);
   ctx->tab_scale = 1.0;
   ctx->tab_updates = 0;
@@ -497,7 +503,7 @@ int lfps_tables_import(lfps_ctx* ctx, const float* phi_ver, const float* phi_sla
   int rc = need_tables(ctx, "lfps_tables_import", false);
   if (rc != LFPS_OK) return rc;
   hipError_t e = launch_table_import(ctx->shape, ctx->tab_ver, ctx->tab_sla, ctx->tab_state, seq_lens, phi_ver,
-                                     phi_sla, (double)ctx->cfg.table_a, (hipStream_t)stream);
+                                     phi_sla, (hipStream_t)stream);
   if (e != hipSuccess) return fail(ctx, LFPS_EHIP, "lfps_tables_import", e);
   ctx->tab_scale = 1.0;
   ctx->tab_updates = 0;
@@ -517,7 +523,7 @@ int lfps_tables_export(lfps_ctx* ctx, double* phi_ver, double* phi_sla, const in
 }
 
 static int table_candidates_impl(lfps_ctx* ctx, const int32_t* seq_lens, int32_t* cand, int32_t* cand_count,
-                                 bool for_step, hipStream_t st) {
+                                 bool for_step, const int32_t* gate, hipStream_t st) {
   const Shape& s = ctx->shape;
   if (ctx->tab_scale < 1e-20) {          // fold the accumulated decay back into the stored entries
     hipError_t e = launch_table_renorm(s, ctx->tab_ver, ctx->tab_sla, ctx->tab_state, st);
@@ -526,7 +532,7 @@ static int table_candidates_impl(lfps_ctx* ctx, const int32_t* seq_lens, int32_t
   }
   LAUNCH(ctx, LFPS_KERNEL_TABLE_FLAGS, st,
          launch_table_flags(s, ctx->tab_ver, ctx->tab_sla, ctx->tab_state, seq_lens, ctx->tab_f0, ctx->tab_fm,
-                            ctx->flag_words, st));
+                            ctx->flag_words, (double)ctx->cfg.table_a, gate, st));
   LAUNCH(ctx, LFPS_KERNEL_TABLE_CANDIDATES, st,
          launch_table_candidates(s, ctx->tab_f0, ctx->tab_fm, ctx->flag_words, seq_lens, cand, cand_count, ctx->flags,
                                  for_step ? ctx->redo_g : nullptr, for_step ? ctx->redo_h : nullptr,
@@ -536,13 +542,13 @@ static int table_candidates_impl(lfps_ctx* ctx, const int32_t* seq_lens, int32_t
 }
 
 static int table_update_impl(lfps_ctx* ctx, const int32_t* idx, const float* idx_score, const int32_t* k,
-                             const int32_t* seq_lens, hipStream_t st) {
+                             const int32_t* seq_lens, const int32_t* gate, hipStream_t st) {
   const Shape& s = ctx->shape;
   if (ctx->tab_updates >= s.Lcap - 1)
     return fail(ctx, LFPS_ECAP, "lfps_table_update: max_seq_len - 1 updates since the last import/init");
   LAUNCH(ctx, LFPS_KERNEL_TABLE_UPDATE, st,
          launch_table_update(s, ctx->tab_ver, ctx->tab_sla, ctx->tab_state, seq_lens, idx, idx_score, k,
-                             (double)ctx->cfg.table_decay, (double)ctx->cfg.table_a, st));
+                             (double)ctx->cfg.table_decay, gate, st));
   ctx->tab_scale *= (double)ctx->cfg.table_decay;
   ctx->tab_updates += 1;
   return LFPS_OK;
@@ -553,7 +559,7 @@ int lfps_table_candidates(lfps_ctx* ctx, const int32_t* seq_lens, int32_t* cand,
   if (!seq_lens || !cand || !cand_count) return fail(ctx, LFPS_EINVAL, "lfps_table_candidates: NULL argument");
   int rc = need_tables(ctx, "lfps_table_candidates", true);
   if (rc != LFPS_OK) return rc;
-  return table_candidates_impl(ctx, seq_lens, cand, cand_count, false, (hipStream_t)stream);
+  return table_candidates_impl(ctx, seq_lens, cand, cand_count, false, nullptr, (hipStream_t)stream);
 }
 
 int lfps_table_update(lfps_ctx* ctx, const int32_t* idx, const float* idx_score, const int32_t* k,
@@ -562,7 +568,20 @@ int lfps_table_update(lfps_ctx* ctx, const int32_t* idx, const float* idx_score,
   if (!idx || !idx_score || !k || !seq_lens) return fail(ctx, LFPS_EINVAL, "lfps_table_update: NULL argument");
   int rc = need_tables(ctx, "lfps_table_update", true);
   if (rc != LFPS_OK) return rc;
-  return table_update_impl(ctx, idx, idx_score, k, seq_lens, (hipStream_t)stream);
+  return table_update_impl(ctx, idx, idx_score, k, seq_lens, nullptr, (hipStream_t)stream);
+}
+
+static int table_step_impl(lfps_ctx* ctx, const float* q, const KvView& v, const int32_t* k, int32_t* topk_idx,
+                           float* topk_score, float* out, const int32_t* gate, hipStream_t st) {
+  const Shape& s = ctx->shape;
+  float* sel = topk_score ? topk_score : ctx->sel_score;
+  int rc = table_candidates_impl(ctx, v.seq_lens, ctx->cand, ctx->cand_count, true, gate, st);
+  if (rc != LFPS_OK) return rc;
+  rc = score_and_select(ctx, q, v, k, topk_idx, sel, gate, st);
+  if (rc != LFPS_OK) return rc;
+  LAUNCH(ctx, LFPS_KERNEL_SPARSE_ATTN, st,
+         launch_sparse_attn(s, ctx->cfg.kv_dtype, v, topk_idx, sel, k, out, gate, st));
+  return table_update_impl(ctx, topk_idx, sel, k, v.seq_lens, gate, st);
 }
 
 int lfps_table_step(lfps_ctx* ctx, const float* q, const lfps_kv* kv, const int32_t* k, int32_t* topk_idx,
@@ -574,15 +593,60 @@ int lfps_table_step(lfps_ctx* ctx, const float* q, const lfps_kv* kv, const int3
   KvView v;
   rc = check_kv(ctx, kv, true, &v);
   if (rc != LFPS_OK) return rc;
+  return table_step_impl(ctx, q, v, k, topk_idx, topk_score, out, nullptr, (hipStream_t)stream);
+}
+
+// ---------------------------------------------------------------------------- head sparsity bypass
+int lfps_priors(lfps_ctx* ctx, const float* q, const lfps_kv* kv, float* kbar, float* vbar, float* sigma2_hat,
+                void* stream) {
+  if (!ctx) return LFPS_EINVAL;
+  if (!q || !kbar || !vbar || !sigma2_hat) return fail(ctx, LFPS_EINVAL, "lfps_priors: NULL argument");
+  KvView v;
+  int rc = check_kv(ctx, kv, true, &v);
+  if (rc != LFPS_OK) return rc;
   hipStream_t st = (hipStream_t)stream;
   const Shape& s = ctx->shape;
-  float* sel = topk_score ? topk_score : ctx->sel_score;
-  rc = table_candidates_impl(ctx, v.seq_lens, ctx->cand, ctx->cand_count, true, st);
+  hipError_t e = launch_prior_means(s, ctx->cfg.kv_dtype, v, kbar, vbar, st);
+  if (e != hipSuccess) return fail(ctx, LFPS_EHIP, "lfps_priors (means)", e);
+  LAUNCH(ctx, LFPS_KERNEL_DENSE_SCORE, st,
+         launch_group_score(s, ctx->cfg.kv_dtype, q, v, nullptr, nullptr, ctx->score, s.score_stride, nullptr, st));
+  e = launch_prior_variance(s, q, v.seq_lens, ctx->score, s.score_stride, sigma2_hat, st);
+  if (e != hipSuccess) return fail(ctx, LFPS_EHIP, "lfps_priors (variance)", e);
+  return LFPS_OK;
+}
+
+int lfps_head_sparsity(lfps_ctx* ctx, const float* q, const lfps_kv* kv, const float* kbar, const float* sigma2_hat,
+                       int32_t n_local, float eps, float* rho, int32_t* gate, void* stream) {
+  if (!ctx) return LFPS_EINVAL;
+  if (!q || !kbar || !sigma2_hat || !gate) return fail(ctx, LFPS_EINVAL, "lfps_head_sparsity: NULL argument");
+  if (n_local < 0) return fail(ctx, LFPS_EINVAL, "lfps_head_sparsity: n_local must be >= 0");
+  KvView v;
+  int rc = check_kv(ctx, kv, false, &v);
   if (rc != LFPS_OK) return rc;
-  rc = score_and_select(ctx, q, v, k, topk_idx, sel, st);
+  hipError_t e = launch_head_sparsity(ctx->shape, ctx->cfg.kv_dtype, q, v, kbar, sigma2_hat, n_local, eps, rho, gate,
+                                      nullptr, nullptr, nullptr, nullptr, (hipStream_t)stream);
+  if (e != hipSuccess) return fail(ctx, LFPS_EHIP, "lfps_head_sparsity", e);
+  return LFPS_OK;
+}
+
+int lfps_table_step_gated(lfps_ctx* ctx, const float* q, const lfps_kv* kv, const int32_t* k, const float* kbar,
+                          const float* vbar, const float* sigma2_hat, int32_t n_local, float eps, int32_t* topk_idx,
+                          float* topk_score, float* out, int32_t* gate_out, void* stream) {
+  if (!ctx) return LFPS_EINVAL;
+  if (!q || !k || !kbar || !vbar || !sigma2_hat || !topk_idx || !out)
+    return fail(ctx, LFPS_EINVAL, "lfps_table_step_gated: NULL argument");
+  if (n_local < 0) return fail(ctx, LFPS_EINVAL, "lfps_table_step_gated: n_local must be >= 0");
+  int rc = need_tables(ctx, "lfps_table_step_gated", true);
   if (rc != LFPS_OK) return rc;
-  LAUNCH(ctx, LFPS_KERNEL_SPARSE_ATTN, st, launch_sparse_attn(s, ctx->cfg.kv_dtype, v, topk_idx, sel, k, out, st));
-  return table_update_impl(ctx, topk_idx, sel, k, v.seq_lens, st);
+  KvView v;
+  rc = check_kv(ctx, kv, true, &v);
+  if (rc != LFPS_OK) return rc;
+  hipStream_t st = (hipStream_t)stream;
+  int32_t* gate = gate_out ? gate_out : ctx->gate;
+  hipError_t e = launch_head_sparsity(ctx->shape, ctx->cfg.kv_dtype, q, v, kbar, sigma2_hat, n_local, eps, nullptr,
+                                      gate, vbar, topk_idx, topk_score, out, st);
+  if (e != hipSuccess) return fail(ctx, LFPS_EHIP, "lfps_table_step_gated (gate)", e);
+  return table_step_impl(ctx, q, v, k, topk_idx, topk_score, out, gate, st);
 }
 
 __global__ void k_fill_f32(float* p, int n, float v) {

@@ -64,15 +64,16 @@ hipError_t launch_filter_select(const Shape& s, const float* score, const int32_
                                 const int32_t* seg_count, const int32_t* seg_rows, int nseg,
                                 const int32_t* cand_count, const int64_t* group_start, int64_t* line_total,
                                 const int32_t* k, int32_t* topk_idx, float* topk_score,
-                                float* thr_state, int32_t* redo_g, int32_t* redo_h, hipStream_t st);
+                                float* thr_state, int32_t* redo_g, int32_t* redo_h, const int32_t* skip_if,
+                                hipStream_t st);
 
 // Per (b, h): the k_b best of score[b,h,0:count]; count = cand_count[b, g(h)] when cand != NULL,
 // else seq_lens[b].  Writes positions (ascending) and their scores.
 // only_if [B,Hq] (or NULL): heads whose entry is 0 are skipped.  thr_state [B,Hq] (or NULL) receives
-// each head's k-th best score.
+// each head's k-th best score.  skip_if [B,Hq] (or NULL): heads whose entry is not 0 are skipped (bypassed heads).
 hipError_t launch_select(const Shape& s, const float* score, int64_t score_stride, const int32_t* cand,
                          const int32_t* count, const int32_t* k, int32_t* topk_idx, float* topk_score,
-                         const int32_t* only_if, float* thr_state, hipStream_t st);
+                         const int32_t* only_if, float* thr_state, const int32_t* skip_if, hipStream_t st);
 
 // Scores of idx[b,h,0:k_b] rows against q[b,h] (one head at a time, no group sharing).
 hipError_t launch_head_score(const Shape& s, int dtype, const float* q, const KvView& kv, const int32_t* idx,
@@ -80,7 +81,7 @@ hipError_t launch_head_score(const Shape& s, int dtype, const float* q, const Kv
 
 // Sparse attention: one workgroup per (b, h), output row written directly.
 hipError_t launch_sparse_attn(const Shape& s, int dtype, const KvView& kv, const int32_t* idx, const float* idx_score,
-                              const int32_t* k, float* out, hipStream_t st);
+                              const int32_t* k, float* out, const int32_t* skip_if, hipStream_t st);
 
 // Full attention: split partials [B*Hkv, n_split, G, D+2] + merge.
 int full_attn_splits(const Shape& s);
@@ -93,21 +94,30 @@ hipError_t launch_full_merge(const Shape& s, const int32_t* seq_lens, const floa
 // entries; state [B*Hq, kTableStateDoubles]; f0 / fm [B*Hq, flag_words] bitmaps written by the scan.
 constexpr int kTableStateDoubles = 16;
 hipError_t launch_table_flags(const Shape& s, const float* tab_ver, const float* tab_sla, const double* state,
-                              const int32_t* seq_lens, uint32_t* f0, uint32_t* fm, int flag_words, hipStream_t st);
+                              const int32_t* seq_lens, uint32_t* f0, uint32_t* fm, int flag_words, double a,
+                              const int32_t* gate, hipStream_t st);
 hipError_t launch_table_candidates(const Shape& s, const uint32_t* f0, const uint32_t* fm, int flag_words,
                                    const int32_t* seq_lens, int32_t* cand, int32_t* cand_count, int32_t* flags,
                                    int32_t* redo_g, int32_t* redo_h, int64_t* group_start, int64_t* line_total,
                                    hipStream_t st);
 hipError_t launch_table_update(const Shape& s, float* tab_ver, float* tab_sla, double* state, const int32_t* seq_lens,
-                               const int32_t* idx, const float* sc, const int32_t* k, double gamma, double a,
+                               const int32_t* idx, const float* sc, const int32_t* k, double gamma, const int32_t* gate,
                                hipStream_t st);
 hipError_t launch_table_import(const Shape& s, float* tab_ver, float* tab_sla, double* state, const int32_t* seq_lens,
-                               const float* phi_ver, const float* phi_sla, double a, hipStream_t st);
+                               const float* phi_ver, const float* phi_sla, hipStream_t st);
 hipError_t launch_table_export(const Shape& s, const float* tab_ver, const float* tab_sla, const double* state,
                                const int32_t* seq_lens, double* phi_ver, double* phi_sla, hipStream_t st);
 hipError_t launch_table_renorm(const Shape& s, float* tab_ver, float* tab_sla, double* state, hipStream_t st);
 hipError_t launch_table_init(const Shape& s, float* tab_ver, float* tab_sla, double* state, const int32_t* seq_lens,
-                             const float* score, int64_t score_stride, double gamma, double a, hipStream_t st);
+                             const float* score, int64_t score_stride, double gamma, hipStream_t st);
+// Head sparsity (Eq. 5-6) and the prefill priors it needs; gate [B,Hq] marks bypassed heads, whose output
+// row (vbar) and index row (-1) the kernel writes when out != NULL.
+hipError_t launch_head_sparsity(const Shape& s, int dtype, const float* q, const KvView& kv, const float* kbar,
+                                const float* sigma2_hat, int n_local, float eps, float* rho, int32_t* gate,
+                                const float* vbar, int32_t* topk_idx, float* topk_score, float* out, hipStream_t st);
+hipError_t launch_prior_means(const Shape& s, int dtype, const KvView& kv, float* kbar, float* vbar, hipStream_t st);
+hipError_t launch_prior_variance(const Shape& s, const float* q, const int32_t* seq_lens, const float* score,
+                                 int64_t score_stride, float* sigma2_hat, hipStream_t st);
 
 // ---- small device helpers ------------------------------------------------------------
 __device__ __forceinline__ float bf16_lo(uint32_t w) { return __uint_as_float(w << 16); }

@@ -308,12 +308,14 @@ __global__ __launch_bounds__(kSelThreads) void k_select(Shape s, const float* __
                                                         const int32_t* __restrict__ kk, int32_t* __restrict__ topk_idx,
                                                         float* __restrict__ topk_score, int cache_elems,
                                                         const int32_t* __restrict__ only_if,
-                                                        float* __restrict__ thr_state) {
+                                                        float* __restrict__ thr_state,
+                                                        const int32_t* __restrict__ skip_if) {
   __shared__ SelectShared<kSelThreads> sm;
   extern __shared__ float cache[];
   const int bh = blockIdx.x, b = bh / s.Hq, h = bh % s.Hq, g = h / s.G;
   const int tid = threadIdx.x;
   if (only_if && only_if[bh] == 0) return;          // this head was already settled by the filtered pass
+  if (skip_if && skip_if[bh] != 0) return;          // bypassed head: its rows were written by the gate
   const bool gather = cand != nullptr;
   int c = gather ? count_arr[b * s.Hkv + g] : count_arr[b];
   const int c_max = gather ? s.cand_cap : s.Lcap;
@@ -364,7 +366,8 @@ __global__ __launch_bounds__(kFilterSelThreads) void k_filter_select(Shape s, co
                                                                float* __restrict__ topk_score,
                                                                float* __restrict__ thr_state,
                                                                int32_t* __restrict__ redo_g,
-                                                               int32_t* __restrict__ redo_h, int cap) {
+                                                               int32_t* __restrict__ redo_h, int cap,
+                                                               const int32_t* __restrict__ skip_if) {
   constexpr int NT = kFilterSelThreads, kSelWaves = NT / 64;
   constexpr int kPiecesPerThread = 4;              // nseg <= 1024
   __shared__ SelectShared<NT> sm;
@@ -376,6 +379,7 @@ __global__ __launch_bounds__(kFilterSelThreads) void k_filter_select(Shape s, co
   const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
   const int bg = b * s.Hkv + g;
   if (bh == 0 && tid == 0) *line_total = 0;          // the scoring pass that read it has finished
+  if (skip_if && skip_if[bh] != 0) return;           // bypassed head: its rows were written by the gate
   int raw[kPiecesPerThread];                         // piece counts of this head, masked once the geometry is known
 #pragma unroll
   for (int u = 0; u < kPiecesPerThread; ++u) {
@@ -533,12 +537,12 @@ hipError_t configure_select(const Shape& s) {
 
 hipError_t launch_select(const Shape& s, const float* score, int64_t score_stride, const int32_t* cand,
                          const int32_t* count, const int32_t* k, int32_t* topk_idx, float* topk_score,
-                         const int32_t* only_if, float* thr_state, hipStream_t st) {
+                         const int32_t* only_if, float* thr_state, const int32_t* skip_if, hipStream_t st) {
   // A conditional launch (only_if) is expected to find nothing to do: it streams from global memory
   // instead of reserving the LDS cache, so that its workgroups are cheap to place and retire.
   const int ce = only_if ? 0 : select_cache_elems(s, cand != nullptr);
   hipLaunchKernelGGL(k_select, dim3(s.B * s.Hq), dim3(kSelThreads), (size_t)ce * 4, st, s, score, score_stride, cand,
-                     count, k, topk_idx, topk_score, ce, only_if, thr_state);
+                     count, k, topk_idx, topk_score, ce, only_if, thr_state, skip_if);
   return hipGetLastError();
 }
 
@@ -546,11 +550,12 @@ hipError_t launch_filter_select(const Shape& s, const float* score, const int32_
                                 const int32_t* seg_count, const int32_t* seg_rows, int nseg,
                                 const int32_t* cand_count, const int64_t* group_start, int64_t* line_total,
                                 const int32_t* k, int32_t* topk_idx, float* topk_score,
-                                float* thr_state, int32_t* redo_g, int32_t* redo_h, hipStream_t st) {
+                                float* thr_state, int32_t* redo_g, int32_t* redo_h, const int32_t* skip_if,
+                                hipStream_t st) {
   const int cap = filter_list_cap(s);
   hipLaunchKernelGGL(k_filter_select, dim3(s.B * s.Hq), dim3(kFilterSelThreads), (size_t)cap * 8, st, s, score, slot_in,
                      score_stride, seg_count, seg_rows, nseg, cand_count, group_start, line_total, k, topk_idx, topk_score, thr_state, redo_g,
-                     redo_h, cap);
+                     redo_h, cap, skip_if);
   return hipGetLastError();
 }
 

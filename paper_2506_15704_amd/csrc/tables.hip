@@ -12,7 +12,7 @@
 //   * statistics: Eq. 8 needs the mean, sum (x-mean)^2 and sum (x-mean)^4 of each table.  The raw
 //     moments M_p = sum x^p (p = 1..4, fp64) follow the update exactly: M_p <- gamma^p M_p +
 //     sum over selected of ((gamma x + delta)^p - (gamma x)^p); a new position adds a zero.
-//     The thresholds of the next step are derived from them when the update ends.
+//     The thresholds of a step are derived from them when its scan starts.
 // Sink positions (< n_sink) are outside the tables: never flagged, counted or updated.
 //
 // The only dense work of a step is the scan (k_table_flags): both tables are read once and two bits
@@ -24,13 +24,15 @@ namespace lfps {
 constexpr int kTabThreads = 256;
 constexpr int kFlagIters = 8;      // 64-position tests per wave of the scan kernel
 
-// head state (doubles): scale, update count, rows the moments cover, raw moments of both tables,
-// thresholds of the next scan in true units
+// head state (doubles): scale, update count, raw moments of both tables, and "the table was flat (every
+// entry equal) when it was imported with N entries" marks.  The thresholds of Eq. 8 are derived from the
+// moments at the start of every scan for the number of rows that scan sees, so a head whose update was
+// skipped (a bypassed head) or a cache that grew by several rows needs no special case: new positions are zeros.
 enum {
-  TS_G = 0, TS_CNT = 1, TS_N = 2,
-  TS_MV = 3,            // M1..M4 of the vertical table: [3..6]
-  TS_MS = 7,            // M1..M4 of the slash table:    [7..10]
-  TS_TAU_V = 11, TS_TAU_S = 12, TS_MEAN_V = 13, TS_MEAN_S = 14,
+  TS_G = 0, TS_CNT = 1,
+  TS_MV = 2,            // M1..M4 of the vertical table: [2..5]
+  TS_MS = 6,            // M1..M4 of the slash table:    [6..9]
+  TS_FLAT_V = 10, TS_FLAT_S = 11, TS_FLAT_N = 12,
 };
 
 // The update count as stored (a double) brought into [0, Lcap - 1]: every slash-frame index formed with
@@ -100,18 +102,43 @@ __global__ __launch_bounds__(kTabThreads) void k_table_flags(Shape s, const floa
                                                              const double* __restrict__ state,
                                                              const int32_t* __restrict__ seq_lens,
                                                              uint32_t* __restrict__ f0, uint32_t* __restrict__ fm,
-                                                             int flag_words, int rows_per_block) {
+                                                             int flag_words, int rows_per_block, double a,
+                                                             const int32_t* __restrict__ gate) {
   __shared__ uint32_t w0[kFlagIters * kTabThreads / 32], wm[kFlagIters * kTabThreads / 32];
   const int bh = blockIdx.y, b = bh / s.Hq;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   int n = seq_lens[b];
   n = n < 0 ? 0 : (n > s.Lcap ? s.Lcap : n);
   const int n_round = (n + 63) & ~63;                     // whole flag words up to the end of the sequence
+  if (gate && gate[bh] != 0) {                            // bypassed head: it proposes no candidates
+    const int w_begin = (blockIdx.x * rows_per_block) >> 5;
+    const int w_end = ((blockIdx.x + 1) * rows_per_block < n_round ? (blockIdx.x + 1) * rows_per_block : n_round) >> 5;
+    for (int w = w_begin + tid; w < w_end; w += kTabThreads) {
+      f0[(int64_t)bh * flag_words + w] = 0u;
+      fm[(int64_t)bh * flag_words + w] = 0u;
+    }
+    return;
+  }
   const double* st = state + (int64_t)bh * kTableStateDoubles;
   const double g = st[TS_G];
   const int cnt = clamp_count(st[TS_CNT], s.Lcap);
-  const float tau_v = float_below(st[TS_TAU_V] / g), tau_s = float_below(st[TS_TAU_S] / g);
-  const float mean_v = float_below(st[TS_MEAN_V] / g), mean_s = float_below(st[TS_MEAN_S] / g);
+  float tau_v, tau_s, mean_v, mean_s;
+  {
+    const double N = (double)(n - s.n_sink > 0 ? n - s.n_sink : 0);
+    double Mv[4], Ms[4], t, m;
+#pragma unroll
+    for (int p = 0; p < 4; ++p) {
+      Mv[p] = st[TS_MV + p];
+      Ms[p] = st[TS_MS + p];
+    }
+    const bool same_n = st[TS_FLAT_N] == N;
+    thresholds_from_moments(Mv, N, a, st[TS_FLAT_V] != 0.0 && (same_n || Mv[1] == 0.0), &t, &m);
+    tau_v = float_below(t / g);
+    mean_v = float_below(m / g);
+    thresholds_from_moments(Ms, N, a, st[TS_FLAT_S] != 0.0 && (same_n || Ms[1] == 0.0), &t, &m);
+    tau_s = float_below(t / g);
+    mean_s = float_below(m / g);
+  }
   const float* ver = tab_ver + (int64_t)bh * s.Lcap;
   const float* sla = tab_sla + (int64_t)bh * 2 * s.Lcap + (s.Lcap - cnt);
   uint32_t* o0 = f0 + (int64_t)bh * flag_words;
@@ -167,10 +194,12 @@ __global__ __launch_bounds__(kTabThreads) void k_table_update(Shape s, float* __
                                                               const int32_t* __restrict__ seq_lens,
                                                               const int32_t* __restrict__ idx,
                                                               const float* __restrict__ sc,
-                                                              const int32_t* __restrict__ kk, double gamma, double a) {
+                                                              const int32_t* __restrict__ kk, double gamma,
+                                                              const int32_t* __restrict__ gate) {
   __shared__ double red[kTabThreads / 64];
   __shared__ float redf[kTabThreads / 64];
   const int bh = blockIdx.x, b = bh / s.Hq, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  if (gate && gate[bh] != 0) return;                        // bypassed head: Eq. 10 is skipped for it
   int n = seq_lens[b];
   n = n < 0 ? 0 : (n > s.Lcap ? s.Lcap : n);
   int kb = kk[b];
@@ -253,15 +282,10 @@ __global__ __launch_bounds__(kTabThreads) void k_table_update(Shape s, float* __
     }
     st[TS_G] = g1;
     st[TS_CNT] = (double)(cnt + 1);
-    const double N = (double)(n + 1 - s.n_sink > 0 ? n + 1 - s.n_sink : 0);   // the next step sees one more row
-    st[TS_N] = N;
-    double tau, mean;
-    thresholds_from_moments(Mv, N, a, Mv[1] == 0.0, &tau, &mean);
-    st[TS_TAU_V] = tau;
-    st[TS_MEAN_V] = mean;
-    thresholds_from_moments(Ms, N, a, Ms[1] == 0.0, &tau, &mean);
-    st[TS_TAU_S] = tau;
-    st[TS_MEAN_S] = mean;
+    if (nv > 0.0) {                                          // entries were changed: no longer a flat table
+      st[TS_FLAT_V] = 0.0;
+      st[TS_FLAT_S] = 0.0;
+    }
   }
 }
 
@@ -271,7 +295,7 @@ __global__ __launch_bounds__(kTabThreads) void k_table_import(Shape s, float* __
                                                               float* __restrict__ tab_sla, double* __restrict__ state,
                                                               const int32_t* __restrict__ seq_lens,
                                                               const float* __restrict__ phi_ver,
-                                                              const float* __restrict__ phi_sla, double a) {
+                                                              const float* __restrict__ phi_sla) {
   __shared__ double red[kTabThreads / 64];
   __shared__ float redf[kTabThreads / 64];
   const int bh = blockIdx.x, b = bh / s.Hq, tid = threadIdx.x;
@@ -314,19 +338,14 @@ __global__ __launch_bounds__(kTabThreads) void k_table_import(Shape s, float* __
     double* st = state + (int64_t)bh * kTableStateDoubles;
     st[TS_G] = 1.0;
     st[TS_CNT] = 0.0;
-    st[TS_N] = N;
 #pragma unroll
     for (int p = 0; p < 4; ++p) {
       st[TS_MV + p] = Mv[p];
       st[TS_MS + p] = Ms[p];
     }
-    double tau, mean;
-    thresholds_from_moments(Mv, N, a, !(hi_v > lo_v), &tau, &mean);
-    st[TS_TAU_V] = tau;
-    st[TS_MEAN_V] = mean;
-    thresholds_from_moments(Ms, N, a, !(hi_s > lo_s), &tau, &mean);
-    st[TS_TAU_S] = tau;
-    st[TS_MEAN_S] = mean;
+    st[TS_FLAT_V] = hi_v > lo_v ? 0.0 : 1.0;
+    st[TS_FLAT_S] = hi_s > lo_s ? 0.0 : 1.0;
+    st[TS_FLAT_N] = N;
   }
 }
 
@@ -371,8 +390,7 @@ __global__ void k_table_renorm_done(double* __restrict__ state, int n_heads) {
 // score[bh, 0:n_b] holds the scaled scores of that query.  grid B*Hq.
 __global__ __launch_bounds__(1024) void k_table_init(Shape s, float* __restrict__ tab_ver, float* __restrict__ tab_sla,
                                                      double* __restrict__ state, const int32_t* __restrict__ seq_lens,
-                                                     const float* __restrict__ score, int64_t score_stride, double gamma,
-                                                     double a) {
+                                                     const float* __restrict__ score, int64_t score_stride, double gamma) {
   __shared__ double red[16];
   __shared__ float redf[16];
   const int bh = blockIdx.x, b = bh / s.Hq, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -414,22 +432,175 @@ __global__ __launch_bounds__(1024) void k_table_init(Shape s, float* __restrict_
     const double N = (double)(n - s.n_sink > 0 ? n - s.n_sink : 0);
     st[TS_G] = 1.0;
     st[TS_CNT] = 0.0;
-    st[TS_N] = N;
 #pragma unroll
     for (int p = 0; p < 4; ++p) {
       st[TS_MV + p] = M[p];
       st[TS_MS + p] = M[p];
     }
-    double tau, mean;
-    thresholds_from_moments(M, N, a, false, &tau, &mean);
-    st[TS_TAU_V] = st[TS_TAU_S] = tau;
-    st[TS_MEAN_V] = st[TS_MEAN_S] = mean;
+    st[TS_FLAT_V] = st[TS_FLAT_S] = N <= 1.0 ? 1.0 : 0.0;    // softmax weights of two or more rows are never all equal in practice
+    st[TS_FLAT_N] = N;
   }
+}
+
+// ----------------------------------------------------------------------------- head sparsity (Eq. 5, Eq. 6)
+// One wave per (b, h).  rho = w_sink / (w_sink + w_global + w_local):
+//   w_sink   = sum over rows [0, n_sink) of exp(q.K_i/sqrt(D)),
+//   w_global = n * exp(q.kbar/sqrt(D) + |q|^2 sigma2_hat / 2)        (log-normal mean of the weights, App. B.1),
+//   w_local  = sum over the newest n_local rows of exp(q.K_i/sqrt(D)).
+// A head with rho > eps is bypassed: its output row is vbar, its index row -1 (Alg. 1 lines 1-4); the later
+// kernels of the step skip it.  The three terms are kept as exponent + log-sum so that a dominant sink
+// (logit in the hundreds) cannot overflow.
+template <typename T>
+__global__ __launch_bounds__(64) void k_head_sparsity(Shape s, const float* __restrict__ q, const T* __restrict__ K,
+                                                      int64_t stride_b, int64_t stride_h, int64_t stride_n,
+                                                      const int32_t* __restrict__ seq_lens,
+                                                      const float* __restrict__ kbar,
+                                                      const float* __restrict__ sigma2_hat, int n_local, float eps,
+                                                      float* __restrict__ rho_out, int32_t* __restrict__ gate_out,
+                                                      const float* __restrict__ vbar, int32_t* __restrict__ topk_idx,
+                                                      float* __restrict__ topk_score, float* __restrict__ out) {
+  const int bh = blockIdx.x, b = bh / s.Hq, h = bh % s.Hq, g = h / s.G, lane = threadIdx.x;
+  int n = seq_lens[b];
+  n = n < 0 ? 0 : (n > s.Lcap ? s.Lcap : n);
+  const float scale = 0.08838834764831845f;
+  const float q0 = q[(int64_t)bh * kD + 2 * lane], q1 = q[(int64_t)bh * kD + 2 * lane + 1];
+  const T* Kbg = K + (int64_t)b * stride_b + (int64_t)g * stride_h;
+  auto logit_of_row = [&](int row) {
+    float k0, k1;
+    if constexpr (sizeof(T) == 2) {
+      const uint32_t w = *reinterpret_cast<const uint32_t*>(Kbg + (int64_t)row * stride_n + 2 * lane);
+      k0 = bf16_lo(w);
+      k1 = bf16_hi(w);
+    } else {
+      k0 = (float)Kbg[(int64_t)row * stride_n + 2 * lane];
+      k1 = (float)Kbg[(int64_t)row * stride_n + 2 * lane + 1];
+    }
+    float d = fmaf(q1, k1, q0 * k0);
+#pragma unroll
+    for (int o = 1; o < 64; o <<= 1) d += __shfl_xor(d, o);
+    return (double)(d * scale);
+  };
+  // log-sum-exp accumulators (double: a handful of terms per head)
+  auto lse_add = [](double& m, double& z, double x) {
+    if (x > m) {
+      z = z * exp(m - x) + 1.0;
+      m = x;
+    } else {
+      z += exp(x - m);
+    }
+  };
+  double m_sink = -INFINITY, z_sink = 0.0, m_loc = -INFINITY, z_loc = 0.0;
+  const int ns = s.n_sink < n ? s.n_sink : n;
+  for (int i = 0; i < ns; ++i) lse_add(m_sink, z_sink, logit_of_row(i));
+  const int lo = n - n_local > 0 ? n - n_local : 0;
+  for (int i = lo; i < n; ++i) lse_add(m_loc, z_loc, logit_of_row(i));
+  float dk = fmaf(q1, kbar[((int64_t)b * s.Hkv + g) * kD + 2 * lane + 1], q0 * kbar[((int64_t)b * s.Hkv + g) * kD + 2 * lane]);
+  float qq = fmaf(q1, q1, q0 * q0);
+#pragma unroll
+  for (int o = 1; o < 64; o <<= 1) {
+    dk += __shfl_xor(dk, o);
+    qq += __shfl_xor(qq, o);
+  }
+  const double l_glob = n > 0 ? log((double)n) + (double)(dk * scale) + (double)qq * (double)sigma2_hat[bh] * 0.5 : -INFINITY;
+  const double l_sink = z_sink > 0.0 ? m_sink + log(z_sink) : -INFINITY;
+  const double l_loc = z_loc > 0.0 ? m_loc + log(z_loc) : -INFINITY;
+  // rho = exp(l_sink) / (exp(l_sink) + exp(l_glob) + exp(l_loc))
+  double rho = 0.0;
+  if (l_sink > -INFINITY) rho = 1.0 / (1.0 + exp(l_glob - l_sink) + exp(l_loc - l_sink));
+  const bool bypass = rho > (double)eps;
+  if (lane == 0) {
+    if (rho_out) rho_out[bh] = (float)rho;
+    gate_out[bh] = bypass ? 1 : 0;
+  }
+  if (bypass && out) {
+    out[(int64_t)bh * kD + 2 * lane] = vbar[((int64_t)b * s.Hkv + g) * kD + 2 * lane];
+    out[(int64_t)bh * kD + 2 * lane + 1] = vbar[((int64_t)b * s.Hkv + g) * kD + 2 * lane + 1];
+    for (int i = lane; i < s.kmax; i += 64) {
+      topk_idx[(int64_t)bh * s.kmax + i] = -1;
+      if (topk_score) topk_score[(int64_t)bh * s.kmax + i] = 0.f;
+    }
+  }
+}
+
+// ----------------------------------------------------------------------------- prefill priors (Sec. 4.2 "Prefilling")
+// Mean K row and mean V row over rows [n_sink, n_b) of one (b, g).  1024 threads: 64 row slots x 16 lanes
+// of 8 channels; fp32 partial sums per thread, fp64 across the row slots.
+template <typename T>
+__global__ __launch_bounds__(1024) void k_prior_means(Shape s, const T* __restrict__ K, const T* __restrict__ V,
+                                                      int64_t stride_b, int64_t stride_h, int64_t stride_n,
+                                                      const int32_t* __restrict__ seq_lens, float* __restrict__ kbar,
+                                                      float* __restrict__ vbar) {
+  __shared__ float red[64][16][8];
+  const int bg = blockIdx.x, b = bg / s.Hkv, g = bg % s.Hkv, tid = threadIdx.x;
+  const int slot = tid >> 4, j = tid & 15;
+  int n = seq_lens[b];
+  n = n < 0 ? 0 : (n > s.Lcap ? s.Lcap : n);
+  const int64_t base = (int64_t)b * stride_b + (int64_t)g * stride_h + 8 * j;
+  for (int which = 0; which < 2; ++which) {
+    const T* X = (which == 0 ? K : V) + base;
+    float acc[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+    for (int r = s.n_sink + slot; r < n; r += 64) {
+      float x[8];
+      if constexpr (sizeof(T) == 2) {
+        const u32x4 w = *reinterpret_cast<const u32x4*>(X + (int64_t)r * stride_n);
+#pragma unroll
+        for (int c = 0; c < 4; ++c) {
+          x[2 * c] = bf16_lo(w[c]);
+          x[2 * c + 1] = bf16_hi(w[c]);
+        }
+      } else {
+        const float4 a0 = reinterpret_cast<const float4*>(X + (int64_t)r * stride_n)[0];
+        const float4 a1 = reinterpret_cast<const float4*>(X + (int64_t)r * stride_n)[1];
+        x[0] = a0.x; x[1] = a0.y; x[2] = a0.z; x[3] = a0.w;
+        x[4] = a1.x; x[5] = a1.y; x[6] = a1.z; x[7] = a1.w;
+      }
+#pragma unroll
+      for (int c = 0; c < 8; ++c) acc[c] += x[c];
+    }
+    __syncthreads();
+#pragma unroll
+    for (int c = 0; c < 8; ++c) red[slot][j][c] = acc[c];
+    __syncthreads();
+    if (tid < kD) {
+      double t = 0.0;
+      for (int sl = 0; sl < 64; ++sl) t += (double)red[sl][tid >> 3][tid & 7];
+      const int cnt = n - s.n_sink;
+      (which == 0 ? kbar : vbar)[(int64_t)bg * kD + tid] = cnt > 0 ? (float)(t / (double)cnt) : 0.f;
+    }
+  }
+}
+
+// sigma2_hat[b, h] = (variance over rows [n_sink, n_b) of score[bh, i]) / |q[b, h]|^2.  grid B*Hq.
+__global__ __launch_bounds__(1024) void k_prior_variance(Shape s, const float* __restrict__ q,
+                                                         const int32_t* __restrict__ seq_lens,
+                                                         const float* __restrict__ score, int64_t score_stride,
+                                                         float* __restrict__ sigma2_hat) {
+  __shared__ double red[16];
+  const int bh = blockIdx.x, b = bh / s.Hq, tid = threadIdx.x;
+  int n = seq_lens[b];
+  n = n < 0 ? 0 : (n > s.Lcap ? s.Lcap : n);
+  const float* sc = score + (int64_t)bh * score_stride;
+  const int cnt = n - s.n_sink;
+  double sum = 0.0;
+  for (int i = s.n_sink + tid; i < n; i += 1024) sum += (double)sc[i];
+  sum = block_sum(sum, red, tid);
+  const double mean = cnt > 0 ? sum / (double)cnt : 0.0;
+  double ss = 0.0;
+  for (int i = s.n_sink + tid; i < n; i += 1024) {
+    const double d = (double)sc[i] - mean;
+    ss += d * d;
+  }
+  ss = block_sum(ss, red, tid);
+  double qq = 0.0;
+  for (int c = tid; c < kD; c += 1024) qq += (double)q[(int64_t)bh * kD + c] * (double)q[(int64_t)bh * kD + c];
+  qq = block_sum(qq, red, tid);
+  if (tid == 0) sigma2_hat[bh] = (cnt > 0 && qq > 0.0) ? (float)(ss / (double)cnt / qq) : 0.f;
 }
 
 // ----------------------------------------------------------------------------- launchers
 hipError_t launch_table_flags(const Shape& s, const float* tab_ver, const float* tab_sla, const double* state,
-                              const int32_t* seq_lens, uint32_t* f0, uint32_t* fm, int flag_words, hipStream_t st) {
+                              const int32_t* seq_lens, uint32_t* f0, uint32_t* fm, int flag_words, double a,
+                              const int32_t* gate, hipStream_t st) {
   // about 4096 workgroups in all, each a whole number of passes
   const int pass_rows = kTabThreads * kFlagIters;
   int per_head = 4096 / (s.B * s.Hq);
@@ -438,22 +609,22 @@ hipError_t launch_table_flags(const Shape& s, const float* tab_ver, const float*
   if (rows_per_block < pass_rows) rows_per_block = pass_rows;
   const int chunks = (s.Lcap + rows_per_block - 1) / rows_per_block;
   hipLaunchKernelGGL(k_table_flags, dim3(chunks, s.B * s.Hq), dim3(kTabThreads), 0, st, s, tab_ver, tab_sla, state,
-                     seq_lens, f0, fm, flag_words, rows_per_block);
+                     seq_lens, f0, fm, flag_words, rows_per_block, a, gate);
   return hipGetLastError();
 }
 
 hipError_t launch_table_update(const Shape& s, float* tab_ver, float* tab_sla, double* state, const int32_t* seq_lens,
-                               const int32_t* idx, const float* sc, const int32_t* k, double gamma, double a,
+                               const int32_t* idx, const float* sc, const int32_t* k, double gamma, const int32_t* gate,
                                hipStream_t st) {
   hipLaunchKernelGGL(k_table_update, dim3(s.B * s.Hq), dim3(kTabThreads), 0, st, s, tab_ver, tab_sla, state, seq_lens,
-                     idx, sc, k, gamma, a);
+                     idx, sc, k, gamma, gate);
   return hipGetLastError();
 }
 
 hipError_t launch_table_import(const Shape& s, float* tab_ver, float* tab_sla, double* state, const int32_t* seq_lens,
-                               const float* phi_ver, const float* phi_sla, double a, hipStream_t st) {
+                               const float* phi_ver, const float* phi_sla, hipStream_t st) {
   hipLaunchKernelGGL(k_table_import, dim3(s.B * s.Hq), dim3(kTabThreads), 0, st, s, tab_ver, tab_sla, state, seq_lens,
-                     phi_ver, phi_sla, a);
+                     phi_ver, phi_sla);
   return hipGetLastError();
 }
 
@@ -475,9 +646,40 @@ hipError_t launch_table_renorm(const Shape& s, float* tab_ver, float* tab_sla, d
 }
 
 hipError_t launch_table_init(const Shape& s, float* tab_ver, float* tab_sla, double* state, const int32_t* seq_lens,
-                             const float* score, int64_t score_stride, double gamma, double a, hipStream_t st) {
+                             const float* score, int64_t score_stride, double gamma, hipStream_t st) {
   hipLaunchKernelGGL(k_table_init, dim3(s.B * s.Hq), dim3(1024), 0, st, s, tab_ver, tab_sla, state, seq_lens, score,
-                     score_stride, gamma, a);
+                     score_stride, gamma);
+  return hipGetLastError();
+}
+
+hipError_t launch_head_sparsity(const Shape& s, int dtype, const float* q, const KvView& kv, const float* kbar,
+                                const float* sigma2_hat, int n_local, float eps, float* rho, int32_t* gate,
+                                const float* vbar, int32_t* topk_idx, float* topk_score, float* out, hipStream_t st) {
+  if (dtype == LFPS_BF16)
+    hipLaunchKernelGGL((k_head_sparsity<uint16_t>), dim3(s.B * s.Hq), dim3(64), 0, st, s, q, (const uint16_t*)kv.k,
+                       kv.stride_b, kv.stride_h, kv.stride_n, kv.seq_lens, kbar, sigma2_hat, n_local, eps, rho, gate,
+                       vbar, topk_idx, topk_score, out);
+  else
+    hipLaunchKernelGGL((k_head_sparsity<float>), dim3(s.B * s.Hq), dim3(64), 0, st, s, q, (const float*)kv.k,
+                       kv.stride_b, kv.stride_h, kv.stride_n, kv.seq_lens, kbar, sigma2_hat, n_local, eps, rho, gate,
+                       vbar, topk_idx, topk_score, out);
+  return hipGetLastError();
+}
+
+hipError_t launch_prior_means(const Shape& s, int dtype, const KvView& kv, float* kbar, float* vbar, hipStream_t st) {
+  if (dtype == LFPS_BF16)
+    hipLaunchKernelGGL((k_prior_means<uint16_t>), dim3(s.B * s.Hkv), dim3(1024), 0, st, s, (const uint16_t*)kv.k,
+                       (const uint16_t*)kv.v, kv.stride_b, kv.stride_h, kv.stride_n, kv.seq_lens, kbar, vbar);
+  else
+    hipLaunchKernelGGL((k_prior_means<float>), dim3(s.B * s.Hkv), dim3(1024), 0, st, s, (const float*)kv.k,
+                       (const float*)kv.v, kv.stride_b, kv.stride_h, kv.stride_n, kv.seq_lens, kbar, vbar);
+  return hipGetLastError();
+}
+
+hipError_t launch_prior_variance(const Shape& s, const float* q, const int32_t* seq_lens, const float* score,
+                                 int64_t score_stride, float* sigma2_hat, hipStream_t st) {
+  hipLaunchKernelGGL(k_prior_variance, dim3(s.B * s.Hq), dim3(1024), 0, st, s, q, seq_lens, score, score_stride,
+                     sigma2_hat);
   return hipGetLastError();
 }
 

@@ -359,3 +359,121 @@ def test_table_entry_points_need_table_mode_and_contents(table_case):
         tab.lfps_table_candidates(dc.seq_lens(1), cand, cnt)       # nothing imported yet
     assert ei.value.code == LFPS_EINVAL
     tab.close()
+
+
+# ----------------------------------------------------------------------------- head sparsity bypass (Eq. 5-6)
+def _sparse_queries(case, t, heads, factor=3.0):
+    """The step-t queries with the given (b, h) scaled up: larger logits, so the sink rows take the softmax."""
+    q = case.q[t].copy()
+    for (b, h) in heads:
+        q[b, h] *= np.float32(factor)
+    return q
+
+
+def test_priors_match_oracle(table_case):
+    dc = table_case
+    s, case = dc.spec, dc.case
+    n_sink = 4
+    ctx = dc.make_ctx(table_mode=True, n_sink=n_sink)
+    kbar = torch.zeros((s.B, s.Hkv, s.D), dtype=torch.float32, device=DEV)
+    vbar = torch.zeros_like(kbar)
+    s2 = torch.zeros((s.B, s.Hq), dtype=torch.float32, device=DEV)
+    ctx.lfps_priors(dc.q(0), ctx.kv_view(dc.K, dc.V, dc.seq_lens(0)), kbar, vbar, s2)
+    kb_, vb_, s2_ = kbar.cpu().numpy(), vbar.cpu().numpy(), s2.cpu().numpy()
+    for (b, g) in ((0, 1), (1, 6)):
+        K, V = dc.group(b, g)
+        n = int(case.seq_lens0[b])
+        for h in range(s.G):
+            ok, ov, os2 = tor.priors(case.q[0, b, s.G * g + h], K, V, n, n_sink)
+            np.testing.assert_allclose(kb_[b, g], ok, rtol=0, atol=2e-6)
+            np.testing.assert_allclose(vb_[b, g], ov, rtol=0, atol=2e-6)
+            assert s2_[b, s.G * g + h] == pytest.approx(os2, rel=2e-5)
+    ctx.close()
+
+
+def test_head_sparsity_ratio_matches_oracle(table_case):
+    dc = table_case
+    s, case = dc.spec, dc.case
+    n_sink, t, eps = 4, 2, 0.85
+    ctx = dc.make_ctx(table_mode=True, n_sink=n_sink)
+    rng = np.random.default_rng(3)
+    kbar = (rng.standard_normal((s.B, s.Hkv, s.D)) * 0.05).astype(np.float32)
+    s2 = rng.uniform(0.0, 0.012, size=(s.B, s.Hq)).astype(np.float32)
+    sparse = [(0, 1), (0, 2), (1, 13), (1, 31)]
+    q = _sparse_queries(case, t, sparse)
+    rho = torch.zeros((s.B, s.Hq), dtype=torch.float32, device=DEV)
+    gate = torch.zeros((s.B, s.Hq), dtype=torch.int32, device=DEV)
+    for n_local in (6, 0):
+        ctx.lfps_head_sparsity(dev(q), ctx.kv_view(dc.K, dc.V, dc.seq_lens(t)), dev(kbar), dev(s2), n_local, eps, rho, gate)
+        rho_h, gate_h = rho.cpu().numpy(), gate.cpu().numpy()
+        for (b, g) in ((0, 0), (1, 3), (1, 7)):
+            K, _ = dc.group(b, g)
+            n = int(case.seq_lens(t)[b])
+            for hh in range(s.G):
+                h = s.G * g + hh
+                want = tor.sparsity_ratio(q[b, h], K, n, kbar[b, g], float(s2[b, h]), n_sink, n_local)
+                assert rho_h[b, h] == pytest.approx(want, rel=2e-4, abs=1e-7), (b, h, n_local)
+                if abs(want - eps) > 1e-3:
+                    assert bool(gate_h[b, h]) == (want > eps)
+        assert gate_h[0, 1] == 1 and gate_h[1, 31] == 1 and gate_h[0, 0] == 0      # the scaled heads are bypassed
+    ctx.close()
+
+
+def test_gated_table_step_matches_oracle(table_case):
+    dc = table_case
+    s, case = dc.spec, dc.case
+    gamma, a, n_sink, n_recent, eps, n_local, t = 0.9, 0.2, 4, 1, 0.97, 6, 3   # eps between the two kinds of head here
+    ctx = dc.make_ctx(table_mode=True, table_decay=gamma, table_a=a, n_sink=n_sink, n_recent=n_recent)
+    rng = np.random.default_rng(9)
+    n = case.seq_lens(t)
+    ver, sla = _make_tables(rng, s.B, s.Hq, case.Lcap, n, n_sink)
+    kbar = (rng.standard_normal((s.B, s.Hkv, s.D)) * 0.05).astype(np.float32)
+    vbar = rng.standard_normal((s.B, s.Hkv, s.D)).astype(np.float32)
+    s2 = rng.uniform(0.0, 0.012, size=(s.B, s.Hq)).astype(np.float32)
+    sparse = [(0, 1), (0, 2), (1, 12), (1, 13), (1, 14), (1, 15), (1, 31)]      # group (1, 3) is bypassed entirely
+    q = _sparse_queries(case, t, sparse)
+    idx = torch.full((s.B, s.Hq, case.kmax), 77, dtype=torch.int32, device=DEV)
+    isc = torch.zeros((s.B, s.Hq, case.kmax), dtype=torch.float32, device=DEV)
+    out = torch.zeros((s.B, s.Hq, s.D), dtype=torch.float32, device=DEV)
+    gate = torch.zeros((s.B, s.Hq), dtype=torch.int32, device=DEV)
+    cnt = torch.zeros((s.B, s.Hkv), dtype=torch.int32, device=DEV)
+    ctx.lfps_tables_import(dev(ver), dev(sla), dev(n))
+    ctx.lfps_table_step_gated(dev(q), ctx.kv_view(dc.K, dc.V, dc.seq_lens(t)), dc.k, dev(kbar), dev(vbar), dev(s2),
+                              n_local, eps, idx, out, isc, gate)
+    ctx.lfps_copy_cand_count(cnt)
+    ev = torch.zeros((s.B, s.Hq, case.Lcap), dtype=torch.float64, device=DEV)
+    es = torch.zeros_like(ev)
+    ctx.lfps_tables_export(ev, es, dev(n + 1))
+    torch.cuda.synchronize()
+    i_, o_, g_, c_ = idx.cpu().numpy(), out.cpu().numpy(), gate.cpu().numpy(), cnt.cpu().numpy()
+    ev, es = ev.cpu().numpy(), es.cpu().numpy()
+    assert sorted(zip(*np.nonzero(g_))) == sorted(sparse)
+    for (b, g) in ((0, 0), (1, 3), (1, 7)):
+        K, V = dc.group(b, g)
+        nb, kb = int(n[b]), int(case.k[b])
+        t64 = [(ver[b, s.G * g + h].astype(np.float64), sla[b, s.G * g + h].astype(np.float64)) for h in range(s.G)]
+        res = tor.gated_table_step(q[b, s.G * g: s.G * (g + 1)], K, V, t64, nb, kb, s.r, a, gamma, kbar[b, g], vbar[b, g],
+                                   [float(x) for x in s2[b, s.G * g: s.G * (g + 1)]], eps, n_recent, n_sink, n_local)
+        assert list(res["gate"]) == [bool(x) for x in g_[b, s.G * g: s.G * (g + 1)]]
+        assert c_[b, g] == len(res["cand"])
+        m = min(nb + 1, case.Lcap)
+        for h in range(s.G):
+            bh = s.G * g + h
+            if res["gate"][h]:
+                np.testing.assert_array_equal(o_[b, bh], vbar[b, g])
+                assert (i_[b, bh] == -1).all()
+                np.testing.assert_array_equal(ev[b, bh, :m], res["tables"][h][0][:m])     # untouched
+                np.testing.assert_array_equal(es[b, bh, :m], res["tables"][h][1][:m])
+            else:
+                ksel = min(kb, len(res["cand"]))
+                got = valid_row(i_[b, bh, :kb])
+                assert_topk_equal_mod_ties(got, res["topk_idx"][h], lambda p: orc.scores(q[b, bh], K, p), ksel, f"b={b} h={bh}")
+                assert_out_close(o_[b, bh], orc.sparse_attn(q[b, bh], K, V, got), f"b={b} h={bh}")
+                if set(got.tolist()) == set(res["topk_idx"][h].tolist()):
+                    old_v = np.r_[gamma * t64[h][0][:nb], 0.0][:m]
+                    old_s = np.r_[0.0, gamma * t64[h][1][:nb]][:m]
+                    assert_tables_close(ev[b, bh, :m], res["tables"][h][0][:m], old_v, 10 * 0.5 / max(ksel, 1), f"ver h={bh}")
+                    assert_tables_close(es[b, bh, :m], res["tables"][h][1][:m], old_s, 10 * 0.5 / max(ksel, 1), f"sla h={bh}")
+    # the fully bypassed group proposes only the always-present rows
+    assert c_[1, 3] == n_sink + n_recent
+    ctx.close()

@@ -329,7 +329,8 @@ def test_gated_step_bypasses_sparse_heads_and_leaves_their_tables():
     assert list(res["gate"]) == [False, True, False] and res["rho"][1] > 0.85
     np.testing.assert_array_equal(res["out"][1], vbar)
     assert len(res["topk_idx"][1]) == 0
-    np.testing.assert_array_equal(res["tables"][1][0], tables[1][0])
+    np.testing.assert_array_equal(res["tables"][1][0], np.r_[tables[1][0], 0.0])
+    np.testing.assert_array_equal(res["tables"][1][1], np.r_[tables[1][1], 0.0])
     # the others behave as in table_step over the candidates of the live heads only
     ref = tor.table_step(q[[0, 2]], K, V, [tables[0], tables[2]], n, k, 1, 0.2, 0.9, n_recent=1, n_sink=n_sink)
     np.testing.assert_array_equal(res["cand"], ref["cand"])
