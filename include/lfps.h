@@ -155,9 +155,12 @@ int lfps_exact_topk(lfps_ctx* ctx, const float* q, const lfps_kv* kv, const int3
  * positions.  Sink rows (< n_sink) are outside the tables, as in the paper: always candidates, never
  * counted or updated.  Radius must be <= 30.  Rows appended since the last update enter the tables as zeros. */
 
-/* Eq. 4 with s = 1: both tables = (softmax over rows [n_sink, n_b) of q.K/sqrt(D)) / (2 (1 - gamma)),
- * from the one query q [B, Hq, D] (e.g. the last prefill query). */
-int lfps_tables_init(lfps_ctx* ctx, const float* q, const lfps_kv* kv, void* stream);
+/* Eq. 4: tables from the attention weights of the last s = n_queries prefill queries.
+ *   q_hist [n_queries, B, Hq, D] fp32, q_hist[j-1] = the j-th most recent query (j = 1: the last one).
+ * Query j sees rows [0, n_b - j + 1); w = softmax over the offloaded rows it sees of q.K/sqrt(D);
+ *   Phi_ver(i) = 1/(2 s (1 - gamma)) sum_j w_j(i),    Phi_sla(i) = 1/(2 s (1 - gamma)) sum_j w_j(i - j + 1)
+ * (the paper uses s = 32).  One dense scoring pass per query. */
+int lfps_tables_init(lfps_ctx* ctx, const float* q_hist, int32_t n_queries, const lfps_kv* kv, void* stream);
 /* Set / read the tables as true values per position: phi_ver, phi_sla [B, Hq, max_seq_len], rows
  * [0, seq_lens[b]) used (fp32 in, fp64 out; entries of sink rows and rows >= n_b read as 0). */
 int lfps_tables_import(lfps_ctx* ctx, const float* phi_ver, const float* phi_sla, const int32_t* seq_lens,

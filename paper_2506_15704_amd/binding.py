@@ -68,7 +68,7 @@ def _load() -> ctypes.CDLL:
         "lfps_set_filter": (ctypes.c_int, [P, I32]),
         "lfps_reset_history": (ctypes.c_int, [P, VP]),
         "lfps_copy_cand_count": (ctypes.c_int, [P, VP, VP]),
-        "lfps_tables_init": (ctypes.c_int, [P, VP, ctypes.POINTER(lfps_kv), VP]),
+        "lfps_tables_init": (ctypes.c_int, [P, VP, I32, ctypes.POINTER(lfps_kv), VP]),
         "lfps_tables_import": (ctypes.c_int, [P, VP, VP, VP, VP]),
         "lfps_tables_export": (ctypes.c_int, [P, VP, VP, VP, VP]),
         "lfps_table_candidates": (ctypes.c_int, [P, VP, VP, VP, VP]),
@@ -240,10 +240,14 @@ class Lfps:
             _ptr(topk_score, torch.float32, (self.B, self.Hq, self.kmax), "topk_score", d), self._stream()))
 
     # ------------------------------------------------------------------ score tables
-    def lfps_tables_init(self, q, kv: lfps_kv):
+    def lfps_tables_init(self, q_hist, kv: lfps_kv):
+        """q_hist: [s, B, Hq, D] (or [B, Hq, D] for one query), most recent query first."""
+        if q_hist.dim() == 3:
+            q_hist = q_hist.unsqueeze(0)
+        s = int(q_hist.shape[0])
         self._check(_lib.lfps_tables_init(
-            self._ctx, _ptr(q, torch.float32, (self.B, self.Hq, self.D), "q", self.device), ctypes.byref(kv),
-            self._stream()))
+            self._ctx, _ptr(q_hist, torch.float32, (s, self.B, self.Hq, self.D), "q_hist", self.device), s,
+            ctypes.byref(kv), self._stream()))
 
     def lfps_tables_import(self, phi_ver, phi_sla, seq_lens):
         d, shp = self.device, (self.B, self.Hq, self.Lcap)

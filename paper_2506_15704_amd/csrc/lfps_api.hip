@@ -475,9 +475,10 @@ static int need_tables(lfps_ctx* ctx, const char* who, bool ready) {
   return LFPS_OK;
 }
 
-int lfps_tables_init(lfps_ctx* ctx, const float* q, const lfps_kv* kv, void* stream) {
+int lfps_tables_init(lfps_ctx* ctx, const float* q_hist, int32_t n_queries, const lfps_kv* kv, void* stream) {
   if (!ctx) return LFPS_EINVAL;
-  if (!q) return fail(ctx, LFPS_EINVAL, "lfps_tables_init: NULL argument");
+  if (!q_hist) return fail(ctx, LFPS_EINVAL, "lfps_tables_init: NULL argument");
+  if (n_queries < 1) return fail(ctx, LFPS_EINVAL, "lfps_tables_init: n_queries must be >= 1");
   int rc = need_tables(ctx, "lfps_tables_init", false);
   if (rc != LFPS_OK) return rc;
   KvView v;
@@ -485,11 +486,17 @@ int lfps_tables_init(lfps_ctx* ctx, const float* q, const lfps_kv* kv, void* str
   if (rc != LFPS_OK) return rc;
   hipStream_t st = (hipStream_t)stream;
   const Shape& s = ctx->shape;
-  LAUNCH(ctx, LFPS_KERNEL_DENSE_SCORE, st,
-         launch_group_score(s, ctx->cfg.kv_dtype, q, v, nullptr, nullptr, ctx->score, s.score_stride, nullptr, st));
-  hipError_t e = launch_table_init(s, ctx->tab_ver, ctx->tab_sla, ctx->tab_state, v.seq_lens, ctx->score,
-                                   s.score_stride, (double)ctx->cfg.table_decay, st);
-  if (e != hipSuccess) return fail(ctx, LFPS_EHIP, "lfps_tables_init", e);
+  const int64_t q_stride = (int64_t)s.B * s.Hq * kD;
+  for (int j = 1; j <= n_queries; ++j) {
+    LAUNCH(ctx, LFPS_KERNEL_DENSE_SCORE, st,
+           launch_group_score(s, ctx->cfg.kv_dtype, q_hist + (int64_t)(j - 1) * q_stride, v, nullptr, nullptr, ctx->score,
+                              s.score_stride, nullptr, st));
+    hipError_t e = launch_table_init(s, ctx->tab_ver, ctx->tab_sla, v.seq_lens, ctx->score, s.score_stride,
+                                     (double)ctx->cfg.table_decay, j, n_queries, st);
+    if (e != hipSuccess) return fail(ctx, LFPS_EHIP, "lfps_tables_init", e);
+  }
+  hipError_t e = launch_table_finish(s, ctx->tab_ver, ctx->tab_sla, ctx->tab_state, v.seq_lens, st);
+  if (e != hipSuccess) return fail(ctx, LFPS_EHIP, "lfps_tables_init (statistics)", e);
   ctx->tab_scale = 1.0;
   ctx->tab_updates = 0;
   ctx->tab_ready = 1;

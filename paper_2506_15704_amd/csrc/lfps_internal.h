@@ -108,8 +108,11 @@ hipError_t launch_table_import(const Shape& s, float* tab_ver, float* tab_sla, d
 hipError_t launch_table_export(const Shape& s, const float* tab_ver, const float* tab_sla, const double* state,
                                const int32_t* seq_lens, double* phi_ver, double* phi_sla, hipStream_t st);
 hipError_t launch_table_renorm(const Shape& s, float* tab_ver, float* tab_sla, double* state, hipStream_t st);
-hipError_t launch_table_init(const Shape& s, float* tab_ver, float* tab_sla, double* state, const int32_t* seq_lens,
-                             const float* score, int64_t score_stride, double gamma, hipStream_t st);
+hipError_t launch_table_init(const Shape& s, float* tab_ver, float* tab_sla, const int32_t* seq_lens,
+                             const float* score, int64_t score_stride, double gamma, int j, int n_queries,
+                             hipStream_t st);
+hipError_t launch_table_finish(const Shape& s, const float* tab_ver, const float* tab_sla, double* state,
+                               const int32_t* seq_lens, hipStream_t st);
 // Head sparsity (Eq. 5-6) and the prefill priors it needs; gate [B,Hq] marks bypassed heads, whose output
 // row (vbar) and index row (-1) the kernel writes when out != NULL.
 hipError_t launch_head_sparsity(const Shape& s, int dtype, const float* q, const KvView& kv, const float* kbar,

@@ -384,23 +384,27 @@ __global__ void k_table_renorm_done(double* __restrict__ state, int n_heads) {
   if (bh < n_heads) state[(int64_t)bh * kTableStateDoubles + TS_G] = 1.0;
 }
 
-// ----------------------------------------------------------------------------- Eq. 4 with one query
-// Tables from the attention weights of one query over rows [n_sink, n_b): both tables are
-// w / (2 (1 - gamma)) (with s = 1 the slash sum of Eq. 4 has its single, unshifted term).
-// score[bh, 0:n_b] holds the scaled scores of that query.  grid B*Hq.
+// ----------------------------------------------------------------------------- Eq. 4
+// Tables from the attention weights of the last s prefill queries.  One launch per query: the j-th most
+// recent query (j = 1..s) sees rows [0, n_b - j + 1); its weights w (softmax over the offloaded rows it
+// sees) are added to the vertical table at i and to the slash table at i + j - 1 (Eq. 4's w_{i-j+1}),
+// times 1/(2 s (1 - gamma)).  j = 1 overwrites, later launches accumulate.  score[bh, 0:n_b] holds the
+// scaled scores of query j.  grid B*Hq.  k_table_finish then derives the statistics.
 __global__ __launch_bounds__(1024) void k_table_init(Shape s, float* __restrict__ tab_ver, float* __restrict__ tab_sla,
-                                                     double* __restrict__ state, const int32_t* __restrict__ seq_lens,
-                                                     const float* __restrict__ score, int64_t score_stride, double gamma) {
+                                                     const int32_t* __restrict__ seq_lens,
+                                                     const float* __restrict__ score, int64_t score_stride, double gamma,
+                                                     int j, int n_queries) {
   __shared__ double red[16];
   __shared__ float redf[16];
   const int bh = blockIdx.x, b = bh / s.Hq, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   int n = seq_lens[b];
   n = n < 0 ? 0 : (n > s.Lcap ? s.Lcap : n);
+  const int seen = n - j + 1 > 0 ? n - j + 1 : 0;           // rows query j sees
   const float* sc = score + (int64_t)bh * score_stride;
   float* ver = tab_ver + (int64_t)bh * s.Lcap;
-  float* sla = tab_sla + (int64_t)bh * 2 * s.Lcap;
+  float* sla = tab_sla + (int64_t)bh * 2 * s.Lcap + s.Lcap;  // position frame (update count 0)
   float m = -INFINITY;
-  for (int i = s.n_sink + tid; i < n; i += 1024) m = fmaxf(m, sc[i]);
+  for (int i = s.n_sink + tid; i < seen; i += 1024) m = fmaxf(m, sc[i]);
 #pragma unroll
   for (int d = 1; d < 64; d <<= 1) m = fmaxf(m, __shfl_xor(m, d));
   if (lane == 0) redf[wave] = m;
@@ -408,37 +412,69 @@ __global__ __launch_bounds__(1024) void k_table_init(Shape s, float* __restrict_
   m = redf[0];
   for (int w = 1; w < 16; ++w) m = fmaxf(m, redf[w]);
   double z = 0.0;
-  for (int i = s.n_sink + tid; i < n; i += 1024) z += (double)expf(sc[i] - m);
+  for (int i = s.n_sink + tid; i < seen; i += 1024) z += (double)expf(sc[i] - m);
   z = block_sum(z, red, tid);
-  const double norm = z > 0.0 ? 1.0 / (2.0 * (1.0 - gamma) * z) : 0.0;
-  double mv[4] = {0, 0, 0, 0};
-  for (int i = tid; i < 2 * s.Lcap; i += 1024) sla[i] = 0.f;
-  __syncthreads();
-  for (int i = tid; i < s.Lcap; i += 1024) {
-    float x = 0.f;
-    if (i >= s.n_sink && i < n) {
-      x = (float)((double)expf(sc[i] - m) * norm);
-      const double xd = x;
-      mv[0] += xd; mv[1] += xd * xd; mv[2] += xd * xd * xd; mv[3] += xd * xd * xd * xd;
+  const double norm = z > 0.0 ? 1.0 / (2.0 * (double)n_queries * (1.0 - gamma) * z) : 0.0;
+  if (j == 1) {
+    for (int i = tid; i < s.Lcap; i += 1024) {
+      ver[i] = 0.f;
+      sla[i - s.Lcap] = 0.f;
+      sla[i] = 0.f;
     }
-    ver[i] = x;
-    sla[i + s.Lcap] = x;
+    __syncthreads();
   }
-  double M[4];
+  // a position receives at most one vertical and one slash contribution per launch: plain read-modify-write
+  for (int i = s.n_sink + tid; i < seen; i += 1024) {
+    const float x = (float)((double)expf(sc[i] - m) * norm);
+    ver[i] += x;
+    sla[i + j - 1] += x;                                     // i + j - 1 <= n - 1
+  }
+}
+
+// Scale 1, update count 0, raw moments and flat marks of the tables as they stand in the position frame.
+__global__ __launch_bounds__(kTabThreads) void k_table_finish(Shape s, const float* __restrict__ tab_ver,
+                                                              const float* __restrict__ tab_sla,
+                                                              double* __restrict__ state,
+                                                              const int32_t* __restrict__ seq_lens) {
+  __shared__ double red[kTabThreads / 64];
+  __shared__ float redf[kTabThreads / 64];
+  const int bh = blockIdx.x, b = bh / s.Hq, tid = threadIdx.x;
+  int n = seq_lens[b];
+  n = n < 0 ? 0 : (n > s.Lcap ? s.Lcap : n);
+  const float* ver = tab_ver + (int64_t)bh * s.Lcap;
+  const float* sla = tab_sla + (int64_t)bh * 2 * s.Lcap + s.Lcap;
+  double mv[4] = {0, 0, 0, 0}, ms[4] = {0, 0, 0, 0};
+  float lo_v = INFINITY, hi_v = -INFINITY, lo_s = INFINITY, hi_s = -INFINITY;
+  for (int i = s.n_sink + tid; i < n; i += kTabThreads) {
+    const float xv = ver[i], xs = sla[i];
+    const double a1 = xv, b1 = xs;
+    mv[0] += a1; mv[1] += a1 * a1; mv[2] += a1 * a1 * a1; mv[3] += a1 * a1 * a1 * a1;
+    ms[0] += b1; ms[1] += b1 * b1; ms[2] += b1 * b1 * b1; ms[3] += b1 * b1 * b1 * b1;
+    lo_v = fminf(lo_v, xv); hi_v = fmaxf(hi_v, xv);
+    lo_s = fminf(lo_s, xs); hi_s = fmaxf(hi_s, xs);
+  }
+  double Mv[4], Ms[4];
 #pragma unroll
-  for (int p = 0; p < 4; ++p) M[p] = block_sum(mv[p], red, tid);
+  for (int p = 0; p < 4; ++p) {
+    Mv[p] = block_sum(mv[p], red, tid);
+    Ms[p] = block_sum(ms[p], red, tid);
+  }
+  lo_v = block_min(lo_v, redf, tid);
+  hi_v = -block_min(-hi_v, redf, tid);
+  lo_s = block_min(lo_s, redf, tid);
+  hi_s = -block_min(-hi_s, redf, tid);
   if (tid == 0) {
     double* st = state + (int64_t)bh * kTableStateDoubles;
-    const double N = (double)(n - s.n_sink > 0 ? n - s.n_sink : 0);
     st[TS_G] = 1.0;
     st[TS_CNT] = 0.0;
 #pragma unroll
     for (int p = 0; p < 4; ++p) {
-      st[TS_MV + p] = M[p];
-      st[TS_MS + p] = M[p];
+      st[TS_MV + p] = Mv[p];
+      st[TS_MS + p] = Ms[p];
     }
-    st[TS_FLAT_V] = st[TS_FLAT_S] = N <= 1.0 ? 1.0 : 0.0;    // softmax weights of two or more rows are never all equal in practice
-    st[TS_FLAT_N] = N;
+    st[TS_FLAT_V] = hi_v > lo_v ? 0.0 : 1.0;
+    st[TS_FLAT_S] = hi_s > lo_s ? 0.0 : 1.0;
+    st[TS_FLAT_N] = (double)(n - s.n_sink > 0 ? n - s.n_sink : 0);
   }
 }
 
@@ -645,10 +681,17 @@ hipError_t launch_table_renorm(const Shape& s, float* tab_ver, float* tab_sla, d
   return hipGetLastError();
 }
 
-hipError_t launch_table_init(const Shape& s, float* tab_ver, float* tab_sla, double* state, const int32_t* seq_lens,
-                             const float* score, int64_t score_stride, double gamma, hipStream_t st) {
-  hipLaunchKernelGGL(k_table_init, dim3(s.B * s.Hq), dim3(1024), 0, st, s, tab_ver, tab_sla, state, seq_lens, score,
-                     score_stride, gamma);
+hipError_t launch_table_init(const Shape& s, float* tab_ver, float* tab_sla, const int32_t* seq_lens,
+                             const float* score, int64_t score_stride, double gamma, int j, int n_queries,
+                             hipStream_t st) {
+  hipLaunchKernelGGL(k_table_init, dim3(s.B * s.Hq), dim3(1024), 0, st, s, tab_ver, tab_sla, seq_lens, score,
+                     score_stride, gamma, j, n_queries);
+  return hipGetLastError();
+}
+
+hipError_t launch_table_finish(const Shape& s, const float* tab_ver, const float* tab_sla, double* state,
+                               const int32_t* seq_lens, hipStream_t st) {
+  hipLaunchKernelGGL(k_table_finish, dim3(s.B * s.Hq), dim3(kTabThreads), 0, st, s, tab_ver, tab_sla, state, seq_lens);
   return hipGetLastError();
 }
 

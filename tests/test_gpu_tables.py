@@ -477,3 +477,42 @@ def test_gated_table_step_matches_oracle(table_case):
     # the fully bypassed group proposes only the always-present rows
     assert c_[1, 3] == n_sink + n_recent
     ctx.close()
+
+
+def test_tables_init_from_several_queries_is_eq4(table_case):
+    """Eq. 4 with s = 4: query j (j-th most recent) sees rows [0, n - j + 1) and its weights land at i in the
+    vertical table and at i + j - 1 in the slash table."""
+    dc = table_case
+    s, case = dc.spec, dc.case
+    gamma, n_sink, nq = 0.95, 4, 4
+    ctx = dc.make_ctx(table_mode=True, table_decay=gamma, table_a=0.2, n_sink=n_sink, n_recent=0)
+    q_hist = np.stack([case.q[j] for j in range(nq)])            # any four query sets serve as the last prefill queries
+    ctx.lfps_tables_init(dev(q_hist), ctx.kv_view(dc.K, dc.V, dc.seq_lens(0)))
+    ev = torch.zeros((s.B, s.Hq, case.Lcap), dtype=torch.float64, device=DEV)
+    es = torch.zeros_like(ev)
+    ctx.lfps_tables_export(ev, es, dc.seq_lens(0))
+    ev, es = ev.cpu().numpy(), es.cpu().numpy()
+    for (b, g) in ((0, 2), (1, 5)):
+        K, _ = dc.group(b, g)
+        n = int(case.seq_lens0[b])
+        for h in (0, 3):
+            bh = s.G * g + h
+            w = np.zeros((nq, n))
+            for j in range(1, nq + 1):
+                seen = n - j + 1
+                sc = orc.scores(q_hist[j - 1, b, bh], K[:seen])
+                w[j - 1, n_sink:seen] = _softmax64(sc[n_sink:])
+            ver, sla = tor.init_tables(w, gamma, n_sink)
+            np.testing.assert_allclose(ev[b, bh, :n], ver, rtol=3e-5, atol=1e-12)
+            np.testing.assert_allclose(es[b, bh, :n], sla, rtol=3e-5, atol=1e-12)
+            assert es[b, bh, :n].sum() == pytest.approx(1 / (2 * (1 - gamma)), rel=1e-5)
+    # the statistics that go with them: candidates from the device equal the oracle's from the exported tables
+    cand = torch.zeros((s.B, s.Hkv, ctx.cand_cap), dtype=torch.int32, device=DEV)
+    cnt = torch.zeros((s.B, s.Hkv), dtype=torch.int32, device=DEV)
+    ctx.lfps_table_candidates(dc.seq_lens(0), cand, cnt)
+    for (b, g) in ((0, 2), (1, 5)):
+        n = int(case.seq_lens0[b])
+        t64 = [(ev[b, s.G * g + h], es[b, s.G * g + h]) for h in range(s.G)]
+        want = tor.group_candidates(t64, n, 0.2, s.r, 0, n_sink)
+        _assert_candidates(cand[b, g, : int(cnt[b, g])].cpu().numpy(), want, t64, n, 0.2, s.r, n_sink, f"b={b} g={g}")
+    ctx.close()
