@@ -85,14 +85,24 @@ __device__ __forceinline__ void find_bin(SelectShared<NT>& sm, uint32_t need, in
 }
 
 // Visits the wave's slice: `i` = row slot, `in` = slot valid, `x` = its sanitised score (from the
-// LDS copy when CACHED, else from global memory).  The trip count is wave-uniform, so ballots
-// inside see the whole wave.
-#define LFPS_FOR_EACH(...)                                                   \
-  _Pragma("unroll 4") for (int it = 0; it < nit; ++it) {                     \
-    const int i = r0 + 64 * it + lane;                                       \
-    const bool in = i < r1;                                                  \
-    const float x = CACHED ? cache[in ? i : r0] : sanitize(sc[in ? i : r0]); \
-    __VA_ARGS__                                                              \
+// LDS copy when CACHED, else from global memory).  Eight 64-slot rows are loaded before the first is
+// used, so a streaming pass keeps eight loads in flight per lane; the trip counts are wave-uniform,
+// so ballots inside see the whole wave.
+#define LFPS_FOR_EACH(...)                                                            \
+  for (int it0 = 0; it0 < nit; it0 += 8) {                                            \
+    float xb_[8];                                                                     \
+    _Pragma("unroll") for (int u_ = 0; u_ < 8; ++u_) {                                \
+      const int i_ = r0 + 64 * (it0 + u_) + lane;                                     \
+      xb_[u_] = CACHED ? cache[i_ < r1 ? i_ : r0] : sanitize(sc[i_ < r1 ? i_ : r0]);  \
+    }                                                                                 \
+    _Pragma("unroll") for (int u_ = 0; u_ < 8; ++u_) {                                \
+      if (it0 + u_ < nit) {                                                           \
+        const int i = r0 + 64 * (it0 + u_) + lane;                                    \
+        const bool in = i < r1;                                                       \
+        const float x = xb_[u_];                                                      \
+        __VA_ARGS__                                                                   \
+      }                                                                               \
+    }                                                                                 \
   }
 
 // `slot_of` (LDS, or NULL for identity) maps an element of the scored list to its candidate slot;
