@@ -42,6 +42,11 @@ def parse_args():
     ap.add_argument("--main-only", dest="all_workloads", action="store_false", help="only the main workload")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-table-mode", action="store_true", help="skip the score-table mode legs")
+    ap.add_argument("--no-paged", action="store_true", help="skip the paged-cache leg")
+    ap.add_argument("--paged-only", action="store_true", help="run only the paged-cache leg of --workload")
+    ap.add_argument("--paged-block", type=int, default=16, help="rows per block of the paged-cache leg")
+    ap.add_argument("--paged-layout", default="block_head_row", choices=["block_head_row", "block_row_head"],
+                    help="memory order inside a block of the paged-cache leg")
     ap.add_argument("--table-only", action="store_true",
                     help="run only the score-table mode of the main workload (for profiling) and print its record")
     ap.add_argument("--calib-copy", action="store_true",
@@ -53,7 +58,7 @@ def parse_args():
 class Runner:
     """Device state of one workload and the step loop."""
 
-    def __init__(self, name, table_mode=False, n_sink=0, gated=False):
+    def __init__(self, name, table_mode=False, n_sink=0, gated=False, paged_block=0, paged_layout="block_head_row"):
         import numpy as np
         import torch
 
@@ -66,6 +71,11 @@ class Runner:
         self.case = case = gen.make_case(spec)
         self.dev = "cuda:0"
         self.K, self.V = gen_device.fill_kv(case, self.dev)
+        self.block_table = None
+        if paged_block:      # the same rows as a block pool in shuffled order
+            Kp, Vp, self.block_table = gen_device.paginate(self.K, self.V, paged_block, seed=spec.seed,
+                                                           layout=paged_layout)
+            self.K, self.V = Kp, Vp
         self.ctx = Lfps(batch=spec.B, n_q_heads=spec.Hq, n_kv_heads=spec.Hkv, head_dim=spec.D,
                         kv_dtype=spec.kv_dtype, max_seq_len=case.Lcap, max_k=case.kmax, radius=spec.r,
                         n_recent=1, n_sink=n_sink, table_mode=table_mode, table_decay=0.95, table_a=0.2)
@@ -80,7 +90,10 @@ class Runner:
         self.q = to(case.q)                                                 # [T+1, B, Hq, D]
         self.seq = to(np.stack([case.seq_lens(t) for t in range(spec.T + 1)]))  # [T+1, B]
         self.k = to(case.k)
-        self.views = [self.ctx.kv_view(self.K, self.V, self.seq[t]) for t in range(spec.T + 1)]
+        if paged_block:
+            self.views = [self.ctx.paged_kv_view(self.K, self.V, self.block_table, self.seq[t]) for t in range(spec.T + 1)]
+        else:
+            self.views = [self.ctx.kv_view(self.K, self.V, self.seq[t]) for t in range(spec.T + 1)]
         shp = (spec.B, spec.Hq, case.kmax)
         self.seed = torch.zeros(shp, dtype=torch.int32, device=self.dev)
         self.buf = [torch.zeros(shp, dtype=torch.int32, device=self.dev) for _ in range(2)]
@@ -278,6 +291,38 @@ def measure(name, steps, warmup, with_baselines=True, use_graph=True):
     return res, r.case
 
 
+def measure_paged(name, steps, warmup, block_size=16, layout="block_head_row"):
+    """The main workload again with the cache as a paged pool (blocks of `block_size` rows in shuffled
+    order, block table per request): same steps, final Top-k and outputs compared bit for bit with the
+    contiguous run."""
+    r0 = Runner(name)
+    spec = r0.spec
+    if steps <= 0:
+        steps = max(1, spec.T - warmup)
+    sec0 = r0.run_timed(steps, warmup)
+    ref_idx, ref_out = r0.prev.clone(), r0.out.clone()
+    r0.close()
+    del r0
+    r = Runner(name, paged_block=block_size, paged_layout=layout)
+    sec = r.run_timed(steps, warmup)
+    same = bool(r.torch.equal(r.prev, ref_idx)) and bool(r.torch.equal(r.out, ref_out))
+    tm, cnts = r.run_kernel_timing(steps, warmup)
+    filtered = tm["filter_score"][1] > 0
+    kname = "filter_score" if filtered else "gather_score"
+    by = float(algorithmic_bytes_score(spec, r.case, cnts, filtered).mean())
+    us = tm[kname][0] / max(tm[kname][1], 1) * 1e3
+    res = {"block_size": block_size,
+           "layout": ("[block, head, row, D]" if layout == "block_head_row" else "[block, row, head, D]") + ", blocks in shuffled order",
+           "ms_per_step": round(sec * 1e3, 4), "contiguous_ms_per_step": round(sec0 * 1e3, 4),
+           "matches_contiguous_bitwise": same,
+           "kernel_us": {k: round(v[0] / steps * 1e3, 2) for k, v in tm.items() if v[1]},
+           "score_kernel": {"kernel": kname, "avg_launch_us": round(us, 2),
+                            "GB_per_s": round(by / (us * 1e-6) / 1e9, 1) if us > 0 else None,
+                            "frac_of_hbm_peak": round(by / (us * 1e-6) / 1e9 / HBM_PEAK_GBS, 4) if us > 0 else None}}
+    r.close()
+    return res
+
+
 def measure_tables(name, steps, warmup):
     """The same workload with the paper's own candidate rule (score tables, Eq. 7-10): lfps_table_step per step,
     tables initialised from the step-0 query (Eq. 4 with one query) during warm-up; first four rows = sinks,
@@ -409,6 +454,11 @@ def main():
         print(json.dumps({"workload": args.workload, "score_table_mode": measure_tables(args.workload, args.steps, args.warmup)}),
               flush=True)
         return
+    if args.paged_only:
+        print(json.dumps({"workload": args.workload,
+                          "paged_kv": measure_paged(args.workload, args.steps, args.warmup, args.paged_block, args.paged_layout)}),
+              flush=True)
+        return
     main_res, case = measure(args.workload, args.steps, args.warmup)
     spec = case.spec
     line = {
@@ -432,6 +482,8 @@ def main():
         tab = measure_tables(args.workload, args.steps, args.warmup)
         tab["speedup_vs_memoryless_step"] = round(main_res["ms_per_step"] / tab["ms_per_step"], 3)
         line["score_table_mode"] = tab
+    if not args.no_paged:
+        line["paged_kv"] = measure_paged(args.workload, args.steps, args.warmup, args.paged_block, args.paged_layout)
     if args.all_workloads:
         others = {}
         for name in ("C1", "C2", "C3", "C4", "C5"):

@@ -68,3 +68,45 @@ def fill_kv(case, device="cuda:0"):
         raise RuntimeError(f"gen_fill_kv(V) failed with hipError {rc}")
     torch.cuda.synchronize(device)
     return K, V
+
+
+def paginate(K, V, block_size: int, seed: int = 0, spare_blocks: int = 3, layout: str = "block_head_row",
+             table_pad: int = 2):
+    """The same cache as a paged pool (data movement only): the rows of every request are cut into
+    blocks of `block_size` rows and scattered over a pool in a seeded random order, with
+    `spare_blocks` unused blocks (filled with 1e4, so that a wrong lookup cannot go unnoticed) mixed in.
+
+    K, V: [B, Hkv, Lcap, D] device tensors.  Returns (K_pool, V_pool, block_table):
+      K_pool, V_pool  [n_blocks, Hkv, block_size, D] views; memory order [block, head, row, D]
+                      (layout "block_head_row") or [block, row, head, D] ("block_row_head")
+      block_table     [B, ceil(Lcap / block_size) + table_pad] int32; the padding columns hold -1.
+    """
+    import torch
+
+    B, Hkv, Lcap, D = K.shape
+    nb = (Lcap + block_size - 1) // block_size
+    n_blocks = B * nb + spare_blocks
+    g = torch.Generator(device="cpu")
+    g.manual_seed(int(seed) + 977)
+    perm = torch.randperm(n_blocks, generator=g)[: B * nb].to(torch.int64)
+    table = torch.full((B, nb + table_pad), -1, dtype=torch.int32)
+    table[:, :nb] = perm.view(B, nb).to(torch.int32)
+    pools = []
+    for X in (K, V):
+        if layout == "block_head_row":
+            pool = torch.full((n_blocks, Hkv, block_size, D), 1e4, dtype=X.dtype, device=X.device)
+            view = pool
+        elif layout == "block_row_head":
+            pool = torch.full((n_blocks, block_size, Hkv, D), 1e4, dtype=X.dtype, device=X.device)
+            view = pool.permute(0, 2, 1, 3)
+        else:
+            raise ValueError(layout)
+        for b in range(B):
+            xb = X[b]
+            if nb * block_size != Lcap:
+                pad = torch.full((Hkv, nb * block_size - Lcap, D), 1e4, dtype=X.dtype, device=X.device)
+                xb = torch.cat([xb, pad], dim=1)
+            blocks = xb.view(Hkv, nb, block_size, D).permute(1, 0, 2, 3)     # [nb, Hkv, bs, D]
+            view[perm[b * nb: (b + 1) * nb].to(X.device)] = blocks
+        pools.append(view)
+    return pools[0], pools[1], table.to(K.device)

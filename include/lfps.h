@@ -69,15 +69,29 @@ typedef struct {
   float table_a;       /* a of Eq. 8 (0.2 / 0.3 in the paper); table mode needs a > 0 */
 } lfps_config;
 
-/* View of the KV cache.  Element (b, g, i, c) of K is k[b*stride_b + g*stride_h + i*stride_n + c]
- * (strides in elements, stride_n >= D, rows 16-byte aligned), same for v.  seq_lens[b] = n_b, the
- * number of valid rows of request b at this step.  The struct itself is host memory; k, v and
- * seq_lens are device pointers. */
+/* View of the KV cache.  The struct itself is host memory; k, v, seq_lens and block_table are device
+ * pointers.  seq_lens[b] = n_b, the number of valid rows of request b at this step.
+ *
+ * Contiguous cache (block_table == NULL): element (b, g, i, c) of K is
+ *   k[b*stride_b + g*stride_h + i*stride_n + c]
+ * (strides in elements, stride_n >= D, rows 16-byte aligned), same for v.
+ *
+ * Paged cache (block_table != NULL): k and v are pools of n_blocks blocks of block_size rows, and
+ * block_table[b*block_table_stride + i/block_size] names the block that holds row i of request b:
+ *   k[block*stride_b + g*stride_h + (i % block_size)*stride_n + c]
+ * so stride_b is the distance between blocks.  block_size is a power of two in [1, 65536];
+ * block_table_stride*block_size >= max_seq_len; n_blocks*block_size < 2^31.  Table entries are
+ * read by the kernels and clamped into [0, n_blocks); only the entries of rows below n_b are read.
+ * The method itself (positions, candidates, Top-k indices) always speaks in logical rows i. */
 typedef struct {
   const void* k;
   const void* v;
   int64_t stride_b, stride_h, stride_n;
   const int32_t* seq_lens; /* [B] */
+  const int32_t* block_table; /* [B, block_table_stride] or NULL */
+  int32_t block_size;
+  int32_t block_table_stride;
+  int32_t n_blocks;
 } lfps_kv;
 
 /* Create / destroy.  lfps_create validates the config, selects cfg->device, allocates the

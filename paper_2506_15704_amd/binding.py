@@ -38,7 +38,9 @@ class lfps_config(ctypes.Structure):
 class lfps_kv(ctypes.Structure):
     _fields_ = [("k", ctypes.c_void_p), ("v", ctypes.c_void_p),
                 ("stride_b", ctypes.c_int64), ("stride_h", ctypes.c_int64), ("stride_n", ctypes.c_int64),
-                ("seq_lens", ctypes.c_void_p)]
+                ("seq_lens", ctypes.c_void_p), ("block_table", ctypes.c_void_p),
+                ("block_size", ctypes.c_int32), ("block_table_stride", ctypes.c_int32),
+                ("n_blocks", ctypes.c_int32)]
 
 
 def _load() -> ctypes.CDLL:
@@ -182,8 +184,32 @@ class Lfps:
             raise ValueError("K and V must share strides")
         sl = _ptr(seq_lens, torch.int32, (self.B,), "seq_lens", self.device)
         view = lfps_kv(K.data_ptr(), V.data_ptr() if V is not None else None,
-                       K.stride(0), K.stride(1), K.stride(2), sl)
+                       K.stride(0), K.stride(1), K.stride(2), sl, None, 0, 0, 0)
         view._keep = (K, V, seq_lens)   # the struct holds raw pointers: keep their tensors alive with it
+        return view
+
+    def paged_kv_view(self, K: torch.Tensor, V: Optional[torch.Tensor], block_table: torch.Tensor,
+                      seq_lens: torch.Tensor) -> lfps_kv:
+        """View of a paged cache: K, V are pools [n_blocks, Hkv, block_size, D] (any strides with a
+        contiguous last dim, e.g. a permuted [n_blocks, block_size, Hkv, D]); block_table [B, max_blocks]
+        int32 names the pool block of every logical block of a request."""
+        for name, t in (("K", K), ("V", V)):
+            if t is None:
+                continue
+            if not t.is_cuda or t.dtype != self.kv_torch_dtype or t.dim() != 4:
+                raise TypeError(f"{name}: expected a 4-d {self.kv_torch_dtype} tensor on the GPU")
+            if t.shape[1] != self.Hkv or t.shape[3] != self.D or t.stride(3) != 1:
+                raise ValueError(f"{name}: expected [n_blocks, Hkv={self.Hkv}, block_size, D={self.D}] with unit channel stride")
+        if V is not None and (V.stride() != K.stride() or V.shape != K.shape):
+            raise ValueError("K and V pools must share shape and strides")
+        if (not block_table.is_cuda or block_table.dtype != torch.int32 or block_table.dim() != 2
+                or block_table.shape[0] != self.B or block_table.stride(1) != 1):
+            raise ValueError(f"block_table: expected an int32 [B={self.B}, max_blocks] tensor on the GPU with unit column stride")
+        sl = _ptr(seq_lens, torch.int32, (self.B,), "seq_lens", self.device)
+        view = lfps_kv(K.data_ptr(), V.data_ptr() if V is not None else None,
+                       K.stride(0), K.stride(1), K.stride(2), sl, block_table.data_ptr(),
+                       int(K.shape[2]), int(block_table.stride(0)), int(K.shape[0]))
+        view._keep = (K, V, seq_lens, block_table)
         return view
 
     # ------------------------------------------------------------------ entry points

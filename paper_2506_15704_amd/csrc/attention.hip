@@ -33,9 +33,9 @@ __device__ __forceinline__ void load8(const T* p, float x[8]) {
 }
 
 // grid B*Hq, kSparseWaves waves per workgroup
-template <typename T, int kSparseWaves>
+template <typename T, int kSparseWaves, bool kPaged>
 __global__ __launch_bounds__(kSparseWaves * 64) void k_sparse_attn(Shape s, const T* __restrict__ V, int64_t stride_b,
-                                                                int64_t stride_h, int64_t stride_n,
+                                                                int64_t stride_h, int64_t stride_n, KvPage pg,
                                                                 const int32_t* __restrict__ seq_lens,
                                                                 const int32_t* __restrict__ idx,
                                                                 const float* __restrict__ idx_score,
@@ -73,7 +73,8 @@ __global__ __launch_bounds__(kSparseWaves * 64) void k_sparse_attn(Shape s, cons
 
   // softmax reference: the largest score among the head's valid rows.  Each lane looks at the
   // entries it will own in the loop below (first 64-entry tile kept in registers).
-  int first_row = -1;
+  using Rows = RowMap<kPaged>;
+  int first_row = -1;                 // as a physical row (never negative), or -1 for "no row"
   float first_s = -INFINITY;
   float m = -INFINITY;
   for (int i = r0 + lane; i < r1; i += 64) {
@@ -81,7 +82,7 @@ __global__ __launch_bounds__(kSparseWaves * 64) void k_sparse_attn(Shape s, cons
     const float sv = sh[i];
     const bool ok = r >= 0 && r < n;
     if (i < r0 + 64) {
-      first_row = ok ? r : -1;
+      first_row = ok ? Rows::phys(pg, b, r) : -1;
       first_s = sv;
     }
     if (ok) m = fmaxf(m, sv);
@@ -94,7 +95,7 @@ __global__ __launch_bounds__(kSparseWaves * 64) void k_sparse_attn(Shape s, cons
 #pragma unroll
   for (int w = 1; w < kSparseWaves; ++w) m = fmaxf(m, redm[w]);
 
-  const T* Vbg = V + (int64_t)b * stride_b + (int64_t)g * stride_h + 8 * j;
+  const T* Vbg = V + Rows::base(b, g, stride_b, stride_h) + 8 * j;
   float acc[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
   float l = 0.f;
   for (int base = r0; base < r1; base += 64) {
@@ -106,7 +107,7 @@ __global__ __launch_bounds__(kSparseWaves * 64) void k_sparse_attn(Shape s, cons
     } else if (base + lane < r1) {
       const int r = ih[base + lane];
       if (r >= 0 && r < n) {
-        my_row = r;
+        my_row = Rows::phys(pg, b, r);
         my_p = __expf(sh[base + lane] - m);
       }
     }
@@ -116,7 +117,7 @@ __global__ __launch_bounds__(kSparseWaves * 64) void k_sparse_attn(Shape s, cons
       const int row = __shfl(my_row, 4 * t + rs);
       float p = __shfl(my_p, 4 * t + rs);
       float x[8];
-      load8(Vbg + (int64_t)(row < 0 ? 0 : row) * stride_n, x);
+      load8(Vbg + Rows::offset(pg, row < 0 ? 0 : row, stride_b, stride_n), x);
       p = row < 0 ? 0.f : p;
 #pragma unroll
       for (int c = 0; c < 8; ++c) acc[c] = fmaf(p, x[c], acc[c]);
@@ -152,13 +153,24 @@ static hipError_t launch_sparse_t(const Shape& s, const KvView& kv, const int32_
   // as many waves per head as keep every head's workgroup resident at once (256 CUs x 32 waves)
   const int heads = s.B * s.Hq;
   const T* V = (const T*)kv.v;
-#define LFPS_LAUNCH_SPARSE(NW)                                                                                   \
-  hipLaunchKernelGGL((k_sparse_attn<T, NW>), dim3(heads), dim3(NW * 64), 0, st, s, V, kv.stride_b, kv.stride_h, \
-                     kv.stride_n, kv.seq_lens, idx, idx_score, k, out, skip_if)
-  if (heads * 16 <= 8192) LFPS_LAUNCH_SPARSE(16);
-  else if (heads * 8 <= 8192) LFPS_LAUNCH_SPARSE(8);
-  else LFPS_LAUNCH_SPARSE(4);
+#define LFPS_LAUNCH_SPARSE_P(NW, PAGED)                                                                        \
+  hipLaunchKernelGGL((k_sparse_attn<T, NW, PAGED>), dim3(heads), dim3(NW * 64), 0, st, s, V, kv.stride_b,      \
+                     kv.stride_h, kv.stride_n, kv.page, kv.seq_lens, idx, idx_score, k, out, skip_if)
+#define LFPS_LAUNCH_SPARSE(NW)          \
+  if (kv.page.table) {                  \
+    LFPS_LAUNCH_SPARSE_P(NW, true);     \
+  } else {                              \
+    LFPS_LAUNCH_SPARSE_P(NW, false);    \
+  }
+  if (heads * 16 <= 8192) {
+    LFPS_LAUNCH_SPARSE(16)
+  } else if (heads * 8 <= 8192) {
+    LFPS_LAUNCH_SPARSE(8)
+  } else {
+    LFPS_LAUNCH_SPARSE(4)
+  }
 #undef LFPS_LAUNCH_SPARSE
+#undef LFPS_LAUNCH_SPARSE_P
   return hipGetLastError();
 }
 
@@ -180,11 +192,11 @@ int full_attn_splits(const Shape& s) {
 __device__ __forceinline__ int rows_per_split(int n, int n_split) { return (((n + n_split - 1) / n_split) + 15) & ~15; }
 
 // grid (n_split, B*Hkv); part [B*Hkv, n_split, G, D+2]: acc[D], m, l
-template <typename T, int G>
+template <typename T, int G, bool kPaged>
 __global__ __launch_bounds__(kAttnThreads) void k_full_attn(Shape s, const float* __restrict__ q,
                                                             const T* __restrict__ K, const T* __restrict__ V,
                                                             int64_t stride_b, int64_t stride_h, int64_t stride_n,
-                                                            const int32_t* __restrict__ seq_lens,
+                                                            KvPage pg, const int32_t* __restrict__ seq_lens,
                                                             float* __restrict__ part, int n_split, float scale) {
   __shared__ float red_acc[4][G][kD];
   __shared__ float red_m[4][G], red_l[4][G];
@@ -205,8 +217,9 @@ __global__ __launch_bounds__(kAttnThreads) void k_full_attn(Shape s, const float
 #pragma unroll
     for (int c = 0; c < 8; ++c) qr[h][c] = qh[c] * scale;
   }
-  const T* Kbg = K + (int64_t)b * stride_b + (int64_t)g * stride_h + 8 * j;
-  const T* Vbg = V + (int64_t)b * stride_b + (int64_t)g * stride_h + 8 * j;
+  using Rows = RowMap<kPaged>;
+  const T* Kbg = K + Rows::base(b, g, stride_b, stride_h) + 8 * j;
+  const T* Vbg = V + Rows::base(b, g, stride_b, stride_h) + 8 * j;
 
   float m[G], l[G], acc[G][8];
 #pragma unroll
@@ -227,8 +240,9 @@ __global__ __launch_bounds__(kAttnThreads) void k_full_attn(Shape s, const float
       int r = r0 + 4 * u + rs;
       ok[u] = r < r_end;
       r = ok[u] ? r : r_end - 1;
-      load8(Kbg + (int64_t)r * stride_n, kx[u]);
-      load8(Vbg + (int64_t)r * stride_n, vx[u]);
+      const int64_t off = Rows::offset(pg, Rows::phys(pg, b, r), stride_b, stride_n);
+      load8(Kbg + off, kx[u]);
+      load8(Vbg + off, vx[u]);
     }
     float sc[U][G];
 #pragma unroll
@@ -354,22 +368,23 @@ static hipError_t launch_full_t(const Shape& s, const float* q, const KvView& kv
   const float scale = 0.08838834764831845f;
   const T* K = (const T*)kv.k;
   const T* V = (const T*)kv.v;
-  switch (s.G) {
-    case 1:
-      hipLaunchKernelGGL((k_full_attn<T, 1>), grid, block, 0, st, s, q, K, V, kv.stride_b, kv.stride_h, kv.stride_n,
-                         kv.seq_lens, part, n_split, scale);
-      break;
-    case 2:
-      hipLaunchKernelGGL((k_full_attn<T, 2>), grid, block, 0, st, s, q, K, V, kv.stride_b, kv.stride_h, kv.stride_n,
-                         kv.seq_lens, part, n_split, scale);
-      break;
-    case 4:
-      hipLaunchKernelGGL((k_full_attn<T, 4>), grid, block, 0, st, s, q, K, V, kv.stride_b, kv.stride_h, kv.stride_n,
-                         kv.seq_lens, part, n_split, scale);
-      break;
-    default:
-      return hipErrorInvalidValue;
+#define LFPS_LAUNCH_FULL_P(GG, PAGED)                                                                        \
+  hipLaunchKernelGGL((k_full_attn<T, GG, PAGED>), grid, block, 0, st, s, q, K, V, kv.stride_b, kv.stride_h,  \
+                     kv.stride_n, kv.page, kv.seq_lens, part, n_split, scale)
+#define LFPS_LAUNCH_FULL(GG)          \
+  if (kv.page.table) {                \
+    LFPS_LAUNCH_FULL_P(GG, true);     \
+  } else {                            \
+    LFPS_LAUNCH_FULL_P(GG, false);    \
   }
+  switch (s.G) {
+    case 1: LFPS_LAUNCH_FULL(1); break;
+    case 2: LFPS_LAUNCH_FULL(2); break;
+    case 4: LFPS_LAUNCH_FULL(4); break;
+    default: return hipErrorInvalidValue;
+  }
+#undef LFPS_LAUNCH_FULL
+#undef LFPS_LAUNCH_FULL_P
   return hipGetLastError();
 }
 

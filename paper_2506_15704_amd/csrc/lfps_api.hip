@@ -157,6 +157,19 @@ int check_kv(lfps_ctx* ctx, const lfps_kv* kv, bool need_v, KvView* out) {
   out->k = kv->k; out->v = kv->v;
   out->stride_b = kv->stride_b; out->stride_h = kv->stride_h; out->stride_n = kv->stride_n;
   out->seq_lens = kv->seq_lens;
+  out->page = KvPage{nullptr, 0, 0, 0};
+  if (kv->block_table) {
+    const int64_t bs = kv->block_size;
+    if (bs < 1 || bs > 65536 || (bs & (bs - 1)))
+      return fail(ctx, LFPS_EINVAL, "paged kv: block_size must be a power of two in [1, 65536]");
+    if (kv->block_table_stride < 1 || (int64_t)kv->block_table_stride * bs < ctx->cfg.max_seq_len)
+      return fail(ctx, LFPS_EINVAL, "paged kv: block_table_stride * block_size must cover max_seq_len");
+    if (kv->n_blocks < 1 || (int64_t)kv->n_blocks * bs > 2147483647LL)
+      return fail(ctx, LFPS_EINVAL, "paged kv: n_blocks must be >= 1 and n_blocks * block_size below 2^31");
+    int shift = 0;
+    while ((1 << shift) < bs) ++shift;
+    out->page = KvPage{kv->block_table, kv->block_table_stride, shift, kv->n_blocks};
+  }
   return LFPS_OK;
 }
 

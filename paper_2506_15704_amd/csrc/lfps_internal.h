@@ -14,12 +14,48 @@ typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 
+// Where the rows of a request live when the cache is paged (table != nullptr): a pool of blocks of
+// 2^shift rows, table[b*table_stride + (i >> shift)] = block of row i of request b.
+struct KvPage {
+  const int32_t* table;
+  int32_t table_stride, shift, n_blocks;
+};
+
 // Strided view of K or V in elements, resolved for one launch.
 struct KvView {
   const void* k;
   const void* v;
   int64_t stride_b, stride_h, stride_n;
   const int32_t* seq_lens;
+  KvPage page;
+};
+
+// Row addressing of the two cache layouts, chosen at compile time.  A logical row i of request b
+// is first turned into a "physical row" p (an int32: i itself, or block * block_size + i % block_size;
+// the only step that reads memory, and only when paged), from which the element offset follows by
+// arithmetic.  Kernels translate where a row id first lives in a register and keep p from there on.
+template <bool kPaged>
+struct RowMap {
+  __device__ __forceinline__ static int phys(const KvPage& pg, int b, int i) {
+    if constexpr (!kPaged) {
+      return i;
+    } else {
+      int blk = pg.table[(int64_t)b * pg.table_stride + (i >> pg.shift)];
+      blk = blk < 0 ? 0 : (blk >= pg.n_blocks ? pg.n_blocks - 1 : blk);   // a bad entry reads a wrong block, never outside the pool
+      return (blk << pg.shift) | (i & ((1 << pg.shift) - 1));
+    }
+  }
+  // element offset of the start of (b, g)'s rows, to which offset(p) is added
+  __device__ __forceinline__ static int64_t base(int b, int g, int64_t stride_b, int64_t stride_h) {
+    return (kPaged ? (int64_t)0 : (int64_t)b * stride_b) + (int64_t)g * stride_h;
+  }
+  __device__ __forceinline__ static int64_t offset(const KvPage& pg, int p, int64_t stride_b, int64_t stride_n) {
+    if constexpr (!kPaged) {
+      return (int64_t)p * stride_n;
+    } else {
+      return (int64_t)(p >> pg.shift) * stride_b + (int64_t)(p & ((1 << pg.shift) - 1)) * stride_n;
+    }
+  }
 };
 
 // Shapes every kernel needs.

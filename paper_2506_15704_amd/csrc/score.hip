@@ -76,10 +76,10 @@ __device__ __forceinline__ void load_query_operand(bf16x8 (&A)[4], const float* 
 // channels to (kk, kb) is valid as long as the A operand uses the same one.
 // The row ids of the next iteration are fetched, and the scores of the previous iteration stored,
 // right after this iteration's loads are issued.
-template <int G, bool GATHER>
+template <int G, bool GATHER, bool kPaged>
 __global__ __launch_bounds__(kScoreThreads) void k_group_score_bf16(Shape s, const float* __restrict__ q,
                                                                     const __bf16* __restrict__ K, int64_t stride_b,
-                                                                    int64_t stride_h, int64_t stride_n,
+                                                                    int64_t stride_h, int64_t stride_n, KvPage pg,
                                                                     const int32_t* __restrict__ seq_lens,
                                                                     const int32_t* __restrict__ cand,
                                                                     const int32_t* __restrict__ cand_count,
@@ -99,28 +99,32 @@ __global__ __launch_bounds__(kScoreThreads) void k_group_score_bf16(Shape s, con
   bf16x8 A[4];
   load_query_operand<G>(A, q, (int64_t)b * s.Hq + (int64_t)g * G, j, kb);
 
-  const __bf16* Kbg = K + (int64_t)b * stride_b + (int64_t)g * stride_h;
+  using Rows = RowMap<kPaged>;
+  const __bf16* Kbg = K + Rows::base(b, g, stride_b, stride_h);
   const int32_t* cbg = GATHER ? cand + (int64_t)bg * s.cand_cap : nullptr;
   float* sc = score + ((int64_t)b * s.Hq + (int64_t)g * G + kb) * score_stride;   // lane group kb -> head kb
   const int step = gridDim.x * 4 * kRowsPerWaveIter;
+  // the row a lane holds for its slot, as a physical row; padding slots read row 0 and are not stored
+  auto physical = [&](int row) { return Rows::phys(pg, b, (row < 0 || row >= n) ? 0 : row); };
 
   float pv[4] = {0.f, 0.f, 0.f, 0.f};   // scores of the previous iteration, not yet stored
   int pbase = -1;
   int my_row = -1;
   if (first + lane < count) my_row = GATHER ? cbg[first + lane] : first + lane;
+  my_row = physical(my_row);
   for (int base = first; base < count; base += step) {
     bf16x8 Bt[4][4];
 #pragma unroll
     for (int t = 0; t < 4; ++t) {
-      int row = __shfl(my_row, 16 * t + j);
-      row = (row < 0 || row >= n) ? 0 : row;            // padding slots read row 0 and are not stored
-      const bf16x8* p = reinterpret_cast<const bf16x8*>(Kbg + (int64_t)row * stride_n) + 4 * kb;
+      const int row = __shfl(my_row, 16 * t + j);
+      const bf16x8* p = reinterpret_cast<const bf16x8*>(Kbg + Rows::offset(pg, row, stride_b, stride_n)) + 4 * kb;
 #pragma unroll
       for (int kk = 0; kk < 4; ++kk) Bt[t][kk] = p[kk];
     }
     const int nb = base + step;
     int next_row = -1;
     if (nb + lane < count) next_row = GATHER ? cbg[nb + lane] : nb + lane;
+    next_row = physical(next_row);
     if (pbase >= 0) {
 #pragma unroll
       for (int t = 0; t < 4; ++t) {
@@ -168,10 +172,10 @@ __global__ __launch_bounds__(kScoreThreads) void k_group_score_bf16(Shape s, con
 // A threshold of -inf keeps every row; NaN means there is no previous step.
 constexpr int kFilterStage = 256;   // survivors one wave can hold per head before it must write them out
 
-template <int G>
+template <int G, bool kPaged>
 __global__ __launch_bounds__(kScoreThreads, 2) void k_filter_score_bf16(
     Shape s, const float* __restrict__ q, const __bf16* __restrict__ K, int64_t stride_b, int64_t stride_h,
-    int64_t stride_n, const int32_t* __restrict__ seq_lens, const int32_t* __restrict__ cand,
+    int64_t stride_n, KvPage page, const int32_t* __restrict__ seq_lens, const int32_t* __restrict__ cand,
     const int32_t* __restrict__ cand_count, const int64_t* __restrict__ group_start,
     const int64_t* __restrict__ line_total, const float* __restrict__ thr_state, float margin,
     float* __restrict__ score, int32_t* __restrict__ slot_out, int64_t score_stride,
@@ -235,7 +239,8 @@ __global__ __launch_bounds__(kScoreThreads, 2) void k_filter_score_bf16(
     const float tau = kb < G ? thr_state[head] - margin : INFINITY;
 
     bf16x8 A[4];                                        // filled after the first tile's loads are on their way
-    const __bf16* Kbg = K + (int64_t)b * stride_b + (int64_t)g * stride_h;
+    using Rows = RowMap<kPaged>;
+    const __bf16* Kbg = K + Rows::base(b, g, stride_b, stride_h);
     const int32_t* cbg = cand + (int64_t)bg * s.cand_cap;
     int run = 0;                                        // survivors of my head already in global memory
     int staged = 0;                                     // survivors of my head waiting in LDS
@@ -261,17 +266,21 @@ __global__ __launch_bounds__(kScoreThreads, 2) void k_filter_score_bf16(
 
     // Two 64-row tiles are kept in flight per wave: while tile i is multiplied, the loads of tile
     // i+1 (issued before) are still arriving.
-    auto issue = [&](bf16x8 (&Bt)[4][4], int (&rows)[4], int ids) {
+    // ids: the row positions of the tile's 64 slots, one per lane; phys: the same rows as physical
+    // rows (paged cache only; ignored otherwise)
+    auto issue = [&](bf16x8 (&Bt)[4][4], int (&rows)[4], int ids, int phys) {
 #pragma unroll
       for (int t = 0; t < 4; ++t) {
         int row = __shfl(ids, 16 * t + j);
         row = (row < 0 || row >= n) ? 0 : row;          // padding slots read row 0 and are never kept
         rows[t] = row;
-        const bf16x8* p = reinterpret_cast<const bf16x8*>(Kbg + (int64_t)row * stride_n) + 4 * kb;
+        const int prow = kPaged ? __shfl(phys, 16 * t + j) : row;
+        const bf16x8* p = reinterpret_cast<const bf16x8*>(Kbg + Rows::offset(page, prow, stride_b, stride_n)) + 4 * kb;
 #pragma unroll
         for (int kk = 0; kk < 4; ++kk) Bt[t][kk] = p[kk];
       }
     };
+    auto lookup = [&](int ids) { return Rows::phys(page, b, (ids < 0 || ids >= n) ? 0 : ids); };
     auto consume = [&](bf16x8 (&Bt)[4][4], int (&rows)[4], int base_slot) {
 #pragma unroll
       for (int t = 0; t < 4; ++t) {
@@ -305,26 +314,86 @@ __global__ __launch_bounds__(kScoreThreads, 2) void k_filter_score_bf16(
     // (the vector-memory counter completes in issue order).
     bf16x8 Bt0[4][4], Bt1[4][4];
     int rows0[4], rows1[4];
-    const int ids_0 = fetch_ids(seg_lo);
-    int ids_b = fetch_ids(seg_lo + T);                  // ids of the next odd tile
-    int ids_a = fetch_ids(seg_lo + 2 * T);              // ids of the next even tile
-    issue(Bt0, rows0, ids_0);
-    load_query_operand<G>(A, q, (int64_t)b * s.Hq + (int64_t)g * G, j, kb);   // overlaps the first tile's latency
     int base_slot = seg_lo;
-    for (; base_slot + 2 * T < seg_hi; base_slot += 2 * T) {   // at least three tiles left: no conditions inside
-      issue(Bt1, rows1, ids_b);
-      ids_b = fetch_ids(base_slot + 3 * T);
-      consume(Bt0, rows0, base_slot);
-      issue(Bt0, rows0, ids_a);
-      ids_a = fetch_ids(base_slot + 4 * T);
-      consume(Bt1, rows1, base_slot + T);
-    }
-    if (base_slot + T < seg_hi) {                       // two tiles left (wave-uniform)
-      issue(Bt1, rows1, ids_b);
-      consume(Bt0, rows0, base_slot);
-      consume(Bt1, rows1, base_slot + T);
+    if constexpr (!kPaged) {
+      const int ids_0 = fetch_ids(seg_lo);
+      int ids_b = fetch_ids(seg_lo + T);                  // ids of the next odd tile
+      int ids_a = fetch_ids(seg_lo + 2 * T);              // ids of the next even tile
+      issue(Bt0, rows0, ids_0, 0);
+      load_query_operand<G>(A, q, (int64_t)b * s.Hq + (int64_t)g * G, j, kb);   // overlaps the first tile's latency
+      for (; base_slot + 2 * T < seg_hi; base_slot += 2 * T) {   // at least three tiles left: no conditions inside
+        issue(Bt1, rows1, ids_b, 0);
+        ids_b = fetch_ids(base_slot + 3 * T);
+        consume(Bt0, rows0, base_slot);
+        issue(Bt0, rows0, ids_a, 0);
+        ids_a = fetch_ids(base_slot + 4 * T);
+        consume(Bt1, rows1, base_slot + T);
+      }
+      if (base_slot + T < seg_hi) {                       // two tiles left (wave-uniform)
+        issue(Bt1, rows1, ids_b, 0);
+        consume(Bt0, rows0, base_slot);
+        consume(Bt1, rows1, base_slot + T);
+      } else {
+        consume(Bt0, rows0, base_slot);
+      }
     } else {
-      consume(Bt0, rows0, base_slot);
+      // Paged cache: a block-table lookup sits between a row id and its address.  A wait completes
+      // everything older than what it waits for, so with tile i in flight every step issues, BEFORE
+      // the loads of tile i+1: the ids of tile i+3 and the lookup for tile i+2 (whose ids were fetched
+      // one step earlier, before the loads of tile i).  The lane shuffles that spread ids and physical
+      // rows of tile i+1 over the wave come first, so that the registers can be refilled in place.
+      int prow[4];
+      auto aim = [&](int (&rows)[4], int ids, int phys) {
+#pragma unroll
+        for (int t = 0; t < 4; ++t) {
+          const int row = __shfl(ids, 16 * t + j);
+          rows[t] = (row < 0 || row >= n) ? 0 : row;
+          prow[t] = __shfl(phys, 16 * t + j);
+        }
+      };
+      auto fire = [&](bf16x8 (&Bt)[4][4]) {
+#pragma unroll
+        for (int t = 0; t < 4; ++t) {
+          const bf16x8* p =
+              reinterpret_cast<const bf16x8*>(Kbg + Rows::offset(page, prow[t], stride_b, stride_n)) + 4 * kb;
+#pragma unroll
+          for (int kk = 0; kk < 4; ++kk) Bt[t][kk] = p[kk];
+        }
+      };
+      int ids_0 = fetch_ids(seg_lo), ids_1 = fetch_ids(seg_lo + T);
+      int phys_0 = lookup(ids_0), phys_1 = lookup(ids_1);
+      aim(rows0, ids_0, phys_0);
+      ids_0 = fetch_ids(seg_lo + 2 * T);
+      __builtin_amdgcn_sched_barrier(0);
+      fire(Bt0);
+      load_query_operand<G>(A, q, (int64_t)b * s.Hq + (int64_t)g * G, j, kb);
+      // here and at the top of every iteration: (ids_1, phys_1) describe the next odd tile, ids_0 the next even one
+      for (; base_slot + 2 * T < seg_hi; base_slot += 2 * T) {
+        aim(rows1, ids_1, phys_1);
+        ids_1 = fetch_ids(base_slot + 3 * T);
+        phys_0 = lookup(ids_0);
+        __builtin_amdgcn_sched_barrier(0);      // the instruction scheduler must not move these two loads
+        fire(Bt1);                              // behind the tile's: the order is what the waits rely on
+        consume(Bt0, rows0, base_slot);
+        aim(rows0, ids_0, phys_0);
+        ids_0 = fetch_ids(base_slot + 4 * T);
+        phys_1 = lookup(ids_1);
+        __builtin_amdgcn_sched_barrier(0);
+        fire(Bt0);
+        consume(Bt1, rows1, base_slot + T);
+      }
+      if (base_slot + T < seg_hi) {
+        aim(rows1, ids_1, phys_1);
+        fire(Bt1);
+        consume(Bt0, rows0, base_slot);
+        consume(Bt1, rows1, base_slot + T);
+      } else {
+        consume(Bt0, rows0, base_slot);
+      }
+      // A use of the prefetched ids on every path: without it the compiler moves the prologue's fetch of
+      // ids_0 down to the loop entry, behind the first tile's loads, and the loop's first wait for it
+      // becomes a wait for everything.
+      asm volatile("" ::"v"(ids_0), "v"(ids_1));
     }
     flush();
     if (j == 0 && kb < G) seg_count[head * nseg + seg] = run;
@@ -333,10 +402,10 @@ __global__ __launch_bounds__(kScoreThreads, 2) void k_filter_score_bf16(
 }
 
 // ----------------------------------------------------------------------------- fp32, vector ALU
-template <int G, bool GATHER>
+template <int G, bool GATHER, bool kPaged>
 __global__ __launch_bounds__(kScoreThreads) void k_group_score_f32(Shape s, const float* __restrict__ q,
                                                                    const float* __restrict__ K, int64_t stride_b,
-                                                                   int64_t stride_h, int64_t stride_n,
+                                                                   int64_t stride_h, int64_t stride_n, KvPage pg,
                                                                    const int32_t* __restrict__ seq_lens,
                                                                    const int32_t* __restrict__ cand,
                                                                    const int32_t* __restrict__ cand_count,
@@ -360,7 +429,8 @@ __global__ __launch_bounds__(kScoreThreads) void k_group_score_f32(Shape s, cons
 #pragma unroll
     for (int c = 0; c < 8; ++c) qr[h][c] = qh[c];
   }
-  const float* Kbg = K + (int64_t)b * stride_b + (int64_t)g * stride_h;
+  using Rows = RowMap<kPaged>;
+  const float* Kbg = K + Rows::base(b, g, stride_b, stride_h);
   const int32_t* cbg = GATHER ? cand + (int64_t)bg * s.cand_cap : nullptr;
   float* sc = score + ((int64_t)b * s.Hq + (int64_t)g * G) * score_stride;
   const int step = gridDim.x * 4 * kRowsPerWaveIter;
@@ -368,11 +438,13 @@ __global__ __launch_bounds__(kScoreThreads) void k_group_score_f32(Shape s, cons
   for (int base = first; base < count; base += step) {
     int my_row = -1;
     if (base + lane < count) my_row = GATHER ? cbg[base + lane] : base + lane;
+    const bool my_ok = my_row >= 0 && my_row < n;
+    const int my_phys = Rows::phys(pg, b, my_ok ? my_row : 0);
 #pragma unroll 4
     for (int t = 0; t < 16; ++t) {
-      int row = __shfl(my_row, 4 * t + rs);
-      bool ok = row >= 0 && row < n;
-      const float4* p = reinterpret_cast<const float4*>(Kbg + (int64_t)(ok ? row : 0) * stride_n) + 2 * j;
+      const bool ok = __shfl((int)my_ok, 4 * t + rs) != 0;
+      const int prow = __shfl(my_phys, 4 * t + rs);
+      const float4* p = reinterpret_cast<const float4*>(Kbg + Rows::offset(pg, prow, stride_b, stride_n)) + 2 * j;
       float4 x0 = p[0], x1 = p[1];
       float acc[G];
 #pragma unroll
@@ -406,9 +478,9 @@ __global__ __launch_bounds__(kScoreThreads) void k_group_score_f32(Shape s, cons
 // ----------------------------------------------------------------------------- per-head index lists
 // Scores of idx[b,h,0:k_b] against q[b,h]; 16 lanes per row.  Used only when the caller of the
 // sparse attention does not supply scores.  grid: (ceil(kmax/256), B*Hq).
-template <typename T>
+template <typename T, bool kPaged>
 __global__ __launch_bounds__(256) void k_head_score(Shape s, const float* __restrict__ q, const T* __restrict__ K,
-                                                    int64_t stride_b, int64_t stride_h, int64_t stride_n,
+                                                    int64_t stride_b, int64_t stride_h, int64_t stride_n, KvPage pg,
                                                     const int32_t* __restrict__ seq_lens,
                                                     const int32_t* __restrict__ idx, const int32_t* __restrict__ kk,
                                                     float* __restrict__ out, float scale) {
@@ -425,12 +497,15 @@ __global__ __launch_bounds__(256) void k_head_score(Shape s, const float* __rest
   const float* qh = q + (int64_t)bh * kD + 8 * j;
 #pragma unroll
   for (int c = 0; c < 8; ++c) qr[c] = qh[c];
-  const T* Kbg = K + (int64_t)b * stride_b + (int64_t)g * stride_h;
-  int my_row = (base + lane < kb) ? idx[(int64_t)bh * s.kmax + base + lane] : -1;
+  using Rows = RowMap<kPaged>;
+  const T* Kbg = K + Rows::base(b, g, stride_b, stride_h);
+  const int my_row = (base + lane < kb) ? idx[(int64_t)bh * s.kmax + base + lane] : -1;
+  const bool my_ok = my_row >= 0 && my_row < n;
+  const int my_phys = Rows::phys(pg, b, my_ok ? my_row : 0);
   for (int t = 0; t < 16; ++t) {
-    int row = __shfl(my_row, 4 * t + rs);
-    bool ok = row >= 0 && row < n;
-    const T* p = Kbg + (int64_t)(ok ? row : 0) * stride_n + 8 * j;
+    const bool ok = __shfl((int)my_ok, 4 * t + rs) != 0;
+    const int prow = __shfl(my_phys, 4 * t + rs);
+    const T* p = Kbg + Rows::offset(pg, prow, stride_b, stride_n) + 8 * j;
     float x[8];
     if constexpr (sizeof(T) == 2) {
       u32x4 w = *reinterpret_cast<const u32x4*>(p);
@@ -468,12 +543,19 @@ static hipError_t launch_gs(const Shape& s, int dtype, const float* q, const KvV
   if (gx < 1) gx = 1;
   dim3 grid(gx, s.B * s.Hkv), block(kScoreThreads);
   const float scale = 0.08838834764831845f;   // 1/sqrt(128)
-  if (dtype == LFPS_BF16)
-    hipLaunchKernelGGL((k_group_score_bf16<G, GATHER>), grid, block, 0, st, s, q, (const __bf16*)kv.k, kv.stride_b,
-                       kv.stride_h, kv.stride_n, kv.seq_lens, cand, cand_count, score, score_stride, scale, only_if);
-  else
-    hipLaunchKernelGGL((k_group_score_f32<G, GATHER>), grid, block, 0, st, s, q, (const float*)kv.k, kv.stride_b,
-                       kv.stride_h, kv.stride_n, kv.seq_lens, cand, cand_count, score, score_stride, scale, only_if);
+#define LFPS_LAUNCH_GS(KERNEL, TYPE, PAGED)                                                                       \
+  hipLaunchKernelGGL((KERNEL<G, GATHER, PAGED>), grid, block, 0, st, s, q, (const TYPE*)kv.k, kv.stride_b,         \
+                     kv.stride_h, kv.stride_n, kv.page, kv.seq_lens, cand, cand_count, score, score_stride, scale, \
+                     only_if)
+  const bool paged = kv.page.table != nullptr;
+  if (dtype == LFPS_BF16) {
+    if (paged) LFPS_LAUNCH_GS(k_group_score_bf16, __bf16, true);
+    else LFPS_LAUNCH_GS(k_group_score_bf16, __bf16, false);
+  } else {
+    if (paged) LFPS_LAUNCH_GS(k_group_score_f32, float, true);
+    else LFPS_LAUNCH_GS(k_group_score_f32, float, false);
+  }
+#undef LFPS_LAUNCH_GS
   return hipGetLastError();
 }
 
@@ -500,7 +582,12 @@ template <int G>
 static hipError_t filter_resident_blocks(int* out) {
   int per_cu = 0, dev = 0;
   hipDeviceProp_t prop;
-  hipError_t e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, k_filter_score_bf16<G>, kScoreThreads, 0);
+  // the paged variant keeps a few more registers live; both must fit the same launch size
+  hipError_t e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, k_filter_score_bf16<G, false>, kScoreThreads, 0);
+  int per_cu_paged = 0;
+  if (e == hipSuccess)
+    e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu_paged, k_filter_score_bf16<G, true>, kScoreThreads, 0);
+  if (per_cu_paged < per_cu) per_cu = per_cu_paged;
   if (e == hipSuccess) e = hipGetDevice(&dev);
   if (e == hipSuccess) e = hipGetDeviceProperties(&prop, dev);
   if (e != hipSuccess) return e;
@@ -527,17 +614,24 @@ hipError_t launch_filter_score(const Shape& s, const float* q, const KvView& kv,
   if (n_blocks < 1) return hipErrorInvalidValue;
   dim3 grid((unsigned)n_blocks), block(kScoreThreads);
   const float scale = 0.08838834764831845f;
-#define LFPS_LAUNCH_FILTER(GG)                                                                                     \
-  hipLaunchKernelGGL((k_filter_score_bf16<GG>), grid, block, 0, st, s, q, (const __bf16*)kv.k, kv.stride_b,       \
-                     kv.stride_h, kv.stride_n, kv.seq_lens, cand, cand_count, group_start, line_total, thr_state, margin, score, \
-                     slot_out,                                                                                     \
-                     score_stride, seg_count, seg_rows_out, filter_min_seg_rows(s), nseg, scale)
+#define LFPS_LAUNCH_FILTER_P(GG, PAGED)                                                                            \
+  hipLaunchKernelGGL((k_filter_score_bf16<GG, PAGED>), grid, block, 0, st, s, q, (const __bf16*)kv.k, kv.stride_b, \
+                     kv.stride_h, kv.stride_n, kv.page, kv.seq_lens, cand, cand_count, group_start, line_total,    \
+                     thr_state, margin, score, slot_out, score_stride, seg_count, seg_rows_out,                    \
+                     filter_min_seg_rows(s), nseg, scale)
+#define LFPS_LAUNCH_FILTER(GG)                 \
+  if (kv.page.table) {                         \
+    LFPS_LAUNCH_FILTER_P(GG, true);            \
+  } else {                                     \
+    LFPS_LAUNCH_FILTER_P(GG, false);           \
+  }
   switch (s.G) {
     case 1: LFPS_LAUNCH_FILTER(1); break;
     case 2: LFPS_LAUNCH_FILTER(2); break;
     case 4: LFPS_LAUNCH_FILTER(4); break;
     default: return hipErrorInvalidValue;
   }
+#undef LFPS_LAUNCH_FILTER_P
 #undef LFPS_LAUNCH_FILTER
   return hipGetLastError();
 }
@@ -546,12 +640,18 @@ hipError_t launch_head_score(const Shape& s, int dtype, const float* q, const Kv
                              const int32_t* k, float* idx_score, hipStream_t st) {
   dim3 grid((s.kmax + 255) / 256, s.B * s.Hq), block(256);
   const float scale = 0.08838834764831845f;
-  if (dtype == LFPS_BF16)
-    hipLaunchKernelGGL((k_head_score<uint16_t>), grid, block, 0, st, s, q, (const uint16_t*)kv.k, kv.stride_b,
-                       kv.stride_h, kv.stride_n, kv.seq_lens, idx, k, idx_score, scale);
-  else
-    hipLaunchKernelGGL((k_head_score<float>), grid, block, 0, st, s, q, (const float*)kv.k, kv.stride_b, kv.stride_h,
-                       kv.stride_n, kv.seq_lens, idx, k, idx_score, scale);
+#define LFPS_LAUNCH_HS(TYPE, PAGED)                                                                            \
+  hipLaunchKernelGGL((k_head_score<TYPE, PAGED>), grid, block, 0, st, s, q, (const TYPE*)kv.k, kv.stride_b,     \
+                     kv.stride_h, kv.stride_n, kv.page, kv.seq_lens, idx, k, idx_score, scale)
+  const bool paged = kv.page.table != nullptr;
+  if (dtype == LFPS_BF16) {
+    if (paged) LFPS_LAUNCH_HS(uint16_t, true);
+    else LFPS_LAUNCH_HS(uint16_t, false);
+  } else {
+    if (paged) LFPS_LAUNCH_HS(float, true);
+    else LFPS_LAUNCH_HS(float, false);
+  }
+#undef LFPS_LAUNCH_HS
   return hipGetLastError();
 }
 

@@ -486,9 +486,9 @@ __global__ __launch_bounds__(kTabThreads) void k_table_finish(Shape s, const flo
 // A head with rho > eps is bypassed: its output row is vbar, its index row -1 (Alg. 1 lines 1-4); the later
 // kernels of the step skip it.  The three terms are kept as exponent + log-sum so that a dominant sink
 // (logit in the hundreds) cannot overflow.
-template <typename T>
+template <typename T, bool kPaged>
 __global__ __launch_bounds__(64) void k_head_sparsity(Shape s, const float* __restrict__ q, const T* __restrict__ K,
-                                                      int64_t stride_b, int64_t stride_h, int64_t stride_n,
+                                                      int64_t stride_b, int64_t stride_h, int64_t stride_n, KvPage pg,
                                                       const int32_t* __restrict__ seq_lens,
                                                       const float* __restrict__ kbar,
                                                       const float* __restrict__ sigma2_hat, int n_local, float eps,
@@ -500,16 +500,18 @@ __global__ __launch_bounds__(64) void k_head_sparsity(Shape s, const float* __re
   n = n < 0 ? 0 : (n > s.Lcap ? s.Lcap : n);
   const float scale = 0.08838834764831845f;
   const float q0 = q[(int64_t)bh * kD + 2 * lane], q1 = q[(int64_t)bh * kD + 2 * lane + 1];
-  const T* Kbg = K + (int64_t)b * stride_b + (int64_t)g * stride_h;
+  using Rows = RowMap<kPaged>;
+  const T* Kbg = K + Rows::base(b, g, stride_b, stride_h);
   auto logit_of_row = [&](int row) {
     float k0, k1;
+    const T* kr = Kbg + Rows::offset(pg, Rows::phys(pg, b, row), stride_b, stride_n) + 2 * lane;
     if constexpr (sizeof(T) == 2) {
-      const uint32_t w = *reinterpret_cast<const uint32_t*>(Kbg + (int64_t)row * stride_n + 2 * lane);
+      const uint32_t w = *reinterpret_cast<const uint32_t*>(kr);
       k0 = bf16_lo(w);
       k1 = bf16_hi(w);
     } else {
-      k0 = (float)Kbg[(int64_t)row * stride_n + 2 * lane];
-      k1 = (float)Kbg[(int64_t)row * stride_n + 2 * lane + 1];
+      k0 = (float)kr[0];
+      k1 = (float)kr[1];
     }
     float d = fmaf(q1, k1, q0 * k0);
 #pragma unroll
@@ -561,9 +563,9 @@ __global__ __launch_bounds__(64) void k_head_sparsity(Shape s, const float* __re
 // ----------------------------------------------------------------------------- prefill priors (Sec. 4.2 "Prefilling")
 // Mean K row and mean V row over rows [n_sink, n_b) of one (b, g).  1024 threads: 64 row slots x 16 lanes
 // of 8 channels; fp32 partial sums per thread, fp64 across the row slots.
-template <typename T>
+template <typename T, bool kPaged>
 __global__ __launch_bounds__(1024) void k_prior_means(Shape s, const T* __restrict__ K, const T* __restrict__ V,
-                                                      int64_t stride_b, int64_t stride_h, int64_t stride_n,
+                                                      int64_t stride_b, int64_t stride_h, int64_t stride_n, KvPage pg,
                                                       const int32_t* __restrict__ seq_lens, float* __restrict__ kbar,
                                                       float* __restrict__ vbar) {
   __shared__ float red[64][16][8];
@@ -571,22 +573,24 @@ __global__ __launch_bounds__(1024) void k_prior_means(Shape s, const T* __restri
   const int slot = tid >> 4, j = tid & 15;
   int n = seq_lens[b];
   n = n < 0 ? 0 : (n > s.Lcap ? s.Lcap : n);
-  const int64_t base = (int64_t)b * stride_b + (int64_t)g * stride_h + 8 * j;
+  using Rows = RowMap<kPaged>;
+  const int64_t base = Rows::base(b, g, stride_b, stride_h) + 8 * j;
   for (int which = 0; which < 2; ++which) {
-    const T* X = (which == 0 ? K : V) + base;
+    const T* X0 = (which == 0 ? K : V) + base;
     float acc[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
     for (int r = s.n_sink + slot; r < n; r += 64) {
       float x[8];
+      const T* X = X0 + Rows::offset(pg, Rows::phys(pg, b, r), stride_b, stride_n);
       if constexpr (sizeof(T) == 2) {
-        const u32x4 w = *reinterpret_cast<const u32x4*>(X + (int64_t)r * stride_n);
+        const u32x4 w = *reinterpret_cast<const u32x4*>(X);
 #pragma unroll
         for (int c = 0; c < 4; ++c) {
           x[2 * c] = bf16_lo(w[c]);
           x[2 * c + 1] = bf16_hi(w[c]);
         }
       } else {
-        const float4 a0 = reinterpret_cast<const float4*>(X + (int64_t)r * stride_n)[0];
-        const float4 a1 = reinterpret_cast<const float4*>(X + (int64_t)r * stride_n)[1];
+        const float4 a0 = reinterpret_cast<const float4*>(X)[0];
+        const float4 a1 = reinterpret_cast<const float4*>(X)[1];
         x[0] = a0.x; x[1] = a0.y; x[2] = a0.z; x[3] = a0.w;
         x[4] = a1.x; x[5] = a1.y; x[6] = a1.z; x[7] = a1.w;
       }
@@ -698,24 +702,35 @@ hipError_t launch_table_finish(const Shape& s, const float* tab_ver, const float
 hipError_t launch_head_sparsity(const Shape& s, int dtype, const float* q, const KvView& kv, const float* kbar,
                                 const float* sigma2_hat, int n_local, float eps, float* rho, int32_t* gate,
                                 const float* vbar, int32_t* topk_idx, float* topk_score, float* out, hipStream_t st) {
-  if (dtype == LFPS_BF16)
-    hipLaunchKernelGGL((k_head_sparsity<uint16_t>), dim3(s.B * s.Hq), dim3(64), 0, st, s, q, (const uint16_t*)kv.k,
-                       kv.stride_b, kv.stride_h, kv.stride_n, kv.seq_lens, kbar, sigma2_hat, n_local, eps, rho, gate,
-                       vbar, topk_idx, topk_score, out);
-  else
-    hipLaunchKernelGGL((k_head_sparsity<float>), dim3(s.B * s.Hq), dim3(64), 0, st, s, q, (const float*)kv.k,
-                       kv.stride_b, kv.stride_h, kv.stride_n, kv.seq_lens, kbar, sigma2_hat, n_local, eps, rho, gate,
-                       vbar, topk_idx, topk_score, out);
+#define LFPS_LAUNCH_HSP(TYPE, PAGED)                                                                             \
+  hipLaunchKernelGGL((k_head_sparsity<TYPE, PAGED>), dim3(s.B * s.Hq), dim3(64), 0, st, s, q, (const TYPE*)kv.k,     \
+                     kv.stride_b, kv.stride_h, kv.stride_n, kv.page, kv.seq_lens, kbar, sigma2_hat, n_local, eps, rho, \
+                     gate, vbar, topk_idx, topk_score, out)
+  const bool paged = kv.page.table != nullptr;
+  if (dtype == LFPS_BF16) {
+    if (paged) LFPS_LAUNCH_HSP(uint16_t, true);
+    else LFPS_LAUNCH_HSP(uint16_t, false);
+  } else {
+    if (paged) LFPS_LAUNCH_HSP(float, true);
+    else LFPS_LAUNCH_HSP(float, false);
+  }
+#undef LFPS_LAUNCH_HSP
   return hipGetLastError();
 }
 
 hipError_t launch_prior_means(const Shape& s, int dtype, const KvView& kv, float* kbar, float* vbar, hipStream_t st) {
-  if (dtype == LFPS_BF16)
-    hipLaunchKernelGGL((k_prior_means<uint16_t>), dim3(s.B * s.Hkv), dim3(1024), 0, st, s, (const uint16_t*)kv.k,
-                       (const uint16_t*)kv.v, kv.stride_b, kv.stride_h, kv.stride_n, kv.seq_lens, kbar, vbar);
-  else
-    hipLaunchKernelGGL((k_prior_means<float>), dim3(s.B * s.Hkv), dim3(1024), 0, st, s, (const float*)kv.k,
-                       (const float*)kv.v, kv.stride_b, kv.stride_h, kv.stride_n, kv.seq_lens, kbar, vbar);
+#define LFPS_LAUNCH_PM(TYPE, PAGED)                                                                              \
+  hipLaunchKernelGGL((k_prior_means<TYPE, PAGED>), dim3(s.B * s.Hkv), dim3(1024), 0, st, s, (const TYPE*)kv.k,       \
+                     (const TYPE*)kv.v, kv.stride_b, kv.stride_h, kv.stride_n, kv.page, kv.seq_lens, kbar, vbar)
+  const bool paged = kv.page.table != nullptr;
+  if (dtype == LFPS_BF16) {
+    if (paged) LFPS_LAUNCH_PM(uint16_t, true);
+    else LFPS_LAUNCH_PM(uint16_t, false);
+  } else {
+    if (paged) LFPS_LAUNCH_PM(float, true);
+    else LFPS_LAUNCH_PM(float, false);
+  }
+#undef LFPS_LAUNCH_PM
   return hipGetLastError();
 }
 
