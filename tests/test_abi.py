@@ -62,3 +62,32 @@ def test_kernel_names():
     from paper_2506_15704_amd import binding as b
     names = b.kernel_names()
     assert len(names) == b.N_KERNELS and names[0] == "candidates" and "gather_score" in names
+
+
+def _struct_fields(name):
+    """(C type, field name) pairs of `typedef struct { ... } name;` in the header, in order."""
+    src = open(HEADER).read()
+    src = re.sub(r"/\*.*?\*/", "", src, flags=re.S)
+    body = re.search(r"typedef struct \{([^}]*)\}\s*" + name + r"\s*;", src).group(1)
+    out = []
+    for decl in body.split(";"):
+        decl = decl.strip()
+        if not decl:
+            continue
+        parts = [p.strip() for p in decl.split(",")]
+        m = re.match(r"(.+?[\s\*])([A-Za-z_0-9]+)$", parts[0])      # "<type> <first name>"
+        ctype = m.group(1).strip()
+        if ctype.endswith("*"):
+            ctype = "ptr"
+        for n in [m.group(2)] + parts[1:]:
+            out.append((ctype, n))
+    return out
+
+
+def test_binding_structs_mirror_the_header_field_by_field():
+    from paper_2506_15704_amd import binding as b
+    ctype_of = {"int32_t": ctypes.c_int32, "int64_t": ctypes.c_int64, "float": ctypes.c_float, "ptr": ctypes.c_void_p}
+    for name, cls in (("lfps_config", b.lfps_config), ("lfps_kv", b.lfps_kv)):
+        want = [(n, ctype_of[t]) for t, n in _struct_fields(name)]
+        got = [(f[0], f[1]) for f in cls._fields_]
+        assert got == want, f"{name}: binding {got} != header {want}"
