@@ -43,6 +43,8 @@ def parse_args():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-table-mode", action="store_true", help="skip the score-table mode legs")
     ap.add_argument("--no-paged", action="store_true", help="skip the paged-cache leg")
+    ap.add_argument("--no-fp8", action="store_true", help="skip the FP8-keys leg")
+    ap.add_argument("--fp8-only", action="store_true", help="run only the FP8-keys leg of --workload")
     ap.add_argument("--paged-only", action="store_true", help="run only the paged-cache leg of --workload")
     ap.add_argument("--paged-block", type=int, default=16, help="rows per block of the paged-cache leg")
     ap.add_argument("--paged-layout", default="block_head_row", choices=["block_head_row", "block_row_head"],
@@ -51,14 +53,15 @@ def parse_args():
                     help="run only the score-table mode of the main workload (for profiling) and print its record")
     ap.add_argument("--calib-copy", action="store_true",
                     help="run only the plain copy kernel (1 GiB, 10 launches): the known-traffic reference for rocprofv3 --pmc")
-    ap.add_argument("--cpu-seconds", type=float, default=15.0, help="CPU-oracle sample budget")
+    ap.add_argument("--cpu-seconds", type=float, default=12.0, help="CPU-oracle sample budget")
     return ap.parse_args()
 
 
 class Runner:
     """Device state of one workload and the step loop."""
 
-    def __init__(self, name, table_mode=False, n_sink=0, gated=False, paged_block=0, paged_layout="block_head_row"):
+    def __init__(self, name, table_mode=False, n_sink=0, gated=False, paged_block=0, paged_layout="block_head_row",
+                 k_dtype=""):
         import numpy as np
         import torch
 
@@ -68,6 +71,9 @@ class Runner:
 
         self.torch, self.np = torch, np
         self.spec = spec = gen.WORKLOADS[name]
+        if k_dtype:          # the same workload with the keys stored in another format
+            import dataclasses
+            self.spec = spec = dataclasses.replace(spec, name=f"{name}-{k_dtype}k", k_dtype=k_dtype)
         self.case = case = gen.make_case(spec)
         self.dev = "cuda:0"
         self.K, self.V = gen_device.fill_kv(case, self.dev)
@@ -78,7 +84,8 @@ class Runner:
             self.K, self.V = Kp, Vp
         self.ctx = Lfps(batch=spec.B, n_q_heads=spec.Hq, n_kv_heads=spec.Hkv, head_dim=spec.D,
                         kv_dtype=spec.kv_dtype, max_seq_len=case.Lcap, max_k=case.kmax, radius=spec.r,
-                        n_recent=1, n_sink=n_sink, table_mode=table_mode, table_decay=0.95, table_a=0.2)
+                        n_recent=1, n_sink=n_sink, table_mode=table_mode, table_decay=0.95, table_a=0.2,
+                        k_fp8=spec.k_dtype == "fp8")
         self.table_mode = table_mode
         self.gated = gated
         if gated:        # prefill priors of the bypass (Sec. 4.2 "Prefilling"), from the step-0 query
@@ -244,7 +251,7 @@ def algorithmic_bytes_score(spec, case, cnts, filtered):
     """Bytes one scoring launch must move.  Per candidate row: its K row (R = D*e bytes) and its
     position (4).  Output: unfiltered, G scores per row (4G); filtered, at least the k selected
     (score, slot) pairs per head (8 k G per group).  Plus the G query rows per (b, g)."""
-    e = 2 if spec.kv_dtype == "bf16" else 4
+    e = 1 if spec.k_dtype == "fp8" else (2 if spec.kv_dtype == "bf16" else 4)
     rows = cnts.sum(axis=(1, 2)).astype(float)
     per_group = spec.G * spec.D * 4
     if filtered:
@@ -323,6 +330,34 @@ def measure_paged(name, steps, warmup, block_size=16, layout="block_head_row"):
     return res
 
 
+def measure_fp8_keys(name, steps, warmup):
+    """The main workload with K stored as OCP FP8 E4M3 (the same draws rounded to 3 mantissa bits; V stays
+    bf16): half the bytes per scored row.  A different input, so nothing is compared with the bf16 run."""
+    r = Runner(name, k_dtype="fp8")
+    spec = r.spec
+    if steps <= 0:
+        steps = max(1, spec.T - warmup)
+    sec = r.run_timed(steps, warmup)
+    recall = r.recall_vs_exact()
+    tm, cnts = r.run_kernel_timing(steps, warmup)
+    filtered = tm["filter_score"][1] > 0
+    kname = "filter_score" if filtered else "gather_score"
+    by = float(algorithmic_bytes_score(spec, r.case, cnts, filtered).mean())
+    us = tm[kname][0] / max(tm[kname][1], 1) * 1e3
+    exact = r.time_baseline("exact", 5)
+    full = r.time_baseline("full", 5)
+    res = {"k_dtype": "fp8 e4m3 (V bf16)", "ms_per_step": round(sec * 1e3, 4), "steps_per_s": round(1.0 / sec, 2),
+           "cand_frac": round(float(cnts.mean() / (spec.L or r.case.seq_lens0.mean())), 4),
+           "recall_vs_exact_topk": round(recall, 4),
+           "kernel_us": {k: round(v[0] / steps * 1e3, 2) for k, v in tm.items() if v[1]},
+           "score_kernel": {"kernel": kname, "bytes_per_launch": round(by), "avg_launch_us": round(us, 2),
+                            "GB_per_s": round(by / (us * 1e-6) / 1e9, 1) if us > 0 else None,
+                            "frac_of_hbm_peak": round(by / (us * 1e-6) / 1e9 / HBM_PEAK_GBS, 4) if us > 0 else None},
+           "exact_topk_ms": round(exact * 1e3, 4), "full_attn_ms": round(full * 1e3, 4)}
+    r.close()
+    return res
+
+
 def measure_tables(name, steps, warmup):
     """The same workload with the paper's own candidate rule (score tables, Eq. 7-10): lfps_table_step per step,
     tables initialised from the step-0 query (Eq. 4 with one query) during warm-up; first four rows = sinks,
@@ -380,7 +415,10 @@ def cpu_baseline(case, budget_s):
     from oracle import lfps_oracle as orc
 
     spec = case.spec
-    groups = [(0, 0), (spec.B - 1, spec.Hkv - 1), (spec.B // 2, 3)]
+    # sampled (request, KV group) pairs, taken in this order until the time budget is spent
+    groups = [(0, 0), (spec.B - 1, spec.Hkv - 1), (spec.B // 2, 3 % spec.Hkv)]
+    groups += [((5 * i + 1) % spec.B, (3 * i + 1) % spec.Hkv) for i in range(24)]
+    groups = list(dict.fromkeys(groups))
     n_steps_max = spec.T
     spent, done = 0.0, 0
     t_start = time.perf_counter()
@@ -454,6 +492,10 @@ def main():
         print(json.dumps({"workload": args.workload, "score_table_mode": measure_tables(args.workload, args.steps, args.warmup)}),
               flush=True)
         return
+    if args.fp8_only:
+        print(json.dumps({"workload": args.workload, "fp8_keys": measure_fp8_keys(args.workload, args.steps, args.warmup)}),
+              flush=True)
+        return
     if args.paged_only:
         print(json.dumps({"workload": args.workload,
                           "paged_kv": measure_paged(args.workload, args.steps, args.warmup, args.paged_block, args.paged_layout)}),
@@ -482,6 +524,8 @@ def main():
         tab = measure_tables(args.workload, args.steps, args.warmup)
         tab["speedup_vs_memoryless_step"] = round(main_res["ms_per_step"] / tab["ms_per_step"], 3)
         line["score_table_mode"] = tab
+    if not args.no_fp8 and spec.kv_dtype == "bf16":
+        line["fp8_keys"] = measure_fp8_keys(args.workload, args.steps, args.warmup)
     if not args.no_paged:
         line["paged_kv"] = measure_paged(args.workload, args.steps, args.warmup, args.paged_block, args.paged_layout)
     if args.all_workloads:

@@ -92,6 +92,42 @@ def bf16_bits_to_f32(bits: np.ndarray) -> np.ndarray:
     return (bits.astype(np.uint32) << np.uint32(16)).view(np.float32)
 
 
+def f32_to_e4m3_bits(x: np.ndarray) -> np.ndarray:
+    """Round-to-nearest-even fp32 -> OCP FP8 E4M3 bit patterns, saturating at +-448 (finite inputs).
+    E4M3: 1 sign, 4 exponent (bias 7), 3 mantissa bits; subnormals are multiples of 2^-9; no infinities."""
+    x = np.ascontiguousarray(x, dtype=np.float32)
+    sign = (x.view(np.uint32) >> np.uint32(24)) & np.uint32(0x80)
+    a = np.abs(x)
+    # normal range: drop 20 mantissa bits with round-to-nearest-even on the bit pattern
+    u = a.view(np.uint32).astype(np.uint32)
+    u = u + np.uint32(0x7FFFF) + ((u >> np.uint32(20)) & np.uint32(1))
+    e = (u >> np.uint32(23)).astype(np.int64) - 127 + 7          # biased E4M3 exponent
+    m = (u >> np.uint32(20)) & np.uint32(7)
+    normal = (np.clip(e, 0, 15).astype(np.uint32) << np.uint32(3)) | m
+    normal = np.where((e > 15) | ((e == 15) & (m == 7)), np.uint32(0x7E), normal)   # beyond 448: saturate
+    # below 2^-6: a multiple of 2^-9, rounded to nearest even (8 * 2^-9 is the smallest normal, bits 0x08)
+    sub = np.rint(a * np.float32(512.0)).astype(np.uint32)
+    bits = np.where(a < np.float32(2.0 ** -6), sub, normal)
+    return (bits | sign).astype(np.uint8)
+
+
+def _e4m3_table() -> np.ndarray:
+    t = np.zeros(256, dtype=np.float32)
+    for b in range(256):
+        e, m = (b >> 3) & 15, b & 7
+        v = (m / 8.0) * 2.0 ** -6 if e == 0 else (1.0 + m / 8.0) * 2.0 ** (e - 7)
+        t[b] = -v if b & 0x80 else v
+    t[0x7F] = t[0xFF] = np.nan
+    return t
+
+
+E4M3_VALUES = _e4m3_table()
+
+
+def e4m3_bits_to_f32(bits: np.ndarray) -> np.ndarray:
+    return E4M3_VALUES[np.asarray(bits, dtype=np.uint8)]
+
+
 def _rms(x: np.ndarray) -> np.ndarray:
     """Scale the last axis to unit root-mean-square."""
     n = np.sqrt(np.mean(np.square(x), axis=-1, keepdims=True))
@@ -105,6 +141,7 @@ class CaseSpec:
     L: Optional[int] = None                 # fixed context length ...
     L_range: Optional[Tuple[int, int]] = None  # ... or ragged, uniform in [lo, hi]
     kv_dtype: str = "bf16"                   # "bf16" | "f32"
+    k_dtype: str = ""                        # "" = same as kv_dtype | "fp8": K stored as OCP FP8 E4M3 (bf16 V)
     k: Optional[int] = None                  # fixed budget ...
     k_frac: Optional[float] = None           # ... or fraction of the initial length, multiple of 64
     r: int = 4                               # expansion radius
@@ -220,7 +257,7 @@ class Case:
         """Regenerate rows of K ("k") or V ("v") of (request b, KV head g) on the CPU.
 
         Returns (values float32 [len(rows), D] as stored, bits) where bits is the uint16
-        bf16 pattern array for bf16 caches and None for fp32 caches."""
+        bf16 pattern array for bf16 caches (uint8 E4M3 patterns for FP8 keys) and None for fp32 caches."""
         spec = self.spec
         D = spec.D
         rows = np.asarray(rows, dtype=np.int64)
@@ -233,6 +270,9 @@ class Case:
         else:
             raise ValueError(which)
         x = x.astype(np.float32)
+        if which == "k" and spec.k_dtype == "fp8":
+            bits = f32_to_e4m3_bits(x)
+            return e4m3_bits_to_f32(bits), bits
         if spec.kv_dtype == "bf16":
             bits = f32_to_bf16_bits(x)
             return bf16_bits_to_f32(bits), bits
@@ -252,7 +292,8 @@ class Case:
 
     def kv_bytes(self) -> int:
         e = 2 if self.spec.kv_dtype == "bf16" else 4
-        return 2 * self.spec.B * self.spec.Hkv * self.Lcap * self.spec.D * e
+        ek = 1 if self.spec.k_dtype == "fp8" else e
+        return self.spec.B * self.spec.Hkv * self.Lcap * self.spec.D * (e + ek)
 
 
 def make_case(spec: CaseSpec) -> Case:

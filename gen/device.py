@@ -39,15 +39,17 @@ def _load():
 
 def fill_kv(case, device="cuda:0"):
     """Allocate K and V [B, Hkv, Lcap, D] on the device and fill them.  Returns (K, V) torch tensors
-    (bfloat16 or float32)."""
+    (bfloat16 or float32; K is float8_e4m3fn when the spec asks for FP8 keys)."""
     import torch
 
     spec = case.spec
     lib = _load()
     dt = torch.bfloat16 if spec.kv_dtype == "bf16" else torch.float32
     shape = (spec.B, spec.Hkv, case.Lcap, spec.D)
-    K = torch.empty(shape, dtype=dt, device=device)
+    k_fp8 = spec.k_dtype == "fp8"
+    K = torch.empty(shape, dtype=torch.float8_e4m3fn if k_fp8 else dt, device=device)
     V = torch.empty(shape, dtype=dt, device=device)
+    fmt = int(spec.kv_dtype == "bf16")
     dev = lambda a: torch.from_numpy(np.ascontiguousarray(a)).to(device)
     key_k = dev(case.key_k.view(np.int64))
     key_v = dev(case.key_v.view(np.int64))
@@ -57,12 +59,12 @@ def fill_kv(case, device="cuda:0"):
     bias = dev(case.bias.astype(np.float32))
     st = torch.cuda.current_stream(device).cuda_stream
     n_hot = spec.n_hot
-    rc = lib.gen_fill_kv(K.data_ptr(), int(spec.kv_dtype == "bf16"), spec.B, spec.Hkv, case.Lcap, n_hot,
+    rc = lib.gen_fill_kv(K.data_ptr(), 2 if k_fp8 else fmt, spec.B, spec.Hkv, case.Lcap, n_hot,
                          key_k.data_ptr(), row_end.data_ptr(), recent.data_ptr(),
                          hot.data_ptr() if n_hot > 0 else None, bias.data_ptr(), st)
     if rc != 0:
         raise RuntimeError(f"gen_fill_kv(K) failed with hipError {rc}")
-    rc = lib.gen_fill_kv(V.data_ptr(), int(spec.kv_dtype == "bf16"), spec.B, spec.Hkv, case.Lcap, 0,
+    rc = lib.gen_fill_kv(V.data_ptr(), fmt, spec.B, spec.Hkv, case.Lcap, 0,
                          key_v.data_ptr(), row_end.data_ptr(), None, None, None, st)
     if rc != 0:
         raise RuntimeError(f"gen_fill_kv(V) failed with hipError {rc}")
@@ -93,20 +95,24 @@ def paginate(K, V, block_size: int, seed: int = 0, spare_blocks: int = 3, layout
     table[:, :nb] = perm.view(B, nb).to(torch.int32)
     pools = []
     for X in (K, V):
+        as_bytes = X.dtype == torch.float8_e4m3fn          # moved as bytes; filler = 448, the largest E4M3 value
+        fill = 0x7E if as_bytes else 1e4
+        if as_bytes:
+            X = X.view(torch.uint8)
         if layout == "block_head_row":
-            pool = torch.full((n_blocks, Hkv, block_size, D), 1e4, dtype=X.dtype, device=X.device)
+            pool = torch.full((n_blocks, Hkv, block_size, D), fill, dtype=X.dtype, device=X.device)
             view = pool
         elif layout == "block_row_head":
-            pool = torch.full((n_blocks, block_size, Hkv, D), 1e4, dtype=X.dtype, device=X.device)
+            pool = torch.full((n_blocks, block_size, Hkv, D), fill, dtype=X.dtype, device=X.device)
             view = pool.permute(0, 2, 1, 3)
         else:
             raise ValueError(layout)
         for b in range(B):
             xb = X[b]
             if nb * block_size != Lcap:
-                pad = torch.full((Hkv, nb * block_size - Lcap, D), 1e4, dtype=X.dtype, device=X.device)
+                pad = torch.full((Hkv, nb * block_size - Lcap, D), fill, dtype=X.dtype, device=X.device)
                 xb = torch.cat([xb, pad], dim=1)
             blocks = xb.view(Hkv, nb, block_size, D).permute(1, 0, 2, 3)     # [nb, Hkv, bs, D]
             view[perm[b * nb: (b + 1) * nb].to(X.device)] = blocks
-        pools.append(view)
+        pools.append(view.view(torch.float8_e4m3fn) if as_bytes else view)
     return pools[0], pools[1], table.to(K.device)

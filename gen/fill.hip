@@ -34,8 +34,25 @@ __device__ __forceinline__ uint16_t bf16_rne(float x) {
   return (uint16_t)(u >> 16);
 }
 
+// fp32 -> OCP FP8 E4M3, round to nearest even, saturating at 448: the recipe of f32_to_e4m3_bits in cases.py.
+__device__ __forceinline__ uint32_t e4m3_rne(float x) {
+  const uint32_t sign = (__float_as_uint(x) >> 24) & 0x80u;
+  const float a = fabsf(x);
+  uint32_t bits;
+  if (a < 0.015625f) {                                  // below 2^-6: a multiple of 2^-9
+    bits = (uint32_t)rintf(a * 512.0f);
+  } else {
+    uint32_t u = __float_as_uint(a);
+    u += 0x7FFFFu + ((u >> 20) & 1u);
+    const int e = (int)(u >> 23) - 127 + 7;
+    const uint32_t m = (u >> 20) & 7u;
+    bits = (e > 15 || (e == 15 && m == 7u)) ? 0x7Eu : (((uint32_t)e << 3) | m);
+  }
+  return bits | sign;
+}
+
 // One thread per 8 channels of one row.  grid.x covers rows*16, grid.y = B*Hkv.
-__global__ __launch_bounds__(256) void k_fill(void* __restrict__ out, int is_bf16, int Hkv, int Lcap, int n_hot,
+__global__ __launch_bounds__(256) void k_fill(void* __restrict__ out, int format, int Hkv, int Lcap, int n_hot,
                                               const uint64_t* __restrict__ keys, const int32_t* __restrict__ row_end,
                                               const int32_t* __restrict__ recent_start,
                                               const int32_t* __restrict__ hot_pos, const float* __restrict__ bias) {
@@ -62,7 +79,12 @@ __global__ __launch_bounds__(256) void k_fill(void* __restrict__ out, int is_bf1
     for (int c = 0; c < 8; ++c) x[c] = 0.f;
   }
   const int64_t o = ((int64_t)bg * Lcap + row) * 128 + c0;
-  if (is_bf16) {
+  if (format == 2) {
+    uint2 w;
+    w.x = e4m3_rne(x[0]) | (e4m3_rne(x[1]) << 8) | (e4m3_rne(x[2]) << 16) | (e4m3_rne(x[3]) << 24);
+    w.y = e4m3_rne(x[4]) | (e4m3_rne(x[5]) << 8) | (e4m3_rne(x[6]) << 16) | (e4m3_rne(x[7]) << 24);
+    *reinterpret_cast<uint2*>((uint8_t*)out + o) = w;
+  } else if (format == 1) {
     uint4 w;
     w.x = bf16_rne(x[0]) | ((uint32_t)bf16_rne(x[1]) << 16);
     w.y = bf16_rne(x[2]) | ((uint32_t)bf16_rne(x[3]) << 16);
@@ -78,15 +100,17 @@ __global__ __launch_bounds__(256) void k_fill(void* __restrict__ out, int is_bf1
 
 }  // namespace
 
-// All pointers are device pointers.  out is [B, Hkv, Lcap, 128] contiguous (bf16 or fp32).
+// All pointers are device pointers.  out is [B, Hkv, Lcap, 128] contiguous; format 0 = fp32, 1 = bf16,
+// 2 = OCP FP8 E4M3.
 // bias == NULL fills a value tensor (no structure).  Returns the hipError_t of the launch.
 extern "C" __attribute__((visibility("default"))) int gen_fill_kv(
-    void* out, int is_bf16, int B, int Hkv, int Lcap, int n_hot, const uint64_t* keys, const int32_t* row_end,
+    void* out, int format, int B, int Hkv, int Lcap, int n_hot, const uint64_t* keys, const int32_t* row_end,
     const int32_t* recent_start, const int32_t* hot_pos, const float* bias, void* stream) {
-  if (!out || !keys || !row_end || B < 1 || Hkv < 1 || Lcap < 1) return (int)hipErrorInvalidValue;
+  if (!out || !keys || !row_end || B < 1 || Hkv < 1 || Lcap < 1 || format < 0 || format > 2)
+    return (int)hipErrorInvalidValue;
   if (bias && (!recent_start || (n_hot > 0 && !hot_pos))) return (int)hipErrorInvalidValue;
   dim3 grid((unsigned)(((int64_t)Lcap * 16 + 255) / 256), (unsigned)(B * Hkv));
-  hipLaunchKernelGGL(k_fill, grid, dim3(256), 0, (hipStream_t)stream, out, is_bf16, Hkv, Lcap, n_hot, keys, row_end,
+  hipLaunchKernelGGL(k_fill, grid, dim3(256), 0, (hipStream_t)stream, out, format, Hkv, Lcap, n_hot, keys, row_end,
                      recent_start, hot_pos, bias);
   return (int)hipGetLastError();
 }

@@ -16,22 +16,6 @@ namespace lfps {
 
 constexpr int kAttnThreads = 256;       // full attention
 
-template <typename T>
-__device__ __forceinline__ void load8(const T* p, float x[8]) {
-  if constexpr (sizeof(T) == 2) {
-    u32x4 w = *reinterpret_cast<const u32x4*>(p);
-#pragma unroll
-    for (int c = 0; c < 4; ++c) {
-      x[2 * c] = bf16_lo(w[c]);
-      x[2 * c + 1] = bf16_hi(w[c]);
-    }
-  } else {
-    float4 a = reinterpret_cast<const float4*>(p)[0], b = reinterpret_cast<const float4*>(p)[1];
-    x[0] = a.x; x[1] = a.y; x[2] = a.z; x[3] = a.w;
-    x[4] = b.x; x[5] = b.y; x[6] = b.z; x[7] = b.w;
-  }
-}
-
 // grid B*Hq, kSparseWaves waves per workgroup
 template <typename T, int kSparseWaves, bool kPaged>
 __global__ __launch_bounds__(kSparseWaves * 64) void k_sparse_attn(Shape s, const T* __restrict__ V, int64_t stride_b,
@@ -192,9 +176,9 @@ int full_attn_splits(const Shape& s) {
 __device__ __forceinline__ int rows_per_split(int n, int n_split) { return (((n + n_split - 1) / n_split) + 15) & ~15; }
 
 // grid (n_split, B*Hkv); part [B*Hkv, n_split, G, D+2]: acc[D], m, l
-template <typename T, int G, bool kPaged>
+template <typename TK, typename T, int G, bool kPaged>
 __global__ __launch_bounds__(kAttnThreads) void k_full_attn(Shape s, const float* __restrict__ q,
-                                                            const T* __restrict__ K, const T* __restrict__ V,
+                                                            const TK* __restrict__ K, const T* __restrict__ V,
                                                             int64_t stride_b, int64_t stride_h, int64_t stride_n,
                                                             KvPage pg, const int32_t* __restrict__ seq_lens,
                                                             float* __restrict__ part, int n_split, float scale) {
@@ -218,7 +202,7 @@ __global__ __launch_bounds__(kAttnThreads) void k_full_attn(Shape s, const float
     for (int c = 0; c < 8; ++c) qr[h][c] = qh[c] * scale;
   }
   using Rows = RowMap<kPaged>;
-  const T* Kbg = K + Rows::base(b, g, stride_b, stride_h) + 8 * j;
+  const TK* Kbg = K + Rows::base(b, g, stride_b, stride_h) + 8 * j;
   const T* Vbg = V + Rows::base(b, g, stride_b, stride_h) + 8 * j;
 
   float m[G], l[G], acc[G][8];
@@ -361,15 +345,15 @@ __global__ __launch_bounds__(kD) void k_full_merge(Shape s, const int32_t* __res
   out[(int64_t)bh * kD + c] = a / l;
 }
 
-template <typename T>
+template <typename TK, typename T>
 static hipError_t launch_full_t(const Shape& s, const float* q, const KvView& kv, float* part, int n_split,
                                 hipStream_t st) {
   dim3 grid(n_split, s.B * s.Hkv), block(kAttnThreads);
   const float scale = 0.08838834764831845f;
-  const T* K = (const T*)kv.k;
+  const TK* K = (const TK*)kv.k;
   const T* V = (const T*)kv.v;
-#define LFPS_LAUNCH_FULL_P(GG, PAGED)                                                                        \
-  hipLaunchKernelGGL((k_full_attn<T, GG, PAGED>), grid, block, 0, st, s, q, K, V, kv.stride_b, kv.stride_h,  \
+#define LFPS_LAUNCH_FULL_P(GG, PAGED)                                                                           \
+  hipLaunchKernelGGL((k_full_attn<TK, T, GG, PAGED>), grid, block, 0, st, s, q, K, V, kv.stride_b, kv.stride_h, \
                      kv.stride_n, kv.page, kv.seq_lens, part, n_split, scale)
 #define LFPS_LAUNCH_FULL(GG)          \
   if (kv.page.table) {                \
@@ -390,8 +374,9 @@ static hipError_t launch_full_t(const Shape& s, const float* q, const KvView& kv
 
 hipError_t launch_full_attn(const Shape& s, int dtype, const float* q, const KvView& kv, float* part, int n_split,
                             hipStream_t st) {
-  return dtype == LFPS_BF16 ? launch_full_t<uint16_t>(s, q, kv, part, n_split, st)
-                            : launch_full_t<float>(s, q, kv, part, n_split, st);
+  if (dtype == LFPS_BF16 && kv.k_fp8) return launch_full_t<uint8_t, uint16_t>(s, q, kv, part, n_split, st);
+  return dtype == LFPS_BF16 ? launch_full_t<uint16_t, uint16_t>(s, q, kv, part, n_split, st)
+                            : launch_full_t<float, float>(s, q, kv, part, n_split, st);
 }
 
 hipError_t launch_full_merge(const Shape& s, const int32_t* seq_lens, const float* part, int n_split, float* out,

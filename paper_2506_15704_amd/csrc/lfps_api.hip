@@ -15,7 +15,7 @@ struct lfps_ctx {
   int n_split_full;
   int filter_on;       // filtered scoring inside lfps_step (bf16 caches)
   int nseg;            // survivor pieces per head (row length of seg_count)
-  int filter_blocks;   // launch size of the filtered scoring kernel: the workgroups the device holds at once
+  int filter_blocks[2];   // launch size of the filtered scoring kernel (contiguous, paged cache): the workgroups the device holds at once
   // workspace (device)
   float* score;        // [B, Hq, score_stride]
   int32_t* slot;       // [B, Hq, score_stride] candidate slots of the filtered survivors
@@ -94,6 +94,8 @@ int check_config(const lfps_config* c, Sizes* z, char* err, size_t errn) {
     if (!(c->table_a > 0.f)) BAD("table_a must be > 0 (got %g)", c->table_a);
     if (c->radius > 30) BAD("table mode supports radius <= 30 (got %d)", c->radius);
   }
+  if (c->k_fp8 != 0 && c->k_fp8 != 1) BAD("k_fp8 must be 0 or 1");
+  if (c->k_fp8 && c->kv_dtype != LFPS_BF16) BAD("k_fp8 needs kv_dtype = LFPS_BF16 (FP8 keys beside bf16 values)");
 #undef BAD
   // LDS of the candidate kernel: one bit per position beside 64 KB of staging, 160 KB per workgroup
   if (((int64_t)c->max_seq_len + 31) / 32 * 4 > 88 * 1024) {
@@ -148,7 +150,8 @@ int check_kv(lfps_ctx* ctx, const lfps_kv* kv, bool need_v, KvView* out) {
   if (!kv->k) return fail(ctx, LFPS_EINVAL, "kv->k is NULL");
   if (need_v && !kv->v) return fail(ctx, LFPS_EINVAL, "kv->v is NULL");
   if (!kv->seq_lens) return fail(ctx, LFPS_EINVAL, "kv->seq_lens is NULL");
-  const int esz = ctx->cfg.kv_dtype == LFPS_BF16 ? 2 : 4;
+  // the strides are shared by K and V: with one-byte K elements the K rows set the alignment
+  const int esz = ctx->cfg.k_fp8 ? 1 : (ctx->cfg.kv_dtype == LFPS_BF16 ? 2 : 4);
   if (kv->stride_n < kD || kv->stride_b < 0 || kv->stride_h < 0)
     return fail(ctx, LFPS_EINVAL, "kv strides: stride_n must be >= head_dim, stride_b/stride_h >= 0");
   if ((kv->stride_n * esz) % 16 || (kv->stride_b * esz) % 16 || (kv->stride_h * esz) % 16 ||
@@ -158,6 +161,7 @@ int check_kv(lfps_ctx* ctx, const lfps_kv* kv, bool need_v, KvView* out) {
   out->stride_b = kv->stride_b; out->stride_h = kv->stride_h; out->stride_n = kv->stride_n;
   out->seq_lens = kv->seq_lens;
   out->page = KvPage{nullptr, 0, 0, 0};
+  out->k_fp8 = ctx->cfg.k_fp8 != 0;
   if (kv->block_table) {
     const int64_t bs = kv->block_size;
     if (bs < 1 || bs > 65536 || (bs & (bs - 1)))
@@ -305,7 +309,7 @@ int lfps_create(const lfps_config* cfg, lfps_ctx** out) {
   if (e == hipSuccess) e = hipMemset(c->gate, 0, (size_t)z.thr_b);
   if (e == hipSuccess) e = configure_candidates(s);
   if (e == hipSuccess) e = configure_select(s);
-  if (e == hipSuccess && c->filter_on) e = filter_score_blocks(s, &c->filter_blocks);
+  if (e == hipSuccess && c->filter_on) e = filter_score_blocks(s, cfg->k_fp8 != 0, c->filter_blocks);
   if (e == hipSuccess) e = hipDeviceSynchronize();
   if (e != hipSuccess) {
     snprintf(g_create_err, sizeof g_create_err, "workspace setup: %s", hipGetErrorString(e));
@@ -401,7 +405,7 @@ static int score_and_select(lfps_ctx* ctx, const float* q, const KvView& v, cons
     LAUNCH(ctx, LFPS_KERNEL_FILTER_SCORE, st,
            launch_filter_score(s, q, v, ctx->cand, ctx->cand_count, ctx->group_start, line_total, ctx->thr_state,
                                kFilterMargin, ctx->score, ctx->slot, s.score_stride, ctx->seg_count, ctx->flags + 1,
-                               ctx->filter_blocks, st));
+                               ctx->filter_blocks[v.page.table ? 1 : 0], st));
     LAUNCH(ctx, LFPS_KERNEL_FILTER_SELECT, st,
            launch_filter_select(s, ctx->score, ctx->slot, s.score_stride, ctx->seg_count, ctx->flags + 1, ctx->nseg,
                                 ctx->cand_count, ctx->group_start, line_total, k, topk_idx, sel, ctx->thr_state,

@@ -28,6 +28,7 @@ struct KvView {
   int64_t stride_b, stride_h, stride_n;
   const int32_t* seq_lens;
   KvPage page;
+  bool k_fp8;   // K elements are one byte (OCP FP8 E4M3); V keeps the cache dtype
 };
 
 // Row addressing of the two cache layouts, chosen at compile time.  A logical row i of request b
@@ -90,7 +91,7 @@ hipError_t launch_group_score(const Shape& s, int dtype, const float* q, const K
 // equal parts, one per wave; the part size of a step is written to *seg_rows_out by the scoring
 // pass and read by the select, which also resets *line_total; see score.hip.
 int filter_nseg(const Shape& s);
-hipError_t filter_score_blocks(const Shape& s, int* out);
+hipError_t filter_score_blocks(const Shape& s, bool fp8, int out[2]);
 hipError_t launch_filter_score(const Shape& s, const float* q, const KvView& kv, const int32_t* cand,
                                const int32_t* cand_count, const int64_t* group_start, const int64_t* line_total,
                                const float* thr_state, float margin, float* score,
@@ -161,6 +162,55 @@ hipError_t launch_prior_variance(const Shape& s, const float* q, const int32_t* 
 // ---- small device helpers ------------------------------------------------------------
 __device__ __forceinline__ float bf16_lo(uint32_t w) { return __uint_as_float(w << 16); }
 __device__ __forceinline__ float bf16_hi(uint32_t w) { return __uint_as_float(w & 0xFFFF0000u); }
+
+// OCP FP8 E4M3 ("FN": no infinities, one NaN pattern per sign, largest value 448) to fp32: four values of
+// one dword, lowest byte first.  The hardware conversion is exact.
+__device__ __forceinline__ void fp8x4_to_f32(uint32_t w, float x[4]) {
+  const auto lo = __builtin_amdgcn_cvt_pk_f32_fp8((int)w, false);
+  const auto hi = __builtin_amdgcn_cvt_pk_f32_fp8((int)w, true);
+  x[0] = lo[0];
+  x[1] = lo[1];
+  x[2] = hi[0];
+  x[3] = hi[1];
+}
+// Eight E4M3 values as eight bf16 (exact: 3 mantissa bits fit bf16's 7, the exponent range is inside fp32's):
+// the upper halves of the fp32 conversions, packed two per dword.
+__device__ __forceinline__ bf16x8 fp8x8_to_bf16x8(uint32_t w0, uint32_t w1) {
+  float a[4], b[4];
+  fp8x4_to_f32(w0, a);
+  fp8x4_to_f32(w1, b);
+  auto pack = [](float lo, float hi) { return (__float_as_uint(hi) & 0xFFFF0000u) | (__float_as_uint(lo) >> 16); };
+  union {
+    u32x4 u;
+    bf16x8 v;
+  } r;
+  r.u[0] = pack(a[0], a[1]);
+  r.u[1] = pack(a[2], a[3]);
+  r.u[2] = pack(b[0], b[1]);
+  r.u[3] = pack(b[2], b[3]);
+  return r.v;
+}
+
+// Eight consecutive elements of a K or V row as fp32: T = float, uint16_t (bf16 bits) or uint8_t (E4M3).
+template <typename T>
+__device__ __forceinline__ void load8(const T* p, float x[8]) {
+  if constexpr (sizeof(T) == 1) {
+    const uint2 w = *reinterpret_cast<const uint2*>(p);
+    fp8x4_to_f32(w.x, x);
+    fp8x4_to_f32(w.y, x + 4);
+  } else if constexpr (sizeof(T) == 2) {
+    u32x4 w = *reinterpret_cast<const u32x4*>(p);
+#pragma unroll
+    for (int c = 0; c < 4; ++c) {
+      x[2 * c] = bf16_lo(w[c]);
+      x[2 * c + 1] = bf16_hi(w[c]);
+    }
+  } else {
+    float4 a = reinterpret_cast<const float4*>(p)[0], b = reinterpret_cast<const float4*>(p)[1];
+    x[0] = a.x; x[1] = a.y; x[2] = a.z; x[3] = a.w;
+    x[4] = b.x; x[5] = b.y; x[6] = b.z; x[7] = b.w;
+  }
+}
 
 // Order-preserving map fp32 -> uint32 (larger float <=> larger key).
 __device__ __forceinline__ uint32_t f2key(float f) {

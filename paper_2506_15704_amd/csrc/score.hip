@@ -66,7 +66,40 @@ __device__ __forceinline__ void load_query_operand(bf16x8 (&A)[4], const float* 
   }
 }
 
-// ----------------------------------------------------------------------------- bf16, MFMA
+// The registers a lane (j, kb) holds of one 64-row K tile: its 32 channels [32 kb, 32 kb + 32) of the
+// four rows 16 t + j, in the storage format of K.  operand(t, kk) is the MFMA B operand of step kk, the
+// channels 32 kb + 8 kk .. + 7 as bf16: the value as stored for a bf16 cache, converted (exactly: every
+// E4M3 value is a bf16 value) when it is multiplied for an FP8 cache, so that a tile in flight costs half
+// the registers and half the loads.
+template <bool kFp8>
+struct KTile;
+template <>
+struct KTile<false> {
+  static constexpr int kElemBytes = 2;
+  bf16x8 v[4][4];
+  __device__ __forceinline__ void load_row(int t, const char* row, int kb) {
+    const bf16x8* p = reinterpret_cast<const bf16x8*>(row) + 4 * kb;
+#pragma unroll
+    for (int kk = 0; kk < 4; ++kk) v[t][kk] = p[kk];
+  }
+  __device__ __forceinline__ bf16x8 operand(int t, int kk) const { return v[t][kk]; }
+};
+template <>
+struct KTile<true> {
+  static constexpr int kElemBytes = 1;
+  u32x4 v[4][2];
+  __device__ __forceinline__ void load_row(int t, const char* row, int kb) {
+    const u32x4* p = reinterpret_cast<const u32x4*>(row) + 2 * kb;
+    v[t][0] = p[0];
+    v[t][1] = p[1];
+  }
+  __device__ __forceinline__ bf16x8 operand(int t, int kk) const {
+    const u32x4 w = v[t][kk >> 1];
+    return (kk & 1) ? fp8x8_to_bf16x8(w[2], w[3]) : fp8x8_to_bf16x8(w[0], w[1]);
+  }
+};
+
+// ----------------------------------------------------------------------------- bf16 / fp8, MFMA
 // grid: (tiles_x, B*Hkv).  GATHER: rows come from cand[bg, 0:count]; else rows are 0..n_b-1.
 //
 // Lane (j, kb) = (lane & 15, lane >> 4) supplies column j of the B operand: for MFMA step kk it
@@ -76,9 +109,9 @@ __device__ __forceinline__ void load_query_operand(bf16x8 (&A)[4], const float* 
 // channels to (kk, kb) is valid as long as the A operand uses the same one.
 // The row ids of the next iteration are fetched, and the scores of the previous iteration stored,
 // right after this iteration's loads are issued.
-template <int G, bool GATHER, bool kPaged>
+template <int G, bool GATHER, bool kPaged, bool kFp8>
 __global__ __launch_bounds__(kScoreThreads) void k_group_score_bf16(Shape s, const float* __restrict__ q,
-                                                                    const __bf16* __restrict__ K, int64_t stride_b,
+                                                                    const void* __restrict__ K, int64_t stride_b,
                                                                     int64_t stride_h, int64_t stride_n, KvPage pg,
                                                                     const int32_t* __restrict__ seq_lens,
                                                                     const int32_t* __restrict__ cand,
@@ -100,7 +133,8 @@ __global__ __launch_bounds__(kScoreThreads) void k_group_score_bf16(Shape s, con
   load_query_operand<G>(A, q, (int64_t)b * s.Hq + (int64_t)g * G, j, kb);
 
   using Rows = RowMap<kPaged>;
-  const __bf16* Kbg = K + Rows::base(b, g, stride_b, stride_h);
+  constexpr int ES = KTile<kFp8>::kElemBytes;
+  const char* Kbg = static_cast<const char*>(K) + Rows::base(b, g, stride_b, stride_h) * ES;
   const int32_t* cbg = GATHER ? cand + (int64_t)bg * s.cand_cap : nullptr;
   float* sc = score + ((int64_t)b * s.Hq + (int64_t)g * G + kb) * score_stride;   // lane group kb -> head kb
   const int step = gridDim.x * 4 * kRowsPerWaveIter;
@@ -113,13 +147,11 @@ __global__ __launch_bounds__(kScoreThreads) void k_group_score_bf16(Shape s, con
   if (first + lane < count) my_row = GATHER ? cbg[first + lane] : first + lane;
   my_row = physical(my_row);
   for (int base = first; base < count; base += step) {
-    bf16x8 Bt[4][4];
+    KTile<kFp8> Bt;
 #pragma unroll
     for (int t = 0; t < 4; ++t) {
       const int row = __shfl(my_row, 16 * t + j);
-      const bf16x8* p = reinterpret_cast<const bf16x8*>(Kbg + Rows::offset(pg, row, stride_b, stride_n)) + 4 * kb;
-#pragma unroll
-      for (int kk = 0; kk < 4; ++kk) Bt[t][kk] = p[kk];
+      Bt.load_row(t, Kbg + Rows::offset(pg, row, stride_b, stride_n) * ES, kb);
     }
     const int nb = base + step;
     int next_row = -1;
@@ -136,7 +168,8 @@ __global__ __launch_bounds__(kScoreThreads) void k_group_score_bf16(Shape s, con
     for (int t = 0; t < 4; ++t) {
       f32x4 acc = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-      for (int kk = 0; kk < 4; ++kk) acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(A[kk], Bt[t][kk], acc, 0, 0, 0);
+      for (int kk = 0; kk < 4; ++kk)
+        acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(A[kk], Bt.operand(t, kk), acc, 0, 0, 0);
       // lane (j, kb): D rows 4*kb .. 4*kb+3 = the three terms (and a zero row) of head kb, column j
       pv[t] = ((acc[0] + acc[1]) + acc[2]) * scale;
     }
@@ -172,9 +205,9 @@ __global__ __launch_bounds__(kScoreThreads) void k_group_score_bf16(Shape s, con
 // A threshold of -inf keeps every row; NaN means there is no previous step.
 constexpr int kFilterStage = 256;   // survivors one wave can hold per head before it must write them out
 
-template <int G, bool kPaged>
+template <int G, bool kPaged, bool kFp8>
 __global__ __launch_bounds__(kScoreThreads, 2) void k_filter_score_bf16(
-    Shape s, const float* __restrict__ q, const __bf16* __restrict__ K, int64_t stride_b, int64_t stride_h,
+    Shape s, const float* __restrict__ q, const void* __restrict__ K, int64_t stride_b, int64_t stride_h,
     int64_t stride_n, KvPage page, const int32_t* __restrict__ seq_lens, const int32_t* __restrict__ cand,
     const int32_t* __restrict__ cand_count, const int64_t* __restrict__ group_start,
     const int64_t* __restrict__ line_total, const float* __restrict__ thr_state, float margin,
@@ -240,7 +273,9 @@ __global__ __launch_bounds__(kScoreThreads, 2) void k_filter_score_bf16(
 
     bf16x8 A[4];                                        // filled after the first tile's loads are on their way
     using Rows = RowMap<kPaged>;
-    const __bf16* Kbg = K + Rows::base(b, g, stride_b, stride_h);
+    using Tile = KTile<kFp8>;
+    constexpr int ES = Tile::kElemBytes;
+    const char* Kbg = static_cast<const char*>(K) + Rows::base(b, g, stride_b, stride_h) * ES;
     const int32_t* cbg = cand + (int64_t)bg * s.cand_cap;
     int run = 0;                                        // survivors of my head already in global memory
     int staged = 0;                                     // survivors of my head waiting in LDS
@@ -268,25 +303,24 @@ __global__ __launch_bounds__(kScoreThreads, 2) void k_filter_score_bf16(
     // i+1 (issued before) are still arriving.
     // ids: the row positions of the tile's 64 slots, one per lane; phys: the same rows as physical
     // rows (paged cache only; ignored otherwise)
-    auto issue = [&](bf16x8 (&Bt)[4][4], int (&rows)[4], int ids, int phys) {
+    auto issue = [&](Tile& Bt, int (&rows)[4], int ids, int phys) {
 #pragma unroll
       for (int t = 0; t < 4; ++t) {
         int row = __shfl(ids, 16 * t + j);
         row = (row < 0 || row >= n) ? 0 : row;          // padding slots read row 0 and are never kept
         rows[t] = row;
         const int prow = kPaged ? __shfl(phys, 16 * t + j) : row;
-        const bf16x8* p = reinterpret_cast<const bf16x8*>(Kbg + Rows::offset(page, prow, stride_b, stride_n)) + 4 * kb;
-#pragma unroll
-        for (int kk = 0; kk < 4; ++kk) Bt[t][kk] = p[kk];
+        Bt.load_row(t, Kbg + Rows::offset(page, prow, stride_b, stride_n) * ES, kb);
       }
     };
     auto lookup = [&](int ids) { return Rows::phys(page, b, (ids < 0 || ids >= n) ? 0 : ids); };
-    auto consume = [&](bf16x8 (&Bt)[4][4], int (&rows)[4], int base_slot) {
+    auto consume = [&](Tile& Bt, int (&rows)[4], int base_slot) {
 #pragma unroll
       for (int t = 0; t < 4; ++t) {
         f32x4 acc = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-        for (int kk = 0; kk < 4; ++kk) acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(A[kk], Bt[t][kk], acc, 0, 0, 0);
+        for (int kk = 0; kk < 4; ++kk)
+          acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(A[kk], Bt.operand(t, kk), acc, 0, 0, 0);
         const float v = ((acc[0] + acc[1]) + acc[2]) * scale;
         const int slot = base_slot + 16 * t + j;
         const bool pass = kb < G && slot < seg_hi && v >= tau;
@@ -312,7 +346,7 @@ __global__ __launch_bounds__(kScoreThreads, 2) void k_filter_score_bf16(
     // Row ids are fetched three tiles ahead, always BEFORE the loads of the tile that precedes
     // their use are issued: a wait for ids then never has to wait for a tile still in flight
     // (the vector-memory counter completes in issue order).
-    bf16x8 Bt0[4][4], Bt1[4][4];
+    Tile Bt0, Bt1;
     int rows0[4], rows1[4];
     int base_slot = seg_lo;
     if constexpr (!kPaged) {
@@ -351,14 +385,9 @@ __global__ __launch_bounds__(kScoreThreads, 2) void k_filter_score_bf16(
           prow[t] = __shfl(phys, 16 * t + j);
         }
       };
-      auto fire = [&](bf16x8 (&Bt)[4][4]) {
+      auto fire = [&](Tile& Bt) {
 #pragma unroll
-        for (int t = 0; t < 4; ++t) {
-          const bf16x8* p =
-              reinterpret_cast<const bf16x8*>(Kbg + Rows::offset(page, prow[t], stride_b, stride_n)) + 4 * kb;
-#pragma unroll
-          for (int kk = 0; kk < 4; ++kk) Bt[t][kk] = p[kk];
-        }
+        for (int t = 0; t < 4; ++t) Bt.load_row(t, Kbg + Rows::offset(page, prow[t], stride_b, stride_n) * ES, kb);
       };
       int ids_0 = fetch_ids(seg_lo), ids_1 = fetch_ids(seg_lo + T);
       int phys_0 = lookup(ids_0), phys_1 = lookup(ids_1);
@@ -507,18 +536,7 @@ __global__ __launch_bounds__(256) void k_head_score(Shape s, const float* __rest
     const int prow = __shfl(my_phys, 4 * t + rs);
     const T* p = Kbg + Rows::offset(pg, prow, stride_b, stride_n) + 8 * j;
     float x[8];
-    if constexpr (sizeof(T) == 2) {
-      u32x4 w = *reinterpret_cast<const u32x4*>(p);
-#pragma unroll
-      for (int c = 0; c < 4; ++c) {
-        x[2 * c] = bf16_lo(w[c]);
-        x[2 * c + 1] = bf16_hi(w[c]);
-      }
-    } else {
-      float4 x0 = reinterpret_cast<const float4*>(p)[0], x1 = reinterpret_cast<const float4*>(p)[1];
-      x[0] = x0.x; x[1] = x0.y; x[2] = x0.z; x[3] = x0.w;
-      x[4] = x1.x; x[5] = x1.y; x[6] = x1.z; x[7] = x1.w;
-    }
+    load8(p, x);
     float a = qr[0] * x[0];
 #pragma unroll
     for (int c = 1; c < 8; ++c) a = fmaf(qr[c], x[c], a);
@@ -543,14 +561,17 @@ static hipError_t launch_gs(const Shape& s, int dtype, const float* q, const KvV
   if (gx < 1) gx = 1;
   dim3 grid(gx, s.B * s.Hkv), block(kScoreThreads);
   const float scale = 0.08838834764831845f;   // 1/sqrt(128)
-#define LFPS_LAUNCH_GS(KERNEL, TYPE, PAGED)                                                                       \
-  hipLaunchKernelGGL((KERNEL<G, GATHER, PAGED>), grid, block, 0, st, s, q, (const TYPE*)kv.k, kv.stride_b,         \
+#define LFPS_LAUNCH_GS(KERNEL, TYPE, ...)                                                                          \
+  hipLaunchKernelGGL((KERNEL<G, GATHER, __VA_ARGS__>), grid, block, 0, st, s, q, (const TYPE*)kv.k, kv.stride_b,   \
                      kv.stride_h, kv.stride_n, kv.page, kv.seq_lens, cand, cand_count, score, score_stride, scale, \
                      only_if)
   const bool paged = kv.page.table != nullptr;
-  if (dtype == LFPS_BF16) {
-    if (paged) LFPS_LAUNCH_GS(k_group_score_bf16, __bf16, true);
-    else LFPS_LAUNCH_GS(k_group_score_bf16, __bf16, false);
+  if (dtype == LFPS_BF16 && kv.k_fp8) {
+    if (paged) LFPS_LAUNCH_GS(k_group_score_bf16, void, true, true);
+    else LFPS_LAUNCH_GS(k_group_score_bf16, void, false, true);
+  } else if (dtype == LFPS_BF16) {
+    if (paged) LFPS_LAUNCH_GS(k_group_score_bf16, void, true, false);
+    else LFPS_LAUNCH_GS(k_group_score_bf16, void, false, false);
   } else {
     if (paged) LFPS_LAUNCH_GS(k_group_score_f32, float, true);
     else LFPS_LAUNCH_GS(k_group_score_f32, float, false);
@@ -579,28 +600,36 @@ int filter_min_seg_rows(const Shape& s) { return (((s.cand_cap + 999) / 1000) + 
 int filter_nseg(const Shape& s) { return s.cand_cap / filter_min_seg_rows(s) + 2; }
 
 template <int G>
-static hipError_t filter_resident_blocks(int* out) {
-  int per_cu = 0, dev = 0;
+static hipError_t filter_resident_blocks(bool fp8, int out[2]) {
+  int dev = 0;
   hipDeviceProp_t prop;
-  // the paged variant keeps a few more registers live; both must fit the same launch size
-  hipError_t e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, k_filter_score_bf16<G, false>, kScoreThreads, 0);
-  int per_cu_paged = 0;
-  if (e == hipSuccess)
-    e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu_paged, k_filter_score_bf16<G, true>, kScoreThreads, 0);
-  if (per_cu_paged < per_cu) per_cu = per_cu_paged;
-  if (e == hipSuccess) e = hipGetDevice(&dev);
+  hipError_t e = hipGetDevice(&dev);
   if (e == hipSuccess) e = hipGetDeviceProperties(&prop, dev);
-  if (e != hipSuccess) return e;
-  *out = per_cu * prop.multiProcessorCount;
-  return hipSuccess;
+  auto resident = [&](const void* kernel, int* n) {
+    int per_cu = 0;
+    if (e == hipSuccess) e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, kernel, kScoreThreads, 0);
+    // two per CU is what the kernels are built for (__launch_bounds__); the FP8 variants would fit three,
+    // measured slightly slower (smaller parts, no more bandwidth)
+    if (per_cu > 2) per_cu = 2;
+    *n = per_cu * prop.multiProcessorCount;
+  };
+  if (fp8) {
+    resident((const void*)k_filter_score_bf16<G, false, true>, &out[0]);
+    resident((const void*)k_filter_score_bf16<G, true, true>, &out[1]);
+  } else {
+    resident((const void*)k_filter_score_bf16<G, false, false>, &out[0]);
+    resident((const void*)k_filter_score_bf16<G, true, false>, &out[1]);
+  }
+  return e;
 }
 
-// Workgroups of the filtered scoring kernel that the current device holds at once (its launch size).
-hipError_t filter_score_blocks(const Shape& s, int* out) {
+// Workgroups of the filtered scoring kernel that the current device holds at once (its launch size), for
+// a contiguous cache (out[0]) and a paged one (out[1]); the variants differ in registers, hence in occupancy.
+hipError_t filter_score_blocks(const Shape& s, bool fp8, int out[2]) {
   switch (s.G) {
-    case 1: return filter_resident_blocks<1>(out);
-    case 2: return filter_resident_blocks<2>(out);
-    case 4: return filter_resident_blocks<4>(out);
+    case 1: return filter_resident_blocks<1>(fp8, out);
+    case 2: return filter_resident_blocks<2>(fp8, out);
+    case 4: return filter_resident_blocks<4>(fp8, out);
     default: return hipErrorInvalidValue;
   }
 }
@@ -614,16 +643,20 @@ hipError_t launch_filter_score(const Shape& s, const float* q, const KvView& kv,
   if (n_blocks < 1) return hipErrorInvalidValue;
   dim3 grid((unsigned)n_blocks), block(kScoreThreads);
   const float scale = 0.08838834764831845f;
-#define LFPS_LAUNCH_FILTER_P(GG, PAGED)                                                                            \
-  hipLaunchKernelGGL((k_filter_score_bf16<GG, PAGED>), grid, block, 0, st, s, q, (const __bf16*)kv.k, kv.stride_b, \
+#define LFPS_LAUNCH_FILTER_P(GG, PAGED, FP8)                                                                       \
+  hipLaunchKernelGGL((k_filter_score_bf16<GG, PAGED, FP8>), grid, block, 0, st, s, q, kv.k, kv.stride_b,           \
                      kv.stride_h, kv.stride_n, kv.page, kv.seq_lens, cand, cand_count, group_start, line_total,    \
                      thr_state, margin, score, slot_out, score_stride, seg_count, seg_rows_out,                    \
                      filter_min_seg_rows(s), nseg, scale)
-#define LFPS_LAUNCH_FILTER(GG)                 \
-  if (kv.page.table) {                         \
-    LFPS_LAUNCH_FILTER_P(GG, true);            \
-  } else {                                     \
-    LFPS_LAUNCH_FILTER_P(GG, false);           \
+#define LFPS_LAUNCH_FILTER(GG)                        \
+  if (kv.page.table && kv.k_fp8) {                    \
+    LFPS_LAUNCH_FILTER_P(GG, true, true);             \
+  } else if (kv.page.table) {                         \
+    LFPS_LAUNCH_FILTER_P(GG, true, false);            \
+  } else if (kv.k_fp8) {                              \
+    LFPS_LAUNCH_FILTER_P(GG, false, true);            \
+  } else {                                            \
+    LFPS_LAUNCH_FILTER_P(GG, false, false);           \
   }
   switch (s.G) {
     case 1: LFPS_LAUNCH_FILTER(1); break;
@@ -644,7 +677,10 @@ hipError_t launch_head_score(const Shape& s, int dtype, const float* q, const Kv
   hipLaunchKernelGGL((k_head_score<TYPE, PAGED>), grid, block, 0, st, s, q, (const TYPE*)kv.k, kv.stride_b,     \
                      kv.stride_h, kv.stride_n, kv.page, kv.seq_lens, idx, k, idx_score, scale)
   const bool paged = kv.page.table != nullptr;
-  if (dtype == LFPS_BF16) {
+  if (dtype == LFPS_BF16 && kv.k_fp8) {
+    if (paged) LFPS_LAUNCH_HS(uint8_t, true);
+    else LFPS_LAUNCH_HS(uint8_t, false);
+  } else if (dtype == LFPS_BF16) {
     if (paged) LFPS_LAUNCH_HS(uint16_t, true);
     else LFPS_LAUNCH_HS(uint16_t, false);
   } else {

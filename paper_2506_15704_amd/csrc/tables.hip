@@ -505,7 +505,13 @@ __global__ __launch_bounds__(64) void k_head_sparsity(Shape s, const float* __re
   auto logit_of_row = [&](int row) {
     float k0, k1;
     const T* kr = Kbg + Rows::offset(pg, Rows::phys(pg, b, row), stride_b, stride_n) + 2 * lane;
-    if constexpr (sizeof(T) == 2) {
+    if constexpr (sizeof(T) == 1) {                 // two E4M3 bytes
+      const uint32_t w = *reinterpret_cast<const uint16_t*>(kr);
+      float x[4];
+      fp8x4_to_f32(w, x);
+      k0 = x[0];
+      k1 = x[1];
+    } else if constexpr (sizeof(T) == 2) {
       const uint32_t w = *reinterpret_cast<const uint32_t*>(kr);
       k0 = bf16_lo(w);
       k1 = bf16_hi(w);
@@ -563,8 +569,8 @@ __global__ __launch_bounds__(64) void k_head_sparsity(Shape s, const float* __re
 // ----------------------------------------------------------------------------- prefill priors (Sec. 4.2 "Prefilling")
 // Mean K row and mean V row over rows [n_sink, n_b) of one (b, g).  1024 threads: 64 row slots x 16 lanes
 // of 8 channels; fp32 partial sums per thread, fp64 across the row slots.
-template <typename T, bool kPaged>
-__global__ __launch_bounds__(1024) void k_prior_means(Shape s, const T* __restrict__ K, const T* __restrict__ V,
+template <typename TK, typename T, bool kPaged>
+__global__ __launch_bounds__(1024) void k_prior_means(Shape s, const TK* __restrict__ K, const T* __restrict__ V,
                                                       int64_t stride_b, int64_t stride_h, int64_t stride_n, KvPage pg,
                                                       const int32_t* __restrict__ seq_lens, float* __restrict__ kbar,
                                                       float* __restrict__ vbar) {
@@ -576,24 +582,14 @@ __global__ __launch_bounds__(1024) void k_prior_means(Shape s, const T* __restri
   using Rows = RowMap<kPaged>;
   const int64_t base = Rows::base(b, g, stride_b, stride_h) + 8 * j;
   for (int which = 0; which < 2; ++which) {
-    const T* X0 = (which == 0 ? K : V) + base;
     float acc[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
     for (int r = s.n_sink + slot; r < n; r += 64) {
       float x[8];
-      const T* X = X0 + Rows::offset(pg, Rows::phys(pg, b, r), stride_b, stride_n);
-      if constexpr (sizeof(T) == 2) {
-        const u32x4 w = *reinterpret_cast<const u32x4*>(X);
-#pragma unroll
-        for (int c = 0; c < 4; ++c) {
-          x[2 * c] = bf16_lo(w[c]);
-          x[2 * c + 1] = bf16_hi(w[c]);
-        }
-      } else {
-        const float4 a0 = reinterpret_cast<const float4*>(X)[0];
-        const float4 a1 = reinterpret_cast<const float4*>(X)[1];
-        x[0] = a0.x; x[1] = a0.y; x[2] = a0.z; x[3] = a0.w;
-        x[4] = a1.x; x[5] = a1.y; x[6] = a1.z; x[7] = a1.w;
-      }
+      const int64_t off = base + Rows::offset(pg, Rows::phys(pg, b, r), stride_b, stride_n);
+      if (which == 0)
+        load8(K + off, x);
+      else
+        load8(V + off, x);
 #pragma unroll
       for (int c = 0; c < 8; ++c) acc[c] += x[c];
     }
@@ -707,7 +703,10 @@ hipError_t launch_head_sparsity(const Shape& s, int dtype, const float* q, const
                      kv.stride_b, kv.stride_h, kv.stride_n, kv.page, kv.seq_lens, kbar, sigma2_hat, n_local, eps, rho, \
                      gate, vbar, topk_idx, topk_score, out)
   const bool paged = kv.page.table != nullptr;
-  if (dtype == LFPS_BF16) {
+  if (dtype == LFPS_BF16 && kv.k_fp8) {
+    if (paged) LFPS_LAUNCH_HSP(uint8_t, true);
+    else LFPS_LAUNCH_HSP(uint8_t, false);
+  } else if (dtype == LFPS_BF16) {
     if (paged) LFPS_LAUNCH_HSP(uint16_t, true);
     else LFPS_LAUNCH_HSP(uint16_t, false);
   } else {
@@ -719,16 +718,20 @@ hipError_t launch_head_sparsity(const Shape& s, int dtype, const float* q, const
 }
 
 hipError_t launch_prior_means(const Shape& s, int dtype, const KvView& kv, float* kbar, float* vbar, hipStream_t st) {
-#define LFPS_LAUNCH_PM(TYPE, PAGED)                                                                              \
-  hipLaunchKernelGGL((k_prior_means<TYPE, PAGED>), dim3(s.B * s.Hkv), dim3(1024), 0, st, s, (const TYPE*)kv.k,       \
-                     (const TYPE*)kv.v, kv.stride_b, kv.stride_h, kv.stride_n, kv.page, kv.seq_lens, kbar, vbar)
+#define LFPS_LAUNCH_PM(KTYPE, TYPE, PAGED)                                                                        \
+  hipLaunchKernelGGL((k_prior_means<KTYPE, TYPE, PAGED>), dim3(s.B * s.Hkv), dim3(1024), 0, st, s,                  \
+                     (const KTYPE*)kv.k, (const TYPE*)kv.v, kv.stride_b, kv.stride_h, kv.stride_n, kv.page,         \
+                     kv.seq_lens, kbar, vbar)
   const bool paged = kv.page.table != nullptr;
-  if (dtype == LFPS_BF16) {
-    if (paged) LFPS_LAUNCH_PM(uint16_t, true);
-    else LFPS_LAUNCH_PM(uint16_t, false);
+  if (dtype == LFPS_BF16 && kv.k_fp8) {
+    if (paged) LFPS_LAUNCH_PM(uint8_t, uint16_t, true);
+    else LFPS_LAUNCH_PM(uint8_t, uint16_t, false);
+  } else if (dtype == LFPS_BF16) {
+    if (paged) LFPS_LAUNCH_PM(uint16_t, uint16_t, true);
+    else LFPS_LAUNCH_PM(uint16_t, uint16_t, false);
   } else {
-    if (paged) LFPS_LAUNCH_PM(float, true);
-    else LFPS_LAUNCH_PM(float, false);
+    if (paged) LFPS_LAUNCH_PM(float, float, true);
+    else LFPS_LAUNCH_PM(float, float, false);
   }
 #undef LFPS_LAUNCH_PM
   return hipGetLastError();

@@ -28,6 +28,14 @@ def dev(a, dtype=None):
     return t.to(DEV)
 
 
+def stored_values(T):
+    """A cache tensor as float32 (FP8 keys are decoded through the generator's table of the 256 E4M3 values)."""
+    if T.dtype == torch.float8_e4m3fn:
+        lut = torch.from_numpy(gen.cases.E4M3_VALUES).to(T.device)
+        return lut[T.view(torch.uint8).long()]
+    return T.float()
+
+
 class DeviceCase:
     """A generated case with its KV cache resident on the GPU."""
 
@@ -54,7 +62,8 @@ class DeviceCase:
         from paper_2506_15704_amd.binding import Lfps
         s = self.spec
         args = dict(batch=s.B, n_q_heads=s.Hq, n_kv_heads=s.Hkv, head_dim=s.D, kv_dtype=s.kv_dtype,
-                    max_seq_len=self.case.Lcap, max_k=self.case.kmax, radius=s.r, n_recent=1, n_sink=0)
+                    max_seq_len=self.case.Lcap, max_k=self.case.kmax, radius=s.r, n_recent=1, n_sink=0,
+                    k_fp8=s.k_dtype == "fp8")
         args.update(kw)
         return Lfps(**args)
 

@@ -72,3 +72,39 @@ def test_named_workloads_shapes():
     q = c3.q.astype(np.float64)
     step_cos = [np.dot(q[t, 0, 0], q[t - 1, 0, 0]) / 128 for t in range(1, 33)]
     assert step_cos[15] < 0.93 and step_cos[31] < 0.93 and min(step_cos[:15]) > 0.98   # drift spikes at t = 16, 32
+
+
+def test_e4m3_rounding_matches_an_independent_implementation():
+    """The generator's fp32 -> FP8 E4M3 rounding against torch's own conversion (in range; beyond +-464 the
+    generator saturates at 448 where torch returns NaN), and the decode table against torch's decode."""
+    import torch
+    from gen.cases import E4M3_VALUES, e4m3_bits_to_f32, f32_to_e4m3_bits
+    rng = np.random.default_rng(3)
+    x = np.concatenate([rng.normal(size=50000).astype(np.float32) * s for s in (1e-3, 0.02, 1.0, 30.0, 300.0)] +
+                       [np.array([0, -0.0, 448, 449, 463.9, 464, 480, 1e5, -1e5, 2 ** -6, 2 ** -7, 2 ** -9, 2 ** -10,
+                                  1.5 * 2 ** -9, 2.5 * 2 ** -9, 0.5 * 2 ** -9, 0.0625, 0.0615], dtype=np.float32)])
+    mine = f32_to_e4m3_bits(x)
+    ref = torch.from_numpy(x).to(torch.float8_e4m3fn).view(torch.uint8).numpy()
+    inside = np.abs(x) < 464
+    np.testing.assert_array_equal(mine[inside], ref[inside])
+    np.testing.assert_array_equal(e4m3_bits_to_f32(mine[~inside]), np.sign(x[~inside]) * 448)
+    every = torch.arange(256, dtype=torch.uint8).view(torch.float8_e4m3fn).float().numpy()
+    np.testing.assert_array_equal(E4M3_VALUES, every)          # NaN patterns compare equal here
+    # every stored value survives the trip through bf16 (what the scoring kernel relies on)
+    finite = np.isfinite(E4M3_VALUES)
+    v = E4M3_VALUES[finite]
+    np.testing.assert_array_equal(gen.bf16_bits_to_f32(gen.f32_to_bf16_bits(v)), v)
+
+
+def test_fp8_key_rows_are_e4m3_values_of_the_bf16_recipe():
+    spec = gen.tiny_spec("fp8_rows", k_dtype="fp8")
+    case = gen.make_case(spec)
+    rows = np.array([0, 3, 5, 100, 700])
+    vals, bits = case.kv_rows("k", 1, 2, rows)
+    assert bits.dtype == np.uint8 and vals.dtype == np.float32
+    np.testing.assert_array_equal(vals, gen.e4m3_bits_to_f32(bits))
+    v_vals, v_bits = case.kv_rows("v", 1, 2, rows)
+    assert v_bits.dtype == np.uint16                       # values stay bf16
+    plain = gen.make_case(gen.tiny_spec("fp8_rows"))       # same seed, bf16 keys: same draws before rounding
+    ref, _ = plain.kv_rows("k", 1, 2, rows)
+    assert np.abs(vals - ref).max() <= 2.0 ** -4 * np.abs(ref).max()   # half an ulp of 3 mantissa bits

@@ -6,7 +6,7 @@ import torch
 
 import gen
 from oracle import lfps_oracle as orc
-from tests.harness import (DEV, DeviceCase, assert_out_close, assert_scores_close,
+from tests.harness import (DEV, DeviceCase, assert_out_close, assert_scores_close, stored_values,
                            assert_topk_equal_mod_ties, dev, valid_row)
 
 pytestmark = pytest.mark.gpu
@@ -18,23 +18,28 @@ def small_bf16():
 
 
 @pytest.fixture(scope="module")
+def small_fp8():
+    return DeviceCase(gen.tiny_spec("small_fp8", B=2, L=2100, k=80, r=2, T=4, k_dtype="fp8"))
+
+
+@pytest.fixture(scope="module")
 def small_f32():
     return DeviceCase(gen.tiny_spec("small_f32", B=2, L=1111, k=64, r=3, T=3, kv_dtype="f32"))
 
 
 # ------------------------------------------------------------------------ generator
-@pytest.mark.parametrize("fx", ["small_bf16", "small_f32"])
+@pytest.mark.parametrize("fx", ["small_bf16", "small_f32", "small_fp8"])
 def test_device_fill_matches_cpu_generator(fx, request):
     dc = request.getfixturevalue(fx)
     rows = np.array([0, 3, 4, 5, 100, dc.case.seq_lens0[1] - 17, dc.case.seq_lens0[1] - 16, dc.case.seq_lens0[1] + 2,
                      dc.case.Lcap - 1] + dc.case.hot_pos[1, 5].tolist())
     for which, T in (("k", dc.K), ("v", dc.V)):
         want, _ = dc.case.kv_rows(which, 1, 5, rows)
-        got = T[1, 5, torch.from_numpy(rows).to(DEV)].float().cpu().numpy()
+        got = stored_values(T[1, 5])[torch.from_numpy(rows).to(DEV)].cpu().numpy()
         np.testing.assert_array_equal(got, want)
     Kfull, Vfull = dc.group(0, 2)
-    np.testing.assert_array_equal(dc.K[0, 2, : len(Kfull)].float().cpu().numpy(), Kfull)
-    np.testing.assert_array_equal(dc.V[0, 2, : len(Vfull)].float().cpu().numpy(), Vfull)
+    np.testing.assert_array_equal(stored_values(dc.K[0, 2, : len(Kfull)]).cpu().numpy(), Kfull)
+    np.testing.assert_array_equal(stored_values(dc.V[0, 2, : len(Vfull)]).cpu().numpy(), Vfull)
 
 
 # ------------------------------------------------------------------------ S1 candidates
@@ -105,7 +110,7 @@ def _teacher_inputs(dc, t, rng=None):
     return prev
 
 
-@pytest.mark.parametrize("fx", ["small_bf16", "small_f32"])
+@pytest.mark.parametrize("fx", ["small_bf16", "small_f32", "small_fp8"])
 def test_score_topk_teacher_forced(fx, request):
     dc = request.getfixturevalue(fx)
     case, spec = dc.case, dc.spec
@@ -174,7 +179,7 @@ def test_select_ties_take_lowest_positions_and_k_exceeding_candidates():
 
 
 # ------------------------------------------------------------------------ S4
-@pytest.mark.parametrize("fx", ["small_bf16", "small_f32"])
+@pytest.mark.parametrize("fx", ["small_bf16", "small_f32", "small_fp8"])
 @pytest.mark.parametrize("with_scores", [True, False])
 def test_sparse_attn_parity(fx, with_scores, request):
     dc = request.getfixturevalue(fx)
@@ -232,7 +237,7 @@ def test_k_equals_n_sparse_attention_is_full_attention(small_bf16):
 
 
 # ------------------------------------------------------------------------ baselines
-@pytest.mark.parametrize("fx", ["small_bf16", "small_f32"])
+@pytest.mark.parametrize("fx", ["small_bf16", "small_f32", "small_fp8"])
 def test_full_attention_and_exact_topk_baselines(fx, request):
     dc = request.getfixturevalue(fx)
     case, spec = dc.case, dc.spec
@@ -274,7 +279,7 @@ def test_cover_invariant_on_device(small_bf16):
 
 
 # ------------------------------------------------------------------------ whole step
-@pytest.mark.parametrize("fx", ["small_bf16", "small_f32"])
+@pytest.mark.parametrize("fx", ["small_bf16", "small_f32", "small_fp8"])
 def test_lfps_step_teacher_forced_multi_step(fx, request):
     """Each step the device gets the ORACLE's previous Top-k; candidates/Top-k/outputs must match."""
     dc = request.getfixturevalue(fx)
@@ -437,11 +442,12 @@ def test_timing_interface(small_bf16):
 
 
 # ------------------------------------------------------------------------ filtered scoring inside lfps_step
-def test_filtered_step_equals_unfiltered_step_whatever_the_history(small_bf16):
+@pytest.mark.parametrize("fx", ["small_bf16", "small_fp8"])
+def test_filtered_step_equals_unfiltered_step_whatever_the_history(fx, request):
     """lfps_step with the score filter (history from the previous call, including deliberately wrong
     histories that force the rescoring path) returns bit-identical Top-k and outputs to the
     unfiltered path."""
-    dc = small_bf16
+    dc = request.getfixturevalue(fx)
     case, spec = dc.case, dc.spec
     ref, flt = dc.make_ctx(), dc.make_ctx()
     ref.lfps_set_filter(False)

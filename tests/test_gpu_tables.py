@@ -206,9 +206,11 @@ def test_many_updates_cross_the_renormalisation():
     ctx.close()
 
 
-@pytest.fixture(scope="module")
-def table_case():
-    return DeviceCase(gen.tiny_spec("tables_bf16", B=2, L=1800, k=64, r=1, T=6))
+@pytest.fixture(scope="module", params=["bf16", "fp8"])
+def table_case(request):
+    """bf16 cache, and the same workload with FP8 (E4M3) keys beside bf16 values."""
+    return DeviceCase(gen.tiny_spec("tables_" + request.param, B=2, L=1800, k=64, r=1, T=6,
+                                    k_dtype="fp8" if request.param == "fp8" else ""))
 
 
 def _softmax64(s):
