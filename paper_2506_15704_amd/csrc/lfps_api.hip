@@ -648,7 +648,7 @@ int lfps_head_sparsity(lfps_ctx* ctx, const float* q, const lfps_kv* kv, const f
   int rc = check_kv(ctx, kv, false, &v);
   if (rc != LFPS_OK) return rc;
   hipError_t e = launch_head_sparsity(ctx->shape, ctx->cfg.kv_dtype, q, v, kbar, sigma2_hat, n_local, eps, rho, gate,
-                                      nullptr, nullptr, nullptr, nullptr, (hipStream_t)stream);
+                                      nullptr, nullptr, nullptr, nullptr, nullptr, (hipStream_t)stream);
   if (e != hipSuccess) return fail(ctx, LFPS_EHIP, "lfps_head_sparsity", e);
   return LFPS_OK;
 }
@@ -668,7 +668,7 @@ int lfps_table_step_gated(lfps_ctx* ctx, const float* q, const lfps_kv* kv, cons
   hipStream_t st = (hipStream_t)stream;
   int32_t* gate = gate_out ? gate_out : ctx->gate;
   hipError_t e = launch_head_sparsity(ctx->shape, ctx->cfg.kv_dtype, q, v, kbar, sigma2_hat, n_local, eps, nullptr,
-                                      gate, vbar, topk_idx, topk_score, out, st);
+                                      gate, vbar, topk_idx, topk_score, out, ctx->filter_on ? ctx->thr_state : nullptr, st);
   if (e != hipSuccess) return fail(ctx, LFPS_EHIP, "lfps_table_step_gated (gate)", e);
   return table_step_impl(ctx, q, v, k, topk_idx, topk_score, out, gate, st);
 }

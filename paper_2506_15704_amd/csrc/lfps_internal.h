@@ -151,10 +151,12 @@ hipError_t launch_table_init(const Shape& s, float* tab_ver, float* tab_sla, con
 hipError_t launch_table_finish(const Shape& s, const float* tab_ver, const float* tab_sla, double* state,
                                const int32_t* seq_lens, hipStream_t st);
 // Head sparsity (Eq. 5-6) and the prefill priors it needs; gate [B,Hq] marks bypassed heads, whose output
-// row (vbar) and index row (-1) the kernel writes when out != NULL.
+// row (vbar) and index row (-1) the kernel writes when out != NULL; thr_state (or NULL): the score filter's
+// per-head history, where a bypassed head without history is given +inf.
 hipError_t launch_head_sparsity(const Shape& s, int dtype, const float* q, const KvView& kv, const float* kbar,
                                 const float* sigma2_hat, int n_local, float eps, float* rho, int32_t* gate,
-                                const float* vbar, int32_t* topk_idx, float* topk_score, float* out, hipStream_t st);
+                                const float* vbar, int32_t* topk_idx, float* topk_score, float* out, float* thr_state,
+                                hipStream_t st);
 hipError_t launch_prior_means(const Shape& s, int dtype, const KvView& kv, float* kbar, float* vbar, hipStream_t st);
 hipError_t launch_prior_variance(const Shape& s, const float* q, const int32_t* seq_lens, const float* score,
                                  int64_t score_stride, float* sigma2_hat, hipStream_t st);

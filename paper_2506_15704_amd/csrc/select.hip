@@ -27,7 +27,7 @@
 namespace lfps {
 
 constexpr int kSelThreads = 1024;       // workgroup of the general kernel
-constexpr int kFilterSelThreads = 256;  // workgroup of the kernel that selects from the short survivor lists
+constexpr int kFilterSelThreads = 512;  // workgroup of the kernel that selects from the short survivor lists
 constexpr int kCacheElems = 32768;      // scores of one head kept in LDS (dynamic, 128 KB)
 
 // NT threads: 2*NT histogram bins (two per thread), up to NT members of the threshold bin ranked directly.
@@ -379,7 +379,7 @@ __global__ __launch_bounds__(kFilterSelThreads) void k_filter_select(Shape s, co
                                                                int32_t* __restrict__ redo_h, int cap,
                                                                const int32_t* __restrict__ skip_if) {
   constexpr int NT = kFilterSelThreads, kSelWaves = NT / 64;
-  constexpr int kPiecesPerThread = 4;              // nseg <= 1024
+  constexpr int kPiecesPerThread = 1024 / NT;      // nseg <= 1024
   __shared__ SelectShared<NT> sm;
   __shared__ int seg_off[kPiecesPerThread * NT];
   __shared__ int wtot[kSelWaves];

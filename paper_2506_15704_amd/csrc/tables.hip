@@ -494,7 +494,8 @@ __global__ __launch_bounds__(64) void k_head_sparsity(Shape s, const float* __re
                                                       const float* __restrict__ sigma2_hat, int n_local, float eps,
                                                       float* __restrict__ rho_out, int32_t* __restrict__ gate_out,
                                                       const float* __restrict__ vbar, int32_t* __restrict__ topk_idx,
-                                                      float* __restrict__ topk_score, float* __restrict__ out) {
+                                                      float* __restrict__ topk_score, float* __restrict__ out,
+                                                      float* __restrict__ thr_state) {
   const int bh = blockIdx.x, b = bh / s.Hq, h = bh % s.Hq, g = h / s.G, lane = threadIdx.x;
   int n = seq_lens[b];
   n = n < 0 ? 0 : (n > s.Lcap ? s.Lcap : n);
@@ -563,6 +564,11 @@ __global__ __launch_bounds__(64) void k_head_sparsity(Shape s, const float* __re
       topk_idx[(int64_t)bh * s.kmax + i] = -1;
       if (topk_score) topk_score[(int64_t)bh * s.kmax + i] = 0.f;
     }
+    // A head bypassed since the history was reset has no k-th score to remember, and a group with such a
+    // head would be taken as "no previous step" by the filtered scoring pass at every step.  +inf keeps
+    // nothing for this head there (its select is skipped anyway) and lets the group's other heads be
+    // filtered; when the head is no longer bypassed its first select falls back to the unfiltered pass.
+    if (thr_state && lane == 0 && isnan(thr_state[bh])) thr_state[bh] = INFINITY;
   }
 }
 
@@ -697,11 +703,12 @@ hipError_t launch_table_finish(const Shape& s, const float* tab_ver, const float
 
 hipError_t launch_head_sparsity(const Shape& s, int dtype, const float* q, const KvView& kv, const float* kbar,
                                 const float* sigma2_hat, int n_local, float eps, float* rho, int32_t* gate,
-                                const float* vbar, int32_t* topk_idx, float* topk_score, float* out, hipStream_t st) {
+                                const float* vbar, int32_t* topk_idx, float* topk_score, float* out, float* thr_state,
+                                hipStream_t st) {
 #define LFPS_LAUNCH_HSP(TYPE, PAGED)                                                                             \
   hipLaunchKernelGGL((k_head_sparsity<TYPE, PAGED>), dim3(s.B * s.Hq), dim3(64), 0, st, s, q, (const TYPE*)kv.k,     \
                      kv.stride_b, kv.stride_h, kv.stride_n, kv.page, kv.seq_lens, kbar, sigma2_hat, n_local, eps, rho, \
-                     gate, vbar, topk_idx, topk_score, out)
+                     gate, vbar, topk_idx, topk_score, out, thr_state)
   const bool paged = kv.page.table != nullptr;
   if (dtype == LFPS_BF16 && kv.k_fp8) {
     if (paged) LFPS_LAUNCH_HSP(uint8_t, true);

@@ -518,3 +518,42 @@ def test_tables_init_from_several_queries_is_eq4(table_case):
         want = tor.group_candidates(t64, n, 0.2, s.r, 0, n_sink)
         _assert_candidates(cand[b, g, : int(cnt[b, g])].cpu().numpy(), want, t64, n, 0.2, s.r, n_sink, f"b={b} g={g}")
     ctx.close()
+
+
+def test_gated_steps_with_and_without_the_score_filter_agree(table_case):
+    """Chained gated steps in which some heads are bypassed from the first step on (they never get a k-th score
+    of their own), then stop being bypassed (eps = 2): the context with the score filter returns bit for bit
+    what the unfiltered context returns, at every step."""
+    dc = table_case
+    s, case = dc.spec, dc.case
+    sparse = [(0, 1), (0, 2), (1, 12), (1, 13), (1, 14), (1, 15), (1, 31)]
+    rng = np.random.default_rng(10)
+    kbar = dev((rng.standard_normal((s.B, s.Hkv, s.D)) * 0.05).astype(np.float32))
+    vbar = dev(rng.standard_normal((s.B, s.Hkv, s.D)).astype(np.float32))
+    s2 = dev(rng.uniform(0.0, 0.012, size=(s.B, s.Hq)).astype(np.float32))
+    runs = []
+    for filtered in (False, True):
+        ctx = dc.make_ctx(table_mode=True, table_decay=0.9, table_a=0.2, n_sink=4, n_recent=1)
+        ctx.lfps_set_filter(filtered)
+        ctx.lfps_tables_init(dc.q(0), ctx.kv_view(dc.K, dc.V, dc.seq_lens(0)))
+        ctx.lfps_timing_enable(True)
+        hist = []
+        for t, eps in ((1, 0.97), (2, 0.97), (3, 0.97), (4, 2.0), (5, 2.0), (6, 0.97)):
+            q = dev(_sparse_queries(case, t, sparse))
+            idx = torch.full((s.B, s.Hq, case.kmax), 77, dtype=torch.int32, device=DEV)
+            isc = torch.zeros((s.B, s.Hq, case.kmax), dtype=torch.float32, device=DEV)
+            out = torch.zeros((s.B, s.Hq, s.D), dtype=torch.float32, device=DEV)
+            gate = torch.zeros((s.B, s.Hq), dtype=torch.int32, device=DEV)
+            ctx.lfps_table_step_gated(q, ctx.kv_view(dc.K, dc.V, dc.seq_lens(t)), dc.k, kbar, vbar, s2, 6, eps,
+                                      idx, out, isc, gate)
+            hist.append((idx, isc, out, gate))
+        tm = ctx.lfps_timing_read()
+        assert (tm["filter_score"][1] > 0) == filtered
+        torch.cuda.synchronize()
+        runs.append(hist)
+        ctx.close()
+    for t, (a_, b_) in enumerate(zip(*runs), start=1):
+        for what, x, y in zip(("idx", "score", "out", "gate"), a_, b_):
+            assert torch.equal(x, y), f"step {t}: {what} differs with the filter on"
+    gates = [int(h[3].sum().item()) for h in runs[1]]
+    assert gates[0] == len(sparse) and gates[3] == 0          # bypassed at first, not bypassed with eps = 2
