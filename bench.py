@@ -27,8 +27,9 @@ HBM_PEAK_GBS = 8000.0   # MI355X published HBM3E peak
 # HBM bytes per launch of the scoring kernel measured with rocprofv3 --pmc (FETCH_SIZE, WRITE_SIZE), scaled
 # by the same counters' reading for a plain copy kernel; see profiles/ for the runs.  None = not measured.
 # Median over the steady-state dispatches of the scoring kernel (k_filter_score_bf16):
-#   profiles/lfps_kernels_C4.md: 944.6 MB fetched + 10.5 MB written; C3: 224.9 + 3.1 MB; C5: 480.3 + 8.9 MB.
-MEASURED_TRAFFIC_BYTES = {"C4": 955.1e6, "C3": 228.0e6, "C5": 489.2e6}
+#   profiles/lfps_kernels_C4.md: 944.5 MB fetched + 10.5 MB written; C3: 225.0 + 3.1 MB; C5: 480.3 + 8.9 MB;
+#   with FP8 keys (C4, same file): 477.6 + 10.5 MB.
+MEASURED_TRAFFIC_BYTES = {"C4": 955.0e6, "C3": 228.1e6, "C5": 489.2e6, "C4-fp8k": 488.1e6}
 
 
 def parse_args():
@@ -350,7 +351,8 @@ def measure_fp8_keys(name, steps, warmup):
            "cand_frac": round(float(cnts.mean() / (spec.L or r.case.seq_lens0.mean())), 4),
            "recall_vs_exact_topk": round(recall, 4),
            "kernel_us": {k: round(v[0] / steps * 1e3, 2) for k, v in tm.items() if v[1]},
-           "score_kernel": {"kernel": kname, "bytes_per_launch": round(by), "avg_launch_us": round(us, 2),
+           "score_kernel": {"kernel": kname, "bytes_per_launch": round(by), "traffic": MEASURED_TRAFFIC_BYTES.get(spec.name),
+                            "avg_launch_us": round(us, 2),
                             "GB_per_s": round(by / (us * 1e-6) / 1e9, 1) if us > 0 else None,
                             "frac_of_hbm_peak": round(by / (us * 1e-6) / 1e9 / HBM_PEAK_GBS, 4) if us > 0 else None},
            "exact_topk_ms": round(exact * 1e3, 4), "full_attn_ms": round(full * 1e3, 4)}
