@@ -1,0 +1,85 @@
+"""Seeded random configurations of the chained step: head grouping, batch, ragged lengths, per-request
+budgets, radius, always-present rows, cache dtype (bf16 / fp32 / FP8 keys) and layout (contiguous / paged)
+drawn together, so that combinations no hand-written case names are exercised.  Every step is checked
+against the CPU oracle given the device's own previous Top-k (candidate counts exactly; Top-k, scores and
+outputs by the rules of tests/harness.py)."""
+import numpy as np
+import pytest
+import torch
+
+import gen
+from gen import device as gen_device
+from oracle import lfps_oracle as orc
+from tests.harness import (DEV, DeviceCase, assert_out_close, assert_scores_close, assert_topk_equal_mod_ties, dev,
+                           valid_row)
+
+pytestmark = pytest.mark.gpu
+
+N_CONFIGS = 40
+
+
+def _draw(i):
+    rng = np.random.default_rng(7000 + i)
+    Hq, Hkv = [(32, 8), (16, 8), (8, 8), (4, 1), (8, 2), (2, 1)][int(rng.integers(0, 6))]
+    lo = int(rng.integers(24, 120)) if i % 6 == 5 else int(rng.integers(24, 3000))     # every sixth: very short contexts
+    hi = lo + (int(rng.integers(0, 100)) if i % 6 == 5 else int(rng.integers(0, 2500)))
+    kind = ("bf16", "f32", "fp8")[i % 3]
+    cfg = dict(Hq=Hq, Hkv=Hkv, B=int(rng.integers(1, 5)), L_range=(lo, hi), kmax=int(rng.integers(1, min(lo, 160) + 1)),
+               r=int(rng.choice([0, 1, 2, 4, 9])), n_recent=int(rng.integers(0, 4)), n_sink=int(rng.integers(0, 5)),
+               kv_dtype="f32" if kind == "f32" else "bf16", k_dtype="fp8" if kind == "fp8" else "",
+               paged=[None, (1, "block_head_row"), (16, "block_row_head"), (64, "block_head_row")][int(rng.integers(0, 4))])
+    cfg["k"] = rng.integers(1, cfg["kmax"] + 1, size=cfg["B"]).astype(np.int32)
+    cfg["k"][int(rng.integers(0, cfg["B"]))] = cfg["kmax"]
+    return cfg
+
+
+@pytest.mark.parametrize("i", range(N_CONFIGS))
+def test_random_configuration_chained_steps(i):
+    c = _draw(i)
+    T = 3
+    spec = gen.tiny_spec(f"rnd{i}", B=c["B"], L=None, L_range=c["L_range"], k=c["kmax"], r=c["r"], T=T, Hq=c["Hq"],
+                         Hkv=c["Hkv"], kv_dtype=c["kv_dtype"], k_dtype=c["k_dtype"], seed=31000 + i,
+                         recency=min(16, c["L_range"][0] // 2))
+    dc = DeviceCase(spec)
+    case, G = dc.case, spec.G
+    ctx = dc.make_ctx(n_recent=c["n_recent"], n_sink=c["n_sink"])
+    if c["paged"]:
+        Kp, Vp, table = gen_device.paginate(dc.K, dc.V, c["paged"][0], seed=i, layout=c["paged"][1])
+        view = lambda t: ctx.paged_kv_view(Kp, Vp, table, dc.seq_lens(t))
+    else:
+        view = lambda t: ctx.kv_view(dc.K, dc.V, dc.seq_lens(t))
+    k_dev = dev(c["k"])
+    shp = (spec.B, spec.Hq, case.kmax)
+    prev = torch.full(shp, -1, dtype=torch.int32, device=DEV)
+    ctx.lfps_exact_topk(dc.q(0), view(0), k_dev, prev)
+    what = f"config {i}: {c}"
+    for t in range(1, T + 1):
+        idx = torch.full(shp, -9, dtype=torch.int32, device=DEV)
+        sc = torch.zeros(shp, dtype=torch.float32, device=DEV)
+        out = torch.full((spec.B, spec.Hq, spec.D), 7.0, dtype=torch.float32, device=DEV)
+        cnt = torch.zeros((spec.B, spec.Hkv), dtype=torch.int32, device=DEV)
+        ctx.lfps_step(dc.q(t), view(t), prev, k_dev, idx, out, sc)
+        ctx.lfps_copy_cand_count(cnt)
+        assert ctx.lfps_poll_status() == 0, what
+        p_h, i_h, s_h, o_h, c_h = (x.cpu().numpy() for x in (prev, idx, sc, out, cnt))
+        n = case.seq_lens(t)
+        for b in range(spec.B):
+            kb, nb = int(c["k"][b]), int(n[b])
+            for g in range(spec.Hkv):
+                K, V = dc.group(b, g)
+                res = orc.lfps_step(case.q[t, b, G * g: G * g + G], K, V,
+                                    [valid_row(p_h[b, G * g + h, :kb]) for h in range(G)], nb, kb, spec.r,
+                                    c["n_recent"], c["n_sink"])
+                assert c_h[b, g] == len(res["cand"]), f"{what}: t{t} b{b} g{g} candidate count"
+                ksel = min(kb, len(res["cand"]))
+                for hh in range(G):
+                    h = G * g + hh
+                    assert (i_h[b, h, ksel:] == -1).all(), f"{what}: padding"
+                    got = i_h[b, h, :ksel]
+                    assert np.all(np.diff(got) > 0), f"{what}: indices not ascending"
+                    assert_topk_equal_mod_ties(got, res["topk_idx"][hh], lambda p: orc.scores(case.q[t, b, h], K, p),
+                                               ksel, f"{what}: t{t} b{b} h{h}")
+                    assert_scores_close(s_h[b, h, :ksel], orc.scores(case.q[t, b, h], K, got), f"{what}: scores")
+                    assert_out_close(o_h[b, h], orc.sparse_attn(case.q[t, b, h], K, V, got), f"{what}: t{t} b{b} h{h}")
+        prev = idx
+    ctx.close()
