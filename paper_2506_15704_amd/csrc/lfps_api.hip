@@ -546,9 +546,22 @@ int lfps_tables_export(lfps_ctx* ctx, double* phi_ver, double* phi_sla, const in
   return LFPS_OK;
 }
 
+// The table entry points keep two counters on the host (accumulated decay, updates since the last start): a
+// captured graph would replay the launches without them, so capture is refused rather than left to go wrong
+// after ~900 replays (when the stored entries would have needed folding).
+static int refuse_capture(lfps_ctx* ctx, hipStream_t st, const char* who) {
+  hipStreamCaptureStatus status = hipStreamCaptureStatusNone;
+  if (hipStreamIsCapturing(st, &status) == hipSuccess && status != hipStreamCaptureStatusNone) {
+    snprintf(ctx->err, sizeof ctx->err, "%s: score-table calls keep host-side counters and cannot be captured into a graph", who);
+    return LFPS_EINVAL;
+  }
+  return LFPS_OK;
+}
+
 static int table_candidates_impl(lfps_ctx* ctx, const int32_t* seq_lens, int32_t* cand, int32_t* cand_count,
                                  bool for_step, const int32_t* gate, hipStream_t st) {
   const Shape& s = ctx->shape;
+  if (int rc = refuse_capture(ctx, st, "lfps_table_candidates / lfps_table_step")) return rc;
   if (ctx->tab_scale < 1e-20) {          // fold the accumulated decay back into the stored entries
     hipError_t e = launch_table_renorm(s, ctx->tab_ver, ctx->tab_sla, ctx->tab_state, st);
     if (e != hipSuccess) return fail(ctx, LFPS_EHIP, "table renormalisation", e);
@@ -568,6 +581,7 @@ static int table_candidates_impl(lfps_ctx* ctx, const int32_t* seq_lens, int32_t
 static int table_update_impl(lfps_ctx* ctx, const int32_t* idx, const float* idx_score, const int32_t* k,
                              const int32_t* seq_lens, const int32_t* gate, hipStream_t st) {
   const Shape& s = ctx->shape;
+  if (int rc = refuse_capture(ctx, st, "lfps_table_update / lfps_table_step")) return rc;
   if (ctx->tab_updates >= s.Lcap - 1)
     return fail(ctx, LFPS_ECAP, "lfps_table_update: max_seq_len - 1 updates since the last import/init");
   LAUNCH(ctx, LFPS_KERNEL_TABLE_UPDATE, st,

@@ -557,3 +557,48 @@ def test_gated_steps_with_and_without_the_score_filter_agree(table_case):
             assert torch.equal(x, y), f"step {t}: {what} differs with the filter on"
     gates = [int(h[3].sum().item()) for h in runs[1]]
     assert gates[0] == len(sparse) and gates[3] == 0          # bypassed at first, not bypassed with eps = 2
+
+
+@pytest.mark.filterwarnings("ignore:The CUDA Graph is empty")
+def test_memoryless_step_can_be_captured_and_table_step_refuses(table_case):
+    """lfps_step is kernel launches only: captured once into a graph and replayed three times with eager work
+    in between, every replay equals the eager result.  The table step keeps host counters and says no."""
+    from paper_2506_15704_amd.binding import LfpsError
+    dc = table_case
+    s, case = dc.spec, dc.case
+    shp = (s.B, s.Hq, case.kmax)
+    ref_ctx, ctx = dc.make_ctx(), dc.make_ctx()
+    seed = torch.zeros(shp, dtype=torch.int32, device=DEV)
+    ref_ctx.lfps_exact_topk(dc.q(0), ref_ctx.kv_view(dc.K, dc.V, dc.seq_lens(0)), dc.k, seed)
+    # fixed buffers the graph works on
+    q, sl, prev = dc.q(1).clone(), dc.seq_lens(1).clone(), seed.clone()
+    idx = torch.zeros(shp, dtype=torch.int32, device=DEV)
+    out = torch.zeros((s.B, s.Hq, s.D), dtype=torch.float32, device=DEV)
+    kv = ctx.kv_view(dc.K, dc.V, sl)
+    ctx.lfps_step(q, kv, prev, dc.k, idx, out)               # warm-up outside the capture (also sets the history)
+    ctx.lfps_reset_history()
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        ctx.lfps_step(q, kv, prev, dc.k, idx, out)
+    want_prev = seed.clone()
+    for t in (1, 2, 3):
+        e_idx = torch.zeros(shp, dtype=torch.int32, device=DEV)
+        e_out = torch.zeros_like(out)
+        ref_ctx.lfps_step(dc.q(t), ref_ctx.kv_view(dc.K, dc.V, dc.seq_lens(t)), want_prev, dc.k, e_idx, e_out)
+        q.copy_(dc.q(t))                                      # eager work between the replays
+        sl.copy_(dc.seq_lens(t))
+        prev.copy_(want_prev)
+        graph.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(idx, e_idx) and torch.equal(out, e_out), f"replay {t}"
+        want_prev = e_idx
+    tab = dc.make_ctx(table_mode=True)
+    tab.lfps_tables_init(dc.q(0), tab.kv_view(dc.K, dc.V, dc.seq_lens(0)))
+    torch.cuda.synchronize()
+    g2 = torch.cuda.CUDAGraph()
+    with pytest.raises(LfpsError) as e:
+        with torch.cuda.graph(g2):
+            tab.lfps_table_step(q, tab.kv_view(dc.K, dc.V, sl), dc.k, idx, out)
+    assert "captured" in str(e.value)
+    torch.cuda.synchronize()
