@@ -156,6 +156,39 @@ class Runner:
         torch.cuda.synchronize()
         return (time.perf_counter() - t0) / steps
 
+    def run_step_percentiles(self, steps, warmup):
+        """The same steps once more with an event pair around every lfps_step call on the stream the kernels
+        run on: p10 / median / p90 of the per-step device time in microseconds."""
+        torch, np = self.torch, self.np
+        self.reset()
+        self.ctx.lfps_reset_history()
+        for _ in range(warmup):
+            self.step()
+        ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(steps)]
+        for a, b in ev:
+            a.record()
+            self.step()
+            b.record()
+        torch.cuda.synchronize()
+        us = np.array([a.elapsed_time(b) * 1e3 for a, b in ev])
+        return {"p10": round(float(np.percentile(us, 10)), 2), "median": round(float(np.median(us)), 2),
+                "p90": round(float(np.percentile(us, 90)), 2)}
+
+    def union_rows_last_step(self):
+        """Rows the sparse attention of the last step had to fetch if every KV group read each selected row
+        once for all its heads: sum over (b, g) of |union over the group's heads of the selected positions|."""
+        torch = self.torch
+        spec = self.spec
+        idx = self.prev
+        total = 0
+        for b in range(spec.B):
+            kb = int(self.case.k[b])
+            rows = idx[b, :, :kb].reshape(spec.Hkv, spec.G * kb)
+            for g in range(spec.Hkv):
+                u = torch.unique(rows[g])
+                total += int((u >= 0).sum().item())
+        return total
+
     def run_timed_graph(self, steps, warmup):
         """The same K steps captured once into a HIP graph and replayed: removes the host launch gaps
         between the kernels of a step.  Returns (seconds per step, outputs equal to the eager run?)."""
@@ -270,6 +303,8 @@ def measure(name, steps, warmup, with_baselines=True, use_graph=True):
     recall = r.recall_vs_exact()
     sec_graph, graph_ok = r.run_timed_graph(steps, warmup) if use_graph else (None, None)
     tm, cnts = r.run_kernel_timing(steps, warmup)
+    union_rows = r.union_rows_last_step()
+    step_us = r.run_step_percentiles(steps, warmup)
     filtered = tm["filter_score"][1] > 0
     kname = "filter_score" if filtered else "gather_score"
     gs_ms, gs_n = tm[kname]
@@ -286,15 +321,31 @@ def measure(name, steps, warmup, with_baselines=True, use_graph=True):
                      "launches": gs_n, "timed_by": "HIP events around each launch, second pass over the same steps",
                      "note": "redo launches of gather_score (heads the filter left short) are in kernel_us"},
         "kernel_us": {k: round(v[0] / steps * 1e3, 2) for k, v in tm.items() if v[1]},   # per step
+        "step_us": step_us,
         "cand_frac": round(float(cnts.mean() / (spec.L or r.case.seq_lens0.mean())), 4),
         "recall_vs_exact_topk": round(recall, 4),
     }
+    # S4: V bytes if every head fetched its own rows (upper bound) and if a group fetched each row once (lower bound)
+    row_bytes = spec.D * (2 if spec.kv_dtype == "bf16" else 4)
+    at_us = tm["sparse_attn"][0] / max(tm["sparse_attn"][1], 1) * 1e3
+    upper = float(r.case.k.sum()) * spec.Hq * row_bytes
+    lower = float(union_rows) * row_bytes
+    res["sparse_attn"] = {"avg_launch_us": round(at_us, 2), "bytes_per_head_rows": round(upper), "bytes_group_union_last_step": round(lower),
+                          "GB_per_s_at_union_bytes": round(lower / (at_us * 1e-6) / 1e9, 1) if at_us > 0 else None,
+                          "GB_per_s_at_per_head_bytes": round(upper / (at_us * 1e-6) / 1e9, 1) if at_us > 0 else None}
     if with_baselines:
         reps = 5 if name in ("C4", "C5") else 20
         exact = r.time_baseline("exact", reps)
         full = r.time_baseline("full", reps)
         res.update({"exact_topk_ms": round(exact * 1e3, 4), "full_attn_ms": round(full * 1e3, 4),
                     "speedup_vs_exact_topk": round(exact / sec, 3), "speedup_vs_full_attn": round(full / sec, 3)})
+        # the contiguous stream of the full-attention baseline as the "achievable" reference beside the 8 TB/s peak
+        t_ref = min(spec.T, 2)
+        stream_bytes = 2.0 * float(r.case.seq_lens(t_ref).sum()) * spec.Hkv * row_bytes
+        stream_gbs = stream_bytes / full / 1e9
+        res["stream_reference"] = {"kernel": "full_attn (contiguous K and V stream)", "bytes": round(stream_bytes),
+                                   "GB_per_s": round(stream_gbs, 1), "frac_of_hbm_peak": round(stream_gbs / HBM_PEAK_GBS, 4)}
+        res["roofline"]["frac_of_stream_reference"] = round(achieved / stream_gbs, 4)
     r.close()
     return res, r.case
 
@@ -514,7 +565,8 @@ def main():
                                f"{spec.kv_dtype} K/V, k={spec.k or spec.k_frac}, r={spec.r}, {spec.T} decode steps",
                    "B": spec.B, "L": spec.L or list(spec.L_range), "k": spec.k or spec.k_frac, "r": spec.r},
         "roofline": main_res["roofline"],
-        "kernel_us": main_res["kernel_us"],
+        "kernel_us": main_res["kernel_us"], "step_us": main_res["step_us"],
+        "sparse_attn": main_res["sparse_attn"], "stream_reference": main_res.get("stream_reference"),
         "ms_per_step_hip_graph": main_res["ms_per_step_hip_graph"],
         "hip_graph_matches_eager": main_res["hip_graph_matches_eager"],
         "cand_frac": main_res["cand_frac"], "recall_vs_exact_topk": main_res["recall_vs_exact_topk"],
