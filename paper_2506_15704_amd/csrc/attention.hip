@@ -214,19 +214,35 @@ __global__ __launch_bounds__(kAttnThreads) void k_full_attn(Shape s, const float
     for (int c = 0; c < 8; ++c) acc[h][c] = 0.f;
   }
 
-  constexpr int U = 4;                       // rows in flight per lane group
-  // wave w takes rows r_begin + 16*(4*i + w) + 4*u + rs
-  for (int r0 = r_begin + 16 * wave; r0 < r_end; r0 += 64) {
+  constexpr int U = 4;                       // rows per lane group and tile
+  // Wave w takes rows r_begin + 16*(4*i + w) + 4*u + rs of tile i.  Two tiles are kept in flight: the loads of
+  // the next one are issued before the current one is used, as raw cache elements (half or a quarter of the
+  // registers of their fp32 form).  Rows past the end are read from the last row and weigh nothing, so no
+  // load sits behind a branch.
+  struct Tile {
+    Raw8<TK> k[U];
+    Raw8<T> v[U];
+    bool ok[U];
+  };
+  auto issue = [&](Tile& t, int r0) {
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      int r = r0 + 4 * u + rs;
+      t.ok[u] = r < r_end;
+      r = t.ok[u] ? r : r_end - 1;
+      const int64_t off = Rows::offset(pg, Rows::phys(pg, b, r), stride_b, stride_n);
+      t.k[u].load(Kbg + off);
+      t.v[u].load(Vbg + off);
+    }
+  };
+  auto consume = [&](const Tile& t) {
     float kx[U][8], vx[U][8];
     bool ok[U];
 #pragma unroll
     for (int u = 0; u < U; ++u) {
-      int r = r0 + 4 * u + rs;
-      ok[u] = r < r_end;
-      r = ok[u] ? r : r_end - 1;
-      const int64_t off = Rows::offset(pg, Rows::phys(pg, b, r), stride_b, stride_n);
-      load8(Kbg + off, kx[u]);
-      load8(Vbg + off, vx[u]);
+      t.k[u].get(kx[u]);
+      t.v[u].get(vx[u]);
+      ok[u] = t.ok[u];
     }
     float sc[U][G];
 #pragma unroll
@@ -267,6 +283,14 @@ __global__ __launch_bounds__(kAttnThreads) void k_full_attn(Shape s, const float
         acc[h][c] = a;
       }
     }
+  };
+  Tile ta, tb;
+  issue(ta, r_begin + 16 * wave);
+  for (int r0 = r_begin + 16 * wave; r0 < r_end; r0 += 128) {
+    issue(tb, r0 + 64);
+    consume(ta);
+    issue(ta, r0 + 128);
+    consume(tb);
   }
 
   // merge the 4 lane groups of the wave, then the 4 waves

@@ -193,25 +193,48 @@ __device__ __forceinline__ bf16x8 fp8x8_to_bf16x8(uint32_t w0, uint32_t w1) {
   return r.v;
 }
 
-// Eight consecutive elements of a K or V row as fp32: T = float, uint16_t (bf16 bits) or uint8_t (E4M3).
+// Eight consecutive elements of a K or V row as they are loaded (T = float, uint16_t = bf16 bits, uint8_t =
+// E4M3), converted to fp32 when used: a row waiting in registers costs 8, 4 or 2 of them.
 template <typename T>
-__device__ __forceinline__ void load8(const T* p, float x[8]) {
-  if constexpr (sizeof(T) == 1) {
-    const uint2 w = *reinterpret_cast<const uint2*>(p);
-    fp8x4_to_f32(w.x, x);
-    fp8x4_to_f32(w.y, x + 4);
-  } else if constexpr (sizeof(T) == 2) {
-    u32x4 w = *reinterpret_cast<const u32x4*>(p);
+struct Raw8;
+template <>
+struct Raw8<float> {
+  float4 a, b;
+  __device__ __forceinline__ void load(const float* p) {
+    a = reinterpret_cast<const float4*>(p)[0];
+    b = reinterpret_cast<const float4*>(p)[1];
+  }
+  __device__ __forceinline__ void get(float x[8]) const {
+    x[0] = a.x; x[1] = a.y; x[2] = a.z; x[3] = a.w;
+    x[4] = b.x; x[5] = b.y; x[6] = b.z; x[7] = b.w;
+  }
+};
+template <>
+struct Raw8<uint16_t> {
+  u32x4 w;
+  __device__ __forceinline__ void load(const uint16_t* p) { w = *reinterpret_cast<const u32x4*>(p); }
+  __device__ __forceinline__ void get(float x[8]) const {
 #pragma unroll
     for (int c = 0; c < 4; ++c) {
       x[2 * c] = bf16_lo(w[c]);
       x[2 * c + 1] = bf16_hi(w[c]);
     }
-  } else {
-    float4 a = reinterpret_cast<const float4*>(p)[0], b = reinterpret_cast<const float4*>(p)[1];
-    x[0] = a.x; x[1] = a.y; x[2] = a.z; x[3] = a.w;
-    x[4] = b.x; x[5] = b.y; x[6] = b.z; x[7] = b.w;
   }
+};
+template <>
+struct Raw8<uint8_t> {
+  uint2 w;
+  __device__ __forceinline__ void load(const uint8_t* p) { w = *reinterpret_cast<const uint2*>(p); }
+  __device__ __forceinline__ void get(float x[8]) const {
+    fp8x4_to_f32(w.x, x);
+    fp8x4_to_f32(w.y, x + 4);
+  }
+};
+template <typename T>
+__device__ __forceinline__ void load8(const T* p, float x[8]) {
+  Raw8<T> r;
+  r.load(p);
+  r.get(x);
 }
 
 // Order-preserving map fp32 -> uint32 (larger float <=> larger key).
