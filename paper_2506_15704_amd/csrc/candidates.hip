@@ -41,19 +41,12 @@ __device__ __forceinline__ int emit_bitmap(const Shape& s, const uint32_t* bm, i
   const int nr = (W + 63) >> 6;                                  // rounds (<= kCandThreads, checked at creation)
   for (int r_ = wv; r_ < nr; r_ += kCandThreads / 64) {
     const int w = r_ * 64 + lane;
-    int c_ = w < W ? __popc(bm[w]) : 0;
-#pragma unroll
-    for (int d = 1; d < 64; d <<= 1) c_ += __shfl_xor(c_, d);
-    if (lane == 0) rcnt[r_] = (uint32_t)c_;
+    const int c_ = wave_inclusive_sum(w < W ? __popc(bm[w]) : 0);
+    if (lane == 63) rcnt[r_] = (uint32_t)c_;                      // the round's total
   }
   __syncthreads();
   int cnt = tid < nr ? (int)rcnt[tid] : 0;
-  int inc = cnt;
-#pragma unroll
-  for (int d = 1; d < 64; d <<= 1) {
-    int o = __shfl_up(inc, d);
-    if (lane >= d) inc += o;
-  }
+  const int inc = wave_inclusive_sum(cnt);
   if (lane == 63) wave_tot[wv] = inc;
   __syncthreads();
   int base = 0, total = 0;
@@ -72,12 +65,7 @@ __device__ __forceinline__ int emit_bitmap(const Shape& s, const uint32_t* bm, i
     const int w = r_ * 64 + lane;
     uint32_t bits = w < W ? bm[w] : 0u;
     const int c_ = __popc(bits);
-    int incl = c_;
-#pragma unroll
-    for (int d = 1; d < 64; d <<= 1) {
-      int o = __shfl_up(incl, d);
-      if (lane >= d) incl += o;
-    }
+    const int incl = wave_inclusive_sum(c_);
     const int tot = __shfl(incl, 63);
     int o_ = incl - c_;
     while (bits) {

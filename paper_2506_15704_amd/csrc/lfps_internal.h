@@ -237,6 +237,18 @@ __device__ __forceinline__ void load8(const T* p, float x[8]) {
   r.get(x);
 }
 
+// Inclusive prefix sum over the 64 lanes of a wave, on the vector ALU alone (DPP row shifts inside each row of
+// 16 lanes, then two row broadcasts for the carries); a scan by lane shuffles costs six LDS-crossbar round trips.
+__device__ __forceinline__ int wave_inclusive_sum(int x) {
+  x += __builtin_amdgcn_update_dpp(0, x, 0x111, 0xf, 0xf, false);   // row_shr:1
+  x += __builtin_amdgcn_update_dpp(0, x, 0x112, 0xf, 0xf, false);   // row_shr:2
+  x += __builtin_amdgcn_update_dpp(0, x, 0x114, 0xf, 0xf, false);   // row_shr:4
+  x += __builtin_amdgcn_update_dpp(0, x, 0x118, 0xf, 0xf, false);   // row_shr:8
+  x += __builtin_amdgcn_update_dpp(0, x, 0x142, 0xa, 0xf, false);   // row_bcast:15 into rows 1 and 3
+  x += __builtin_amdgcn_update_dpp(0, x, 0x143, 0xc, 0xf, false);   // row_bcast:31 into rows 2 and 3
+  return x;
+}
+
 // Order-preserving map fp32 -> uint32 (larger float <=> larger key).
 __device__ __forceinline__ uint32_t f2key(float f) {
   uint32_t u = __float_as_uint(f);

@@ -239,12 +239,7 @@ __device__ __forceinline__ void select_body(SelectShared<NT>& sm, float* __restr
       const float x = cache[i];
       mine += (x > thr ? 0x10000u : 0u) + (x == thr ? 1u : 0u);
     }
-    uint32_t inc = mine;
-#pragma unroll
-    for (int d = 1; d < 64; d <<= 1) {
-      const uint32_t o = __shfl_up(inc, d);
-      if (lane >= d) inc += o;
-    }
+    const uint32_t inc = (uint32_t)wave_inclusive_sum((int)mine);
     if (lane == 63) sm.cnt_gt[wv] = inc;
     __syncthreads();
     uint32_t before = inc - mine;
@@ -432,12 +427,7 @@ __global__ __launch_bounds__(kFilterSelThreads) void k_filter_select(Shape s, co
     }
     cnt += cntp[u];
   }
-  int inc = cnt;
-#pragma unroll
-  for (int d = 1; d < 64; d <<= 1) {
-    int o = __shfl_up(inc, d);
-    if (lane >= d) inc += o;
-  }
+  const int inc = wave_inclusive_sum(cnt);
   if (lane == 63) wtot[wv] = inc;
   __syncthreads();
   int base = 0, n = 0;
