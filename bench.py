@@ -62,7 +62,7 @@ class Runner:
     """Device state of one workload and the step loop."""
 
     def __init__(self, name, table_mode=False, n_sink=0, gated=False, paged_block=0, paged_layout="block_head_row",
-                 k_dtype=""):
+                 k_dtype="", v_dtype=""):
         import numpy as np
         import torch
 
@@ -74,7 +74,8 @@ class Runner:
         self.spec = spec = gen.WORKLOADS[name]
         if k_dtype:          # the same workload with the keys stored in another format
             import dataclasses
-            self.spec = spec = dataclasses.replace(spec, name=f"{name}-{k_dtype}k", k_dtype=k_dtype)
+            self.spec = spec = dataclasses.replace(spec, name=f"{name}-{k_dtype}k" + ("v" if v_dtype else ""),
+                                                   k_dtype=k_dtype, v_dtype=v_dtype)
         self.case = case = gen.make_case(spec)
         self.dev = "cuda:0"
         self.K, self.V = gen_device.fill_kv(case, self.dev)
@@ -86,7 +87,7 @@ class Runner:
         self.ctx = Lfps(batch=spec.B, n_q_heads=spec.Hq, n_kv_heads=spec.Hkv, head_dim=spec.D,
                         kv_dtype=spec.kv_dtype, max_seq_len=case.Lcap, max_k=case.kmax, radius=spec.r,
                         n_recent=1, n_sink=n_sink, table_mode=table_mode, table_decay=0.95, table_a=0.2,
-                        k_fp8=spec.k_dtype == "fp8")
+                        k_fp8=spec.k_dtype == "fp8", v_fp8=spec.v_dtype == "fp8")
         self.table_mode = table_mode
         self.gated = gated
         if gated:        # prefill priors of the bypass (Sec. 4.2 "Prefilling"), from the step-0 query
@@ -382,10 +383,11 @@ def measure_paged(name, steps, warmup, block_size=16, layout="block_head_row"):
     return res
 
 
-def measure_fp8_keys(name, steps, warmup):
-    """The main workload with K stored as OCP FP8 E4M3 (the same draws rounded to 3 mantissa bits; V stays
-    bf16): half the bytes per scored row.  A different input, so nothing is compared with the bf16 run."""
-    r = Runner(name, k_dtype="fp8")
+def measure_fp8_keys(name, steps, warmup, with_v=False):
+    """The main workload with K (and, with_v, V) stored as OCP FP8 E4M3 (the same draws rounded to 3 mantissa
+    bits): half the bytes per scored (and per gathered) row.  A different input, so nothing is compared with
+    the bf16 run."""
+    r = Runner(name, k_dtype="fp8", v_dtype="fp8" if with_v else "")
     spec = r.spec
     if steps <= 0:
         steps = max(1, spec.T - warmup)
@@ -398,7 +400,7 @@ def measure_fp8_keys(name, steps, warmup):
     us = tm[kname][0] / max(tm[kname][1], 1) * 1e3
     exact = r.time_baseline("exact", 5)
     full = r.time_baseline("full", 5)
-    res = {"k_dtype": "fp8 e4m3 (V bf16)", "ms_per_step": round(sec * 1e3, 4), "steps_per_s": round(1.0 / sec, 2),
+    res = {"k_dtype": "fp8 e4m3 (V fp8 e4m3)" if with_v else "fp8 e4m3 (V bf16)", "ms_per_step": round(sec * 1e3, 4), "steps_per_s": round(1.0 / sec, 2),
            "cand_frac": round(float(cnts.mean() / (spec.L or r.case.seq_lens0.mean())), 4),
            "recall_vs_exact_topk": round(recall, 4),
            "kernel_us": {k: round(v[0] / steps * 1e3, 2) for k, v in tm.items() if v[1]},
@@ -546,7 +548,8 @@ def main():
               flush=True)
         return
     if args.fp8_only:
-        print(json.dumps({"workload": args.workload, "fp8_keys": measure_fp8_keys(args.workload, args.steps, args.warmup)}),
+        print(json.dumps({"workload": args.workload, "fp8_keys": measure_fp8_keys(args.workload, args.steps, args.warmup),
+                          "fp8_keys_and_values": measure_fp8_keys(args.workload, args.steps, args.warmup, with_v=True)}),
               flush=True)
         return
     if args.paged_only:
@@ -580,6 +583,7 @@ def main():
         line["score_table_mode"] = tab
     if not args.no_fp8 and spec.kv_dtype == "bf16":
         line["fp8_keys"] = measure_fp8_keys(args.workload, args.steps, args.warmup)
+        line["fp8_keys_and_values"] = measure_fp8_keys(args.workload, args.steps, args.warmup, with_v=True)
     if not args.no_paged:
         line["paged_kv"] = measure_paged(args.workload, args.steps, args.warmup, args.paged_block, args.paged_layout)
     if args.all_workloads:

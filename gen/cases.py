@@ -141,7 +141,8 @@ class CaseSpec:
     L: Optional[int] = None                 # fixed context length ...
     L_range: Optional[Tuple[int, int]] = None  # ... or ragged, uniform in [lo, hi]
     kv_dtype: str = "bf16"                   # "bf16" | "f32"
-    k_dtype: str = ""                        # "" = same as kv_dtype | "fp8": K stored as OCP FP8 E4M3 (bf16 V)
+    k_dtype: str = ""                        # "" = same as kv_dtype | "fp8": K stored as OCP FP8 E4M3
+    v_dtype: str = ""                        # "" = same as kv_dtype | "fp8": V stored as OCP FP8 E4M3
     k: Optional[int] = None                  # fixed budget ...
     k_frac: Optional[float] = None           # ... or fraction of the initial length, multiple of 64
     r: int = 4                               # expansion radius
@@ -270,7 +271,7 @@ class Case:
         else:
             raise ValueError(which)
         x = x.astype(np.float32)
-        if which == "k" and spec.k_dtype == "fp8":
+        if (which == "k" and spec.k_dtype == "fp8") or (which == "v" and spec.v_dtype == "fp8"):
             bits = f32_to_e4m3_bits(x)
             return e4m3_bits_to_f32(bits), bits
         if spec.kv_dtype == "bf16":
@@ -293,7 +294,8 @@ class Case:
     def kv_bytes(self) -> int:
         e = 2 if self.spec.kv_dtype == "bf16" else 4
         ek = 1 if self.spec.k_dtype == "fp8" else e
-        return self.spec.B * self.spec.Hkv * self.Lcap * self.spec.D * (e + ek)
+        ev = 1 if self.spec.v_dtype == "fp8" else e
+        return self.spec.B * self.spec.Hkv * self.Lcap * self.spec.D * (ev + ek)
 
 
 def make_case(spec: CaseSpec) -> Case:

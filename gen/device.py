@@ -48,7 +48,8 @@ def fill_kv(case, device="cuda:0"):
     shape = (spec.B, spec.Hkv, case.Lcap, spec.D)
     k_fp8 = spec.k_dtype == "fp8"
     K = torch.empty(shape, dtype=torch.float8_e4m3fn if k_fp8 else dt, device=device)
-    V = torch.empty(shape, dtype=dt, device=device)
+    v_fp8 = spec.v_dtype == "fp8"
+    V = torch.empty(shape, dtype=torch.float8_e4m3fn if v_fp8 else dt, device=device)
     fmt = int(spec.kv_dtype == "bf16")
     dev = lambda a: torch.from_numpy(np.ascontiguousarray(a)).to(device)
     key_k = dev(case.key_k.view(np.int64))
@@ -64,7 +65,7 @@ def fill_kv(case, device="cuda:0"):
                          hot.data_ptr() if n_hot > 0 else None, bias.data_ptr(), st)
     if rc != 0:
         raise RuntimeError(f"gen_fill_kv(K) failed with hipError {rc}")
-    rc = lib.gen_fill_kv(V.data_ptr(), fmt, spec.B, spec.Hkv, case.Lcap, 0,
+    rc = lib.gen_fill_kv(V.data_ptr(), 2 if v_fp8 else fmt, spec.B, spec.Hkv, case.Lcap, 0,
                          key_v.data_ptr(), row_end.data_ptr(), None, None, None, st)
     if rc != 0:
         raise RuntimeError(f"gen_fill_kv(V) failed with hipError {rc}")

@@ -67,8 +67,11 @@ typedef struct {
   int32_t table_mode;  /* 1: also allocate the per-head score tables used by the lfps_table_* entry points */
   float table_decay;   /* gamma of Eq. 10 (the paper's decay factor r = 0.95); table mode needs 0 < gamma < 1 */
   float table_a;       /* a of Eq. 8 (0.2 / 0.3 in the paper); table mode needs a > 0 */
-  int32_t k_fp8;       /* 1: K is stored as OCP FP8 E4M3, one byte per element (V stays bf16: needs kv_dtype = LFPS_BF16).
-                          The values are used as they are; a dequantisation scale is the caller's to fold into q. */
+  int32_t k_fp8;       /* 1: K is stored as OCP FP8 E4M3, one byte per element (needs kv_dtype = LFPS_BF16, which then
+                          describes V).  The values are used as they are; a dequantisation scale is the caller's to
+                          fold into q. */
+  int32_t v_fp8;       /* 1: V is stored as OCP FP8 E4M3 as well (needs kv_dtype = LFPS_BF16; a scale of V is a factor
+                          on the output rows and the caller's to apply) */
 } lfps_config;
 
 /* View of the KV cache.  The struct itself is host memory; k, v, seq_lens and block_table are device
@@ -77,7 +80,7 @@ typedef struct {
  * Contiguous cache (block_table == NULL): element (b, g, i, c) of K is
  *   k[b*stride_b + g*stride_h + i*stride_n + c]
  * (strides in elements, stride_n >= D, rows 16-byte aligned), same for v.  K and V share the element
- * strides also when K is FP8 (cfg.k_fp8): then a K element is one byte and a V element two.
+ * strides also when only one of them is FP8 (cfg.k_fp8, cfg.v_fp8): an FP8 element is one byte.
  *
  * Paged cache (block_table != NULL): k and v are pools of n_blocks blocks of block_size rows, and
  * block_table[b*block_table_stride + i/block_size] names the block that holds row i of request b:

@@ -32,7 +32,8 @@ class lfps_config(ctypes.Structure):
     _fields_ = [(n, ctypes.c_int32) for n in (
         "batch", "n_q_heads", "n_kv_heads", "head_dim", "kv_dtype", "max_seq_len", "max_k",
         "radius", "n_recent", "n_sink", "cand_cap", "device", "table_mode")] + [
-        ("table_decay", ctypes.c_float), ("table_a", ctypes.c_float), ("k_fp8", ctypes.c_int32)]
+        ("table_decay", ctypes.c_float), ("table_a", ctypes.c_float), ("k_fp8", ctypes.c_int32),
+        ("v_fp8", ctypes.c_int32)]
 
 
 class lfps_kv(ctypes.Structure):
@@ -135,13 +136,15 @@ class Lfps:
     def __init__(self, batch: int, n_q_heads: int = 32, n_kv_heads: int = 8, head_dim: int = 128,
                  kv_dtype: str = "bf16", max_seq_len: int = 0, max_k: int = 0, radius: int = 0,
                  n_recent: int = 1, n_sink: int = 0, cand_cap: int = 0, device: int = 0,
-                 table_mode: bool = False, table_decay: float = 0.95, table_a: float = 0.2, k_fp8: bool = False):
+                 table_mode: bool = False, table_decay: float = 0.95, table_a: float = 0.2, k_fp8: bool = False,
+                 v_fp8: bool = False):
         self.cfg = lfps_config(batch, n_q_heads, n_kv_heads, head_dim,
                                LFPS_BF16 if kv_dtype == "bf16" else LFPS_F32, max_seq_len, max_k,
                                radius, n_recent, n_sink, cand_cap, device, int(bool(table_mode)),
-                               float(table_decay), float(table_a), int(bool(k_fp8)))
+                               float(table_decay), float(table_a), int(bool(k_fp8)), int(bool(v_fp8)))
         self.kv_torch_dtype = torch.bfloat16 if kv_dtype == "bf16" else torch.float32
         self.k_torch_dtype = torch.float8_e4m3fn if k_fp8 else self.kv_torch_dtype
+        self.v_torch_dtype = torch.float8_e4m3fn if v_fp8 else self.kv_torch_dtype
         self.device = torch.device("cuda", device)
         self._ctx = ctypes.c_void_p(None)
         rc = _lib.lfps_create(ctypes.byref(self.cfg), ctypes.byref(self._ctx))
@@ -175,7 +178,7 @@ class Lfps:
         for name, t in (("K", K), ("V", V)):
             if t is None:
                 continue
-            want = self.k_torch_dtype if name == "K" else self.kv_torch_dtype
+            want = self.k_torch_dtype if name == "K" else self.v_torch_dtype
             if not t.is_cuda or t.dtype != want or t.dim() != 4:
                 raise TypeError(f"{name}: expected a 4-d {want} tensor on the GPU")
             if t.shape[0] != self.B or t.shape[1] != self.Hkv or t.shape[3] != self.D or t.stride(3) != 1:
@@ -198,7 +201,7 @@ class Lfps:
         for name, t in (("K", K), ("V", V)):
             if t is None:
                 continue
-            want = self.k_torch_dtype if name == "K" else self.kv_torch_dtype
+            want = self.k_torch_dtype if name == "K" else self.v_torch_dtype
             if not t.is_cuda or t.dtype != want or t.dim() != 4:
                 raise TypeError(f"{name}: expected a 4-d {want} tensor on the GPU")
             if t.shape[1] != self.Hkv or t.shape[3] != self.D or t.stride(3) != 1:

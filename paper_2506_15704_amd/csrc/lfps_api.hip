@@ -96,6 +96,8 @@ int check_config(const lfps_config* c, Sizes* z, char* err, size_t errn) {
   }
   if (c->k_fp8 != 0 && c->k_fp8 != 1) BAD("k_fp8 must be 0 or 1");
   if (c->k_fp8 && c->kv_dtype != LFPS_BF16) BAD("k_fp8 needs kv_dtype = LFPS_BF16 (FP8 keys beside bf16 values)");
+  if (c->v_fp8 != 0 && c->v_fp8 != 1) BAD("v_fp8 must be 0 or 1");
+  if (c->v_fp8 && c->kv_dtype != LFPS_BF16) BAD("v_fp8 needs kv_dtype = LFPS_BF16");
 #undef BAD
   // LDS of the candidate kernel: one bit per position beside 64 KB of staging, 160 KB per workgroup
   if (((int64_t)c->max_seq_len + 31) / 32 * 4 > 88 * 1024) {
@@ -151,7 +153,7 @@ int check_kv(lfps_ctx* ctx, const lfps_kv* kv, bool need_v, KvView* out) {
   if (need_v && !kv->v) return fail(ctx, LFPS_EINVAL, "kv->v is NULL");
   if (!kv->seq_lens) return fail(ctx, LFPS_EINVAL, "kv->seq_lens is NULL");
   // the strides are shared by K and V: with one-byte K elements the K rows set the alignment
-  const int esz = ctx->cfg.k_fp8 ? 1 : (ctx->cfg.kv_dtype == LFPS_BF16 ? 2 : 4);
+  const int esz = (ctx->cfg.k_fp8 || ctx->cfg.v_fp8) ? 1 : (ctx->cfg.kv_dtype == LFPS_BF16 ? 2 : 4);
   if (kv->stride_n < kD || kv->stride_b < 0 || kv->stride_h < 0)
     return fail(ctx, LFPS_EINVAL, "kv strides: stride_n must be >= head_dim, stride_b/stride_h >= 0");
   if ((kv->stride_n * esz) % 16 || (kv->stride_b * esz) % 16 || (kv->stride_h * esz) % 16 ||
@@ -162,6 +164,7 @@ int check_kv(lfps_ctx* ctx, const lfps_kv* kv, bool need_v, KvView* out) {
   out->seq_lens = kv->seq_lens;
   out->page = KvPage{nullptr, 0, 0, 0};
   out->k_fp8 = ctx->cfg.k_fp8 != 0;
+  out->v_fp8 = ctx->cfg.v_fp8 != 0;
   if (kv->block_table) {
     const int64_t bs = kv->block_size;
     if (bs < 1 || bs > 65536 || (bs & (bs - 1)))

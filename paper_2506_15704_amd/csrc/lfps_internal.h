@@ -28,7 +28,8 @@ struct KvView {
   int64_t stride_b, stride_h, stride_n;
   const int32_t* seq_lens;
   KvPage page;
-  bool k_fp8;   // K elements are one byte (OCP FP8 E4M3); V keeps the cache dtype
+  bool k_fp8;   // K elements are one byte (OCP FP8 E4M3)
+  bool v_fp8;   // V elements are one byte; otherwise V has the cache dtype
 };
 
 // Row addressing of the two cache layouts, chosen at compile time.  A logical row i of request b

@@ -730,9 +730,15 @@ hipError_t launch_prior_means(const Shape& s, int dtype, const KvView& kv, float
                      (const KTYPE*)kv.k, (const TYPE*)kv.v, kv.stride_b, kv.stride_h, kv.stride_n, kv.page,         \
                      kv.seq_lens, kbar, vbar)
   const bool paged = kv.page.table != nullptr;
-  if (dtype == LFPS_BF16 && kv.k_fp8) {
+  if (dtype == LFPS_BF16 && kv.k_fp8 && kv.v_fp8) {
+    if (paged) LFPS_LAUNCH_PM(uint8_t, uint8_t, true);
+    else LFPS_LAUNCH_PM(uint8_t, uint8_t, false);
+  } else if (dtype == LFPS_BF16 && kv.k_fp8) {
     if (paged) LFPS_LAUNCH_PM(uint8_t, uint16_t, true);
     else LFPS_LAUNCH_PM(uint8_t, uint16_t, false);
+  } else if (dtype == LFPS_BF16 && kv.v_fp8) {
+    if (paged) LFPS_LAUNCH_PM(uint16_t, uint8_t, true);
+    else LFPS_LAUNCH_PM(uint16_t, uint8_t, false);
   } else if (dtype == LFPS_BF16) {
     if (paged) LFPS_LAUNCH_PM(uint16_t, uint16_t, true);
     else LFPS_LAUNCH_PM(uint16_t, uint16_t, false);

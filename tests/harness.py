@@ -63,7 +63,7 @@ class DeviceCase:
         s = self.spec
         args = dict(batch=s.B, n_q_heads=s.Hq, n_kv_heads=s.Hkv, head_dim=s.D, kv_dtype=s.kv_dtype,
                     max_seq_len=self.case.Lcap, max_k=self.case.kmax, radius=s.r, n_recent=1, n_sink=0,
-                    k_fp8=s.k_dtype == "fp8")
+                    k_fp8=s.k_dtype == "fp8", v_fp8=s.v_dtype == "fp8")
         args.update(kw)
         return Lfps(**args)
 

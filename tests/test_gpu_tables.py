@@ -206,11 +206,12 @@ def test_many_updates_cross_the_renormalisation():
     ctx.close()
 
 
-@pytest.fixture(scope="module", params=["bf16", "fp8"])
+@pytest.fixture(scope="module", params=["bf16", "fp8", "fp8kv"])
 def table_case(request):
-    """bf16 cache, and the same workload with FP8 (E4M3) keys beside bf16 values."""
+    """bf16 cache, the same workload with FP8 (E4M3) keys beside bf16 values, and with FP8 keys and values."""
     return DeviceCase(gen.tiny_spec("tables_" + request.param, B=2, L=1800, k=64, r=1, T=6,
-                                    k_dtype="fp8" if request.param == "fp8" else ""))
+                                    k_dtype="fp8" if request.param != "bf16" else "",
+                                    v_dtype="fp8" if request.param == "fp8kv" else ""))
 
 
 def _softmax64(s):
