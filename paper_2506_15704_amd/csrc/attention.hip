@@ -82,29 +82,53 @@ __global__ __launch_bounds__(kSparseWaves * 64) void k_sparse_attn(Shape s, cons
   const T* Vbg = V + Rows::base(b, g, stride_b, stride_h) + 8 * j;
   float acc[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
   float l = 0.f;
-  for (int base = r0; base < r1; base += 64) {
-    int my_row = -1;
-    float my_p = 0.f;
-    if (base == r0) {
-      my_row = first_row;
-      my_p = my_row >= 0 ? __expf(first_s - m) : 0.f;
-    } else if (base + lane < r1) {
-      const int r = ih[base + lane];
-      if (r >= 0 && r < n) {
-        my_row = Rows::phys(pg, b, r);
-        my_p = __expf(sh[base + lane] - m);
-      }
+  // A tile = 64 entries of the list, one per lane (row, weight); the entries of the next tile are fetched
+  // before the rows of the current one.  The rows of a tile are read in two batches of eight loads per lane
+  // (32 rows per wave), every load of a batch issued before the first is used: the compiler, left alone,
+  // orders one load ahead of its use and the loop becomes a chain of single memory round trips.
+  constexpr int kBatch = 8;
+  auto entry = [&](int i, int& row, float& sv) {          // list entry i of my lane: physical row or -1, score
+    row = -1;
+    sv = 0.f;
+    if (i < r1) {
+      const int r = ih[i];
+      sv = sh[i];
+      if (r >= 0 && r < n) row = Rows::phys(pg, b, r);
     }
+  };
+  int next_row = -1;
+  float next_s = 0.f;
+  if (r0 + 64 < r1) entry(r0 + 64 + lane, next_row, next_s);
+  int my_row = first_row;
+  float my_p = my_row >= 0 ? __expf(first_s - m) : 0.f;
+  for (int base = r0; base < r1; base += 64) {
     l += my_p;
+    const int cur_row = my_row;
+    const float cur_p = my_p;
+    my_row = next_row;                                      // becomes current at the next trip
+    my_p = my_row >= 0 ? __expf(next_s - m) : 0.f;
+    if (base + 128 < r1) entry(base + 128 + lane, next_row, next_s);
+    else next_row = -1;
 #pragma unroll
-    for (int t = 0; t < 16; ++t) {
-      const int row = __shfl(my_row, 4 * t + rs);
-      float p = __shfl(my_p, 4 * t + rs);
-      float x[8];
-      load8(Vbg + Rows::offset(pg, row < 0 ? 0 : row, stride_b, stride_n), x);
-      p = row < 0 ? 0.f : p;
+    for (int half = 0; half < 16 / kBatch; ++half) {
+      Raw8<T> rw[kBatch];
+      float pw[kBatch];
 #pragma unroll
-      for (int c = 0; c < 8; ++c) acc[c] = fmaf(p, x[c], acc[c]);
+      for (int u = 0; u < kBatch; ++u) {
+        const int t = half * kBatch + u;
+        const int row = __shfl(cur_row, 4 * t + rs);
+        const float p = __shfl(cur_p, 4 * t + rs);
+        rw[u].load(Vbg + Rows::offset(pg, row < 0 ? 0 : row, stride_b, stride_n));
+        pw[u] = row < 0 ? 0.f : p;
+      }
+      __builtin_amdgcn_sched_barrier(0);                    // keep the batch's loads ahead of its arithmetic
+#pragma unroll
+      for (int u = 0; u < kBatch; ++u) {
+        float x[8];
+        rw[u].get(x);
+#pragma unroll
+        for (int c = 0; c < 8; ++c) acc[c] = fmaf(pw[u], x[c], acc[c]);
+      }
     }
   }
 #pragma unroll
@@ -146,9 +170,9 @@ static hipError_t launch_sparse_t(const Shape& s, const KvView& kv, const int32_
   } else {                              \
     LFPS_LAUNCH_SPARSE_P(NW, false);    \
   }
-  if (heads * 16 <= 8192) {
+  if (heads * 16 <= 4096) {
     LFPS_LAUNCH_SPARSE(16)
-  } else if (heads * 8 <= 8192) {
+  } else if (heads * 8 <= 4096) {
     LFPS_LAUNCH_SPARSE(8)
   } else {
     LFPS_LAUNCH_SPARSE(4)
