@@ -87,7 +87,8 @@ typedef struct {
  *   k[block*stride_b + g*stride_h + (i % block_size)*stride_n + c]
  * so stride_b is the distance between blocks.  block_size is a power of two in [1, 65536];
  * block_table_stride*block_size >= max_seq_len; n_blocks*block_size < 2^31.  Table entries are
- * read by the kernels and clamped into [0, n_blocks); only the entries of rows below n_b are read.
+ * read by the kernels and clamped into [0, n_blocks); only the entries of rows below n_b are read,
+ * and the first entry of every request (padding slots read row 0, also when n_b = 0).
  * The method itself (positions, candidates, Top-k indices) always speaks in logical rows i. */
 typedef struct {
   const void* k;
