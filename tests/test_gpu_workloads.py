@@ -8,7 +8,8 @@ import torch
 
 import bench
 from oracle import lfps_oracle as orc
-from tests.harness import assert_out_close, assert_scores_close, assert_topk_equal_mod_ties
+import gen
+from tests.harness import DEV, DeviceCase, assert_out_close, assert_scores_close, assert_topk_equal_mod_ties, valid_row
 
 pytestmark = pytest.mark.gpu
 
@@ -217,3 +218,86 @@ def test_score_table_mode_at_full_size_on_sampled_groups(name):
                     assert_tables_close(es[b, h, :m].cpu().numpy(), ws[:m], old_s, half, f"{name} slash t{t} b{b} h{h}")
     finally:
         r.close()
+
+
+def test_largest_supported_context():
+    """max_seq_len at the capacity of the candidate bitmap (720 896 rows): one KV group, seeded by the exact
+    Top-k, then chained steps (the second and third through the score filter) and one score-table step,
+    against the oracle."""
+    import time
+    from oracle import lfps_tables_oracle as tor
+    Lcap = 88 * 1024 * 8
+    T = 3
+    spec = gen.tiny_spec("maxlen", B=1, L=Lcap - T, k=2048, r=4, T=T, Hq=4, Hkv=1, n_hot=16, recency=64)
+    dc = DeviceCase(spec)
+    case = dc.case
+    assert case.Lcap == Lcap
+    from paper_2506_15704_amd.binding import LfpsError, workspace_bytes
+    with pytest.raises(LfpsError):
+        workspace_bytes(batch=1, n_q_heads=4, n_kv_heads=1, head_dim=128, kv_dtype=1, max_seq_len=Lcap + 1, max_k=2048,
+                        radius=4, n_recent=1, n_sink=0, cand_cap=0, device=0)
+    ctx = dc.make_ctx()
+    # the oracle's inputs: every K row (regenerated on the CPU in chunks), V rows only where they are read
+    K = np.empty((Lcap, spec.D), dtype=np.float32)
+    for r0 in range(0, Lcap, 65536):
+        rows = np.arange(r0, min(Lcap, r0 + 65536))
+        K[r0:r0 + len(rows)] = case.kv_rows("k", 0, 0, rows)[0]
+    V = np.zeros((Lcap, spec.D), dtype=np.float32)
+
+    def need_v(rows):
+        rows = np.unique(np.asarray(rows).ravel())
+        rows = rows[(rows >= 0) & (rows < Lcap)]
+        V[rows] = case.kv_rows("v", 0, 0, rows)[0]
+
+    shp = (1, 4, case.kmax)
+    prev = torch.zeros(shp, dtype=torch.int32, device=DEV)
+    ctx.lfps_exact_topk(dc.q(0), ctx.kv_view(dc.K, dc.V, dc.seq_lens(0)), dc.k, prev)
+    p0 = prev.cpu().numpy()
+    I, _ = orc.exact_topk(case.q[0, 0, 2], K, int(case.seq_lens0[0]), 2048)        # one head: 720 896 fp64 dot products
+    assert_topk_equal_mod_ties(p0[0, 2], I, lambda p: orc.scores(case.q[0, 0, 2], K, p), 2048, "exact h2")
+    for t in range(1, T + 1):
+        idx = torch.zeros(shp, dtype=torch.int32, device=DEV)
+        out = torch.zeros((1, 4, spec.D), dtype=torch.float32, device=DEV)
+        ctx.lfps_step(dc.q(t), ctx.kv_view(dc.K, dc.V, dc.seq_lens(t)), prev, dc.k, idx, out)
+        assert ctx.lfps_poll_status() == 0
+        p_h, i_h, o_h = prev.cpu().numpy(), idx.cpu().numpy(), out.cpu().numpy()
+        n = int(case.seq_lens(t)[0])
+        cand_rows = np.unique(np.concatenate([p_h[0, h][:, None] + np.arange(-spec.r, spec.r + 2)[None, :] for h in range(4)]))
+        need_v(np.concatenate([cand_rows, [n - 1], i_h.ravel()]))
+        res = orc.lfps_step(case.q[t, 0], K, V, [p_h[0, h] for h in range(4)], n, 2048, spec.r, 1, 0)
+        for h in range(4):
+            assert_topk_equal_mod_ties(i_h[0, h], res["topk_idx"][h], lambda p: orc.scores(case.q[t, 0, h], K, p), 2048,
+                                       f"t{t} h{h}")
+            assert_out_close(o_h[0, h], orc.sparse_attn(case.q[t, 0, h], K, V, i_h[0, h]), f"t{t} h{h}")
+        prev = idx
+    ctx.close()
+    # one score-table step at the same length: Eq. 4 start from the step-0 query, then a step
+    tab = dc.make_ctx(table_mode=True, table_decay=0.95, table_a=0.2, n_sink=4, n_recent=1)
+    tab.lfps_tables_init(dc.q(0), tab.kv_view(dc.K, dc.V, dc.seq_lens(0)))
+    ev = torch.zeros((1, 4, Lcap), dtype=torch.float64, device=DEV)
+    es = torch.zeros_like(ev)
+    tab.lfps_tables_export(ev, es, dc.seq_lens(0))
+    t64 = [(ev[0, h].cpu().numpy(), es[0, h].cpu().numpy()) for h in range(4)]
+    idx = torch.zeros(shp, dtype=torch.int32, device=DEV)
+    out = torch.zeros((1, 4, spec.D), dtype=torch.float32, device=DEV)
+    cnt = torch.zeros((1, 1), dtype=torch.int32, device=DEV)
+    cand = torch.zeros((1, 1, tab.cand_cap), dtype=torch.int32, device=DEV)
+    tab.lfps_table_candidates(dc.seq_lens(1), cand, cnt)
+    tab.lfps_table_step(dc.q(1), tab.kv_view(dc.K, dc.V, dc.seq_lens(1)), dc.k, idx, out)
+    n1 = int(case.seq_lens(1)[0])
+    i_h, o_h = idx.cpu().numpy(), out.cpu().numpy()
+    need_v(i_h)
+    cand_o = tor.group_candidates(t64, n1, 0.2, spec.r, 1, 4)
+    cand_d = cand[0, 0, : int(cnt[0, 0])].cpu().numpy()
+    diff = np.setxor1d(cand_d, cand_o)
+    assert len(diff) <= max(4, len(cand_o) // 1000), (len(diff), len(cand_o))   # entries within rounding of a threshold or mean
+    for h in range(4):
+        got = valid_row(i_h[0, h])
+        if len(diff) == 0:
+            s_o = orc.scores(case.q[1, 0, h], K, cand_o)
+            ksel = min(2048, len(cand_o))
+            want = cand_o[np.argsort(-s_o, kind="stable")[:ksel]]
+            assert_topk_equal_mod_ties(got, want, lambda p: orc.scores(case.q[1, 0, h], K, p), ksel, f"table step h{h}")
+        assert_out_close(o_h[0, h], orc.sparse_attn(case.q[1, 0, h], K, V, got), f"table step h{h}")
+    assert tab.lfps_poll_status() == 0
+    tab.close()
