@@ -577,6 +577,9 @@ def main():
         "speedup_vs_exact_topk": main_res.get("speedup_vs_exact_topk"),
         "speedup_vs_full_attn": main_res.get("speedup_vs_full_attn"),
     }
+    # the paper's own figures (its Sec. 5: indexing on one Xeon Gold 6430 core, attention on an RTX 4090): context only
+    line["paper_context"] = {"speedup_vs_full_attention": 22.8, "speedup_vs_exact_topk": 9.6,
+                             "note": "other hardware and a trained model's attention; not a target for this metric"}
     if not args.no_table_mode:
         tab = measure_tables(args.workload, args.steps, args.warmup)
         tab["speedup_vs_memoryless_step"] = round(main_res["ms_per_step"] / tab["ms_per_step"], 3)
