@@ -91,8 +91,8 @@ def test_every_entry_point_is_bit_identical_to_the_contiguous_cache(cases, dtype
 @pytest.mark.parametrize("dtype,block_size,layout", LAYOUTS[:3] + LAYOUTS[5:6] + LAYOUTS[7:8])
 def test_chained_steps_paged_equal_contiguous_and_oracle(cases, dtype, block_size, layout):
     """Free-running lfps_step chains (filtered scoring from the second step on) over both layouts give the
-    same Top-k and outputs at every step; the last step is checked against the oracle given the device's
-    own previous Top-k."""
+    same Top-k and outputs at every step; one more step on the paged view, started from the oracle's exact
+    Top-k, is checked against the oracle."""
     dc = cases[dtype]
     spec, case = dc.spec, dc.case
     Kp, Vp, table = gen_device.paginate(dc.K, dc.V, block_size, seed=11, layout=layout)
@@ -113,21 +113,29 @@ def test_chained_steps_paged_equal_contiguous_and_oracle(cases, dtype, block_siz
     for t, (a, b_) in enumerate(zip(runs["flat"], runs["paged"]), start=1):
         for what, x, y in zip(("prev", "idx", "score", "out"), a, b_):
             assert torch.equal(x, y), f"step {t}: {what} differs between the two layouts"
-    t = spec.T
-    prev, idx, _sc, out = (x.cpu().numpy() for x in runs["paged"][-1])
-    n = case.seq_lens(t)
+    # one teacher-forced step on the paged view against the oracle: the oracle's exact Top-k of step 0 is the history
+    ctx = dc.make_ctx()
     G = spec.G
-    for b in range(spec.B):
+    groups = [(b, g) for b in range(spec.B) for g in (0, spec.Hkv - 1)]
+    prev = np.full((spec.B, spec.Hq, case.kmax), -1, dtype=np.int32)
+    for (b, g) in groups:
+        K, _ = dc.group(b, g)
+        for h in range(G * g, G * g + G):
+            prev[b, h, : int(case.k[b])] = orc.exact_topk(case.q[0, b, h], K, int(case.seq_lens0[b]), int(case.k[b]))[0]
+    idx, sc, out = _bufs(dc)
+    ctx.lfps_step(dc.q(1), ctx.paged_kv_view(Kp, Vp, table, dc.seq_lens(1)), dev(prev), dc.k, idx, out, sc)
+    idx, out = idx.cpu().numpy(), out.cpu().numpy()
+    n = case.seq_lens(1)
+    for (b, g) in groups:
         kb = int(case.k[b])
-        for g in (0, spec.Hkv - 1):
-            K, V = dc.group(b, g)
-            res = orc.lfps_step(case.q[t, b, G * g: G * g + G], K, V,
-                                [valid_row(prev[b, G * g + h, :kb]) for h in range(G)], int(n[b]), kb, spec.r, 1, 0)
-            for hh in range(G):
-                h = G * g + hh
-                assert_topk_equal_mod_ties(idx[b, h, :kb], res["topk_idx"][hh],
-                                           lambda p: orc.scores(case.q[t, b, h], K, p), kb, f"paged step b{b} h{h}")
-                assert_out_close(out[b, h], orc.sparse_attn(case.q[t, b, h], K, V, idx[b, h, :kb]), f"paged out b{b} h{h}")
+        K, V = dc.group(b, g)
+        res = orc.lfps_step(case.q[1, b, G * g: G * g + G], K, V, [prev[b, G * g + h, :kb] for h in range(G)],
+                            int(n[b]), kb, spec.r, 1, 0)
+        for hh in range(G):
+            h = G * g + hh
+            assert_topk_equal_mod_ties(idx[b, h, :kb], res["topk_idx"][hh],
+                                       lambda p: orc.scores(case.q[1, b, h], K, p), kb, f"paged step b{b} h{h}")
+            assert_out_close(out[b, h], orc.sparse_attn(case.q[1, b, h], K, V, idx[b, h, :kb]), f"paged out b{b} h{h}")
 
 
 def test_table_mode_and_bypass_paged_equal_contiguous(cases):

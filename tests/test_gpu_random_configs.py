@@ -1,8 +1,8 @@
 """Seeded random configurations of the chained step: head grouping, batch, ragged lengths, per-request
 budgets, radius, always-present rows, cache dtype (bf16 / fp32 / FP8 keys / FP8 keys and values) and layout (contiguous / paged)
-drawn together, so that combinations no hand-written case names are exercised.  Every step is checked
-against the CPU oracle given the device's own previous Top-k (candidate counts exactly; Top-k, scores and
-outputs by the rules of tests/harness.py)."""
+drawn together, so that combinations no hand-written case names are exercised.  Teacher-forced: every step
+the device starts from the oracle's previous Top-k and is checked against the oracle's step (candidate counts
+exactly; Top-k, scores and outputs by the rules of tests/harness.py)."""
 import numpy as np
 import pytest
 import torch
@@ -51,25 +51,38 @@ def test_random_configuration_chained_steps(i):
         view = lambda t: ctx.kv_view(dc.K, dc.V, dc.seq_lens(t))
     k_dev = dev(c["k"])
     shp = (spec.B, spec.Hq, case.kmax)
-    prev = torch.full(shp, -1, dtype=torch.int32, device=DEV)
-    ctx.lfps_exact_topk(dc.q(0), view(0), k_dev, prev)
     what = f"config {i}: {c}"
+    # the seeding step: the oracle's exact Top-k is the history the device is given (teacher forcing: at every
+    # step the device starts from the oracle's previous Top-k, never the other way round)
+    seed_dev = torch.full(shp, -1, dtype=torch.int32, device=DEV)
+    ctx.lfps_exact_topk(dc.q(0), view(0), k_dev, seed_dev)
+    seed_h = seed_dev.cpu().numpy()
+    prev = np.full(shp, -1, dtype=np.int32)
+    for b in range(spec.B):
+        kb, nb = int(c["k"][b]), int(case.seq_lens0[b])
+        for h in range(spec.Hq):
+            K, _ = dc.group(b, h // G)
+            I, _ = orc.exact_topk(case.q[0, b, h], K, nb, kb)
+            assert_topk_equal_mod_ties(seed_h[b, h, :kb], I, lambda p: orc.scores(case.q[0, b, h], K, p), kb,
+                                       f"{what}: exact Top-k b{b} h{h}")
+            prev[b, h, :kb] = I
     for t in range(1, T + 1):
         idx = torch.full(shp, -9, dtype=torch.int32, device=DEV)
         sc = torch.zeros(shp, dtype=torch.float32, device=DEV)
         out = torch.full((spec.B, spec.Hq, spec.D), 7.0, dtype=torch.float32, device=DEV)
         cnt = torch.zeros((spec.B, spec.Hkv), dtype=torch.int32, device=DEV)
-        ctx.lfps_step(dc.q(t), view(t), prev, k_dev, idx, out, sc)
+        ctx.lfps_step(dc.q(t), view(t), dev(prev), k_dev, idx, out, sc)
         ctx.lfps_copy_cand_count(cnt)
         assert ctx.lfps_poll_status() == 0, what
-        p_h, i_h, s_h, o_h, c_h = (x.cpu().numpy() for x in (prev, idx, sc, out, cnt))
+        i_h, s_h, o_h, c_h = (x.cpu().numpy() for x in (idx, sc, out, cnt))
         n = case.seq_lens(t)
+        nxt = np.full(shp, -1, dtype=np.int32)
         for b in range(spec.B):
             kb, nb = int(c["k"][b]), int(n[b])
             for g in range(spec.Hkv):
                 K, V = dc.group(b, g)
                 res = orc.lfps_step(case.q[t, b, G * g: G * g + G], K, V,
-                                    [valid_row(p_h[b, G * g + h, :kb]) for h in range(G)], nb, kb, spec.r,
+                                    [valid_row(prev[b, G * g + h, :kb]) for h in range(G)], nb, kb, spec.r,
                                     c["n_recent"], c["n_sink"])
                 assert c_h[b, g] == len(res["cand"]), f"{what}: t{t} b{b} g{g} candidate count"
                 ksel = min(kb, len(res["cand"]))
@@ -82,5 +95,6 @@ def test_random_configuration_chained_steps(i):
                                                ksel, f"{what}: t{t} b{b} h{h}")
                     assert_scores_close(s_h[b, h, :ksel], orc.scores(case.q[t, b, h], K, got), f"{what}: scores")
                     assert_out_close(o_h[b, h], orc.sparse_attn(case.q[t, b, h], K, V, got), f"{what}: t{t} b{b} h{h}")
-        prev = idx
+                    nxt[b, h, :ksel] = res["topk_idx"][hh]
+        prev = nxt
     ctx.close()

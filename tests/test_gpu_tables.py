@@ -278,6 +278,10 @@ def _teacher_forced_table_steps(dc, view, gamma, a, n_sink, n_recent, groups, st
             nd = _assert_candidates(c_[b, g, : cn_[b, g]], res["cand"], t64, nb, a, r, n_sink, f"t={t} b={b} g={g}")
             if exact_cands:
                 assert nd == 0, "sampled groups are expected to match exactly"
+            mm = min(nb + 1, case.Lcap)
+            for h in range(s.G):                         # teacher forcing: the next step starts from the oracle's tables
+                new_ver[b, s.G * g + h, :mm] = res["tables"][h][0][:mm]
+                new_sla[b, s.G * g + h, :mm] = res["tables"][h][1][:mm]
             if nd:
                 continue                                 # a different (band-explained) candidate set: nothing further to compare
             for h in range(s.G):
@@ -357,10 +361,16 @@ def test_table_step_free_running_from_init(table_case):
     ctx.lfps_tables_init(dc.q(0), ctx.kv_view(dc.K, dc.V, dc.seq_lens(0)))
     ev = torch.zeros((s.B, s.Hq, case.Lcap), dtype=torch.float64, device=DEV)
     es = torch.zeros_like(ev)
-    ctx.lfps_tables_export(ev, es, dc.seq_lens(0))
     b, g = 1, 2
     K, V = dc.group(b, g)
-    t64 = [(ev[b, s.G * g + h].cpu().numpy(), es[b, s.G * g + h].cpu().numpy()) for h in range(s.G)]
+    n0 = int(case.seq_lens0[b])
+    t64 = []                                 # the oracle's own Eq. 4 start for the sampled group
+    for h in range(s.G):
+        sc0 = orc.scores(case.q[0, b, s.G * g + h], K[:n0])
+        w = np.zeros(n0)
+        w[n_sink:] = _softmax64(sc0[n_sink:])
+        ver0, sla0 = tor.init_tables(w[None, :], gamma, n_sink)
+        t64.append((np.r_[ver0, np.zeros(case.Lcap - n0)], np.r_[sla0, np.zeros(case.Lcap - n0)]))
     idx = torch.zeros((s.B, s.Hq, case.kmax), dtype=torch.int32, device=DEV)
     out = torch.zeros((s.B, s.Hq, s.D), dtype=torch.float32, device=DEV)
     cand = torch.zeros((s.B, s.Hkv, ctx.cand_cap), dtype=torch.int32, device=DEV)

@@ -9,7 +9,7 @@ import torch
 import bench
 from oracle import lfps_oracle as orc
 import gen
-from tests.harness import DEV, DeviceCase, assert_out_close, assert_scores_close, assert_topk_equal_mod_ties, valid_row
+from tests.harness import DEV, DeviceCase, assert_out_close, assert_scores_close, assert_topk_equal_mod_ties, dev, valid_row
 
 pytestmark = pytest.mark.gpu
 
@@ -250,17 +250,20 @@ def test_largest_supported_context():
         V[rows] = case.kv_rows("v", 0, 0, rows)[0]
 
     shp = (1, 4, case.kmax)
-    prev = torch.zeros(shp, dtype=torch.int32, device=DEV)
-    ctx.lfps_exact_topk(dc.q(0), ctx.kv_view(dc.K, dc.V, dc.seq_lens(0)), dc.k, prev)
-    p0 = prev.cpu().numpy()
-    I, _ = orc.exact_topk(case.q[0, 0, 2], K, int(case.seq_lens0[0]), 2048)        # one head: 720 896 fp64 dot products
-    assert_topk_equal_mod_ties(p0[0, 2], I, lambda p: orc.scores(case.q[0, 0, 2], K, p), 2048, "exact h2")
+    seed = torch.zeros(shp, dtype=torch.int32, device=DEV)
+    ctx.lfps_exact_topk(dc.q(0), ctx.kv_view(dc.K, dc.V, dc.seq_lens(0)), dc.k, seed)
+    p0 = seed.cpu().numpy()
+    p_h = np.zeros(shp, dtype=np.int32)                   # the oracle's Top-k: the history the device is given
+    for h in range(4):                                    # 720 896 fp64 dot products per head
+        I, _ = orc.exact_topk(case.q[0, 0, h], K, int(case.seq_lens0[0]), 2048)
+        assert_topk_equal_mod_ties(p0[0, h], I, lambda p: orc.scores(case.q[0, 0, h], K, p), 2048, f"exact h{h}")
+        p_h[0, h] = I
     for t in range(1, T + 1):
         idx = torch.zeros(shp, dtype=torch.int32, device=DEV)
         out = torch.zeros((1, 4, spec.D), dtype=torch.float32, device=DEV)
-        ctx.lfps_step(dc.q(t), ctx.kv_view(dc.K, dc.V, dc.seq_lens(t)), prev, dc.k, idx, out)
+        ctx.lfps_step(dc.q(t), ctx.kv_view(dc.K, dc.V, dc.seq_lens(t)), dev(p_h), dc.k, idx, out)
         assert ctx.lfps_poll_status() == 0
-        p_h, i_h, o_h = prev.cpu().numpy(), idx.cpu().numpy(), out.cpu().numpy()
+        i_h, o_h = idx.cpu().numpy(), out.cpu().numpy()
         n = int(case.seq_lens(t)[0])
         cand_rows = np.unique(np.concatenate([p_h[0, h][:, None] + np.arange(-spec.r, spec.r + 2)[None, :] for h in range(4)]))
         need_v(np.concatenate([cand_rows, [n - 1], i_h.ravel()]))
@@ -269,15 +272,23 @@ def test_largest_supported_context():
             assert_topk_equal_mod_ties(i_h[0, h], res["topk_idx"][h], lambda p: orc.scores(case.q[t, 0, h], K, p), 2048,
                                        f"t{t} h{h}")
             assert_out_close(o_h[0, h], orc.sparse_attn(case.q[t, 0, h], K, V, i_h[0, h]), f"t{t} h{h}")
-        prev = idx
+        p_h = np.stack(res["topk_idx"])[None].astype(np.int32)
     ctx.close()
-    # one score-table step at the same length: Eq. 4 start from the step-0 query, then a step
+    # one score-table step at the same length: Eq. 4 start from the step-0 query (the oracle's tables for the
+    # expectation, the device's own for the device), then a step
     tab = dc.make_ctx(table_mode=True, table_decay=0.95, table_a=0.2, n_sink=4, n_recent=1)
     tab.lfps_tables_init(dc.q(0), tab.kv_view(dc.K, dc.V, dc.seq_lens(0)))
-    ev = torch.zeros((1, 4, Lcap), dtype=torch.float64, device=DEV)
-    es = torch.zeros_like(ev)
-    tab.lfps_tables_export(ev, es, dc.seq_lens(0))
-    t64 = [(ev[0, h].cpu().numpy(), es[0, h].cpu().numpy()) for h in range(4)]
+    n0 = int(case.seq_lens0[0])
+    t64 = []
+    for h in range(4):
+        sc0 = orc.scores(case.q[0, 0, h], K[:n0])
+        w = np.zeros(n0)
+        e = np.exp(sc0[4:] - sc0[4:].max())
+        w[4:] = e / e.sum()                                  # attention weights of the query over the non-sink rows
+        # Eq. 4 with one query: both tables hold w / (2 (1 - gamma)) (written out; the oracle's loop form is
+        # checked against the device at small sizes)
+        tab0 = np.r_[w / (2.0 * (1.0 - 0.95)), np.zeros(Lcap - n0)]
+        t64.append((tab0.copy(), tab0.copy()))
     idx = torch.zeros(shp, dtype=torch.int32, device=DEV)
     out = torch.zeros((1, 4, spec.D), dtype=torch.float32, device=DEV)
     cnt = torch.zeros((1, 1), dtype=torch.int32, device=DEV)
