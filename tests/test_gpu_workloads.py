@@ -152,8 +152,8 @@ def test_worst_case_candidate_count_at_full_size():
 @pytest.mark.parametrize("name", ["C2", "C4", "C5"])
 def test_score_table_mode_at_full_size_on_sampled_groups(name):
     """The score-table form (Eq. 4 start, Eq. 7-10 steps) in the configuration bench.py times: tables are
-    exported before and after every step, and for sampled (request, KV group) pairs the oracle redoes the
-    step from the exported state (so each step is compared on its own, whatever the earlier tie choices)."""
+    compared with the oracle's Eq. 4 start, and for sampled (request, KV group) pairs the oracle runs the steps
+    from its own tables, which the device is given before every step (teacher forcing)."""
     from oracle import lfps_tables_oracle as tor
     from tests.test_gpu_tables import _assert_candidates, assert_tables_close
     r = bench.Runner(name, table_mode=True, n_sink=4)
@@ -167,25 +167,44 @@ def test_score_table_mode_at_full_size_on_sampled_groups(name):
         es = torch.zeros_like(ev)
         r.ctx.lfps_tables_init(r.q[0], r.views[0])
         r.ctx.lfps_tables_export(ev, es, r.seq[0])
+        orc_tab = {}                                         # the oracle's tables of the sampled groups (fp64, per head)
         for (b, g) in samples:                               # Eq. 4 with one query
             K, _ = kv_cpu[(b, g)]
             n0 = int(case.seq_lens0[b])
-            h = G * g + 1
-            s0 = orc.scores(case.q[0, b, h], K[:n0])
-            w = np.zeros(n0)
-            e = np.exp(s0[n_sink:] - s0[n_sink:].max())
-            w[n_sink:] = e / e.sum()
-            ver, _ = tor.init_tables(w[None, :], gamma, n_sink) if n0 <= 4096 else (w / (2 * (1 - gamma)), None)
-            np.testing.assert_allclose(ev[b, h, :n0].cpu().numpy(), ver, rtol=3e-5, atol=1e-12)
+            orc_tab[(b, g)] = []
+            for hh in range(G):
+                h = G * g + hh
+                s0 = orc.scores(case.q[0, b, h], K[:n0])
+                w = np.zeros(n0)
+                e = np.exp(s0[n_sink:] - s0[n_sink:].max())
+                w[n_sink:] = e / e.sum()
+                # one query: both tables are w / (2 (1 - gamma)); the oracle's loop form is used where it is affordable
+                ver = tor.init_tables(w[None, :], gamma, n_sink)[0] if n0 <= 4096 else w / (2 * (1 - gamma))
+                np.testing.assert_allclose(ev[b, h, :n0].cpu().numpy(), ver, rtol=3e-5, atol=1e-12)
+                np.testing.assert_allclose(es[b, h, :n0].cpu().numpy(), ver, rtol=3e-5, atol=1e-12)
+                orc_tab[(b, g)].append((ver.copy(), ver.copy()))
         idx = torch.zeros_like(r.seed)
         sc = torch.zeros_like(r.sel_score)
         out = torch.zeros_like(r.out)
         cnt = torch.zeros((spec.B, spec.Hkv), dtype=torch.int32, device=r.dev)
         for t in (1, 2):
             n_t = case.seq_lens(t)
-            r.ctx.lfps_tables_export(ev, es, r.seq[t])
-            before = {(b, g): [(ev[b, G * g + hh].cpu().numpy().copy(), es[b, G * g + hh].cpu().numpy().copy())
-                               for hh in range(G)] for (b, g) in samples}
+            # Teacher forcing: the device's tables (all heads, as exported) with the sampled groups' heads replaced
+            # by the oracle's, rounded to the fp32 the device stores; the oracle continues from the same rounded values.
+            v32, s32 = ev.to(torch.float32), es.to(torch.float32)
+            before = {}
+            for (b, g) in samples:
+                before[(b, g)] = []
+                for hh in range(G):
+                    h = G * g + hh
+                    pair = []
+                    for dst, src in ((v32, orc_tab[(b, g)][hh][0]), (s32, orc_tab[(b, g)][hh][1])):
+                        row = np.zeros(case.Lcap, dtype=np.float32)
+                        row[: len(src)] = src[: case.Lcap]
+                        dst[b, h] = torch.from_numpy(row).to(r.dev)
+                        pair.append(row.astype(np.float64))
+                    before[(b, g)].append(tuple(pair))
+            r.ctx.lfps_tables_import(v32, s32, r.seq[t])
             r.ctx.lfps_table_candidates(r.seq[t], r.cand, cnt)
             r.ctx.lfps_table_step(r.q[t], r.views[t], r.k, idx, out, sc)
             assert r.ctx.lfps_poll_status() == 0
@@ -195,27 +214,29 @@ def test_score_table_mode_at_full_size_on_sampled_groups(name):
                 K, V = kv_cpu[(b, g)]
                 n, kb = int(n_t[b]), int(case.k[b])
                 t64 = before[(b, g)]
-                want = tor.group_candidates(t64, n, a, spec.r, n_recent, n_sink)
+                res = tor.table_step(case.q[t, b, G * g: G * g + G], K, V, t64, n, kb, spec.r, a, gamma, n_recent, n_sink)
+                orc_tab[(b, g)] = res["tables"]
                 got_c = r.cand[b, g, : int(cnt_h[b, g])].cpu().numpy()
-                nd = _assert_candidates(got_c, want, t64, n, a, spec.r, n_sink, f"{name} t{t} b{b} g{g}")
+                nd = _assert_candidates(got_c, res["cand"], t64, n, a, spec.r, n_sink, f"{name} t{t} b{b} g{g}")
                 assert nd <= 2
+                if nd:
+                    continue                                 # a band-explained difference in the candidate set: stop here
                 ksel = min(kb, len(got_c))
                 for hh in range(G):
                     h = G * g + hh
                     got = idx_h[b, h, :ksel]
                     assert np.all(idx_h[b, h, ksel:] == -1)
-                    s_c = orc.scores(case.q[t, b, h], K, got_c)
-                    I = got_c[np.lexsort((got_c, -s_c))[:ksel]]
-                    assert_topk_equal_mod_ties(got, I, lambda p: orc.scores(case.q[t, b, h], K, p), ksel, f"{name} t{t} b{b} h{h}")
+                    assert_topk_equal_mod_ties(got, res["topk_idx"][hh], lambda p: orc.scores(case.q[t, b, h], K, p), ksel,
+                                               f"{name} t{t} b{b} h{h}")
                     assert_out_close(out_h[b, h], orc.sparse_attn(case.q[t, b, h], K, V, got), f"{name} out t{t} b{b} h{h}")
-                    # Eq. 10 from the device's own selection
-                    wv, ws = tor.update_tables(t64[hh][0], t64[hh][1], n, got, orc.scores(case.q[t, b, h], K, got), gamma, n_sink)
-                    m = min(n + 1, case.Lcap)
-                    old_v = np.r_[gamma * t64[hh][0][:n], 0.0][:m]
-                    old_s = np.r_[0.0, gamma * t64[hh][1][:n]][:m]
-                    half = 10 * 0.5 / max(ksel - n_sink, 1)
-                    assert_tables_close(ev[b, h, :m].cpu().numpy(), wv[:m], old_v, half, f"{name} vertical t{t} b{b} h{h}")
-                    assert_tables_close(es[b, h, :m].cpu().numpy(), ws[:m], old_s, half, f"{name} slash t{t} b{b} h{h}")
+                    if set(got.tolist()) == set(res["topk_idx"][hh].tolist()):      # Eq. 10 on the same selection
+                        wv, ws = res["tables"][hh]
+                        m = min(n + 1, case.Lcap)
+                        old_v = np.r_[gamma * t64[hh][0][:n], 0.0][:m]
+                        old_s = np.r_[0.0, gamma * t64[hh][1][:n]][:m]
+                        half = 10 * 0.5 / max(ksel - n_sink, 1)
+                        assert_tables_close(ev[b, h, :m].cpu().numpy(), wv[:m], old_v, half, f"{name} vertical t{t} b{b} h{h}")
+                        assert_tables_close(es[b, h, :m].cpu().numpy(), ws[:m], old_s, half, f"{name} slash t{t} b{b} h{h}")
     finally:
         r.close()
 
