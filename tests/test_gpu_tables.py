@@ -549,10 +549,12 @@ def test_tables_init_from_several_queries_is_eq4(table_case):
     es = torch.zeros_like(ev)
     ctx.lfps_tables_export(ev, es, dc.seq_lens(0))
     ev, es = ev.cpu().numpy(), es.cpu().numpy()
+    orc_tab = {}
     for (b, g) in ((0, 2), (1, 5)):
         K, _ = dc.group(b, g)
         n = int(case.seq_lens0[b])
-        for h in (0, 3):
+        orc_tab[(b, g)] = []
+        for h in range(s.G):
             bh = s.G * g + h
             w = np.zeros((nq, n))
             for j in range(1, nq + 1):
@@ -560,16 +562,17 @@ def test_tables_init_from_several_queries_is_eq4(table_case):
                 sc = orc.scores(q_hist[j - 1, b, bh], K[:seen])
                 w[j - 1, n_sink:seen] = _softmax64(sc[n_sink:])
             ver, sla = tor.init_tables(w, gamma, n_sink)
+            orc_tab[(b, g)].append((ver, sla))
             np.testing.assert_allclose(ev[b, bh, :n], ver, rtol=3e-5, atol=1e-12)
             np.testing.assert_allclose(es[b, bh, :n], sla, rtol=3e-5, atol=1e-12)
             assert es[b, bh, :n].sum() == pytest.approx(1 / (2 * (1 - gamma)), rel=1e-5)
-    # the statistics that go with them: candidates from the device equal the oracle's from the exported tables
+    # the statistics that go with them: candidates from the device equal the oracle's from its own tables
     cand = torch.zeros((s.B, s.Hkv, ctx.cand_cap), dtype=torch.int32, device=DEV)
     cnt = torch.zeros((s.B, s.Hkv), dtype=torch.int32, device=DEV)
     ctx.lfps_table_candidates(dc.seq_lens(0), cand, cnt)
     for (b, g) in ((0, 2), (1, 5)):
         n = int(case.seq_lens0[b])
-        t64 = [(ev[b, s.G * g + h], es[b, s.G * g + h]) for h in range(s.G)]
+        t64 = orc_tab[(b, g)]
         want = tor.group_candidates(t64, n, 0.2, s.r, 0, n_sink)
         _assert_candidates(cand[b, g, : int(cnt[b, g])].cpu().numpy(), want, t64, n, 0.2, s.r, n_sink, f"b={b} g={g}")
     ctx.close()
