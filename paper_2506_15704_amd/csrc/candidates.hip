@@ -223,14 +223,24 @@ __global__ __launch_bounds__(kCandThreads) void k_table_candidates(Shape s, cons
   uint16_t* stage = reinterpret_cast<uint16_t*>(rcnt + ((words_cap + 63) >> 6));
   const int r = s.radius;
   for (int w = tid; w < W; w += kCandThreads) {
+    // the words of all heads (G <= 4) are fetched before any is used: sixteen loads in flight per thread
+    uint32_t lo[4], mid[4], hi[4], mean[4];
+#pragma unroll
+    for (int h = 0; h < 4; ++h) {
+      const bool live = h < s.G;
+      const int64_t row = ((int64_t)b * s.Hq + (int64_t)g * s.G + (live ? h : 0)) * flag_words;
+      lo[h] = (live && w > 0) ? f0[row + w - 1] : 0u;
+      mid[h] = live ? f0[row + w] : 0u;
+      hi[h] = (live && w + 1 < W) ? f0[row + w + 1] : 0u;
+      mean[h] = live ? fm[row + w] : 0u;
+    }
     uint32_t acc = 0u;
-    for (int h = 0; h < s.G; ++h) {
-      const int64_t row = ((int64_t)b * s.Hq + (int64_t)g * s.G + h) * flag_words;
-      const uint32_t lo = w > 0 ? f0[row + w - 1] : 0u, mid = f0[row + w], hi = w + 1 < W ? f0[row + w + 1] : 0u;
-      uint32_t d = mid;
-      for (int e = 1; e <= r + 1; ++e) d |= (mid << e) | (lo >> (32 - e));      // j = i + e
-      for (int e = 1; e <= r; ++e) d |= (mid >> e) | (hi << (32 - e));           // j = i - e
-      acc |= d & fm[row + w];
+#pragma unroll
+    for (int h = 0; h < 4; ++h) {
+      uint32_t d = mid[h];
+      for (int e = 1; e <= r + 1; ++e) d |= (mid[h] << e) | (lo[h] >> (32 - e));      // j = i + e
+      for (int e = 1; e <= r; ++e) d |= (mid[h] >> e) | (hi[h] << (32 - e));           // j = i - e
+      acc |= d & mean[h];
     }
     bm[w] = acc;
   }
