@@ -36,8 +36,29 @@ def _draw(i):
 
 @pytest.mark.parametrize("i", range(N_CONFIGS))
 def test_random_configuration_chained_steps(i):
-    c = _draw(i)
-    T = 3
+    _run(i, _draw(i), T=3)
+
+
+# Many requests with short contexts: hundreds of (request, KV group) units, so that one wave of the filtered
+# scoring kernel crosses several groups and the group tables are read in more than one batch of 64.
+MANY = [dict(Hq=32, Hkv=8, B=48, L_range=(150, 700), kmax=40, r=2, n_recent=1, n_sink=0, kv_dtype="bf16", k_dtype="",
+             v_dtype="", paged=None),
+        dict(Hq=8, Hkv=8, B=70, L_range=(90, 400), kmax=24, r=1, n_recent=2, n_sink=4, kv_dtype="bf16", k_dtype="fp8",
+             v_dtype="", paged=(16, "block_head_row")),
+        dict(Hq=16, Hkv=8, B=33, L_range=(64, 900), kmax=33, r=4, n_recent=0, n_sink=1, kv_dtype="f32", k_dtype="",
+             v_dtype="", paged=None)]
+
+
+@pytest.mark.parametrize("j", range(len(MANY)))
+def test_many_requests_short_contexts(j):
+    c = dict(MANY[j])
+    rng = np.random.default_rng(9100 + j)
+    c["k"] = rng.integers(1, c["kmax"] + 1, size=c["B"]).astype(np.int32)
+    c["k"][int(rng.integers(0, c["B"]))] = c["kmax"]
+    _run(1000 + j, c, T=2)
+
+
+def _run(i, c, T):
     spec = gen.tiny_spec(f"rnd{i}", B=c["B"], L=None, L_range=c["L_range"], k=c["kmax"], r=c["r"], T=T, Hq=c["Hq"],
                          Hkv=c["Hkv"], kv_dtype=c["kv_dtype"], k_dtype=c["k_dtype"], v_dtype=c["v_dtype"], seed=31000 + i,
                          recency=min(16, c["L_range"][0] // 2))
