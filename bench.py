@@ -423,6 +423,7 @@ def measure_tables(name, steps, warmup):
         steps = max(1, spec.T - warmup)
     sec = r.run_timed(steps, max(warmup, 1))
     recall = r.recall_vs_exact()
+    sec_graph, graph_ok = r.run_timed_graph(steps, max(warmup, 1))   # the tables' state is in device memory: replayable
     torch = r.torch
     # per-kernel times and candidate counts over the same steps
     r.reset()
@@ -442,6 +443,7 @@ def measure_tables(name, steps, warmup):
     scan_bytes = float(lens.sum()) * spec.Hq * 8.0            # both fp32 tables of every head, read once per step
     scan_us = tm["table_flags"][0] / max(tm["table_flags"][1], 1) * 1e3
     res = {"steps_per_s": round(1.0 / sec, 2), "ms_per_step": round(sec * 1e3, 4), "steps": steps,
+           "ms_per_step_hip_graph": round(sec_graph * 1e3, 4), "hip_graph_matches_eager": graph_ok,
            "decay": 0.95, "a": 0.2, "n_sink": 4,
            "cand_frac": round(float(cn.mean() / (spec.L or r.case.seq_lens0.mean())), 4),
            "recall_vs_exact_topk": round(recall, 4),

@@ -194,8 +194,10 @@ int lfps_tables_export(lfps_ctx* ctx, double* phi_ver, double* phi_sla, const in
 int lfps_table_candidates(lfps_ctx* ctx, const int32_t* seq_lens, int32_t* cand, int32_t* cand_count, void* stream);
 /* Eq. 10: decay by gamma, slash history moved from i-1 to i, and on the selected positions
  * idx[b,h,0:k_b] (scaled scores idx_score) the softmax weight over the selected set minus 1/(2|C_2|).
- * seq_lens is the length the step saw.  Returns LFPS_ECAP after max_seq_len - 1 updates without an
- * import or init. */
+ * seq_lens is the length the step saw.  The slash table has room for max_seq_len - 1 updates after an
+ * import or init: the call that would exceed it returns LFPS_ECAP, and (for updates replayed from a
+ * recorded graph, which the host does not see) the kernel leaves the tables alone and raises
+ * LFPS_FLAG_TABLE_FULL.  The table calls keep their state in device memory and may be recorded into a graph. */
 int lfps_table_update(lfps_ctx* ctx, const int32_t* idx, const float* idx_score, const int32_t* k,
                       const int32_t* seq_lens, void* stream);
 /* Alg. 1 lines 5-9 then Eq. 1: table candidates, exact scores over them, per-head Top-k (fewer than k_b
@@ -231,6 +233,7 @@ int lfps_copy_cand_count(lfps_ctx* ctx, int32_t* dst, void* stream);
 /* Status flags raised by kernels since the last poll.  Synchronises `stream`, copies the flag
  * word to *flags (host) and clears it. */
 #define LFPS_FLAG_CAND_OVERFLOW 1
+#define LFPS_FLAG_TABLE_FULL 2      /* a table update was skipped: max_seq_len - 1 updates since the last import / init */
 int lfps_poll_status(lfps_ctx* ctx, int32_t* flags, void* stream);
 
 /* Per-kernel timing for benchmarks.  While enabled, every kernel launch is bracketed by HIP

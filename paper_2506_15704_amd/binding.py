@@ -19,6 +19,7 @@ LIB_PATH = os.path.join(_PKG, "liblfps.so")
 LFPS_F32, LFPS_BF16 = 0, 1
 LFPS_OK, LFPS_EINVAL, LFPS_ECAP, LFPS_EHIP, LFPS_ENOMEM = 0, -1, -2, -3, -4
 LFPS_FLAG_CAND_OVERFLOW = 1
+LFPS_FLAG_TABLE_FULL = 2
 N_KERNELS = 13
 
 

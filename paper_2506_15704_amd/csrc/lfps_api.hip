@@ -31,8 +31,7 @@ struct lfps_ctx {
   uint32_t* tab_f0;    // [B, Hq, flag_words]
   uint32_t* tab_fm;    // [B, Hq, flag_words]
   int flag_words;
-  double tab_scale;    // host copy of the tables' scale factor (all heads share it): decides when to fold it back
-  int tab_updates;     // updates since the last import / init
+  int tab_updates;     // update calls since the last import / init (graph replays are not seen here: the kernel checks too)
   int tab_ready;
   int32_t* gate;       // [B, Hq] bypass marks of the current gated step
   int32_t* cand;       // [B, Hkv, cand_cap]
@@ -299,7 +298,6 @@ int lfps_create(const lfps_config* cfg, lfps_ctx** out) {
     c->tab_fm = (uint32_t*)p;
     p += z.tflag_b;
     c->flag_words = z.flag_words;
-    c->tab_scale = 1.0;
   }
   c->gate = (int32_t*)p;
   c->nseg = z.nseg;
@@ -517,7 +515,6 @@ int lfps_tables_init(lfps_ctx* ctx, const float* q_hist, int32_t n_queries, cons
   }
   hipError_t e = launch_table_finish(s, ctx->tab_ver, ctx->tab_sla, ctx->tab_state, v.seq_lens, st);
   if (e != hipSuccess) return fail(ctx, LFPS_EHIP, "lfps_tables_init (statistics)", e);
-  ctx->tab_scale = 1.0;
   ctx->tab_updates = 0;
   ctx->tab_ready = 1;
   return LFPS_OK;
@@ -532,7 +529,6 @@ int lfps_tables_import(lfps_ctx* ctx, const float* phi_ver, const float* phi_sla
   hipError_t e = launch_table_import(ctx->shape, ctx->tab_ver, ctx->tab_sla, ctx->tab_state, seq_lens, phi_ver,
                                      phi_sla, (hipStream_t)stream);
   if (e != hipSuccess) return fail(ctx, LFPS_EHIP, "lfps_tables_import", e);
-  ctx->tab_scale = 1.0;
   ctx->tab_updates = 0;
   ctx->tab_ready = 1;
   return LFPS_OK;
@@ -549,26 +545,12 @@ int lfps_tables_export(lfps_ctx* ctx, double* phi_ver, double* phi_sla, const in
   return LFPS_OK;
 }
 
-// The table entry points keep two counters on the host (accumulated decay, updates since the last start): a
-// captured graph would replay the launches without them, so capture is refused rather than left to go wrong
-// after ~900 replays (when the stored entries would have needed folding).
-static int refuse_capture(lfps_ctx* ctx, hipStream_t st, const char* who) {
-  hipStreamCaptureStatus status = hipStreamCaptureStatusNone;
-  if (hipStreamIsCapturing(st, &status) == hipSuccess && status != hipStreamCaptureStatusNone) {
-    snprintf(ctx->err, sizeof ctx->err, "%s: score-table calls keep host-side counters and cannot be captured into a graph", who);
-    return LFPS_EINVAL;
-  }
-  return LFPS_OK;
-}
-
 static int table_candidates_impl(lfps_ctx* ctx, const int32_t* seq_lens, int32_t* cand, int32_t* cand_count,
                                  bool for_step, const int32_t* gate, hipStream_t st) {
   const Shape& s = ctx->shape;
-  if (int rc = refuse_capture(ctx, st, "lfps_table_candidates / lfps_table_step")) return rc;
-  if (ctx->tab_scale < 1e-20) {          // fold the accumulated decay back into the stored entries
-    hipError_t e = launch_table_renorm(s, ctx->tab_ver, ctx->tab_sla, ctx->tab_state, st);
-    if (e != hipSuccess) return fail(ctx, LFPS_EHIP, "table renormalisation", e);
-    ctx->tab_scale = 1.0;
+  {                                      // heads whose accumulated decay has become small fold it into their entries
+    hipError_t e = launch_table_fold(s, ctx->tab_ver, ctx->tab_sla, ctx->tab_state, st);
+    if (e != hipSuccess) return fail(ctx, LFPS_EHIP, "table fold", e);
   }
   LAUNCH(ctx, LFPS_KERNEL_TABLE_FLAGS, st,
          launch_table_flags(s, ctx->tab_ver, ctx->tab_sla, ctx->tab_state, seq_lens, ctx->tab_f0, ctx->tab_fm,
@@ -584,13 +566,11 @@ static int table_candidates_impl(lfps_ctx* ctx, const int32_t* seq_lens, int32_t
 static int table_update_impl(lfps_ctx* ctx, const int32_t* idx, const float* idx_score, const int32_t* k,
                              const int32_t* seq_lens, const int32_t* gate, hipStream_t st) {
   const Shape& s = ctx->shape;
-  if (int rc = refuse_capture(ctx, st, "lfps_table_update / lfps_table_step")) return rc;
   if (ctx->tab_updates >= s.Lcap - 1)
     return fail(ctx, LFPS_ECAP, "lfps_table_update: max_seq_len - 1 updates since the last import/init");
   LAUNCH(ctx, LFPS_KERNEL_TABLE_UPDATE, st,
          launch_table_update(s, ctx->tab_ver, ctx->tab_sla, ctx->tab_state, seq_lens, idx, idx_score, k,
-                             (double)ctx->cfg.table_decay, gate, st));
-  ctx->tab_scale *= (double)ctx->cfg.table_decay;
+                             (double)ctx->cfg.table_decay, gate, ctx->flags, st));
   ctx->tab_updates += 1;
   return LFPS_OK;
 }

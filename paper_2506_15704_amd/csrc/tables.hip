@@ -4,8 +4,8 @@
 // step, moves slash history from i-1 to i, and adds (w_i - 1/(2|C_2|)) on the selected positions only.
 // Stored so that a step touches the selected entries and nothing else:
 //   * scale: a table entry is  Phi(i) = g * A(i)  with one factor g per head.  The decay is g <- gamma g;
-//     a selected entry becomes A(i) += delta_i / (gamma g).  (When g gets small the host asks for a
-//     dense pass that folds g back into A.)
+//     a selected entry becomes A(i) += delta_i / (gamma g).  (When g gets small a dense pass
+//     folds it back into A: k_table_fold, which every step launches and which decides per head.)
 //   * slash frame: A_sla is stored at index  i - cnt + Lcap  (cnt = updates applied so far), so the move
 //     of history from i-1 to i is the increment of cnt.  The entry of a new position is the slot its
 //     predecessor had; position 0 moves onto a slot that was never written (zero).
@@ -195,11 +195,18 @@ __global__ __launch_bounds__(kTabThreads) void k_table_update(Shape s, float* __
                                                               const int32_t* __restrict__ idx,
                                                               const float* __restrict__ sc,
                                                               const int32_t* __restrict__ kk, double gamma,
-                                                              const int32_t* __restrict__ gate) {
+                                                              const int32_t* __restrict__ gate,
+                                                              int32_t* __restrict__ flags) {
   __shared__ double red[kTabThreads / 64];
   __shared__ float redf[kTabThreads / 64];
   const int bh = blockIdx.x, b = bh / s.Hq, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   if (gate && gate[bh] != 0) return;                        // bypassed head: Eq. 10 is skipped for it
+  // The slash frame has room for Lcap - 1 moves since the tables were last written whole: past that the
+  // update is refused here (the host refuses it too, but counts only the calls it sees, not graph replays).
+  if (state[(int64_t)bh * kTableStateDoubles + TS_CNT] >= (double)(s.Lcap - 1)) {   // workgroup-uniform
+    if (tid == 0) atomicOr(flags, LFPS_FLAG_TABLE_FULL);
+    return;
+  }
   int n = seq_lens[b];
   n = n < 0 ? 0 : (n > s.Lcap ? s.Lcap : n);
   int kb = kk[b];
@@ -369,19 +376,22 @@ __global__ __launch_bounds__(kTabThreads) void k_table_export(Shape s, const flo
   phi_sla[(int64_t)bh * s.Lcap + i] = in ? g * (double)tab_sla[(int64_t)bh * 2 * s.Lcap + (s.Lcap - cnt) + i] : 0.0;
 }
 
-// Folds the scale into the stored values (A <- g A, g <- 1).  grid (chunks over 2*Lcap, B*Hq).
-__global__ __launch_bounds__(kTabThreads) void k_table_renorm(Shape s, float* __restrict__ tab_ver,
-                                                              float* __restrict__ tab_sla,
-                                                              const double* __restrict__ state) {
-  const int bh = blockIdx.y;
+// Folds a head's scale into its stored values (A <- g A, g <- 1) once the scale has become small; the
+// values themselves (g A) do not change.  One workgroup per head decides for itself from the head's state,
+// so the launch is part of every step (it costs a launch that finds nothing to do) and needs no host-side
+// count: a recorded graph replays it like any other kernel.  grid B*Hq.
+constexpr double kFoldBelow = 1e-20;       // gamma = 0.95 gets here after ~900 updates; stored values stay < 1e20 * Phi
+__global__ __launch_bounds__(kTabThreads) void k_table_fold(Shape s, float* __restrict__ tab_ver, float* __restrict__ tab_sla,
+                                                     double* __restrict__ state) {
+  const int bh = blockIdx.x, tid = threadIdx.x;
   const double g = state[(int64_t)bh * kTableStateDoubles + TS_G];
-  const int i = blockIdx.x * kTabThreads + threadIdx.x;
-  if (i < s.Lcap) tab_ver[(int64_t)bh * s.Lcap + i] = (float)(g * (double)tab_ver[(int64_t)bh * s.Lcap + i]);
-  if (i < 2 * s.Lcap) tab_sla[(int64_t)bh * 2 * s.Lcap + i] = (float)(g * (double)tab_sla[(int64_t)bh * 2 * s.Lcap + i]);
-}
-__global__ void k_table_renorm_done(double* __restrict__ state, int n_heads) {
-  const int bh = blockIdx.x * 256 + threadIdx.x;
-  if (bh < n_heads) state[(int64_t)bh * kTableStateDoubles + TS_G] = 1.0;
+  if (!(g < kFoldBelow)) return;             // workgroup-uniform
+  float* ver = tab_ver + (int64_t)bh * s.Lcap;
+  float* sla = tab_sla + (int64_t)bh * 2 * s.Lcap;
+  for (int i = tid; i < s.Lcap; i += kTabThreads) ver[i] = (float)(g * (double)ver[i]);
+  for (int i = tid; i < 2 * s.Lcap; i += kTabThreads) sla[i] = (float)(g * (double)sla[i]);
+  __syncthreads();                           // every thread has read g
+  if (tid == 0) state[(int64_t)bh * kTableStateDoubles + TS_G] = 1.0;
 }
 
 // ----------------------------------------------------------------------------- Eq. 4
@@ -657,9 +667,9 @@ hipError_t launch_table_flags(const Shape& s, const float* tab_ver, const float*
 
 hipError_t launch_table_update(const Shape& s, float* tab_ver, float* tab_sla, double* state, const int32_t* seq_lens,
                                const int32_t* idx, const float* sc, const int32_t* k, double gamma, const int32_t* gate,
-                               hipStream_t st) {
+                               int32_t* flags, hipStream_t st) {
   hipLaunchKernelGGL(k_table_update, dim3(s.B * s.Hq), dim3(kTabThreads), 0, st, s, tab_ver, tab_sla, state, seq_lens,
-                     idx, sc, k, gamma, gate);
+                     idx, sc, k, gamma, gate, flags);
   return hipGetLastError();
 }
 
@@ -677,13 +687,8 @@ hipError_t launch_table_export(const Shape& s, const float* tab_ver, const float
   return hipGetLastError();
 }
 
-hipError_t launch_table_renorm(const Shape& s, float* tab_ver, float* tab_sla, double* state, hipStream_t st) {
-  hipLaunchKernelGGL(k_table_renorm, dim3((2 * s.Lcap + kTabThreads - 1) / kTabThreads, s.B * s.Hq), dim3(kTabThreads),
-                     0, st, s, tab_ver, tab_sla, state);
-  hipError_t e = hipGetLastError();
-  if (e != hipSuccess) return e;
-  const int nh = s.B * s.Hq;
-  hipLaunchKernelGGL(k_table_renorm_done, dim3((nh + 255) / 256), dim3(256), 0, st, state, nh);
+hipError_t launch_table_fold(const Shape& s, float* tab_ver, float* tab_sla, double* state, hipStream_t st) {
+  hipLaunchKernelGGL(k_table_fold, dim3(s.B * s.Hq), dim3(kTabThreads), 0, st, s, tab_ver, tab_sla, state);
   return hipGetLastError();
 }
 

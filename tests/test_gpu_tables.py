@@ -617,11 +617,10 @@ def test_gated_steps_with_and_without_the_score_filter_agree(table_case):
     assert gates[0] == len(sparse) and gates[3] == 0          # bypassed at first, not bypassed with eps = 2
 
 
-@pytest.mark.filterwarnings("ignore:The CUDA Graph is empty")
-def test_memoryless_step_can_be_captured_and_table_step_refuses(table_case):
-    """lfps_step is kernel launches only: captured once into a graph and replayed three times with eager work
-    in between, every replay equals the eager result.  The table step keeps host counters and says no."""
-    from paper_2506_15704_amd.binding import LfpsError
+def test_memoryless_and_table_steps_can_be_captured(table_case):
+    """lfps_step and lfps_table_step are kernel launches only (the tables' scale and update count live in device
+    memory): each is captured once into a graph and replayed three times with eager work in between, and every
+    replay equals the eager result of a second context given the same inputs."""
     dc = table_case
     s, case = dc.spec, dc.case
     shp = (s.B, s.Hq, case.kmax)
@@ -651,12 +650,95 @@ def test_memoryless_step_can_be_captured_and_table_step_refuses(table_case):
         torch.cuda.synchronize()
         assert torch.equal(idx, e_idx) and torch.equal(out, e_out), f"replay {t}"
         want_prev = e_idx
-    tab = dc.make_ctx(table_mode=True)
-    tab.lfps_tables_init(dc.q(0), tab.kv_view(dc.K, dc.V, dc.seq_lens(0)))
+    ref_ctx.close()
+    ctx.close()
+
+    # the table step: both contexts start from the same Eq. 4 tables; the graph's context never runs a step eagerly
+    warm = dc.make_ctx(table_mode=True, n_sink=4)            # loads every kernel of the step before the capture
+    warm.lfps_tables_init(dc.q(0), warm.kv_view(dc.K, dc.V, dc.seq_lens(0)))
+    warm.lfps_table_step(dc.q(1), warm.kv_view(dc.K, dc.V, dc.seq_lens(1)), dc.k, idx, out)
+    torch.cuda.synchronize()
+    warm.close()
+    ref_tab, tab = dc.make_ctx(table_mode=True, n_sink=4), dc.make_ctx(table_mode=True, n_sink=4)
+    for c in (ref_tab, tab):
+        c.lfps_tables_init(dc.q(0), c.kv_view(dc.K, dc.V, dc.seq_lens(0)))
+    isc = torch.zeros(shp, dtype=torch.float32, device=DEV)
     torch.cuda.synchronize()
     g2 = torch.cuda.CUDAGraph()
-    with pytest.raises(LfpsError) as e:
-        with torch.cuda.graph(g2):
-            tab.lfps_table_step(q, tab.kv_view(dc.K, dc.V, sl), dc.k, idx, out)
-    assert "captured" in str(e.value)
+    with torch.cuda.graph(g2):
+        tab.lfps_table_step(q, tab.kv_view(dc.K, dc.V, sl), dc.k, idx, out, isc)
+    for t in (1, 2, 3, 4):
+        e_idx = torch.zeros(shp, dtype=torch.int32, device=DEV)
+        e_out = torch.zeros_like(out)
+        e_isc = torch.zeros_like(isc)
+        ref_tab.lfps_table_step(dc.q(t), ref_tab.kv_view(dc.K, dc.V, dc.seq_lens(t)), dc.k, e_idx, e_out, e_isc)
+        q.copy_(dc.q(t))
+        sl.copy_(dc.seq_lens(t))
+        g2.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(idx, e_idx) and torch.equal(isc, e_isc) and torch.equal(out, e_out), f"table replay {t}"
+    ev, es = (torch.zeros((s.B, s.Hq, case.Lcap), dtype=torch.float64, device=DEV) for _ in range(2))
+    rv, rs = torch.zeros_like(ev), torch.zeros_like(es)
+    tab.lfps_tables_export(ev, es, sl)
+    ref_tab.lfps_tables_export(rv, rs, sl)
+    assert torch.equal(ev, rv) and torch.equal(es, rs)
+    assert tab.lfps_poll_status() == 0
+    ref_tab.close()
+    tab.close()
+
+
+def test_replayed_updates_stop_at_the_table_capacity():
+    """The slash frame holds max_seq_len - 1 moves.  Updates replayed from a graph are not counted by the host:
+    the kernel itself leaves the tables alone from then on and raises LFPS_FLAG_TABLE_FULL; an eager call beyond
+    the capacity returns the error code."""
+    from paper_2506_15704_amd.binding import LFPS_FLAG_TABLE_FULL, Lfps, LfpsError
+    rng = np.random.default_rng(71)
+    B, Hq, Hkv, kmax, Lcap, n0 = 1, 8, 2, 6, 40, 20
+    ctx = Lfps(batch=B, n_q_heads=Hq, n_kv_heads=Hkv, max_seq_len=Lcap, max_k=kmax, radius=1, n_recent=0, n_sink=0,
+               table_mode=True, table_decay=0.9, table_a=0.2, cand_cap=Lcap)
+    n = np.array([n0], dtype=np.int32)
+    ver, sla = _make_tables(rng, B, Hq, Lcap, n, 0)
+    ctx.lfps_tables_import(dev(ver), dev(sla), dev(n))
+    idx = dev(np.stack([[rng.choice(n0, size=kmax, replace=False) for _ in range(Hq)]]).astype(np.int32))
+    sc = dev(rng.standard_normal((B, Hq, kmax)).astype(np.float32))
+    k, nd = dev(np.array([kmax], dtype=np.int32)), dev(n)
+    warm = Lfps(batch=B, n_q_heads=Hq, n_kv_heads=Hkv, max_seq_len=Lcap, max_k=kmax, radius=1, n_recent=0, n_sink=0,
+                table_mode=True, table_decay=0.9, table_a=0.2, cand_cap=Lcap)
+    warm.lfps_tables_import(dev(ver), dev(sla), nd)
+    warm.lfps_table_update(idx, sc, k, nd)                   # loads the kernel before the capture
     torch.cuda.synchronize()
+    warm.close()
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g):
+        ctx.lfps_table_update(idx, sc, k, nd)
+
+    def export():
+        ev, es = (torch.zeros((B, Hq, Lcap), dtype=torch.float64, device=DEV) for _ in range(2))
+        ctx.lfps_tables_export(ev, es, nd)
+        torch.cuda.synchronize()
+        return ev, es
+
+    for _ in range(Lcap - 2):
+        g.replay()
+    assert ctx.lfps_poll_status() == 0
+    before_last = export()
+    g.replay()                                               # update number Lcap - 1: the last one that fits
+    assert ctx.lfps_poll_status() == 0
+    full = export()
+    assert not torch.equal(full[0], before_last[0])
+    for _ in range(5):
+        g.replay()
+    assert ctx.lfps_poll_status() == LFPS_FLAG_TABLE_FULL
+    after = export()
+    assert torch.equal(after[0], full[0]) and torch.equal(after[1], full[1])
+    ctx.close()
+    # the host's own count: eager calls beyond the capacity are refused with an error code
+    ctx = Lfps(batch=B, n_q_heads=Hq, n_kv_heads=Hkv, max_seq_len=Lcap, max_k=kmax, radius=1, n_recent=0, n_sink=0,
+               table_mode=True, table_decay=0.9, table_a=0.2, cand_cap=Lcap)
+    ctx.lfps_tables_import(dev(ver), dev(sla), nd)
+    for _ in range(Lcap - 1):
+        ctx.lfps_table_update(idx, sc, k, nd)
+    with pytest.raises(LfpsError):
+        ctx.lfps_table_update(idx, sc, k, nd)
+    assert ctx.lfps_poll_status() == 0
+    ctx.close()
