@@ -44,7 +44,7 @@ def parse_args():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-table-mode", action="store_true", help="skip the score-table mode legs")
     ap.add_argument("--no-paged", action="store_true", help="skip the paged-cache leg")
-    ap.add_argument("--no-fp8", action="store_true", help="skip the FP8-keys leg")
+    ap.add_argument("--no-fp8", action="store_true", help="skip the legs with other cache formats (FP8 keys / values, fp16)")
     ap.add_argument("--fp8-only", action="store_true", help="run only the FP8-keys leg of --workload")
     ap.add_argument("--paged-only", action="store_true", help="run only the paged-cache leg of --workload")
     ap.add_argument("--paged-block", type=int, default=16, help="rows per block of the paged-cache leg")
@@ -62,7 +62,7 @@ class Runner:
     """Device state of one workload and the step loop."""
 
     def __init__(self, name, table_mode=False, n_sink=0, gated=False, paged_block=0, paged_layout="block_head_row",
-                 k_dtype="", v_dtype=""):
+                 k_dtype="", v_dtype="", kv_dtype=""):
         import numpy as np
         import torch
 
@@ -76,6 +76,9 @@ class Runner:
             import dataclasses
             self.spec = spec = dataclasses.replace(spec, name=f"{name}-{k_dtype}k" + ("v" if v_dtype else ""),
                                                    k_dtype=k_dtype, v_dtype=v_dtype)
+        if kv_dtype:         # the same workload with the whole cache in another 16-bit format
+            import dataclasses
+            self.spec = spec = dataclasses.replace(spec, name=f"{name}-{kv_dtype}", kv_dtype=kv_dtype)
         self.case = case = gen.make_case(spec)
         self.dev = "cuda:0"
         self.K, self.V = gen_device.fill_kv(case, self.dev)
@@ -286,7 +289,7 @@ def algorithmic_bytes_score(spec, case, cnts, filtered):
     """Bytes one scoring launch must move.  Per candidate row: its K row (R = D*e bytes) and its
     position (4).  Output: unfiltered, G scores per row (4G); filtered, at least the k selected
     (score, slot) pairs per head (8 k G per group).  Plus the G query rows per (b, g)."""
-    e = 1 if spec.k_dtype == "fp8" else (2 if spec.kv_dtype == "bf16" else 4)
+    e = 1 if spec.k_dtype == "fp8" else (4 if spec.kv_dtype == "f32" else 2)
     rows = cnts.sum(axis=(1, 2)).astype(float)
     per_group = spec.G * spec.D * 4
     if filtered:
@@ -409,6 +412,31 @@ def measure_fp8_keys(name, steps, warmup, with_v=False):
                             "GB_per_s": round(by / (us * 1e-6) / 1e9, 1) if us > 0 else None,
                             "frac_of_hbm_peak": round(by / (us * 1e-6) / 1e9 / HBM_PEAK_GBS, 4) if us > 0 else None},
            "exact_topk_ms": round(exact * 1e3, 4), "full_attn_ms": round(full * 1e3, 4)}
+    r.close()
+    return res
+
+
+def measure_fp16_cache(name, steps, warmup):
+    """The main workload with K and V stored as fp16 (the same draws rounded to half precision): same bytes as
+    bf16, the scoring runs on the fp16 MFMA.  A different input, so nothing is compared with the bf16 run."""
+    r = Runner(name, kv_dtype="f16")
+    spec = r.spec
+    if steps <= 0:
+        steps = max(1, spec.T - warmup)
+    sec = r.run_timed(steps, warmup)
+    recall = r.recall_vs_exact()
+    tm, cnts = r.run_kernel_timing(steps, warmup)
+    filtered = tm["filter_score"][1] > 0
+    kname = "filter_score" if filtered else "gather_score"
+    by = float(algorithmic_bytes_score(spec, r.case, cnts, filtered).mean())
+    us = tm[kname][0] / max(tm[kname][1], 1) * 1e3
+    res = {"kv_dtype": "fp16", "ms_per_step": round(sec * 1e3, 4), "steps_per_s": round(1.0 / sec, 2),
+           "cand_frac": round(float(cnts.mean() / (spec.L or r.case.seq_lens0.mean())), 4),
+           "recall_vs_exact_topk": round(recall, 4),
+           "kernel_us": {k: round(v[0] / steps * 1e3, 2) for k, v in tm.items() if v[1]},
+           "score_kernel": {"kernel": kname, "bytes_per_launch": round(by), "avg_launch_us": round(us, 2),
+                            "GB_per_s": round(by / (us * 1e-6) / 1e9, 1) if us > 0 else None,
+                            "frac_of_hbm_peak": round(by / (us * 1e-6) / 1e9 / HBM_PEAK_GBS, 4) if us > 0 else None}}
     r.close()
     return res
 
@@ -589,6 +617,7 @@ def main():
     if not args.no_fp8 and spec.kv_dtype == "bf16":
         line["fp8_keys"] = measure_fp8_keys(args.workload, args.steps, args.warmup)
         line["fp8_keys_and_values"] = measure_fp8_keys(args.workload, args.steps, args.warmup, with_v=True)
+        line["fp16_cache"] = measure_fp16_cache(args.workload, args.steps, args.warmup)
     if not args.no_paged:
         line["paged_kv"] = measure_paged(args.workload, args.steps, args.warmup, args.paged_block, args.paged_layout)
     if args.all_workloads:

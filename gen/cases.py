@@ -23,6 +23,7 @@ Sec. 5 "Setup" and App. A of the paper):
               recency band (last 64 prefill rows and every appended row), else 0.
 * values    : V[b,g,i] = z (its own stream).
 * bf16      : one round-to-nearest-even of the fp32 value, done in integer arithmetic.
+* fp16      : one round-to-nearest-even of the fp32 value (numpy's float16 conversion; the device's v_cvt_f16_f32).
 * queries   : q0[b,h] = rms(u[b,g(h)] + 0.3 N), q_t = rms(q_{t-1} + d_t N), d_t = drift
               (optionally a larger drift every `spike_every` steps); rms(x) scales to unit RMS.
 """
@@ -140,7 +141,7 @@ class CaseSpec:
     B: int
     L: Optional[int] = None                 # fixed context length ...
     L_range: Optional[Tuple[int, int]] = None  # ... or ragged, uniform in [lo, hi]
-    kv_dtype: str = "bf16"                   # "bf16" | "f32"
+    kv_dtype: str = "bf16"                   # "bf16" | "f16" | "f32"
     k_dtype: str = ""                        # "" = same as kv_dtype | "fp8": K stored as OCP FP8 E4M3
     v_dtype: str = ""                        # "" = same as kv_dtype | "fp8": V stored as OCP FP8 E4M3
     k: Optional[int] = None                  # fixed budget ...
@@ -258,7 +259,7 @@ class Case:
         """Regenerate rows of K ("k") or V ("v") of (request b, KV head g) on the CPU.
 
         Returns (values float32 [len(rows), D] as stored, bits) where bits is the uint16
-        bf16 pattern array for bf16 caches (uint8 E4M3 patterns for FP8 keys) and None for fp32 caches."""
+        bf16 / fp16 pattern array for 16-bit caches (uint8 E4M3 patterns for FP8 keys) and None for fp32 caches."""
         spec = self.spec
         D = spec.D
         rows = np.asarray(rows, dtype=np.int64)
@@ -277,6 +278,9 @@ class Case:
         if spec.kv_dtype == "bf16":
             bits = f32_to_bf16_bits(x)
             return bf16_bits_to_f32(bits), bits
+        if spec.kv_dtype == "f16":                         # IEEE half, round to nearest even (|x| stays far below 65504)
+            h = x.astype(np.float16)
+            return h.astype(np.float32), h.view(np.uint16)
         return x, None
 
     def kv_group(self, b: int, g: int, n_rows: Optional[int] = None, chunk: int = 16384):
@@ -292,7 +296,7 @@ class Case:
         return K, V
 
     def kv_bytes(self) -> int:
-        e = 2 if self.spec.kv_dtype == "bf16" else 4
+        e = 4 if self.spec.kv_dtype == "f32" else 2
         ek = 1 if self.spec.k_dtype == "fp8" else e
         ev = 1 if self.spec.v_dtype == "fp8" else e
         return self.spec.B * self.spec.Hkv * self.Lcap * self.spec.D * (ev + ek)

@@ -39,18 +39,18 @@ def _load():
 
 def fill_kv(case, device="cuda:0"):
     """Allocate K and V [B, Hkv, Lcap, D] on the device and fill them.  Returns (K, V) torch tensors
-    (bfloat16 or float32; K is float8_e4m3fn when the spec asks for FP8 keys)."""
+    (bfloat16, float16 or float32; K is float8_e4m3fn when the spec asks for FP8 keys)."""
     import torch
 
     spec = case.spec
     lib = _load()
-    dt = torch.bfloat16 if spec.kv_dtype == "bf16" else torch.float32
+    dt = {"bf16": torch.bfloat16, "f16": torch.float16, "f32": torch.float32}[spec.kv_dtype]
     shape = (spec.B, spec.Hkv, case.Lcap, spec.D)
     k_fp8 = spec.k_dtype == "fp8"
     K = torch.empty(shape, dtype=torch.float8_e4m3fn if k_fp8 else dt, device=device)
     v_fp8 = spec.v_dtype == "fp8"
     V = torch.empty(shape, dtype=torch.float8_e4m3fn if v_fp8 else dt, device=device)
-    fmt = int(spec.kv_dtype == "bf16")
+    fmt = {"f32": 0, "bf16": 1, "f16": 3}[spec.kv_dtype]
     dev = lambda a: torch.from_numpy(np.ascontiguousarray(a)).to(device)
     key_k = dev(case.key_k.view(np.int64))
     key_v = dev(case.key_v.view(np.int64))

@@ -1,5 +1,5 @@
 // Device-side fill of a synthetic KV cache: the same integer recipe as gen/cases.py
-// (splitmix64 counters -> Irwin-Hall(12) normal -> one fp32 bias add -> optional bf16 RNE),
+// (splitmix64 counters -> Irwin-Hall(12) normal -> one fp32 bias add -> optional bf16 / fp16 / E4M3 RNE),
 // so the device cache holds exactly the bits the CPU regenerates row by row.
 // Input generation only: nothing of the attention method is computed here.
 #include <hip/hip_runtime.h>
@@ -84,6 +84,14 @@ __global__ __launch_bounds__(256) void k_fill(void* __restrict__ out, int format
     w.x = e4m3_rne(x[0]) | (e4m3_rne(x[1]) << 8) | (e4m3_rne(x[2]) << 16) | (e4m3_rne(x[3]) << 24);
     w.y = e4m3_rne(x[4]) | (e4m3_rne(x[5]) << 8) | (e4m3_rne(x[6]) << 16) | (e4m3_rne(x[7]) << 24);
     *reinterpret_cast<uint2*>((uint8_t*)out + o) = w;
+  } else if (format == 3) {
+    union {
+      _Float16 h[8];
+      uint4 w;
+    } u;
+#pragma unroll
+    for (int c = 0; c < 8; ++c) u.h[c] = (_Float16)x[c];      // round to nearest even
+    *reinterpret_cast<uint4*>((uint16_t*)out + o) = u.w;
   } else if (format == 1) {
     uint4 w;
     w.x = bf16_rne(x[0]) | ((uint32_t)bf16_rne(x[1]) << 16);
@@ -101,12 +109,12 @@ __global__ __launch_bounds__(256) void k_fill(void* __restrict__ out, int format
 }  // namespace
 
 // All pointers are device pointers.  out is [B, Hkv, Lcap, 128] contiguous; format 0 = fp32, 1 = bf16,
-// 2 = OCP FP8 E4M3.
+// 2 = OCP FP8 E4M3, 3 = fp16.
 // bias == NULL fills a value tensor (no structure).  Returns the hipError_t of the launch.
 extern "C" __attribute__((visibility("default"))) int gen_fill_kv(
     void* out, int format, int B, int Hkv, int Lcap, int n_hot, const uint64_t* keys, const int32_t* row_end,
     const int32_t* recent_start, const int32_t* hot_pos, const float* bias, void* stream) {
-  if (!out || !keys || !row_end || B < 1 || Hkv < 1 || Lcap < 1 || format < 0 || format > 2)
+  if (!out || !keys || !row_end || B < 1 || Hkv < 1 || Lcap < 1 || format < 0 || format > 3)
     return (int)hipErrorInvalidValue;
   if (bias && (!recent_start || (n_hot > 0 && !hot_pos))) return (int)hipErrorInvalidValue;
   dim3 grid((unsigned)(((int64_t)Lcap * 16 + 255) / 256), (unsigned)(B * Hkv));

@@ -22,7 +22,8 @@
  *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  All work is
  *     enqueued asynchronously on it, in order.  Use one context per stream at a time.
  *   - Positions and counts are int32.  A negative entry in an index array is padding.
- *   - q is fp32 [B, Hq, D].  K and V rows are D contiguous elements (bf16 or fp32); the view
+ *   - q is fp32 [B, Hq, D] (with an fp16 cache every |q| element must stay below 65504, the fp16 range).
+ *     K and V rows are D contiguous elements (bf16, fp16 or fp32); the view
  *     struct gives the element strides between requests, KV heads and rows.
  *   - Argument errors that the host can see (NULL pointers, bad shapes/strides) return
  *     LFPS_EINVAL before anything is launched.  Values that live in device memory (k, seq_lens,
@@ -49,7 +50,7 @@ typedef enum {
   LFPS_ENOMEM = -4  /* workspace allocation failed in lfps_create */
 } lfps_status;
 
-typedef enum { LFPS_F32 = 0, LFPS_BF16 = 1 } lfps_dtype;
+typedef enum { LFPS_F32 = 0, LFPS_BF16 = 1, LFPS_F16 = 2 } lfps_dtype;   /* fp32, bfloat16, IEEE half */
 
 typedef struct {
   int32_t batch;       /* B >= 1 */
@@ -152,7 +153,7 @@ int lfps_sparse_attn(lfps_ctx* ctx, const float* q, const lfps_kv* kv, const int
  * select into topk_idx (this step's index set, the next step's prev_topk), attention into out.
  * S4 reuses S3's scores, so only V rows are gathered.  prev_topk and topk_idx must not overlap.
  *   topk_score [B, Hq, kmax] fp32 out or NULL
- * With a bf16 cache the scoring pass keeps, per head, only rows whose score reaches the k-th best
+ * With a bf16 or fp16 cache the scoring pass keeps, per head, only rows whose score reaches the k-th best
  * score of the PREVIOUS lfps_step call on this context minus a margin (the context remembers one
  * float per head); a head for which that leaves fewer than k rows is rescored without the filter
  * in the same call.  The result is therefore the same exact Top-k over the candidates whatever

@@ -16,7 +16,8 @@ import torch
 _PKG = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_PKG, "liblfps.so")
 
-LFPS_F32, LFPS_BF16 = 0, 1
+LFPS_F32, LFPS_BF16, LFPS_F16 = 0, 1, 2
+_KV_DTYPES = {"f32": (LFPS_F32, torch.float32), "bf16": (LFPS_BF16, torch.bfloat16), "f16": (LFPS_F16, torch.float16)}
 LFPS_OK, LFPS_EINVAL, LFPS_ECAP, LFPS_EHIP, LFPS_ENOMEM = 0, -1, -2, -3, -4
 LFPS_FLAG_CAND_OVERFLOW = 1
 LFPS_FLAG_TABLE_FULL = 2
@@ -140,10 +141,10 @@ class Lfps:
                  table_mode: bool = False, table_decay: float = 0.95, table_a: float = 0.2, k_fp8: bool = False,
                  v_fp8: bool = False):
         self.cfg = lfps_config(batch, n_q_heads, n_kv_heads, head_dim,
-                               LFPS_BF16 if kv_dtype == "bf16" else LFPS_F32, max_seq_len, max_k,
+                               _KV_DTYPES[kv_dtype][0], max_seq_len, max_k,
                                radius, n_recent, n_sink, cand_cap, device, int(bool(table_mode)),
                                float(table_decay), float(table_a), int(bool(k_fp8)), int(bool(v_fp8)))
-        self.kv_torch_dtype = torch.bfloat16 if kv_dtype == "bf16" else torch.float32
+        self.kv_torch_dtype = _KV_DTYPES[kv_dtype][1]
         self.k_torch_dtype = torch.float8_e4m3fn if k_fp8 else self.kv_torch_dtype
         self.v_torch_dtype = torch.float8_e4m3fn if v_fp8 else self.kv_torch_dtype
         self.device = torch.device("cuda", device)

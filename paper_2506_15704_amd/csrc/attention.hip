@@ -185,6 +185,7 @@ static hipError_t launch_sparse_t(const Shape& s, const KvView& kv, const int32_
 hipError_t launch_sparse_attn(const Shape& s, int dtype, const KvView& kv, const int32_t* idx, const float* idx_score,
                               const int32_t* k, float* out, const int32_t* skip_if, hipStream_t st) {
   if (dtype == LFPS_BF16 && kv.v_fp8) return launch_sparse_t<uint8_t>(s, kv, idx, idx_score, k, out, skip_if, st);
+  if (dtype == LFPS_F16) return launch_sparse_t<_Float16>(s, kv, idx, idx_score, k, out, skip_if, st);
   return dtype == LFPS_BF16 ? launch_sparse_t<uint16_t>(s, kv, idx, idx_score, k, out, skip_if, st)
                             : launch_sparse_t<float>(s, kv, idx, idx_score, k, out, skip_if, st);
 }
@@ -426,6 +427,7 @@ hipError_t launch_full_attn(const Shape& s, int dtype, const float* q, const KvV
   if (dtype == LFPS_BF16 && kv.k_fp8 && kv.v_fp8) return launch_full_t<uint8_t, uint8_t>(s, q, kv, part, n_split, st);
   if (dtype == LFPS_BF16 && kv.k_fp8) return launch_full_t<uint8_t, uint16_t>(s, q, kv, part, n_split, st);
   if (dtype == LFPS_BF16 && kv.v_fp8) return launch_full_t<uint16_t, uint8_t>(s, q, kv, part, n_split, st);
+  if (dtype == LFPS_F16) return launch_full_t<_Float16, _Float16>(s, q, kv, part, n_split, st);
   return dtype == LFPS_BF16 ? launch_full_t<uint16_t, uint16_t>(s, q, kv, part, n_split, st)
                             : launch_full_t<float, float>(s, q, kv, part, n_split, st);
 }

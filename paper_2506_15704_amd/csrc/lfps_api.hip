@@ -13,7 +13,7 @@ struct lfps_ctx {
   lfps_config cfg;
   Shape shape;
   int n_split_full;
-  int filter_on;       // filtered scoring inside lfps_step (bf16 caches)
+  int filter_on;       // filtered scoring inside lfps_step (bf16 / fp16 / FP8-key caches)
   int nseg;            // survivor pieces per head (row length of seg_count)
   int filter_blocks[2];   // launch size of the filtered scoring kernel (contiguous, paged cache): the workgroups the device holds at once
   // workspace (device)
@@ -81,7 +81,8 @@ int check_config(const lfps_config* c, Sizes* z, char* err, size_t errn) {
   const int G = c->n_q_heads / c->n_kv_heads;
   if (G != 1 && G != 2 && G != 4) BAD("heads per KV group must be 1, 2 or 4 (got %d)", G);
   if (c->head_dim != kD) BAD("head_dim must be %d (got %d)", kD, c->head_dim);
-  if (c->kv_dtype != LFPS_F32 && c->kv_dtype != LFPS_BF16) BAD("kv_dtype must be LFPS_F32 or LFPS_BF16");
+  if (c->kv_dtype != LFPS_F32 && c->kv_dtype != LFPS_BF16 && c->kv_dtype != LFPS_F16)
+    BAD("kv_dtype must be LFPS_F32, LFPS_BF16 or LFPS_F16");
   if (c->max_seq_len < 1) BAD("max_seq_len must be >= 1");
   if (c->max_k < 1 || c->max_k > c->max_seq_len) BAD("max_k must be in [1, max_seq_len]");
   if (c->radius < 0 || c->n_recent < 0 || c->n_sink < 0) BAD("radius, n_recent, n_sink must be >= 0");
@@ -120,7 +121,7 @@ int check_config(const lfps_config* c, Sizes* z, char* err, size_t errn) {
   z->count_b = align256((int64_t)c->batch * c->n_kv_heads * 4);
   z->sel_b = align256((int64_t)c->batch * c->n_q_heads * c->max_k * 4);
   z->part_b = align256((int64_t)c->batch * c->n_kv_heads * z->n_split_full * G * (kD + 2) * 4);
-  const bool filt = c->kv_dtype == LFPS_BF16;
+  const bool filt = c->kv_dtype == LFPS_BF16 || c->kv_dtype == LFPS_F16;
   z->nseg = filter_nseg(s);
   z->slot_b = filt ? z->score_b : 0;
   z->seg_b = align256((int64_t)c->batch * c->n_q_heads * z->nseg * 4);
@@ -152,7 +153,7 @@ int check_kv(lfps_ctx* ctx, const lfps_kv* kv, bool need_v, KvView* out) {
   if (need_v && !kv->v) return fail(ctx, LFPS_EINVAL, "kv->v is NULL");
   if (!kv->seq_lens) return fail(ctx, LFPS_EINVAL, "kv->seq_lens is NULL");
   // the strides are shared by K and V: with one-byte K elements the K rows set the alignment
-  const int esz = (ctx->cfg.k_fp8 || ctx->cfg.v_fp8) ? 1 : (ctx->cfg.kv_dtype == LFPS_BF16 ? 2 : 4);
+  const int esz = (ctx->cfg.k_fp8 || ctx->cfg.v_fp8) ? 1 : (ctx->cfg.kv_dtype == LFPS_F32 ? 4 : 2);
   if (kv->stride_n < kD || kv->stride_b < 0 || kv->stride_h < 0)
     return fail(ctx, LFPS_EINVAL, "kv strides: stride_n must be >= head_dim, stride_b/stride_h >= 0");
   if ((kv->stride_n * esz) % 16 || (kv->stride_b * esz) % 16 || (kv->stride_h * esz) % 16 ||
@@ -164,6 +165,7 @@ int check_kv(lfps_ctx* ctx, const lfps_kv* kv, bool need_v, KvView* out) {
   out->page = KvPage{nullptr, 0, 0, 0};
   out->k_fp8 = ctx->cfg.k_fp8 != 0;
   out->v_fp8 = ctx->cfg.v_fp8 != 0;
+  out->f16 = ctx->cfg.kv_dtype == LFPS_F16;
   if (kv->block_table) {
     const int64_t bs = kv->block_size;
     if (bs < 1 || bs > 65536 || (bs & (bs - 1)))
@@ -310,7 +312,8 @@ int lfps_create(const lfps_config* cfg, lfps_ctx** out) {
   if (e == hipSuccess) e = hipMemset(c->gate, 0, (size_t)z.thr_b);
   if (e == hipSuccess) e = configure_candidates(s);
   if (e == hipSuccess) e = configure_select(s);
-  if (e == hipSuccess && c->filter_on) e = filter_score_blocks(s, cfg->k_fp8 != 0, c->filter_blocks);
+  if (e == hipSuccess && c->filter_on)
+    e = filter_score_blocks(s, cfg->k_fp8 ? 1 : (cfg->kv_dtype == LFPS_F16 ? 2 : 0), c->filter_blocks);
   if (e == hipSuccess) e = hipDeviceSynchronize();
   if (e != hipSuccess) {
     snprintf(g_create_err, sizeof g_create_err, "workspace setup: %s", hipGetErrorString(e));
@@ -394,7 +397,7 @@ int lfps_sparse_attn(lfps_ctx* ctx, const float* q, const lfps_kv* kv, const int
 }
 
 // S2 + S3 over ctx->cand / ctx->cand_count inside the chained entry points.  With the score filter on
-// (bf16 caches): survivors of the per-head threshold first, then the unfiltered pass for the heads it
+// (16-bit and FP8-key caches): survivors of the per-head threshold first, then the unfiltered pass for the heads it
 // left short (both launches exit at once when no head is marked).  The candidates kernel of the same
 // step has cleared the marks and laid the groups on the line (group_start, line_total).
 static int score_and_select(lfps_ctx* ctx, const float* q, const KvView& v, const int32_t* k, int32_t* topk_idx,

@@ -11,6 +11,7 @@ constexpr int kD = 128;           // head_dim the kernels are written for
 constexpr int kMaxSplits = 64;    // upper bound of split-K partials per head (full attention)
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef _Float16 f16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 
@@ -30,6 +31,7 @@ struct KvView {
   KvPage page;
   bool k_fp8;   // K elements are one byte (OCP FP8 E4M3)
   bool v_fp8;   // V elements are one byte; otherwise V has the cache dtype
+  bool f16;     // the cache dtype is fp16 (K and V)
 };
 
 // Row addressing of the two cache layouts, chosen at compile time.  A logical row i of request b
@@ -92,7 +94,7 @@ hipError_t launch_group_score(const Shape& s, int dtype, const float* q, const K
 // equal parts, one per wave; the part size of a step is written to *seg_rows_out by the scoring
 // pass and read by the select, which also resets *line_total; see score.hip.
 int filter_nseg(const Shape& s);
-hipError_t filter_score_blocks(const Shape& s, bool fp8, int out[2]);
+hipError_t filter_score_blocks(const Shape& s, int k_kind, int out[2]);
 hipError_t launch_filter_score(const Shape& s, const float* q, const KvView& kv, const int32_t* cand,
                                const int32_t* cand_count, const int64_t* group_start, const int64_t* line_total,
                                const float* thr_state, float margin, float* score,
@@ -194,8 +196,8 @@ __device__ __forceinline__ bf16x8 fp8x8_to_bf16x8(uint32_t w0, uint32_t w1) {
   return r.v;
 }
 
-// Eight consecutive elements of a K or V row as they are loaded (T = float, uint16_t = bf16 bits, uint8_t =
-// E4M3), converted to fp32 when used: a row waiting in registers costs 8, 4 or 2 of them.
+// Eight consecutive elements of a K or V row as they are loaded (T = float, uint16_t = bf16 bits, _Float16,
+// uint8_t = E4M3), converted to fp32 when used: a row waiting in registers costs 8, 4 or 2 of them.
 template <typename T>
 struct Raw8;
 template <>
@@ -220,6 +222,15 @@ struct Raw8<uint16_t> {
       x[2 * c] = bf16_lo(w[c]);
       x[2 * c + 1] = bf16_hi(w[c]);
     }
+  }
+};
+template <>
+struct Raw8<_Float16> {
+  f16x8 w;
+  __device__ __forceinline__ void load(const _Float16* p) { w = *reinterpret_cast<const f16x8*>(p); }
+  __device__ __forceinline__ void get(float x[8]) const {
+#pragma unroll
+    for (int c = 0; c < 8; ++c) x[c] = (float)w[c];
   }
 };
 template <>

@@ -11,6 +11,9 @@
 //     and A's row 4*h + t holds term t of head h.  bf16 x bf16 products are exact in fp32, so
 //     the sum D[4h+0] + D[4h+1] + D[4h+2] is the fp32-accumulated dot product with the fp32
 //     query; it lands in lane group h without any cross-lane reduction.
+//   fp16 cache: the same with v_mfma_f32_16x16x32_f16; the query terms are fp16 too, the second and third
+//     scaled up by 2^11 and 2^22 so that they stay normal numbers, and scaled back when the three
+//     D rows are added (fp16 x fp16 products are exact in fp32 as well).  |q| must stay below 65504.
 //   fp32 cache: 16 lanes per row, 8 channels each, fp32 FMAs and a 4-step xor-shuffle reduce.
 #include "lfps_internal.h"
 
@@ -19,24 +22,62 @@ namespace lfps {
 constexpr int kScoreThreads = 256;           // 4 waves
 constexpr int kRowsPerWaveIter = 64;         // rows a wave scores per loop iteration
 
+// Storage format of the K rows a scoring kernel reads.
+enum { kKindBf16 = 0, kKindFp8 = 1, kKindF16 = 2 };
+
 // Round-to-nearest-even bf16 bits of x (the building block of the three-term split q = q0 + q1 + q2).
 __device__ __forceinline__ uint16_t bf16_rne_bits(float x) {
   uint32_t u = __float_as_uint(x);
   u += 0x7FFFu + ((u >> 16) & 1u);
   return (uint16_t)(u >> 16);
 }
-union Bf16x8Bits {
-  bf16x8 v;
-  u32x4 u;
-  uint16_t h[8];
+
+// Term t (0, 1, 2) of the three-way split of an fp32 query element into the operand's 16-bit format, as bits,
+// and the sum of the three MFMA results that undoes the split.
+template <typename Op>
+struct Split3;
+template <>
+struct Split3<bf16x8> {
+  __device__ static __forceinline__ uint16_t term(float f, int t) {
+    const uint16_t t0 = bf16_rne_bits(f);
+    const float r1 = f - __uint_as_float((uint32_t)t0 << 16);
+    const uint16_t t1 = bf16_rne_bits(r1);
+    const float r2 = r1 - __uint_as_float((uint32_t)t1 << 16);
+    const uint16_t t2 = bf16_rne_bits(r2);
+    return t == 0 ? t0 : (t == 1 ? t1 : t2);            // selected without branching
+  }
+  __device__ static __forceinline__ float sum(const f32x4& acc) { return (acc[0] + acc[1]) + acc[2]; }
 };
+template <>
+struct Split3<f16x8> {
+  // q = t0 + t1 / 2^11 + t2 / 2^22 (11 significant bits per term; the scaling keeps t1, t2 normal)
+  __device__ static __forceinline__ uint16_t term(float f, int t) {
+    const _Float16 t0 = (_Float16)f;
+    const float r1 = f - (float)t0;
+    const _Float16 t1 = (_Float16)(r1 * 2048.0f);
+    const float r2 = r1 - (float)t1 * (1.0f / 2048.0f);
+    const _Float16 t2 = (_Float16)(r2 * 4194304.0f);
+    const _Float16 sel = t == 0 ? t0 : (t == 1 ? t1 : t2);
+    return __builtin_bit_cast(uint16_t, sel);
+  }
+  __device__ static __forceinline__ float sum(const f32x4& acc) {
+    return (acc[0] + acc[1] * (1.0f / 2048.0f)) + acc[2] * (1.0f / 4194304.0f);
+  }
+};
+
+__device__ __forceinline__ f32x4 mfma16(bf16x8 a, bf16x8 b, f32x4 c) {
+  return __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, b, c, 0, 0, 0);
+}
+__device__ __forceinline__ f32x4 mfma16(f16x8 a, f16x8 b, f32x4 c) {
+  return __builtin_amdgcn_mfma_f32_16x16x32_f16(a, b, c, 0, 0, 0);
+}
 
 // The MFMA A operand of lane (j, kb): row m = j of the 16x32 A tile of step kk holds term (m & 3)
 // of head (m >> 2), channels of the 16-byte chunk kk + 4*kb of the row (the chunk that lane group kb
 // loads from K at step kk).  Heads >= G contribute zeros.  The query is fetched with eight 16-byte
 // loads issued together; a lane-dependent branch here would serialise 32 single loads.
-template <int G>
-__device__ __forceinline__ void load_query_operand(bf16x8 (&A)[4], const float* __restrict__ q, int64_t head0, int j,
+template <int G, typename Op>
+__device__ __forceinline__ void load_query_operand(Op (&A)[4], const float* __restrict__ q, int64_t head0, int j,
                                                    int kb) {
   const int h = j >> 2, t = j & 3;
   const float4* qh = reinterpret_cast<const float4*>(q + (head0 + (h < G ? h : 0)) * kD);
@@ -50,18 +91,12 @@ __device__ __forceinline__ void load_query_operand(bf16x8 (&A)[4], const float* 
 #pragma unroll
   for (int kk = 0; kk < 4; ++kk) {
     const float f[8] = {x[kk][0].x, x[kk][0].y, x[kk][0].z, x[kk][0].w, x[kk][1].x, x[kk][1].y, x[kk][1].z, x[kk][1].w};
-    Bf16x8Bits a;
+    union {
+      Op v;
+      uint16_t h[8];
+    } a;
 #pragma unroll
-    for (int c = 0; c < 8; ++c) {
-      // terms 0, 1, 2 of the three-way bf16 split, selected without branching
-      const uint16_t t0 = bf16_rne_bits(f[c]);
-      const float r1 = f[c] - __uint_as_float((uint32_t)t0 << 16);
-      const uint16_t t1 = bf16_rne_bits(r1);
-      const float r2 = r1 - __uint_as_float((uint32_t)t1 << 16);
-      const uint16_t t2 = bf16_rne_bits(r2);
-      const uint16_t sel = t == 0 ? t0 : (t == 1 ? t1 : t2);
-      a.h[c] = live ? sel : (uint16_t)0;
-    }
+    for (int c = 0; c < 8; ++c) a.h[c] = live ? Split3<Op>::term(f[c], t) : (uint16_t)0;
     A[kk] = a.v;
   }
 }
@@ -71,10 +106,11 @@ __device__ __forceinline__ void load_query_operand(bf16x8 (&A)[4], const float* 
 // channels 32 kb + 8 kk .. + 7 as bf16: the value as stored for a bf16 cache, converted (exactly: every
 // E4M3 value is a bf16 value) when it is multiplied for an FP8 cache, so that a tile in flight costs half
 // the registers and half the loads.
-template <bool kFp8>
+template <int kKind>
 struct KTile;
 template <>
-struct KTile<false> {
+struct KTile<kKindBf16> {
+  using Operand = bf16x8;
   static constexpr int kElemBytes = 2;
   bf16x8 v[4][4];
   __device__ __forceinline__ void load_row(int t, const char* row, int kb) {
@@ -85,7 +121,20 @@ struct KTile<false> {
   __device__ __forceinline__ bf16x8 operand(int t, int kk) const { return v[t][kk]; }
 };
 template <>
-struct KTile<true> {
+struct KTile<kKindF16> {
+  using Operand = f16x8;
+  static constexpr int kElemBytes = 2;
+  f16x8 v[4][4];
+  __device__ __forceinline__ void load_row(int t, const char* row, int kb) {
+    const f16x8* p = reinterpret_cast<const f16x8*>(row) + 4 * kb;
+#pragma unroll
+    for (int kk = 0; kk < 4; ++kk) v[t][kk] = p[kk];
+  }
+  __device__ __forceinline__ f16x8 operand(int t, int kk) const { return v[t][kk]; }
+};
+template <>
+struct KTile<kKindFp8> {
+  using Operand = bf16x8;
   static constexpr int kElemBytes = 1;
   u32x4 v[4][2];
   __device__ __forceinline__ void load_row(int t, const char* row, int kb) {
@@ -99,7 +148,7 @@ struct KTile<true> {
   }
 };
 
-// ----------------------------------------------------------------------------- bf16 / fp8, MFMA
+// ----------------------------------------------------------------------------- bf16 / fp16 / fp8, MFMA
 // grid: (tiles_x, B*Hkv).  GATHER: rows come from cand[bg, 0:count]; else rows are 0..n_b-1.
 //
 // Lane (j, kb) = (lane & 15, lane >> 4) supplies column j of the B operand: for MFMA step kk it
@@ -109,7 +158,7 @@ struct KTile<true> {
 // channels to (kk, kb) is valid as long as the A operand uses the same one.
 // The row ids of the next iteration are fetched, and the scores of the previous iteration stored,
 // right after this iteration's loads are issued.
-template <int G, bool GATHER, bool kPaged, bool kFp8>
+template <int G, bool GATHER, bool kPaged, int kKind>
 __global__ __launch_bounds__(kScoreThreads) void k_group_score_bf16(Shape s, const float* __restrict__ q,
                                                                     const void* __restrict__ K, int64_t stride_b,
                                                                     int64_t stride_h, int64_t stride_n, KvPage pg,
@@ -129,11 +178,12 @@ __global__ __launch_bounds__(kScoreThreads) void k_group_score_bf16(Shape s, con
   const int first = (blockIdx.x * 4 + wave) * kRowsPerWaveIter;
   if (first >= count) return;
 
-  bf16x8 A[4];
+  using Op = typename KTile<kKind>::Operand;
+  Op A[4];
   load_query_operand<G>(A, q, (int64_t)b * s.Hq + (int64_t)g * G, j, kb);
 
   using Rows = RowMap<kPaged>;
-  constexpr int ES = KTile<kFp8>::kElemBytes;
+  constexpr int ES = KTile<kKind>::kElemBytes;
   const char* Kbg = static_cast<const char*>(K) + Rows::base(b, g, stride_b, stride_h) * ES;
   const int32_t* cbg = GATHER ? cand + (int64_t)bg * s.cand_cap : nullptr;
   float* sc = score + ((int64_t)b * s.Hq + (int64_t)g * G + kb) * score_stride;   // lane group kb -> head kb
@@ -147,7 +197,7 @@ __global__ __launch_bounds__(kScoreThreads) void k_group_score_bf16(Shape s, con
   if (first + lane < count) my_row = GATHER ? cbg[first + lane] : first + lane;
   my_row = physical(my_row);
   for (int base = first; base < count; base += step) {
-    KTile<kFp8> Bt;
+    KTile<kKind> Bt;
 #pragma unroll
     for (int t = 0; t < 4; ++t) {
       const int row = __shfl(my_row, 16 * t + j);
@@ -169,9 +219,9 @@ __global__ __launch_bounds__(kScoreThreads) void k_group_score_bf16(Shape s, con
       f32x4 acc = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
       for (int kk = 0; kk < 4; ++kk)
-        acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(A[kk], Bt.operand(t, kk), acc, 0, 0, 0);
+        acc = mfma16(A[kk], Bt.operand(t, kk), acc);
       // lane (j, kb): D rows 4*kb .. 4*kb+3 = the three terms (and a zero row) of head kb, column j
-      pv[t] = ((acc[0] + acc[1]) + acc[2]) * scale;
+      pv[t] = Split3<Op>::sum(acc) * scale;
     }
     pbase = base;
     my_row = next_row;
@@ -205,7 +255,7 @@ __global__ __launch_bounds__(kScoreThreads) void k_group_score_bf16(Shape s, con
 // A threshold of -inf keeps every row; NaN means there is no previous step.
 constexpr int kFilterStage = 256;   // survivors one wave can hold per head before it must write them out
 
-template <int G, bool kPaged, bool kFp8>
+template <int G, bool kPaged, int kKind>
 __global__ __launch_bounds__(kScoreThreads, 2) void k_filter_score_bf16(
     Shape s, const float* __restrict__ q, const void* __restrict__ K, int64_t stride_b, int64_t stride_h,
     int64_t stride_n, KvPage page, const int32_t* __restrict__ seq_lens, const int32_t* __restrict__ cand,
@@ -271,9 +321,10 @@ __global__ __launch_bounds__(kScoreThreads, 2) void k_filter_score_bf16(
     }
     const float tau = kb < G ? thr_state[head] - margin : INFINITY;
 
-    bf16x8 A[4];                                        // filled after the first tile's loads are on their way
     using Rows = RowMap<kPaged>;
-    using Tile = KTile<kFp8>;
+    using Tile = KTile<kKind>;
+    using Op = typename Tile::Operand;
+    Op A[4];                                            // filled after the first tile's loads are on their way
     constexpr int ES = Tile::kElemBytes;
     const char* Kbg = static_cast<const char*>(K) + Rows::base(b, g, stride_b, stride_h) * ES;
     const int32_t* cbg = cand + (int64_t)bg * s.cand_cap;
@@ -320,8 +371,8 @@ __global__ __launch_bounds__(kScoreThreads, 2) void k_filter_score_bf16(
         f32x4 acc = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
         for (int kk = 0; kk < 4; ++kk)
-          acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(A[kk], Bt.operand(t, kk), acc, 0, 0, 0);
-        const float v = ((acc[0] + acc[1]) + acc[2]) * scale;
+          acc = mfma16(A[kk], Bt.operand(t, kk), acc);
+        const float v = Split3<Op>::sum(acc) * scale;
         const int slot = base_slot + 16 * t + j;
         const bool pass = kb < G && slot < seg_hi && v >= tau;
         const uint32_t gm = (uint32_t)(__ballot(pass) >> (16 * kb)) & 0xFFFFu;   // my head's 16 rows
@@ -567,11 +618,14 @@ static hipError_t launch_gs(const Shape& s, int dtype, const float* q, const KvV
                      only_if)
   const bool paged = kv.page.table != nullptr;
   if (dtype == LFPS_BF16 && kv.k_fp8) {
-    if (paged) LFPS_LAUNCH_GS(k_group_score_bf16, void, true, true);
-    else LFPS_LAUNCH_GS(k_group_score_bf16, void, false, true);
+    if (paged) LFPS_LAUNCH_GS(k_group_score_bf16, void, true, kKindFp8);
+    else LFPS_LAUNCH_GS(k_group_score_bf16, void, false, kKindFp8);
   } else if (dtype == LFPS_BF16) {
-    if (paged) LFPS_LAUNCH_GS(k_group_score_bf16, void, true, false);
-    else LFPS_LAUNCH_GS(k_group_score_bf16, void, false, false);
+    if (paged) LFPS_LAUNCH_GS(k_group_score_bf16, void, true, kKindBf16);
+    else LFPS_LAUNCH_GS(k_group_score_bf16, void, false, kKindBf16);
+  } else if (dtype == LFPS_F16) {
+    if (paged) LFPS_LAUNCH_GS(k_group_score_bf16, void, true, kKindF16);
+    else LFPS_LAUNCH_GS(k_group_score_bf16, void, false, kKindF16);
   } else {
     if (paged) LFPS_LAUNCH_GS(k_group_score_f32, float, true);
     else LFPS_LAUNCH_GS(k_group_score_f32, float, false);
@@ -599,8 +653,8 @@ hipError_t launch_group_score(const Shape& s, int dtype, const float* q, const K
 int filter_min_seg_rows(const Shape& s) { return (((s.cand_cap + 999) / 1000) + 63) & ~63; }
 int filter_nseg(const Shape& s) { return s.cand_cap / filter_min_seg_rows(s) + 2; }
 
-template <int G>
-static hipError_t filter_resident_blocks(bool fp8, int out[2]) {
+template <int G, int kKind>
+static hipError_t filter_resident_blocks(int out[2]) {
   int dev = 0;
   hipDeviceProp_t prop;
   hipError_t e = hipGetDevice(&dev);
@@ -613,25 +667,29 @@ static hipError_t filter_resident_blocks(bool fp8, int out[2]) {
     if (per_cu > 2) per_cu = 2;
     *n = per_cu * prop.multiProcessorCount;
   };
-  if (fp8) {
-    resident((const void*)k_filter_score_bf16<G, false, true>, &out[0]);
-    resident((const void*)k_filter_score_bf16<G, true, true>, &out[1]);
-  } else {
-    resident((const void*)k_filter_score_bf16<G, false, false>, &out[0]);
-    resident((const void*)k_filter_score_bf16<G, true, false>, &out[1]);
-  }
+  resident((const void*)k_filter_score_bf16<G, false, kKind>, &out[0]);
+  resident((const void*)k_filter_score_bf16<G, true, kKind>, &out[1]);
   return e;
 }
 
 // Workgroups of the filtered scoring kernel that the current device holds at once (its launch size), for
 // a contiguous cache (out[0]) and a paged one (out[1]); the variants differ in registers, hence in occupancy.
-hipError_t filter_score_blocks(const Shape& s, bool fp8, int out[2]) {
+// k_kind: 0 bf16, 1 FP8, 2 fp16 keys.
+hipError_t filter_score_blocks(const Shape& s, int k_kind, int out[2]) {
+#define LFPS_RESIDENT(GG)                                                   \
+  switch (k_kind) {                                                         \
+    case kKindBf16: return filter_resident_blocks<GG, kKindBf16>(out);      \
+    case kKindFp8: return filter_resident_blocks<GG, kKindFp8>(out);        \
+    case kKindF16: return filter_resident_blocks<GG, kKindF16>(out);        \
+    default: return hipErrorInvalidValue;                                   \
+  }
   switch (s.G) {
-    case 1: return filter_resident_blocks<1>(fp8, out);
-    case 2: return filter_resident_blocks<2>(fp8, out);
-    case 4: return filter_resident_blocks<4>(fp8, out);
+    case 1: LFPS_RESIDENT(1)
+    case 2: LFPS_RESIDENT(2)
+    case 4: LFPS_RESIDENT(4)
     default: return hipErrorInvalidValue;
   }
+#undef LFPS_RESIDENT
 }
 
 hipError_t launch_filter_score(const Shape& s, const float* q, const KvView& kv, const int32_t* cand,
@@ -641,6 +699,7 @@ hipError_t launch_filter_score(const Shape& s, const float* q, const KvView& kv,
                                int n_blocks, hipStream_t st) {
   const int nseg = filter_nseg(s);
   if (n_blocks < 1) return hipErrorInvalidValue;
+  const bool f16 = kv.f16;
   dim3 grid((unsigned)n_blocks), block(kScoreThreads);
   const float scale = 0.08838834764831845f;
 #define LFPS_LAUNCH_FILTER_P(GG, PAGED, FP8)                                                                       \
@@ -650,13 +709,17 @@ hipError_t launch_filter_score(const Shape& s, const float* q, const KvView& kv,
                      filter_min_seg_rows(s), nseg, scale)
 #define LFPS_LAUNCH_FILTER(GG)                        \
   if (kv.page.table && kv.k_fp8) {                    \
-    LFPS_LAUNCH_FILTER_P(GG, true, true);             \
+    LFPS_LAUNCH_FILTER_P(GG, true, kKindFp8);         \
+  } else if (kv.page.table && f16) {                  \
+    LFPS_LAUNCH_FILTER_P(GG, true, kKindF16);         \
   } else if (kv.page.table) {                         \
-    LFPS_LAUNCH_FILTER_P(GG, true, false);            \
+    LFPS_LAUNCH_FILTER_P(GG, true, kKindBf16);        \
   } else if (kv.k_fp8) {                              \
-    LFPS_LAUNCH_FILTER_P(GG, false, true);            \
+    LFPS_LAUNCH_FILTER_P(GG, false, kKindFp8);        \
+  } else if (f16) {                                   \
+    LFPS_LAUNCH_FILTER_P(GG, false, kKindF16);        \
   } else {                                            \
-    LFPS_LAUNCH_FILTER_P(GG, false, false);           \
+    LFPS_LAUNCH_FILTER_P(GG, false, kKindBf16);       \
   }
   switch (s.G) {
     case 1: LFPS_LAUNCH_FILTER(1); break;
@@ -683,6 +746,9 @@ hipError_t launch_head_score(const Shape& s, int dtype, const float* q, const Kv
   } else if (dtype == LFPS_BF16) {
     if (paged) LFPS_LAUNCH_HS(uint16_t, true);
     else LFPS_LAUNCH_HS(uint16_t, false);
+  } else if (dtype == LFPS_F16) {
+    if (paged) LFPS_LAUNCH_HS(_Float16, true);
+    else LFPS_LAUNCH_HS(_Float16, false);
   } else {
     if (paged) LFPS_LAUNCH_HS(float, true);
     else LFPS_LAUNCH_HS(float, false);

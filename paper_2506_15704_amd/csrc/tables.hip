@@ -19,6 +19,8 @@
 // per position and head are written (initial candidate; above the mean).
 #include "lfps_internal.h"
 
+#include <type_traits>
+
 namespace lfps {
 
 constexpr int kTabThreads = 256;
@@ -522,7 +524,7 @@ __global__ __launch_bounds__(64) void k_head_sparsity(Shape s, const float* __re
       fp8x4_to_f32(w, x);
       k0 = x[0];
       k1 = x[1];
-    } else if constexpr (sizeof(T) == 2) {
+    } else if constexpr (sizeof(T) == 2 && !std::is_same<T, _Float16>::value) {   // two bf16
       const uint32_t w = *reinterpret_cast<const uint32_t*>(kr);
       k0 = bf16_lo(w);
       k1 = bf16_hi(w);
@@ -721,6 +723,9 @@ hipError_t launch_head_sparsity(const Shape& s, int dtype, const float* q, const
   } else if (dtype == LFPS_BF16) {
     if (paged) LFPS_LAUNCH_HSP(uint16_t, true);
     else LFPS_LAUNCH_HSP(uint16_t, false);
+  } else if (dtype == LFPS_F16) {
+    if (paged) LFPS_LAUNCH_HSP(_Float16, true);
+    else LFPS_LAUNCH_HSP(_Float16, false);
   } else {
     if (paged) LFPS_LAUNCH_HSP(float, true);
     else LFPS_LAUNCH_HSP(float, false);
@@ -747,6 +752,9 @@ hipError_t launch_prior_means(const Shape& s, int dtype, const KvView& kv, float
   } else if (dtype == LFPS_BF16) {
     if (paged) LFPS_LAUNCH_PM(uint16_t, uint16_t, true);
     else LFPS_LAUNCH_PM(uint16_t, uint16_t, false);
+  } else if (dtype == LFPS_F16) {
+    if (paged) LFPS_LAUNCH_PM(_Float16, _Float16, true);
+    else LFPS_LAUNCH_PM(_Float16, _Float16, false);
   } else {
     if (paged) LFPS_LAUNCH_PM(float, float, true);
     else LFPS_LAUNCH_PM(float, float, false);

@@ -58,7 +58,9 @@ def test_config_validation_without_gpu():
         assert ei.value.code == b.LFPS_EINVAL
     # FP8 keys / values: flags are 0 or 1 and need the two-byte (bf16) cache description
     assert b.workspace_bytes(**{**good, "k_fp8": 1, "v_fp8": 1}) > 0
-    for bad in (dict(k_fp8=2), dict(v_fp8=-1), dict(k_fp8=1, kv_dtype=0), dict(v_fp8=1, kv_dtype=0)):
+    assert b.workspace_bytes(**{**good, "kv_dtype": b.LFPS_F16}) == b.workspace_bytes(**good)   # fp16: same sizes as bf16
+    for bad in (dict(k_fp8=2), dict(v_fp8=-1), dict(k_fp8=1, kv_dtype=0), dict(v_fp8=1, kv_dtype=0),
+                dict(k_fp8=1, kv_dtype=b.LFPS_F16), dict(kv_dtype=3)):
         with pytest.raises(b.LfpsError) as ei:
             b.workspace_bytes(**{**good, **bad})
         assert ei.value.code == b.LFPS_EINVAL

@@ -108,3 +108,18 @@ def test_fp8_key_rows_are_e4m3_values_of_the_bf16_recipe():
     plain = gen.make_case(gen.tiny_spec("fp8_rows"))       # same seed, bf16 keys: same draws before rounding
     ref, _ = plain.kv_rows("k", 1, 2, rows)
     assert np.abs(vals - ref).max() <= 2.0 ** -4 * np.abs(ref).max()   # half an ulp of 3 mantissa bits
+
+
+def test_fp16_rows_are_the_half_rounding_of_the_same_draws():
+    import torch
+    spec = gen.tiny_spec("f16_rows", kv_dtype="f16")
+    case = gen.make_case(spec)
+    rows = np.array([0, 3, 5, 100, 700])
+    plain = gen.make_case(gen.tiny_spec("f16_rows", kv_dtype="f32"))    # same seed: the draws before rounding
+    for which in ("k", "v"):
+        vals, bits = case.kv_rows(which, 1, 2, rows)
+        ref, _ = plain.kv_rows(which, 1, 2, rows)
+        assert bits.dtype == np.uint16 and vals.dtype == np.float32
+        want = torch.from_numpy(ref).to(torch.float16)                  # an independent round-to-nearest-even
+        np.testing.assert_array_equal(bits, want.view(torch.int16).numpy().view(np.uint16))
+        np.testing.assert_array_equal(vals, want.float().numpy())

@@ -18,7 +18,7 @@ pytestmark = pytest.mark.gpu
 
 LAYOUTS = [("bf16", 16, "block_head_row"), ("bf16", 64, "block_row_head"), ("f32", 32, "block_head_row"),
            ("bf16", 1, "block_head_row"), ("bf16", 4096, "block_row_head"), ("fp8", 16, "block_head_row"),
-           ("fp8", 128, "block_row_head"), ("fp8kv", 32, "block_row_head")]
+           ("fp8", 128, "block_row_head"), ("fp8kv", 32, "block_row_head"), ("f16", 16, "block_row_head")]
 
 
 @pytest.fixture(scope="module")
@@ -26,7 +26,8 @@ def cases():
     return {"bf16": DeviceCase(gen.tiny_spec("paged_bf16", B=3, L=2500, k=96, r=2, T=4)),
             "f32": DeviceCase(gen.tiny_spec("paged_f32", B=2, L=1111, k=64, r=3, T=3, kv_dtype="f32")),
             "fp8": DeviceCase(gen.tiny_spec("paged_fp8", B=2, L=1700, k=64, r=2, T=3, k_dtype="fp8")),
-            "fp8kv": DeviceCase(gen.tiny_spec("paged_fp8kv", B=2, L=1300, k=64, r=2, T=3, k_dtype="fp8", v_dtype="fp8"))}
+            "fp8kv": DeviceCase(gen.tiny_spec("paged_fp8kv", B=2, L=1300, k=64, r=2, T=3, k_dtype="fp8", v_dtype="fp8")),
+            "f16": DeviceCase(gen.tiny_spec("paged_f16", B=2, L=1500, k=64, r=2, T=3, kv_dtype="f16"))}
 
 
 def _views(ctx, dc, t, block_size, layout, seed=5):
@@ -88,7 +89,7 @@ def test_every_entry_point_is_bit_identical_to_the_contiguous_cache(cases, dtype
             assert_out_close(full[b, h], orc.full_attn(case.q[t, b, h], K, V, int(n[b])), f"paged full b{b} h{h}")
 
 
-@pytest.mark.parametrize("dtype,block_size,layout", LAYOUTS[:3] + LAYOUTS[5:6] + LAYOUTS[7:8])
+@pytest.mark.parametrize("dtype,block_size,layout", LAYOUTS[:3] + LAYOUTS[5:6] + LAYOUTS[7:9])
 def test_chained_steps_paged_equal_contiguous_and_oracle(cases, dtype, block_size, layout):
     """Free-running lfps_step chains (filtered scoring from the second step on) over both layouts give the
     same Top-k and outputs at every step; one more step on the paged view, started from the oracle's exact

@@ -28,12 +28,17 @@ def small_fp8kv():
 
 
 @pytest.fixture(scope="module")
+def small_f16():
+    return DeviceCase(gen.tiny_spec("small_f16", B=2, L=2300, k=88, r=2, T=4, kv_dtype="f16"))
+
+
+@pytest.fixture(scope="module")
 def small_f32():
     return DeviceCase(gen.tiny_spec("small_f32", B=2, L=1111, k=64, r=3, T=3, kv_dtype="f32"))
 
 
 # ------------------------------------------------------------------------ generator
-@pytest.mark.parametrize("fx", ["small_bf16", "small_f32", "small_fp8", "small_fp8kv"])
+@pytest.mark.parametrize("fx", ["small_bf16", "small_f32", "small_fp8", "small_fp8kv", "small_f16"])
 def test_device_fill_matches_cpu_generator(fx, request):
     dc = request.getfixturevalue(fx)
     rows = np.array([0, 3, 4, 5, 100, dc.case.seq_lens0[1] - 17, dc.case.seq_lens0[1] - 16, dc.case.seq_lens0[1] + 2,
@@ -115,7 +120,7 @@ def _teacher_inputs(dc, t, rng=None):
     return prev
 
 
-@pytest.mark.parametrize("fx", ["small_bf16", "small_f32", "small_fp8", "small_fp8kv"])
+@pytest.mark.parametrize("fx", ["small_bf16", "small_f32", "small_fp8", "small_fp8kv", "small_f16"])
 def test_score_topk_teacher_forced(fx, request):
     dc = request.getfixturevalue(fx)
     case, spec = dc.case, dc.spec
@@ -184,7 +189,7 @@ def test_select_ties_take_lowest_positions_and_k_exceeding_candidates():
 
 
 # ------------------------------------------------------------------------ S4
-@pytest.mark.parametrize("fx", ["small_bf16", "small_f32", "small_fp8", "small_fp8kv"])
+@pytest.mark.parametrize("fx", ["small_bf16", "small_f32", "small_fp8", "small_fp8kv", "small_f16"])
 @pytest.mark.parametrize("with_scores", [True, False])
 def test_sparse_attn_parity(fx, with_scores, request):
     dc = request.getfixturevalue(fx)
@@ -242,7 +247,7 @@ def test_k_equals_n_sparse_attention_is_full_attention(small_bf16):
 
 
 # ------------------------------------------------------------------------ baselines
-@pytest.mark.parametrize("fx", ["small_bf16", "small_f32", "small_fp8", "small_fp8kv"])
+@pytest.mark.parametrize("fx", ["small_bf16", "small_f32", "small_fp8", "small_fp8kv", "small_f16"])
 def test_full_attention_and_exact_topk_baselines(fx, request):
     dc = request.getfixturevalue(fx)
     case, spec = dc.case, dc.spec
@@ -284,7 +289,7 @@ def test_cover_invariant_on_device(small_bf16):
 
 
 # ------------------------------------------------------------------------ whole step
-@pytest.mark.parametrize("fx", ["small_bf16", "small_f32", "small_fp8", "small_fp8kv"])
+@pytest.mark.parametrize("fx", ["small_bf16", "small_f32", "small_fp8", "small_fp8kv", "small_f16"])
 def test_lfps_step_teacher_forced_multi_step(fx, request):
     """Each step the device gets the ORACLE's previous Top-k; candidates/Top-k/outputs must match."""
     dc = request.getfixturevalue(fx)
@@ -447,7 +452,7 @@ def test_timing_interface(small_bf16):
 
 
 # ------------------------------------------------------------------------ filtered scoring inside lfps_step
-@pytest.mark.parametrize("fx", ["small_bf16", "small_fp8"])
+@pytest.mark.parametrize("fx", ["small_bf16", "small_fp8", "small_f16"])
 def test_filtered_step_equals_unfiltered_step_whatever_the_history(fx, request):
     """lfps_step with the score filter (history from the previous call, including deliberately wrong
     histories that force the rescoring path) returns bit-identical Top-k and outputs to the

@@ -1,5 +1,5 @@
 """Seeded random configurations of the chained step: head grouping, batch, ragged lengths, per-request
-budgets, radius, always-present rows, cache dtype (bf16 / fp32 / FP8 keys / FP8 keys and values) and layout (contiguous / paged)
+budgets, radius, always-present rows, cache dtype (bf16 / fp16 / fp32 / FP8 keys / FP8 keys and values) and layout (contiguous / paged)
 drawn together, so that combinations no hand-written case names are exercised.  Teacher-forced: every step
 the device starts from the oracle's previous Top-k and is checked against the oracle's step (candidate counts
 exactly; Top-k, scores and outputs by the rules of tests/harness.py)."""
@@ -23,10 +23,10 @@ def _draw(i):
     Hq, Hkv = [(32, 8), (16, 8), (8, 8), (4, 1), (8, 2), (2, 1)][int(rng.integers(0, 6))]
     lo = int(rng.integers(24, 120)) if i % 6 == 5 else int(rng.integers(24, 3000))     # every sixth: very short contexts
     hi = lo + (int(rng.integers(0, 100)) if i % 6 == 5 else int(rng.integers(0, 2500)))
-    kind = ("bf16", "f32", "fp8", "fp8kv")[i % 4]
+    kind = "f16" if i % 8 == 6 else ("bf16", "f32", "fp8", "fp8kv")[i % 4]
     cfg = dict(Hq=Hq, Hkv=Hkv, B=int(rng.integers(1, 5)), L_range=(lo, hi), kmax=int(rng.integers(1, min(lo, 160) + 1)),
                r=int(rng.choice([0, 1, 2, 4, 9])), n_recent=int(rng.integers(0, 4)), n_sink=int(rng.integers(0, 5)),
-               kv_dtype="f32" if kind == "f32" else "bf16", k_dtype="fp8" if kind in ("fp8", "fp8kv") else "",
+               kv_dtype=kind if kind in ("f32", "f16") else "bf16", k_dtype="fp8" if kind in ("fp8", "fp8kv") else "",
                v_dtype="fp8" if kind == "fp8kv" else "",
                paged=[None, (1, "block_head_row"), (16, "block_row_head"), (64, "block_head_row")][int(rng.integers(0, 4))])
     cfg["k"] = rng.integers(1, cfg["kmax"] + 1, size=cfg["B"]).astype(np.int32)

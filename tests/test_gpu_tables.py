@@ -206,11 +206,13 @@ def test_many_updates_cross_the_renormalisation():
     ctx.close()
 
 
-@pytest.fixture(scope="module", params=["bf16", "fp8", "fp8kv"])
+@pytest.fixture(scope="module", params=["bf16", "fp8", "fp8kv", "f16"])
 def table_case(request):
-    """bf16 cache, the same workload with FP8 (E4M3) keys beside bf16 values, and with FP8 keys and values."""
+    """bf16 cache, the same workload with FP8 (E4M3) keys beside bf16 values, with FP8 keys and values, and
+    with an fp16 cache."""
     return DeviceCase(gen.tiny_spec("tables_" + request.param, B=2, L=1800, k=64, r=1, T=6,
-                                    k_dtype="fp8" if request.param != "bf16" else "",
+                                    kv_dtype="f16" if request.param == "f16" else "bf16",
+                                    k_dtype="fp8" if request.param in ("fp8", "fp8kv") else "",
                                     v_dtype="fp8" if request.param == "fp8kv" else ""))
 
 
