@@ -565,3 +565,46 @@ def test_small_workload_other_seeds(seed):
                 assert_out_close(out_h[b, h], orc.sparse_attn(case.q[t, b, h], K, V, idx_h[b, h, :kb]), f"seed {seed} out")
             prev_orc[(b, g)] = res["topk_idx"]
         prev_dev = nxt
+
+
+def test_fp16_cache_extreme_values():
+    """fp16 keys at the ends of the format (subnormal-only rows, rows near the largest finite value) against
+    queries of very different size: the fp16 matrix-core path (query split into three scaled fp16 terms) keeps
+    the fp32-accumulate accuracy, and subnormal keys are not flushed."""
+    from paper_2506_15704_amd.binding import Lfps
+    rng = np.random.default_rng(5)
+    L, D, Hq = 256, 128, 4
+    K = rng.standard_normal((L, D)).astype(np.float32)
+    K[64:128] = rng.integers(-1023, 1024, size=(64, D)).astype(np.float32) * np.float32(2.0 ** -24)   # subnormal fp16
+    K[128:192] = rng.choice([-1.0, 1.0], size=(64, D)).astype(np.float32) * rng.uniform(2e3, 6e4, size=(64, D)).astype(np.float32)
+    K[192:224] *= np.float32(1e-3)
+    K16 = torch.from_numpy(K).to(torch.float16)
+    Kf = K16.float().numpy()                                  # the stored values
+    assert np.abs(Kf[64:128]).max() < 6.2e-5 and np.abs(Kf[64:128]).max() > 0 and np.isfinite(Kf).all()
+    q = rng.standard_normal((1, Hq, D)).astype(np.float32)
+    q[0, 1] *= np.float32(1e3)
+    q[0, 2] *= np.float32(1e-3)
+    q[0, 3] *= np.float32(1e4)
+    ctx = Lfps(batch=1, n_q_heads=Hq, n_kv_heads=1, kv_dtype="f16", max_seq_len=L, max_k=32, radius=0, cand_cap=L)
+    Kd = K16.reshape(1, 1, L, D).to(DEV)
+    Vd = torch.zeros_like(Kd)
+    n = torch.tensor([L], dtype=torch.int32, device=DEV)
+    kv = ctx.kv_view(Kd, Vd, n)
+    cand = torch.arange(L, dtype=torch.int32, device=DEV).reshape(1, 1, L)
+    cnt = torch.tensor([[L]], dtype=torch.int32, device=DEV)
+    k = torch.tensor([32], dtype=torch.int32, device=DEV)
+    idx = torch.zeros((1, Hq, 32), dtype=torch.int32, device=DEV)
+    cs = torch.zeros((1, Hq, L), dtype=torch.float32, device=DEV)
+    ctx.lfps_score_topk(dev(q), kv, cand, cnt, k, idx, None, cs)
+    dense = torch.zeros((1, Hq, 32), dtype=torch.int32, device=DEV)
+    ctx.lfps_exact_topk(dev(q), kv, k, dense)
+    cs_h, idx_h, dense_h = cs.cpu().numpy(), idx.cpu().numpy(), dense.cpu().numpy()
+    for h in range(Hq):
+        ref = orc.scores(q[0, h], Kf, np.arange(L))
+        assert_scores_close(cs_h[0, h], ref, f"fp16 extremes h{h}")
+        I, _ = orc.exact_topk(q[0, h], Kf, L, 32)
+        for got, what in ((idx_h[0, h], "gathered"), (dense_h[0, h], "dense")):
+            assert_topk_equal_mod_ties(got, I, lambda p: orc.scores(q[0, h], Kf, p), 32, f"fp16 extremes {what} h{h}")
+    # the subnormal rows carry signal for the large query: a flush to zero would be far outside the tolerance
+    assert np.abs(orc.scores(q[0, 1], Kf, np.arange(64, 128))).max() > 0.05
+    ctx.close()
