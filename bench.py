@@ -27,9 +27,9 @@ HBM_PEAK_GBS = 8000.0   # MI355X published HBM3E peak
 # HBM bytes per launch of the scoring kernel measured with rocprofv3 --pmc (FETCH_SIZE, WRITE_SIZE), scaled
 # by the same counters' reading for a plain copy kernel; see profiles/ for the runs.  None = not measured.
 # Median over the steady-state dispatches of the scoring kernel (k_filter_score_bf16):
-#   profiles/lfps_kernels_C4.md: 944.5 MB fetched + 10.5 MB written; C3: 225.0 + 3.1 MB; C5: 480.3 + 8.9 MB;
-#   with FP8 keys (C4, same file): 477.6 + 10.5 MB.
-MEASURED_TRAFFIC_BYTES = {"C4": 955.0e6, "C3": 228.1e6, "C5": 489.2e6, "C4-fp8k": 488.1e6}
+#   profiles/lfps_kernels_C4.md: 941.1 MB fetched + 10.5 MB written; C3: 222.4 + 3.1 MB; C5: 476.9 + 8.9 MB;
+#   with FP8 keys (C4, same file): 477.8 + 10.5 MB.
+MEASURED_TRAFFIC_BYTES = {"C4": 951.6e6, "C3": 225.5e6, "C5": 485.8e6, "C4-fp8k": 488.3e6}
 
 
 def parse_args():

@@ -551,10 +551,6 @@ int lfps_tables_export(lfps_ctx* ctx, double* phi_ver, double* phi_sla, const in
 static int table_candidates_impl(lfps_ctx* ctx, const int32_t* seq_lens, int32_t* cand, int32_t* cand_count,
                                  bool for_step, const int32_t* gate, hipStream_t st) {
   const Shape& s = ctx->shape;
-  {                                      // heads whose accumulated decay has become small fold it into their entries
-    hipError_t e = launch_table_fold(s, ctx->tab_ver, ctx->tab_sla, ctx->tab_state, st);
-    if (e != hipSuccess) return fail(ctx, LFPS_EHIP, "table fold", e);
-  }
   LAUNCH(ctx, LFPS_KERNEL_TABLE_FLAGS, st,
          launch_table_flags(s, ctx->tab_ver, ctx->tab_sla, ctx->tab_state, seq_lens, ctx->tab_f0, ctx->tab_fm,
                             ctx->flag_words, (double)ctx->cfg.table_a, gate, st));

@@ -147,7 +147,6 @@ hipError_t launch_table_import(const Shape& s, float* tab_ver, float* tab_sla, d
                                const float* phi_ver, const float* phi_sla, hipStream_t st);
 hipError_t launch_table_export(const Shape& s, const float* tab_ver, const float* tab_sla, const double* state,
                                const int32_t* seq_lens, double* phi_ver, double* phi_sla, hipStream_t st);
-hipError_t launch_table_fold(const Shape& s, float* tab_ver, float* tab_sla, double* state, hipStream_t st);
 hipError_t launch_table_init(const Shape& s, float* tab_ver, float* tab_sla, const int32_t* seq_lens,
                              const float* score, int64_t score_stride, double gamma, int j, int n_queries,
                              hipStream_t st);

@@ -5,7 +5,7 @@
 // Stored so that a step touches the selected entries and nothing else:
 //   * scale: a table entry is  Phi(i) = g * A(i)  with one factor g per head.  The decay is g <- gamma g;
 //     a selected entry becomes A(i) += delta_i / (gamma g).  (When g gets small a dense pass
-//     folds it back into A: k_table_fold, which every step launches and which decides per head.)
+//     folds it back into A, at the end of the update that made it small; each head decides for itself.)
 //   * slash frame: A_sla is stored at index  i - cnt + Lcap  (cnt = updates applied so far), so the move
 //     of history from i-1 to i is the increment of cnt.  The entry of a new position is the slot its
 //     predecessor had; position 0 moves onto a slot that was never written (zero).
@@ -25,6 +25,7 @@ namespace lfps {
 
 constexpr int kTabThreads = 256;
 constexpr int kFlagIters = 8;      // 64-position tests per wave of the scan kernel
+constexpr double kFoldBelow = 1e-20;   // gamma = 0.95 gets here after ~900 updates; stored values stay < 1e20 * Phi
 
 // head state (doubles): scale, update count, raw moments of both tables, and "the table was flat (every
 // entry equal) when it was imported with N entries" marks.  The thresholds of Eq. 8 are derived from the
@@ -296,6 +297,26 @@ __global__ __launch_bounds__(kTabThreads) void k_table_update(Shape s, float* __
       st[TS_FLAT_S] = 0.0;
     }
   }
+  // Once the scale has become small it is folded into the stored values (A <- g A, g <- 1; the values g A
+  // do not change).  The head decides for itself from its own state, here at the end of the update that
+  // made the scale small, so no host-side count is involved and a recorded graph folds when an eager run would.
+  // This step's additions were made in L2 (atomics): they are waited for, and the entries are then read
+  // with device-scope loads, which do not look at this CU's vector cache (it may hold the old values).
+  if (g1 < kFoldBelow) {                                     // workgroup-uniform
+    __threadfence();
+    __syncthreads();
+    float* sla_all = tab_sla + (int64_t)bh * 2 * s.Lcap;
+    for (int i = tid; i < s.Lcap; i += kTabThreads) {
+      const float x = __hip_atomic_load(&ver[i], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      ver[i] = (float)(g1 * (double)x);
+    }
+    for (int i = tid; i < 2 * s.Lcap; i += kTabThreads) {
+      const float x = __hip_atomic_load(&sla_all[i], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      sla_all[i] = (float)(g1 * (double)x);
+    }
+    __syncthreads();
+    if (tid == 0) st[TS_G] = 1.0;
+  }
 }
 
 // ----------------------------------------------------------------------------- import / export / renormalise
@@ -376,24 +397,6 @@ __global__ __launch_bounds__(kTabThreads) void k_table_export(Shape s, const flo
   const bool in = i >= s.n_sink && i < n;
   phi_ver[(int64_t)bh * s.Lcap + i] = in ? g * (double)tab_ver[(int64_t)bh * s.Lcap + i] : 0.0;
   phi_sla[(int64_t)bh * s.Lcap + i] = in ? g * (double)tab_sla[(int64_t)bh * 2 * s.Lcap + (s.Lcap - cnt) + i] : 0.0;
-}
-
-// Folds a head's scale into its stored values (A <- g A, g <- 1) once the scale has become small; the
-// values themselves (g A) do not change.  One workgroup per head decides for itself from the head's state,
-// so the launch is part of every step (it costs a launch that finds nothing to do) and needs no host-side
-// count: a recorded graph replays it like any other kernel.  grid B*Hq.
-constexpr double kFoldBelow = 1e-20;       // gamma = 0.95 gets here after ~900 updates; stored values stay < 1e20 * Phi
-__global__ __launch_bounds__(kTabThreads) void k_table_fold(Shape s, float* __restrict__ tab_ver, float* __restrict__ tab_sla,
-                                                     double* __restrict__ state) {
-  const int bh = blockIdx.x, tid = threadIdx.x;
-  const double g = state[(int64_t)bh * kTableStateDoubles + TS_G];
-  if (!(g < kFoldBelow)) return;             // workgroup-uniform
-  float* ver = tab_ver + (int64_t)bh * s.Lcap;
-  float* sla = tab_sla + (int64_t)bh * 2 * s.Lcap;
-  for (int i = tid; i < s.Lcap; i += kTabThreads) ver[i] = (float)(g * (double)ver[i]);
-  for (int i = tid; i < 2 * s.Lcap; i += kTabThreads) sla[i] = (float)(g * (double)sla[i]);
-  __syncthreads();                           // every thread has read g
-  if (tid == 0) state[(int64_t)bh * kTableStateDoubles + TS_G] = 1.0;
 }
 
 // ----------------------------------------------------------------------------- Eq. 4
@@ -686,11 +689,6 @@ hipError_t launch_table_export(const Shape& s, const float* tab_ver, const float
                                const int32_t* seq_lens, double* phi_ver, double* phi_sla, hipStream_t st) {
   hipLaunchKernelGGL(k_table_export, dim3((s.Lcap + kTabThreads - 1) / kTabThreads, s.B * s.Hq), dim3(kTabThreads), 0,
                      st, s, tab_ver, tab_sla, state, seq_lens, phi_ver, phi_sla);
-  return hipGetLastError();
-}
-
-hipError_t launch_table_fold(const Shape& s, float* tab_ver, float* tab_sla, double* state, hipStream_t st) {
-  hipLaunchKernelGGL(k_table_fold, dim3(s.B * s.Hq), dim3(kTabThreads), 0, st, s, tab_ver, tab_sla, state);
   return hipGetLastError();
 }
 

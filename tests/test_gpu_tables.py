@@ -194,8 +194,8 @@ def test_many_updates_cross_the_renormalisation():
     for step in range(steps):
         idx = np.stack([[rng.choice(int(n[0]), size=kmax, replace=False) for _ in range(Hq)]]).astype(np.int32)
         sc = rng.standard_normal((B, Hq, kmax)).astype(np.float32)
-        ctx.lfps_table_candidates(dev(n), cand, cnt)    # the renormalisation is triggered from here
-        ctx.lfps_table_update(dev(idx), dev(sc), dev(k), dev(n))
+        ctx.lfps_table_candidates(dev(n), cand, cnt)
+        ctx.lfps_table_update(dev(idx), dev(sc), dev(k), dev(n))     # folds the scale at the end of update 67
         v64, s64 = _oracle_update_all(v64, s64, n, idx, sc, k, gamma, 0)
         n = n + 1
     ev = torch.zeros((B, Hq, Lcap), dtype=torch.float64, device=DEV)
