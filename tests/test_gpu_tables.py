@@ -319,16 +319,16 @@ def _draw_table_config(i):
     rng = np.random.default_rng(9100 + i)
     Hq, Hkv = [(32, 8), (16, 8), (8, 8), (4, 1), (8, 2), (2, 1)][int(rng.integers(0, 6))]
     lo = int(rng.integers(200, 2500))
-    kind = ("bf16", "f32", "fp8", "fp8kv")[i % 4]
+    kind = "f16" if i >= 12 else ("bf16", "f32", "fp8", "fp8kv")[i % 4]
     return dict(Hq=Hq, Hkv=Hkv, B=int(rng.integers(1, 4)), L_range=(lo, lo + int(rng.integers(0, 1500))),
                 kmax=int(rng.integers(8, 97)), r=int(rng.choice([0, 1, 2, 4])), n_recent=int(rng.integers(0, 3)),
                 n_sink=int(rng.integers(0, 5)), a=float(rng.choice([0.1, 0.2, 0.3])), gamma=float(rng.choice([0.6, 0.9, 0.95])),
-                kv_dtype="f32" if kind == "f32" else "bf16", k_dtype="fp8" if kind in ("fp8", "fp8kv") else "",
+                kv_dtype=kind if kind in ("f32", "f16") else "bf16", k_dtype="fp8" if kind in ("fp8", "fp8kv") else "",
                 v_dtype="fp8" if kind == "fp8kv" else "",
                 paged=[None, (16, "block_row_head"), (64, "block_head_row")][int(rng.integers(0, 3))])
 
 
-@pytest.mark.parametrize("i", range(12))
+@pytest.mark.parametrize("i", range(15))
 def test_table_step_random_configurations(i):
     """Seeded random configurations of the score-table step (head grouping, ragged lengths, per-request budgets,
     radius, a, decay, sink / recent rows, cache dtype and layout): two teacher-forced steps against the oracle on
