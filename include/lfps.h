@@ -53,7 +53,7 @@ typedef enum {
 typedef enum { LFPS_F32 = 0, LFPS_BF16 = 1, LFPS_F16 = 2 } lfps_dtype;   /* fp32, bfloat16, IEEE half */
 
 typedef struct {
-  int32_t batch;       /* B >= 1 */
+  int32_t batch;       /* B >= 1; B * Hq <= 65535 */
   int32_t n_q_heads;   /* Hq, a multiple of n_kv_heads; Hq/Hkv must be 1, 2 or 4 */
   int32_t n_kv_heads;  /* Hkv */
   int32_t head_dim;    /* D, must be 128 */

@@ -80,6 +80,8 @@ int check_config(const lfps_config* c, Sizes* z, char* err, size_t errn) {
     BAD("n_q_heads (%d) must be a positive multiple of n_kv_heads (%d)", c->n_q_heads, c->n_kv_heads);
   const int G = c->n_q_heads / c->n_kv_heads;
   if (G != 1 && G != 2 && G != 4) BAD("heads per KV group must be 1, 2 or 4 (got %d)", G);
+  if ((int64_t)c->batch * c->n_q_heads > 65535)
+    BAD("batch * n_q_heads must be <= 65535 (one grid row per head; got %d * %d)", c->batch, c->n_q_heads);
   if (c->head_dim != kD) BAD("head_dim must be %d (got %d)", kD, c->head_dim);
   if (c->kv_dtype != LFPS_F32 && c->kv_dtype != LFPS_BF16 && c->kv_dtype != LFPS_F16)
     BAD("kv_dtype must be LFPS_F32, LFPS_BF16 or LFPS_F16");

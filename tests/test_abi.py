@@ -42,7 +42,7 @@ def test_config_validation_without_gpu():
                 radius=2, n_recent=1, n_sink=0, cand_cap=0, device=0)
     assert b.workspace_bytes(**good) > 0
     for bad in (dict(head_dim=64), dict(n_q_heads=24), dict(batch=0), dict(max_k=0), dict(max_k=5000),
-                dict(radius=-1), dict(kv_dtype=7), dict(n_q_heads=64)):
+                dict(radius=-1), dict(kv_dtype=7), dict(n_q_heads=64), dict(batch=2048)):
         with pytest.raises(b.LfpsError) as ei:
             b.workspace_bytes(**{**good, **bad})
         assert ei.value.code == b.LFPS_EINVAL
