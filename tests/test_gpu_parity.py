@@ -608,3 +608,47 @@ def test_fp16_cache_extreme_values():
     # the subnormal rows carry signal for the large query: a flush to zero would be far outside the tolerance
     assert np.abs(orc.scores(q[0, 1], Kf, np.arange(64, 128))).max() > 0.05
     ctx.close()
+
+
+def test_non_finite_queries_stay_in_bounds_and_in_their_group(small_bf16):
+    """A NaN query and an infinite one (garbage in): the step still ends, every selected index of those heads is a
+    valid, distinct row of the request, the count is right, and the heads of the other KV groups get exactly what
+    a clean run gives them (a group shares nothing with another).  Two steps, so the second goes through the score filter."""
+    dc = small_bf16
+    case, spec = dc.case, dc.spec
+    shp = (spec.B, spec.Hq, case.kmax)
+    clean, dirty = dc.make_ctx(), dc.make_ctx()
+    seed = torch.zeros(shp, dtype=torch.int32, device=DEV)
+    clean.lfps_exact_topk(dc.q(0), clean.kv_view(dc.K, dc.V, dc.seq_lens(0)), dc.k, seed)
+    bad_heads = [(0, 1), (1, 6), (2, 31)]                      # in KV groups 0, 1 and 7
+    bad_groups = {(b, h // spec.G) for b, h in bad_heads}
+    prev_c, prev_d = seed, seed
+    for t in (1, 2):
+        q = dc.q(t).clone()
+        qd = q.clone()
+        qd[0, 1, 5] = float("nan")
+        qd[1, 6, :] = float("inf")
+        qd[2, 31, 100] = float("-inf")
+        res = []
+        for ctx, qq, prev in ((clean, q, prev_c), (dirty, qd, prev_d)):
+            idx = torch.full(shp, -5, dtype=torch.int32, device=DEV)
+            sc = torch.zeros(shp, dtype=torch.float32, device=DEV)
+            out = torch.zeros((spec.B, spec.Hq, spec.D), dtype=torch.float32, device=DEV)
+            ctx.lfps_step(qq, ctx.kv_view(dc.K, dc.V, dc.seq_lens(t)), prev, dc.k, idx, out, sc)
+            assert ctx.lfps_poll_status() == 0
+            res.append((idx, out))
+        (ic, oc), (id_, od) = res
+        n = case.seq_lens(t)
+        idh = id_.cpu().numpy()
+        for b in range(spec.B):
+            kb = int(case.k[b])
+            for h in range(spec.Hq):
+                if (b, h // spec.G) in bad_groups:
+                    got = idh[b, h, :kb]
+                    assert np.all((got >= 0) & (got < n[b])) and len(np.unique(got)) == kb, f"t{t} b{b} h{h}"
+                    assert np.all(idh[b, h, kb:] == -1)
+                else:
+                    assert torch.equal(id_[b, h], ic[b, h]) and torch.equal(od[b, h], oc[b, h]), f"t{t} b{b} h{h}"
+        prev_c, prev_d = ic, id_
+    clean.close()
+    dirty.close()
