@@ -87,7 +87,8 @@ hipError_t launch_group_score(const Shape& s, int dtype, const float* q, const K
                               const int32_t* cand_count, float* score, int64_t score_stride, const int32_t* only_if,
                               hipStream_t st);
 
-// Filtered scoring (bf16 cache): per head only rows with score >= thr_state[b,h] - margin are kept, as
+// Filtered scoring (bf16, fp16 or FP8 keys; the kernel keeps its first name, k_filter_score_bf16): per
+// head only rows with score >= thr_state[b,h] - margin are kept, as
 // (score, position) lists in at most filter_nseg(s) pieces per head.  The kernel runs with exactly
 // n_blocks workgroups (filter_score_blocks: what the device holds at once) and cuts the candidate
 // slots of all groups (placed on one line by the candidates kernel: group_start, line_total) into

@@ -233,7 +233,7 @@ __global__ __launch_bounds__(kScoreThreads) void k_group_score_bf16(Shape s, con
   }
 }
 
-// ----------------------------------------------------------------------------- bf16, MFMA, filtered output
+// ----------------------------------------------------------------------------- bf16 / fp16 / fp8, MFMA, filtered output
 // The same scoring, but only rows whose score reaches a per-head threshold are written out
 // (the threshold is the previous step's k-th best score minus a margin: consecutive decode steps
 // select almost the same rows, the premise of the method).  Writing every score costs far more
