@@ -99,3 +99,15 @@ def test_binding_structs_mirror_the_header_field_by_field():
         want = [(n, ctype_of[t]) for t, n in _struct_fields(name)]
         got = [(f[0], f[1]) for f in cls._fields_]
         assert got == want, f"{name}: binding {got} != header {want}"
+
+
+def test_bench_refuses_more_than_one_gpu():
+    """The one-GPU build says so instead of running a multi-GPU job it does not have."""
+    import os
+    import subprocess
+    import sys
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    res = subprocess.run([sys.executable, os.path.join(root, "bench.py"), "--gpus", "2"], capture_output=True, text=True,
+                         timeout=120)
+    assert res.returncode != 0
+    assert "one-GPU" in (res.stdout + res.stderr)
