@@ -140,6 +140,8 @@ class Lfps:
                  n_recent: int = 1, n_sink: int = 0, cand_cap: int = 0, device: int = 0,
                  table_mode: bool = False, table_decay: float = 0.95, table_a: float = 0.2, k_fp8: bool = False,
                  v_fp8: bool = False):
+        if kv_dtype not in _KV_DTYPES:
+            raise ValueError(f"kv_dtype must be one of {sorted(_KV_DTYPES)} (got {kv_dtype!r})")
         self.cfg = lfps_config(batch, n_q_heads, n_kv_heads, head_dim,
                                _KV_DTYPES[kv_dtype][0], max_seq_len, max_k,
                                radius, n_recent, n_sink, cand_cap, device, int(bool(table_mode)),
