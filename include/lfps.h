@@ -21,6 +21,9 @@
  *     The context owns only its workspace (candidate scores, split partials, event pool).
  *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  All work is
  *     enqueued asynchronously on it, in order.  Use one context per stream at a time.
+ *   - Entry points that only enqueue kernels (the S1..S4 calls, lfps_step, the lfps_table_* steps, the
+ *     baselines) keep all their state in device memory and may be recorded into a HIP graph; the ones that
+ *     synchronise, copy to the host or read events (create/destroy, poll_status, timing_read) may not.
  *   - Positions and counts are int32.  A negative entry in an index array is padding.
  *   - q is fp32 [B, Hq, D] (with an fp16 cache every |q| element must stay below 65504, the fp16 range).
  *     K and V rows are D contiguous elements (bf16, fp16 or fp32); the view
