@@ -58,6 +58,27 @@ def test_many_requests_short_contexts(j):
     _run(1000 + j, c, T=2)
 
 
+# Longer contexts and larger budgets: the dense select of the seeding step streams its scores (more than fit
+# the LDS copy), candidate sets reach the whole context, survivor lists of the filtered pass are long.
+MID = [dict(Hq=8, Hkv=2, B=1, L_range=(34317, 37140), kmax=1018, r=4, n_recent=0, n_sink=4, kv_dtype="bf16", k_dtype="fp8",
+            v_dtype="fp8", paged=(128, "block_row_head")),
+       dict(Hq=4, Hkv=1, B=2, L_range=(33000, 36000), kmax=1500, r=2, n_recent=2, n_sink=0, kv_dtype="f16", k_dtype="",
+            v_dtype="", paged=None),
+       dict(Hq=16, Hkv=8, B=1, L_range=(25591, 29514), kmax=532, r=4, n_recent=3, n_sink=2, kv_dtype="bf16", k_dtype="",
+            v_dtype="", paged=(16, "block_head_row")),
+       dict(Hq=8, Hkv=2, B=1, L_range=(9977, 12669), kmax=1265, r=2, n_recent=1, n_sink=4, kv_dtype="f32", k_dtype="",
+            v_dtype="", paged=None)]
+
+
+@pytest.mark.parametrize("j", range(len(MID)))
+def test_mid_size_configurations(j):
+    c = dict(MID[j])
+    rng = np.random.default_rng(9300 + j)
+    c["k"] = rng.integers(c["kmax"] // 2, c["kmax"] + 1, size=c["B"]).astype(np.int32)
+    c["k"][int(rng.integers(0, c["B"]))] = c["kmax"]
+    _run(2000 + j, c, T=3)
+
+
 def _run(i, c, T):
     spec = gen.tiny_spec(f"rnd{i}", B=c["B"], L=None, L_range=c["L_range"], k=c["kmax"], r=c["r"], T=T, Hq=c["Hq"],
                          Hkv=c["Hkv"], kv_dtype=c["kv_dtype"], k_dtype=c["k_dtype"], v_dtype=c["v_dtype"], seed=31000 + i,
