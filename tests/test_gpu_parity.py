@@ -652,3 +652,17 @@ def test_non_finite_queries_stay_in_bounds_and_in_their_group(small_bf16):
         prev_c, prev_d = ic, id_
     clean.close()
     dirty.close()
+
+
+def test_calibration_copy_copies():
+    """The counter-calibration kernel is a plain copy: every byte arrives, sizes that are not a multiple of
+    16 bytes are refused."""
+    from paper_2506_15704_amd.binding import LfpsError, lfps_calib_copy
+    src = torch.arange(0, 3 * 1024 * 1024 + 16, dtype=torch.int32, device=DEV)
+    dst = torch.zeros_like(src)
+    lfps_calib_copy(dst, src)
+    torch.cuda.synchronize()
+    assert torch.equal(dst, src)
+    odd_src = torch.zeros(20, dtype=torch.uint8, device=DEV)
+    with pytest.raises(LfpsError):
+        lfps_calib_copy(torch.zeros_like(odd_src), odd_src)
