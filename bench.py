@@ -558,6 +558,9 @@ def main():
         print("bench.py needs a GPU (no CPU fallback exists)", file=sys.stderr)
         sys.exit(2)
 
+    from paper_2506_15704_amd import build as lib_build
+    lib_build.ensure_built()                      # loads what is built; compiles only if nothing is
+
     if args.calib_copy:
         from paper_2506_15704_amd.binding import lfps_calib_copy
         src = torch.ones(1 << 28, dtype=torch.float32, device="cuda:0")

@@ -38,5 +38,11 @@ def build_library(verbose: bool = False) -> str:
     return LIB_PATH
 
 
+def ensure_built() -> str:
+    """For tests, the smoke run and the benchmark: compile only if no library is there yet (the binding itself
+    never builds and never falls back: without the library it raises)."""
+    return LIB_PATH if os.path.exists(LIB_PATH) else build_library()
+
+
 if __name__ == "__main__":
     print(build_library(verbose=True))

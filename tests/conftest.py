@@ -10,3 +10,6 @@ if ROOT not in sys.path:
 
 def pytest_configure(config):
     config.addinivalue_line("markers", "gpu: needs a real MI355X (run with -m gpu)")
+    # the tests load the library that is built in-tree; only when there is none do they compile it first
+    from paper_2506_15704_amd import build as lib_build
+    lib_build.ensure_built()
