@@ -111,3 +111,20 @@ def test_bench_refuses_more_than_one_gpu():
                          timeout=120)
     assert res.returncode != 0
     assert "one-GPU" in (res.stdout + res.stderr)
+
+
+def test_binding_raises_without_the_library(tmp_path):
+    """No CPU path in the product: a copy of the package without liblfps.so cannot even be imported."""
+    import os
+    import shutil
+    import subprocess
+    import sys
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    pkg = tmp_path / "paper_2506_15704_amd"
+    pkg.mkdir()
+    for name in ("__init__.py", "binding.py"):
+        shutil.copy(os.path.join(root, "paper_2506_15704_amd", name), pkg / name)
+    res = subprocess.run([sys.executable, "-c", "import paper_2506_15704_amd.binding"], capture_output=True, text=True,
+                         cwd=str(tmp_path), env={**os.environ, "PYTHONPATH": str(tmp_path)}, timeout=300)
+    assert res.returncode != 0
+    assert "ImportError" in res.stderr and "no CPU fallback" in res.stderr
