@@ -22,9 +22,17 @@ SAMPLES = {
 }
 
 
-@pytest.mark.parametrize("name", ["C1", "C2", "C3", "C4", "C5"])
+VARIANTS = {"C4-fp8k": dict(k_dtype="fp8"), "C4-fp8kv": dict(k_dtype="fp8", v_dtype="fp8"), "C4-f16": dict(kv_dtype="f16"),
+            "C4-paged16": dict(paged_block=16), "C5-paged64": dict(paged_block=64, paged_layout="block_row_head")}
+
+
+@pytest.mark.parametrize("name", ["C1", "C2", "C3", "C4", "C5"] + sorted(VARIANTS))
 def test_workload_steps_match_oracle_on_sampled_groups(name):
-    r = bench.Runner(name)
+    """The benchmark's workloads at full size, in the launch configuration bench.py times (also with the cache
+    in the other formats and as a paged pool): steps teacher-forced on sampled KV groups against the oracle."""
+    variant = VARIANTS.get(name, {})
+    name = name.split("-")[0]
+    r = bench.Runner(name, **variant)
     try:
         spec, case = r.spec, r.case
         G = spec.G
