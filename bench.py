@@ -54,6 +54,10 @@ def parse_args():
                     help="run only the score-table mode of the main workload (for profiling) and print its record")
     ap.add_argument("--calib-copy", action="store_true",
                     help="run only the plain copy kernel (1 GiB, 10 launches): the known-traffic reference for rocprofv3 --pmc")
+    ap.add_argument("--sweep", action="store_true",
+                    help="run only a grid of batch sizes and context lengths with the C4 recipe and print its record")
+    ap.add_argument("--sweep-batches", default="1,4,16,32", help="batch sizes of --sweep")
+    ap.add_argument("--sweep-contexts", default="32768,131072,524288", help="context lengths of --sweep")
     ap.add_argument("--cpu-seconds", type=float, default=12.0, help="CPU-oracle sample budget")
     return ap.parse_args()
 
@@ -62,7 +66,7 @@ class Runner:
     """Device state of one workload and the step loop."""
 
     def __init__(self, name, table_mode=False, n_sink=0, gated=False, paged_block=0, paged_layout="block_head_row",
-                 k_dtype="", v_dtype="", kv_dtype=""):
+                 k_dtype="", v_dtype="", kv_dtype="", override=None):
         import numpy as np
         import torch
 
@@ -72,6 +76,9 @@ class Runner:
 
         self.torch, self.np = torch, np
         self.spec = spec = gen.WORKLOADS[name]
+        if override:         # the same recipe at another batch size / context length / budget (--sweep)
+            import dataclasses
+            self.spec = spec = dataclasses.replace(spec, **override)
         if k_dtype:          # the same workload with the keys stored in another format
             import dataclasses
             self.spec = spec = dataclasses.replace(spec, name=f"{name}-{k_dtype}k" + ("v" if v_dtype else ""),
@@ -298,8 +305,8 @@ def algorithmic_bytes_score(spec, case, cnts, filtered):
     return rows * (spec.D * e + 4 + 4 * spec.G) + cnts.shape[1] * cnts.shape[2] * per_group
 
 
-def measure(name, steps, warmup, with_baselines=True, use_graph=True):
-    r = Runner(name)
+def measure(name, steps, warmup, with_baselines=True, use_graph=True, override=None):
+    r = Runner(name, override=override)
     spec = r.spec
     if steps <= 0:
         steps = max(1, spec.T - warmup)
@@ -338,7 +345,7 @@ def measure(name, steps, warmup, with_baselines=True, use_graph=True):
                           "GB_per_s_at_union_bytes": round(lower / (at_us * 1e-6) / 1e9, 1) if at_us > 0 else None,
                           "GB_per_s_at_per_head_bytes": round(upper / (at_us * 1e-6) / 1e9, 1) if at_us > 0 else None}
     if with_baselines:
-        reps = 5 if name in ("C4", "C5") else 20
+        reps = 5 if name in ("C4", "C5") or override else 20
         exact = r.time_baseline("exact", reps)
         full = r.time_baseline("full", reps)
         res.update({"exact_topk_ms": round(exact * 1e3, 4), "full_attn_ms": round(full * 1e3, 4),
@@ -352,6 +359,26 @@ def measure(name, steps, warmup, with_baselines=True, use_graph=True):
         res["roofline"]["frac_of_stream_reference"] = round(achieved / stream_gbs, 4)
     r.close()
     return res, r.case
+
+
+def measure_sweep(batches, contexts, steps, warmup):
+    """The C4 recipe (bf16, r = 4, budget = context / 64) over a grid of batch sizes and context lengths: how the step,
+    its dominant kernel and the two baselines scale with B x L on this GPU."""
+    rows = []
+    for L in contexts:
+        for B in batches:
+            ov = dict(name=f"C4-B{B}-L{L}", B=B, L=L, k=max(64, L // 64), T=max(steps + warmup, 4))
+            res, _ = measure("C4", steps, warmup, with_baselines=True, use_graph=False, override=ov)
+            rows.append({"B": B, "L": L, "k": ov["k"], "ms_per_step": round(res["ms_per_step"], 4),
+                         "steps_per_s": round(res["steps_per_s"], 1), "cand_frac": res["cand_frac"],
+                         "score_kernel": res["roofline"]["kernel"], "score_kernel_us": res["roofline"]["avg_launch_us"],
+                         "score_kernel_GB_per_s": res["roofline"]["achieved"],
+                         "score_kernel_frac_of_peak": res["roofline"]["frac"],
+                         "exact_topk_ms": res["exact_topk_ms"], "full_attn_ms": res["full_attn_ms"],
+                         "speedup_vs_exact_topk": res["speedup_vs_exact_topk"],
+                         "speedup_vs_full_attn": res["speedup_vs_full_attn"]})
+            print(json.dumps(rows[-1]), file=sys.stderr, flush=True)
+    return rows
 
 
 def measure_paged(name, steps, warmup, block_size=16, layout="block_head_row"):
@@ -576,6 +603,11 @@ def main():
                           "avg_ms": round(dt * 1e3, 4), "GB_per_s_read_plus_write": round(2 * (1 << 30) / dt / 1e9, 1)}))
         return
 
+    if args.sweep:
+        rows = measure_sweep([int(x) for x in args.sweep_batches.split(",")], [int(x) for x in args.sweep_contexts.split(",")],
+                             args.steps if args.steps > 0 else 6, args.warmup)
+        print(json.dumps({"sweep": "C4 recipe (bf16, r=4, k=L/64)", "rows": rows}), flush=True)
+        return
     if args.table_only:
         print(json.dumps({"workload": args.workload, "score_table_mode": measure_tables(args.workload, args.steps, args.warmup)}),
               flush=True)

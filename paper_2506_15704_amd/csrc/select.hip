@@ -523,7 +523,11 @@ static int select_cache_elems(const Shape& s, bool gather) {
 int filter_list_cap(const Shape& s) {
   int cap = 4 * s.kmax;
   if (cap < 1024) cap = 1024;
-  if (cap > 7680) cap = 7680;   // 60 KB of LDS: two workgroups per CU
+  if (cap > 7680) {             // 60 KB of LDS: two workgroups per CU ...
+    cap = 7680;
+    // ... unless the budget itself needs more room: twice the budget, up to 128 KB (one workgroup per CU)
+    if (2 * s.kmax > cap) cap = 2 * s.kmax < 16384 ? 2 * s.kmax : 16384;
+  }
   return cap;
 }
 

@@ -67,6 +67,9 @@ MID = [dict(Hq=8, Hkv=2, B=1, L_range=(34317, 37140), kmax=1018, r=4, n_recent=0
        dict(Hq=16, Hkv=8, B=1, L_range=(25591, 29514), kmax=532, r=4, n_recent=3, n_sink=2, kv_dtype="bf16", k_dtype="",
             v_dtype="", paged=(16, "block_head_row")),
        dict(Hq=8, Hkv=2, B=1, L_range=(9977, 12669), kmax=1265, r=2, n_recent=1, n_sink=4, kv_dtype="f32", k_dtype="",
+            v_dtype="", paged=None),
+       # a budget beyond what the filtered select holds at two workgroups per CU: the larger survivor list
+       dict(Hq=4, Hkv=1, B=1, L_range=(21000, 22000), kmax=4500, r=1, n_recent=1, n_sink=0, kv_dtype="bf16", k_dtype="",
             v_dtype="", paged=None)]
 
 
