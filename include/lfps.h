@@ -160,7 +160,8 @@ int lfps_sparse_attn(lfps_ctx* ctx, const float* q, const lfps_kv* kv, const int
  * score of the PREVIOUS lfps_step call on this context minus a margin (the context remembers one
  * float per head); a head for which that leaves fewer than k rows is rescored without the filter
  * in the same call.  The result is therefore the same exact Top-k over the candidates whatever
- * the remembered value is; only the time differs.  lfps_set_filter(ctx, 0) turns the filter off,
+ * the remembered value is; only the time differs.  (A context whose max_k exceeds ~13 000 starts with the
+ * filter off: a head's survivors would not fit the select's on-chip list.)  lfps_set_filter(ctx, 0) turns the filter off,
  * lfps_reset_history forgets the remembered scores (e.g. when the context moves to other requests). */
 int lfps_step(lfps_ctx* ctx, const float* q, const lfps_kv* kv, const int32_t* prev_topk, const int32_t* k,
               int32_t* topk_idx, float* topk_score, float* out, void* stream);

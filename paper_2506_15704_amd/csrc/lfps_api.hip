@@ -305,7 +305,9 @@ int lfps_create(const lfps_config* cfg, lfps_ctx** out) {
   }
   c->gate = (int32_t*)p;
   c->nseg = z.nseg;
-  c->filter_on = z.slot_b ? 1 : 0;
+  // The filtered pass pays off only if a head's survivors (about 1.25 x its budget) fit the select's list; with a
+  // budget too large for that every head would be rescored anyway, so such a context starts with the filter off.
+  c->filter_on = (z.slot_b && (int64_t)cfg->max_k + cfg->max_k / 4 <= filter_list_cap(s)) ? 1 : 0;
   e = hipMemset(c->flags, 0, 256);
   if (e == hipSuccess) e = hipMemset(c->seg_count, 0, (size_t)(z.seg_b + z.thr_b + z.redo_b));   // counts, marks, line length
   if (e == hipSuccess) e = hipMemset(c->thr_state, 0xFF, (size_t)z.thr_b);   // all-ones = NaN: "no history"

@@ -95,6 +95,7 @@ hipError_t launch_group_score(const Shape& s, int dtype, const float* q, const K
 // equal parts, one per wave; the part size of a step is written to *seg_rows_out by the scoring
 // pass and read by the select, which also resets *line_total; see score.hip.
 int filter_nseg(const Shape& s);
+int filter_list_cap(const Shape& s);   // survivors per head the filtered select can hold
 hipError_t filter_score_blocks(const Shape& s, int k_kind, int out[2]);
 hipError_t launch_filter_score(const Shape& s, const float* q, const KvView& kv, const int32_t* cand,
                                const int32_t* cand_count, const int64_t* group_start, const int64_t* line_total,

@@ -70,6 +70,9 @@ MID = [dict(Hq=8, Hkv=2, B=1, L_range=(34317, 37140), kmax=1018, r=4, n_recent=0
             v_dtype="", paged=None),
        # a budget beyond what the filtered select holds at two workgroups per CU: the larger survivor list
        dict(Hq=4, Hkv=1, B=1, L_range=(21000, 22000), kmax=4500, r=1, n_recent=1, n_sink=0, kv_dtype="bf16", k_dtype="",
+            v_dtype="", paged=None),
+       # a budget that no survivor list can hold: such a context runs without the filtered pass
+       dict(Hq=4, Hkv=1, B=1, L_range=(15000, 15500), kmax=14000, r=1, n_recent=1, n_sink=2, kv_dtype="bf16", k_dtype="",
             v_dtype="", paged=None)]
 
 
