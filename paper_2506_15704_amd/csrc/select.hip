@@ -108,12 +108,15 @@ __device__ __forceinline__ void find_bin(SelectShared<NT>& sm, uint32_t need, in
 // `slot_of` (LDS, or NULL for identity) maps an element of the scored list to its candidate slot;
 // `cbg` (or NULL for identity) maps a candidate slot to its position.  `thr_out` receives the
 // k-th largest score.
-template <bool CACHED, int NT>
+// kHaveRange: the caller has already seen every element (it filled the cache) and passes its own
+// thread's smallest and largest in pre_lo / pre_hi, which saves the first pass over the data.
+template <bool CACHED, int NT, bool kHaveRange = false>
 __device__ __forceinline__ void select_body(SelectShared<NT>& sm, float* __restrict__ cache,
                                             const float* __restrict__ sc, int c, int ksel,
                                             const int32_t* __restrict__ slot_of, const int32_t* __restrict__ cbg,
                                             int32_t* __restrict__ oi, float* __restrict__ os,
-                                            float* __restrict__ thr_out) {
+                                            float* __restrict__ thr_out, float pre_lo = FLT_MAX,
+                                            float pre_hi = -FLT_MAX) {
   constexpr int kSelWaves = NT / 64, kBins = 2 * NT, kListCap = NT;
   const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
   const int chunk = (((c + kSelWaves - 1) / kSelWaves) + 63) & ~63;
@@ -128,8 +131,10 @@ __device__ __forceinline__ void select_body(SelectShared<NT>& sm, float* __restr
       if (i < r1) cache[i] = sanitize(sc[i]);
     }
   }
-  float lo = FLT_MAX, hi = -FLT_MAX;
-  LFPS_FOR_EACH(lo = in ? fminf(lo, x) : lo; hi = in ? fmaxf(hi, x) : hi;)
+  float lo = pre_lo, hi = pre_hi;
+  if constexpr (!kHaveRange) {
+    LFPS_FOR_EACH(lo = in ? fminf(lo, x) : lo; hi = in ? fmaxf(hi, x) : hi;)
+  }
 #pragma unroll
   for (int d = 1; d < 64; d <<= 1) {
     lo = fminf(lo, __shfl_xor(lo, d));
@@ -475,6 +480,7 @@ __global__ __launch_bounds__(kFilterSelThreads) void k_filter_select(Shape s, co
   int top = 1;
   while (top < np) top <<= 1;
   constexpr int kGatherBatch = 12;
+  float my_lo = FLT_MAX, my_hi = -FLT_MAX;             // range of the elements this thread copies
   for (int e0 = tid; e0 < n; e0 += kGatherBatch * NT) {
     int pc[kGatherBatch];
 #pragma unroll
@@ -504,13 +510,16 @@ __global__ __launch_bounds__(kFilterSelThreads) void k_filter_select(Shape s, co
     for (int u = 0; u < kGatherBatch; ++u) {
       const int e = e0 + u * NT;
       if (e < n) {
-        cache[e] = sanitize(v[u]);
+        const float x = sanitize(v[u]);
+        cache[e] = x;
         lslot[e] = ps[u];
+        my_lo = fminf(my_lo, x);
+        my_hi = fmaxf(my_hi, x);
       }
     }
   }
   __syncthreads();
-  select_body<true, NT>(sm, cache, nullptr, n, ksel, lslot, nullptr, oi, os, thr_state + bh);
+  select_body<true, NT, true>(sm, cache, nullptr, n, ksel, lslot, nullptr, oi, os, thr_state + bh, my_lo, my_hi);
 }
 
 
