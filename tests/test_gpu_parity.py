@@ -666,3 +666,49 @@ def test_calibration_copy_copies():
     odd_src = torch.zeros(20, dtype=torch.uint8, device=DEV)
     with pytest.raises(LfpsError):
         lfps_calib_copy(torch.zeros_like(odd_src), odd_src)
+
+
+def test_two_contexts_on_two_streams(small_bf16, small_fp8):
+    """Contexts share nothing: two of them stepping at the same time on two streams (default priority) give what
+    each gives alone."""
+    cases = (small_bf16, small_fp8)
+    alone = []
+    for dc in cases:
+        shp = (dc.spec.B, dc.spec.Hq, dc.case.kmax)
+        ctx = dc.make_ctx()
+        prev = torch.zeros(shp, dtype=torch.int32, device=DEV)
+        ctx.lfps_exact_topk(dc.q(0), ctx.kv_view(dc.K, dc.V, dc.seq_lens(0)), dc.k, prev)
+        outs = []
+        for t in (1, 2, 3):
+            idx = torch.zeros(shp, dtype=torch.int32, device=DEV)
+            out = torch.zeros((dc.spec.B, dc.spec.Hq, dc.spec.D), dtype=torch.float32, device=DEV)
+            ctx.lfps_step(dc.q(t), ctx.kv_view(dc.K, dc.V, dc.seq_lens(t)), prev, dc.k, idx, out)
+            outs.append((idx, out))
+            prev = idx
+        torch.cuda.synchronize()
+        alone.append(outs)
+        ctx.close()
+    streams = [torch.cuda.Stream(device=DEV) for _ in cases]
+    ctxs, prevs, together = [], [], [[], []]
+    for i, dc in enumerate(cases):
+        shp = (dc.spec.B, dc.spec.Hq, dc.case.kmax)
+        ctxs.append(dc.make_ctx())
+        prevs.append(torch.zeros(shp, dtype=torch.int32, device=DEV))
+        ctxs[i].lfps_exact_topk(dc.q(0), ctxs[i].kv_view(dc.K, dc.V, dc.seq_lens(0)), dc.k, prevs[i])
+    inputs = [[(dc.q(t), dc.seq_lens(t)) for t in (1, 2, 3)] for dc in cases]     # made on the default stream
+    torch.cuda.synchronize()
+    for t in range(3):
+        for i, dc in enumerate(cases):
+            with torch.cuda.stream(streams[i]):
+                shp = (dc.spec.B, dc.spec.Hq, dc.case.kmax)
+                idx = torch.zeros(shp, dtype=torch.int32, device=DEV)
+                out = torch.zeros((dc.spec.B, dc.spec.Hq, dc.spec.D), dtype=torch.float32, device=DEV)
+                q, sl = inputs[i][t]
+                ctxs[i].lfps_step(q, ctxs[i].kv_view(dc.K, dc.V, sl), prevs[i], dc.k, idx, out)
+                together[i].append((idx, out))
+                prevs[i] = idx
+    torch.cuda.synchronize()
+    for i in range(2):
+        for t in range(3):
+            assert torch.equal(together[i][t][0], alone[i][t][0]) and torch.equal(together[i][t][1], alone[i][t][1]), (i, t)
+        ctxs[i].close()
