@@ -39,7 +39,8 @@ Readings where the paper is silent (the same ones the library takes):
 Pins (tests/test_tables_oracle_pins.py): scipy's kurtosis, closed forms of kappa for equal spikes,
 scale invariance of tau's selection, Eq. 12 (table sums follow S' = gamma S + 1/2 and start at
 1/(2(1 - gamma))), geometric-series fixed points of Eq. 10 for a constant selection, the diagonal
-motion of slash history, brute force of Eq. 7/9 by per-position predicates, the printed offsets.
+motion of slash history, brute force of Eq. 7/9 by per-position predicates, the printed offsets, the union over
+the heads of a KV group written out by hand and by a per-position predicate over every head.
 """
 from __future__ import annotations
 

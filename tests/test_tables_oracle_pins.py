@@ -123,6 +123,65 @@ def test_group_candidates_add_recent_and_sink_rows():
     np.testing.assert_array_equal(c, [0, 1, 2, 48, 49])
 
 
+def test_group_candidates_are_the_union_over_the_heads_written_out_by_hand():
+    """Two heads of one KV group whose tables select disjoint positions (a vertical spike for the
+    first head, a slash spike for the second): the group's set is the sorted union of both heads'
+    sets, written out by hand; dropping either head loses its positions."""
+    n = 64
+    # head 0: one vertical spike at 10, the neighbourhood 8..13 above the mean through the slash table
+    ver0, sla0 = np.zeros(n), np.full(n, 1.0)
+    ver0[10] = 500.0
+    sla0[8:14] += 1e-3
+    # head 1: one slash spike at 40; only 40 and 41 clear a mean (through the vertical table)
+    ver1, sla1 = np.full(n, 1.0), np.zeros(n)
+    sla1[40] = 300.0
+    ver1[40:42] += 1e-3
+    # r = 2: offsets -2 .. 3 around each initial candidate, then the mean filter
+    want0 = [8, 9, 10, 11, 12, 13]
+    want1 = [40, 41]
+    np.testing.assert_array_equal(tor.head_candidates(ver0, sla0, n, 0.2, 2), want0)
+    np.testing.assert_array_equal(tor.head_candidates(ver1, sla1, n, 0.2, 2), want1)
+    got = tor.group_candidates([(ver0, sla0), (ver1, sla1)], n, 0.2, 2, n_recent=1, n_sink=0)
+    np.testing.assert_array_equal(got, want0 + want1 + [n - 1])
+    # the order of the heads does not matter, and a single head gives only its own positions
+    np.testing.assert_array_equal(tor.group_candidates([(ver1, sla1), (ver0, sla0)], n, 0.2, 2, 1, 0), got)
+    np.testing.assert_array_equal(tor.group_candidates([(ver1, sla1)], n, 0.2, 2, 1, 0), want1 + [n - 1])
+
+
+@pytest.mark.parametrize("seed", range(4))
+def test_group_candidates_by_per_position_brute_force_over_all_heads(seed):
+    """j is in the group's set iff it is a newest / sink row or SOME head keeps it (that head's own
+    thresholds and means): a per-position predicate over every head, G = 2..4, overlapping sets."""
+    rng = np.random.default_rng(700 + seed)
+    G, n, r, a = int(rng.integers(2, 5)), int(rng.integers(40, 160)), int(rng.integers(0, 4)), 0.25
+    n_sink, n_recent = int(rng.integers(0, 3)), int(rng.integers(0, 3))
+    tables = []
+    for _ in range(G):
+        ver, sla = rng.gamma(0.12, size=n), rng.gamma(0.12, size=n)
+        ver[:n_sink] = 0
+        sla[:n_sink] = 0
+        tables.append((ver, sla))
+
+    def head_keeps(ver, sla, j):
+        xv, xs = ver[n_sink:n], sla[n_sink:n]
+
+        def t(x):
+            d = x - x.mean()
+            return a * x.mean() * (d ** 2).sum() ** 2 / (d ** 4).sum()
+
+        tv, ts = t(xv), t(xs)
+        in_c0 = lambda i: n_sink <= i < n and (ver[i] > tv or sla[i] > ts)
+        return n_sink <= j < n and (ver[j] > xv.mean() or sla[j] > xs.mean()) and \
+            any(in_c0(j - d) for d in range(-r, r + 2))
+
+    want = [j for j in range(n)
+            if j < n_sink or j >= n - n_recent or any(head_keeps(v, s, j) for (v, s) in tables)]
+    got = tor.group_candidates(tables, n, a, r, n_recent, n_sink)
+    np.testing.assert_array_equal(got, np.array(want, dtype=np.int64))
+    per_head = [set(tor.head_candidates(v, s, n, a, r, n_sink).tolist()) for (v, s) in tables]
+    assert any(per_head[h] - per_head[0] for h in range(1, G)), "the heads must differ for the pin to bite"
+
+
 # ----------------------------------------------------------------------------- Eq. 4 and Eq. 12
 def test_init_tables_sum_and_diagonal_alignment():
     rng = np.random.default_rng(9)
@@ -334,5 +393,11 @@ def test_gated_step_bypasses_sparse_heads_and_leaves_their_tables():
     # the others behave as in table_step over the candidates of the live heads only
     ref = tor.table_step(q[[0, 2]], K, V, [tables[0], tables[2]], n, k, 1, 0.2, 0.9, n_recent=1, n_sink=n_sink)
     np.testing.assert_array_equal(res["cand"], ref["cand"])
+    # ... which is the union of the live heads' own sets (each pinned by brute force above) with the newest row
+    # and the sinks; the bypassed head's positions are not proposed
+    own = [set(tor.head_candidates(t[0], t[1], n, 0.2, 1, n_sink).tolist()) for t in tables]
+    want = own[0] | own[2] | {n - 1} | set(range(n_sink))
+    assert sorted(want) == res["cand"].tolist()
+    assert own[1] - want, "head 1 must have positions of its own for this to test anything"
     np.testing.assert_array_equal(res["topk_idx"][2], ref["topk_idx"][1])
     np.testing.assert_allclose(res["out"][0], ref["out"][0], rtol=1e-14)
