@@ -25,7 +25,9 @@
  *     baselines) keep all their state in device memory and may be recorded into a HIP graph; the ones that
  *     synchronise, copy to the host or read events (create/destroy, poll_status, timing_read) may not.
  *   - Positions and counts are int32.  A negative entry in an index array is padding.
- *   - q is fp32 [B, Hq, D] (with an fp16 cache every |q| element must stay below 65504, the fp16 range).
+ *   - q is fp32 [B, Hq, D].  With an fp16 cache every |q| element must stay below 65504, the fp16 range: an
+ *     element beyond it is clamped to +-65504 by the scoring kernels (the scores stay finite but belong to the
+ *     clamped query) and LFPS_FLAG_Q_RANGE is raised.
  *     K and V rows are D contiguous elements (bf16, fp16 or fp32); the view
  *     struct gives the element strides between requests, KV heads and rows.
  *   - Argument errors that the host can see (NULL pointers, bad shapes/strides) return
@@ -135,7 +137,9 @@ int lfps_candidates(lfps_ctx* ctx, const int32_t* prev_topk, const int32_t* k, c
 /* S2 + S3 — exact dot products over the candidates only, then the k best per query head
  * (Alg. 1 line 8; Sec. 1 Steps 1-2 restricted to the candidate set).
  * score(b,h,j) = q[b,h] . K[b,g(h),cand[b,g,j]] / sqrt(D), fp32 accumulate.
- *   cand, cand_count  as produced by lfps_candidates (ascending positions in [0, n_b))
+ *   cand, cand_count  as produced by lfps_candidates (ascending positions in [0, n_b)).  An entry outside
+ *              [0, n_b) scores -inf: it is taken only when fewer than k_b valid candidates exist, and then
+ *              written as -1 (score 0) where it would stand.
  *   topk_idx   [B, Hq, kmax] int32 out: the min(k_b, c) selected positions, ascending; rest -1.
  *              Equal scores at the cut are resolved towards the lower position.
  *   topk_score [B, Hq, kmax] fp32 out or NULL: the score of each selected position (0 for padding)
@@ -229,6 +233,8 @@ int lfps_table_step_gated(lfps_ctx* ctx, const float* q, const lfps_kv* kv, cons
                           const float* vbar, const float* sigma2_hat, int32_t n_local, float eps, int32_t* topk_idx,
                           float* topk_score, float* out, int32_t* gate_out, void* stream);
 
+/* Switches the score filter of the chained steps on or off (on: only for caches it exists for, bf16 / fp16 / FP8
+ * keys; a no-op otherwise).  lfps_reset_history makes every head start without a remembered score. */
 int lfps_set_filter(lfps_ctx* ctx, int32_t on);
 int lfps_reset_history(lfps_ctx* ctx, void* stream);
 /* Copies the candidate counts [B, Hkv] of the last lfps_step call into dst (device, int32),
@@ -239,7 +245,14 @@ int lfps_copy_cand_count(lfps_ctx* ctx, int32_t* dst, void* stream);
  * word to *flags (host) and clears it. */
 #define LFPS_FLAG_CAND_OVERFLOW 1
 #define LFPS_FLAG_TABLE_FULL 2      /* a table update was skipped: max_seq_len - 1 updates since the last import / init */
+#define LFPS_FLAG_Q_RANGE 4         /* fp16 cache: a query element beyond +-65504 was clamped to the fp16 range by a
+                                       scoring kernel (the scores of that head are those of the clamped query) */
 int lfps_poll_status(lfps_ctx* ctx, int32_t* flags, void* stream);
+/* Heads that the filtered scoring pass of lfps_step / lfps_table_step left with fewer than k rows (or more than the
+ * select's list holds) and that were therefore rescored without the filter, since the last call (host out-pointer;
+ * synchronises `stream` and clears the count).  Results do not depend on it: it tells how often the remembered
+ * k-th score was of no use (first step after a reset, a sudden change of the query). */
+int lfps_poll_rescored(lfps_ctx* ctx, int32_t* n_heads, void* stream);
 
 /* Per-kernel timing for benchmarks.  While enabled, every kernel launch is bracketed by HIP
  * events on the launch stream (at most LFPS_TIMING_MAX_LAUNCHES launches between reads; later

@@ -21,6 +21,7 @@ _KV_DTYPES = {"f32": (LFPS_F32, torch.float32), "bf16": (LFPS_BF16, torch.bfloat
 LFPS_OK, LFPS_EINVAL, LFPS_ECAP, LFPS_EHIP, LFPS_ENOMEM = 0, -1, -2, -3, -4
 LFPS_FLAG_CAND_OVERFLOW = 1
 LFPS_FLAG_TABLE_FULL = 2
+LFPS_FLAG_Q_RANGE = 4
 N_KERNELS = 13
 
 
@@ -66,6 +67,7 @@ def _load() -> ctypes.CDLL:
         "lfps_full_attn_decode": (ctypes.c_int, [P, VP, ctypes.POINTER(lfps_kv), VP, VP]),
         "lfps_exact_topk": (ctypes.c_int, [P, VP, ctypes.POINTER(lfps_kv), VP, VP, VP, VP]),
         "lfps_poll_status": (ctypes.c_int, [P, ctypes.POINTER(I32), VP]),
+        "lfps_poll_rescored": (ctypes.c_int, [P, ctypes.POINTER(I32), VP]),
         "lfps_timing_enable": (ctypes.c_int, [P, I32]),
         "lfps_timing_read": (ctypes.c_int, [P, ctypes.POINTER(ctypes.c_float), ctypes.POINTER(I32), VP]),
         "lfps_kernel_name": (ctypes.c_char_p, [I32]),
@@ -367,6 +369,11 @@ class Lfps:
         flags = ctypes.c_int32(0)
         self._check(_lib.lfps_poll_status(self._ctx, ctypes.byref(flags), self._stream()))
         return flags.value
+
+    def lfps_poll_rescored(self) -> int:
+        n = ctypes.c_int32(0)
+        self._check(_lib.lfps_poll_rescored(self._ctx, ctypes.byref(n), self._stream()))
+        return n.value
 
     def lfps_timing_enable(self, on: bool):
         self._check(_lib.lfps_timing_enable(self._ctx, int(bool(on))))

@@ -38,7 +38,7 @@ struct lfps_ctx {
   int32_t* cand_count; // [B, Hkv]
   float* sel_score;    // [B, Hq, kmax]
   float* part;         // split partials of the full-attention baseline
-  int32_t* flags;      // [0] status flags, [1] part size chosen by the last filtered scoring pass
+  int32_t* flags;      // [0] status flags, [1] part size chosen by the last filtered scoring pass, [2] heads rescored since the last poll
   int64_t ws_bytes;
   // timing
   int timing_on;
@@ -316,8 +316,10 @@ int lfps_create(const lfps_config* cfg, lfps_ctx** out) {
   if (e == hipSuccess) e = hipMemset(c->gate, 0, (size_t)z.thr_b);
   if (e == hipSuccess) e = configure_candidates(s);
   if (e == hipSuccess) e = configure_select(s);
-  if (e == hipSuccess && c->filter_on)
+  // the launch size of the filtered pass is needed whenever that pass can be switched on (lfps_set_filter)
+  if (e == hipSuccess && c->slot)
     e = filter_score_blocks(s, cfg->k_fp8 ? 1 : (cfg->kv_dtype == LFPS_F16 ? 2 : 0), c->filter_blocks);
+  if (e == hipSuccess && c->slot && (c->filter_blocks[0] < 1 || c->filter_blocks[1] < 1)) e = hipErrorLaunchFailure;
   if (e == hipSuccess) e = hipDeviceSynchronize();
   if (e != hipSuccess) {
     snprintf(g_create_err, sizeof g_create_err, "workspace setup: %s", hipGetErrorString(e));
@@ -375,9 +377,10 @@ int lfps_score_topk(lfps_ctx* ctx, const float* q, const lfps_kv* kv, const int3
   float* sc = cand_score ? cand_score : ctx->score;
   const int64_t stride = cand_score ? s.cand_cap : s.score_stride;
   LAUNCH(ctx, LFPS_KERNEL_GATHER_SCORE, st,
-         launch_group_score(s, ctx->cfg.kv_dtype, q, v, cand, cand_count, sc, stride, nullptr, st));
+         launch_group_score(s, ctx->cfg.kv_dtype, q, v, cand, cand_count, sc, stride, nullptr, ctx->flags, st));
   LAUNCH(ctx, LFPS_KERNEL_SELECT, st,
-         launch_select(s, sc, stride, cand, cand_count, k, topk_idx, topk_score, nullptr, nullptr, nullptr, st));
+         launch_select(s, sc, stride, cand, cand_count, k, topk_idx, topk_score, nullptr, nullptr, nullptr, v.seq_lens,
+                       st));
   return LFPS_OK;
 }
 
@@ -413,20 +416,20 @@ static int score_and_select(lfps_ctx* ctx, const float* q, const KvView& v, cons
     LAUNCH(ctx, LFPS_KERNEL_FILTER_SCORE, st,
            launch_filter_score(s, q, v, ctx->cand, ctx->cand_count, ctx->group_start, line_total, ctx->thr_state,
                                kFilterMargin, ctx->score, ctx->slot, s.score_stride, ctx->seg_count, ctx->flags + 1,
-                               ctx->filter_blocks[v.page.table ? 1 : 0], st));
+                               ctx->filter_blocks[v.page.table ? 1 : 0], ctx->flags, st));
     LAUNCH(ctx, LFPS_KERNEL_FILTER_SELECT, st,
            launch_filter_select(s, ctx->score, ctx->slot, s.score_stride, ctx->seg_count, ctx->flags + 1, ctx->nseg,
                                 ctx->cand_count, ctx->group_start, line_total, k, topk_idx, sel, ctx->thr_state,
-                                ctx->redo_g, ctx->redo_h, skip_if, st));
+                                ctx->redo_g, ctx->redo_h, skip_if, ctx->flags + 2, st));
     only_g = ctx->redo_g;
     only_h = ctx->redo_h;
   }
   LAUNCH(ctx, LFPS_KERNEL_GATHER_SCORE, st,
          launch_group_score(s, ctx->cfg.kv_dtype, q, v, ctx->cand, ctx->cand_count, ctx->score, s.score_stride,
-                            only_g, st));
+                            only_g, ctx->flags, st));
   LAUNCH(ctx, LFPS_KERNEL_SELECT, st,
          launch_select(s, ctx->score, s.score_stride, ctx->cand, ctx->cand_count, k, topk_idx, sel, only_h,
-                       ctx->thr_state, skip_if, st));
+                       ctx->thr_state, skip_if, nullptr, st));
   return LFPS_OK;
 }
 
@@ -480,10 +483,11 @@ int lfps_exact_topk(lfps_ctx* ctx, const float* q, const lfps_kv* kv, const int3
   hipStream_t st = (hipStream_t)stream;
   const Shape& s = ctx->shape;
   LAUNCH(ctx, LFPS_KERNEL_DENSE_SCORE, st,
-         launch_group_score(s, ctx->cfg.kv_dtype, q, v, nullptr, nullptr, ctx->score, s.score_stride, nullptr, st));
+         launch_group_score(s, ctx->cfg.kv_dtype, q, v, nullptr, nullptr, ctx->score, s.score_stride, nullptr, ctx->flags,
+                            st));
   LAUNCH(ctx, LFPS_KERNEL_SELECT, st,
          launch_select(s, ctx->score, s.score_stride, nullptr, v.seq_lens, k, topk_idx, topk_score, nullptr, nullptr,
-                       nullptr, st));
+                       nullptr, nullptr, st));
   return LFPS_OK;
 }
 
@@ -515,7 +519,7 @@ int lfps_tables_init(lfps_ctx* ctx, const float* q_hist, int32_t n_queries, cons
   for (int j = 1; j <= n_queries; ++j) {
     LAUNCH(ctx, LFPS_KERNEL_DENSE_SCORE, st,
            launch_group_score(s, ctx->cfg.kv_dtype, q_hist + (int64_t)(j - 1) * q_stride, v, nullptr, nullptr, ctx->score,
-                              s.score_stride, nullptr, st));
+                              s.score_stride, nullptr, ctx->flags, st));
     hipError_t e = launch_table_init(s, ctx->tab_ver, ctx->tab_sla, v.seq_lens, ctx->score, s.score_stride,
                                      (double)ctx->cfg.table_decay, j, n_queries, st);
     if (e != hipSuccess) return fail(ctx, LFPS_EHIP, "lfps_tables_init", e);
@@ -633,7 +637,8 @@ int lfps_priors(lfps_ctx* ctx, const float* q, const lfps_kv* kv, float* kbar, f
   hipError_t e = launch_prior_means(s, ctx->cfg.kv_dtype, v, kbar, vbar, st);
   if (e != hipSuccess) return fail(ctx, LFPS_EHIP, "lfps_priors (means)", e);
   LAUNCH(ctx, LFPS_KERNEL_DENSE_SCORE, st,
-         launch_group_score(s, ctx->cfg.kv_dtype, q, v, nullptr, nullptr, ctx->score, s.score_stride, nullptr, st));
+         launch_group_score(s, ctx->cfg.kv_dtype, q, v, nullptr, nullptr, ctx->score, s.score_stride, nullptr, ctx->flags,
+                            st));
   e = launch_prior_variance(s, q, v.seq_lens, ctx->score, s.score_stride, sigma2_hat, st);
   if (e != hipSuccess) return fail(ctx, LFPS_EHIP, "lfps_priors (variance)", e);
   return LFPS_OK;
@@ -711,6 +716,17 @@ int lfps_poll_status(lfps_ctx* ctx, int32_t* flags, void* stream) {
   if (e == hipSuccess) e = hipMemsetAsync(ctx->flags, 0, 4, st);
   if (e == hipSuccess) e = hipStreamSynchronize(st);
   if (e != hipSuccess) return fail(ctx, LFPS_EHIP, "lfps_poll_status", e);
+  return LFPS_OK;
+}
+
+int lfps_poll_rescored(lfps_ctx* ctx, int32_t* n_heads, void* stream) {
+  if (!ctx) return LFPS_EINVAL;
+  if (!n_heads) return fail(ctx, LFPS_EINVAL, "lfps_poll_rescored: NULL argument");
+  hipStream_t st = (hipStream_t)stream;
+  hipError_t e = hipMemcpyAsync(n_heads, ctx->flags + 2, 4, hipMemcpyDeviceToHost, st);
+  if (e == hipSuccess) e = hipMemsetAsync(ctx->flags + 2, 0, 4, st);
+  if (e == hipSuccess) e = hipStreamSynchronize(st);
+  if (e != hipSuccess) return fail(ctx, LFPS_EHIP, "lfps_poll_rescored", e);
   return LFPS_OK;
 }
 

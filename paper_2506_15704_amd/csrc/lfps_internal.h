@@ -83,9 +83,11 @@ hipError_t launch_candidates(const Shape& s, const int32_t* prev_topk, const int
 // Scores of candidate rows (cand != NULL) or of all rows 0..n_b-1 (cand == NULL) for the G heads
 // of each KV group.  score is [B, Hq, score_stride].
 // only_if [B,Hkv] (or NULL): groups whose entry is 0 are skipped.
+// flags: the context's status word (LFPS_FLAG_Q_RANGE is raised there).  A candidate entry outside [0, n_b)
+// scores -inf.
 hipError_t launch_group_score(const Shape& s, int dtype, const float* q, const KvView& kv, const int32_t* cand,
                               const int32_t* cand_count, float* score, int64_t score_stride, const int32_t* only_if,
-                              hipStream_t st);
+                              int32_t* flags, hipStream_t st);
 
 // Filtered scoring (bf16, fp16 or FP8 keys; the kernel keeps its first name, k_filter_score_bf16): per
 // head only rows with score >= thr_state[b,h] - margin are kept, as
@@ -101,21 +103,23 @@ hipError_t launch_filter_score(const Shape& s, const float* q, const KvView& kv,
                                const int32_t* cand_count, const int64_t* group_start, const int64_t* line_total,
                                const float* thr_state, float margin, float* score,
                                int32_t* slot_out, int64_t score_stride, int32_t* seg_count, int32_t* seg_rows_out,
-                               int n_blocks, hipStream_t st);
+                               int n_blocks, int32_t* flags, hipStream_t st);
 hipError_t launch_filter_select(const Shape& s, const float* score, const int32_t* slot_in, int64_t score_stride,
                                 const int32_t* seg_count, const int32_t* seg_rows, int nseg,
                                 const int32_t* cand_count, const int64_t* group_start, int64_t* line_total,
                                 const int32_t* k, int32_t* topk_idx, float* topk_score,
                                 float* thr_state, int32_t* redo_g, int32_t* redo_h, const int32_t* skip_if,
-                                hipStream_t st);
+                                int32_t* rescored, hipStream_t st);
 
 // Per (b, h): the k_b best of score[b,h,0:count]; count = cand_count[b, g(h)] when cand != NULL,
 // else seq_lens[b].  Writes positions (ascending) and their scores.
 // only_if [B,Hq] (or NULL): heads whose entry is 0 are skipped.  thr_state [B,Hq] (or NULL) receives
 // each head's k-th best score.  skip_if [B,Hq] (or NULL): heads whose entry is not 0 are skipped (bypassed heads).
+// seq_lens [B] (or NULL; with cand only): a selected candidate entry outside [0, n_b) is written as -1.
 hipError_t launch_select(const Shape& s, const float* score, int64_t score_stride, const int32_t* cand,
                          const int32_t* count, const int32_t* k, int32_t* topk_idx, float* topk_score,
-                         const int32_t* only_if, float* thr_state, const int32_t* skip_if, hipStream_t st);
+                         const int32_t* only_if, float* thr_state, const int32_t* skip_if, const int32_t* seq_lens,
+                         hipStream_t st);
 
 // Scores of idx[b,h,0:k_b] rows against q[b,h] (one head at a time, no group sharing).
 hipError_t launch_head_score(const Shape& s, int dtype, const float* q, const KvView& kv, const int32_t* idx,

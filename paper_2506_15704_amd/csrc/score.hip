@@ -38,6 +38,8 @@ template <typename Op>
 struct Split3;
 template <>
 struct Split3<bf16x8> {
+  using Elem = uint16_t;
+  static constexpr bool kHalf = false;
   __device__ static __forceinline__ uint16_t term(float f, int t) {
     const uint16_t t0 = bf16_rne_bits(f);
     const float r1 = f - __uint_as_float((uint32_t)t0 << 16);
@@ -50,6 +52,8 @@ struct Split3<bf16x8> {
 };
 template <>
 struct Split3<f16x8> {
+  using Elem = _Float16;
+  static constexpr bool kHalf = true;
   // q = t0 + t1 / 2^11 + t2 / 2^22 (11 significant bits per term; the scaling keeps t1, t2 normal)
   __device__ static __forceinline__ uint16_t term(float f, int t) {
     const _Float16 t0 = (_Float16)f;
@@ -76,8 +80,10 @@ __device__ __forceinline__ f32x4 mfma16(f16x8 a, f16x8 b, f32x4 c) {
 // of head (m >> 2), channels of the 16-byte chunk kk + 4*kb of the row (the chunk that lane group kb
 // loads from K at step kk).  Heads >= G contribute zeros.  The query is fetched with eight 16-byte
 // loads issued together; a lane-dependent branch here would serialise 32 single loads.
+// Returns true if this lane met a query element beyond the fp16 range (fp16 operands only): the element is
+// clamped to +-65504 so that the scores stay finite, and the caller raises LFPS_FLAG_Q_RANGE.
 template <int G, typename Op>
-__device__ __forceinline__ void load_query_operand(Op (&A)[4], const float* __restrict__ q, int64_t head0, int j,
+__device__ __forceinline__ bool load_query_operand(Op (&A)[4], const float* __restrict__ q, int64_t head0, int j,
                                                    int kb) {
   const int h = j >> 2, t = j & 3;
   const float4* qh = reinterpret_cast<const float4*>(q + (head0 + (h < G ? h : 0)) * kD);
@@ -88,9 +94,19 @@ __device__ __forceinline__ void load_query_operand(Op (&A)[4], const float* __re
     x[kk][1] = qh[2 * (kk + 4 * kb) + 1];
   }
   const bool live = h < G && t < 3;
+  bool clipped = false;
 #pragma unroll
   for (int kk = 0; kk < 4; ++kk) {
-    const float f[8] = {x[kk][0].x, x[kk][0].y, x[kk][0].z, x[kk][0].w, x[kk][1].x, x[kk][1].y, x[kk][1].z, x[kk][1].w};
+    float f[8] = {x[kk][0].x, x[kk][0].y, x[kk][0].z, x[kk][0].w, x[kk][1].x, x[kk][1].y, x[kk][1].z, x[kk][1].w};
+    if constexpr (sizeof(typename Split3<Op>::Elem) == sizeof(_Float16) && Split3<Op>::kHalf) {
+#pragma unroll
+      for (int c = 0; c < 8; ++c) {
+        if (fabsf(f[c]) > 65504.0f) {               // also +-inf; a NaN goes through as in the other formats
+          clipped |= live;
+          f[c] = copysignf(65504.0f, f[c]);
+        }
+      }
+    }
     union {
       Op v;
       uint16_t h[8];
@@ -99,6 +115,12 @@ __device__ __forceinline__ void load_query_operand(Op (&A)[4], const float* __re
     for (int c = 0; c < 8; ++c) a.h[c] = live ? Split3<Op>::term(f[c], t) : (uint16_t)0;
     A[kk] = a.v;
   }
+  return clipped;
+}
+
+// One lane of the wave reports a clamped query element (fp16 caches only; compiled out otherwise).
+__device__ __forceinline__ void report_q_range(bool clipped, int32_t* __restrict__ flags) {
+  if (__ballot(clipped) != 0 && (threadIdx.x & 63) == 0) atomicOr(flags, LFPS_FLAG_Q_RANGE);
 }
 
 // The registers a lane (j, kb) holds of one 64-row K tile: its 32 channels [32 kb, 32 kb + 32) of the
@@ -166,7 +188,8 @@ __global__ __launch_bounds__(kScoreThreads) void k_group_score_bf16(Shape s, con
                                                                     const int32_t* __restrict__ cand,
                                                                     const int32_t* __restrict__ cand_count,
                                                                     float* __restrict__ score, int64_t score_stride,
-                                                                    float scale, const int32_t* __restrict__ only_if) {
+                                                                    float scale, const int32_t* __restrict__ only_if,
+                                                                    int32_t* __restrict__ flags) {
   const int bg = blockIdx.y, b = bg / s.Hkv, g = bg % s.Hkv;
   if (only_if && only_if[bg] == 0) return;      // group already settled by the filtered pass
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
@@ -180,7 +203,7 @@ __global__ __launch_bounds__(kScoreThreads) void k_group_score_bf16(Shape s, con
 
   using Op = typename KTile<kKind>::Operand;
   Op A[4];
-  load_query_operand<G>(A, q, (int64_t)b * s.Hq + (int64_t)g * G, j, kb);
+  report_q_range(load_query_operand<G>(A, q, (int64_t)b * s.Hq + (int64_t)g * G, j, kb), flags);
 
   using Rows = RowMap<kPaged>;
   constexpr int ES = KTile<kKind>::kElemBytes;
@@ -188,24 +211,30 @@ __global__ __launch_bounds__(kScoreThreads) void k_group_score_bf16(Shape s, con
   const int32_t* cbg = GATHER ? cand + (int64_t)bg * s.cand_cap : nullptr;
   float* sc = score + ((int64_t)b * s.Hq + (int64_t)g * G + kb) * score_stride;   // lane group kb -> head kb
   const int step = gridDim.x * 4 * kRowsPerWaveIter;
-  // the row a lane holds for its slot, as a physical row; padding slots read row 0 and are not stored
-  auto physical = [&](int row) { return Rows::phys(pg, b, (row < 0 || row >= n) ? 0 : row); };
+  // the row a lane holds for its slot, as a physical row; padding slots read row 0 and are not stored.  A
+  // candidate entry outside [0, n) also reads row 0 and its score is stored as -inf: it ranks below every row.
+  auto valid = [&](int row) { return row >= 0 && row < n; };
+  auto physical = [&](int row) { return Rows::phys(pg, b, valid(row) ? row : 0); };
 
   float pv[4] = {0.f, 0.f, 0.f, 0.f};   // scores of the previous iteration, not yet stored
   int pbase = -1;
   int my_row = -1;
   if (first + lane < count) my_row = GATHER ? cbg[first + lane] : first + lane;
+  int my_ok = valid(my_row);
   my_row = physical(my_row);
   for (int base = first; base < count; base += step) {
     KTile<kKind> Bt;
+    bool ok_t[4] = {true, true, true, true};
 #pragma unroll
     for (int t = 0; t < 4; ++t) {
       const int row = __shfl(my_row, 16 * t + j);
+      if constexpr (GATHER) ok_t[t] = __shfl(my_ok, 16 * t + j) != 0;
       Bt.load_row(t, Kbg + Rows::offset(pg, row, stride_b, stride_n) * ES, kb);
     }
     const int nb = base + step;
     int next_row = -1;
     if (nb + lane < count) next_row = GATHER ? cbg[nb + lane] : nb + lane;
+    const int next_ok = valid(next_row);
     next_row = physical(next_row);
     if (pbase >= 0) {
 #pragma unroll
@@ -221,10 +250,11 @@ __global__ __launch_bounds__(kScoreThreads) void k_group_score_bf16(Shape s, con
       for (int kk = 0; kk < 4; ++kk)
         acc = mfma16(A[kk], Bt.operand(t, kk), acc);
       // lane (j, kb): D rows 4*kb .. 4*kb+3 = the three terms (and a zero row) of head kb, column j
-      pv[t] = Split3<Op>::sum(acc) * scale;
+      pv[t] = ok_t[t] ? Split3<Op>::sum(acc) * scale : -INFINITY;
     }
     pbase = base;
     my_row = next_row;
+    my_ok = next_ok;
   }
 #pragma unroll
   for (int t = 0; t < 4; ++t) {
@@ -262,7 +292,8 @@ __global__ __launch_bounds__(kScoreThreads, 2) void k_filter_score_bf16(
     const int32_t* __restrict__ cand_count, const int64_t* __restrict__ group_start,
     const int64_t* __restrict__ line_total, const float* __restrict__ thr_state, float margin,
     float* __restrict__ score, int32_t* __restrict__ slot_out, int64_t score_stride,
-    int32_t* __restrict__ seg_count, int32_t* __restrict__ seg_rows_out, int min_seg_rows, int nseg, float scale) {
+    int32_t* __restrict__ seg_count, int32_t* __restrict__ seg_rows_out, int min_seg_rows, int nseg, float scale,
+    int32_t* __restrict__ flags) {
   __shared__ float stage_score[4][G][kFilterStage];
   __shared__ int32_t stage_slot[4][G][kFilterStage];
   const int tid = threadIdx.x, lane = tid & 63;
@@ -405,7 +436,7 @@ __global__ __launch_bounds__(kScoreThreads, 2) void k_filter_score_bf16(
       int ids_b = fetch_ids(seg_lo + T);                  // ids of the next odd tile
       int ids_a = fetch_ids(seg_lo + 2 * T);              // ids of the next even tile
       issue(Bt0, rows0, ids_0, 0);
-      load_query_operand<G>(A, q, (int64_t)b * s.Hq + (int64_t)g * G, j, kb);   // overlaps the first tile's latency
+      report_q_range(load_query_operand<G>(A, q, (int64_t)b * s.Hq + (int64_t)g * G, j, kb), flags);   // overlaps the first tile's latency
       for (; base_slot + 2 * T < seg_hi; base_slot += 2 * T) {   // at least three tiles left: no conditions inside
         issue(Bt1, rows1, ids_b, 0);
         ids_b = fetch_ids(base_slot + 3 * T);
@@ -446,7 +477,7 @@ __global__ __launch_bounds__(kScoreThreads, 2) void k_filter_score_bf16(
       ids_0 = fetch_ids(seg_lo + 2 * T);
       __builtin_amdgcn_sched_barrier(0);
       fire(Bt0);
-      load_query_operand<G>(A, q, (int64_t)b * s.Hq + (int64_t)g * G, j, kb);
+      report_q_range(load_query_operand<G>(A, q, (int64_t)b * s.Hq + (int64_t)g * G, j, kb), flags);
       // here and at the top of every iteration: (ids_1, phys_1) describe the next odd tile, ids_0 the next even one
       for (; base_slot + 2 * T < seg_hi; base_slot += 2 * T) {
         aim(rows1, ids_1, phys_1);
@@ -490,7 +521,8 @@ __global__ __launch_bounds__(kScoreThreads) void k_group_score_f32(Shape s, cons
                                                                    const int32_t* __restrict__ cand,
                                                                    const int32_t* __restrict__ cand_count,
                                                                    float* __restrict__ score, int64_t score_stride,
-                                                                   float scale, const int32_t* __restrict__ only_if) {
+                                                                   float scale, const int32_t* __restrict__ only_if,
+                                                                   int32_t* __restrict__ flags) {
   const int bg = blockIdx.y, b = bg / s.Hkv, g = bg % s.Hkv;
   if (only_if && only_if[bg] == 0) return;
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
@@ -545,11 +577,11 @@ __global__ __launch_bounds__(kScoreThreads) void k_group_score_f32(Shape s, cons
         for (int h = 0; h < G; ++h) acc[h] += __shfl_xor(acc[h], d);
       }
       int slot = base + 4 * t + rs;
-      if (ok && slot < count && j < G) {
+      if (slot < count && j < G) {     // a candidate entry outside [0, n) scores -inf: it ranks below every row
         float v = acc[0];
 #pragma unroll
         for (int h = 1; h < G; ++h) v = (j == h) ? acc[h] : v;
-        sc[(int64_t)j * score_stride + slot] = v * scale;
+        sc[(int64_t)j * score_stride + slot] = ok ? v * scale : -INFINITY;
       }
     }
   }
@@ -602,7 +634,7 @@ __global__ __launch_bounds__(256) void k_head_score(Shape s, const float* __rest
 template <int G, bool GATHER>
 static hipError_t launch_gs(const Shape& s, int dtype, const float* q, const KvView& kv, const int32_t* cand,
                             const int32_t* cand_count, float* score, int64_t score_stride, const int32_t* only_if,
-                            hipStream_t st) {
+                            int32_t* flags, hipStream_t st) {
   const int rows_max = GATHER ? s.cand_cap : s.Lcap;
   const int per_block = 4 * kRowsPerWaveIter;
   int tiles = (rows_max + per_block - 1) / per_block;
@@ -615,7 +647,7 @@ static hipError_t launch_gs(const Shape& s, int dtype, const float* q, const KvV
 #define LFPS_LAUNCH_GS(KERNEL, TYPE, ...)                                                                          \
   hipLaunchKernelGGL((KERNEL<G, GATHER, __VA_ARGS__>), grid, block, 0, st, s, q, (const TYPE*)kv.k, kv.stride_b,   \
                      kv.stride_h, kv.stride_n, kv.page, kv.seq_lens, cand, cand_count, score, score_stride, scale, \
-                     only_if)
+                     only_if, flags)
   const bool paged = kv.page.table != nullptr;
   if (dtype == LFPS_BF16 && kv.k_fp8) {
     if (paged) LFPS_LAUNCH_GS(k_group_score_bf16, void, true, kKindFp8);
@@ -636,15 +668,15 @@ static hipError_t launch_gs(const Shape& s, int dtype, const float* q, const KvV
 
 hipError_t launch_group_score(const Shape& s, int dtype, const float* q, const KvView& kv, const int32_t* cand,
                               const int32_t* cand_count, float* score, int64_t score_stride, const int32_t* only_if,
-                              hipStream_t st) {
+                              int32_t* flags, hipStream_t st) {
   const bool gather = cand != nullptr;
   switch (s.G) {
-    case 1: return gather ? launch_gs<1, true>(s, dtype, q, kv, cand, cand_count, score, score_stride, only_if, st)
-                          : launch_gs<1, false>(s, dtype, q, kv, cand, cand_count, score, score_stride, only_if, st);
-    case 2: return gather ? launch_gs<2, true>(s, dtype, q, kv, cand, cand_count, score, score_stride, only_if, st)
-                          : launch_gs<2, false>(s, dtype, q, kv, cand, cand_count, score, score_stride, only_if, st);
-    case 4: return gather ? launch_gs<4, true>(s, dtype, q, kv, cand, cand_count, score, score_stride, only_if, st)
-                          : launch_gs<4, false>(s, dtype, q, kv, cand, cand_count, score, score_stride, only_if, st);
+    case 1: return gather ? launch_gs<1, true>(s, dtype, q, kv, cand, cand_count, score, score_stride, only_if, flags, st)
+                          : launch_gs<1, false>(s, dtype, q, kv, cand, cand_count, score, score_stride, only_if, flags, st);
+    case 2: return gather ? launch_gs<2, true>(s, dtype, q, kv, cand, cand_count, score, score_stride, only_if, flags, st)
+                          : launch_gs<2, false>(s, dtype, q, kv, cand, cand_count, score, score_stride, only_if, flags, st);
+    case 4: return gather ? launch_gs<4, true>(s, dtype, q, kv, cand, cand_count, score, score_stride, only_if, flags, st)
+                          : launch_gs<4, false>(s, dtype, q, kv, cand, cand_count, score, score_stride, only_if, flags, st);
     default: return hipErrorInvalidValue;
   }
 }
@@ -696,7 +728,7 @@ hipError_t launch_filter_score(const Shape& s, const float* q, const KvView& kv,
                                const int32_t* cand_count, const int64_t* group_start, const int64_t* line_total,
                                const float* thr_state, float margin, float* score,
                                int32_t* slot_out, int64_t score_stride, int32_t* seg_count, int32_t* seg_rows_out,
-                               int n_blocks, hipStream_t st) {
+                               int n_blocks, int32_t* flags, hipStream_t st) {
   const int nseg = filter_nseg(s);
   if (n_blocks < 1) return hipErrorInvalidValue;
   const bool f16 = kv.f16;
@@ -706,7 +738,7 @@ hipError_t launch_filter_score(const Shape& s, const float* q, const KvView& kv,
   hipLaunchKernelGGL((k_filter_score_bf16<GG, PAGED, FP8>), grid, block, 0, st, s, q, kv.k, kv.stride_b,           \
                      kv.stride_h, kv.stride_n, kv.page, kv.seq_lens, cand, cand_count, group_start, line_total,    \
                      thr_state, margin, score, slot_out, score_stride, seg_count, seg_rows_out,                    \
-                     filter_min_seg_rows(s), nseg, scale)
+                     filter_min_seg_rows(s), nseg, scale, flags)
 #define LFPS_LAUNCH_FILTER(GG)                        \
   if (kv.page.table && kv.k_fp8) {                    \
     LFPS_LAUNCH_FILTER_P(GG, true, kKindFp8);         \

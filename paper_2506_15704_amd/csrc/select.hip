@@ -106,8 +106,9 @@ __device__ __forceinline__ void find_bin(SelectShared<NT>& sm, uint32_t need, in
   }
 
 // `slot_of` (LDS, or NULL for identity) maps an element of the scored list to its candidate slot;
-// `cbg` (or NULL for identity) maps a candidate slot to its position.  `thr_out` receives the
-// k-th largest score.
+// `cbg` (or NULL for identity) maps a candidate slot to its position; a position outside [0, n_valid)
+// (a bad entry of a caller's candidate list: its score is -inf, so it is taken only when fewer than k
+// valid candidates exist) is written as -1 with score 0.  `thr_out` receives the k-th largest score.
 // kHaveRange: the caller has already seen every element (it filled the cache) and passes its own
 // thread's smallest and largest in pre_lo / pre_hi, which saves the first pass over the data.
 template <bool CACHED, int NT, bool kHaveRange = false>
@@ -116,7 +117,7 @@ __device__ __forceinline__ void select_body(SelectShared<NT>& sm, float* __restr
                                             const int32_t* __restrict__ slot_of, const int32_t* __restrict__ cbg,
                                             int32_t* __restrict__ oi, float* __restrict__ os,
                                             float* __restrict__ thr_out, float pre_lo = FLT_MAX,
-                                            float pre_hi = -FLT_MAX) {
+                                            float pre_hi = -FLT_MAX, int n_valid = 0x7FFFFFFF) {
   constexpr int kSelWaves = NT / 64, kBins = 2 * NT, kListCap = NT;
   const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
   const int chunk = (((c + kSelWaves - 1) / kSelWaves) + 63) & ~63;
@@ -260,8 +261,10 @@ __device__ __forceinline__ void select_body(SelectShared<NT>& sm, float* __restr
       if (take) {
         if (pos < (uint32_t)ksel) {
           const int sl = slot_of ? slot_of[i] : i;
-          oi[pos] = cbg ? cbg[sl] : sl;
-          if (os) os[pos] = x;
+          const int p = cbg ? cbg[sl] : sl;
+          const bool okp = (uint32_t)p < (uint32_t)n_valid;
+          oi[pos] = okp ? p : -1;
+          if (os) os[pos] = okp ? x : 0.f;
         }
         ++pos;
       }
@@ -292,8 +295,10 @@ __device__ __forceinline__ void select_body(SelectShared<NT>& sm, float* __restr
         const uint32_t pos = out_run + lanes_below(m_take);
         if (pos < (uint32_t)ksel) {
           const int sl = slot_of ? slot_of[i] : i;
-          oi[pos] = cbg ? cbg[sl] : sl;
-          if (os) os[pos] = x;
+          const int p = cbg ? cbg[sl] : sl;
+          const bool okp = (uint32_t)p < (uint32_t)n_valid;
+          oi[pos] = okp ? p : -1;
+          if (os) os[pos] = okp ? x : 0.f;
         }
       }
       eq_run += __popcll(m_eq);
@@ -308,8 +313,8 @@ __device__ __forceinline__ void select_body(SelectShared<NT>& sm, float* __restr
 // the register-resident variant.
 __device__ __noinline__ void select_stream(SelectShared<kSelThreads>& sm, const float* __restrict__ sc, int c, int ksel,
                                            const int32_t* __restrict__ cbg, int32_t* __restrict__ oi,
-                                           float* __restrict__ os, float* __restrict__ thr_out) {
-  select_body<false, kSelThreads>(sm, nullptr, sc, c, ksel, nullptr, cbg, oi, os, thr_out);
+                                           float* __restrict__ os, float* __restrict__ thr_out, int n_valid) {
+  select_body<false, kSelThreads>(sm, nullptr, sc, c, ksel, nullptr, cbg, oi, os, thr_out, FLT_MAX, -FLT_MAX, n_valid);
 }
 
 __global__ __launch_bounds__(kSelThreads) void k_select(Shape s, const float* __restrict__ score,
@@ -319,7 +324,8 @@ __global__ __launch_bounds__(kSelThreads) void k_select(Shape s, const float* __
                                                         float* __restrict__ topk_score, int cache_elems,
                                                         const int32_t* __restrict__ only_if,
                                                         float* __restrict__ thr_state,
-                                                        const int32_t* __restrict__ skip_if) {
+                                                        const int32_t* __restrict__ skip_if,
+                                                        const int32_t* __restrict__ seq_lens) {
   __shared__ SelectShared<kSelThreads> sm;
   extern __shared__ float cache[];
   const int bh = blockIdx.x, b = bh / s.Hq, h = bh % s.Hq, g = h / s.G;
@@ -348,10 +354,15 @@ __global__ __launch_bounds__(kSelThreads) void k_select(Shape s, const float* __
 
   const float* sc = score + (int64_t)bh * score_stride;
   const int32_t* cbg = gather ? cand + ((int64_t)b * s.Hkv + g) * s.cand_cap : nullptr;
+  int n_valid = 0x7FFFFFFF;
+  if (gather && seq_lens) {
+    n_valid = seq_lens[b];
+    n_valid = n_valid < 0 ? 0 : (n_valid > s.Lcap ? s.Lcap : n_valid);
+  }
   if (c <= cache_elems)
-    select_body<true, kSelThreads>(sm, cache, sc, c, ksel, nullptr, cbg, oi, os, thr_out);
+    select_body<true, kSelThreads>(sm, cache, sc, c, ksel, nullptr, cbg, oi, os, thr_out, FLT_MAX, -FLT_MAX, n_valid);
   else
-    select_stream(sm, sc, c, ksel, cbg, oi, os, thr_out);
+    select_stream(sm, sc, c, ksel, cbg, oi, os, thr_out, n_valid);
 }
 
 // ----------------------------------------------------------------------------- filtered input
@@ -377,7 +388,8 @@ __global__ __launch_bounds__(kFilterSelThreads) void k_filter_select(Shape s, co
                                                                float* __restrict__ thr_state,
                                                                int32_t* __restrict__ redo_g,
                                                                int32_t* __restrict__ redo_h, int cap,
-                                                               const int32_t* __restrict__ skip_if) {
+                                                               const int32_t* __restrict__ skip_if,
+                                                               int32_t* __restrict__ rescored) {
   constexpr int NT = kFilterSelThreads, kSelWaves = NT / 64;
   constexpr int kPiecesPerThread = 1024 / NT;      // nseg <= 1024
   __shared__ SelectShared<NT> sm;
@@ -454,6 +466,7 @@ __global__ __launch_bounds__(kFilterSelThreads) void k_filter_select(Shape s, co
     if (tid == 0) {
       redo_g[bg] = 1;
       redo_h[bh] = 1;
+      if (rescored) atomicAdd(rescored, 1);          // heads sent to the unfiltered pass since the last poll
     }
     return;
   }
@@ -550,12 +563,13 @@ hipError_t configure_select(const Shape& s) {
 
 hipError_t launch_select(const Shape& s, const float* score, int64_t score_stride, const int32_t* cand,
                          const int32_t* count, const int32_t* k, int32_t* topk_idx, float* topk_score,
-                         const int32_t* only_if, float* thr_state, const int32_t* skip_if, hipStream_t st) {
+                         const int32_t* only_if, float* thr_state, const int32_t* skip_if, const int32_t* seq_lens,
+                         hipStream_t st) {
   // A conditional launch (only_if) is expected to find nothing to do: it streams from global memory
   // instead of reserving the LDS cache, so that its workgroups are cheap to place and retire.
   const int ce = only_if ? 0 : select_cache_elems(s, cand != nullptr);
   hipLaunchKernelGGL(k_select, dim3(s.B * s.Hq), dim3(kSelThreads), (size_t)ce * 4, st, s, score, score_stride, cand,
-                     count, k, topk_idx, topk_score, ce, only_if, thr_state, skip_if);
+                     count, k, topk_idx, topk_score, ce, only_if, thr_state, skip_if, seq_lens);
   return hipGetLastError();
 }
 
@@ -564,11 +578,11 @@ hipError_t launch_filter_select(const Shape& s, const float* score, const int32_
                                 const int32_t* cand_count, const int64_t* group_start, int64_t* line_total,
                                 const int32_t* k, int32_t* topk_idx, float* topk_score,
                                 float* thr_state, int32_t* redo_g, int32_t* redo_h, const int32_t* skip_if,
-                                hipStream_t st) {
+                                int32_t* rescored, hipStream_t st) {
   const int cap = filter_list_cap(s);
   hipLaunchKernelGGL(k_filter_select, dim3(s.B * s.Hq), dim3(kFilterSelThreads), (size_t)cap * 8, st, s, score, slot_in,
                      score_stride, seg_count, seg_rows, nseg, cand_count, group_start, line_total, k, topk_idx, topk_score, thr_state, redo_g,
-                     redo_h, cap, skip_if);
+                     redo_h, cap, skip_if, rescored);
   return hipGetLastError();
 }
 
