@@ -112,7 +112,8 @@ typedef struct {
 int lfps_create(const lfps_config* cfg, lfps_ctx** out);
 int lfps_destroy(lfps_ctx* ctx);
 /* Text of the last error on this context (host string owned by the context; "" if none).
- * With ctx == NULL: text of the last lfps_create failure in this thread. */
+ * With ctx == NULL: text of the last failure of a call that takes no context (lfps_create,
+ * lfps_workspace_bytes, lfps_sparse_attn_noalloc) in this thread. */
 const char* lfps_last_error(const lfps_ctx* ctx);
 /* Device bytes lfps_create will allocate for this config (host out-pointer). */
 int lfps_workspace_bytes(const lfps_config* cfg, int64_t* out);
@@ -155,6 +156,25 @@ int lfps_score_topk(lfps_ctx* ctx, const float* q, const lfps_kv* kv, const int3
  *   out       [B, Hq, D] fp32 (zeros for a head with no valid index) */
 int lfps_sparse_attn(lfps_ctx* ctx, const float* q, const lfps_kv* kv, const int32_t* idx,
                      const float* idx_score, const int32_t* k, float* out, void* stream);
+
+/* S4 for callers that cannot allocate device memory (code recorded into a HIP graph, serving loops and harnesses
+ * that forbid hipMalloc): the same result as lfps_sparse_attn(ctx, q, kv, idx, NULL, k, out) without a context.
+ * Nothing is allocated, by this call or before it: the scores of the selected rows, which lfps_sparse_attn keeps in
+ * its context's workspace between its two kernels, go to a static device array of LFPS_NOALLOC_MAX_SCORES floats
+ * (8 MiB, held by every GPU the library runs on until the process ends).
+ *   cfg   the shapes and cache format as for lfps_create (batch, heads, head_dim, kv_dtype, k_fp8 / v_fp8,
+ *         max_seq_len, max_k; the other fields must be valid but are not used); cfg->device must be the
+ *         CURRENT device.  batch * n_q_heads * max_k must not exceed LFPS_NOALLOC_MAX_SCORES: LFPS_ECAP otherwise.
+ *   q [B, Hq, D], idx [B, Hq, kmax], k [B], out [B, Hq, D]: device pointers owned by the caller, as for
+ *         lfps_sparse_attn.
+ * Errors are returned as lfps_status; their text is lfps_last_error(NULL) in the calling thread.
+ * All calls on one GPU share that GPU's array: two calls that overlap in time on one GPU (different streams or
+ * threads) race on it.  The array keeps the previous call's scores; nothing in it needs clearing (every entry
+ * that is read has been written by the same call).  The first call on a device looks the array's address up
+ * (hipGetSymbolAddress), so make that call outside stream capture. */
+#define LFPS_NOALLOC_MAX_SCORES 2097152
+int lfps_sparse_attn_noalloc(const lfps_config* cfg, const float* q, const lfps_kv* kv, const int32_t* idx,
+                             const int32_t* k, float* out, void* stream);
 
 /* S1..S4 in one call (Alg. 1 lines 6-8 and 10, then Eq. 1): candidates from prev_topk, score,
  * select into topk_idx (this step's index set, the next step's prev_topk), attention into out.

@@ -23,6 +23,7 @@ LFPS_FLAG_CAND_OVERFLOW = 1
 LFPS_FLAG_TABLE_FULL = 2
 LFPS_FLAG_Q_RANGE = 4
 N_KERNELS = 13
+NOALLOC_MAX_SCORES = 2097152
 
 
 class LfpsError(RuntimeError):
@@ -64,6 +65,7 @@ def _load() -> ctypes.CDLL:
         "lfps_score_topk": (ctypes.c_int, [P, VP, ctypes.POINTER(lfps_kv), VP, VP, VP, VP, VP, VP, VP]),
         "lfps_sparse_attn": (ctypes.c_int, [P, VP, ctypes.POINTER(lfps_kv), VP, VP, VP, VP, VP]),
         "lfps_step": (ctypes.c_int, [P, VP, ctypes.POINTER(lfps_kv), VP, VP, VP, VP, VP, VP]),
+        "lfps_sparse_attn_noalloc": (ctypes.c_int, [ctypes.POINTER(lfps_config), VP, ctypes.POINTER(lfps_kv), VP, VP, VP, VP]),
         "lfps_full_attn_decode": (ctypes.c_int, [P, VP, ctypes.POINTER(lfps_kv), VP, VP]),
         "lfps_exact_topk": (ctypes.c_int, [P, VP, ctypes.POINTER(lfps_kv), VP, VP, VP, VP]),
         "lfps_poll_status": (ctypes.c_int, [P, ctypes.POINTER(I32), VP]),
@@ -252,6 +254,17 @@ class Lfps:
             _ptr(idx_score, torch.float32, (self.B, self.Hq, self.kmax), "idx_score", d),
             _ptr(k, torch.int32, (self.B,), "k", d),
             _ptr(out, torch.float32, (self.B, self.Hq, self.D), "out", d), self._stream()))
+
+    def lfps_sparse_attn_noalloc(self, q, kv: lfps_kv, idx, k, out):
+        """The context-free, allocation-free S4 (scores recomputed into the library's static array), called with
+        this context's configuration."""
+        d = self.device
+        rc = _lib.lfps_sparse_attn_noalloc(
+            ctypes.byref(self.cfg), _ptr(q, torch.float32, (self.B, self.Hq, self.D), "q", d), ctypes.byref(kv),
+            _ptr(idx, torch.int32, (self.B, self.Hq, self.kmax), "idx", d), _ptr(k, torch.int32, (self.B,), "k", d),
+            _ptr(out, torch.float32, (self.B, self.Hq, self.D), "out", d), self._stream())
+        if rc != LFPS_OK:
+            raise LfpsError(rc, _lib.lfps_last_error(None).decode())
 
     def lfps_step(self, q, kv: lfps_kv, prev_topk, k, topk_idx, out, topk_score=None):
         d = self.device

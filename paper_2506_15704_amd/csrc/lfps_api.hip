@@ -3,6 +3,7 @@
 #include <stdio.h>
 #include <string.h>
 
+#include <mutex>
 #include <new>
 
 #include "lfps_internal.h"
@@ -149,38 +150,48 @@ int fail(lfps_ctx* ctx, int code, const char* what, hipError_t e = hipSuccess) {
   return code;
 }
 
-int check_kv(lfps_ctx* ctx, const lfps_kv* kv, bool need_v, KvView* out) {
-  if (!kv) return fail(ctx, LFPS_EINVAL, "kv view is NULL");
-  if (!kv->k) return fail(ctx, LFPS_EINVAL, "kv->k is NULL");
-  if (need_v && !kv->v) return fail(ctx, LFPS_EINVAL, "kv->v is NULL");
-  if (!kv->seq_lens) return fail(ctx, LFPS_EINVAL, "kv->seq_lens is NULL");
+// Validates a cache view against a configuration; the reason of a refusal goes to err.
+int check_kv_cfg(const lfps_config& cfg, char* err, size_t errn, const lfps_kv* kv, bool need_v, KvView* out) {
+#define BAD(text)                  \
+  do {                             \
+    snprintf(err, errn, "%s", text); \
+    return LFPS_EINVAL;            \
+  } while (0)
+  if (!kv) BAD("kv view is NULL");
+  if (!kv->k) BAD("kv->k is NULL");
+  if (need_v && !kv->v) BAD("kv->v is NULL");
+  if (!kv->seq_lens) BAD("kv->seq_lens is NULL");
   // the strides are shared by K and V: with one-byte K elements the K rows set the alignment
-  const int esz = (ctx->cfg.k_fp8 || ctx->cfg.v_fp8) ? 1 : (ctx->cfg.kv_dtype == LFPS_F32 ? 4 : 2);
+  const int esz = (cfg.k_fp8 || cfg.v_fp8) ? 1 : (cfg.kv_dtype == LFPS_F32 ? 4 : 2);
   if (kv->stride_n < kD || kv->stride_b < 0 || kv->stride_h < 0)
-    return fail(ctx, LFPS_EINVAL, "kv strides: stride_n must be >= head_dim, stride_b/stride_h >= 0");
+    BAD("kv strides: stride_n must be >= head_dim, stride_b/stride_h >= 0");
   if ((kv->stride_n * esz) % 16 || (kv->stride_b * esz) % 16 || (kv->stride_h * esz) % 16 ||
       ((uintptr_t)kv->k % 16) || (kv->v && ((uintptr_t)kv->v % 16)))
-    return fail(ctx, LFPS_EINVAL, "kv rows must be 16-byte aligned (base pointers and strides)");
+    BAD("kv rows must be 16-byte aligned (base pointers and strides)");
   out->k = kv->k; out->v = kv->v;
   out->stride_b = kv->stride_b; out->stride_h = kv->stride_h; out->stride_n = kv->stride_n;
   out->seq_lens = kv->seq_lens;
   out->page = KvPage{nullptr, 0, 0, 0};
-  out->k_fp8 = ctx->cfg.k_fp8 != 0;
-  out->v_fp8 = ctx->cfg.v_fp8 != 0;
-  out->f16 = ctx->cfg.kv_dtype == LFPS_F16;
+  out->k_fp8 = cfg.k_fp8 != 0;
+  out->v_fp8 = cfg.v_fp8 != 0;
+  out->f16 = cfg.kv_dtype == LFPS_F16;
   if (kv->block_table) {
     const int64_t bs = kv->block_size;
-    if (bs < 1 || bs > 65536 || (bs & (bs - 1)))
-      return fail(ctx, LFPS_EINVAL, "paged kv: block_size must be a power of two in [1, 65536]");
-    if (kv->block_table_stride < 1 || (int64_t)kv->block_table_stride * bs < ctx->cfg.max_seq_len)
-      return fail(ctx, LFPS_EINVAL, "paged kv: block_table_stride * block_size must cover max_seq_len");
+    if (bs < 1 || bs > 65536 || (bs & (bs - 1))) BAD("paged kv: block_size must be a power of two in [1, 65536]");
+    if (kv->block_table_stride < 1 || (int64_t)kv->block_table_stride * bs < cfg.max_seq_len)
+      BAD("paged kv: block_table_stride * block_size must cover max_seq_len");
     if (kv->n_blocks < 1 || (int64_t)kv->n_blocks * bs > 2147483647LL)
-      return fail(ctx, LFPS_EINVAL, "paged kv: n_blocks must be >= 1 and n_blocks * block_size below 2^31");
+      BAD("paged kv: n_blocks must be >= 1 and n_blocks * block_size below 2^31");
     int shift = 0;
     while ((1 << shift) < bs) ++shift;
     out->page = KvPage{kv->block_table, kv->block_table_stride, shift, kv->n_blocks};
   }
+#undef BAD
   return LFPS_OK;
+}
+
+int check_kv(lfps_ctx* ctx, const lfps_kv* kv, bool need_v, KvView* out) {
+  return check_kv_cfg(ctx->cfg, ctx->err, sizeof ctx->err, kv, need_v, out);
 }
 
 // Brackets one launch with events when timing is on.
@@ -456,6 +467,89 @@ int lfps_step(lfps_ctx* ctx, const float* q, const lfps_kv* kv, const int32_t* p
   if (rc != LFPS_OK) return rc;
   LAUNCH(ctx, LFPS_KERNEL_SPARSE_ATTN, st,
          launch_sparse_attn(s, ctx->cfg.kv_dtype, v, topk_idx, sel, k, out, nullptr, st));
+  return LFPS_OK;
+}
+
+// ---------------------------------------------------------------------------- allocation-free S4
+// The scores of the selected rows (the scratch buffer between the per-head scoring kernel and the attention
+// kernel, `sel_score` in a context's workspace) live in a file-scope device array here, so the call needs no
+// context and allocates nothing.  The array's name is a host-side handle, not a device address: the address is
+// looked up once per device and only that pointer is ever handed to a kernel.
+static __device__ __align__(256) float scratch[LFPS_NOALLOC_MAX_SCORES];
+namespace {
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mu;
+float* g_scratch_ptr[kMaxDevices] = {};
+
+// The current device's copy of `scratch` (each device holds its own, at its own address).
+int scratch_on_current_device(int device, float** out, char* err, size_t errn) {
+  if (device < 0 || device >= kMaxDevices) {
+    snprintf(err, errn, "device ordinal %d is beyond the %d this entry point supports", device, kMaxDevices);
+    return LFPS_EINVAL;
+  }
+  std::lock_guard<std::mutex> lock(g_scratch_mu);
+  if (!g_scratch_ptr[device]) {
+    float* p = nullptr;
+    hipError_t e = hipGetSymbolAddress((void**)&p, HIP_SYMBOL(scratch));
+    if (e != hipSuccess || !p) {
+      snprintf(err, errn, "hipGetSymbolAddress(scratch) on device %d: %s", device, hipGetErrorString(e));
+      (void)hipGetLastError();
+      return LFPS_EHIP;
+    }
+    g_scratch_ptr[device] = p;
+  }
+  *out = g_scratch_ptr[device];
+  return LFPS_OK;
+}
+}  // namespace
+
+int lfps_sparse_attn_noalloc(const lfps_config* cfg, const float* q, const lfps_kv* kv, const int32_t* idx,
+                             const int32_t* k, float* out, void* stream) {
+  char* err = g_create_err;
+  const size_t errn = sizeof g_create_err;
+  Sizes z;
+  int rc = check_config(cfg, &z, err, errn);
+  if (rc != LFPS_OK) return rc;
+  if (!q || !idx || !k || !out) {
+    snprintf(err, errn, "lfps_sparse_attn_noalloc: NULL argument");
+    return LFPS_EINVAL;
+  }
+  const int64_t need = (int64_t)cfg->batch * cfg->n_q_heads * cfg->max_k;
+  if (need > (int64_t)LFPS_NOALLOC_MAX_SCORES) {
+    snprintf(err, errn,
+             "lfps_sparse_attn_noalloc: batch * n_q_heads * max_k = %lld exceeds the static scratch of %lld scores "
+             "(use a context and lfps_sparse_attn for larger shapes)",
+             (long long)need, (long long)LFPS_NOALLOC_MAX_SCORES);
+    return LFPS_ECAP;
+  }
+  int dev = -1;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) {
+    snprintf(err, errn, "hipGetDevice: %s", hipGetErrorString(e));
+    return LFPS_EHIP;
+  }
+  if (dev != cfg->device) {
+    snprintf(err, errn, "lfps_sparse_attn_noalloc: cfg->device is %d but the current device is %d", cfg->device, dev);
+    return LFPS_EINVAL;
+  }
+  KvView v;
+  rc = check_kv_cfg(*cfg, err, errn, kv, true, &v);
+  if (rc != LFPS_OK) return rc;
+  float* sel = nullptr;
+  rc = scratch_on_current_device(dev, &sel, err, errn);
+  if (rc != LFPS_OK) return rc;
+  Shape s{};
+  s.B = cfg->batch; s.Hq = cfg->n_q_heads; s.Hkv = cfg->n_kv_heads; s.G = z.G;
+  s.Lcap = cfg->max_seq_len; s.kmax = cfg->max_k; s.cand_cap = z.cand_cap;
+  s.radius = cfg->radius; s.n_recent = cfg->n_recent; s.n_sink = cfg->n_sink;
+  s.score_stride = z.score_stride;
+  hipStream_t st = (hipStream_t)stream;
+  e = launch_head_score(s, cfg->kv_dtype, q, v, idx, k, sel, st);
+  if (e == hipSuccess) e = launch_sparse_attn(s, cfg->kv_dtype, v, idx, sel, k, out, nullptr, st);
+  if (e != hipSuccess) {
+    snprintf(err, errn, "lfps_sparse_attn_noalloc: %s", hipGetErrorString(e));
+    return LFPS_EHIP;
+  }
   return LFPS_OK;
 }
 
