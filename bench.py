@@ -148,9 +148,13 @@ class Runner:
             else:
                 self.ctx.lfps_table_step(self.q[t], self.views[t], self.k, dst, self.out)
         else:
-            self.ctx.lfps_step(self.q[t], self.views[t], self.prev, self.k, dst, self.out)
+            self.ctx.lfps_step(self.q[t], self.views[t], self.prev, self.k, dst, self.out, self.sel_score)
         self.prev = dst
         self.cur ^= 1
+
+    def sel_score_last(self):
+        """Scores of the rows selected by the last lfps_step call (its topk_score output)."""
+        return self.sel_score
 
 
     def run_timed(self, steps, warmup):
@@ -338,7 +342,17 @@ def measure(name, steps, warmup, with_baselines=True, use_graph=True, override=N
     }
     # S4: V bytes if every head fetched its own rows (upper bound) and if a group fetched each row once (lower bound)
     row_bytes = spec.D * (2 if spec.kv_dtype == "bf16" else 4)
-    at_us = tm["sparse_attn"][0] / max(tm["sparse_attn"][1], 1) * 1e3
+    # S4 alone: the stand-alone kernel (lfps_sparse_attn) on the last step's Top-k and scores, event-timed
+    import torch
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    scratch_out = torch.zeros_like(r.out)
+    for i in range(3 + 20):
+        if i == 3:
+            e0.record()
+        r.ctx.lfps_sparse_attn(r.q[r.t], r.views[r.t], r.prev, r.sel_score_last(), r.k, scratch_out)
+    e1.record()
+    torch.cuda.synchronize()
+    at_us = e0.elapsed_time(e1) * 1e3 / 20
     upper = float(r.case.k.sum()) * spec.Hq * row_bytes
     lower = float(union_rows) * row_bytes
     res["sparse_attn"] = {"avg_launch_us": round(at_us, 2), "bytes_per_head_rows": round(upper), "bytes_group_union_last_step": round(lower),

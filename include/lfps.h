@@ -293,7 +293,9 @@ enum {
   LFPS_KERNEL_TABLE_FLAGS = 10,
   LFPS_KERNEL_TABLE_CANDIDATES = 11,
   LFPS_KERNEL_TABLE_UPDATE = 12,
-  LFPS_N_KERNELS = 13
+  LFPS_KERNEL_FILTER_SELECT_ATTEND = 13,   /* S3 + S4 from the filtered pass's survivor lists (chained steps) */
+  LFPS_KERNEL_SELECT_ATTEND = 14,          /* S3 + S4 from full score rows (heads the filter left short; unfiltered contexts) */
+  LFPS_N_KERNELS = 15
 };
 #define LFPS_TIMING_MAX_LAUNCHES 4096
 int lfps_timing_enable(lfps_ctx* ctx, int32_t on);

@@ -22,7 +22,7 @@ LFPS_OK, LFPS_EINVAL, LFPS_ECAP, LFPS_EHIP, LFPS_ENOMEM = 0, -1, -2, -3, -4
 LFPS_FLAG_CAND_OVERFLOW = 1
 LFPS_FLAG_TABLE_FULL = 2
 LFPS_FLAG_Q_RANGE = 4
-N_KERNELS = 13
+N_KERNELS = 15
 NOALLOC_MAX_SCORES = 2097152
 
 

@@ -10,7 +10,7 @@
 //
 // Full: split-K over contiguous row ranges with the G heads of a group sharing every K and V
 // row; running (max, sum, acc) per lane group, merged with the online-softmax rule.
-#include "lfps_internal.h"
+#include "attend.h"
 
 namespace lfps {
 
@@ -26,133 +26,17 @@ __global__ __launch_bounds__(kSparseWaves * 64) void k_sparse_attn(Shape s, cons
                                                                 const int32_t* __restrict__ kk,
                                                                 float* __restrict__ out,
                                                                 const int32_t* __restrict__ skip_if) {
-  __shared__ float red[kSparseWaves][kD];
-  __shared__ float redm[kSparseWaves], redl[kSparseWaves];
-  // Workgroups are dealt to the 8 XCDs round-robin (workgroup i runs on XCD i % 8) and every XCD has
-  // its own L2.  The heads of a KV group select largely the same rows, so the G workgroups of a group
-  // are given ids that differ by multiples of 8: they run on one XCD at about the same time and a V
-  // row fetched for one head is an L2 hit for the others.
-  int bh = blockIdx.x;
-  {
-    const int n_kvg = s.B * s.Hkv;                 // KV groups in the launch
-    if (n_kvg % 8 == 0) {
-      const int xcd = bh & 7, slot = bh >> 3;
-      bh = ((slot / s.G) * 8 + xcd) * s.G + slot % s.G;
-    }
-  }
+  __shared__ AttendShared sm;
+  const int bh = head_of_block(s, blockIdx.x);
   if (skip_if && skip_if[bh] != 0) return;            // bypassed head: the gate wrote its output row
   const int b = bh / s.Hq, h = bh % s.Hq, g = h / s.G;
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  const int j = lane & 15, rs = lane >> 4;
   int n = seq_lens[b];
   n = n < 0 ? 0 : (n > s.Lcap ? s.Lcap : n);
   int kb = kk[b];
   kb = kb < 0 ? 0 : (kb > s.kmax ? s.kmax : kb);
-  const int32_t* ih = idx + (int64_t)bh * s.kmax;
-  const float* sh = idx_score + (int64_t)bh * s.kmax;
-
-  // wave w takes entries [r0, r1) of the head's index list
-  const int chunk = (((kb + kSparseWaves - 1) / kSparseWaves) + 63) & ~63;
-  const int r0 = wave * chunk, r1 = r0 + chunk < kb ? r0 + chunk : kb;
-
-  // softmax reference: the largest score among the head's valid rows.  Each lane looks at the
-  // entries it will own in the loop below (first 64-entry tile kept in registers).
-  using Rows = RowMap<kPaged>;
-  int first_row = -1;                 // as a physical row (never negative), or -1 for "no row"
-  float first_s = -INFINITY;
-  float m = -INFINITY;
-  for (int i = r0 + lane; i < r1; i += 64) {
-    const int r = ih[i];
-    const float sv = sh[i];
-    const bool ok = r >= 0 && r < n;
-    if (i < r0 + 64) {
-      first_row = ok ? Rows::phys(pg, b, r) : -1;
-      first_s = sv;
-    }
-    if (ok) m = fmaxf(m, sv);
-  }
-#pragma unroll
-  for (int d = 1; d < 64; d <<= 1) m = fmaxf(m, __shfl_xor(m, d));
-  if (lane == 0) redm[wave] = m;
-  __syncthreads();
-  m = redm[0];
-#pragma unroll
-  for (int w = 1; w < kSparseWaves; ++w) m = fmaxf(m, redm[w]);
-
-  const T* Vbg = V + Rows::base(b, g, stride_b, stride_h) + 8 * j;
-  float acc[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
-  float l = 0.f;
-  // A tile = 64 entries of the list, one per lane (row, weight); the entries of the next tile are fetched
-  // before the rows of the current one.  The rows of a tile are read in two batches of eight loads per lane
-  // (32 rows per wave), every load of a batch issued before the first is used: the compiler, left alone,
-  // orders one load ahead of its use and the loop becomes a chain of single memory round trips.
-  constexpr int kBatch = 8;
-  auto entry = [&](int i, int& row, float& sv) {          // list entry i of my lane: physical row or -1, score
-    row = -1;
-    sv = 0.f;
-    if (i < r1) {
-      const int r = ih[i];
-      sv = sh[i];
-      if (r >= 0 && r < n) row = Rows::phys(pg, b, r);
-    }
-  };
-  int next_row = -1;
-  float next_s = 0.f;
-  if (r0 + 64 < r1) entry(r0 + 64 + lane, next_row, next_s);
-  int my_row = first_row;
-  float my_p = my_row >= 0 ? __expf(first_s - m) : 0.f;
-  for (int base = r0; base < r1; base += 64) {
-    l += my_p;
-    const int cur_row = my_row;
-    const float cur_p = my_p;
-    my_row = next_row;                                      // becomes current at the next trip
-    my_p = my_row >= 0 ? __expf(next_s - m) : 0.f;
-    if (base + 128 < r1) entry(base + 128 + lane, next_row, next_s);
-    else next_row = -1;
-#pragma unroll
-    for (int half = 0; half < 16 / kBatch; ++half) {
-      Raw8<T> rw[kBatch];
-      float pw[kBatch];
-#pragma unroll
-      for (int u = 0; u < kBatch; ++u) {
-        const int t = half * kBatch + u;
-        const int row = __shfl(cur_row, 4 * t + rs);
-        const float p = __shfl(cur_p, 4 * t + rs);
-        rw[u].load(Vbg + Rows::offset(pg, row < 0 ? 0 : row, stride_b, stride_n));
-        pw[u] = row < 0 ? 0.f : p;
-      }
-      __builtin_amdgcn_sched_barrier(0);                    // keep the batch's loads ahead of its arithmetic
-#pragma unroll
-      for (int u = 0; u < kBatch; ++u) {
-        float x[8];
-        rw[u].get(x);
-#pragma unroll
-        for (int c = 0; c < 8; ++c) acc[c] = fmaf(pw[u], x[c], acc[c]);
-      }
-    }
-  }
-#pragma unroll
-  for (int d = 1; d < 64; d <<= 1) l += __shfl_xor(l, d);
-#pragma unroll
-  for (int c = 0; c < 8; ++c) {
-    acc[c] += __shfl_xor(acc[c], 16);
-    acc[c] += __shfl_xor(acc[c], 32);
-  }
-  if (rs == 0) {
-#pragma unroll
-    for (int c = 0; c < 8; ++c) red[wave][8 * j + c] = acc[c];
-  }
-  if (lane == 0) redl[wave] = l;
-  __syncthreads();
-  if (tid < kD) {
-    float a = 0.f, ls = 0.f;
-#pragma unroll
-    for (int w = 0; w < kSparseWaves; ++w) {
-      a += red[w][tid];
-      ls += redl[w];
-    }
-    out[(int64_t)bh * kD + tid] = ls > 0.f ? a / ls : 0.f;
-  }
+  attend_rows<T, kSparseWaves, kPaged>(sm, V, stride_b, stride_h, stride_n, pg, b, g, n, kb,
+                                       idx + (int64_t)bh * s.kmax, idx_score + (int64_t)bh * s.kmax, false, 0.f,
+                                       out + (int64_t)bh * kD);
 }
 
 template <typename T>

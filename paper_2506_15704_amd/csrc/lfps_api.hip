@@ -55,7 +55,7 @@ static thread_local char g_create_err[512] = "";
 static const char* const kKernelNames[LFPS_N_KERNELS] = {
     "candidates", "gather_score", "select", "sparse_attn",
     "dense_score", "full_attn", "full_merge", "head_score", "filter_score", "filter_select",
-    "table_flags", "table_candidates", "table_update"};
+    "table_flags", "table_candidates", "table_update", "filter_select_attend", "select_attend"};
 
 // Margin below the previous step's k-th best score at which the filtered pass keeps a row.
 static const float kFilterMargin = 0.125f;
@@ -414,12 +414,12 @@ int lfps_sparse_attn(lfps_ctx* ctx, const float* q, const lfps_kv* kv, const int
   return LFPS_OK;
 }
 
-// S2 + S3 over ctx->cand / ctx->cand_count inside the chained entry points.  With the score filter on
-// (16-bit and FP8-key caches): survivors of the per-head threshold first, then the unfiltered pass for the heads it
-// left short (both launches exit at once when no head is marked).  The candidates kernel of the same
-// step has cleared the marks and laid the groups on the line (group_start, line_total).
-static int score_and_select(lfps_ctx* ctx, const float* q, const KvView& v, const int32_t* k, int32_t* topk_idx,
-                            float* sel, const int32_t* skip_if, hipStream_t st) {
+// S2 + S3 + S4 over ctx->cand / ctx->cand_count inside the chained entry points.  With the score filter on
+// (16-bit and FP8-key caches): survivors of the per-head threshold first, selected and attended to in one kernel;
+// then the unfiltered pass for the heads it left short (both launches exit at once when no head is marked).  The
+// candidates kernel of the same step has cleared the marks and laid the groups on the line (group_start, line_total).
+static int score_select_attend(lfps_ctx* ctx, const float* q, const KvView& v, const int32_t* k, int32_t* topk_idx,
+                               float* sel, float* out, const int32_t* skip_if, hipStream_t st) {
   const Shape& s = ctx->shape;
   int64_t* line_total = ctx->group_start + (int64_t)s.B * s.Hkv;
   const int32_t *only_g = nullptr, *only_h = nullptr;
@@ -428,19 +428,20 @@ static int score_and_select(lfps_ctx* ctx, const float* q, const KvView& v, cons
            launch_filter_score(s, q, v, ctx->cand, ctx->cand_count, ctx->group_start, line_total, ctx->thr_state,
                                kFilterMargin, ctx->score, ctx->slot, s.score_stride, ctx->seg_count, ctx->flags + 1,
                                ctx->filter_blocks[v.page.table ? 1 : 0], ctx->flags, st));
-    LAUNCH(ctx, LFPS_KERNEL_FILTER_SELECT, st,
-           launch_filter_select(s, ctx->score, ctx->slot, s.score_stride, ctx->seg_count, ctx->flags + 1, ctx->nseg,
-                                ctx->cand_count, ctx->group_start, line_total, k, topk_idx, sel, ctx->thr_state,
-                                ctx->redo_g, ctx->redo_h, skip_if, ctx->flags + 2, st));
+    LAUNCH(ctx, LFPS_KERNEL_FILTER_SELECT_ATTEND, st,
+           launch_filter_select_attend(s, ctx->cfg.kv_dtype, ctx->score, ctx->slot, s.score_stride, ctx->seg_count,
+                                       ctx->flags + 1, ctx->nseg, ctx->cand_count, ctx->group_start, line_total, k,
+                                       topk_idx, sel, ctx->thr_state, ctx->redo_g, ctx->redo_h, skip_if, ctx->flags + 2,
+                                       v, out, st));
     only_g = ctx->redo_g;
     only_h = ctx->redo_h;
   }
   LAUNCH(ctx, LFPS_KERNEL_GATHER_SCORE, st,
          launch_group_score(s, ctx->cfg.kv_dtype, q, v, ctx->cand, ctx->cand_count, ctx->score, s.score_stride,
                             only_g, ctx->flags, st));
-  LAUNCH(ctx, LFPS_KERNEL_SELECT, st,
-         launch_select(s, ctx->score, s.score_stride, ctx->cand, ctx->cand_count, k, topk_idx, sel, only_h,
-                       ctx->thr_state, skip_if, nullptr, st));
+  LAUNCH(ctx, LFPS_KERNEL_SELECT_ATTEND, st,
+         launch_select_attend(s, ctx->cfg.kv_dtype, ctx->score, s.score_stride, ctx->cand, ctx->cand_count, k, topk_idx,
+                              sel, only_h, ctx->thr_state, skip_if, v, out, st));
   return LFPS_OK;
 }
 
@@ -463,11 +464,7 @@ int lfps_step(lfps_ctx* ctx, const float* q, const lfps_kv* kv, const int32_t* p
   LAUNCH(ctx, LFPS_KERNEL_CANDIDATES, st,
          launch_candidates(s, prev_topk, k, v.seq_lens, ctx->cand, ctx->cand_count, ctx->flags, ctx->redo_g,
                            ctx->redo_h, ctx->filter_on ? ctx->group_start : nullptr, line_total, st));
-  rc = score_and_select(ctx, q, v, k, topk_idx, sel, nullptr, st);
-  if (rc != LFPS_OK) return rc;
-  LAUNCH(ctx, LFPS_KERNEL_SPARSE_ATTN, st,
-         launch_sparse_attn(s, ctx->cfg.kv_dtype, v, topk_idx, sel, k, out, nullptr, st));
-  return LFPS_OK;
+  return score_select_attend(ctx, q, v, k, topk_idx, sel, out, nullptr, st);
 }
 
 // ---------------------------------------------------------------------------- allocation-free S4
@@ -699,10 +696,8 @@ static int table_step_impl(lfps_ctx* ctx, const float* q, const KvView& v, const
   float* sel = topk_score ? topk_score : ctx->sel_score;
   int rc = table_candidates_impl(ctx, v.seq_lens, ctx->cand, ctx->cand_count, true, gate, st);
   if (rc != LFPS_OK) return rc;
-  rc = score_and_select(ctx, q, v, k, topk_idx, sel, gate, st);
+  rc = score_select_attend(ctx, q, v, k, topk_idx, sel, out, gate, st);
   if (rc != LFPS_OK) return rc;
-  LAUNCH(ctx, LFPS_KERNEL_SPARSE_ATTN, st,
-         launch_sparse_attn(s, ctx->cfg.kv_dtype, v, topk_idx, sel, k, out, gate, st));
   return table_update_impl(ctx, topk_idx, sel, k, v.seq_lens, gate, st);
 }
 

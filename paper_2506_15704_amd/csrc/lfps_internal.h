@@ -104,12 +104,21 @@ hipError_t launch_filter_score(const Shape& s, const float* q, const KvView& kv,
                                const float* thr_state, float margin, float* score,
                                int32_t* slot_out, int64_t score_stride, int32_t* seg_count, int32_t* seg_rows_out,
                                int n_blocks, int32_t* flags, hipStream_t st);
-hipError_t launch_filter_select(const Shape& s, const float* score, const int32_t* slot_in, int64_t score_stride,
-                                const int32_t* seg_count, const int32_t* seg_rows, int nseg,
-                                const int32_t* cand_count, const int64_t* group_start, int64_t* line_total,
-                                const int32_t* k, int32_t* topk_idx, float* topk_score,
-                                float* thr_state, int32_t* redo_g, int32_t* redo_h, const int32_t* skip_if,
-                                int32_t* rescored, hipStream_t st);
+// S3 + S4 of the chained steps in one kernel per stage of the filter (select_attend.hip).  From the survivor
+// lists of the filtered scoring pass: heads left short are marked in redo_g / redo_h (and counted in *rescored)
+// and not touched; the others get their Top-k rows (topk_idx, topk_score: both required) and their output row.
+hipError_t configure_select_attend(const Shape& s);
+hipError_t launch_filter_select_attend(const Shape& s, int dtype, const float* score, const int32_t* slot_in,
+                                       int64_t score_stride, const int32_t* seg_count, const int32_t* seg_rows, int nseg,
+                                       const int32_t* cand_count, const int64_t* group_start, int64_t* line_total,
+                                       const int32_t* k, int32_t* topk_idx, float* topk_score, float* thr_state,
+                                       int32_t* redo_g, int32_t* redo_h, const int32_t* skip_if, int32_t* rescored,
+                                       const KvView& kv, float* out, hipStream_t st);
+// From the full score rows [B, Hq, score_stride] over cand: every head, or (only_if [B,Hq]) the marked ones.
+hipError_t launch_select_attend(const Shape& s, int dtype, const float* score, int64_t score_stride, const int32_t* cand,
+                                const int32_t* cand_count, const int32_t* k, int32_t* topk_idx, float* topk_score,
+                                const int32_t* only_if, float* thr_state, const int32_t* skip_if, const KvView& kv,
+                                float* out, hipStream_t st);
 
 // Per (b, h): the k_b best of score[b,h,0:count]; count = cand_count[b, g(h)] when cand != NULL,
 // else seq_lens[b].  Writes positions (ascending) and their scores.
