@@ -196,7 +196,11 @@ int lfps_full_attn_decode(lfps_ctx* ctx, const float* q, const lfps_kv* kv, floa
 
 /* Baseline: exact Top-k, Sec. 1 Steps 1-2 over all n_b keys (the "exact Top-k" upper bound of
  * Sec. 5): scores every row, selects the k_b best per head.  Outputs as lfps_score_topk.
- * Also the seed of step 0 (the previous Top-k of the first LFPS step). */
+ * Also the seed of step 0 (the previous Top-k of the first LFPS step).
+ * With a 16-bit or FP8-key cache of about a million rows or more (batch * n_kv_heads * max_seq_len) and the score
+ * filter on, the scores are not written out and read back: a threshold per head is taken from a scored sample of
+ * the rows, one filtered pass over all rows keeps what reaches it, and heads left short are rescored the plain
+ * way, so the result is the same exact Top-k either way. */
 int lfps_exact_topk(lfps_ctx* ctx, const float* q, const lfps_kv* kv, const int32_t* k, int32_t* topk_idx,
                     float* topk_score, void* stream);
 

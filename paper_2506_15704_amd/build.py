@@ -11,7 +11,7 @@ PKG_DIR = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(PKG_DIR, "csrc")
 INCLUDE = os.path.join(os.path.dirname(PKG_DIR), "include")
 LIB_PATH = os.path.join(PKG_DIR, "liblfps.so")
-SOURCES = ["lfps_api.hip", "candidates.hip", "score.hip", "select.hip", "select_attend.hip", "attention.hip", "tables.hip"]
+SOURCES = ["lfps_api.hip", "candidates.hip", "score.hip", "select.hip", "select_attend.hip", "attention.hip", "tables.hip", "exact_topk.hip"]
 
 HIPCC_FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",

@@ -1,0 +1,91 @@
+// Exact Top-k baseline (Sec. 1 Steps 1-2 over all keys; the "exact Top-k" upper bound of Sec. 5), set-up of its
+// fast form.  Writing a score for every row and selecting from that array costs a second and further passes over
+// 4 bytes per row and head; instead the baseline takes the machinery of the chained steps:
+//   1. a strided sample of each group's rows is scored (the gather kernel) and, per head, the sample score of a
+//      rank chosen so that, with near certainty, at least k rows of the whole context reach it becomes a threshold;
+//   2. the filtered scoring kernel streams all rows once and keeps only those that reach the threshold;
+//   3. the select picks the exact k best from the survivors; a head whose survivors are fewer than k (or too many
+//      for the on-chip list) is rescored the plain way, so the result is always the exact Top-k.
+#include "lfps_internal.h"
+
+namespace lfps {
+
+// grid B*Hkv, 256 threads.
+__global__ __launch_bounds__(256) void k_dense_prep(Shape s, const int32_t* __restrict__ seq_lens,
+                                                    const int32_t* __restrict__ kk, int ns_max,
+                                                    int32_t* __restrict__ x_cnt, int64_t* __restrict__ x_start,
+                                                    int32_t* __restrict__ x_nsg, int32_t* __restrict__ x_ns,
+                                                    int32_t* __restrict__ x_rank, int32_t* __restrict__ sample,
+                                                    int32_t* __restrict__ redo_g, int32_t* __restrict__ redo_h) {
+  __shared__ long long part[256];
+  const int bg = blockIdx.x, b = bg / s.Hkv, g = bg % s.Hkv, tid = threadIdx.x;
+  const int n_groups = s.B * s.Hkv;
+  auto len = [&](int bb) {
+    int n = seq_lens[bb];
+    return n < 0 ? 0 : (n > s.Lcap ? s.Lcap : n);
+  };
+  // my place on the line: rows of the groups before mine (and, for the last group, the line's length)
+  long long before = 0, all = 0;
+  for (int i = tid; i < n_groups; i += 256) {
+    const long long n_i = len(i / s.Hkv);
+    before += i < bg ? n_i : 0;
+    all += n_i;
+  }
+  part[tid] = before;
+  __syncthreads();
+  for (int d = 128; d >= 1; d >>= 1) {
+    if (tid < d) part[tid] += part[tid + d];
+    __syncthreads();
+  }
+  const long long my_start = part[0];
+  __syncthreads();
+  part[tid] = all;
+  __syncthreads();
+  for (int d = 128; d >= 1; d >>= 1) {
+    if (tid < d) part[tid] += part[tid + d];
+    __syncthreads();
+  }
+  const long long total = part[0];
+  const int n = len(b);
+  int kb = kk[b];
+  kb = kb < 0 ? 0 : (kb > s.kmax ? s.kmax : kb);
+  kb = kb < n ? kb : n;
+  // the sample: ns rows i * n / ns (all rows when n is small)
+  int ns = ns_max < s.cand_cap ? ns_max : s.cand_cap;
+  ns = ns < n ? ns : n;
+  // the sample rank r: with p = k / n the number of sample rows among the true k best is Binomial(ns, p); four
+  // standard deviations above its mean (plus a few) leaves the r-th best sample score below the true k-th score
+  // except with probability ~1e-5 (and then the head is simply rescored).  With the whole context sampled, r = k.
+  int r = kb;
+  if (ns < n) {
+    const float p = (float)kb / (float)n;
+    const float mean = (float)ns * p, sd = sqrtf((float)ns * p * (1.f - p));
+    r = (int)ceilf(mean + 4.f * sd) + 4;
+  }
+  r = r > s.kmax ? s.kmax : r;
+  r = r > ns ? ns : r;
+  if (tid == 0) {
+    x_cnt[bg] = n;
+    x_start[bg] = my_start;
+    if (bg == n_groups - 1) x_start[n_groups] = total;
+    x_nsg[bg] = ns;
+    redo_g[bg] = 0;
+    if (g == 0) {
+      x_ns[b] = ns;
+      x_rank[b] = r;
+    }
+  }
+  if (tid < s.G) redo_h[(int64_t)b * s.Hq + (int64_t)g * s.G + tid] = 0;
+  int32_t* out = sample + (int64_t)bg * s.cand_cap;
+  for (int i = tid; i < ns; i += 256) out[i] = (int)(((long long)i * n) / ns);
+}
+
+hipError_t launch_dense_prep(const Shape& s, const int32_t* seq_lens, const int32_t* k, int ns_max, int32_t* x_cnt,
+                             int64_t* x_start, int32_t* x_nsg, int32_t* x_ns, int32_t* x_rank, int32_t* sample,
+                             int32_t* redo_g, int32_t* redo_h, hipStream_t st) {
+  hipLaunchKernelGGL(k_dense_prep, dim3(s.B * s.Hkv), dim3(256), 0, st, s, seq_lens, k, ns_max, x_cnt, x_start, x_nsg,
+                     x_ns, x_rank, sample, redo_g, redo_h);
+  return hipGetLastError();
+}
+
+}  // namespace lfps

@@ -39,6 +39,14 @@ struct lfps_ctx {
   int32_t* cand_count; // [B, Hkv]
   float* sel_score;    // [B, Hq, kmax]
   float* part;         // split partials of the full-attention baseline
+  // exact Top-k baseline in its filtered form (x_fast): the dense rows on the line, the sample and its rank
+  int x_fast;
+  int32_t* x_cnt;      // [B, Hkv] rows of each group
+  int32_t* x_nsg;      // [B, Hkv] sample rows of each group
+  int32_t* x_ns;       // [B] the same per request
+  int32_t* x_rank;     // [B] rank of the sample score taken as threshold
+  int64_t* x_start;    // [B*Hkv + 1] place of each group on the line of all rows, then the line's length
+  float* thr_x;        // [B, Hq] thresholds of the dense filtered pass
   int32_t* flags;      // [0] status flags, [1] part size chosen by the last filtered scoring pass, [2] heads rescored since the last poll
   int64_t ws_bytes;
   // timing
@@ -59,12 +67,15 @@ static const char* const kKernelNames[LFPS_N_KERNELS] = {
 
 // Margin below the previous step's k-th best score at which the filtered pass keeps a row.
 static const float kFilterMargin = 0.125f;
+// Exact Top-k baseline: rows sampled per KV group for the threshold, and the size from which the filtered form is used.
+static const int kExactSampleRows = 4096;
+static const int64_t kExactFastMinRows = 1 << 20;
 
 namespace {
 
 struct Sizes {
   int32_t G, cand_cap, score_stride, n_split_full, nseg, flag_words;
-  int64_t score_b, cand_b, count_b, sel_b, part_b, slot_b, seg_b, thr_b, redo_b, tver_b, tsla_b, tstate_b, tflag_b, total;
+  int64_t score_b, cand_b, count_b, sel_b, part_b, slot_b, seg_b, thr_b, redo_b, tver_b, tsla_b, tstate_b, tflag_b, x_b, total;
 };
 
 int64_t align256(int64_t x) { return (x + 255) & ~(int64_t)255; }
@@ -126,6 +137,12 @@ int check_config(const lfps_config* c, Sizes* z, char* err, size_t errn) {
   z->part_b = align256((int64_t)c->batch * c->n_kv_heads * z->n_split_full * G * (kD + 2) * 4);
   const bool filt = c->kv_dtype == LFPS_BF16 || c->kv_dtype == LFPS_F16;
   z->nseg = filter_nseg(s);
+  {
+    Shape sd = s;                        // the dense filtered pass of the exact Top-k baseline cuts all Lcap rows
+    sd.cand_cap = s.Lcap;
+    const int nd = filter_nseg(sd);
+    z->nseg = nd > z->nseg ? nd : z->nseg;
+  }
   z->slot_b = filt ? z->score_b : 0;
   z->seg_b = align256((int64_t)c->batch * c->n_q_heads * z->nseg * 4);
   z->thr_b = align256((int64_t)c->batch * c->n_q_heads * 4);
@@ -137,8 +154,9 @@ int check_config(const lfps_config* c, Sizes* z, char* err, size_t errn) {
   z->tsla_b = c->table_mode ? align256(heads * c->max_seq_len * 8) : 0;
   z->tstate_b = c->table_mode ? align256(heads * kTableStateDoubles * 8) : 0;
   z->tflag_b = c->table_mode ? align256(heads * z->flag_words * 4) : 0;
+  z->x_b = 3 * z->count_b + 2 * align256((int64_t)c->batch * 4) + align256(((int64_t)c->batch * c->n_kv_heads + 1) * 8) + z->thr_b;
   z->total = z->score_b + z->cand_b + z->count_b + z->sel_b + z->part_b + z->slot_b + z->seg_b + z->thr_b +
-             z->redo_b + 256 + z->tver_b + z->tsla_b + z->tstate_b + 2 * z->tflag_b + z->thr_b /* gate marks */;
+             z->redo_b + 256 + z->x_b + z->tver_b + z->tsla_b + z->tstate_b + 2 * z->tflag_b + z->thr_b /* gate marks */;
   return LFPS_OK;
 }
 
@@ -301,6 +319,16 @@ int lfps_create(const lfps_config* cfg, lfps_ctx** out) {
   p += z.redo_b;
   c->flags = (int32_t*)p;
   p += 256;
+  {
+    const int64_t per_b = align256((int64_t)cfg->batch * 4);
+    c->x_cnt = (int32_t*)p;
+    c->x_nsg = (int32_t*)(p + z.count_b);
+    c->x_ns = (int32_t*)(p + 2 * z.count_b);
+    c->x_rank = (int32_t*)(p + 2 * z.count_b + per_b);
+    c->x_start = (int64_t*)(p + 2 * z.count_b + 2 * per_b);
+    c->thr_x = (float*)(p + 2 * z.count_b + 2 * per_b + align256(((int64_t)cfg->batch * cfg->n_kv_heads + 1) * 8));
+    p += z.x_b;
+  }
   if (cfg->table_mode) {
     c->tab_ver = (float*)p;
     p += z.tver_b;
@@ -319,6 +347,9 @@ int lfps_create(const lfps_config* cfg, lfps_ctx** out) {
   // The filtered pass pays off only if a head's survivors (about 1.25 x its budget) fit the select's list; with a
   // budget too large for that every head would be rescored anyway, so such a context starts with the filter off.
   c->filter_on = (z.slot_b && (int64_t)cfg->max_k + cfg->max_k / 4 <= filter_list_cap(s)) ? 1 : 0;
+  // The exact Top-k baseline takes the filtered scoring pass too (threshold from a sample of the rows) once the
+  // contexts are large enough for the extra launches to pay: about a million rows in all.
+  c->x_fast = (z.slot_b && (int64_t)cfg->batch * cfg->n_kv_heads * cfg->max_seq_len >= kExactFastMinRows) ? 1 : 0;
   e = hipMemset(c->flags, 0, 256);
   if (e == hipSuccess) e = hipMemset(c->seg_count, 0, (size_t)(z.seg_b + z.thr_b + z.redo_b));   // counts, marks, line length
   if (e == hipSuccess) e = hipMemset(c->thr_state, 0xFF, (size_t)z.thr_b);   // all-ones = NaN: "no history"
@@ -427,7 +458,7 @@ static int score_select_attend(lfps_ctx* ctx, const float* q, const KvView& v, c
     LAUNCH(ctx, LFPS_KERNEL_FILTER_SCORE, st,
            launch_filter_score(s, q, v, ctx->cand, ctx->cand_count, ctx->group_start, line_total, ctx->thr_state,
                                kFilterMargin, ctx->score, ctx->slot, s.score_stride, ctx->seg_count, ctx->flags + 1,
-                               ctx->filter_blocks[v.page.table ? 1 : 0], ctx->flags, st));
+                               ctx->filter_blocks[v.page.table ? 1 : 0], ctx->flags, false, ctx->nseg, st));
     LAUNCH(ctx, LFPS_KERNEL_FILTER_SELECT_ATTEND, st,
            launch_filter_select_attend(s, ctx->cfg.kv_dtype, ctx->score, ctx->slot, s.score_stride, ctx->seg_count,
                                        ctx->flags + 1, ctx->nseg, ctx->cand_count, ctx->group_start, line_total, k,
@@ -573,11 +604,39 @@ int lfps_exact_topk(lfps_ctx* ctx, const float* q, const lfps_kv* kv, const int3
   if (rc != LFPS_OK) return rc;
   hipStream_t st = (hipStream_t)stream;
   const Shape& s = ctx->shape;
+  const int32_t *only_g = nullptr, *only_h = nullptr;
+  if (ctx->x_fast && ctx->filter_on) {      // (lfps_set_filter(ctx, 0) also selects the plain form)
+    // Threshold per head from a scored sample of the rows, then one filtered pass over all rows and the select from
+    // its survivors (exact_topk.hip); heads left short are rescored the plain way below.
+    Shape sd = s;
+    sd.cand_cap = s.Lcap;                 // the "candidates" of the dense pass are all rows of a group
+    int64_t* x_total = ctx->x_start + (int64_t)s.B * s.Hkv;
+    hipError_t e = launch_dense_prep(s, v.seq_lens, k, kExactSampleRows, ctx->x_cnt, ctx->x_start, ctx->x_nsg, ctx->x_ns,
+                                     ctx->x_rank, ctx->cand, ctx->redo_g, ctx->redo_h, st);
+    if (e != hipSuccess) return fail(ctx, LFPS_EHIP, "lfps_exact_topk (set-up)", e);
+    LAUNCH(ctx, LFPS_KERNEL_GATHER_SCORE, st,
+           launch_group_score(s, ctx->cfg.kv_dtype, q, v, ctx->cand, ctx->x_nsg, ctx->score, s.score_stride, nullptr,
+                              ctx->flags, st));
+    LAUNCH(ctx, LFPS_KERNEL_SELECT, st,      // the rank-th best sample score of every head -> thr_x (the rows go to scratch)
+           launch_select(s, ctx->score, s.score_stride, nullptr, ctx->x_ns, ctx->x_rank, ctx->slot, nullptr, nullptr,
+                         ctx->thr_x, nullptr, nullptr, st));
+    LAUNCH(ctx, LFPS_KERNEL_FILTER_SCORE, st,
+           launch_filter_score(sd, q, v, nullptr, ctx->x_cnt, ctx->x_start, x_total, ctx->thr_x, 0.f, ctx->score,
+                               ctx->slot, s.score_stride, ctx->seg_count, ctx->flags + 1,
+                               ctx->filter_blocks[v.page.table ? 1 : 0], ctx->flags, true, ctx->nseg, st));
+    LAUNCH(ctx, LFPS_KERNEL_FILTER_SELECT_ATTEND, st,
+           launch_filter_select_attend(sd, ctx->cfg.kv_dtype, ctx->score, ctx->slot, s.score_stride, ctx->seg_count,
+                                       ctx->flags + 1, ctx->nseg, ctx->x_cnt, ctx->x_start, x_total, k, topk_idx,
+                                       topk_score ? topk_score : ctx->sel_score, ctx->thr_x, ctx->redo_g, ctx->redo_h,
+                                       nullptr, nullptr, v, nullptr, st));
+    only_g = ctx->redo_g;
+    only_h = ctx->redo_h;
+  }
   LAUNCH(ctx, LFPS_KERNEL_DENSE_SCORE, st,
-         launch_group_score(s, ctx->cfg.kv_dtype, q, v, nullptr, nullptr, ctx->score, s.score_stride, nullptr, ctx->flags,
+         launch_group_score(s, ctx->cfg.kv_dtype, q, v, nullptr, nullptr, ctx->score, s.score_stride, only_g, ctx->flags,
                             st));
   LAUNCH(ctx, LFPS_KERNEL_SELECT, st,
-         launch_select(s, ctx->score, s.score_stride, nullptr, v.seq_lens, k, topk_idx, topk_score, nullptr, nullptr,
+         launch_select(s, ctx->score, s.score_stride, nullptr, v.seq_lens, k, topk_idx, topk_score, only_h, nullptr,
                        nullptr, nullptr, st));
   return LFPS_OK;
 }

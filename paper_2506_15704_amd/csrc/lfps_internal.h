@@ -103,7 +103,7 @@ hipError_t launch_filter_score(const Shape& s, const float* q, const KvView& kv,
                                const int32_t* cand_count, const int64_t* group_start, const int64_t* line_total,
                                const float* thr_state, float margin, float* score,
                                int32_t* slot_out, int64_t score_stride, int32_t* seg_count, int32_t* seg_rows_out,
-                               int n_blocks, int32_t* flags, hipStream_t st);
+                               int n_blocks, int32_t* flags, bool dense, int nseg, hipStream_t st);
 // S3 + S4 of the chained steps in one kernel per stage of the filter (select_attend.hip).  From the survivor
 // lists of the filtered scoring pass: heads left short are marked in redo_g / redo_h (and counted in *rescored)
 // and not touched; the others get their Top-k rows (topk_idx, topk_score: both required) and their output row.
@@ -113,7 +113,15 @@ hipError_t launch_filter_select_attend(const Shape& s, int dtype, const float* s
                                        const int32_t* cand_count, const int64_t* group_start, int64_t* line_total,
                                        const int32_t* k, int32_t* topk_idx, float* topk_score, float* thr_state,
                                        int32_t* redo_g, int32_t* redo_h, const int32_t* skip_if, int32_t* rescored,
-                                       const KvView& kv, float* out, hipStream_t st);
+                                       const KvView& kv, float* out, hipStream_t st);   // out == NULL: select only
+
+// Exact Top-k baseline, set-up of its filtered dense pass (exact_topk.hip): every group's rows 0..n_b-1 laid on the
+// line (x_cnt, x_start, x_start[B*Hkv] = the line's length), a strided sample of at most ns_max rows per group
+// (sample [B, Hkv, cand_cap], x_nsg [B*Hkv] / x_ns [B] its length) and the rank x_rank [B] whose sample score is
+// taken as the threshold; the redo marks are cleared.
+hipError_t launch_dense_prep(const Shape& s, const int32_t* seq_lens, const int32_t* k, int ns_max, int32_t* x_cnt,
+                             int64_t* x_start, int32_t* x_nsg, int32_t* x_ns, int32_t* x_rank, int32_t* sample,
+                             int32_t* redo_g, int32_t* redo_h, hipStream_t st);
 // From the full score rows [B, Hq, score_stride] over cand: every head, or (only_if [B,Hq]) the marked ones.
 hipError_t launch_select_attend(const Shape& s, int dtype, const float* score, int64_t score_stride, const int32_t* cand,
                                 const int32_t* cand_count, const int32_t* k, int32_t* topk_idx, float* topk_score,

@@ -285,7 +285,9 @@ __global__ __launch_bounds__(kScoreThreads) void k_group_score_bf16(Shape s, con
 // A threshold of -inf keeps every row; NaN means there is no previous step.
 constexpr int kFilterStage = 256;   // survivors one wave can hold per head before it must write them out
 
-template <int G, bool kPaged, int kKind>
+// kDense: the "candidates" of a group are all its rows 0..count-1 (no list is read): the exact Top-k baseline's
+// scoring pass with a threshold from a sample of the rows.
+template <int G, bool kPaged, int kKind, bool kDense>
 __global__ __launch_bounds__(kScoreThreads, 2) void k_filter_score_bf16(
     Shape s, const float* __restrict__ q, const void* __restrict__ K, int64_t stride_b, int64_t stride_h,
     int64_t stride_n, KvPage page, const int32_t* __restrict__ seq_lens, const int32_t* __restrict__ cand,
@@ -422,7 +424,9 @@ __global__ __launch_bounds__(kScoreThreads, 2) void k_filter_score_bf16(
     // two tiles in flight are exact counts instead of "everything outstanding".
     auto fetch_ids = [&](int base_slot) {
       const int sl = base_slot + lane;
-      return cbg[sl < seg_hi ? sl : seg_hi - 1];
+      const int at = sl < seg_hi ? sl : seg_hi - 1;
+      if constexpr (kDense) return at;
+      else return cbg[at];
     };
 
     // Row ids are fetched three tiles ahead, always BEFORE the loads of the tile that precedes
@@ -699,8 +703,8 @@ static hipError_t filter_resident_blocks(int out[2]) {
     if (per_cu > 2) per_cu = 2;
     *n = per_cu * prop.multiProcessorCount;
   };
-  resident((const void*)k_filter_score_bf16<G, false, kKind>, &out[0]);
-  resident((const void*)k_filter_score_bf16<G, true, kKind>, &out[1]);
+  resident((const void*)k_filter_score_bf16<G, false, kKind, false>, &out[0]);
+  resident((const void*)k_filter_score_bf16<G, true, kKind, false>, &out[1]);
   return e;
 }
 
@@ -728,17 +732,22 @@ hipError_t launch_filter_score(const Shape& s, const float* q, const KvView& kv,
                                const int32_t* cand_count, const int64_t* group_start, const int64_t* line_total,
                                const float* thr_state, float margin, float* score,
                                int32_t* slot_out, int64_t score_stride, int32_t* seg_count, int32_t* seg_rows_out,
-                               int n_blocks, int32_t* flags, hipStream_t st) {
-  const int nseg = filter_nseg(s);
+                               int n_blocks, int32_t* flags, bool dense, int nseg, hipStream_t st) {
   if (n_blocks < 1) return hipErrorInvalidValue;
   const bool f16 = kv.f16;
   dim3 grid((unsigned)n_blocks), block(kScoreThreads);
   const float scale = 0.08838834764831845f;
-#define LFPS_LAUNCH_FILTER_P(GG, PAGED, FP8)                                                                       \
-  hipLaunchKernelGGL((k_filter_score_bf16<GG, PAGED, FP8>), grid, block, 0, st, s, q, kv.k, kv.stride_b,           \
+#define LFPS_LAUNCH_FILTER_D(GG, PAGED, FP8, DENSE)                                                                \
+  hipLaunchKernelGGL((k_filter_score_bf16<GG, PAGED, FP8, DENSE>), grid, block, 0, st, s, q, kv.k, kv.stride_b,    \
                      kv.stride_h, kv.stride_n, kv.page, kv.seq_lens, cand, cand_count, group_start, line_total,    \
                      thr_state, margin, score, slot_out, score_stride, seg_count, seg_rows_out,                    \
                      filter_min_seg_rows(s), nseg, scale, flags)
+#define LFPS_LAUNCH_FILTER_P(GG, PAGED, FP8)       \
+  if (dense) {                                     \
+    LFPS_LAUNCH_FILTER_D(GG, PAGED, FP8, true);    \
+  } else {                                         \
+    LFPS_LAUNCH_FILTER_D(GG, PAGED, FP8, false);   \
+  }
 #define LFPS_LAUNCH_FILTER(GG)                        \
   if (kv.page.table && kv.k_fp8) {                    \
     LFPS_LAUNCH_FILTER_P(GG, true, kKindFp8);         \
@@ -760,6 +769,7 @@ hipError_t launch_filter_score(const Shape& s, const float* q, const KvView& kv,
     default: return hipErrorInvalidValue;
   }
 #undef LFPS_LAUNCH_FILTER_P
+#undef LFPS_LAUNCH_FILTER_D
 #undef LFPS_LAUNCH_FILTER
   return hipGetLastError();
 }

@@ -180,6 +180,7 @@ __global__ __launch_bounds__(kFilterSelThreads) void k_filter_select_attend(
   }
   // ---- S4 over the rows just selected.  The barrier orders this workgroup's stores of (position, score) before
   // its loads of them, and frees the select's LDS for the partial sums.
+  if (out == nullptr) return;                       // select only (the exact Top-k baseline)
   __syncthreads();
   AttendShared& as = *reinterpret_cast<AttendShared*>(cache);
   attend_rows<T, kSelWaves, kPaged>(as, V, stride_b, stride_h, stride_n, page, b, g, n, kb, oi, os, ksel > 0, top,

@@ -173,3 +173,58 @@ def test_rescored_heads_are_counted():
     assert ctx.lfps_poll_rescored() == spec.B * spec.Hq
     assert ctx.lfps_poll_status() == 0
     ctx.close()
+
+
+@pytest.mark.parametrize("variant", ["bf16", "fp8", "ragged_small_k", "paged"])
+def test_exact_topk_filtered_form_equals_plain_form(variant):
+    """Contexts of a million rows and more take the exact Top-k baseline through a sampled threshold and the
+    filtered scoring pass; with the filter switched off the same context scores and selects the plain way.  Both
+    must return the same rows and scores for every head (ascending positions, ties to the lower position), and
+    sampled heads are checked against the oracle."""
+    kw = dict(B=4, L=33000, k=512, r=1, T=1, n_hot=8, recency=32)
+    if variant == "fp8":
+        kw.update(k_dtype="fp8")
+    if variant == "ragged_small_k":
+        kw.update(L=None, L_range=(20000, 40000), k=None, k_frac=0.004, B=6)
+    spec = gen.tiny_spec("xfast_" + variant, **kw)
+    dc = DeviceCase(spec)
+    case = dc.case
+    assert spec.B * spec.Hkv * case.Lcap >= 1 << 20
+    fast, plain = dc.make_ctx(), dc.make_ctx()
+    plain.lfps_set_filter(False)
+    shp = (spec.B, spec.Hq, case.kmax)
+    if variant == "paged":
+        from gen import device as gen_device
+        Kp, Vp, bt = gen_device.paginate(dc.K, dc.V, 32, seed=5, layout="block_head_row")
+        view = lambda ctx: ctx.paged_kv_view(Kp, Vp, bt, dc.seq_lens(1))
+    else:
+        view = lambda ctx: ctx.kv_view(dc.K, dc.V, dc.seq_lens(1))
+    res = []
+    for ctx in (fast, plain):
+        ctx.lfps_timing_enable(True)
+        idx = torch.zeros(shp, dtype=torch.int32, device=DEV)
+        sc = torch.zeros(shp, dtype=torch.float32, device=DEV)
+        ctx.lfps_exact_topk(dc.q(1), view(ctx), dc.k, idx, sc)
+        tm = ctx.lfps_timing_read()
+        assert ctx.lfps_poll_status() == 0
+        res.append((idx, sc, tm))
+    assert res[0][2]["filter_score"][1] == 1 and res[1][2]["filter_score"][1] == 0     # the two forms did run
+    assert torch.equal(res[0][0], res[1][0])
+    assert torch.equal(res[0][1], res[1][1])
+    # without the scores output as well
+    idx2 = torch.zeros(shp, dtype=torch.int32, device=DEV)
+    fast.lfps_exact_topk(dc.q(1), view(fast), dc.k, idx2)
+    assert torch.equal(idx2, res[0][0])
+    idx_h = res[0][0].cpu().numpy()
+    n = case.seq_lens(1)
+    for (b, g) in ((0, 0), (spec.B - 1, 5)):
+        K, _ = dc.group(b, g)
+        kb = int(case.k[b])
+        for hh in range(spec.G):
+            h = spec.G * g + hh
+            I, _ = orc.exact_topk(case.q[1, b, h], K, int(n[b]), kb)
+            assert_topk_equal_mod_ties(idx_h[b, h, :kb], I, lambda p: orc.scores(case.q[1, b, h], K, p), kb,
+                                       f"{variant} b{b} h{h}")
+            assert np.all(idx_h[b, h, kb:] == -1)
+    fast.close()
+    plain.close()
