@@ -24,12 +24,16 @@ if ROOT not in sys.path:
 
 HBM_PEAK_GBS = 8000.0   # MI355X published HBM3E peak
 
-# HBM bytes per launch of the scoring kernel measured with rocprofv3 --pmc (FETCH_SIZE, WRITE_SIZE), scaled
-# by the same counters' reading for a plain copy kernel; see profiles/ for the runs.  None = not measured.
-# Median over the steady-state dispatches of the scoring kernel (k_filter_score_bf16):
-#   profiles/lfps_kernels_C4.md: 941.1 MB fetched + 10.5 MB written; C3: 222.4 + 3.1 MB; C5: 476.9 + 8.9 MB;
-#   with FP8 keys (C4, same file): 477.8 + 10.5 MB.
-MEASURED_TRAFFIC_BYTES = {"C4": 951.6e6, "C3": 225.5e6, "C5": 485.8e6, "C4-fp8k": 488.3e6}
+def measured_traffic(key, kernel="filter_score"):
+    """HBM bytes per launch of a kernel as rocprofv3 counted them (--pmc FETCH_SIZE, then WRITE_SIZE, each scaled by
+    the same counter's reading for a plain copy kernel of known size): profiles/traffic.json, written together with
+    the summaries under profiles/ from the same runs.  None when that workload / kernel was not profiled."""
+    try:
+        with open(os.path.join(ROOT, "profiles", "traffic.json")) as f:
+            rec = json.load(f).get(key, {}).get(kernel)
+    except (OSError, ValueError):
+        return None
+    return None if rec is None else float(rec["fetch_bytes"]) + float(rec["write_bytes"])
 
 
 def parse_args():
@@ -54,11 +58,13 @@ def parse_args():
                     help="run only the score-table mode of the main workload (for profiling) and print its record")
     ap.add_argument("--calib-copy", action="store_true",
                     help="run only the plain copy kernel (1 GiB, 10 launches): the known-traffic reference for rocprofv3 --pmc")
+    ap.add_argument("--peaky-only", action="store_true",
+                    help="run only the concentrated-attention variant of C4 (memoryless and score-table steps) and print its record")
     ap.add_argument("--sweep", action="store_true",
                     help="run only a grid of batch sizes and context lengths with the C4 recipe and print its record")
     ap.add_argument("--sweep-batches", default="1,4,16,32", help="batch sizes of --sweep")
     ap.add_argument("--sweep-contexts", default="32768,131072,524288", help="context lengths of --sweep")
-    ap.add_argument("--cpu-seconds", type=float, default=12.0, help="CPU-oracle sample budget")
+    ap.add_argument("--cpu-seconds", type=float, default=8.0, help="CPU-oracle sample budget (per leg: one core, all cores)")
     return ap.parse_args()
 
 
@@ -75,7 +81,7 @@ class Runner:
         from paper_2506_15704_amd.binding import Lfps
 
         self.torch, self.np = torch, np
-        self.spec = spec = gen.WORKLOADS[name]
+        self.spec = spec = gen.WORKLOADS.get(name) or gen.EXTRA_WORKLOADS[name]
         if override:         # the same recipe at another batch size / context length / budget (--sweep)
             import dataclasses
             self.spec = spec = dataclasses.replace(spec, **override)
@@ -274,11 +280,12 @@ class Runner:
         torch.cuda.synchronize()
         return (time.perf_counter() - t0) / reps
 
-    def recall_vs_exact(self):
+    def recall_vs_exact(self, ex=None):
         """Eq. 2 overlap of the chained LFPS Top-k with the exact Top-k at the last step run."""
         torch = self.torch
-        ex = torch.zeros_like(self.seed)
-        self.ctx.lfps_exact_topk(self.q[self.t], self.views[self.t], self.k, ex)
+        if ex is None:
+            ex = torch.zeros_like(self.seed)
+            self.ctx.lfps_exact_topk(self.q[self.t], self.views[self.t], self.k, ex)
         got = self.prev
         L = int(self.seq[self.t].max().item()) + 1
         hits = 0
@@ -287,9 +294,34 @@ class Runner:
             kb = int(self.case.k[b])
             a = torch.zeros((self.spec.Hq, L), dtype=torch.bool, device=self.dev)
             a.scatter_(1, ex[b, :, :kb].long(), True)
-            hits += int(a.gather(1, got[b, :, :kb].clamp_min(0).long()).sum().item())
+            g = got[b, :, :kb]
+            hits += int((a.gather(1, g.clamp_min(0).long()) & (g >= 0)).sum().item())
             tot += self.spec.Hq * kb
         return hits / tot
+
+    def quality_per_step(self, n_steps):
+        """The free-running chain from the seed, step by step: Eq. 2 overlap of its Top-k with the exact Top-k of
+        the same query, and the largest absolute difference between its output rows and full attention's
+        (both references computed by this library's baselines on the device: statistics, not parity)."""
+        torch = self.torch
+        self.reset()
+        self.ctx.lfps_reset_history()
+        ex = torch.zeros_like(self.seed)
+        full = torch.zeros_like(self.out)
+        rec, err, byp = [], [], []
+        for _ in range(n_steps):
+            self.step()
+            t = self.t
+            self.ctx.lfps_exact_topk(self.q[t], self.views[t], self.k, ex)
+            self.ctx.lfps_full_attn_decode(self.q[t], self.views[t], full)
+            rec.append(round(self.recall_vs_exact(ex), 4))
+            err.append(round(float((self.out - full).abs().max().item()), 4))
+            if self.gated:
+                byp.append(round(float(self.gate.float().mean().item()), 4))
+        res = {"steps": n_steps, "recall_vs_exact_topk": rec, "max_abs_err_vs_full_attn": err}
+        if self.gated:
+            res["bypassed_head_frac"] = byp      # (a bypassed head selects nothing: it counts as recall 0)
+        return res
 
     def close(self):
         self.ctx.close()
@@ -309,7 +341,7 @@ def algorithmic_bytes_score(spec, case, cnts, filtered):
     return rows * (spec.D * e + 4 + 4 * spec.G) + cnts.shape[1] * cnts.shape[2] * per_group
 
 
-def measure(name, steps, warmup, with_baselines=True, use_graph=True, override=None):
+def measure(name, steps, warmup, with_baselines=True, use_graph=True, override=None, with_quality=False):
     r = Runner(name, override=override)
     spec = r.spec
     if steps <= 0:
@@ -331,7 +363,7 @@ def measure(name, steps, warmup, with_baselines=True, use_graph=True, override=N
         "ms_per_step_hip_graph": round(sec_graph * 1e3, 4) if sec_graph else None, "hip_graph_matches_eager": graph_ok,
         "roofline": {"bound": "hbm", "kernel": kname, "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS,
                      "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4),
-                     "traffic": MEASURED_TRAFFIC_BYTES.get(name),
+                     "traffic": measured_traffic(spec.name, kname),
                      "bytes_per_launch": round(bytes_per_launch), "avg_launch_us": round(gs_avg_s * 1e6, 2),
                      "launches": gs_n, "timed_by": "HIP events around each launch, second pass over the same steps",
                      "note": "redo launches of gather_score (heads the filter left short) are in kernel_us"},
@@ -358,12 +390,36 @@ def measure(name, steps, warmup, with_baselines=True, use_graph=True, override=N
     res["sparse_attn"] = {"avg_launch_us": round(at_us, 2), "bytes_per_head_rows": round(upper), "bytes_group_union_last_step": round(lower),
                           "GB_per_s_at_union_bytes": round(lower / (at_us * 1e-6) / 1e9, 1) if at_us > 0 else None,
                           "GB_per_s_at_per_head_bytes": round(upper / (at_us * 1e-6) / 1e9, 1) if at_us > 0 else None}
+    # The whole step against the HBM roofline: the bytes one step must move at least (per KV group with c candidates
+    # and budget k per head, R bytes per row: S1 reads G k ids and writes c; S2 reads c rows and their ids and writes
+    # the survivors' (score, position) pairs, at least k per head; S3 reads them and writes k (position, score) pairs
+    # per head; S4 reads those and one V row per selected position of the group) over the median step time.
+    e_k = 1 if spec.k_dtype == "fp8" else (4 if spec.kv_dtype == "f32" else 2)
+    ksum = float(r.case.k.sum())
+    rows_scored = float(cnts.sum(axis=(1, 2)).mean())
+    s1 = ksum * spec.Hq * 4 + rows_scored * 4
+    s2 = rows_scored * (spec.D * e_k + 4) + ksum * spec.Hq * 8 + spec.B * spec.Hq * spec.D * 4
+    s3 = 2 * ksum * spec.Hq * 8
+    s4 = ksum * spec.Hq * 8 + lower + spec.B * spec.Hq * spec.D * 4
+    step_bytes = s1 + s2 + s3 + s4
+    res["whole_step"] = {"bytes": round(step_bytes), "GB_per_s": round(step_bytes / (step_us["median"] * 1e-6) / 1e9, 1),
+                         "frac_of_hbm_peak": round(step_bytes / (step_us["median"] * 1e-6) / 1e9 / HBM_PEAK_GBS, 4),
+                         "bytes_by_stage": {"S1": round(s1), "S2": round(s2), "S3": round(s3), "S4": round(s4)}}
+    res["sparse_attn"]["frac_of_hbm_peak_at_union_bytes"] = round(lower / (at_us * 1e-6) / 1e9 / HBM_PEAK_GBS, 4) if at_us > 0 else None
+    if with_quality:
+        res["per_step"] = r.quality_per_step(spec.T)
     if with_baselines:
         reps = 5 if name in ("C4", "C5") or override else 20
         exact = r.time_baseline("exact", reps)
         full = r.time_baseline("full", reps)
         res.update({"exact_topk_ms": round(exact * 1e3, 4), "full_attn_ms": round(full * 1e3, 4),
                     "speedup_vs_exact_topk": round(exact / sec, 3), "speedup_vs_full_attn": round(full / sec, 3)})
+        # what the bytes alone would give: the exact Top-k baseline must read every K row once and the V rows of
+        # its selection; full attention every K and V row
+        n_rows = float(r.case.seq_lens(min(spec.T, 2)).sum()) * spec.Hkv
+        x_bytes = n_rows * spec.D * e_k + lower
+        res["byte_ratio_vs_exact_topk"] = round(x_bytes / step_bytes, 3)
+        res["exact_topk_frac_of_hbm_peak"] = round(x_bytes / exact / 1e9 / HBM_PEAK_GBS, 4)
         # the contiguous stream of the full-attention baseline as the "achievable" reference beside the 8 TB/s peak
         t_ref = min(spec.T, 2)
         stream_bytes = 2.0 * float(r.case.seq_lens(t_ref).sum()) * spec.Hkv * row_bytes
@@ -448,7 +504,7 @@ def measure_fp8_keys(name, steps, warmup, with_v=False):
            "cand_frac": round(float(cnts.mean() / (spec.L or r.case.seq_lens0.mean())), 4),
            "recall_vs_exact_topk": round(recall, 4),
            "kernel_us": {k: round(v[0] / steps * 1e3, 2) for k, v in tm.items() if v[1]},
-           "score_kernel": {"kernel": kname, "bytes_per_launch": round(by), "traffic": MEASURED_TRAFFIC_BYTES.get(spec.name),
+           "score_kernel": {"kernel": kname, "bytes_per_launch": round(by), "traffic": measured_traffic(spec.name, kname),
                             "avg_launch_us": round(us, 2),
                             "GB_per_s": round(by / (us * 1e-6) / 1e9, 1) if us > 0 else None,
                             "frac_of_hbm_peak": round(by / (us * 1e-6) / 1e9 / HBM_PEAK_GBS, 4) if us > 0 else None},
@@ -482,7 +538,7 @@ def measure_fp16_cache(name, steps, warmup):
     return res
 
 
-def measure_tables(name, steps, warmup):
+def measure_tables(name, steps, warmup, with_quality=False):
     """The same workload with the paper's own candidate rule (score tables, Eq. 7-10): lfps_table_step per step,
     tables initialised from the step-0 query (Eq. 4 with one query) during warm-up; first four rows = sinks,
     kept outside the tables as in the paper.  Reported next to the memoryless path, not as `value`."""
@@ -521,6 +577,8 @@ def measure_tables(name, steps, warmup):
                           "GB_per_s": round(scan_bytes / (scan_us * 1e-6) / 1e9, 1) if scan_us > 0 else None,
                           "frac_of_hbm_peak": round(scan_bytes / (scan_us * 1e-6) / 1e9 / HBM_PEAK_GBS, 4) if scan_us > 0 else None},
            "heads": heads}
+    if with_quality:
+        res["per_step"] = r.quality_per_step(spec.T)
     r.close()
     # the same with the head-sparsity bypass in front (Eq. 5-6, eps = 0.85, six local rows)
     rg = Runner(name, table_mode=True, n_sink=4, gated=True)
@@ -528,13 +586,93 @@ def measure_tables(name, steps, warmup):
     sec_g = rg.run_timed(steps, max(warmup, 1))
     res["with_bypass"] = {"ms_per_step": round(sec_g * 1e3, 4), "eps": 0.85, "n_local": 6,
                           "bypassed_head_frac_last_step": round(float(rg.gate.float().mean().item()), 4)}
+    if with_quality:
+        res["with_bypass"]["per_step"] = rg.quality_per_step(spec.T)
     rg.close()
     return res
 
 
+def measure_peaky(steps, warmup):
+    """The concentrated-attention variant of C4 (gen.C4_PEAKY: a few hundred rows per KV group carry most of the
+    softmax mass and the sinks are strong), on which the paper's own rule has something to find: the memoryless step,
+    the score-table step and the score-table step with the head-sparsity bypass, each with its candidate fraction
+    (the paper's Table 4 reports 1.7 % of the positions scored at 128K, a = 0.2), Eq. 2 recall and error against
+    full attention per step."""
+    name = "C4-peaky"
+    mem, _ = measure(name, steps, warmup, with_baselines=True, use_graph=False, with_quality=True)
+    tab = measure_tables(name, steps, warmup, with_quality=True)
+    keep = ("ms_per_step", "steps_per_s", "cand_frac", "kernel_us", "per_step", "exact_topk_ms", "full_attn_ms",
+            "speedup_vs_exact_topk", "speedup_vs_full_attn")
+    return {"workload": "C4 with concentrated attention: 384 hot rows per KV group at logit +6.7, sinks at +13.5",
+            "paper_table4_fraction_scored_128k_a0.2": 0.017,
+            "memoryless": {k: mem[k] for k in keep if k in mem},
+            "score_table": {k: tab[k] for k in ("ms_per_step", "steps_per_s", "cand_frac", "kernel_us", "per_step", "with_bypass")},
+            "table_step_over_memoryless_step": round(tab["ms_per_step"] / mem["ms_per_step"], 3)}
+
+
+def _oracle_chain_worker(spec, b, g, n_steps, barrier, results):
+    """One host process of the all-cores oracle timing: the oracle's chained lfps_step on one (request, KV group),
+    started together with the other workers (inputs are generated before the barrier and not timed)."""
+    import numpy as np  # noqa: F401
+    from threadpoolctl import threadpool_limits
+
+    import gen
+    from oracle import lfps_oracle as orc
+
+    case = gen.make_case(spec)
+    K, V = case.kv_group(b, g)
+    kb = int(case.k[b])
+    with threadpool_limits(limits=1):
+        prev = [orc.exact_topk(case.q[0, b, spec.G * g + h], K, int(case.seq_lens0[b]), kb)[0] for h in range(spec.G)]
+        barrier.wait()
+        t0 = time.perf_counter()
+        for t in range(1, n_steps + 1):
+            res = orc.lfps_step(case.q[t, b, spec.G * g: spec.G * (g + 1)], K, V, prev, int(case.seq_lens(t)[b]), kb,
+                                spec.r, 1, 0)
+            prev = res["topk_idx"]
+        results.put((n_steps, time.perf_counter() - t0))
+
+
+def cpu_baseline_all_cores(spec, per_group_step_s, budget_s):
+    """The oracle's lfps_step on every host core at once: one process per core, each chaining the decode steps of
+    its own (request, KV group), all started together.  Returns (group-steps per second over all workers, workers,
+    steps per worker)."""
+    import multiprocessing as mp
+
+    cores = int(os.environ.get("OMP_NUM_THREADS") or 0) or min(os.cpu_count() or 1, 16)
+    cores = max(1, min(cores, 16, spec.B * spec.Hkv))
+    n_steps = int(max(1, min(spec.T, budget_s / max(per_group_step_s, 1e-6))))
+    ctx = mp.get_context("spawn")                 # the parent holds the GPU: workers start clean and never touch it
+    barrier, results = ctx.Barrier(cores), ctx.Queue()
+    groups = [((7 * i + 1) % spec.B, (3 * i + 2) % spec.Hkv) for i in range(cores)]
+    procs = [ctx.Process(target=_oracle_chain_worker, args=(spec, b, g, n_steps, barrier, results)) for (b, g) in groups]
+    import queue
+    for p_ in procs:
+        p_.start()
+    got, deadline = [], time.perf_counter() + 600
+    try:
+        while len(got) < len(procs):
+            try:
+                got.append(results.get(timeout=1.0))
+            except queue.Empty:
+                if any(p_.exitcode not in (None, 0) for p_ in procs) or time.perf_counter() > deadline:
+                    raise RuntimeError("a worker of the all-cores oracle timing ended early")
+    except RuntimeError:
+        barrier.abort()
+        for p_ in procs:
+            if p_.is_alive():
+                p_.terminate()
+        raise
+    finally:
+        for p_ in procs:
+            p_.join(timeout=30)
+    slowest = max(t for _, t in got)
+    return sum(n for n, _ in got) / slowest, cores, n_steps
+
+
 def cpu_baseline(case, budget_s):
-    """The oracle's LFPS step (fp64 numpy, one thread) chained over a few steps on a sample of
-    (request, KV group) pairs, scaled to the whole batch."""
+    """The oracle's LFPS step (fp64 numpy) on a bounded sample of (request, KV group) pairs chained over the decode
+    steps, scaled to the whole batch: on all host cores at once (`value`, one process per core) and on one thread."""
     import numpy as np
     from threadpoolctl import threadpool_limits
 
@@ -579,13 +717,21 @@ def cpu_baseline(case, budget_s):
     per_group_step = spent / max(done, 1)
     groups_n = spec.B * spec.Hkv
     step_s = per_group_step * groups_n
-    return {"value": 1.0 / step_s, "unit": "steps/s", "cores": 1, "kind": "oracle",
-            "sample": f"{done} oracle lfps_step calls (fp64 numpy, 1 thread) on (request, KV group) samples of {spec.name}, "
-                      f"{per_group_step * 1e3:.1f} ms each, scaled by B*Hkv = {groups_n} groups per step",
-            "oracle_exact_topk_steps_per_s": 1.0 / (exact_group * groups_n),
-            "oracle_full_attn_steps_per_s": 1.0 / (full_group * groups_n),
-            "oracle_speedup_vs_exact_topk": exact_group / per_group_step,
-            "host_cores_available": os.cpu_count()}
+    one_core = {"value": 1.0 / step_s, "unit": "steps/s", "cores": 1,
+                "sample": f"{done} oracle lfps_step calls (fp64 numpy, 1 thread) on (request, KV group) samples of {spec.name}, "
+                          f"{per_group_step * 1e3:.1f} ms each, scaled by B*Hkv = {groups_n} groups per step",
+                "oracle_exact_topk_steps_per_s": 1.0 / (exact_group * groups_n),
+                "oracle_full_attn_steps_per_s": 1.0 / (full_group * groups_n),
+                "oracle_speedup_vs_exact_topk": exact_group / per_group_step}
+    try:
+        rate, cores, n_chain = cpu_baseline_all_cores(spec, per_group_step, budget_s)
+    except Exception as exc:                        # the one-core figure stands in, and says so
+        return {**one_core, "kind": "oracle", "all_cores_failed": repr(exc), "host_cores_available": os.cpu_count()}
+    return {"value": rate / groups_n, "unit": "steps/s", "cores": cores, "kind": "oracle",
+            "sample": f"{cores} host processes at once (one per core, fp64 numpy, 1 thread each), each chaining {n_chain} oracle "
+                      f"lfps_step calls on its own (request, KV group) of {spec.name}; {rate:.1f} group-steps/s in all, "
+                      f"scaled by B*Hkv = {groups_n} groups per step",
+            "one_core": one_core, "host_cores_available": os.cpu_count()}
 
 
 def main():
@@ -622,6 +768,9 @@ def main():
                              args.steps if args.steps > 0 else 6, args.warmup)
         print(json.dumps({"sweep": "C4 recipe (bf16, r=4, k=L/64)", "rows": rows}), flush=True)
         return
+    if args.peaky_only:
+        print(json.dumps({"peaky_workload": measure_peaky(args.steps, args.warmup)}), flush=True)
+        return
     if args.table_only:
         print(json.dumps({"workload": args.workload, "score_table_mode": measure_tables(args.workload, args.steps, args.warmup)}),
               flush=True)
@@ -636,7 +785,7 @@ def main():
                           "paged_kv": measure_paged(args.workload, args.steps, args.warmup, args.paged_block, args.paged_layout)}),
               flush=True)
         return
-    main_res, case = measure(args.workload, args.steps, args.warmup)
+    main_res, case = measure(args.workload, args.steps, args.warmup, with_quality=True)
     spec = case.spec
     line = {
         "metric": "LFPS decode steps/s per layer", "value": round(main_res["steps_per_s"], 2), "unit": "steps/s",
@@ -655,12 +804,15 @@ def main():
         "exact_topk_ms": main_res.get("exact_topk_ms"), "full_attn_ms": main_res.get("full_attn_ms"),
         "speedup_vs_exact_topk": main_res.get("speedup_vs_exact_topk"),
         "speedup_vs_full_attn": main_res.get("speedup_vs_full_attn"),
+        "byte_ratio_vs_exact_topk": main_res.get("byte_ratio_vs_exact_topk"),
+        "exact_topk_frac_of_hbm_peak": main_res.get("exact_topk_frac_of_hbm_peak"),
+        "whole_step": main_res["whole_step"], "per_step": main_res.get("per_step"),
     }
     # the paper's own figures (its Sec. 5: indexing on one Xeon Gold 6430 core, attention on an RTX 4090): context only
     line["paper_context"] = {"speedup_vs_full_attention": 22.8, "speedup_vs_exact_topk": 9.6,
                              "note": "other hardware and a trained model's attention; not a target for this metric"}
     if not args.no_table_mode:
-        tab = measure_tables(args.workload, args.steps, args.warmup)
+        tab = measure_tables(args.workload, args.steps, args.warmup, with_quality=True)
         tab["speedup_vs_memoryless_step"] = round(main_res["ms_per_step"] / tab["ms_per_step"], 3)
         line["score_table_mode"] = tab
     if not args.no_fp8 and spec.kv_dtype == "bf16":
@@ -674,10 +826,13 @@ def main():
         for name in ("C1", "C2", "C3", "C4", "C5"):
             if name == args.workload:
                 continue
-            res, _ = measure(name, 0, args.warmup)
+            res, _ = measure(name, 0, args.warmup, with_quality=True)
             others[name] = {k: res[k] for k in ("steps_per_s", "ms_per_step", "ms_per_step_hip_graph", "cand_frac", "recall_vs_exact_topk",
-                                                "speedup_vs_exact_topk", "speedup_vs_full_attn", "kernel_us")}
+                                                "speedup_vs_exact_topk", "speedup_vs_full_attn", "byte_ratio_vs_exact_topk",
+                                                "exact_topk_ms", "full_attn_ms", "kernel_us", "whole_step", "per_step")}
             others[name]["roofline_frac"] = res["roofline"]["frac"]
+            others[name]["score_kernel"] = {k: res["roofline"][k] for k in ("kernel", "achieved", "frac", "bytes_per_launch", "avg_launch_us", "traffic")}
+            others[name]["sparse_attn_frac_at_union_bytes"] = res["sparse_attn"]["frac_of_hbm_peak_at_union_bytes"]
             others[name]["steps_per_s"] = round(others[name]["steps_per_s"], 2)
             others[name]["ms_per_step"] = round(others[name]["ms_per_step"], 4)
             if not args.no_table_mode:
@@ -685,6 +840,8 @@ def main():
                 others[name]["score_table_mode"] = {k: t[k] for k in ("steps_per_s", "ms_per_step", "cand_frac",
                                                                         "recall_vs_exact_topk", "kernel_us")}
         line["other_workloads"] = others
+        if not args.no_table_mode:
+            line["peaky_workload"] = measure_peaky(args.steps, args.warmup)
     if not args.no_cpu_baseline:
         line["cpu_baseline"] = cpu_baseline(case, args.cpu_seconds)
     print(json.dumps(line), flush=True)
