@@ -721,13 +721,13 @@ static int table_candidates_impl(lfps_ctx* ctx, const int32_t* seq_lens, int32_t
 }
 
 static int table_update_impl(lfps_ctx* ctx, const int32_t* idx, const float* idx_score, const int32_t* k,
-                             const int32_t* seq_lens, const int32_t* gate, hipStream_t st) {
+                             const int32_t* seq_lens, const int32_t* gate, bool distinct, hipStream_t st) {
   const Shape& s = ctx->shape;
   if (ctx->tab_updates >= s.Lcap - 1)
     return fail(ctx, LFPS_ECAP, "lfps_table_update: max_seq_len - 1 updates since the last import/init");
   LAUNCH(ctx, LFPS_KERNEL_TABLE_UPDATE, st,
          launch_table_update(s, ctx->tab_ver, ctx->tab_sla, ctx->tab_state, seq_lens, idx, idx_score, k,
-                             (double)ctx->cfg.table_decay, gate, ctx->flags, st));
+                             (double)ctx->cfg.table_decay, gate, ctx->flags, distinct, st));
   ctx->tab_updates += 1;
   return LFPS_OK;
 }
@@ -746,7 +746,7 @@ int lfps_table_update(lfps_ctx* ctx, const int32_t* idx, const float* idx_score,
   if (!idx || !idx_score || !k || !seq_lens) return fail(ctx, LFPS_EINVAL, "lfps_table_update: NULL argument");
   int rc = need_tables(ctx, "lfps_table_update", true);
   if (rc != LFPS_OK) return rc;
-  return table_update_impl(ctx, idx, idx_score, k, seq_lens, nullptr, (hipStream_t)stream);
+  return table_update_impl(ctx, idx, idx_score, k, seq_lens, nullptr, false, (hipStream_t)stream);   // a caller's list
 }
 
 static int table_step_impl(lfps_ctx* ctx, const float* q, const KvView& v, const int32_t* k, int32_t* topk_idx,
@@ -757,7 +757,7 @@ static int table_step_impl(lfps_ctx* ctx, const float* q, const KvView& v, const
   if (rc != LFPS_OK) return rc;
   rc = score_select_attend(ctx, q, v, k, topk_idx, sel, out, gate, st);
   if (rc != LFPS_OK) return rc;
-  return table_update_impl(ctx, topk_idx, sel, k, v.seq_lens, gate, st);
+  return table_update_impl(ctx, topk_idx, sel, k, v.seq_lens, gate, true, st);   // the select's rows are distinct
 }
 
 int lfps_table_step(lfps_ctx* ctx, const float* q, const lfps_kv* kv, const int32_t* k, int32_t* topk_idx,

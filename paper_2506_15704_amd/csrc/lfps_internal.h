@@ -165,7 +165,7 @@ hipError_t launch_table_candidates(const Shape& s, const uint32_t* f0, const uin
                                    hipStream_t st);
 hipError_t launch_table_update(const Shape& s, float* tab_ver, float* tab_sla, double* state, const int32_t* seq_lens,
                                const int32_t* idx, const float* sc, const int32_t* k, double gamma, const int32_t* gate,
-                               int32_t* flags, hipStream_t st);
+                               int32_t* flags, bool distinct, hipStream_t st);   // distinct: no position twice in a head's list
 hipError_t launch_table_import(const Shape& s, float* tab_ver, float* tab_sla, double* state, const int32_t* seq_lens,
                                const float* phi_ver, const float* phi_sla, hipStream_t st);
 hipError_t launch_table_export(const Shape& s, const float* tab_ver, const float* tab_sla, const double* state,

@@ -192,6 +192,10 @@ __global__ __launch_bounds__(kTabThreads) void k_table_flags(Shape s, const floa
 // ----------------------------------------------------------------------------- update (Eq. 10)
 // grid B*Hq.  The step saw n rows and selected idx[bh, 0:k_b] with scaled scores sc; entries outside
 // [n_sink, n) are padding.  w = softmax over the valid entries; delta = w - 1/(2 * valid).
+// kDistinct: the positions of a head's list are known to be distinct (the library's own Top-k), so an entry's old
+// value can be read beside the addition; otherwise (a caller's list, where a position may appear twice) every
+// addition returns the value it found, which keeps the moments exact for a repeated position too.
+template <bool kDistinct>
 __global__ __launch_bounds__(kTabThreads) void k_table_update(Shape s, float* __restrict__ tab_ver,
                                                               float* __restrict__ tab_sla, double* __restrict__ state,
                                                               const int32_t* __restrict__ seq_lens,
@@ -254,8 +258,21 @@ __global__ __launch_bounds__(kTabThreads) void k_table_update(Shape s, float* __
     const int p = ih[e];
     if (p >= s.n_sink && p < n) {
       const double delta = (double)expf(sh[e] - m) / zsum - half;
-      const double xv = gamma * g * (double)ver[p];          // decayed old value
-      const double xs = p - 1 >= s.n_sink ? gamma * g * (double)sla[p - 1] : 0.0;   // decayed value moving in from p-1
+      const float inc = (float)(delta / g1);
+      // (hardware fp32 adds in L2.)  Position p in the next frame (cnt + 1) is the slot of p - 1 in this one (for
+      // p = 0 the never-written slot just below the frame).
+      float old_v, old_s = 0.f;
+      if constexpr (kDistinct) {
+        old_v = ver[p];
+        if (p - 1 >= s.n_sink) old_s = sla[p - 1];
+        unsafeAtomicAdd(&ver[p], inc);
+        unsafeAtomicAdd(&sla[p - 1], inc);
+      } else {
+        old_v = unsafeAtomicAdd(&ver[p], inc);
+        old_s = unsafeAtomicAdd(&sla[p - 1], inc);
+      }
+      const double xv = gamma * g * (double)old_v;           // decayed old value
+      const double xs = p - 1 >= s.n_sink ? gamma * g * (double)old_s : 0.0;   // decayed value moving in from p-1
       const double yv = xv + delta, ys = xs + delta;
       dv[0] += yv - xv;
       dv[1] += yv * yv - xv * xv;
@@ -265,12 +282,6 @@ __global__ __launch_bounds__(kTabThreads) void k_table_update(Shape s, float* __
       ds[1] += ys * ys - xs * xs;
       ds[2] += ys * ys * ys - xs * xs * xs;
       ds[3] += ys * ys * ys * ys - xs * xs * xs * xs;
-      const float inc = (float)(delta / g1);
-      // (hardware fp32 add in L2; a selected position may appear twice in a caller's list)
-      unsafeAtomicAdd(&ver[p], inc);
-      // position p in the next frame (cnt + 1) is the slot of p - 1 in this one (for p = 0 the
-      // never-written slot just below the frame)
-      unsafeAtomicAdd(&sla[p - 1], inc);
     }
   }
   double tv[4], ts[4];
@@ -672,9 +683,13 @@ hipError_t launch_table_flags(const Shape& s, const float* tab_ver, const float*
 
 hipError_t launch_table_update(const Shape& s, float* tab_ver, float* tab_sla, double* state, const int32_t* seq_lens,
                                const int32_t* idx, const float* sc, const int32_t* k, double gamma, const int32_t* gate,
-                               int32_t* flags, hipStream_t st) {
-  hipLaunchKernelGGL(k_table_update, dim3(s.B * s.Hq), dim3(kTabThreads), 0, st, s, tab_ver, tab_sla, state, seq_lens,
-                     idx, sc, k, gamma, gate, flags);
+                               int32_t* flags, bool distinct, hipStream_t st) {
+  if (distinct)
+    hipLaunchKernelGGL(k_table_update<true>, dim3(s.B * s.Hq), dim3(kTabThreads), 0, st, s, tab_ver, tab_sla, state,
+                       seq_lens, idx, sc, k, gamma, gate, flags);
+  else
+    hipLaunchKernelGGL(k_table_update<false>, dim3(s.B * s.Hq), dim3(kTabThreads), 0, st, s, tab_ver, tab_sla, state,
+                       seq_lens, idx, sc, k, gamma, gate, flags);
   return hipGetLastError();
 }
 

@@ -760,3 +760,130 @@ def test_replayed_updates_stop_at_the_table_capacity():
         ctx.lfps_table_update(idx, sc, k, nd)
     assert ctx.lfps_poll_status() == 0
     ctx.close()
+
+
+def _assert_candidates_band(got, want, tables64, n, a, r, n_sink, band, what):
+    """As _assert_candidates with a wider band: for chains in which the device's fp32 tables and the oracle's fp64
+    tables have drifted apart by the accumulated rounding of many updates."""
+    global BAND
+    keep = BAND
+    BAND = band
+    try:
+        return _assert_candidates(got, want, tables64, n, a, r, n_sink, what)
+    finally:
+        BAND = keep
+
+
+@pytest.mark.parametrize("gamma", [0.9, 0.6])
+def test_scan_after_many_updates_without_import(gamma):
+    """The scan reads the tables only where the per-block upper bounds allow an initial candidate; the bounds are
+    maintained by the update alone (raised, never lowered) once the tables have been imported.  Forty updates with
+    given lists (clustered around a few positions, the context growing by a row per step, positions repeated now
+    and then) on the device and in the oracle from the same start: the candidates of every step must be the
+    oracle's, modulo entries within rounding of a threshold or mean."""
+    from paper_2506_15704_amd.binding import Lfps
+    rng = np.random.default_rng(77)
+    B, Hq, Hkv, kmax, r, a = 2, 8, 2, 40, 2, 0.2
+    n0, steps = np.array([2900, 1500], dtype=np.int32), 40
+    Lcap = int(n0.max()) + steps + 2
+    n_sink = 2
+    ctx = Lfps(batch=B, n_q_heads=Hq, n_kv_heads=Hkv, max_seq_len=Lcap, max_k=kmax, radius=r, n_recent=1, n_sink=n_sink,
+               table_mode=True, table_decay=gamma, table_a=a, cand_cap=Lcap)
+    n = n0.copy()
+    k = np.array([kmax, 24], dtype=np.int32)
+    ver, sla = _make_tables(rng, B, Hq, Lcap, n, n_sink)
+    ctx.lfps_tables_import(dev(ver), dev(sla), dev(n))
+    v64, s64 = ver.astype(np.float64), sla.astype(np.float64)
+    cand = torch.zeros((B, Hkv, ctx.cand_cap), dtype=torch.int32, device=DEV)
+    cnt = torch.zeros((B, Hkv), dtype=torch.int32, device=DEV)
+    pools = [[np.sort(rng.choice(int(n0[b]) - 64, size=6, replace=False)) + 16 for _ in range(Hq)] for b in range(B)]
+    G = Hq // Hkv
+    total_diff = 0
+    for step in range(steps):
+        idx = np.full((B, Hq, kmax), -1, dtype=np.int32)
+        sc = rng.standard_normal((B, Hq, kmax)).astype(np.float32)
+        for b in range(B):
+            for h in range(Hq):
+                # most picks fall within +-12 rows of the head's six centres, a few anywhere, the newest row now and then
+                near = (rng.choice(pools[b][h], size=k[b] - 6) + rng.integers(-12, 13, size=k[b] - 6)) % int(n[b])
+                row = np.unique(np.r_[near, rng.choice(int(n[b]), size=5), [int(n[b]) - 1]])[: k[b]]
+                idx[b, h, : len(row)] = row
+                if step % 7 == 3 and len(row) < k[b]:
+                    idx[b, h, len(row)] = row[0]                     # a position given twice
+                sc[b, h, : len(row)] += 3.0 * rng.random(len(row))
+        ctx.lfps_table_candidates(dev(n), cand, cnt)
+        c_, cn_ = cand.cpu().numpy(), cnt.cpu().numpy()
+        for b in range(B):
+            for g in range(Hkv):
+                t64 = [(v64[b, G * g + h], s64[b, G * g + h]) for h in range(G)]
+                want = tor.group_candidates(t64, int(n[b]), a, r, 1, n_sink)
+                total_diff += _assert_candidates_band(c_[b, g, : cn_[b, g]], want, t64, int(n[b]), a, r, n_sink, 2e-4,
+                                                      f"step {step} b{b} g{g}")
+        ctx.lfps_table_update(dev(idx), dev(sc), dev(k), dev(n))
+        for b in range(B):                                          # the oracle's Eq. 10 on the same lists
+            for h in range(Hq):
+                nv, ns = tor.update_tables(v64[b, h], s64[b, h], int(n[b]), idx[b, h, : k[b]], sc[b, h, : k[b]].astype(np.float64),
+                                           gamma, n_sink)
+                v64[b, h, : n[b] + 1], s64[b, h, : n[b] + 1] = nv, ns
+        n = n + 1
+    assert total_diff <= 6, total_diff
+    assert ctx.lfps_poll_status() == 0
+    ctx.close()
+
+
+def test_table_steps_chained_on_the_device_without_import():
+    """lfps_table_step keeps its own tables from step to step (no import in between): the oracle follows from the
+    same Eq. 4 start, taking at every step the device's index sets once they have been checked to be legal Top-k
+    sets of the oracle's candidates, so both chains see the same selections.  The device's candidates (a scan that
+    trusts the upper bounds its own updates maintain) must be the oracle's at every step."""
+    spec = gen.tiny_spec("tables_chain", B=2, L=2600, k=96, r=2, T=14, n_hot=12, recency=32)
+    dc = DeviceCase(spec)
+    s, case = dc.spec, dc.case
+    gamma, a, n_sink, n_recent = 0.9, 0.2, 4, 1
+    ctx = dc.make_ctx(table_mode=True, table_decay=gamma, table_a=a, n_sink=n_sink, n_recent=n_recent)
+    ctx.lfps_tables_init(dc.q(0), ctx.kv_view(dc.K, dc.V, dc.seq_lens(0)))
+    groups = [(0, 1), (1, 6)]
+    t64 = {}
+    for (b, g) in groups:                    # the oracle's own Eq. 4 start
+        K, _ = dc.group(b, g)
+        n0 = int(case.seq_lens0[b])
+        t64[(b, g)] = []
+        for h in range(s.G):
+            sc0 = orc.scores(case.q[0, b, s.G * g + h], K[:n0])
+            w = np.zeros(n0)
+            w[n_sink:] = _softmax64(sc0[n_sink:])
+            ver0, sla0 = tor.init_tables(w[None, :], gamma, n_sink)
+            t64[(b, g)].append((np.r_[ver0, np.zeros(case.Lcap - n0)], np.r_[sla0, np.zeros(case.Lcap - n0)]))
+    idx = torch.zeros((s.B, s.Hq, case.kmax), dtype=torch.int32, device=DEV)
+    isc = torch.zeros((s.B, s.Hq, case.kmax), dtype=torch.float32, device=DEV)
+    out = torch.zeros((s.B, s.Hq, s.D), dtype=torch.float32, device=DEV)
+    cand = torch.zeros((s.B, s.Hkv, ctx.cand_cap), dtype=torch.int32, device=DEV)
+    cnt = torch.zeros((s.B, s.Hkv), dtype=torch.int32, device=DEV)
+    total_diff = 0
+    for t in range(1, s.T + 1):
+        n = case.seq_lens(t)
+        ctx.lfps_table_candidates(dev(n), cand, cnt)
+        ctx.lfps_table_step(dc.q(t), ctx.kv_view(dc.K, dc.V, dc.seq_lens(t)), dc.k, idx, out, isc)
+        c_, cn_, i_ = cand.cpu().numpy(), cnt.cpu().numpy(), idx.cpu().numpy()
+        for (b, g) in groups:
+            K, V = dc.group(b, g)
+            nb, kb = int(n[b]), int(case.k[b])
+            tabs = t64[(b, g)]
+            want = tor.group_candidates(tabs, nb, a, s.r, n_recent, n_sink)
+            got_c = c_[b, g, : cn_[b, g]]
+            total_diff += _assert_candidates_band(got_c, want, tabs, nb, a, s.r, n_sink, 1e-4, f"t={t} b={b} g={g}")
+            new_tabs = []
+            for h in range(s.G):
+                bh = s.G * g + h
+                ksel = min(kb, len(got_c))
+                got = valid_row(i_[b, bh, :kb])
+                I_h, _ = orc.score_topk(case.q[t, b, bh], K, got_c, ksel)     # the oracle's select on the set the device used
+                assert_topk_equal_mod_ties(got, I_h, lambda p: orc.scores(case.q[t, b, bh], K, p), ksel, f"t={t} b={b} h={bh}")
+                # Eq. 10 in the oracle on the (legal) set the device selected, with the oracle's own scores
+                new_tabs.append(tor.update_tables(tabs[h][0], tabs[h][1], nb, got, orc.scores(case.q[t, b, bh], K, got),
+                                                  gamma, n_sink))
+            pad = lambda x: np.r_[x, np.zeros(max(0, case.Lcap - len(x)))][: case.Lcap]   # (the last step's new position lies past the capacity)
+            t64[(b, g)] = [(pad(v_), pad(s_)) for (v_, s_) in new_tabs]
+    assert total_diff <= 4, total_diff
+    assert ctx.lfps_poll_status() == 0
+    ctx.close()
