@@ -58,6 +58,9 @@ def parse_args():
                     help="run only the score-table mode of the main workload (for profiling) and print its record")
     ap.add_argument("--calib-copy", action="store_true",
                     help="run only the plain copy kernel (1 GiB, 10 launches): the known-traffic reference for rocprofv3 --pmc")
+    ap.add_argument("--host-kv-only", action="store_true",
+                    help="run only the host-resident-cache leg of --workload and print its record")
+    ap.add_argument("--no-host-kv", action="store_true", help="skip the host-resident-cache leg")
     ap.add_argument("--peaky-only", action="store_true",
                     help="run only the concentrated-attention variant of C4 (memoryless and score-table steps) and print its record")
     ap.add_argument("--sweep", action="store_true",
@@ -483,6 +486,46 @@ def measure_paged(name, steps, warmup, block_size=16, layout="block_head_row"):
     return res
 
 
+def measure_host_kv(name, steps, warmup):
+    """The paper's placement (its Sec. 4 overview): the KV cache stays in pinned host memory and the kernels fetch
+    only the rows they touch over the host link.  Reported: the step time, the bytes a step moves over the link
+    (candidate K rows once per KV group, selected V rows per head) against the stream of all keys that a
+    transfer-then-index design needs (Sec. 1), and the link rate reached; final Top-k and outputs compared bit
+    for bit with the device-resident run."""
+    import torch
+    r0 = Runner(name)
+    spec = r0.spec
+    if steps <= 0:
+        steps = max(1, min(spec.T - warmup, 10))
+    steps = min(steps, 10)                       # a step takes milliseconds here: keep the leg short
+    r0.run_timed(steps, warmup)
+    ref_idx, ref_out = r0.prev.clone(), r0.out.clone()
+    Kh = torch.empty(r0.K.shape, dtype=r0.K.dtype, pin_memory=True)
+    Vh = torch.empty(r0.V.shape, dtype=r0.V.dtype, pin_memory=True)
+    Kh.copy_(r0.K)
+    Vh.copy_(r0.V)
+    torch.cuda.synchronize()
+    r0.K, r0.V = Kh, Vh                          # the same runner over the host-resident copy
+    r0.views = [r0.ctx.kv_view(Kh, Vh, r0.seq[t]) for t in range(spec.T + 1)]
+    sec = r0.run_timed(steps, warmup)
+    same = bool(torch.equal(r0.prev, ref_idx)) and bool(torch.equal(r0.out, ref_out))
+    tm, cnts = r0.run_kernel_timing(steps, warmup)
+    e = 2 if spec.kv_dtype != "f32" else 4
+    k_rows = float(cnts.sum(axis=(1, 2)).mean())
+    v_rows = float(r0.case.k.sum()) * spec.Hq
+    link_bytes = (k_rows + v_rows) * spec.D * e
+    all_k = float(r0.case.seq_lens(min(spec.T, 2)).sum()) * spec.Hkv * spec.D * e
+    res = {"workload": spec.name, "kv_in": "pinned host memory (hipHostMalloc), rows fetched by the kernels over the host link",
+           "ms_per_step": round(sec * 1e3, 3), "steps": steps, "matches_device_resident_bitwise": same,
+           "link_bytes_per_step": round(link_bytes), "k_rows_bytes": round(k_rows * spec.D * e),
+           "v_rows_bytes_per_head_fetch": round(v_rows * spec.D * e),
+           "all_keys_bytes": round(all_k), "fraction_of_all_keys_stream": round(link_bytes / all_k, 4),
+           "link_GB_per_s": round(link_bytes / sec / 1e9, 1),
+           "kernel_us": {k: round(v[0] / steps * 1e3, 1) for k, v in tm.items() if v[1]}}
+    r0.close()
+    return res
+
+
 def measure_fp8_keys(name, steps, warmup, with_v=False):
     """The main workload with K (and, with_v, V) stored as OCP FP8 E4M3 (the same draws rounded to 3 mantissa
     bits): half the bytes per scored (and per gathered) row.  A different input, so nothing is compared with
@@ -768,6 +811,9 @@ def main():
                              args.steps if args.steps > 0 else 6, args.warmup)
         print(json.dumps({"sweep": "C4 recipe (bf16, r=4, k=L/64)", "rows": rows}), flush=True)
         return
+    if args.host_kv_only:
+        print(json.dumps({"host_resident_kv": measure_host_kv(args.workload, args.steps, args.warmup)}), flush=True)
+        return
     if args.peaky_only:
         print(json.dumps({"peaky_workload": measure_peaky(args.steps, args.warmup)}), flush=True)
         return
@@ -819,6 +865,8 @@ def main():
         line["fp8_keys"] = measure_fp8_keys(args.workload, args.steps, args.warmup)
         line["fp8_keys_and_values"] = measure_fp8_keys(args.workload, args.steps, args.warmup, with_v=True)
         line["fp16_cache"] = measure_fp16_cache(args.workload, args.steps, args.warmup)
+    if not args.no_host_kv:
+        line["host_resident_kv"] = measure_host_kv(args.workload, args.steps, args.warmup)
     if not args.no_paged:
         line["paged_kv"] = measure_paged(args.workload, args.steps, args.warmup, args.paged_block, args.paged_layout)
     if args.all_workloads:

@@ -96,6 +96,11 @@ typedef struct {
  * read by the kernels and clamped into [0, n_blocks); only the entries of rows below n_b are read,
  * and the first entry of every request (padding slots read row 0, also when n_b = 0).
  * The method itself (positions, candidates, Top-k indices) always speaks in logical rows i. */
+/* Host-resident cache (the paper's placement, Sec. 4 overview: the KV cache in host memory): k and v may also
+ * point to pinned host memory that the device can address (hipHostMalloc; pass what lfps_host_device_pointer
+ * returns for it).  Every kernel then fetches exactly the rows it touches over the host link: the candidate rows
+ * of K once per KV group, the selected rows of V per head; nothing else changes, results are bit-identical to a
+ * device-resident cache.  seq_lens and block_table stay in device memory. */
 typedef struct {
   const void* k;
   const void* v;
@@ -106,6 +111,10 @@ typedef struct {
   int32_t block_table_stride;
   int32_t n_blocks;
 } lfps_kv;
+
+/* The address at which the current device sees a pinned host allocation (hipHostMalloc'ed memory, e.g. a pinned
+ * torch tensor): host in, *dev out.  LFPS_EHIP if the memory is not mapped for the device. */
+int lfps_host_device_pointer(const void* host, void** dev);
 
 /* Create / destroy.  lfps_create validates the config, selects cfg->device, allocates the
  * workspace (lfps_workspace_bytes) and synchronises the device once.  *out is NULL on error. */

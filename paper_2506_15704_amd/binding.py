@@ -60,6 +60,7 @@ def _load() -> ctypes.CDLL:
         "lfps_destroy": (ctypes.c_int, [P]),
         "lfps_last_error": (ctypes.c_char_p, [P]),
         "lfps_workspace_bytes": (ctypes.c_int, [ctypes.POINTER(lfps_config), ctypes.POINTER(ctypes.c_int64)]),
+        "lfps_host_device_pointer": (ctypes.c_int, [VP, ctypes.POINTER(VP)]),
         "lfps_cand_cap": (I32, [P]),
         "lfps_candidates": (ctypes.c_int, [P, VP, VP, VP, VP, VP, VP]),
         "lfps_score_topk": (ctypes.c_int, [P, VP, ctypes.POINTER(lfps_kv), VP, VP, VP, VP, VP, VP, VP]),
@@ -108,6 +109,20 @@ def workspace_bytes(**cfg) -> int:
     if rc != LFPS_OK:
         raise LfpsError(rc, _lib.lfps_last_error(None).decode())
     return out.value
+
+
+def _cache_ptr(t: torch.Tensor) -> int:
+    """Address of a cache tensor for the kernels: a GPU tensor's own, or for a pinned host tensor (a host-resident
+    cache) the address at which the device sees it."""
+    if t.is_cuda:
+        return t.data_ptr()
+    if not t.is_pinned():
+        raise TypeError("a cache tensor must live on the GPU or in pinned host memory")
+    dev = ctypes.c_void_p(None)
+    rc = _lib.lfps_host_device_pointer(t.data_ptr(), ctypes.byref(dev))
+    if rc != LFPS_OK:
+        raise LfpsError(rc, _lib.lfps_last_error(None).decode())
+    return dev.value
 
 
 def _ptr(t: Optional[torch.Tensor], dtype, shape, name: str, device) -> Optional[int]:
@@ -182,13 +197,14 @@ class Lfps:
         return torch.cuda.current_stream(self.device).cuda_stream
 
     def kv_view(self, K: torch.Tensor, V: Optional[torch.Tensor], seq_lens: torch.Tensor) -> lfps_kv:
-        """View of a [B, Hkv, Lcap', D] cache (any strides with a contiguous last dim)."""
+        """View of a [B, Hkv, Lcap', D] cache (any strides with a contiguous last dim); K and V on the GPU, or in
+        pinned host memory for a host-resident cache (rows are then fetched over the host link)."""
         for name, t in (("K", K), ("V", V)):
             if t is None:
                 continue
             want = self.k_torch_dtype if name == "K" else self.v_torch_dtype
-            if not t.is_cuda or t.dtype != want or t.dim() != 4:
-                raise TypeError(f"{name}: expected a 4-d {want} tensor on the GPU")
+            if not (t.is_cuda or t.is_pinned()) or t.dtype != want or t.dim() != 4:
+                raise TypeError(f"{name}: expected a 4-d {want} tensor on the GPU (or in pinned host memory)")
             if t.shape[0] != self.B or t.shape[1] != self.Hkv or t.shape[3] != self.D or t.stride(3) != 1:
                 raise ValueError(f"{name}: expected [B={self.B}, Hkv={self.Hkv}, rows, D={self.D}] with unit channel stride")
             if t.shape[2] < self.Lcap:
@@ -196,7 +212,7 @@ class Lfps:
         if V is not None and V.stride() != K.stride():
             raise ValueError("K and V must share strides")
         sl = _ptr(seq_lens, torch.int32, (self.B,), "seq_lens", self.device)
-        view = lfps_kv(K.data_ptr(), V.data_ptr() if V is not None else None,
+        view = lfps_kv(_cache_ptr(K), _cache_ptr(V) if V is not None else None,
                        K.stride(0), K.stride(1), K.stride(2), sl, None, 0, 0, 0)
         view._keep = (K, V, seq_lens)   # the struct holds raw pointers: keep their tensors alive with it
         return view

@@ -259,6 +259,18 @@ int lfps_calib_copy(void* dst, const void* src, int64_t bytes, void* stream) {
   return hipGetLastError() == hipSuccess ? LFPS_OK : LFPS_EHIP;
 }
 
+int lfps_host_device_pointer(const void* host, void** dev) {
+  if (!host || !dev) return LFPS_EINVAL;
+  *dev = nullptr;
+  hipError_t e = hipHostGetDevicePointer(dev, const_cast<void*>(host), 0);
+  if (e != hipSuccess || !*dev) {
+    snprintf(g_create_err, sizeof g_create_err, "hipHostGetDevicePointer: %s", hipGetErrorString(e));
+    (void)hipGetLastError();
+    return LFPS_EHIP;
+  }
+  return LFPS_OK;
+}
+
 int lfps_workspace_bytes(const lfps_config* cfg, int64_t* out) {
   Sizes z;
   int rc = check_config(cfg, &z, g_create_err, sizeof g_create_err);

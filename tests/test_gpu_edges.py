@@ -228,3 +228,64 @@ def test_exact_topk_filtered_form_equals_plain_form(variant):
             assert np.all(idx_h[b, h, kb:] == -1)
     fast.close()
     plain.close()
+
+
+@pytest.mark.parametrize("fmt", ["bf16", "fp8kv", "f32"])
+def test_host_resident_cache_gives_identical_results(fmt):
+    """The paper's placement: K and V stay in (pinned) host memory and the kernels fetch the rows they touch over
+    the host link.  Same entry points, same kernels; every result must equal the device-resident run bit for bit
+    (exact Top-k seed, three chained steps through the filtered pass, full attention, a score-table step)."""
+    kw = dict(B=2, L=2200, k=80, r=2, T=3)
+    if fmt == "fp8kv":
+        kw.update(k_dtype="fp8", v_dtype="fp8")
+    if fmt == "f32":
+        kw.update(kv_dtype="f32")
+    spec = gen.tiny_spec("hostkv_" + fmt, **kw)
+    dc = DeviceCase(spec)
+    case = dc.case
+
+    def pinned(t):
+        raw = t.view(torch.uint8) if t.dtype == torch.float8_e4m3fn else t
+        h = torch.empty(raw.shape, dtype=raw.dtype, pin_memory=True)
+        h.copy_(raw)
+        return h.view(t.dtype) if t.dtype == torch.float8_e4m3fn else h
+
+    Kh, Vh = pinned(dc.K), pinned(dc.V)
+    assert Kh.is_pinned() and not Kh.is_cuda
+    shp = (spec.B, spec.Hq, case.kmax)
+    runs = []
+    for K, V in ((dc.K, dc.V), (Kh, Vh)):
+        ctx = dc.make_ctx()
+        tab = dc.make_ctx(table_mode=True, table_decay=0.9, table_a=0.2, n_sink=2)
+        got = []
+        prev = torch.zeros(shp, dtype=torch.int32, device=DEV)
+        ctx.lfps_exact_topk(dc.q(0), ctx.kv_view(K, V, dc.seq_lens(0)), dc.k, prev)
+        got.append(prev.clone())
+        for t in (1, 2, 3):
+            idx = torch.zeros(shp, dtype=torch.int32, device=DEV)
+            sc = torch.zeros(shp, dtype=torch.float32, device=DEV)
+            out = torch.zeros((spec.B, spec.Hq, spec.D), dtype=torch.float32, device=DEV)
+            ctx.lfps_step(dc.q(t), ctx.kv_view(K, V, dc.seq_lens(t)), prev, dc.k, idx, out, sc)
+            got += [idx, sc, out]
+            prev = idx
+        full = torch.zeros((spec.B, spec.Hq, spec.D), dtype=torch.float32, device=DEV)
+        ctx.lfps_full_attn_decode(dc.q(3), ctx.kv_view(K, V, dc.seq_lens(3)), full)
+        got.append(full)
+        tab.lfps_tables_init(dc.q(0), tab.kv_view(K, V, dc.seq_lens(0)))
+        t_idx = torch.zeros(shp, dtype=torch.int32, device=DEV)
+        t_out = torch.zeros((spec.B, spec.Hq, spec.D), dtype=torch.float32, device=DEV)
+        tab.lfps_table_step(dc.q(1), tab.kv_view(K, V, dc.seq_lens(1)), dc.k, t_idx, t_out)
+        got += [t_idx, t_out]
+        torch.cuda.synchronize()
+        assert ctx.lfps_poll_status() == 0 and tab.lfps_poll_status() == 0
+        runs.append(got)
+        ctx.close()
+        tab.close()
+    for i, (a, b_) in enumerate(zip(*runs)):
+        assert torch.equal(a, b_), f"result {i} differs between the device-resident and the host-resident cache"
+    # and one oracle check of the host-resident run itself
+    K0, V0 = dc.group(1, 3)
+    idx3, out3 = runs[1][7].cpu().numpy(), runs[1][9].cpu().numpy()
+    h = 4 * 3 + 1
+    ref = orc.sparse_attn(case.q[3, 1, h], K0, V0, idx3[1, h, : int(case.k[1])])
+    assert_out_close(out3[1, h], ref, "host-resident step 3")
