@@ -2,7 +2,8 @@
 // fast form.  Writing a score for every row and selecting from that array costs a second and further passes over
 // 4 bytes per row and head; instead the baseline takes the machinery of the chained steps:
 //   1. a strided sample of each group's rows is scored (the gather kernel) and, per head, the sample score of a
-//      rank chosen so that, with near certainty, at least k rows of the whole context reach it becomes a threshold;
+//      rank chosen so that, with near certainty, between k rows and the select's list capacity reach it becomes a
+//      threshold;
 //   2. the filtered scoring kernel streams all rows once and keeps only those that reach the threshold;
 //   3. the select picks the exact k best from the survivors; a head whose survivors are fewer than k (or too many
 //      for the on-chip list) is rescored the plain way, so the result is always the exact Top-k.
@@ -12,7 +13,7 @@ namespace lfps {
 
 // grid B*Hkv, 256 threads.
 __global__ __launch_bounds__(256) void k_dense_prep(Shape s, const int32_t* __restrict__ seq_lens,
-                                                    const int32_t* __restrict__ kk, int ns_max,
+                                                    const int32_t* __restrict__ kk, int ns_max, int list_cap,
                                                     int32_t* __restrict__ x_cnt, int64_t* __restrict__ x_start,
                                                     int32_t* __restrict__ x_nsg, int32_t* __restrict__ x_ns,
                                                     int32_t* __restrict__ x_rank, int32_t* __restrict__ sample,
@@ -50,18 +51,38 @@ __global__ __launch_bounds__(256) void k_dense_prep(Shape s, const int32_t* __re
   int kb = kk[b];
   kb = kb < 0 ? 0 : (kb > s.kmax ? s.kmax : kb);
   kb = kb < n ? kb : n;
-  // the sample: ns rows i * n / ns (all rows when n is small)
-  int ns = ns_max < s.cand_cap ? ns_max : s.cand_cap;
-  ns = ns < n ? ns : n;
-  // the sample rank r: with p = k / n the number of sample rows among the true k best is Binomial(ns, p); four
-  // standard deviations above its mean (plus a few) leaves the r-th best sample score below the true k-th score
-  // except with probability ~1e-5 (and then the head is simply rescored).  With the whole context sampled, r = k.
-  int r = kb;
-  if (ns < n) {
-    const float p = (float)kb / (float)n;
-    const float mean = (float)ns * p, sd = sqrtf((float)ns * p * (1.f - p));
-    r = (int)ceilf(mean + 4.f * sd) + 4;
+  // The sample and the rank r of the sample score that becomes the threshold.  With p = k / n the rows of the whole
+  // context above the r-th best of ns sampled scores number about n r / ns, with a relative spread of 1 / sqrt(r).
+  // That count must land between k (else too few survive) and the select's list capacity: it is aimed at t k with
+  // t = min(2, (1 + cap / k) / 2), the middle of the two limits, and r is made large enough for both to lie
+  // z = 4.5 standard deviations away (a miss costs a rescoring of that head, never a wrong result); the sample
+  // size follows as ns = (r / t) n / k.  A context no larger than that is sampled whole, with r = k.
+  int ns = n, r = kb;
+  if (kb > 0 && n > kb) {
+    const float c = (float)list_cap / (float)kb;
+    const float t = fminf(2.f, 0.5f * (1.f + c));
+    if (t > 1.05f) {
+      const float sr = 4.5f * t / (t - 1.f);
+      r = (int)ceilf(sr * sr);
+      const float want = ((float)r / t) * ((float)n / (float)kb);
+      int cap_ns = ns_max < s.cand_cap ? ns_max : s.cand_cap;
+      cap_ns = cap_ns < n ? cap_ns : n;
+      if (want < (float)cap_ns) {
+        ns = (int)ceilf(want);
+      } else {                                   // no room for the wanted sample: what fits, with the rank that aims at t k
+        ns = cap_ns;
+        r = ns < n ? (int)(t * (float)ns * (float)kb / (float)n) : kb;
+      }
+      if (ns >= n) {
+        ns = n;
+        r = kb;
+      }
+    } else {                                     // the list barely holds the budget: no room to aim, sample everything
+      ns = n < s.cand_cap ? n : s.cand_cap;
+      r = ns == n ? kb : 1;
+    }
   }
+  r = r < 1 ? 1 : r;
   r = r > s.kmax ? s.kmax : r;
   r = r > ns ? ns : r;
   if (tid == 0) {
@@ -80,10 +101,10 @@ __global__ __launch_bounds__(256) void k_dense_prep(Shape s, const int32_t* __re
   for (int i = tid; i < ns; i += 256) out[i] = (int)(((long long)i * n) / ns);
 }
 
-hipError_t launch_dense_prep(const Shape& s, const int32_t* seq_lens, const int32_t* k, int ns_max, int32_t* x_cnt,
+hipError_t launch_dense_prep(const Shape& s, const int32_t* seq_lens, const int32_t* k, int ns_max, int list_cap, int32_t* x_cnt,
                              int64_t* x_start, int32_t* x_nsg, int32_t* x_ns, int32_t* x_rank, int32_t* sample,
                              int32_t* redo_g, int32_t* redo_h, hipStream_t st) {
-  hipLaunchKernelGGL(k_dense_prep, dim3(s.B * s.Hkv), dim3(256), 0, st, s, seq_lens, k, ns_max, x_cnt, x_start, x_nsg,
+  hipLaunchKernelGGL(k_dense_prep, dim3(s.B * s.Hkv), dim3(256), 0, st, s, seq_lens, k, ns_max, list_cap, x_cnt, x_start, x_nsg,
                      x_ns, x_rank, sample, redo_g, redo_h);
   return hipGetLastError();
 }

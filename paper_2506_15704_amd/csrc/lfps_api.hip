@@ -68,7 +68,7 @@ static const char* const kKernelNames[LFPS_N_KERNELS] = {
 // Margin below the previous step's k-th best score at which the filtered pass keeps a row.
 static const float kFilterMargin = 0.125f;
 // Exact Top-k baseline: rows sampled per KV group for the threshold, and the size from which the filtered form is used.
-static const int kExactSampleRows = 4096;
+static const int kExactSampleRows = 32768;   // at most; the set-up kernel sizes the sample for the budget and the list
 static const int64_t kExactFastMinRows = 1 << 20;
 
 namespace {
@@ -623,7 +623,7 @@ int lfps_exact_topk(lfps_ctx* ctx, const float* q, const lfps_kv* kv, const int3
     Shape sd = s;
     sd.cand_cap = s.Lcap;                 // the "candidates" of the dense pass are all rows of a group
     int64_t* x_total = ctx->x_start + (int64_t)s.B * s.Hkv;
-    hipError_t e = launch_dense_prep(s, v.seq_lens, k, kExactSampleRows, ctx->x_cnt, ctx->x_start, ctx->x_nsg, ctx->x_ns,
+    hipError_t e = launch_dense_prep(s, v.seq_lens, k, kExactSampleRows, filter_list_cap(s), ctx->x_cnt, ctx->x_start, ctx->x_nsg, ctx->x_ns,
                                      ctx->x_rank, ctx->cand, ctx->redo_g, ctx->redo_h, st);
     if (e != hipSuccess) return fail(ctx, LFPS_EHIP, "lfps_exact_topk (set-up)", e);
     LAUNCH(ctx, LFPS_KERNEL_GATHER_SCORE, st,

@@ -117,9 +117,11 @@ hipError_t launch_filter_select_attend(const Shape& s, int dtype, const float* s
 
 // Exact Top-k baseline, set-up of its filtered dense pass (exact_topk.hip): every group's rows 0..n_b-1 laid on the
 // line (x_cnt, x_start, x_start[B*Hkv] = the line's length), a strided sample of at most ns_max rows per group
+// (sized for the select's list capacity list_cap)
 // (sample [B, Hkv, cand_cap], x_nsg [B*Hkv] / x_ns [B] its length) and the rank x_rank [B] whose sample score is
 // taken as the threshold; the redo marks are cleared.
-hipError_t launch_dense_prep(const Shape& s, const int32_t* seq_lens, const int32_t* k, int ns_max, int32_t* x_cnt,
+hipError_t launch_dense_prep(const Shape& s, const int32_t* seq_lens, const int32_t* k, int ns_max, int list_cap,
+                             int32_t* x_cnt,
                              int64_t* x_start, int32_t* x_nsg, int32_t* x_ns, int32_t* x_rank, int32_t* sample,
                              int32_t* redo_g, int32_t* redo_h, hipStream_t st);
 // From the full score rows [B, Hq, score_stride] over cand: every head, or (only_if [B,Hq]) the marked ones.
