@@ -369,7 +369,7 @@ def measure(name, steps, warmup, with_baselines=True, use_graph=True, override=N
                      "traffic": measured_traffic(spec.name, kname),
                      "bytes_per_launch": round(bytes_per_launch), "avg_launch_us": round(gs_avg_s * 1e6, 2),
                      "launches": gs_n, "timed_by": "HIP events around each launch, second pass over the same steps",
-                     "note": "redo launches of gather_score (heads the filter left short) are in kernel_us"},
+                     "note": "heads the filter leaves short are rescored inside filter_select_attend (kernel_us)"},
         "kernel_us": {k: round(v[0] / steps * 1e3, 2) for k, v in tm.items() if v[1]},   # per step
         "step_us": step_us,
         "cand_frac": round(float(cnts.mean() / (spec.L or r.case.seq_lens0.mean())), 4),

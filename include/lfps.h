@@ -192,8 +192,10 @@ int lfps_sparse_attn_noalloc(const lfps_config* cfg, const float* q, const lfps_
  * With a bf16 or fp16 cache the scoring pass keeps, per head, only rows whose score reaches the k-th best
  * score of the PREVIOUS lfps_step call on this context minus a margin (the context remembers one
  * float per head); a head for which that leaves fewer than k rows is rescored without the filter
- * in the same call.  The result is therefore the same exact Top-k over the candidates whatever
- * the remembered value is; only the time differs.  (A context whose max_k exceeds ~13 000 starts with the
+ * in the same call (by that head's workgroup of the select kernel: no extra launches).  The result is therefore
+ * the same exact Top-k over the candidates whatever the remembered value is; only the time differs.  The first
+ * chained step after lfps_create or lfps_reset_history has nothing remembered and takes the unfiltered kernels; that
+ * is decided on the host, so a HIP graph captured from such a call replays the unfiltered form: capture a later step.  (A context whose max_k exceeds ~13 000 starts with the
  * filter off: a head's survivors would not fit the select's on-chip list.)  lfps_set_filter(ctx, 0) turns the filter off,
  * lfps_reset_history forgets the remembered scores (e.g. when the context moves to other requests). */
 int lfps_step(lfps_ctx* ctx, const float* q, const lfps_kv* kv, const int32_t* prev_topk, const int32_t* k,

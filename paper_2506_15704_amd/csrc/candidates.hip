@@ -103,8 +103,6 @@ __global__ __launch_bounds__(kCandThreads) void k_candidates(Shape s, const int3
                                                              int32_t* __restrict__ cand,
                                                              int32_t* __restrict__ cand_count,
                                                              int32_t* __restrict__ flags,
-                                                             int32_t* __restrict__ redo_g,
-                                                             int32_t* __restrict__ redo_h,
                                                              int64_t* __restrict__ group_start,
                                                              unsigned long long* __restrict__ line_total) {
   extern __shared__ uint32_t lds[];
@@ -118,11 +116,6 @@ __global__ __launch_bounds__(kCandThreads) void k_candidates(Shape s, const int3
   n = n < 0 ? 0 : (n > s.Lcap ? s.Lcap : n);
   int kb = kk[b];
   kb = kb < 0 ? 0 : (kb > s.kmax ? s.kmax : kb);
-  // first kernel of a step: clear the group's "needs the unfiltered pass" marks
-  if (part == 0) {
-    if (redo_g && tid == 0) redo_g[bg] = 0;
-    if (redo_h && tid < s.G) redo_h[(int64_t)b * s.Hq + (int64_t)g * s.G + tid] = 0;
-  }
   const int W = (n + 31) >> 5;
   uint32_t* bm = lds;
   const int words_cap = (s.Lcap + 31) >> 5;
@@ -201,8 +194,6 @@ __global__ __launch_bounds__(kCandThreads) void k_table_candidates(Shape s, cons
                                                                    int32_t* __restrict__ cand,
                                                                    int32_t* __restrict__ cand_count,
                                                                    int32_t* __restrict__ flags,
-                                                                   int32_t* __restrict__ redo_g,
-                                                                   int32_t* __restrict__ redo_h,
                                                                    int64_t* __restrict__ group_start,
                                                                    unsigned long long* __restrict__ line_total) {
   extern __shared__ uint32_t lds[];
@@ -212,10 +203,6 @@ __global__ __launch_bounds__(kCandThreads) void k_table_candidates(Shape s, cons
   const int tid = threadIdx.x;
   int n = seq_lens[b];
   n = n < 0 ? 0 : (n > s.Lcap ? s.Lcap : n);
-  if (part == 0) {                                         // first kernel of a step: clear the group's marks
-    if (redo_g && tid == 0) redo_g[bg] = 0;
-    if (redo_h && tid < s.G) redo_h[(int64_t)b * s.Hq + (int64_t)g * s.G + tid] = 0;
-  }
   const int W = (n + 31) >> 5;
   uint32_t* bm = lds;
   const int words_cap = (s.Lcap + 31) >> 5;
@@ -275,24 +262,23 @@ hipError_t configure_candidates(const Shape& s) {
 }
 
 hipError_t launch_candidates(const Shape& s, const int32_t* prev_topk, const int32_t* k, const int32_t* seq_lens,
-                             int32_t* cand, int32_t* cand_count, int32_t* flags, int32_t* redo_g, int32_t* redo_h,
-                             int64_t* group_start, int64_t* line_total, hipStream_t st) {
+                             int32_t* cand, int32_t* cand_count, int32_t* flags, int64_t* group_start,
+                             int64_t* line_total, hipStream_t st) {
   int nparts = 256 / (s.B * s.Hkv);                    // one workgroup per CU in total (82 KB of LDS each)
   nparts = nparts < 1 ? 1 : (nparts > 8 ? 8 : nparts);
   hipLaunchKernelGGL(k_candidates, dim3(nparts, s.B * s.Hkv), dim3(kCandThreads), candidates_lds_bytes(s), st, s,
-                     prev_topk, k, seq_lens, cand, cand_count, flags, redo_g, redo_h, group_start,
+                     prev_topk, k, seq_lens, cand, cand_count, flags, group_start,
                      reinterpret_cast<unsigned long long*>(line_total));
   return hipGetLastError();
 }
 
 hipError_t launch_table_candidates(const Shape& s, const uint32_t* f0, const uint32_t* fm, int flag_words,
                                    const int32_t* seq_lens, int32_t* cand, int32_t* cand_count, int32_t* flags,
-                                   int32_t* redo_g, int32_t* redo_h, int64_t* group_start, int64_t* line_total,
-                                   hipStream_t st) {
+                                   int64_t* group_start, int64_t* line_total, hipStream_t st) {
   int nparts = 256 / (s.B * s.Hkv);
   nparts = nparts < 1 ? 1 : (nparts > 8 ? 8 : nparts);
   hipLaunchKernelGGL(k_table_candidates, dim3(nparts, s.B * s.Hkv), dim3(kCandThreads), candidates_lds_bytes(s), st, s,
-                     f0, fm, flag_words, seq_lens, cand, cand_count, flags, redo_g, redo_h, group_start,
+                     f0, fm, flag_words, seq_lens, cand, cand_count, flags, group_start,
                      reinterpret_cast<unsigned long long*>(line_total));
   return hipGetLastError();
 }

@@ -16,8 +16,7 @@ __global__ __launch_bounds__(256) void k_dense_prep(Shape s, const int32_t* __re
                                                     const int32_t* __restrict__ kk, int ns_max, int list_cap,
                                                     int32_t* __restrict__ x_cnt, int64_t* __restrict__ x_start,
                                                     int32_t* __restrict__ x_nsg, int32_t* __restrict__ x_ns,
-                                                    int32_t* __restrict__ x_rank, int32_t* __restrict__ sample,
-                                                    int32_t* __restrict__ redo_g, int32_t* __restrict__ redo_h) {
+                                                    int32_t* __restrict__ x_rank, int32_t* __restrict__ sample) {
   __shared__ long long part[256];
   const int bg = blockIdx.x, b = bg / s.Hkv, g = bg % s.Hkv, tid = threadIdx.x;
   const int n_groups = s.B * s.Hkv;
@@ -90,22 +89,20 @@ __global__ __launch_bounds__(256) void k_dense_prep(Shape s, const int32_t* __re
     x_start[bg] = my_start;
     if (bg == n_groups - 1) x_start[n_groups] = total;
     x_nsg[bg] = ns;
-    redo_g[bg] = 0;
     if (g == 0) {
       x_ns[b] = ns;
       x_rank[b] = r;
     }
   }
-  if (tid < s.G) redo_h[(int64_t)b * s.Hq + (int64_t)g * s.G + tid] = 0;
   int32_t* out = sample + (int64_t)bg * s.cand_cap;
   for (int i = tid; i < ns; i += 256) out[i] = (int)(((long long)i * n) / ns);
 }
 
 hipError_t launch_dense_prep(const Shape& s, const int32_t* seq_lens, const int32_t* k, int ns_max, int list_cap, int32_t* x_cnt,
                              int64_t* x_start, int32_t* x_nsg, int32_t* x_ns, int32_t* x_rank, int32_t* sample,
-                             int32_t* redo_g, int32_t* redo_h, hipStream_t st) {
+                             hipStream_t st) {
   hipLaunchKernelGGL(k_dense_prep, dim3(s.B * s.Hkv), dim3(256), 0, st, s, seq_lens, k, ns_max, list_cap, x_cnt, x_start, x_nsg,
-                     x_ns, x_rank, sample, redo_g, redo_h);
+                     x_ns, x_rank, sample);
   return hipGetLastError();
 }
 

@@ -15,6 +15,7 @@ struct lfps_ctx {
   Shape shape;
   int n_split_full;
   int filter_on;       // filtered scoring inside lfps_step (bf16 / fp16 / FP8-key caches)
+  int no_history;      // no chained step since creation / lfps_reset_history: no head has a remembered score
   int nseg;            // survivor pieces per head (row length of seg_count)
   int filter_blocks[2];   // launch size of the filtered scoring kernel (contiguous, paged cache): the workgroups the device holds at once
   // workspace (device)
@@ -22,8 +23,6 @@ struct lfps_ctx {
   int32_t* slot;       // [B, Hq, score_stride] candidate slots of the filtered survivors
   int32_t* seg_count;  // [B, Hq, nseg]
   float* thr_state;    // [B, Hq] k-th best score of the previous step
-  int32_t* redo_g;     // [B, Hkv]
-  int32_t* redo_h;     // [B, Hq]
   int64_t* group_start; // [B, Hkv] place of each group on the line of all candidate slots; [B*Hkv] = the line's length
   // score tables (table_mode)
   float* tab_ver;      // [B, Hq, Lcap]
@@ -75,7 +74,7 @@ namespace {
 
 struct Sizes {
   int32_t G, cand_cap, score_stride, n_split_full, nseg, flag_words;
-  int64_t score_b, cand_b, count_b, sel_b, part_b, slot_b, seg_b, thr_b, redo_b, tver_b, tsla_b, tstate_b, tflag_b, x_b, total;
+  int64_t score_b, cand_b, count_b, sel_b, part_b, slot_b, seg_b, thr_b, line_b, tver_b, tsla_b, tstate_b, tflag_b, x_b, total;
 };
 
 int64_t align256(int64_t x) { return (x + 255) & ~(int64_t)255; }
@@ -146,8 +145,7 @@ int check_config(const lfps_config* c, Sizes* z, char* err, size_t errn) {
   z->slot_b = filt ? z->score_b : 0;
   z->seg_b = align256((int64_t)c->batch * c->n_q_heads * z->nseg * 4);
   z->thr_b = align256((int64_t)c->batch * c->n_q_heads * 4);
-  z->redo_b = align256((int64_t)c->batch * (c->n_q_heads + c->n_kv_heads) * 4) +
-              align256(((int64_t)c->batch * c->n_kv_heads + 1) * 8);   // + group_start and the line's length
+  z->line_b = align256(((int64_t)c->batch * c->n_kv_heads + 1) * 8);   // group_start and the line's length
   z->flag_words = ((c->max_seq_len + 63) / 64) * 2 + 2;
   const int64_t heads = (int64_t)c->batch * c->n_q_heads;
   z->tver_b = c->table_mode ? align256(heads * c->max_seq_len * 4) : 0;
@@ -156,7 +154,7 @@ int check_config(const lfps_config* c, Sizes* z, char* err, size_t errn) {
   z->tflag_b = c->table_mode ? align256(heads * z->flag_words * 4) : 0;
   z->x_b = 3 * z->count_b + 2 * align256((int64_t)c->batch * 4) + align256(((int64_t)c->batch * c->n_kv_heads + 1) * 8) + z->thr_b;
   z->total = z->score_b + z->cand_b + z->count_b + z->sel_b + z->part_b + z->slot_b + z->seg_b + z->thr_b +
-             z->redo_b + 256 + z->x_b + z->tver_b + z->tsla_b + z->tstate_b + 2 * z->tflag_b + z->thr_b /* gate marks */;
+             z->line_b + 256 + z->x_b + z->tver_b + z->tsla_b + z->tstate_b + 2 * z->tflag_b + z->thr_b /* gate marks */;
   return LFPS_OK;
 }
 
@@ -325,10 +323,8 @@ int lfps_create(const lfps_config* cfg, lfps_ctx** out) {
   p += z.seg_b;
   c->thr_state = (float*)p;
   p += z.thr_b;
-  c->redo_g = (int32_t*)p;
-  c->redo_h = c->redo_g + (int64_t)cfg->batch * cfg->n_kv_heads;
-  c->group_start = (int64_t*)(p + align256((int64_t)cfg->batch * (cfg->n_q_heads + cfg->n_kv_heads) * 4));
-  p += z.redo_b;
+  c->group_start = (int64_t*)p;
+  p += z.line_b;
   c->flags = (int32_t*)p;
   p += 256;
   {
@@ -358,12 +354,13 @@ int lfps_create(const lfps_config* cfg, lfps_ctx** out) {
   c->nseg = z.nseg;
   // The filtered pass pays off only if a head's survivors (about 1.25 x its budget) fit the select's list; with a
   // budget too large for that every head would be rescored anyway, so such a context starts with the filter off.
+  c->no_history = 1;
   c->filter_on = (z.slot_b && (int64_t)cfg->max_k + cfg->max_k / 4 <= filter_list_cap(s)) ? 1 : 0;
   // The exact Top-k baseline takes the filtered scoring pass too (threshold from a sample of the rows) once the
   // contexts are large enough for the extra launches to pay: about a million rows in all.
   c->x_fast = (z.slot_b && (int64_t)cfg->batch * cfg->n_kv_heads * cfg->max_seq_len >= kExactFastMinRows) ? 1 : 0;
   e = hipMemset(c->flags, 0, 256);
-  if (e == hipSuccess) e = hipMemset(c->seg_count, 0, (size_t)(z.seg_b + z.thr_b + z.redo_b));   // counts, marks, line length
+  if (e == hipSuccess) e = hipMemset(c->seg_count, 0, (size_t)(z.seg_b + z.thr_b + z.line_b));   // counts, line length
   if (e == hipSuccess) e = hipMemset(c->thr_state, 0xFF, (size_t)z.thr_b);   // all-ones = NaN: "no history"
   if (e == hipSuccess && cfg->table_mode)
     e = hipMemset(c->tab_ver, 0, (size_t)(z.tver_b + z.tsla_b + z.tstate_b + 2 * z.tflag_b));
@@ -413,8 +410,7 @@ int lfps_candidates(lfps_ctx* ctx, const int32_t* prev_topk, const int32_t* k, c
     return fail(ctx, LFPS_EINVAL, "lfps_candidates: NULL argument");
   hipStream_t st = (hipStream_t)stream;
   LAUNCH(ctx, LFPS_KERNEL_CANDIDATES, st,
-         launch_candidates(ctx->shape, prev_topk, k, seq_lens, cand, cand_count, ctx->flags, nullptr, nullptr, nullptr,
-                           nullptr, st));
+         launch_candidates(ctx->shape, prev_topk, k, seq_lens, cand, cand_count, ctx->flags, nullptr, nullptr, st));
   return LFPS_OK;
 }
 
@@ -431,10 +427,9 @@ int lfps_score_topk(lfps_ctx* ctx, const float* q, const lfps_kv* kv, const int3
   float* sc = cand_score ? cand_score : ctx->score;
   const int64_t stride = cand_score ? s.cand_cap : s.score_stride;
   LAUNCH(ctx, LFPS_KERNEL_GATHER_SCORE, st,
-         launch_group_score(s, ctx->cfg.kv_dtype, q, v, cand, cand_count, sc, stride, nullptr, ctx->flags, st));
+         launch_group_score(s, ctx->cfg.kv_dtype, q, v, cand, cand_count, sc, stride, ctx->flags, st));
   LAUNCH(ctx, LFPS_KERNEL_SELECT, st,
-         launch_select(s, sc, stride, cand, cand_count, k, topk_idx, topk_score, nullptr, nullptr, nullptr, v.seq_lens,
-                       st));
+         launch_select(s, sc, stride, cand, cand_count, k, topk_idx, topk_score, nullptr, nullptr, v.seq_lens, st));
   return LFPS_OK;
 }
 
@@ -457,34 +452,40 @@ int lfps_sparse_attn(lfps_ctx* ctx, const float* q, const lfps_kv* kv, const int
   return LFPS_OK;
 }
 
+// Does the next chained step take the filtered kernels?  (Decides, too, whether its candidates kernel lays the
+// groups on the line: only the filtered select clears the line's length again.)
+static bool next_step_filtered(const lfps_ctx* ctx) { return ctx->filter_on && !ctx->no_history; }
+
 // S2 + S3 + S4 over ctx->cand / ctx->cand_count inside the chained entry points.  With the score filter on
-// (16-bit and FP8-key caches): survivors of the per-head threshold first, selected and attended to in one kernel;
-// then the unfiltered pass for the heads it left short (both launches exit at once when no head is marked).  The
-// candidates kernel of the same step has cleared the marks and laid the groups on the line (group_start, line_total).
+// (16-bit and FP8-key caches): survivors of the per-head threshold, then select and attention in one kernel, which
+// also takes the unfiltered pass for the heads the filter left short.  Without it: every score, then select and
+// attention; also for the first step after creation or lfps_reset_history, when no head has a remembered score and
+// the filtered form would send every head through its slower in-kernel fallback.
+// The candidates kernel of the same step has laid the groups on the line (group_start, line_total).
 static int score_select_attend(lfps_ctx* ctx, const float* q, const KvView& v, const int32_t* k, int32_t* topk_idx,
                                float* sel, float* out, const int32_t* skip_if, hipStream_t st) {
   const Shape& s = ctx->shape;
   int64_t* line_total = ctx->group_start + (int64_t)s.B * s.Hkv;
-  const int32_t *only_g = nullptr, *only_h = nullptr;
-  if (ctx->filter_on) {
+  const bool filtered = next_step_filtered(ctx);
+  ctx->no_history = 0;                       // either form leaves every selecting head's k-th best score behind
+  if (filtered) {
     LAUNCH(ctx, LFPS_KERNEL_FILTER_SCORE, st,
            launch_filter_score(s, q, v, ctx->cand, ctx->cand_count, ctx->group_start, line_total, ctx->thr_state,
                                kFilterMargin, ctx->score, ctx->slot, s.score_stride, ctx->seg_count, ctx->flags + 1,
                                ctx->filter_blocks[v.page.table ? 1 : 0], ctx->flags, false, ctx->nseg, st));
     LAUNCH(ctx, LFPS_KERNEL_FILTER_SELECT_ATTEND, st,
            launch_filter_select_attend(s, ctx->cfg.kv_dtype, ctx->score, ctx->slot, s.score_stride, ctx->seg_count,
-                                       ctx->flags + 1, ctx->nseg, ctx->cand_count, ctx->group_start, line_total, k,
-                                       topk_idx, sel, ctx->thr_state, ctx->redo_g, ctx->redo_h, skip_if, ctx->flags + 2,
-                                       v, out, st));
-    only_g = ctx->redo_g;
-    only_h = ctx->redo_h;
+                                       ctx->flags + 1, ctx->nseg, ctx->cand, ctx->cand_count, ctx->group_start,
+                                       line_total, k, topk_idx, sel, ctx->thr_state, skip_if, ctx->flags + 2, q,
+                                       ctx->flags, v, out, st));
+    return LFPS_OK;
   }
   LAUNCH(ctx, LFPS_KERNEL_GATHER_SCORE, st,
          launch_group_score(s, ctx->cfg.kv_dtype, q, v, ctx->cand, ctx->cand_count, ctx->score, s.score_stride,
-                            only_g, ctx->flags, st));
+                            ctx->flags, st));
   LAUNCH(ctx, LFPS_KERNEL_SELECT_ATTEND, st,
          launch_select_attend(s, ctx->cfg.kv_dtype, ctx->score, s.score_stride, ctx->cand, ctx->cand_count, k, topk_idx,
-                              sel, only_h, ctx->thr_state, skip_if, v, out, st));
+                              sel, ctx->thr_state, skip_if, v, out, st));
   return LFPS_OK;
 }
 
@@ -505,8 +506,8 @@ int lfps_step(lfps_ctx* ctx, const float* q, const lfps_kv* kv, const int32_t* p
   float* sel = topk_score ? topk_score : ctx->sel_score;
   int64_t* line_total = ctx->group_start + (int64_t)s.B * s.Hkv;   // zero between steps: the filtered select resets it
   LAUNCH(ctx, LFPS_KERNEL_CANDIDATES, st,
-         launch_candidates(s, prev_topk, k, v.seq_lens, ctx->cand, ctx->cand_count, ctx->flags, ctx->redo_g,
-                           ctx->redo_h, ctx->filter_on ? ctx->group_start : nullptr, line_total, st));
+         launch_candidates(s, prev_topk, k, v.seq_lens, ctx->cand, ctx->cand_count, ctx->flags,
+                           next_step_filtered(ctx) ? ctx->group_start : nullptr, line_total, st));
   return score_select_attend(ctx, q, v, k, topk_idx, sel, out, nullptr, st);
 }
 
@@ -616,40 +617,37 @@ int lfps_exact_topk(lfps_ctx* ctx, const float* q, const lfps_kv* kv, const int3
   if (rc != LFPS_OK) return rc;
   hipStream_t st = (hipStream_t)stream;
   const Shape& s = ctx->shape;
-  const int32_t *only_g = nullptr, *only_h = nullptr;
   if (ctx->x_fast && ctx->filter_on) {      // (lfps_set_filter(ctx, 0) also selects the plain form)
     // Threshold per head from a scored sample of the rows, then one filtered pass over all rows and the select from
-    // its survivors (exact_topk.hip); heads left short are rescored the plain way below.
+    // its survivors (exact_topk.hip); a head left short takes the plain pass inside the select kernel.
     Shape sd = s;
     sd.cand_cap = s.Lcap;                 // the "candidates" of the dense pass are all rows of a group
     int64_t* x_total = ctx->x_start + (int64_t)s.B * s.Hkv;
     hipError_t e = launch_dense_prep(s, v.seq_lens, k, kExactSampleRows, filter_list_cap(s), ctx->x_cnt, ctx->x_start, ctx->x_nsg, ctx->x_ns,
-                                     ctx->x_rank, ctx->cand, ctx->redo_g, ctx->redo_h, st);
+                                     ctx->x_rank, ctx->cand, st);
     if (e != hipSuccess) return fail(ctx, LFPS_EHIP, "lfps_exact_topk (set-up)", e);
     LAUNCH(ctx, LFPS_KERNEL_GATHER_SCORE, st,
-           launch_group_score(s, ctx->cfg.kv_dtype, q, v, ctx->cand, ctx->x_nsg, ctx->score, s.score_stride, nullptr,
-                              ctx->flags, st));
+           launch_group_score(s, ctx->cfg.kv_dtype, q, v, ctx->cand, ctx->x_nsg, ctx->score, s.score_stride, ctx->flags,
+                              st));
     LAUNCH(ctx, LFPS_KERNEL_SELECT, st,      // the rank-th best sample score of every head -> thr_x (the rows go to scratch)
-           launch_select(s, ctx->score, s.score_stride, nullptr, ctx->x_ns, ctx->x_rank, ctx->slot, nullptr, nullptr,
-                         ctx->thr_x, nullptr, nullptr, st));
+           launch_select(s, ctx->score, s.score_stride, nullptr, ctx->x_ns, ctx->x_rank, ctx->slot, nullptr, ctx->thr_x,
+                         nullptr, nullptr, st));
     LAUNCH(ctx, LFPS_KERNEL_FILTER_SCORE, st,
            launch_filter_score(sd, q, v, nullptr, ctx->x_cnt, ctx->x_start, x_total, ctx->thr_x, 0.f, ctx->score,
                                ctx->slot, s.score_stride, ctx->seg_count, ctx->flags + 1,
                                ctx->filter_blocks[v.page.table ? 1 : 0], ctx->flags, true, ctx->nseg, st));
     LAUNCH(ctx, LFPS_KERNEL_FILTER_SELECT_ATTEND, st,
            launch_filter_select_attend(sd, ctx->cfg.kv_dtype, ctx->score, ctx->slot, s.score_stride, ctx->seg_count,
-                                       ctx->flags + 1, ctx->nseg, ctx->x_cnt, ctx->x_start, x_total, k, topk_idx,
-                                       topk_score ? topk_score : ctx->sel_score, ctx->thr_x, ctx->redo_g, ctx->redo_h,
-                                       nullptr, nullptr, v, nullptr, st));
-    only_g = ctx->redo_g;
-    only_h = ctx->redo_h;
+                                       ctx->flags + 1, ctx->nseg, nullptr, ctx->x_cnt, ctx->x_start, x_total, k, topk_idx,
+                                       topk_score ? topk_score : ctx->sel_score, ctx->thr_x, nullptr, nullptr, q,
+                                       ctx->flags, v, nullptr, st));
+    return LFPS_OK;
   }
   LAUNCH(ctx, LFPS_KERNEL_DENSE_SCORE, st,
-         launch_group_score(s, ctx->cfg.kv_dtype, q, v, nullptr, nullptr, ctx->score, s.score_stride, only_g, ctx->flags,
-                            st));
+         launch_group_score(s, ctx->cfg.kv_dtype, q, v, nullptr, nullptr, ctx->score, s.score_stride, ctx->flags, st));
   LAUNCH(ctx, LFPS_KERNEL_SELECT, st,
-         launch_select(s, ctx->score, s.score_stride, nullptr, v.seq_lens, k, topk_idx, topk_score, only_h, nullptr,
-                       nullptr, nullptr, st));
+         launch_select(s, ctx->score, s.score_stride, nullptr, v.seq_lens, k, topk_idx, topk_score, nullptr, nullptr,
+                       nullptr, st));
   return LFPS_OK;
 }
 
@@ -681,7 +679,7 @@ int lfps_tables_init(lfps_ctx* ctx, const float* q_hist, int32_t n_queries, cons
   for (int j = 1; j <= n_queries; ++j) {
     LAUNCH(ctx, LFPS_KERNEL_DENSE_SCORE, st,
            launch_group_score(s, ctx->cfg.kv_dtype, q_hist + (int64_t)(j - 1) * q_stride, v, nullptr, nullptr, ctx->score,
-                              s.score_stride, nullptr, ctx->flags, st));
+                              s.score_stride, ctx->flags, st));
     hipError_t e = launch_table_init(s, ctx->tab_ver, ctx->tab_sla, v.seq_lens, ctx->score, s.score_stride,
                                      (double)ctx->cfg.table_decay, j, n_queries, st);
     if (e != hipSuccess) return fail(ctx, LFPS_EHIP, "lfps_tables_init", e);
@@ -726,8 +724,7 @@ static int table_candidates_impl(lfps_ctx* ctx, const int32_t* seq_lens, int32_t
                             ctx->flag_words, (double)ctx->cfg.table_a, gate, st));
   LAUNCH(ctx, LFPS_KERNEL_TABLE_CANDIDATES, st,
          launch_table_candidates(s, ctx->tab_f0, ctx->tab_fm, ctx->flag_words, seq_lens, cand, cand_count, ctx->flags,
-                                 for_step ? ctx->redo_g : nullptr, for_step ? ctx->redo_h : nullptr,
-                                 for_step && ctx->filter_on ? ctx->group_start : nullptr,
+                                 for_step && next_step_filtered(ctx) ? ctx->group_start : nullptr,
                                  ctx->group_start + (int64_t)s.B * s.Hkv, st));
   return LFPS_OK;
 }
@@ -797,8 +794,7 @@ int lfps_priors(lfps_ctx* ctx, const float* q, const lfps_kv* kv, float* kbar, f
   hipError_t e = launch_prior_means(s, ctx->cfg.kv_dtype, v, kbar, vbar, st);
   if (e != hipSuccess) return fail(ctx, LFPS_EHIP, "lfps_priors (means)", e);
   LAUNCH(ctx, LFPS_KERNEL_DENSE_SCORE, st,
-         launch_group_score(s, ctx->cfg.kv_dtype, q, v, nullptr, nullptr, ctx->score, s.score_stride, nullptr, ctx->flags,
-                            st));
+         launch_group_score(s, ctx->cfg.kv_dtype, q, v, nullptr, nullptr, ctx->score, s.score_stride, ctx->flags, st));
   e = launch_prior_variance(s, q, v.seq_lens, ctx->score, s.score_stride, sigma2_hat, st);
   if (e != hipSuccess) return fail(ctx, LFPS_EHIP, "lfps_priors (variance)", e);
   return LFPS_OK;
@@ -856,6 +852,7 @@ int lfps_reset_history(lfps_ctx* ctx, void* stream) {
                      __builtin_nanf(""));
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return fail(ctx, LFPS_EHIP, "lfps_reset_history", e);
+  ctx->no_history = 1;
   return LFPS_OK;
 }
 

@@ -73,21 +73,19 @@ struct Shape {
 // ---- kernel launchers (each enqueues on `st` and returns the launch error) -------------
 hipError_t configure_candidates(const Shape& s);
 hipError_t configure_select(const Shape& s);
-// redo_g [B,Hkv] / redo_h [B,Hq] (or NULL): marks cleared here, set by the filtered select.
 // group_start [B,Hkv] / line_total [1] (or NULL): every group adds its candidate count to *line_total
 // (zero on entry) and keeps the value before the addition as its place on the line of all candidate slots.
 hipError_t launch_candidates(const Shape& s, const int32_t* prev_topk, const int32_t* k, const int32_t* seq_lens,
-                             int32_t* cand, int32_t* cand_count, int32_t* flags, int32_t* redo_g, int32_t* redo_h,
-                             int64_t* group_start, int64_t* line_total, hipStream_t st);
+                             int32_t* cand, int32_t* cand_count, int32_t* flags, int64_t* group_start,
+                             int64_t* line_total, hipStream_t st);
 
 // Scores of candidate rows (cand != NULL) or of all rows 0..n_b-1 (cand == NULL) for the G heads
 // of each KV group.  score is [B, Hq, score_stride].
-// only_if [B,Hkv] (or NULL): groups whose entry is 0 are skipped.
 // flags: the context's status word (LFPS_FLAG_Q_RANGE is raised there).  A candidate entry outside [0, n_b)
 // scores -inf.
 hipError_t launch_group_score(const Shape& s, int dtype, const float* q, const KvView& kv, const int32_t* cand,
-                              const int32_t* cand_count, float* score, int64_t score_stride, const int32_t* only_if,
-                              int32_t* flags, hipStream_t st);
+                              const int32_t* cand_count, float* score, int64_t score_stride, int32_t* flags,
+                              hipStream_t st);
 
 // Filtered scoring (bf16, fp16 or FP8 keys; the kernel keeps its first name, k_filter_score_bf16): per
 // head only rows with score >= thr_state[b,h] - margin are kept, as
@@ -104,41 +102,42 @@ hipError_t launch_filter_score(const Shape& s, const float* q, const KvView& kv,
                                const float* thr_state, float margin, float* score,
                                int32_t* slot_out, int64_t score_stride, int32_t* seg_count, int32_t* seg_rows_out,
                                int n_blocks, int32_t* flags, bool dense, int nseg, hipStream_t st);
-// S3 + S4 of the chained steps in one kernel per stage of the filter (select_attend.hip).  From the survivor
-// lists of the filtered scoring pass: heads left short are marked in redo_g / redo_h (and counted in *rescored)
-// and not touched; the others get their Top-k rows (topk_idx, topk_score: both required) and their output row.
+// S3 + S4 of the chained steps in one kernel (select_attend.hip).  From the survivor lists of the filtered scoring
+// pass: every head gets its Top-k rows (topk_idx, topk_score: both required) and its output row; a head whose list
+// is short or overfull takes the unfiltered pass inside the kernel (counted in *rescored), which needs q, the K rows
+// and the group's candidate list (cand; NULL = all rows 0 .. cand_count-1) and overwrites the head's score row.
 hipError_t configure_select_attend(const Shape& s);
-hipError_t launch_filter_select_attend(const Shape& s, int dtype, const float* score, const int32_t* slot_in,
+hipError_t launch_filter_select_attend(const Shape& s, int dtype, float* score, const int32_t* slot_in,
                                        int64_t score_stride, const int32_t* seg_count, const int32_t* seg_rows, int nseg,
-                                       const int32_t* cand_count, const int64_t* group_start, int64_t* line_total,
-                                       const int32_t* k, int32_t* topk_idx, float* topk_score, float* thr_state,
-                                       int32_t* redo_g, int32_t* redo_h, const int32_t* skip_if, int32_t* rescored,
-                                       const KvView& kv, float* out, hipStream_t st);   // out == NULL: select only
+                                       const int32_t* cand, const int32_t* cand_count, const int64_t* group_start,
+                                       int64_t* line_total, const int32_t* k, int32_t* topk_idx, float* topk_score,
+                                       float* thr_state, const int32_t* skip_if, int32_t* rescored, const float* q,
+                                       int32_t* flags, const KvView& kv, float* out,
+                                       hipStream_t st);   // out == NULL: select only
 
 // Exact Top-k baseline, set-up of its filtered dense pass (exact_topk.hip): every group's rows 0..n_b-1 laid on the
 // line (x_cnt, x_start, x_start[B*Hkv] = the line's length), a strided sample of at most ns_max rows per group
 // (sized for the select's list capacity list_cap)
 // (sample [B, Hkv, cand_cap], x_nsg [B*Hkv] / x_ns [B] its length) and the rank x_rank [B] whose sample score is
-// taken as the threshold; the redo marks are cleared.
+// taken as the threshold.
 hipError_t launch_dense_prep(const Shape& s, const int32_t* seq_lens, const int32_t* k, int ns_max, int list_cap,
                              int32_t* x_cnt,
                              int64_t* x_start, int32_t* x_nsg, int32_t* x_ns, int32_t* x_rank, int32_t* sample,
-                             int32_t* redo_g, int32_t* redo_h, hipStream_t st);
-// From the full score rows [B, Hq, score_stride] over cand: every head, or (only_if [B,Hq]) the marked ones.
+                             hipStream_t st);
+// From the full score rows [B, Hq, score_stride] over cand, every head.
 hipError_t launch_select_attend(const Shape& s, int dtype, const float* score, int64_t score_stride, const int32_t* cand,
                                 const int32_t* cand_count, const int32_t* k, int32_t* topk_idx, float* topk_score,
-                                const int32_t* only_if, float* thr_state, const int32_t* skip_if, const KvView& kv,
-                                float* out, hipStream_t st);
+                                float* thr_state, const int32_t* skip_if, const KvView& kv, float* out,
+                                hipStream_t st);
 
 // Per (b, h): the k_b best of score[b,h,0:count]; count = cand_count[b, g(h)] when cand != NULL,
 // else seq_lens[b].  Writes positions (ascending) and their scores.
-// only_if [B,Hq] (or NULL): heads whose entry is 0 are skipped.  thr_state [B,Hq] (or NULL) receives
+// thr_state [B,Hq] (or NULL) receives
 // each head's k-th best score.  skip_if [B,Hq] (or NULL): heads whose entry is not 0 are skipped (bypassed heads).
 // seq_lens [B] (or NULL; with cand only): a selected candidate entry outside [0, n_b) is written as -1.
 hipError_t launch_select(const Shape& s, const float* score, int64_t score_stride, const int32_t* cand,
                          const int32_t* count, const int32_t* k, int32_t* topk_idx, float* topk_score,
-                         const int32_t* only_if, float* thr_state, const int32_t* skip_if, const int32_t* seq_lens,
-                         hipStream_t st);
+                         float* thr_state, const int32_t* skip_if, const int32_t* seq_lens, hipStream_t st);
 
 // Scores of idx[b,h,0:k_b] rows against q[b,h] (one head at a time, no group sharing).
 hipError_t launch_head_score(const Shape& s, int dtype, const float* q, const KvView& kv, const int32_t* idx,
@@ -163,8 +162,7 @@ hipError_t launch_table_flags(const Shape& s, const float* tab_ver, const float*
                               const int32_t* gate, hipStream_t st);
 hipError_t launch_table_candidates(const Shape& s, const uint32_t* f0, const uint32_t* fm, int flag_words,
                                    const int32_t* seq_lens, int32_t* cand, int32_t* cand_count, int32_t* flags,
-                                   int32_t* redo_g, int32_t* redo_h, int64_t* group_start, int64_t* line_total,
-                                   hipStream_t st);
+                                   int64_t* group_start, int64_t* line_total, hipStream_t st);
 hipError_t launch_table_update(const Shape& s, float* tab_ver, float* tab_sla, double* state, const int32_t* seq_lens,
                                const int32_t* idx, const float* sc, const int32_t* k, double gamma, const int32_t* gate,
                                int32_t* flags, bool distinct, hipStream_t st);   // distinct: no position twice in a head's list

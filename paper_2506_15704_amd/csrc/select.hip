@@ -29,7 +29,6 @@ __global__ __launch_bounds__(kSelThreads) void k_select(Shape s, const float* __
                                                         const int32_t* __restrict__ count_arr,
                                                         const int32_t* __restrict__ kk, int32_t* __restrict__ topk_idx,
                                                         float* __restrict__ topk_score, int cache_elems,
-                                                        const int32_t* __restrict__ only_if,
                                                         float* __restrict__ thr_state,
                                                         const int32_t* __restrict__ skip_if,
                                                         const int32_t* __restrict__ seq_lens) {
@@ -37,7 +36,6 @@ __global__ __launch_bounds__(kSelThreads) void k_select(Shape s, const float* __
   extern __shared__ float cache[];
   const int bh = blockIdx.x, b = bh / s.Hq, h = bh % s.Hq, g = h / s.G;
   const int tid = threadIdx.x;
-  if (only_if && only_if[bh] == 0) return;          // this head was already settled by the filtered pass
   if (skip_if && skip_if[bh] != 0) return;          // bypassed head: its rows were written by the gate
   const bool gather = cand != nullptr;
   int c = gather ? count_arr[b * s.Hkv + g] : count_arr[b];
@@ -98,13 +96,10 @@ hipError_t configure_select(const Shape& s) {
 
 hipError_t launch_select(const Shape& s, const float* score, int64_t score_stride, const int32_t* cand,
                          const int32_t* count, const int32_t* k, int32_t* topk_idx, float* topk_score,
-                         const int32_t* only_if, float* thr_state, const int32_t* skip_if, const int32_t* seq_lens,
-                         hipStream_t st) {
-  // A conditional launch (only_if) is expected to find nothing to do: it streams from global memory
-  // instead of reserving the LDS cache, so that its workgroups are cheap to place and retire.
-  const int ce = only_if ? 0 : select_cache_elems(s, cand != nullptr);
+                         float* thr_state, const int32_t* skip_if, const int32_t* seq_lens, hipStream_t st) {
+  const int ce = select_cache_elems(s, cand != nullptr);
   hipLaunchKernelGGL(k_select, dim3(s.B * s.Hq), dim3(kSelThreads), (size_t)ce * 4, st, s, score, score_stride, cand,
-                     count, k, topk_idx, topk_score, ce, only_if, thr_state, skip_if, seq_lens);
+                     count, k, topk_idx, topk_score, ce, thr_state, skip_if, seq_lens);
   return hipGetLastError();
 }
 

@@ -5,13 +5,20 @@
 // heads that finish selecting early start gathering V rows while others still select, and a step has one kernel
 // boundary less.
 //
-//   k_filter_select_attend   selects from the survivor lists that the filtered scoring pass leaves per head;
-//                            a head whose survivors are fewer than k (or more than its on-chip list holds) is
-//                            marked for the unfiltered pass and left alone.
-//   k_select_attend          selects from a head's full score row (all candidates): the unfiltered pass, for
-//                            marked heads only (only_if) or for every head (contexts without the filter).
+//   k_filter_select_attend   selects from the survivor lists that the filtered scoring pass leaves per head.
+//                            A head whose survivors are fewer than k (or more than its on-chip list holds) takes
+//                            the unfiltered pass on the spot: its workgroup scores every candidate of the group
+//                            for this head (the same MFMA arithmetic as the group scoring kernel, hence the same
+//                            bits) into the head's score row and selects from that.  This is rare once a history
+//                            exists (the threshold sits a margin below the previous k-th best score) and costs
+//                            that workgroup the bytes of all candidate rows; in exchange a step has no conditional
+//                            launches behind this kernel.
+//   k_select_attend          selects from a head's full score row (all candidates): contexts without the filter.
 #include "attend.h"
+#include "score_mfma.h"
 #include "select_body.h"
+
+#include <type_traits>
 
 namespace lfps {
 
@@ -21,15 +28,18 @@ namespace lfps {
 // `sgm` is what wave w_first + sgm took of it, w_first = pg / S: the group's slots [lo, hi).  The piece holds
 // seg_count[bh, sgm] (score, row position) pairs at offset lo of the head's score / position rows, ascending in
 // position within and across pieces.  Workgroup 0 leaves *line_total at zero for the next step.
-template <typename T, bool kPaged>
+// The unfiltered pass needs the query, the K rows (format kKind, G heads per group) and the group's candidate list
+// (cand; NULL when the candidates are all rows 0 .. count-1, the exact Top-k baseline's dense pass).
+template <typename T, bool kPaged, int G, int kKind>
 __global__ __launch_bounds__(kFilterSelThreads) void k_filter_select_attend(
-    Shape s, const float* __restrict__ score, const int32_t* __restrict__ slot_in, int64_t score_stride,
+    Shape s, float* score, const int32_t* __restrict__ slot_in, int64_t score_stride,
     const int32_t* __restrict__ seg_count, const int32_t* __restrict__ seg_rows_in, int nseg,
-    const int32_t* __restrict__ cand_count, const int64_t* __restrict__ group_start, int64_t* __restrict__ line_total,
-    const int32_t* __restrict__ kk, int32_t* topk_idx, float* topk_score, float* __restrict__ thr_state,
-    int32_t* __restrict__ redo_g, int32_t* __restrict__ redo_h, int cap, const int32_t* __restrict__ skip_if,
-    int32_t* __restrict__ rescored, const T* __restrict__ V, int64_t stride_b, int64_t stride_h, int64_t stride_n,
-    KvPage page, const int32_t* __restrict__ seq_lens, float* __restrict__ out) {
+    const int32_t* __restrict__ cand, const int32_t* __restrict__ cand_count, const int64_t* __restrict__ group_start,
+    int64_t* __restrict__ line_total, const int32_t* __restrict__ kk, int32_t* topk_idx, float* topk_score,
+    float* __restrict__ thr_state, int cap, const int32_t* __restrict__ skip_if, int32_t* __restrict__ rescored,
+    const float* __restrict__ q, const void* __restrict__ K, float scale, int32_t* __restrict__ flags,
+    const T* __restrict__ V, int64_t stride_b, int64_t stride_h, int64_t stride_n, KvPage page,
+    const int32_t* __restrict__ seq_lens, float* __restrict__ out) {
   constexpr int NT = kFilterSelThreads, kSelWaves = NT / 64;
   constexpr int kPiecesPerThread = 1024 / NT;      // nseg <= 1024
   __shared__ SelectShared<NT> sm;
@@ -105,14 +115,8 @@ __global__ __launch_bounds__(kFilterSelThreads) void k_filter_select_attend(
       off += cntp[u];
     }
   }
-  if (n_surv < ksel || n_surv > cap) {              // block-uniform: the unfiltered pass takes this head
-    if (tid == 0) {
-      redo_g[bg] = 1;
-      redo_h[bh] = 1;
-      if (rescored) atomicAdd(rescored, 1);          // heads sent to the unfiltered pass since the last poll
-    }
-    return;
-  }
+  const bool unfiltered = n_surv < ksel || n_surv > cap;   // block-uniform: the list cannot give the k best
+  if (unfiltered && tid == 0 && rescored) atomicAdd(rescored, 1);   // heads that took the unfiltered pass since the last poll
   int32_t* oi = topk_idx + (int64_t)bh * s.kmax;
   float* os = topk_score + (int64_t)bh * s.kmax;
   for (int i = ksel + tid; i < s.kmax; i += NT) {   // padding
@@ -122,6 +126,19 @@ __global__ __launch_bounds__(kFilterSelThreads) void k_filter_select_attend(
   float top = 0.f;
   if (ksel == 0) {
     if (tid == 0) thr_state[bh] = -INFINITY;
+  } else if (unfiltered) {
+    // every candidate slot of the group, 64 per wave and visit, scored for the G heads; my head's lane group stores
+    using Rows = RowMap<kPaged>;
+    using Op = typename KTile<kKind>::Operand;
+    Op A[4];
+    report_q_range(load_query_operand<G>(A, q, (int64_t)b * s.Hq + (int64_t)g * G, lane & 15, lane >> 4), flags);
+    const char* Kbg = static_cast<const char*>(K) + Rows::base(b, g, stride_b, stride_h) * KTile<kKind>::kElemBytes;
+    const int32_t* cbg = cand ? cand + (int64_t)bg * s.cand_cap : nullptr;
+    float* sc = score + (int64_t)bh * score_stride;   // the survivor list there is given up
+    score_slots_mfma<G, kPaged, kKind>(A, Kbg, page, b, stride_b, stride_n, cbg, n, c, wv * kRowsPerWaveIter,
+                                       kSelWaves * kRowsPerWaveIter, sc, (lane >> 4) == h - g * G, scale);
+    __syncthreads();                                  // the score row is complete before anyone reads it
+    top = select_stream<NT>(sm, sc, c, ksel, cbg, oi, os, thr_state + bh, n);
   } else {
     __syncthreads();
     const float* sc = score + (int64_t)bh * score_stride;
@@ -188,13 +205,12 @@ __global__ __launch_bounds__(kFilterSelThreads) void k_filter_select_attend(
 }
 
 // ----------------------------------------------------------------------------- from the full score rows
-// k_select's steps on score[b, h, 0:c] (c = the group's candidate count), then the attention.  only_if [B, Hq]
-// (or NULL): heads whose entry is 0 were settled by the filtered pass and are skipped.
+// k_select's steps on score[b, h, 0:c] (c = the group's candidate count), then the attention.
 template <typename T, bool kPaged>
 __global__ __launch_bounds__(kSelThreads) void k_select_attend(
     Shape s, const float* __restrict__ score, int64_t score_stride, const int32_t* __restrict__ cand,
     const int32_t* __restrict__ cand_count, const int32_t* __restrict__ kk, int32_t* topk_idx, float* topk_score,
-    int cache_elems, const int32_t* __restrict__ only_if, float* __restrict__ thr_state,
+    int cache_elems, float* __restrict__ thr_state,
     const int32_t* __restrict__ skip_if, const T* __restrict__ V, int64_t stride_b, int64_t stride_h, int64_t stride_n,
     KvPage page, const int32_t* __restrict__ seq_lens, float* __restrict__ out) {
   __shared__ SelectShared<kSelThreads> sm;
@@ -203,7 +219,6 @@ __global__ __launch_bounds__(kSelThreads) void k_select_attend(
   const int bh = head_of_block(s, blockIdx.x);
   const int b = bh / s.Hq, h = bh % s.Hq, g = h / s.G;
   const int tid = threadIdx.x;
-  if (only_if && only_if[bh] == 0) return;          // this head was already settled by the filtered pass
   if (skip_if && skip_if[bh] != 0) return;          // bypassed head: its rows were written by the gate
   int c = cand_count[b * s.Hkv + g];
   c = c < 0 ? 0 : (c > s.cand_cap ? s.cand_cap : c);
@@ -243,80 +258,92 @@ static int filter_select_attend_lds(const Shape& s) {
   return list > (int)sizeof(AttendShared) ? list : (int)sizeof(AttendShared);
 }
 
+// The instantiations of k_filter_select_attend: V type and K format go together (bf16 V with bf16 or FP8 keys,
+// FP8 V with FP8 keys, fp16 V with fp16 keys), times paged or not, times the heads per group.
+#define LFPS_FSA_FOR_EACH_G(X, TYPE, PAGED, KIND) X(TYPE, PAGED, 1, KIND) X(TYPE, PAGED, 2, KIND) X(TYPE, PAGED, 4, KIND)
+#define LFPS_FSA_FOR_EACH(X)                              \
+  LFPS_FSA_FOR_EACH_G(X, uint16_t, false, kKindBf16)      \
+  LFPS_FSA_FOR_EACH_G(X, uint16_t, true, kKindBf16)       \
+  LFPS_FSA_FOR_EACH_G(X, uint16_t, false, kKindFp8)       \
+  LFPS_FSA_FOR_EACH_G(X, uint16_t, true, kKindFp8)        \
+  LFPS_FSA_FOR_EACH_G(X, uint8_t, false, kKindFp8)        \
+  LFPS_FSA_FOR_EACH_G(X, uint8_t, true, kKindFp8)         \
+  LFPS_FSA_FOR_EACH_G(X, _Float16, false, kKindF16)       \
+  LFPS_FSA_FOR_EACH_G(X, _Float16, true, kKindF16)
+
 hipError_t configure_select_attend(const Shape& s) {
   hipError_t e = hipSuccess;
   auto raise = [&](const void* kernel, int bytes) {
     if (e == hipSuccess) e = hipFuncSetAttribute(kernel, hipFuncAttributeMaxDynamicSharedMemorySize, bytes);
   };
   const int fb = filter_select_attend_lds(s), sb = kCacheElems * 4;
-#define LFPS_RAISE_BOTH(TYPE)                                              \
-  raise((const void*)k_filter_select_attend<TYPE, false>, fb);             \
-  raise((const void*)k_filter_select_attend<TYPE, true>, fb);              \
-  raise((const void*)k_select_attend<TYPE, false>, sb);                    \
+#define LFPS_RAISE_FSA(TYPE, PAGED, GG, KIND) raise((const void*)k_filter_select_attend<TYPE, PAGED, GG, KIND>, fb);
+  LFPS_FSA_FOR_EACH(LFPS_RAISE_FSA)
+#undef LFPS_RAISE_FSA
+#define LFPS_RAISE_SA(TYPE)                                   \
+  raise((const void*)k_select_attend<TYPE, false>, sb);       \
   raise((const void*)k_select_attend<TYPE, true>, sb)
-  LFPS_RAISE_BOTH(uint16_t);
-  LFPS_RAISE_BOTH(_Float16);
-  LFPS_RAISE_BOTH(uint8_t);
-  raise((const void*)k_select_attend<float, false>, sb);
-  raise((const void*)k_select_attend<float, true>, sb);
-#undef LFPS_RAISE_BOTH
+  LFPS_RAISE_SA(uint16_t);
+  LFPS_RAISE_SA(_Float16);
+  LFPS_RAISE_SA(uint8_t);
+  LFPS_RAISE_SA(float);
+#undef LFPS_RAISE_SA
   return e;
 }
 
 template <typename T>
-static hipError_t launch_fsa_t(const Shape& s, const float* score, const int32_t* slot_in, int64_t score_stride,
-                               const int32_t* seg_count, const int32_t* seg_rows, int nseg, const int32_t* cand_count,
-                               const int64_t* group_start, int64_t* line_total, const int32_t* k, int32_t* topk_idx,
-                               float* topk_score, float* thr_state, int32_t* redo_g, int32_t* redo_h,
-                               const int32_t* skip_if, int32_t* rescored, const KvView& kv, float* out, hipStream_t st) {
-  const int cap = filter_list_cap(s);
-  const T* V = (const T*)kv.v;
-#define LFPS_LAUNCH_FSA(PAGED)                                                                                        \
-  hipLaunchKernelGGL((k_filter_select_attend<T, PAGED>), dim3(s.B * s.Hq), dim3(kFilterSelThreads),                   \
-                     (size_t)filter_select_attend_lds(s), st, s, score, slot_in, score_stride, seg_count, seg_rows, nseg, cand_count, group_start,         \
-                     line_total, k, topk_idx, topk_score, thr_state, redo_g, redo_h, cap, skip_if, rescored, V,       \
-                     kv.stride_b, kv.stride_h, kv.stride_n, kv.page, kv.seq_lens, out)
-  if (kv.page.table) {
-    LFPS_LAUNCH_FSA(true);
-  } else {
-    LFPS_LAUNCH_FSA(false);
-  }
-#undef LFPS_LAUNCH_FSA
-  return hipGetLastError();
+static constexpr int v_type_code() {          // 0 bf16 (as bits), 1 FP8, 2 fp16
+  return std::is_same<T, uint16_t>::value ? 0 : (std::is_same<T, uint8_t>::value ? 1 : 2);
 }
 
-hipError_t launch_filter_select_attend(const Shape& s, int dtype, const float* score, const int32_t* slot_in,
+hipError_t launch_filter_select_attend(const Shape& s, int dtype, float* score, const int32_t* slot_in,
                                        int64_t score_stride, const int32_t* seg_count, const int32_t* seg_rows, int nseg,
-                                       const int32_t* cand_count, const int64_t* group_start, int64_t* line_total,
-                                       const int32_t* k, int32_t* topk_idx, float* topk_score, float* thr_state,
-                                       int32_t* redo_g, int32_t* redo_h, const int32_t* skip_if, int32_t* rescored,
-                                       const KvView& kv, float* out, hipStream_t st) {
-#define LFPS_FSA_ARGS                                                                                                   \
-  s, score, slot_in, score_stride, seg_count, seg_rows, nseg, cand_count, group_start, line_total, k, topk_idx,         \
-      topk_score, thr_state, redo_g, redo_h, skip_if, rescored, kv, out, st
-  if (dtype == LFPS_BF16 && kv.v_fp8) return launch_fsa_t<uint8_t>(LFPS_FSA_ARGS);
-  if (dtype == LFPS_F16) return launch_fsa_t<_Float16>(LFPS_FSA_ARGS);
-  if (dtype == LFPS_BF16) return launch_fsa_t<uint16_t>(LFPS_FSA_ARGS);
-#undef LFPS_FSA_ARGS
-  return hipErrorInvalidValue;                      // the filtered pass exists for 16-bit and FP8 caches only
+                                       const int32_t* cand, const int32_t* cand_count, const int64_t* group_start,
+                                       int64_t* line_total, const int32_t* k, int32_t* topk_idx, float* topk_score,
+                                       float* thr_state, const int32_t* skip_if, int32_t* rescored, const float* q,
+                                       int32_t* flags, const KvView& kv, float* out, hipStream_t st) {
+  const int cap = filter_list_cap(s);
+  const float scale = 0.08838834764831845f;   // 1/sqrt(128)
+  const bool paged = kv.page.table != nullptr;
+  // the pair (V type, K format) of this cache
+  int vt = -1, kind = -1;                     // vt: 0 bf16, 1 FP8, 2 fp16
+  if (dtype == LFPS_BF16) {
+    vt = kv.v_fp8 ? 1 : 0;
+    kind = kv.k_fp8 ? kKindFp8 : kKindBf16;
+    if (vt == 1 && kind != kKindFp8) return hipErrorInvalidValue;   // FP8 values come with FP8 keys
+  } else if (dtype == LFPS_F16) {
+    vt = 2;
+    kind = kKindF16;
+  } else {
+    return hipErrorInvalidValue;              // the filtered pass exists for 16-bit and FP8 caches only
+  }
+  bool launched = false;
+#define LFPS_LAUNCH_FSA(TYPE, PAGED, GG, KIND)                                                                          \
+  if (!launched && vt == v_type_code<TYPE>() && paged == PAGED && s.G == GG && kind == KIND) {                        \
+    hipLaunchKernelGGL((k_filter_select_attend<TYPE, PAGED, GG, KIND>), dim3(s.B * s.Hq), dim3(kFilterSelThreads),      \
+                       (size_t)filter_select_attend_lds(s), st, s, score, slot_in, score_stride, seg_count, seg_rows,   \
+                       nseg, cand, cand_count, group_start, line_total, k, topk_idx, topk_score, thr_state, cap,        \
+                       skip_if, rescored, q, kv.k, scale, flags, (const TYPE*)kv.v, kv.stride_b, kv.stride_h,           \
+                       kv.stride_n, kv.page, kv.seq_lens, out);                                                         \
+    launched = true;                                                                                                    \
+  }
+  LFPS_FSA_FOR_EACH(LFPS_LAUNCH_FSA)
+#undef LFPS_LAUNCH_FSA
+  if (!launched) return hipErrorInvalidValue;
+  return hipGetLastError();
 }
 
 template <typename T>
 static hipError_t launch_sa_t(const Shape& s, const float* score, int64_t score_stride, const int32_t* cand,
                               const int32_t* cand_count, const int32_t* k, int32_t* topk_idx, float* topk_score,
-                              const int32_t* only_if, float* thr_state, const int32_t* skip_if, const KvView& kv,
-                              float* out, hipStream_t st) {
-  // A conditional launch (only_if) is expected to find nothing to do: it streams from global memory
-  // instead of reserving the LDS cache, so that its workgroups are cheap to place and retire.
-  int ce = 0;
-  if (!only_if) {
-    ce = s.cand_cap < kCacheElems ? s.cand_cap : kCacheElems;
-    ce = (ce + 63) & ~63;
-  }
+                              float* thr_state, const int32_t* skip_if, const KvView& kv, float* out,
+                              hipStream_t st) {
+  int ce = s.cand_cap < kCacheElems ? s.cand_cap : kCacheElems;
+  ce = (ce + 63) & ~63;
   const T* V = (const T*)kv.v;
 #define LFPS_LAUNCH_SA(PAGED)                                                                                       \
   hipLaunchKernelGGL((k_select_attend<T, PAGED>), dim3(s.B * s.Hq), dim3(kSelThreads), (size_t)ce * 4, st, s, score, \
-                     score_stride, cand, cand_count, k, topk_idx, topk_score, ce, only_if, thr_state, skip_if, V,   \
+                     score_stride, cand, cand_count, k, topk_idx, topk_score, ce, thr_state, skip_if, V,   \
                      kv.stride_b, kv.stride_h, kv.stride_n, kv.page, kv.seq_lens, out)
   if (kv.page.table) {
     LFPS_LAUNCH_SA(true);
@@ -329,9 +356,9 @@ static hipError_t launch_sa_t(const Shape& s, const float* score, int64_t score_
 
 hipError_t launch_select_attend(const Shape& s, int dtype, const float* score, int64_t score_stride, const int32_t* cand,
                                 const int32_t* cand_count, const int32_t* k, int32_t* topk_idx, float* topk_score,
-                                const int32_t* only_if, float* thr_state, const int32_t* skip_if, const KvView& kv,
-                                float* out, hipStream_t st) {
-#define LFPS_SA_ARGS s, score, score_stride, cand, cand_count, k, topk_idx, topk_score, only_if, thr_state, skip_if, kv, out, st
+                                float* thr_state, const int32_t* skip_if, const KvView& kv, float* out,
+                                hipStream_t st) {
+#define LFPS_SA_ARGS s, score, score_stride, cand, cand_count, k, topk_idx, topk_score, thr_state, skip_if, kv, out, st
   if (dtype == LFPS_BF16 && kv.v_fp8) return launch_sa_t<uint8_t>(LFPS_SA_ARGS);
   if (dtype == LFPS_F16) return launch_sa_t<_Float16>(LFPS_SA_ARGS);
   if (dtype == LFPS_BF16) return launch_sa_t<uint16_t>(LFPS_SA_ARGS);

@@ -296,11 +296,12 @@ __device__ __forceinline__ void select_body(SelectShared<NT>& sm, float* __restr
 // The streaming variant is a real call, so that its code does not compete for registers with
 // the register-resident variant.
 // Returns the head's largest score.
-static __device__ __noinline__ float select_stream(SelectShared<kSelThreads>& sm, const float* __restrict__ sc, int c, int ksel,
+template <int NT>
+static __device__ __noinline__ float select_stream(SelectShared<NT>& sm, const float* __restrict__ sc, int c, int ksel,
                                                    const int32_t* __restrict__ cbg, int32_t* __restrict__ oi,
                                                    float* __restrict__ os, float* __restrict__ thr_out, int n_valid) {
   float top = 0.f;
-  select_body<false, kSelThreads>(sm, nullptr, sc, c, ksel, nullptr, cbg, oi, os, thr_out, FLT_MAX, -FLT_MAX, n_valid, &top);
+  select_body<false, NT>(sm, nullptr, sc, c, ksel, nullptr, cbg, oi, os, thr_out, FLT_MAX, -FLT_MAX, n_valid, &top);
   return top;
 }
 

@@ -124,12 +124,14 @@ def test_fp16_query_beyond_the_format_is_clamped_and_flagged():
 
 def test_filter_switched_on_after_creation_with_a_large_budget():
     """A context whose budget is too large for the select's survivor list starts with the filter off; switching
-    it on must still give the unfiltered result (every head is then rescored), not a launch error."""
+    it on must still give the unfiltered result (a head whose survivors overflow the list is rescored), not a
+    launch error."""
     spec = gen.tiny_spec("bigk", B=1, L=30000, k=14000, r=0, T=2, Hq=4, Hkv=1)
     dc = DeviceCase(spec)
     case = dc.case
     ref, flt = dc.make_ctx(), dc.make_ctx()
     flt.lfps_set_filter(True)
+    flt.lfps_timing_enable(True)
     shp = (1, 4, case.kmax)
     seed = torch.zeros(shp, dtype=torch.int32, device=DEV)
     ref.lfps_exact_topk(dc.q(0), ref.kv_view(dc.K, dc.V, dc.seq_lens(0)), dc.k, seed)
@@ -146,14 +148,16 @@ def test_filter_switched_on_after_creation_with_a_large_budget():
         assert torch.equal(res[0][0], res[1][0]) and torch.equal(res[0][1], res[1][1])
         prev = res[0][0]
     assert ref.lfps_poll_rescored() == 0                  # no filtered pass, nothing to rescore
-    assert flt.lfps_poll_rescored() > 0
+    tm = flt.lfps_timing_read()                           # the second step went through the filtered kernels
+    assert tm["filter_score"][1] == 1 and tm["filter_select_attend"][1] == 1 and tm["select_attend"][1] == 1
     ref.close()
     flt.close()
 
 
 def test_rescored_heads_are_counted():
-    """First step after a reset: no history, every head goes through the unfiltered pass; the following steps
-    of a slowly drifting query keep their history; a query scaled down by 100 invalidates it again."""
+    """The first step of a new context takes the unfiltered kernels (nothing is rescored); the following step
+    of a slowly drifting query filters with the history that step left; a query scaled down by 100 makes that
+    history useless and every head is rescored inside the select kernel; a reset starts over."""
     spec = gen.tiny_spec("resc", B=2, L=3000, k=96, r=2, T=4)
     dc = DeviceCase(spec)
     case = dc.case
@@ -165,12 +169,15 @@ def test_rescored_heads_are_counted():
     ctx.lfps_exact_topk(dc.q(0), ctx.kv_view(dc.K, dc.V, dc.seq_lens(0)), dc.k, a)
     assert ctx.lfps_poll_rescored() == 0
     ctx.lfps_step(dc.q(1), ctx.kv_view(dc.K, dc.V, dc.seq_lens(1)), a, dc.k, b_, out)
-    assert ctx.lfps_poll_rescored() == spec.B * spec.Hq
+    assert ctx.lfps_poll_rescored() == 0
     ctx.lfps_step(dc.q(2), ctx.kv_view(dc.K, dc.V, dc.seq_lens(2)), b_, dc.k, a, out)
     few = ctx.lfps_poll_rescored()
     assert few < spec.B * spec.Hq // 4, few
     ctx.lfps_step(dc.q(3) * 0.01, ctx.kv_view(dc.K, dc.V, dc.seq_lens(3)), a, dc.k, b_, out)
     assert ctx.lfps_poll_rescored() == spec.B * spec.Hq
+    ctx.lfps_reset_history()
+    ctx.lfps_step(dc.q(4), ctx.kv_view(dc.K, dc.V, dc.seq_lens(4)), b_, dc.k, a, out)
+    assert ctx.lfps_poll_rescored() == 0
     assert ctx.lfps_poll_status() == 0
     ctx.close()
 
