@@ -32,10 +32,15 @@ __device__ __forceinline__ void set_bit_range(uint32_t* bm, int lo, int hi) {  /
 // of the rounds by a block scan, (c) per round every lane expands its word into a wave-private LDS
 // stage at the lane's offset within the round, then the wave copies the stage out with consecutive
 // lanes writing consecutive entries.  `part` of `nparts` workgroups that share the group emit every
-// nparts-th round.  Returns the group's total (untruncated) to every thread.
-__device__ __forceinline__ int emit_bitmap(const Shape& s, const uint32_t* bm, int W, uint32_t* rcnt, uint16_t* stage,
-                                           int* wave_tot, int bg, int part, int nparts, int32_t* __restrict__ cand,
-                                           int32_t* __restrict__ cand_count, int32_t* __restrict__ flags) {
+// nparts-th round.  group_start / line_total (or NULL): the group's place on the line of all candidate slots that
+// the filtered scoring pass cuts into equal parts: the group adds its (truncated) count to *line_total (the caller
+// has left it at zero) and keeps the value before the addition.  The addition is issued as soon as the count is
+// known and its result stored after the emission, so its round trip hides behind the emission.
+__device__ __forceinline__ void emit_bitmap(const Shape& s, const uint32_t* bm, int W, uint32_t* rcnt, uint16_t* stage,
+                                            int* wave_tot, int bg, int part, int nparts, int32_t* __restrict__ cand,
+                                            int32_t* __restrict__ cand_count, int32_t* __restrict__ flags,
+                                            int64_t* __restrict__ group_start,
+                                            unsigned long long* __restrict__ line_total) {
   const int tid = threadIdx.x;
   const int lane = tid & 63, wv = tid >> 6;
   const int nr = (W + 63) >> 6;                                  // rounds (<= kCandThreads, checked at creation)
@@ -57,6 +62,9 @@ __device__ __forceinline__ int emit_bitmap(const Shape& s, const uint32_t* bm, i
     total += t;
   }
   if (tid < nr) rcnt[tid] = (uint32_t)(base + inc - cnt);        // now the exclusive offset of round tid
+  const bool places = tid == 0 && part == 0 && group_start != nullptr;
+  unsigned long long place = 0;
+  if (places) place = atomicAdd(line_total, (unsigned long long)(total > s.cand_cap ? s.cand_cap : total));
   __syncthreads();
 
   int32_t* out = cand + (int64_t)bg * s.cand_cap;
@@ -92,7 +100,7 @@ __device__ __forceinline__ int emit_bitmap(const Shape& s, const uint32_t* bm, i
     }
     cand_count[bg] = kept;
   }
-  return total;
+  if (places) group_start[bg] = (int64_t)place;
 }
 
 // Dynamic LDS: bitmap words [ceil(Lcap/32)], round counts/offsets [ceil(words/64)], then a
@@ -112,18 +120,15 @@ __global__ __launch_bounds__(kCandThreads) void k_candidates(Shape s, const int3
   const int bg = blockIdx.y, b = bg / s.Hkv, g = bg % s.Hkv;
   const int part = blockIdx.x, nparts = gridDim.x;
   const int tid = threadIdx.x;
-  int n = seq_lens[b];
-  n = n < 0 ? 0 : (n > s.Lcap ? s.Lcap : n);
-  int kb = kk[b];
-  kb = kb < 0 ? 0 : (kb > s.kmax ? s.kmax : kb);
-  const int W = (n + 31) >> 5;
   uint32_t* bm = lds;
   const int words_cap = (s.Lcap + 31) >> 5;
   uint32_t* rcnt = lds + words_cap;
   uint16_t* stage = reinterpret_cast<uint16_t*>(rcnt + ((words_cap + 63) >> 6));
 
   // The previous Top-k of the group's heads: issue every load of a round before touching LDS, so
-  // their latencies overlap (4 heads x 2 entries per thread and round).
+  // their latencies overlap (4 heads x 2 entries per thread and round).  The first round is fetched
+  // up to the row length kmax, not the request's budget, and masked when used: its loads then wait
+  // for nothing (neither the budget nor the length), and the three fetches share one round trip.
   constexpr int kU = 2;
   const int r = s.radius;
   const int32_t* pt = prev_topk + ((int64_t)b * s.Hq + (int64_t)g * s.G) * s.kmax;
@@ -133,15 +138,19 @@ __global__ __launch_bounds__(kCandThreads) void k_candidates(Shape s, const int3
 #pragma unroll
     for (int u = 0; u < kU; ++u) {
       const int j = tid + u * kCandThreads;
-      first_ids[h * kU + u] = (h < s.G && j < kb) ? pt[(int64_t)h * s.kmax + j] : -1;
+      first_ids[h * kU + u] = (h < s.G && j < s.kmax) ? pt[(int64_t)h * s.kmax + j] : -1;
     }
-
-  for (int w = tid; w < W; w += kCandThreads) bm[w] = 0u;
+  for (int w = tid; w < words_cap; w += kCandThreads) bm[w] = 0u;
+  int n = seq_lens[b];
+  n = n < 0 ? 0 : (n > s.Lcap ? s.Lcap : n);
+  int kb = kk[b];
+  kb = kb < 0 ? 0 : (kb > s.kmax ? s.kmax : kb);
+  const int W = (n + 31) >> 5;
   __syncthreads();
 
 #pragma unroll
   for (int e = 0; e < 4 * kU; ++e) {
-    const int i = first_ids[e];
+    const int i = (tid + (e % kU) * kCandThreads < kb) ? first_ids[e] : -1;
     if (i >= 0 && i < n) {
       const int lo = i - r < 0 ? 0 : i - r;
       const int64_t hi64 = (int64_t)i + r + 1;
@@ -173,13 +182,7 @@ __global__ __launch_bounds__(kCandThreads) void k_candidates(Shape s, const int3
   }
   __syncthreads();
 
-  const int total = emit_bitmap(s, bm, W, rcnt, stage, wave_tot, bg, part, nparts, cand, cand_count, flags);
-  // the group's place on the line of all candidate slots that the filtered scoring pass cuts into
-  // equal parts (the caller has left *line_total at zero)
-  if (tid == 0 && part == 0 && group_start) {
-    const int kept = total > s.cand_cap ? s.cand_cap : total;
-    group_start[bg] = (int64_t)atomicAdd(line_total, (unsigned long long)kept);
-  }
+  emit_bitmap(s, bm, W, rcnt, stage, wave_tot, bg, part, nparts, cand, cand_count, flags, group_start, line_total);
 }
 
 // ----------------------------------------------------------------------------- score-table form
@@ -237,11 +240,7 @@ __global__ __launch_bounds__(kCandThreads) void k_table_candidates(Shape s, cons
     if (s.n_sink > 0) set_bit_range(bm, 0, (s.n_sink > n ? n : s.n_sink) - 1);
   }
   __syncthreads();
-  const int total = emit_bitmap(s, bm, W, rcnt, stage, wave_tot, bg, part, nparts, cand, cand_count, flags);
-  if (tid == 0 && part == 0 && group_start) {              // the group's place on the line of all candidate slots
-    const int kept = total > s.cand_cap ? s.cand_cap : total;
-    group_start[bg] = (int64_t)atomicAdd(line_total, (unsigned long long)kept);
-  }
+  emit_bitmap(s, bm, W, rcnt, stage, wave_tot, bg, part, nparts, cand, cand_count, flags, group_start, line_total);
 }
 
 static size_t candidates_lds_bytes(const Shape& s) {
